@@ -1,0 +1,348 @@
+"""Pins for the CPU oracle: hand-worked bytes, closed forms, invariants, brute
+force, textbook reductions.  None of these re-uses the oracle's own formulas."""
+import itertools
+
+import numpy as np
+import pytest
+import scipy.sparse
+
+from oracle import egt_oracle as O
+from paper_2605_11582_amd import synth
+from helpers import read_fixture
+
+
+def _rand_w(R, K, seed, scale=0.02):
+    rng = np.random.default_rng(seed)
+    return (rng.standard_normal((R, K)) * scale).astype(np.float16)
+
+
+def _rand_x(K, seed):
+    return np.random.default_rng(seed).standard_normal(K).astype(np.float16)
+
+
+# ----------------------------------------------------------------- fixture
+def _fixture():
+    fx = read_fixture("handworked_1x32.txt")
+    w = np.array([float(v) for v in fx["w"]], dtype=np.float16)[None, :]
+    mask = np.array([int(v) for v in fx["mask"]], dtype=np.uint8)[None, :]
+    return fx, w, mask
+
+
+def test_handworked_int4_bytes():
+    fx, w, mask = _fixture()
+    p = O.pack_2bitcsr(w, mask, 2, 32, O.VAL_INT4)
+    assert [int(v, 16) for v in fx["idx_words"]] == p["idx"].tolist()
+    assert [int(v, 16) for v in fx["value_bytes"]] == p["values"].tolist()
+    assert [int(v, 16) for v in fx["qparams"]] == p["qparams"].reshape(-1).tolist()
+    assert [int(v) for v in fx["row_ptr"]] == p["row_ptr"].tolist()
+    col, w_hat, q = O.decode_2bitcsr(p)
+    assert [int(v) for v in fx["offs"]] == (col[0] % 4).tolist()
+    assert [int(v) for v in fx["q"]] == q[0].tolist()
+    x = np.arange(1, 33).astype(np.float16)
+    y, a = O.gemv(p, x)
+    assert y[0] == float(fx["y"][0]) and a[0] == float(fx["abs_sum"][0])
+
+
+def test_handworked_fp16_bytes():
+    fx, w, mask = _fixture()
+    p = O.pack_2bitcsr(w, mask, 2, 0, O.VAL_FP16)
+    assert [int(v, 16) for v in fx["fp16_bits"]] == p["values"].view(np.uint16).tolist()
+    assert [int(v, 16) for v in fx["idx_words"]] == p["idx"].tolist()
+    assert p["qparams"] is None
+    y, _ = O.gemv(p, np.arange(1, 33).astype(np.float16))
+    assert y[0] == float(fx["y_fp16"][0])
+
+
+# ----------------------------------------------------------------- size model
+def test_size_ratio_30_percent():
+    # the paper's figure: index + weights = 30 % of the original CSR
+    m = O.size_model(11008, 4096, 2, value_bits=4, csr_index_bits=16)
+    assert m["ratio"] == pytest.approx(6 / 20) and m["ratio"] == pytest.approx(0.30)
+    assert O.size_model(64, 64, 2, 16, 32)["ratio"] == pytest.approx(18 / 48)       # 37.5 %
+    assert O.size_model(64, 64, 2, 16, 16)["ratio"] == pytest.approx(18 / 32)       # 56.25 %
+    # INT4 + 2 bit + group-128 parameters against FP16 + int32 CSR: 6.5 / 48
+    m = O.size_model(128, 1024, 2, 4, 32, group=128, csr_value_bits=16)
+    assert m["ratio"] == pytest.approx(6.5 / 48)
+    # 1:4 has the same per-non-zero ratio
+    assert O.size_model(64, 64, 1, 4, 16)["ratio"] == pytest.approx(0.30)
+
+
+def test_buffer_sizes_closed_form():
+    assert O.buffer_sizes(11008, 4096, 2, 128, O.VAL_INT4) == (44036, 11272192, 5636096, 1409024)
+    assert O.buffer_sizes(11008, 4096, 2, 0, O.VAL_FP16) == (44036, 45088768, 5636096, 0)
+    assert O.buffer_sizes(4096, 11008, 1, 128, O.VAL_INT4) == (16388, 4096 * 2752 // 2, 4096 * 2752 // 4, 4096 * 86 * 4)
+    w = _rand_w(8, 64, 1)
+    for n, kind, g in [(2, O.VAL_INT4, 32), (1, O.VAL_INT4, 16), (2, O.VAL_FP16, 0), (4, O.VAL_INT4, 64)]:
+        p = O.pack_2bitcsr(w, O.prune_n4_magnitude(w, n), n, g, kind)
+        sizes = O.buffer_sizes(8, 64, n, g, kind)
+        got = (p["row_ptr"].nbytes, p["values"].nbytes, p["idx"].nbytes,
+               0 if p["qparams"] is None else p["qparams"].nbytes)
+        assert got == sizes
+
+
+# ----------------------------------------------------------------- pruning
+@pytest.mark.parametrize("n", [1, 2, 3])
+def test_prune_is_top_n_by_sort(n):
+    w = _rand_w(16, 64, 7)
+    w[0, :8] = np.float16(0.5)                 # ties -> lower column wins
+    w[1, 4:8] = [0.0, -0.0, 0.25, -0.25]
+    mask = O.prune_n4_magnitude(w, n)
+    assert np.all(mask.reshape(16, 16, 4).sum(axis=2) == n)
+    for r in range(16):
+        for c in range(16):
+            grp = np.abs(w[r, 4 * c:4 * c + 4].astype(np.float64))
+            order = sorted(range(4), key=lambda j: (-grp[j], j))
+            expect = np.zeros(4, dtype=np.uint8)
+            expect[order[:n]] = 1
+            assert np.array_equal(mask[r, 4 * c:4 * c + 4], expect)
+
+
+def test_prune_equals_eq3_ranking_with_constant_statistics():
+    # Eq. (3) with a constant activation norm and gradient ranks like |w|
+    w = _rand_w(8, 32, 3)
+    score = O.importance_eq3(w, np.full(32, 1.7), np.full((8, 32), 0.3))
+    mask = O.prune_n4_magnitude(w, 2)
+    s = score.reshape(8, 8, 4)
+    top2 = np.argsort(-s, axis=2, kind="stable")[:, :, :2]
+    expect = np.zeros_like(s, dtype=np.uint8)
+    np.put_along_axis(expect, top2, 1, axis=2)
+    assert np.array_equal(mask, expect.reshape(8, 32))
+
+
+# ----------------------------------------------------------------- structure
+@pytest.mark.parametrize("n,kind,g", [(2, 0, 32), (1, 0, 32), (2, 1, 0), (3, 0, 16), (4, 0, 64)])
+def test_structure_invariants(n, kind, g):
+    R, K = 12, 128
+    w = _rand_w(R, K, 11 + n)
+    p = O.pack_2bitcsr(w, O.prune_n4_magnitude(w, n), n, g, kind)
+    S = n * K // 4
+    assert np.all(np.diff(p["row_ptr"].astype(np.int64)) == S)
+    assert p["row_ptr"][-1] == n * R * K // 4
+    # decode the index words by hand: 8 fields of 2 bits, low bits first
+    fields = np.array([[(int(wd) >> (2 * k)) & 3 for k in range(8)] for wd in p["idx"]]).reshape(R, K // 4, n)
+    assert np.all(np.diff(fields, axis=2) > 0) if n > 1 else True
+    assert fields.min() >= 0 and fields.max() <= 3
+    if kind == 0:
+        assert p["values"].size == R * S // 2
+        z = p["qparams"][:, :, 1].view(np.float16).astype(np.float64)
+        assert np.all(z == np.rint(z)) and z.min() >= 0 and z.max() <= 15
+
+
+def test_overfull_group_is_an_error():
+    w = _rand_w(2, 32, 5)
+    mask = O.prune_n4_magnitude(w, 2)
+    mask[1, 4:8] = [1, 1, 1, 0]
+    with pytest.raises(ValueError):
+        O.pack_2bitcsr(w, mask, 2, 32, O.VAL_INT4)
+
+
+def test_nonfinite_kept_weight_is_an_error():
+    w = _rand_w(2, 32, 5)
+    mask = O.prune_n4_magnitude(w, 2)
+    r, c = np.argwhere(mask == 1)[3]
+    w[r, c] = np.float16(np.inf)
+    with pytest.raises(FloatingPointError):
+        O.pack_2bitcsr(w, mask, 2, 32, O.VAL_INT4)
+
+
+# ----------------------------------------------------------------- round trips
+def test_fp16_round_trip_returns_original_bits():
+    w = _rand_w(16, 96, 21)
+    mask = O.prune_n4_magnitude(w, 2)
+    p = O.pack_2bitcsr(w, mask, 2, 0, O.VAL_FP16)
+    W = O.dense_from_packed(p)
+    assert np.array_equal(W, np.where(mask == 1, w.astype(np.float64), 0.0))
+    assert np.array_equal(O.mask_from_packed(p), mask)
+
+
+def test_padding_slots_and_fp16_idempotence():
+    w = _rand_w(16, 128, 22)
+    mask = O.prune_n4_magnitude(w, 2)
+    mask[3, 8:12] = [0, 0, 1, 0]             # an under-full group: padded with offset 0
+    mask[4, :] = 0                            # an empty row: every group padded with 0,1
+    for kind, g in [(O.VAL_INT4, 64), (O.VAL_FP16, 0)]:
+        p = O.pack_2bitcsr(w, mask, 2, g, kind)
+        W1, m1 = O.dense_from_packed(p), O.mask_from_packed(p)
+        assert np.all(m1 >= mask) and np.all(m1.reshape(16, 32, 4).sum(axis=2) == 2)
+        assert np.all(W1[(m1 == 1) & (mask == 0)] == 0)          # padding decodes to exact zero
+        assert m1[3, 8:12].tolist() == [1, 0, 1, 0]
+        assert np.array_equal(m1[4], np.tile([1, 1, 0, 0], 32))
+    # FP16 values: decoding and packing again reproduces every buffer byte for byte
+    p = O.pack_2bitcsr(w, mask, 2, 0, O.VAL_FP16)
+    p2 = O.pack_2bitcsr(O.dense_from_packed(p).astype(np.float16), O.mask_from_packed(p), 2, 0, O.VAL_FP16)
+    for k in ("row_ptr", "values", "idx"):
+        assert np.array_equal(p[k], p2[k])
+
+
+def test_lossless_grid_round_trip():
+    # weights exactly on an fp16-exact grid s0*{-z..15-z} survive quantisation
+    rng = np.random.default_rng(5)
+    s0, z0 = 0.125, 6
+    codes = rng.integers(0, 16, size=(8, 64))
+    codes[:, 0], codes[:, 1] = 0, 15         # make every group span the full range
+    codes[:, 32], codes[:, 33] = 0, 15
+    w = (s0 * (codes - z0)).astype(np.float16)
+    mask = np.ones_like(codes, dtype=np.uint8)
+    p = O.pack_2bitcsr(w, mask, 4, 32, O.VAL_INT4)
+    assert np.array_equal(O.dense_from_packed(p), w.astype(np.float64))
+    assert np.all(p["qparams"][:, :, 0].view(np.float16) == np.float16(s0))
+    assert np.all(p["qparams"][:, :, 1].view(np.float16) == np.float16(z0))
+
+
+# ----------------------------------------------------------------- quantiser bounds
+def test_quantiser_error_bounds():
+    w = _rand_w(32, 256, 31)
+    n, g = 2, 128
+    mask = O.prune_n4_magnitude(w, n)
+    p = O.pack_2bitcsr(w, mask, n, g, O.VAL_INT4)
+    col, w_hat, q = O.decode_2bitcsr(p)
+    assert q.min() >= 0 and q.max() <= 15
+    s = p["qparams"][:, :, 0].view(np.float16).astype(np.float64)
+    z = p["qparams"][:, :, 1].view(np.float16).astype(np.float64)
+    rows = np.arange(32)[:, None]
+    v = w.astype(np.float64)[rows, col]
+    s_slot, z_slot = s[rows, col // g], z[rows, col // g]
+    unclamped = np.rint(v / s_slot) + z_slot
+    inside = (unclamped >= 0) & (unclamped <= 15)
+    err = np.abs(v - w_hat)
+    assert np.all(err[inside] <= s_slot[inside] / 2 + 1e-12)
+    assert np.all(err <= 1.5 * s_slot + 1e-12)
+    # extremes land on code 0 / 15 (within one step after the scale is rounded)
+    for r in range(32):
+        for G in range(2):
+            sel = (col[r] // g) == G
+            assert q[r][sel].min() <= 1 and q[r][sel].max() >= 14
+
+
+def test_all_zero_group_and_zero_mask():
+    w = np.zeros((4, 64), dtype=np.float16)
+    p = O.pack_2bitcsr(w, np.zeros((4, 64), dtype=np.uint8), 2, 32, O.VAL_INT4)
+    assert np.all(p["qparams"][:, :, 0].view(np.float16) == 1.0)
+    assert np.all(p["qparams"][:, :, 1] == 0) and np.all(p["values"] == 0)
+    y, a = O.gemv(p, _rand_x(64, 1))
+    assert np.all(y == 0) and np.all(a == 0)
+    # a non-zero matrix under an all-zero mask also multiplies to exactly zero
+    w2 = _rand_w(4, 64, 9)
+    for kind, g in [(0, 32), (1, 0)]:
+        p2 = O.pack_2bitcsr(w2, np.zeros((4, 64), dtype=np.uint8), 2, g, kind)
+        y, _ = O.gemv(p2, _rand_x(64, 2))
+        assert np.all(y == 0)
+
+
+# ----------------------------------------------------------------- the product
+def _python_loops_gemv(p, x):
+    """Decode and multiply with nothing but Python integers and floats."""
+    R, K, n, g = p["rows"], p["cols"], p["n_keep"], p["group"]
+    S = n * K // 4
+    xs = [float(v) for v in x]
+    ys = []
+    for r in range(R):
+        acc = 0.0
+        for j in range(S):
+            t = int(p["row_ptr"][r]) + j
+            off = (int(p["idx"][t // 8]) >> (2 * (t % 8))) & 3
+            c = 4 * (j // n) + off
+            if p["val_kind"] == O.VAL_FP16:
+                wv = float(p["values"].view(np.float16)[t])
+            else:
+                byte = int(p["values"][t // 2])
+                qv = (byte >> 4) if t % 2 else (byte & 15)
+                s = float(p["qparams"][r, c // g, 0:1].view(np.float16)[0])
+                z = float(p["qparams"][r, c // g, 1:2].view(np.float16)[0])
+                wv = s * (qv - z)
+            acc += wv * xs[c]
+        ys.append(acc)
+    return np.array(ys)
+
+
+@pytest.mark.parametrize("n,kind,g", [(2, 0, 32), (1, 0, 16), (2, 1, 0), (1, 1, 0)])
+def test_gemv_against_python_loops_and_dense_matmul(n, kind, g):
+    R, K = 8, 32
+    w = _rand_w(R, K, 40 + n)
+    x = _rand_x(K, 41)
+    p = O.pack_2bitcsr(w, O.prune_n4_magnitude(w, n), n, g, kind)
+    y, a = O.gemv(p, x)
+    np.testing.assert_allclose(y, _python_loops_gemv(p, x), rtol=0, atol=1e-12)
+    W = O.dense_from_packed(p)
+    np.testing.assert_allclose(y, W @ x.astype(np.float64), rtol=0, atol=1e-12)
+    np.testing.assert_allclose(a, np.abs(W) @ np.abs(x.astype(np.float64)), rtol=0, atol=1e-12)
+
+
+def test_gemv_config1_against_scipy_csr():
+    seed = synth.seed_for(1)
+    w = synth.weights(1024, 1024, seed)
+    x = synth.activations(1024, seed)
+    p = O.pack_2bitcsr(w, O.prune_n4_magnitude(w, 2), 2, 128, O.VAL_INT4)
+    y, _ = O.gemv(p, x)
+    W = O.dense_from_packed(p)
+    assert (W != 0).sum() <= 1024 * 512
+    y_csr = scipy.sparse.csr_matrix(W) @ x.astype(np.float64)
+    np.testing.assert_allclose(y, y_csr, rtol=0, atol=1e-10)
+
+
+def test_special_inputs():
+    R, K = 16, 64
+    w = _rand_w(R, K, 50)
+    p = O.pack_2bitcsr(w, O.prune_n4_magnitude(w, 2), 2, 32, O.VAL_INT4)
+    W = O.dense_from_packed(p)
+    for j in (0, 17, 63):                      # one-hot x picks column j
+        e = np.zeros(K, dtype=np.float16)
+        e[j] = 1
+        assert np.array_equal(O.gemv(p, e)[0], W[:, j])
+    y1, _ = O.gemv(p, np.ones(K, dtype=np.float16))
+    np.testing.assert_allclose(y1, W.sum(axis=1), atol=1e-12)
+    x = _rand_x(K, 51)
+    assert np.array_equal(O.gemv(p, (2 * x).astype(np.float16))[0], 2 * O.gemv(p, x)[0])
+
+
+def test_smallm_equals_independent_gemvs():
+    R, K, M = 16, 64, 5
+    w = _rand_w(R, K, 60)
+    X = np.random.default_rng(61).standard_normal((M, K)).astype(np.float16)
+    p = O.pack_2bitcsr(w, O.prune_n4_magnitude(w, 2), 2, 32, O.VAL_INT4)
+    Y, A = O.gemm_smallm(p, X)
+    assert Y.shape == (M, R)
+    for m in range(M):
+        y, a = O.gemv(p, X[m])
+        assert np.array_equal(Y[m], y) and np.array_equal(A[m], a)
+    np.testing.assert_allclose(Y, X.astype(np.float64) @ O.dense_from_packed(p).T, atol=1e-12)
+
+
+def test_full_mask_sparse_path_equals_dense_int4_path():
+    # n_keep = 4 keeps everything: 2bit-CSR and the dense INT4 format hold the same codes
+    R, K, g = 8, 128, 64
+    w = _rand_w(R, K, 70)
+    x = _rand_x(K, 71)
+    p = O.pack_2bitcsr(w, np.ones((R, K), dtype=np.uint8), 4, g, O.VAL_INT4)
+    qb, qp = O.quant_int4_dense(w, g)
+    assert np.array_equal(qb.reshape(-1), p["values"])
+    assert np.array_equal(qp, p["qparams"])
+    y_s, a_s = O.gemv(p, x)
+    y_d, a_d = O.int4_gemv(qb, qp, g, x)
+    np.testing.assert_allclose(y_s, y_d, atol=1e-12)
+    np.testing.assert_allclose(a_s, a_d, atol=1e-12)
+    # dense path against its own brute force from the nibbles
+    q = np.array([[(int(qb[r, c // 2]) >> (4 * (c % 2))) & 15 for c in range(K)] for r in range(R)], dtype=np.float64)
+    s = qp[:, :, 0].view(np.float16).astype(np.float64)
+    z = qp[:, :, 1].view(np.float16).astype(np.float64)
+    Wd = np.array([[s[r, c // g] * (q[r, c] - z[r, c // g]) for c in range(K)] for r in range(R)])
+    np.testing.assert_allclose(y_d, Wd @ x.astype(np.float64), atol=1e-12)
+    # and the quantised matrix stays within half a step of the original
+    assert np.all(np.abs(Wd - w.astype(np.float64)) <= 0.5 * np.repeat(s, g, axis=1) * 1.0001 + 1e-12)
+
+
+def test_single_rounding_of_scale():
+    # (xmax-xmin)/15 chosen so that rounding through float32 first would differ
+    # from one direct float64 -> float16 rounding (a double-rounding trap).
+    target = np.float64(1.0) + 2.0 ** -11 + 2.0 ** -30    # just above an fp16 tie
+    assert np.float16(target) != np.float16(np.float32(target))
+    s16, z = O.quant_params(np.array([0.0]), np.array([15.0 * target]))
+    assert s16[0] == np.float16(1.0) + np.float16(2.0 ** -10)
+
+
+def test_synth_is_seeded():
+    a = synth.weights(4, 32, synth.seed_for(1))
+    b = synth.weights(4, 32, synth.seed_for(1))
+    assert np.array_equal(a.view(np.uint16), b.view(np.uint16))
+    assert abs(float(synth.weights(256, 256, 3).astype(np.float64).std()) - 0.02) < 0.001
+    assert len(synth.sparse_layers()) == 16
