@@ -1,0 +1,156 @@
+/* egt.h - C ABI of the SparseGemv library for MI355X (gfx950).
+ *
+ * The library implements the decode-time product y = W.x of the paper's
+ * "Revised Kernel" section (Sec. 3.3): W is a weight matrix compressed offline by
+ * group-wise INT4 quantisation (Sec. 3.2 "Adaptive Group-Wise Quantization") and
+ * N:4 semi-structured pruning (Sec. 3.2 "Sparsification"), stored in the
+ * index-compressed CSR variant of Sec. 3.3 "Sparse Index Structure" (called
+ * 2bit-CSR here); x is an FP16 activation vector.  A small-M form serves the
+ * parallel verification step of Sec. 3.4, where several candidate tokens pass
+ * through the same linear layers at once.
+ *
+ * General rules
+ *  - Plain C linkage, no exceptions cross the boundary, no global state; every
+ *    call is thread-safe with respect to the library (buffers are the caller's).
+ *  - The library never allocates or frees device memory and keeps no handles.
+ *    Every buffer is owned by the caller.
+ *  - "HOST" functions take host pointers and run on the CPU.  "DEVICE" functions
+ *    take device pointers (16-byte aligned), enqueue kernels on `stream`
+ *    (a hipStream_t passed as void*, NULL = the default stream) and return
+ *    without synchronising.
+ *  - Argument errors are detected on the host before anything is written or
+ *    launched; outputs are untouched when a call returns an error.
+ *  - FP16 numbers cross the boundary as their IEEE binary16 bit patterns
+ *    (uint16_t).
+ *
+ * The 2bit-CSR format (canonical layout)
+ *    R rows, K columns, K % 32 == 0.  Columns are cut into 4-groups [4c, 4c+4).
+ *    n = n_keep (1..4) entries of every 4-group own a slot; a row has
+ *    S = n*K/4 slots in ascending column order and the in-group offsets (0..3)
+ *    of one 4-group are strictly ascending.
+ *      row_ptr  uint32[R+1]   first slot of each row (slot units); rows are
+ *                             uniform, so row_ptr[r] = r*S.
+ *      idx      uint16[T/8]   T = R*S.  Slot t lives in word t>>3 at bits
+ *                             [2*(t&7), 2*(t&7)+1]: the first slot of a word
+ *                             sits in its least-significant bits, so
+ *                             offset = (word >> 2*(t&7)) & 3.
+ *      values   INT4: uint8[T/2], slot t in byte t>>1, low nibble for even t.
+ *               FP16: uint16[T], raw bits of the kept weight (+0.0 for padding).
+ *      qparams  INT4 only: uint16[R][K/g][2] = FP16 bits of {scale s, zero z} of
+ *               the group of g consecutive *dense* columns; z is an integer
+ *               0..15; a code q decodes to s*(q - z).
+ *    Quantiser (per row and group, over the kept values V of the group):
+ *      xmin = min(0, min V), xmax = max(0, max V),
+ *      s = fp16((xmax - xmin)/15) rounded once to nearest-even, s = 1 if that is 0,
+ *      z = clamp(rint(-xmin/s), 0, 15), q = clamp(rint(v/s) + z, 0, 15),
+ *      all in binary64 with rint = ties-to-even.
+ *    A 4-group whose mask keeps fewer than n entries is padded with the
+ *    smallest unused offsets; padding slots hold an exact zero (q = z or +0.0).
+ */
+#ifndef EGT_H
+#define EGT_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  EGT_OK = 0,
+  EGT_ERR_NULL = 1,        /* a required pointer is NULL                                  */
+  EGT_ERR_SHAPE = 2,       /* rows/cols/n_keep/group/M/leading dimension out of range     */
+  EGT_ERR_MASK = 3,        /* a 4-group of the mask keeps more than n_keep entries        */
+  EGT_ERR_NONFINITE = 4,   /* a kept weight is NaN or Inf                                 */
+  EGT_ERR_BUFFER = 5,      /* inconsistent buffer contents (e.g. row_ptr not uniform)     */
+  EGT_ERR_UNSUPPORTED = 6, /* valid format, but no kernel covers it                       */
+  EGT_ERR_HIP = 7          /* the HIP runtime reported an error at launch                 */
+} egt_status;
+
+typedef enum { EGT_VAL_INT4 = 0, EGT_VAL_FP16 = 1 } egt_val_kind;
+
+/* A view of one matrix in 2bit-CSR.  The struct itself lives in host memory.
+ * Its pointer fields are host pointers for pack/unpack and device pointers for
+ * the GEMV calls.  The library never owns them. */
+typedef struct {
+  int32_t rows, cols;    /* R = output features, K = input features (reduction axis) */
+  int32_t n_keep;        /* n of n:4                                                  */
+  int32_t group_size;    /* g, along dense K; INT4 only; 0 for FP16 values            */
+  int32_t val_kind;      /* egt_val_kind                                              */
+  uint32_t *row_ptr;     /* [R+1]                                                     */
+  void *values;          /* INT4: T/2 bytes; FP16: 2*T bytes                          */
+  uint16_t *idx;         /* [T/8]                                                     */
+  uint16_t *qparams;     /* INT4: [R][K/g][2]; FP16 values: NULL                      */
+} egt_2bitcsr;
+
+/* Text for a status code (static storage, never NULL). */
+const char *egt_status_str(int status);
+
+/* HOST.  Byte sizes of the four buffers {row_ptr, values, idx, qparams} of a
+ * matrix (Sec. 3.3 "Sparse Index Structure").  EGT_ERR_SHAPE unless
+ * cols % 32 == 0, n_keep in 1..4 and, for INT4, group > 0, group % 4 == 0 and
+ * cols % group == 0 (group must be 0 for FP16 values). */
+egt_status egt_2bitcsr_sizes(int rows, int cols, int n_keep, int group, int val_kind,
+                             size_t bytes[4]);
+
+/* HOST.  N:4 magnitude pruning mask (Sec. 3.2 "Sparsification"; Eq. (3) with a
+ * constant activation norm and gradient reduces to |W_ij|).  w: rows x cols FP16
+ * bits, row stride ldw elements.  mask: rows x cols bytes, row stride ldm, set to
+ * 1 for the n_keep entries of largest magnitude of every 4-group (equal
+ * magnitudes: lower column wins; -0.0 has magnitude 0), else 0.  cols % 4 == 0. */
+egt_status egt_prune_n4(const uint16_t *w, int64_t ldw, int rows, int cols, int n_keep,
+                        uint8_t *mask, int64_t ldm);
+
+/* HOST.  Encoder of Sec. 3.3 "Sparse Index Structure" fused with the quantiser of
+ * Sec. 3.2: dense FP16 W + 0/1 mask + group size -> 2bit-CSR.  `out` has its five
+ * scalars ignored on input and filled on success; its four buffers are
+ * caller-allocated HOST memory of the sizes egt_2bitcsr_sizes reports (qparams
+ * may be NULL for FP16 values).  Errors: EGT_ERR_MASK when a 4-group keeps more
+ * than n_keep entries, EGT_ERR_NONFINITE when a kept weight is NaN/Inf. */
+egt_status egt_pack_2bitcsr(const uint16_t *w, int64_t ldw, const uint8_t *mask, int64_t ldm,
+                            int rows, int cols, int n_keep, int group, int val_kind,
+                            egt_2bitcsr *out);
+
+/* HOST.  Inverse of the encoder: writes the decoded matrix (FP16 bits; s*(q-z)
+ * rounded once to FP16 for INT4 values; 0 where no slot exists) and the mask of
+ * positions that own a slot.  Either output may be NULL.  EGT_ERR_BUFFER when
+ * row_ptr is not the uniform progression or offsets are not ascending. */
+egt_status egt_unpack_2bitcsr(const egt_2bitcsr *in, uint16_t *w_dense, int64_t ldw,
+                              uint8_t *mask, int64_t ldm);
+
+/* HOST.  Dense group-wise INT4 quantiser of the earlier "Gemv" kernel that
+ * Sec. 3.3 starts from: every column kept, same quantiser as above.
+ * q: rows x cols/2 bytes (column c in byte c>>1, low nibble for even c);
+ * qparams: [rows][cols/group][2] FP16 bits.  cols % group == 0, group % 8 == 0. */
+egt_status egt_quant_int4(const uint16_t *w, int64_t ldw, int rows, int cols, int group,
+                          uint8_t *q, uint16_t *qparams);
+
+/* DEVICE.  y[r] = sum_c s(r,c/g) * (q(r,c) - z(r,c/g)) * x[c]: the dense
+ * weight-only INT4 GEMV (Sec. 3.3, "previous generation of Gemv").  x: cols FP16,
+ * y: rows FP16 (FP32 accumulation, one rounding at the end). */
+egt_status egt_int4_gemv(const uint8_t *q, const uint16_t *qparams, int rows, int cols,
+                         int group, const uint16_t *x, uint16_t *y, void *stream);
+
+/* DEVICE.  SparseGemv (Sec. 3.3 "Computational Acceleration"): y = W.x for W in
+ * 2bit-CSR with INT4 or FP16 values.  x: cols FP16, y: rows FP16.  A row whose
+ * row_ptr entry is not r*S yields NaN in y[r] (the kernel checks it). */
+egt_status egt_sparse_gemv(const egt_2bitcsr *w, const uint16_t *x, uint16_t *y, void *stream);
+
+/* DEVICE.  Small-M form for tree-based parallel verification (Sec. 3.4): the M
+ * candidate rows of X go through the same compressed matrix in one call.
+ * X: M x K row-major with row stride ldx; Y: M x R row-major with row stride ldy;
+ * Y[m][r] = sum_k W[r][k] * X[m][k]; 1 <= M <= 64. */
+egt_status egt_sparse_gemm_smallm(const egt_2bitcsr *w, const uint16_t *X, int64_t ldx,
+                                  uint16_t *Y, int64_t ldy, int M, void *stream);
+
+/* DEVICE.  Measurement aid: streams `bytes` (a multiple of 16) from `src` with
+ * 128-bit loads and folds them into one 32-bit word per workgroup written to
+ * `sink` (at least 4096 words).  Gives the read bandwidth a kernel of that size
+ * can reach at all on the device; not part of the method. */
+egt_status egt_stream_read(const void *src, size_t bytes, uint32_t *sink, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* EGT_H */

@@ -1,0 +1,228 @@
+"""Thin ctypes binding of libegt.so: argument marshalling only.
+
+Host functions take and return numpy arrays; device functions take torch tensors
+(used for device memory and the current stream, nothing else).  There is no CPU
+fallback: if the built library is missing, loading raises.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from dataclasses import dataclass
+
+import numpy as np
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_PKG, "libegt.so")
+
+VAL_INT4 = 0
+VAL_FP16 = 1
+
+SYMBOLS = (
+    "egt_status_str", "egt_2bitcsr_sizes", "egt_prune_n4", "egt_pack_2bitcsr",
+    "egt_unpack_2bitcsr", "egt_quant_int4", "egt_int4_gemv", "egt_sparse_gemv",
+    "egt_sparse_gemm_smallm", "egt_stream_read",
+)
+
+
+class EgtError(RuntimeError):
+    def __init__(self, status: int, text: str):
+        super().__init__(f"egt status {status}: {text}")
+        self.status = status
+
+
+class View(C.Structure):
+    """Mirror of `egt_2bitcsr`."""
+    _fields_ = [("rows", C.c_int32), ("cols", C.c_int32), ("n_keep", C.c_int32),
+                ("group_size", C.c_int32), ("val_kind", C.c_int32),
+                ("row_ptr", C.c_void_p), ("values", C.c_void_p), ("idx", C.c_void_p),
+                ("qparams", C.c_void_p)]
+
+
+_lib = None
+
+
+def lib() -> C.CDLL:
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(f"{LIB_PATH} is not built: run `python -m paper_2605_11582_amd.build` "
+                               "(there is no fallback path)")
+        L = C.CDLL(LIB_PATH)
+        L.egt_status_str.restype = C.c_char_p
+        L.egt_status_str.argtypes = [C.c_int]
+        L.egt_2bitcsr_sizes.argtypes = [C.c_int] * 5 + [C.POINTER(C.c_size_t)]
+        L.egt_prune_n4.argtypes = [C.c_void_p, C.c_int64, C.c_int, C.c_int, C.c_int, C.c_void_p, C.c_int64]
+        L.egt_pack_2bitcsr.argtypes = [C.c_void_p, C.c_int64, C.c_void_p, C.c_int64, C.c_int, C.c_int,
+                                       C.c_int, C.c_int, C.c_int, C.POINTER(View)]
+        L.egt_unpack_2bitcsr.argtypes = [C.POINTER(View), C.c_void_p, C.c_int64, C.c_void_p, C.c_int64]
+        L.egt_quant_int4.argtypes = [C.c_void_p, C.c_int64, C.c_int, C.c_int, C.c_int, C.c_void_p, C.c_void_p]
+        L.egt_int4_gemv.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_void_p,
+                                    C.c_void_p, C.c_void_p]
+        L.egt_sparse_gemv.argtypes = [C.POINTER(View), C.c_void_p, C.c_void_p, C.c_void_p]
+        L.egt_sparse_gemm_smallm.argtypes = [C.POINTER(View), C.c_void_p, C.c_int64, C.c_void_p,
+                                             C.c_int64, C.c_int, C.c_void_p]
+        L.egt_stream_read.argtypes = [C.c_void_p, C.c_size_t, C.c_void_p, C.c_void_p]
+        for name in SYMBOLS:
+            if name != "egt_status_str":
+                getattr(L, name).restype = C.c_int
+        _lib = L
+    return _lib
+
+
+def status_str(status: int) -> str:
+    return lib().egt_status_str(int(status)).decode()
+
+
+def _check(status: int) -> None:
+    if status != 0:
+        raise EgtError(status, status_str(status))
+
+
+def _np_ptr(a: np.ndarray) -> int:
+    return a.ctypes.data
+
+
+def _f16_bits(a: np.ndarray) -> np.ndarray:
+    a = np.asarray(a)
+    if a.dtype == np.float16:
+        a = a.view(np.uint16)
+    if a.dtype != np.uint16:
+        raise TypeError("expected float16 or its uint16 bits")
+    return a
+
+
+def _row_major(a: np.ndarray) -> np.ndarray:
+    if a.ndim != 2 or a.strides[1] != a.itemsize or a.strides[0] % a.itemsize:
+        a = np.ascontiguousarray(a)
+    return a
+
+
+def _ld(a: np.ndarray) -> int:
+    """Leading dimension in elements (numpy reports stride 0 for empty arrays)."""
+    return max(a.strides[0] // a.itemsize, a.shape[1])
+
+
+# ------------------------------------------------------------------ host calls
+def sizes(rows: int, cols: int, n_keep: int, group: int, val_kind: int):
+    out = (C.c_size_t * 4)()
+    _check(lib().egt_2bitcsr_sizes(rows, cols, n_keep, group, val_kind, out))
+    return tuple(int(v) for v in out)
+
+
+def prune_n4(w: np.ndarray, n_keep: int) -> np.ndarray:
+    w = _row_major(_f16_bits(w))
+    rows, cols = w.shape
+    mask = np.empty((rows, cols), dtype=np.uint8)
+    _check(lib().egt_prune_n4(_np_ptr(w), _ld(w), rows, cols, n_keep, _np_ptr(mask), cols))
+    return mask
+
+
+@dataclass
+class Packed:
+    """One matrix in 2bit-CSR; the four buffers are numpy (host) or torch (device)."""
+    rows: int
+    cols: int
+    n_keep: int
+    group: int
+    val_kind: int
+    row_ptr: object
+    values: object
+    idx: object
+    qparams: object
+
+    def _ptr(self, b):
+        if b is None:
+            return None
+        return b.ctypes.data if isinstance(b, np.ndarray) else b.data_ptr()
+
+    def view(self) -> View:
+        return View(self.rows, self.cols, self.n_keep, self.group, self.val_kind,
+                    self._ptr(self.row_ptr), self._ptr(self.values), self._ptr(self.idx),
+                    self._ptr(self.qparams))
+
+    def nbytes(self) -> int:
+        return sum(sizes(self.rows, self.cols, self.n_keep, self.group, self.val_kind))
+
+    def to(self, device) -> "Packed":
+        import torch
+        def up(b):
+            if b is None:
+                return None
+            return torch.from_numpy(np.ascontiguousarray(b).view(np.uint8).reshape(-1)).to(device)
+        return Packed(self.rows, self.cols, self.n_keep, self.group, self.val_kind,
+                      up(self.row_ptr), up(self.values), up(self.idx), up(self.qparams))
+
+
+def pack_2bitcsr(w: np.ndarray, mask: np.ndarray, n_keep: int, group: int, val_kind: int) -> Packed:
+    w = _row_major(_f16_bits(w))
+    mask = _row_major(np.asarray(mask, dtype=np.uint8))
+    rows, cols = w.shape
+    if mask.shape != w.shape:
+        raise ValueError("mask shape")
+    b = sizes(rows, cols, n_keep, group, val_kind)
+    row_ptr = np.empty(b[0] // 4, dtype=np.uint32)
+    values = np.empty(b[1], dtype=np.uint8)
+    idx = np.empty(b[2] // 2, dtype=np.uint16)
+    qparams = np.empty((rows, cols // group, 2), dtype=np.uint16) if val_kind == VAL_INT4 else None
+    p = Packed(rows, cols, n_keep, group, val_kind, row_ptr, values, idx, qparams)
+    v = p.view()
+    _check(lib().egt_pack_2bitcsr(_np_ptr(w), _ld(w), _np_ptr(mask), _ld(mask),
+                                  rows, cols, n_keep, group, val_kind, C.byref(v)))
+    return p
+
+
+def unpack_2bitcsr(p: Packed):
+    w = np.empty((p.rows, p.cols), dtype=np.uint16)
+    mask = np.empty((p.rows, p.cols), dtype=np.uint8)
+    v = p.view()
+    _check(lib().egt_unpack_2bitcsr(C.byref(v), _np_ptr(w), p.cols, _np_ptr(mask), p.cols))
+    return w.view(np.float16), mask
+
+
+def quant_int4(w: np.ndarray, group: int):
+    w = _row_major(_f16_bits(w))
+    rows, cols = w.shape
+    if cols % 2 or group <= 0 or cols % group:
+        _check(2)
+    q = np.empty((rows, cols // 2), dtype=np.uint8)
+    qparams = np.empty((rows, cols // group, 2), dtype=np.uint16)
+    _check(lib().egt_quant_int4(_np_ptr(w), _ld(w), rows, cols, group, _np_ptr(q), _np_ptr(qparams)))
+    return q, qparams
+
+
+# ------------------------------------------------------------------ device calls
+def _stream_ptr(stream=None) -> int:
+    import torch
+    s = stream if stream is not None else torch.cuda.current_stream()
+    return int(s.cuda_stream)
+
+
+def _dev(t):
+    if not t.is_cuda or not t.is_contiguous():
+        raise ValueError("expected a contiguous device tensor")
+    return t.data_ptr()
+
+
+def int4_gemv(q, qparams, rows: int, cols: int, group: int, x, y, stream=None) -> None:
+    """q, qparams, x, y: device tensors (uint8 / int16-viewable / float16 / float16)."""
+    _check(lib().egt_int4_gemv(_dev(q), _dev(qparams), rows, cols, group, _dev(x), _dev(y),
+                               _stream_ptr(stream)))
+
+
+def sparse_gemv(p: Packed, x, y, stream=None) -> None:
+    v = p.view()
+    _check(lib().egt_sparse_gemv(C.byref(v), _dev(x), _dev(y), _stream_ptr(stream)))
+
+
+def sparse_gemm_smallm(p: Packed, X, Y, stream=None) -> None:
+    """X: (M, K) float16 device tensor, Y: (M, R) float16 device tensor; rows may be strided."""
+    if X.dim() != 2 or Y.dim() != 2 or X.stride(1) != 1 or Y.stride(1) != 1:
+        raise ValueError("X and Y must be row-major 2-D tensors")
+    v = p.view()
+    _check(lib().egt_sparse_gemm_smallm(C.byref(v), X.data_ptr(), X.stride(0), Y.data_ptr(),
+                                        Y.stride(0), X.shape[0], _stream_ptr(stream)))
+
+
+def stream_read(src, nbytes: int, sink, stream=None) -> None:
+    _check(lib().egt_stream_read(_dev(src), nbytes, _dev(sink), _stream_ptr(stream)))

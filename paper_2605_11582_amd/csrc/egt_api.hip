@@ -1,0 +1,95 @@
+// Device entry points of the C ABI: argument checks on the host, then dispatch to
+// a kernel.  Nothing here synchronises or allocates.
+#include "egt_device.h"
+
+namespace {
+
+egt_status check_view(const egt_2bitcsr *w) {
+  if (!w) return EGT_ERR_NULL;
+  if (w->rows < 0 || w->cols < 0 || w->cols % 32 != 0) return EGT_ERR_SHAPE;
+  if (w->n_keep < 1 || w->n_keep > 4) return EGT_ERR_SHAPE;
+  if (w->val_kind == EGT_VAL_INT4) {
+    if (w->group_size <= 0 || w->group_size % 4 != 0 || w->cols % w->group_size != 0)
+      return EGT_ERR_SHAPE;
+    if (!w->qparams) return EGT_ERR_NULL;
+  } else if (w->val_kind == EGT_VAL_FP16) {
+    if (w->group_size != 0) return EGT_ERR_SHAPE;
+  } else {
+    return EGT_ERR_SHAPE;
+  }
+  if ((uint64_t)w->rows * (uint64_t)w->n_keep * (uint64_t)(w->cols / 4) >= (1ull << 32))
+    return EGT_ERR_SHAPE;
+  if (!w->row_ptr || !w->values || !w->idx) return EGT_ERR_NULL;
+  return EGT_OK;
+}
+
+inline bool aligned16(const void *p) { return ((uintptr_t)p & 15u) == 0; }
+
+// Streams `n16` 16-byte words; every workgroup folds what it read into one word.
+__global__ __launch_bounds__(256) void k_stream_read(const uint4 *__restrict__ src, size_t n16,
+                                                      uint32_t *__restrict__ sink) {
+  uint32_t acc = 0;
+  const size_t stride = (size_t)gridDim.x * blockDim.x;
+  size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  for (; i + 3 * stride < n16; i += 4 * stride) {
+    const uint4 a = src[i], b = src[i + stride], c = src[i + 2 * stride], d = src[i + 3 * stride];
+    acc ^= a.x ^ a.y ^ a.z ^ a.w ^ b.x ^ b.y ^ b.z ^ b.w ^ c.x ^ c.y ^ c.z ^ c.w ^ d.x ^ d.y ^ d.z ^ d.w;
+  }
+  for (; i < n16; i += stride) {
+    const uint4 a = src[i];
+    acc ^= a.x ^ a.y ^ a.z ^ a.w;
+  }
+  for (int o = 32; o > 0; o >>= 1) acc ^= __shfl_xor(acc, o, 64);
+  __shared__ uint32_t part[4];
+  if ((threadIdx.x & 63) == 0) part[threadIdx.x >> 6] = acc;
+  __syncthreads();
+  if (threadIdx.x == 0) sink[blockIdx.x] = part[0] ^ part[1] ^ part[2] ^ part[3];
+}
+
+}  // namespace
+
+extern "C" {
+
+egt_status egt_int4_gemv(const uint8_t *q, const uint16_t *qparams, int rows, int cols, int group,
+                         const uint16_t *x, uint16_t *y, void *stream) {
+  if (!q || !qparams || !x || !y) return EGT_ERR_NULL;
+  if (rows < 0 || cols < 0 || group <= 0 || group % 8 != 0 || cols % group != 0)
+    return EGT_ERR_SHAPE;
+  if (!aligned16(q) || !aligned16(qparams) || !aligned16(x)) return EGT_ERR_BUFFER;
+  const hipError_t e = egt::launch_int4(q, qparams, rows, cols, group, x, y, (hipStream_t)stream);
+  return e == hipSuccess ? EGT_OK : EGT_ERR_HIP;
+}
+
+egt_status egt_sparse_gemm_smallm(const egt_2bitcsr *w, const uint16_t *X, int64_t ldx,
+                                  uint16_t *Y, int64_t ldy, int M, void *stream) {
+  const egt_status st = check_view(w);
+  if (st != EGT_OK) return st;
+  if (!X || !Y) return EGT_ERR_NULL;
+  if (M < 1 || M > 64 || ldx < w->cols || ldy < w->rows) return EGT_ERR_SHAPE;
+  if (!aligned16(w->row_ptr) || !aligned16(w->values) || !aligned16(w->idx) ||
+      (w->qparams && !aligned16(w->qparams)) || !aligned16(X))
+    return EGT_ERR_BUFFER;
+  const hipError_t e = egt::launch_sparse(*w, X, ldx, Y, ldy, M, (hipStream_t)stream);
+  return e == hipSuccess ? EGT_OK : EGT_ERR_HIP;
+}
+
+egt_status egt_sparse_gemv(const egt_2bitcsr *w, const uint16_t *x, uint16_t *y, void *stream) {
+  if (!w) return EGT_ERR_NULL;
+  return egt_sparse_gemm_smallm(w, x, w->cols, y, w->rows, 1, stream);
+}
+
+egt_status egt_stream_read(const void *src, size_t bytes, uint32_t *sink, void *stream) {
+  if (!src || !sink) return EGT_ERR_NULL;
+  if (bytes % 16 != 0) return EGT_ERR_SHAPE;
+  if (!aligned16(src)) return EGT_ERR_BUFFER;
+  if (bytes == 0) return EGT_OK;
+  const size_t n16 = bytes / 16;
+  size_t blocks = (n16 + 1023) / 1024;                // 4 x 16 B per thread when large
+  if (blocks > 4096) blocks = 4096;
+  if (blocks < 1) blocks = 1;
+  hipLaunchKernelGGL(k_stream_read, dim3((unsigned)blocks), dim3(256), 0, (hipStream_t)stream,
+                     (const uint4 *)src, n16, sink);
+  return hipGetLastError() == hipSuccess ? EGT_OK : EGT_ERR_HIP;
+}
+
+}  // extern "C"

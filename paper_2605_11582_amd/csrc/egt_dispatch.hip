@@ -1,0 +1,16 @@
+// Kernel selection for the device entry points.
+#include "egt_device.h"
+
+namespace egt {
+
+hipError_t launch_sparse(const egt_2bitcsr &w, const uint16_t *X, int64_t ldx, uint16_t *Y,
+                         int64_t ldy, int M, hipStream_t stream) {
+  return launch_sparse_generic(w, X, ldx, Y, ldy, M, stream);
+}
+
+hipError_t launch_int4(const uint8_t *q, const uint16_t *qparams, int rows, int cols, int group,
+                       const uint16_t *x, uint16_t *y, hipStream_t stream) {
+  return launch_int4_generic(q, qparams, rows, cols, group, x, y, stream);
+}
+
+}  // namespace egt

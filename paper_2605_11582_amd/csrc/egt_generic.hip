@@ -1,0 +1,115 @@
+// Generic (any n_keep, any group size, any K % 32 == 0) kernels of the SparseGemv
+// library.  They follow the format slot by slot with scalar FP32 arithmetic and
+// serve every shape the tuned kernels do not cover.  One wavefront per matrix
+// row; lanes stride over the row's index words.
+#include "egt_device.h"
+
+namespace egt {
+
+// One wave per row, MT activation rows per pass (blockIdx.y selects the M-chunk).
+template <int VAL_KIND, int MT>
+__global__ __launch_bounds__(256) void k_sparse_generic(
+    const uint32_t *__restrict__ row_ptr, const uint8_t *__restrict__ values,
+    const uint16_t *__restrict__ idx, const uint16_t *__restrict__ qparams, int rows, int cols,
+    int n_keep, int group, const __half *__restrict__ X, int64_t ldx, __half *__restrict__ Y,
+    int64_t ldy, int M) {
+  const int lane = threadIdx.x & 63;
+  const int r = blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
+  if (r >= rows) return;
+  const int m0 = blockIdx.y * MT;
+  const uint32_t S = (uint32_t)n_keep * (uint32_t)(cols >> 2);
+  const uint32_t t_row = row_ptr[r];
+  // the format has uniform rows: anything else is reported as NaN, never followed
+  const bool ok = t_row == (uint32_t)r * S;
+  float acc[MT];
+#pragma unroll
+  for (int m = 0; m < MT; ++m) acc[m] = 0.f;
+  const int G = VAL_KIND == EGT_VAL_INT4 ? cols / group : 0;
+  if (ok) {
+    for (uint32_t w = lane; w < (S >> 3); w += 64) {
+      const uint32_t t0 = t_row + 8 * w;
+      const uint32_t iw = idx[t0 >> 3];
+      uint32_t nib = 0;
+      uint4 hv = {0, 0, 0, 0};
+      if (VAL_KIND == EGT_VAL_INT4) nib = *(const uint32_t *)(values + (t0 >> 1));
+      else hv = *(const uint4 *)(values + 2ull * t0);
+      const uint32_t hw[4] = {hv.x, hv.y, hv.z, hv.w};
+#pragma unroll
+      for (int k = 0; k < 8; ++k) {
+        const uint32_t j = 8 * w + k;                       // slot inside the row
+        const int col = 4 * (int)(j / (uint32_t)n_keep) + (int)((iw >> (2 * k)) & 3u);
+        float wv;
+        if (VAL_KIND == EGT_VAL_INT4) {
+          const int q = (nib >> (4 * k)) & 15;
+          const uint16_t *p = qparams + ((size_t)r * G + col / group) * 2;
+          wv = __half2float(__ushort_as_half(p[0])) * ((float)q - __half2float(__ushort_as_half(p[1])));
+        } else {
+          wv = __half2float(__ushort_as_half((uint16_t)(hw[k >> 1] >> (16 * (k & 1)))));
+        }
+#pragma unroll
+        for (int m = 0; m < MT; ++m)
+          if (m0 + m < M) acc[m] = fmaf(wv, __half2float(X[(int64_t)(m0 + m) * ldx + col]), acc[m]);
+      }
+    }
+  }
+#pragma unroll
+  for (int m = 0; m < MT; ++m) {
+    float v = acc[m];
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+    if (lane == 0 && m0 + m < M)
+      Y[(int64_t)(m0 + m) * ldy + r] = ok ? __float2half(v) : __ushort_as_half((uint16_t)0x7E00);
+  }
+}
+
+// Dense group-quantised INT4 GEMV, one wave per row, lanes stride over 8-column words.
+__global__ __launch_bounds__(256) void k_int4_generic(const uint8_t *__restrict__ q,
+                                                       const uint16_t *__restrict__ qparams,
+                                                       int rows, int cols, int group,
+                                                       const __half *__restrict__ x,
+                                                       __half *__restrict__ y) {
+  const int lane = threadIdx.x & 63;
+  const int r = blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
+  if (r >= rows) return;
+  const int G = cols / group;
+  const uint32_t *qr = (const uint32_t *)(q + (size_t)r * (cols >> 1));
+  float acc = 0.f;
+  for (int w = lane; w < (cols >> 3); w += 64) {
+    const uint32_t nib = qr[w];
+    const int c0 = 8 * w;                                   // group % 8 == 0: one group per word
+    const uint16_t *p = qparams + ((size_t)r * G + c0 / group) * 2;
+    const float s = __half2float(__ushort_as_half(p[0])), z = __half2float(__ushort_as_half(p[1]));
+    float part = 0.f;
+#pragma unroll
+    for (int k = 0; k < 8; ++k)
+      part = fmaf((float)((nib >> (4 * k)) & 15) - z, __half2float(x[c0 + k]), part);
+    acc = fmaf(s, part, acc);
+  }
+  for (int o = 32; o > 0; o >>= 1) acc += __shfl_xor(acc, o, 64);
+  if (lane == 0) y[r] = __float2half(acc);
+}
+
+hipError_t launch_sparse_generic(const egt_2bitcsr &w, const uint16_t *X, int64_t ldx, uint16_t *Y,
+                                 int64_t ldy, int M, hipStream_t stream) {
+  if (w.rows == 0) return hipSuccess;
+  const dim3 block(256);
+  const int mt = M == 1 ? 1 : 4;
+  const dim3 grid((w.rows + 3) / 4, (M + mt - 1) / mt);
+#define EGT_GO(KIND, MT)                                                                        \
+  hipLaunchKernelGGL((k_sparse_generic<KIND, MT>), grid, block, 0, stream, w.row_ptr,          \
+                     (const uint8_t *)w.values, w.idx, w.qparams, w.rows, w.cols, w.n_keep,     \
+                     w.group_size, (const __half *)X, ldx, (__half *)Y, ldy, M)
+  if (w.val_kind == EGT_VAL_INT4) { if (mt == 1) EGT_GO(EGT_VAL_INT4, 1); else EGT_GO(EGT_VAL_INT4, 4); }
+  else { if (mt == 1) EGT_GO(EGT_VAL_FP16, 1); else EGT_GO(EGT_VAL_FP16, 4); }
+#undef EGT_GO
+  return hipGetLastError();
+}
+
+hipError_t launch_int4_generic(const uint8_t *q, const uint16_t *qparams, int rows, int cols,
+                               int group, const uint16_t *x, uint16_t *y, hipStream_t stream) {
+  if (rows == 0) return hipSuccess;
+  hipLaunchKernelGGL(k_int4_generic, dim3((rows + 3) / 4), dim3(256), 0, stream, q, qparams, rows,
+                     cols, group, (const __half *)x, (__half *)y);
+  return hipGetLastError();
+}
+
+}  // namespace egt

@@ -1,0 +1,350 @@
+// Host side of the SparseGemv library: shape rules, N:4 magnitude pruning, the
+// group-wise INT4 quantiser and the 2bit-CSR encoder / decoder (Sec. 3.2 and
+// Sec. 3.3 "Sparse Index Structure" of the paper).  Plain C++, no GPU calls.
+#include "egt.h"
+
+#include <algorithm>
+#include <atomic>
+#include <cmath>
+#include <cstring>
+#include <thread>
+#include <vector>
+
+namespace {
+
+// ---------------------------------------------------------------- binary16
+inline double half_to_double(uint16_t h) {
+  const int sign = h >> 15, e = (h >> 10) & 31, m = h & 1023;
+  double v;
+  if (e == 0) v = std::ldexp((double)m, -24);
+  else if (e == 31) v = m ? NAN : INFINITY;
+  else v = std::ldexp((double)(m + 1024), e - 25);
+  return sign ? -v : v;
+}
+
+// One rounding, nearest-even, straight from binary64 (never through binary32).
+inline uint16_t double_to_half(double v) {
+  const uint16_t sign = std::signbit(v) ? 0x8000u : 0u;
+  if (std::isnan(v)) return sign | 0x7E00u;
+  double a = std::fabs(v);
+  if (a >= 65520.0) return sign | 0x7C00u;          // rounds to infinity
+  if (a < std::ldexp(1.0, -14)) {                    // subnormal range: units of 2^-24
+    const double q = std::nearbyint(std::ldexp(a, 24));
+    return sign | (uint16_t)q;                       // q == 1024 is the smallest normal
+  }
+  int e;
+  std::frexp(a, &e);                                 // a = f * 2^e, f in [0.5, 1)
+  e -= 1;                                            // a in [2^e, 2^(e+1))
+  double q = std::nearbyint(std::ldexp(a, 10 - e));  // in [1024, 2048]
+  if (q >= 2048.0) { q = 1024.0; e += 1; }
+  return sign | (uint16_t)(((e + 15) << 10) + ((int)q - 1024));
+}
+
+inline bool half_is_finite(uint16_t h) { return ((h >> 10) & 31) != 31; }
+
+// ---------------------------------------------------------------- threading
+template <class F>
+void parallel_rows(int rows, F &&body) {
+  unsigned hw = std::thread::hardware_concurrency();
+  int nt = (int)std::min<unsigned>(hw ? hw : 1u, 16u);
+  nt = std::max(1, std::min(nt, rows / 64));
+  if (nt <= 1) { body(0, rows); return; }
+  std::vector<std::thread> th;
+  const int chunk = (rows + nt - 1) / nt;
+  for (int t = 0; t < nt; ++t) {
+    const int r0 = t * chunk, r1 = std::min(rows, r0 + chunk);
+    if (r0 >= r1) break;
+    th.emplace_back([&body, r0, r1] { body(r0, r1); });
+  }
+  for (auto &x : th) x.join();
+}
+
+// ---------------------------------------------------------------- shape rules
+egt_status check_shape(int rows, int cols, int n_keep, int group, int val_kind) {
+  if (rows < 0 || cols < 0) return EGT_ERR_SHAPE;
+  if (cols % 32 != 0) return EGT_ERR_SHAPE;
+  if (n_keep < 1 || n_keep > 4) return EGT_ERR_SHAPE;
+  if (val_kind == EGT_VAL_INT4) {
+    if (group <= 0 || group % 4 != 0 || cols % group != 0) return EGT_ERR_SHAPE;
+  } else if (val_kind == EGT_VAL_FP16) {
+    if (group != 0) return EGT_ERR_SHAPE;
+  } else {
+    return EGT_ERR_SHAPE;
+  }
+  const uint64_t slots = (uint64_t)rows * (uint64_t)n_keep * (uint64_t)(cols / 4);
+  if (slots >= (1ull << 32)) return EGT_ERR_SHAPE;   // row_ptr is uint32
+  return EGT_OK;
+}
+
+// Scale and zero point of one group from the extrema of its kept values.
+struct QParam { uint16_t s_bits; double s; int z; };
+inline QParam make_qparam(double vmin, double vmax) {
+  const double xmin = std::min(0.0, vmin), xmax = std::max(0.0, vmax);
+  uint16_t sb = double_to_half((xmax - xmin) / 15.0);
+  if ((sb & 0x7FFF) == 0) sb = 0x3C00;               // s == 0 -> 1.0
+  const double s = half_to_double(sb);
+  double z = std::nearbyint(-xmin / s);
+  z = std::min(15.0, std::max(0.0, z));
+  return {sb, s, (int)z};
+}
+inline int make_code(double v, const QParam &p) {
+  double q = std::nearbyint(v / p.s) + (double)p.z;
+  q = std::min(15.0, std::max(0.0, q));
+  return (int)q;
+}
+
+// Chosen in-group offsets of one 4-group: the kept ones plus, if fewer than n,
+// the smallest unused offsets.  Returns a 4-bit set, or -1 when over-full.
+inline int choose4(const uint8_t *m, int n) {
+  int set = 0, cnt = 0;
+  for (int j = 0; j < 4; ++j) if (m[j]) { set |= 1 << j; ++cnt; }
+  if (cnt > n) return -1;
+  for (int j = 0; j < 4 && cnt < n; ++j) if (!(set >> j & 1)) { set |= 1 << j; ++cnt; }
+  return set;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char *egt_status_str(int status) {
+  switch (status) {
+    case EGT_OK: return "ok";
+    case EGT_ERR_NULL: return "null pointer";
+    case EGT_ERR_SHAPE: return "bad shape";
+    case EGT_ERR_MASK: return "mask keeps more than n_keep entries in a 4-group";
+    case EGT_ERR_NONFINITE: return "non-finite kept weight";
+    case EGT_ERR_BUFFER: return "inconsistent buffer contents";
+    case EGT_ERR_UNSUPPORTED: return "unsupported configuration";
+    case EGT_ERR_HIP: return "HIP runtime error";
+    default: return "unknown status";
+  }
+}
+
+egt_status egt_2bitcsr_sizes(int rows, int cols, int n_keep, int group, int val_kind,
+                             size_t bytes[4]) {
+  if (!bytes) return EGT_ERR_NULL;
+  const egt_status st = check_shape(rows, cols, n_keep, group, val_kind);
+  if (st != EGT_OK) return st;
+  const size_t slots = (size_t)rows * (size_t)n_keep * (size_t)(cols / 4);
+  bytes[0] = 4 * ((size_t)rows + 1);
+  bytes[1] = val_kind == EGT_VAL_INT4 ? slots / 2 : slots * 2;
+  bytes[2] = 2 * (slots / 8);
+  bytes[3] = val_kind == EGT_VAL_INT4 ? 4 * (size_t)rows * (size_t)(cols / group) : 0;
+  return EGT_OK;
+}
+
+egt_status egt_prune_n4(const uint16_t *w, int64_t ldw, int rows, int cols, int n_keep,
+                        uint8_t *mask, int64_t ldm) {
+  if (!w || !mask) return EGT_ERR_NULL;
+  if (rows < 0 || cols < 0 || cols % 4 != 0 || n_keep < 1 || n_keep > 4 || ldw < cols || ldm < cols)
+    return EGT_ERR_SHAPE;
+  parallel_rows(rows, [=](int r0, int r1) {
+    for (int r = r0; r < r1; ++r) {
+      const uint16_t *wr = w + (int64_t)r * ldw;
+      uint8_t *mr = mask + (int64_t)r * ldm;
+      for (int c = 0; c < cols; c += 4) {
+        // |w| ordering of finite binary16 numbers = ordering of the low 15 bits
+        int mag[4];
+        for (int j = 0; j < 4; ++j) mag[j] = wr[c + j] & 0x7FFF;
+        for (int j = 0; j < 4; ++j) {
+          int beats = 0;
+          for (int i = 0; i < 4; ++i) {
+            if (i == j) continue;
+            beats += i < j ? (mag[i] >= mag[j]) : (mag[i] > mag[j]);
+          }
+          mr[c + j] = beats < n_keep ? 1 : 0;
+        }
+      }
+    }
+  });
+  return EGT_OK;
+}
+
+egt_status egt_pack_2bitcsr(const uint16_t *w, int64_t ldw, const uint8_t *mask, int64_t ldm,
+                            int rows, int cols, int n_keep, int group, int val_kind,
+                            egt_2bitcsr *out) {
+  if (!w || !mask || !out) return EGT_ERR_NULL;
+  egt_status st = check_shape(rows, cols, n_keep, group, val_kind);
+  if (st != EGT_OK) return st;
+  if (ldw < cols || ldm < cols) return EGT_ERR_SHAPE;
+  if (!out->row_ptr || !out->values || !out->idx) return EGT_ERR_NULL;
+  if (val_kind == EGT_VAL_INT4 && !out->qparams) return EGT_ERR_NULL;
+
+  // pass 1: validate everything before a single output byte is written
+  std::atomic<int> err(EGT_OK);
+  parallel_rows(rows, [&](int r0, int r1) {
+    for (int r = r0; r < r1 && err.load(std::memory_order_relaxed) == EGT_OK; ++r) {
+      const uint16_t *wr = w + (int64_t)r * ldw;
+      const uint8_t *mr = mask + (int64_t)r * ldm;
+      for (int c = 0; c < cols; c += 4) {
+        int cnt = 0;
+        for (int j = 0; j < 4; ++j) {
+          if (!mr[c + j]) continue;
+          ++cnt;
+          if (!half_is_finite(wr[c + j])) { int e = EGT_OK; err.compare_exchange_strong(e, EGT_ERR_NONFINITE); }
+        }
+        if (cnt > n_keep) { err.store(EGT_ERR_MASK); }
+      }
+    }
+  });
+  if (err.load() != EGT_OK) return (egt_status)err.load();
+
+  const int64_t S = (int64_t)n_keep * (cols / 4);
+  const int G = val_kind == EGT_VAL_INT4 ? cols / group : 0;
+  uint8_t *vals8 = (uint8_t *)out->values;
+  uint16_t *vals16 = (uint16_t *)out->values;
+  uint32_t *row_ptr = out->row_ptr;
+  uint16_t *idx = out->idx, *qparams = out->qparams;
+
+  parallel_rows(rows, [=](int r0, int r1) {
+    std::vector<QParam> qp((size_t)std::max(G, 1));
+    for (int r = r0; r < r1; ++r) {
+      const uint16_t *wr = w + (int64_t)r * ldw;
+      const uint8_t *mr = mask + (int64_t)r * ldm;
+      row_ptr[r] = (uint32_t)((int64_t)r * S);
+      if (val_kind == EGT_VAL_INT4) {
+        for (int g = 0; g < G; ++g) {
+          double vmin = INFINITY, vmax = -INFINITY;
+          for (int c = g * group; c < (g + 1) * group; ++c) {
+            if (!mr[c]) continue;
+            const double v = half_to_double(wr[c]);
+            vmin = std::min(vmin, v);
+            vmax = std::max(vmax, v);
+          }
+          if (vmin > vmax) { vmin = 0.0; vmax = 0.0; }          // nothing kept
+          qp[g] = make_qparam(vmin, vmax);
+          uint16_t *o = qparams + ((int64_t)r * G + g) * 2;
+          o[0] = qp[g].s_bits;
+          o[1] = double_to_half((double)qp[g].z);
+        }
+      }
+      int64_t t = (int64_t)r * S;                                 // global slot id
+      uint32_t word = 0;
+      uint32_t byte = 0;
+      for (int c = 0; c < cols; c += 4) {
+        const int set = choose4(mr + c, n_keep);
+        for (int j = 0; j < 4; ++j) {
+          if (!(set >> j & 1)) continue;
+          word |= (uint32_t)j << (2 * (t & 7));
+          const bool kept = mr[c + j] != 0;
+          if (val_kind == EGT_VAL_FP16) {
+            vals16[t] = kept ? wr[c + j] : (uint16_t)0;
+          } else {
+            const QParam &p = qp[(c + j) / group];
+            const int q = kept ? make_code(half_to_double(wr[c + j]), p) : p.z;
+            if (t & 1) { vals8[t >> 1] = (uint8_t)(byte | (q << 4)); }
+            else byte = (uint32_t)q;
+          }
+          if ((t & 7) == 7) { idx[t >> 3] = (uint16_t)word; word = 0; }
+          ++t;
+        }
+      }
+    }
+  });
+  row_ptr[rows] = (uint32_t)((int64_t)rows * S);
+  out->rows = rows; out->cols = cols; out->n_keep = n_keep;
+  out->group_size = group; out->val_kind = val_kind;
+  return EGT_OK;
+}
+
+egt_status egt_unpack_2bitcsr(const egt_2bitcsr *in, uint16_t *w_dense, int64_t ldw,
+                              uint8_t *mask, int64_t ldm) {
+  if (!in) return EGT_ERR_NULL;
+  const int rows = in->rows, cols = in->cols, n = in->n_keep, group = in->group_size;
+  egt_status st = check_shape(rows, cols, n, group, in->val_kind);
+  if (st != EGT_OK) return st;
+  if (!in->row_ptr || !in->values || !in->idx) return EGT_ERR_NULL;
+  if (in->val_kind == EGT_VAL_INT4 && !in->qparams) return EGT_ERR_NULL;
+  if ((w_dense && ldw < cols) || (mask && ldm < cols)) return EGT_ERR_SHAPE;
+  const int64_t S = (int64_t)n * (cols / 4);
+  for (int r = 0; r <= rows; ++r)
+    if (in->row_ptr[r] != (uint32_t)((int64_t)r * S)) return EGT_ERR_BUFFER;
+  // offsets of a 4-group must ascend strictly
+  std::atomic<int> err(EGT_OK);
+  const uint16_t *idx = in->idx;
+  parallel_rows(rows, [&](int r0, int r1) {
+    for (int r = r0; r < r1; ++r) {
+      int64_t t = (int64_t)r * S;
+      for (int c = 0; c < cols; c += 4) {
+        int prev = -1;
+        for (int k = 0; k < n; ++k, ++t) {
+          const int off = (idx[t >> 3] >> (2 * (t & 7))) & 3;
+          if (off <= prev) err.store(EGT_ERR_BUFFER);
+          prev = off;
+        }
+      }
+    }
+  });
+  if (err.load() != EGT_OK) return (egt_status)err.load();
+
+  const uint8_t *vals8 = (const uint8_t *)in->values;
+  const uint16_t *vals16 = (const uint16_t *)in->values;
+  const uint16_t *qparams = in->qparams;
+  const int val_kind = in->val_kind;
+  const int G = val_kind == EGT_VAL_INT4 ? cols / group : 0;
+  parallel_rows(rows, [=](int r0, int r1) {
+    for (int r = r0; r < r1; ++r) {
+      if (w_dense) std::memset(w_dense + (int64_t)r * ldw, 0, sizeof(uint16_t) * (size_t)cols);
+      if (mask) std::memset(mask + (int64_t)r * ldm, 0, (size_t)cols);
+      int64_t t = (int64_t)r * S;
+      for (int c = 0; c < cols; c += 4) {
+        for (int k = 0; k < n; ++k, ++t) {
+          const int col = c + ((idx[t >> 3] >> (2 * (t & 7))) & 3);
+          if (mask) mask[(int64_t)r * ldm + col] = 1;
+          if (!w_dense) continue;
+          uint16_t bits;
+          if (val_kind == EGT_VAL_FP16) {
+            bits = vals16[t];
+          } else {
+            const int q = (vals8[t >> 1] >> (4 * (t & 1))) & 15;
+            const uint16_t *p = qparams + ((int64_t)r * G + col / group) * 2;
+            bits = double_to_half(half_to_double(p[0]) * ((double)q - half_to_double(p[1])));
+          }
+          w_dense[(int64_t)r * ldw + col] = bits;
+        }
+      }
+    }
+  });
+  return EGT_OK;
+}
+
+egt_status egt_quant_int4(const uint16_t *w, int64_t ldw, int rows, int cols, int group,
+                          uint8_t *q, uint16_t *qparams) {
+  if (!w || !q || !qparams) return EGT_ERR_NULL;
+  if (rows < 0 || cols < 0 || group <= 0 || group % 8 != 0 || cols % group != 0 || ldw < cols)
+    return EGT_ERR_SHAPE;
+  std::atomic<int> err(EGT_OK);
+  parallel_rows(rows, [&](int r0, int r1) {
+    for (int r = r0; r < r1; ++r)
+      for (int c = 0; c < cols; ++c)
+        if (!half_is_finite(w[(int64_t)r * ldw + c])) err.store(EGT_ERR_NONFINITE);
+  });
+  if (err.load() != EGT_OK) return (egt_status)err.load();
+  const int G = cols / group;
+  parallel_rows(rows, [=](int r0, int r1) {
+    for (int r = r0; r < r1; ++r) {
+      const uint16_t *wr = w + (int64_t)r * ldw;
+      for (int g = 0; g < G; ++g) {
+        double vmin = INFINITY, vmax = -INFINITY;
+        for (int c = g * group; c < (g + 1) * group; ++c) {
+          const double v = half_to_double(wr[c]);
+          vmin = std::min(vmin, v);
+          vmax = std::max(vmax, v);
+        }
+        const QParam p = make_qparam(vmin, vmax);
+        uint16_t *o = qparams + ((int64_t)r * G + g) * 2;
+        o[0] = p.s_bits;
+        o[1] = double_to_half((double)p.z);
+        for (int c = g * group; c < (g + 1) * group; c += 2) {
+          const int q0 = make_code(half_to_double(wr[c]), p);
+          const int q1 = make_code(half_to_double(wr[c + 1]), p);
+          q[(int64_t)r * (cols / 2) + c / 2] = (uint8_t)(q0 | (q1 << 4));
+        }
+      }
+    }
+  });
+  return EGT_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,204 @@
+"""Host half of the C ABI against the oracle: bit-exact packing, error codes,
+symbol export.  Runs without a GPU."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+from hypothesis import given, settings, strategies as st
+
+from oracle import egt_oracle as O
+from paper_2605_11582_amd import binding as B, synth
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _same_packed(p, o):
+    assert (p.rows, p.cols, p.n_keep, p.group, p.val_kind) == (o["rows"], o["cols"], o["n_keep"], o["group"], o["val_kind"])
+    assert np.array_equal(p.row_ptr, o["row_ptr"])
+    assert np.array_equal(p.idx, o["idx"])
+    assert np.array_equal(p.values, o["values"])
+    if o["qparams"] is None:
+        assert p.qparams is None
+    else:
+        assert np.array_equal(p.qparams, o["qparams"])
+
+
+def test_library_exports_every_declared_symbol():
+    text = open(os.path.join(ROOT, "include", "egt.h")).read()
+    declared = set(re.findall(r"\b(egt_[a-z0-9_]+)\s*\(", text))
+    assert declared == set(B.SYMBOLS)
+    L = ctypes.CDLL(B.LIB_PATH)
+    for name in declared:
+        assert getattr(L, name) is not None
+
+
+def test_status_strings():
+    assert B.status_str(0) == "ok"
+    assert len({B.status_str(i) for i in range(8)}) == 8
+
+
+def test_sizes_match_oracle_and_reject_bad_shapes():
+    for args in [(11008, 4096, 2, 128, 0), (4096, 11008, 1, 128, 0), (11008, 4096, 2, 0, 1), (8, 32, 3, 16, 0), (0, 32, 2, 32, 0)]:
+        assert B.sizes(*args) == O.buffer_sizes(*args)
+    for bad in [(8, 48, 2, 16, 0), (8, 64, 5, 32, 0), (8, 64, 0, 32, 0), (8, 64, 2, 48, 0), (8, 64, 2, 6, 0),
+                (8, 64, 2, 32, 1), (8, 64, 2, 0, 0), (8, 64, 2, 32, 7), (-1, 64, 2, 32, 0)]:
+        with pytest.raises(B.EgtError) as e:
+            B.sizes(*bad)
+        assert e.value.status == 2
+        with pytest.raises(ValueError):
+            O.check_shape(*bad)
+
+
+@pytest.mark.parametrize("n", [1, 2, 3, 4])
+def test_prune_matches_oracle(n):
+    w = synth.weights(64, 256, 123 + n)
+    w[0, :16] = np.float16(0.25)
+    w[1, :8] = [0.0, -0.0, 0.5, -0.5, -0.0, 0.0, 0.0, -0.0]
+    assert np.array_equal(B.prune_n4(w, n), O.prune_n4_magnitude(w, n))
+
+
+@pytest.mark.parametrize("n,g,kind", [(2, 128, 0), (1, 128, 0), (2, 0, 1), (1, 0, 1), (3, 64, 0), (4, 32, 0), (2, 4, 0)])
+def test_pack_bit_exact_config_like(n, g, kind):
+    w = synth.weights(96, 512, 777 + 10 * n + kind)
+    mask = O.prune_n4_magnitude(w, n)
+    mask[5, 16:20] = 0                       # under-full groups and an empty row
+    mask[6, :] = 0
+    _same_packed(B.pack_2bitcsr(w, mask, n, g, kind), O.pack_2bitcsr(w, mask, n, g, kind))
+
+
+def test_pack_bit_exact_config1():
+    seed = synth.seed_for(1)
+    w = synth.weights(1024, 1024, seed)
+    mask = B.prune_n4(w, 2)
+    assert np.array_equal(mask, O.prune_n4_magnitude(w, 2))
+    _same_packed(B.pack_2bitcsr(w, mask, 2, 128, 0), O.pack_2bitcsr(w, mask, 2, 128, 0))
+
+
+def test_pack_handles_wide_value_ranges_and_subnormals():
+    rng = np.random.default_rng(9)
+    # exponents all over the binary16 range, including subnormals and exact ties
+    bits = rng.integers(0, 0x7C00, size=(32, 256)).astype(np.uint16) | (rng.integers(0, 2, size=(32, 256)).astype(np.uint16) << 15)
+    w = bits.view(np.float16)
+    mask = O.prune_n4_magnitude(w, 2)
+    _same_packed(B.pack_2bitcsr(w, mask, 2, 32, 0), O.pack_2bitcsr(w, mask, 2, 32, 0))
+    small = (rng.integers(0, 64, size=(16, 128)).astype(np.uint16)).view(np.float16)   # subnormals only
+    m2 = O.prune_n4_magnitude(small, 2)
+    _same_packed(B.pack_2bitcsr(small, m2, 2, 64, 0), O.pack_2bitcsr(small, m2, 2, 64, 0))
+    # half-integer multiples of the scale: ties must go to even on both sides
+    grid = (0.5 * rng.integers(-14, 17, size=(16, 128))).astype(np.float16)
+    grid[:, 0], grid[:, 1] = -7.0, 8.0
+    m3 = np.ones_like(grid, dtype=np.uint8)
+    _same_packed(B.pack_2bitcsr(grid, m3, 4, 128, 0), O.pack_2bitcsr(grid, m3, 4, 128, 0))
+
+
+@settings(max_examples=60, deadline=None)
+@given(rows=st.integers(0, 9), kb=st.integers(1, 6), n=st.integers(1, 4), kind=st.integers(0, 1),
+       gsel=st.integers(0, 3), seed=st.integers(0, 2 ** 31), drop=st.floats(0, 0.5))
+def test_pack_bit_exact_random(rows, kb, n, kind, gsel, seed, drop):
+    cols = 32 * kb
+    groups = [g for g in (4, 8, 16, 32, 64, 96, 128, 192) if cols % g == 0]
+    g = 0 if kind == 1 else groups[gsel % len(groups)]
+    rng = np.random.default_rng(seed)
+    w = (rng.standard_normal((rows, cols)) * rng.choice([1e-4, 0.02, 3.0, 500.0])).astype(np.float16)
+    mask = O.prune_n4_magnitude(w, n) if rows else np.zeros((0, cols), dtype=np.uint8)
+    mask = mask & (rng.random(mask.shape) >= drop)          # random under-full groups
+    _same_packed(B.pack_2bitcsr(w, mask.astype(np.uint8), n, g, kind), O.pack_2bitcsr(w, mask, n, g, kind))
+
+
+def test_pack_errors_leave_outputs_untouched():
+    w = synth.weights(8, 64, 5)
+    mask = O.prune_n4_magnitude(w, 2)
+    bad = mask.copy()
+    bad[7, 60:64] = [1, 1, 1, 0]
+    with pytest.raises(B.EgtError) as e:
+        B.pack_2bitcsr(w, bad, 2, 32, 0)
+    assert e.value.status == 3
+    w2 = w.copy()
+    r, c = np.argwhere(mask == 1)[-1]
+    w2[r, c] = np.float16(np.nan)
+    with pytest.raises(B.EgtError) as e:
+        B.pack_2bitcsr(w2, mask, 2, 32, 0)
+    assert e.value.status == 4
+    w2[r, c] = w[r, c]
+    r, c = np.argwhere(mask == 0)[0]
+    w2[r, c] = np.float16(np.inf)            # a pruned entry is never looked at
+    B.pack_2bitcsr(w2, mask, 2, 32, 0)
+    # direct call with canary buffers: nothing is written on error
+    b = B.sizes(8, 64, 2, 32, 0)
+    bufs = [np.full(n, 0xA5, dtype=np.uint8) for n in b]
+    v = B.View(0, 0, 0, 0, 0, *[x.ctypes.data for x in bufs])
+    st_ = B.lib().egt_pack_2bitcsr(w.ctypes.data, 64, bad.ctypes.data, 64, 8, 64, 2, 32, 0, ctypes.byref(v))
+    assert st_ == 3 and all(np.all(x == 0xA5) for x in bufs)
+    assert B.lib().egt_pack_2bitcsr(None, 64, bad.ctypes.data, 64, 8, 64, 2, 32, 0, ctypes.byref(v)) == 1
+    assert B.lib().egt_pack_2bitcsr(w.ctypes.data, 32, bad.ctypes.data, 64, 8, 64, 2, 32, 0, ctypes.byref(v)) == 2
+
+
+def test_strided_inputs():
+    big = synth.weights(16, 256, 11)
+    w = big[:, 64:192]                         # row stride 256, 128 columns
+    mask_big = np.zeros((16, 200), dtype=np.uint8)
+    mask_big[:, :128] = O.prune_n4_magnitude(np.ascontiguousarray(w), 2)
+    mask = mask_big[:, :128]
+    p = B.pack_2bitcsr(w, mask, 2, 64, 0)
+    _same_packed(p, O.pack_2bitcsr(np.ascontiguousarray(w), np.ascontiguousarray(mask), 2, 64, 0))
+
+
+@pytest.mark.parametrize("n,g,kind", [(2, 64, 0), (1, 32, 0), (2, 0, 1), (3, 16, 0)])
+def test_unpack_matches_oracle_decode(n, g, kind):
+    w = synth.weights(40, 256, 31 + n)
+    mask = O.prune_n4_magnitude(w, n)
+    mask[3, 8:12] = 0
+    p = B.pack_2bitcsr(w, mask, n, g, kind)
+    o = O.pack_2bitcsr(w, mask, n, g, kind)
+    wd, md = B.unpack_2bitcsr(p)
+    assert np.array_equal(md, O.mask_from_packed(o))
+    assert np.array_equal(wd.view(np.uint16), O.dense_from_packed(o).astype(np.float16).view(np.uint16))
+    if kind == 1:                              # FP16 values: pack(unpack(P)) == P byte for byte
+        p2 = B.pack_2bitcsr(wd, md, n, g, kind)
+        assert np.array_equal(p2.values, p.values) and np.array_equal(p2.idx, p.idx)
+
+
+def test_unpack_rejects_broken_buffers():
+    w = synth.weights(8, 64, 77)
+    p = B.pack_2bitcsr(w, O.prune_n4_magnitude(w, 2), 2, 32, 0)
+    good = p.row_ptr.copy()
+    p.row_ptr[3] += 8
+    with pytest.raises(B.EgtError) as e:
+        B.unpack_2bitcsr(p)
+    assert e.value.status == 5
+    p.row_ptr[:] = good
+    p.idx[0] = 0x0000                          # offsets 0,0: not ascending
+    with pytest.raises(B.EgtError) as e:
+        B.unpack_2bitcsr(p)
+    assert e.value.status == 5
+
+
+@pytest.mark.parametrize("g", [8, 32, 128])
+def test_quant_int4_dense_bit_exact(g):
+    w = synth.weights(48, 512, 55 + g)
+    q, qp = B.quant_int4(w, g)
+    oq, oqp = O.quant_int4_dense(w, g)
+    assert np.array_equal(q, oq) and np.array_equal(qp, oqp)
+
+
+def test_device_entry_points_reject_bad_arguments_without_a_gpu():
+    L = B.lib()
+    v = B.View(8, 64, 2, 32, 0, 16, 16, 16, 16)          # fake non-null aligned pointers, never used
+    assert L.egt_sparse_gemv(None, 16, 16, None) == 1
+    assert L.egt_sparse_gemv(ctypes.byref(v), None, 16, None) == 1
+    assert L.egt_sparse_gemm_smallm(ctypes.byref(v), 16, 64, 16, 8, 0, None) == 2
+    assert L.egt_sparse_gemm_smallm(ctypes.byref(v), 16, 64, 16, 8, 65, None) == 2
+    assert L.egt_sparse_gemm_smallm(ctypes.byref(v), 16, 32, 16, 8, 2, None) == 2
+    assert L.egt_sparse_gemm_smallm(ctypes.byref(v), 16, 64, 16, 4, 2, None) == 2
+    v2 = B.View(8, 48, 2, 16, 0, 16, 16, 16, 16)
+    assert L.egt_sparse_gemv(ctypes.byref(v2), 16, 16, None) == 2
+    v3 = B.View(8, 64, 2, 32, 0, 16, 16, 16, None)
+    assert L.egt_sparse_gemv(ctypes.byref(v3), 16, 16, None) == 1
+    v4 = B.View(8, 64, 2, 32, 0, 16, 24, 16, 16)         # misaligned values pointer
+    assert L.egt_sparse_gemv(ctypes.byref(v4), 16, 16, None) == 5
+    assert L.egt_int4_gemv(None, 16, 8, 64, 32, 16, 16, None) == 1
+    assert L.egt_int4_gemv(16, 16, 8, 64, 12, 16, 16, None) == 2
+    assert L.egt_stream_read(16, 24, 16, None) == 2
+    assert L.egt_stream_read(None, 32, 16, None) == 1
