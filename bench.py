@@ -1,0 +1,197 @@
+#!/usr/bin/env python3
+"""Benchmark of the SparseGemv hot path on one MI355X.
+
+A step is one `egt_sparse_gemv` call (stage x, stream the 2bit-CSR row data,
+dequantise, gather, multiply-accumulate, reduce, store) on the headline workload:
+W 11008 x 4096, 2:4 sparse, INT4 group 128, 2bit-CSR; x FP16; M = 1.  Inputs are
+resident in HBM before the timed region.  Consecutive steps cycle over enough
+distinct device copies of the packed matrix to exceed twice the 256 MB last-level
+cache, so every launch streams its weights from HBM.
+
+Prints ONE JSON line (see README / DESIGN for the fields).
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0
+LLC_BYTES = 256 << 20
+
+
+def algorithmic_bytes(rows, cols, n_keep, group, kind, m=1):
+    """Bytes the method itself has to move per call: the four buffers of the
+    matrix (row_ptr[R] only), x once, y once."""
+    slots = rows * n_keep * cols // 4
+    val = slots // 2 if kind == 0 else 2 * slots
+    idx = slots // 4
+    qp = 4 * rows * (cols // group) if kind == 0 else 0
+    return val + idx + qp + 4 * rows + 4 + m * 2 * cols + m * 2 * rows
+
+
+def dense_int4_bytes(rows, cols, group):
+    return rows * cols // 2 + 4 * rows * (cols // group) + 2 * cols + 2 * rows
+
+
+def time_loop(torch, fn, steps, warmup):
+    for i in range(warmup):
+        fn(i)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    e0.record()
+    for i in range(steps):
+        fn(i)
+    e1.record()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    return e0.elapsed_time(e1) * 1e-3 / steps, wall / steps
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=4000)
+    ap.add_argument("--warmup", type=int, default=400)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--extra", action="store_true", help="also time the other configurations")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no sharding, no collectives); use --gpus 1",
+              file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2605_11582_amd import binding as B, synth
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(2)
+    B.lib()
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+
+    R, K, N, GRP = 11008, 4096, 2, 128
+    seed = synth.seed_for(synth.HEADLINE)
+    w = synth.weights(R, K, seed)
+    x = synth.activations(K, seed)
+    mask = B.prune_n4(w, N)
+    p = B.pack_2bitcsr(w, mask, N, GRP, B.VAL_INT4)
+    nbytes = algorithmic_bytes(R, K, N, GRP, 0)
+    copies = max(2, -(-2 * LLC_BYTES // p.nbytes()))
+    packed = [p.to(dev) for _ in range(copies)]
+    xd = torch.from_numpy(x.view(np.int16)).to(dev).view(torch.float16)
+    ys = [torch.empty(R, dtype=torch.float16, device=dev) for _ in range(copies)]
+
+    def step(i):
+        B.sparse_gemv(packed[i % copies], xd, ys[i % copies])
+
+    t_dev, t_wall = time_loop(torch, step, args.steps, args.warmup)
+    # the same launch on one copy only (weights stay in the last-level cache)
+    t_hot, _ = time_loop(torch, lambda i: B.sparse_gemv(packed[0], xd, ys[0]), args.steps, args.warmup)
+
+    # read ceiling: a plain 128-bit streaming read of the same number of bytes, same rotation
+    pool = [torch.empty(p.nbytes(), dtype=torch.uint8, device=dev).random_(0, 255) for _ in range(copies)]
+    sink = torch.zeros(4096, dtype=torch.int32, device=dev)
+    nb16 = p.nbytes() // 16 * 16
+    t_read, _ = time_loop(torch, lambda i: B.stream_read(pool[i % copies], nb16, sink), args.steps, args.warmup)
+    big = torch.empty(1 << 30, dtype=torch.uint8, device=dev).random_(0, 255)
+    t_big, _ = time_loop(torch, lambda i: B.stream_read(big, 1 << 30, sink), 20, 3)
+    del big, pool
+
+    gbps = nbytes / t_dev / 1e9
+    result = {
+        "metric": "SparseGemv achieved HBM GB/s, INT4 2:4 11008x4096, M=1",
+        "value": round(gbps, 1),
+        "unit": "GB/s",
+        "us_per_call": round(t_dev * 1e6, 3),
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": t_dev * 1e3,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "int4 weights x fp16 activations, fp32 accumulate",
+        "data": "synthetic",
+        "config": {"workload": "headline: W 11008x4096 2:4 sparse INT4 g128 in 2bit-CSR, x FP16, M=1",
+                   "rotating_copies": copies, "bytes_per_call": nbytes},
+        "roofline": {"bound": "hbm", "achieved": round(gbps, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                     "frac": round(gbps / HBM_PEAK_GBPS, 4), "traffic": None,
+                     "kernel": "egt_sparse_gemv (headline shape)",
+                     "frac_of_read_ceiling": round(t_read / t_dev * nbytes / nb16, 4)},
+        "hot_cache_us_per_call": round(t_hot * 1e6, 3),
+        "host_wall_us_per_call": round(t_wall * 1e6, 3),
+        "read_ceiling": {"same_size_us": round(t_read * 1e6, 3), "same_size_gbps": round(nb16 / t_read / 1e9, 1),
+                         "one_gib_gbps": round((1 << 30) / t_big / 1e9, 1)},
+    }
+
+    if args.extra:
+        extra = {}
+        # config 3: sparse FP16 values
+        p3 = B.pack_2bitcsr(w, mask, N, 0, B.VAL_FP16)
+        c3 = max(2, -(-2 * LLC_BYTES // p3.nbytes()))
+        pk3 = [p3.to(dev) for _ in range(c3)]
+        t3, _ = time_loop(torch, lambda i: B.sparse_gemv(pk3[i % c3], xd, ys[0]), 1000, 100)
+        b3 = algorithmic_bytes(R, K, N, 0, 1)
+        extra["config3_sparse_fp16_11008x4096"] = {"us": round(t3 * 1e6, 3), "gbps": round(b3 / t3 / 1e9, 1), "bytes": b3}
+        del pk3
+        # config 2: dense INT4 4096x4096
+        w2 = synth.weights(4096, 4096, synth.seed_for(2))
+        q2, qp2 = B.quant_int4(w2, 128)
+        c2 = max(2, -(-2 * LLC_BYTES // (q2.nbytes + qp2.nbytes)))
+        q2d = [torch.from_numpy(q2).to(dev) for _ in range(c2)]
+        qp2d = [torch.from_numpy(qp2.view(np.int16)).to(dev) for _ in range(c2)]
+        x2 = torch.from_numpy(synth.activations(4096, synth.seed_for(2)).view(np.int16)).to(dev).view(torch.float16)
+        y2 = torch.empty(4096, dtype=torch.float16, device=dev)
+        t2, _ = time_loop(torch, lambda i: B.int4_gemv(q2d[i % c2], qp2d[i % c2], 4096, 4096, 128, x2, y2), 2000, 200)
+        b2 = dense_int4_bytes(4096, 4096, 128)
+        extra["config2_dense_int4_4096x4096"] = {"us": round(t2 * 1e6, 3), "gbps": round(b2 / t2 / 1e9, 1), "bytes": b2}
+        del q2d, qp2d
+        # config 5: small M on both shapes
+        for (r5, k5, mi) in ((11008, 4096, 0), (4096, 11008, 1)):
+            w5 = synth.weights(r5, k5, synth.seed_for(5, mi))
+            p5 = B.pack_2bitcsr(w5, B.prune_n4(w5, 2), 2, 128, B.VAL_INT4)
+            c5 = max(2, -(-2 * LLC_BYTES // p5.nbytes()))
+            pk5 = [p5.to(dev) for _ in range(c5)]
+            for M in (1, 4, 16, 64):
+                X = torch.from_numpy(synth.activation_rows(M, k5, 5).view(np.int16)).to(dev).view(torch.float16)
+                Y = torch.empty((M, r5), dtype=torch.float16, device=dev)
+                t5, _ = time_loop(torch, lambda i: B.sparse_gemm_smallm(pk5[i % c5], X, Y), 500, 50)
+                b5 = algorithmic_bytes(r5, k5, 2, 128, 0, M)
+                extra[f"config5_{r5}x{k5}_M{M}"] = {"us": round(t5 * 1e6, 3), "gbps": round(b5 / t5 / 1e9, 1),
+                                                   "bytes": b5, "tflops": round(2 * M * r5 * k5 / 2 / t5 / 1e12, 2)}
+            del pk5
+        result["extra"] = extra
+
+    if not args.no_cpu_baseline:
+        from oracle import egt_oracle as O
+        sample = 1024
+        sub_w = w[:sample]
+        o = O.pack_2bitcsr(sub_w, O.prune_n4_magnitude(sub_w, N), N, GRP, O.VAL_INT4)
+        reps, t0 = 0, time.perf_counter()
+        while True:
+            O.gemv(o, x)
+            reps += 1
+            if time.perf_counter() - t0 > 10.0:
+                break
+        t_cpu = (time.perf_counter() - t0) / reps
+        sample_bytes = algorithmic_bytes(sample, K, N, GRP, 0)
+        result["cpu_baseline"] = {"value": round(sample_bytes / t_cpu / 1e9, 4), "unit": "GB/s", "cores": 1,
+                                  "kind": "oracle",
+                                  "sample": f"oracle gemv (decode + multiply, float64 numpy) on the first {sample} "
+                                            f"rows of the headline matrix, {reps} repetitions, "
+                                            f"{t_cpu * 1e3:.1f} ms each; host has {os.cpu_count()} logical CPUs"}
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()

@@ -18,6 +18,8 @@
  *    take device pointers (16-byte aligned), enqueue kernels on `stream`
  *    (a hipStream_t passed as void*, NULL = the default stream) and return
  *    without synchronising.
+ *  - A device call on a matrix with rows == 0 is a no-op that returns EGT_OK
+ *    without looking at the buffer pointers.
  *  - Argument errors are detected on the host before anything is written or
  *    launched; outputs are untouched when a call returns an error.
  *  - FP16 numbers cross the boundary as their IEEE binary16 bit patterns
@@ -86,6 +88,10 @@ typedef struct {
 
 /* Text for a status code (static storage, never NULL). */
 const char *egt_status_str(int status);
+
+/* Text of the HIP error behind the most recent EGT_ERR_HIP returned to the
+ * calling thread ("no error" if there was none).  Diagnostic aid. */
+const char *egt_last_hip_error(void);
 
 /* HOST.  Byte sizes of the four buffers {row_ptr, values, idx, qparams} of a
  * matrix (Sec. 3.3 "Sparse Index Structure").  EGT_ERR_SHAPE unless

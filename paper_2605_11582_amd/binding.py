@@ -19,7 +19,7 @@ VAL_INT4 = 0
 VAL_FP16 = 1
 
 SYMBOLS = (
-    "egt_status_str", "egt_2bitcsr_sizes", "egt_prune_n4", "egt_pack_2bitcsr",
+    "egt_status_str", "egt_last_hip_error", "egt_2bitcsr_sizes", "egt_prune_n4", "egt_pack_2bitcsr",
     "egt_unpack_2bitcsr", "egt_quant_int4", "egt_int4_gemv", "egt_sparse_gemv",
     "egt_sparse_gemm_smallm", "egt_stream_read",
 )
@@ -48,9 +48,16 @@ def lib() -> C.CDLL:
         if not os.path.exists(LIB_PATH):
             raise RuntimeError(f"{LIB_PATH} is not built: run `python -m paper_2605_11582_amd.build` "
                                "(there is no fallback path)")
+        # One HIP runtime per process: PyTorch ships its own libamdhip64 (same soname
+        # as the system one).  Importing torch first makes the loader bind libegt.so
+        # to that copy, so streams and device pointers mean the same thing on both
+        # sides; loading libegt.so first would pull in a second runtime.
+        import torch  # noqa: F401
         L = C.CDLL(LIB_PATH)
         L.egt_status_str.restype = C.c_char_p
         L.egt_status_str.argtypes = [C.c_int]
+        L.egt_last_hip_error.restype = C.c_char_p
+        L.egt_last_hip_error.argtypes = []
         L.egt_2bitcsr_sizes.argtypes = [C.c_int] * 5 + [C.POINTER(C.c_size_t)]
         L.egt_prune_n4.argtypes = [C.c_void_p, C.c_int64, C.c_int, C.c_int, C.c_int, C.c_void_p, C.c_int64]
         L.egt_pack_2bitcsr.argtypes = [C.c_void_p, C.c_int64, C.c_void_p, C.c_int64, C.c_int, C.c_int,
@@ -64,7 +71,7 @@ def lib() -> C.CDLL:
                                              C.c_int64, C.c_int, C.c_void_p]
         L.egt_stream_read.argtypes = [C.c_void_p, C.c_size_t, C.c_void_p, C.c_void_p]
         for name in SYMBOLS:
-            if name != "egt_status_str":
+            if name not in ("egt_status_str", "egt_last_hip_error"):
                 getattr(L, name).restype = C.c_int
         _lib = L
     return _lib
@@ -76,7 +83,10 @@ def status_str(status: int) -> str:
 
 def _check(status: int) -> None:
     if status != 0:
-        raise EgtError(status, status_str(status))
+        text = status_str(status)
+        if status == 7:
+            text += ": " + lib().egt_last_hip_error().decode()
+        raise EgtError(status, text)
 
 
 def _np_ptr(a: np.ndarray) -> int:

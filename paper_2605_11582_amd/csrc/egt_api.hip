@@ -11,7 +11,7 @@ egt_status check_view(const egt_2bitcsr *w) {
   if (w->val_kind == EGT_VAL_INT4) {
     if (w->group_size <= 0 || w->group_size % 4 != 0 || w->cols % w->group_size != 0)
       return EGT_ERR_SHAPE;
-    if (!w->qparams) return EGT_ERR_NULL;
+    if (!w->qparams && w->rows != 0) return EGT_ERR_NULL;
   } else if (w->val_kind == EGT_VAL_FP16) {
     if (w->group_size != 0) return EGT_ERR_SHAPE;
   } else {
@@ -19,11 +19,20 @@ egt_status check_view(const egt_2bitcsr *w) {
   }
   if ((uint64_t)w->rows * (uint64_t)w->n_keep * (uint64_t)(w->cols / 4) >= (1ull << 32))
     return EGT_ERR_SHAPE;
+  if (w->rows == 0) return EGT_OK;                  // empty matrix: its buffers may be NULL
   if (!w->row_ptr || !w->values || !w->idx) return EGT_ERR_NULL;
   return EGT_OK;
 }
 
 inline bool aligned16(const void *p) { return ((uintptr_t)p & 15u) == 0; }
+
+thread_local hipError_t g_last_hip_error = hipSuccess;
+
+inline egt_status done(hipError_t e) {
+  if (e == hipSuccess) return EGT_OK;
+  g_last_hip_error = e;
+  return EGT_ERR_HIP;
+}
 
 // Streams `n16` 16-byte words; every workgroup folds what it read into one word.
 __global__ __launch_bounds__(256) void k_stream_read(const uint4 *__restrict__ src, size_t n16,
@@ -48,29 +57,35 @@ __global__ __launch_bounds__(256) void k_stream_read(const uint4 *__restrict__ s
 
 }  // namespace
 
+namespace egt {
+void note_hip_error(hipError_t e) { g_last_hip_error = e; }
+}  // namespace egt
+
 extern "C" {
+
+const char *egt_last_hip_error(void) { return hipGetErrorString(g_last_hip_error); }
 
 egt_status egt_int4_gemv(const uint8_t *q, const uint16_t *qparams, int rows, int cols, int group,
                          const uint16_t *x, uint16_t *y, void *stream) {
-  if (!q || !qparams || !x || !y) return EGT_ERR_NULL;
   if (rows < 0 || cols < 0 || group <= 0 || group % 8 != 0 || cols % group != 0)
     return EGT_ERR_SHAPE;
+  if (rows == 0) return EGT_OK;                     // nothing to compute, pointers not examined
+  if (!q || !qparams || !x || !y) return EGT_ERR_NULL;
   if (!aligned16(q) || !aligned16(qparams) || !aligned16(x)) return EGT_ERR_BUFFER;
-  const hipError_t e = egt::launch_int4(q, qparams, rows, cols, group, x, y, (hipStream_t)stream);
-  return e == hipSuccess ? EGT_OK : EGT_ERR_HIP;
+  return done(egt::launch_int4(q, qparams, rows, cols, group, x, y, (hipStream_t)stream));
 }
 
 egt_status egt_sparse_gemm_smallm(const egt_2bitcsr *w, const uint16_t *X, int64_t ldx,
                                   uint16_t *Y, int64_t ldy, int M, void *stream) {
   const egt_status st = check_view(w);
   if (st != EGT_OK) return st;
-  if (!X || !Y) return EGT_ERR_NULL;
   if (M < 1 || M > 64 || ldx < w->cols || ldy < w->rows) return EGT_ERR_SHAPE;
+  if (w->rows == 0) return EGT_OK;                  // nothing to compute, pointers not examined
+  if (!X || !Y) return EGT_ERR_NULL;
   if (!aligned16(w->row_ptr) || !aligned16(w->values) || !aligned16(w->idx) ||
       (w->qparams && !aligned16(w->qparams)) || !aligned16(X))
     return EGT_ERR_BUFFER;
-  const hipError_t e = egt::launch_sparse(*w, X, ldx, Y, ldy, M, (hipStream_t)stream);
-  return e == hipSuccess ? EGT_OK : EGT_ERR_HIP;
+  return done(egt::launch_sparse(*w, X, ldx, Y, ldy, M, (hipStream_t)stream));
 }
 
 egt_status egt_sparse_gemv(const egt_2bitcsr *w, const uint16_t *x, uint16_t *y, void *stream) {
@@ -87,9 +102,8 @@ egt_status egt_stream_read(const void *src, size_t bytes, uint32_t *sink, void *
   size_t blocks = (n16 + 1023) / 1024;                // 4 x 16 B per thread when large
   if (blocks > 4096) blocks = 4096;
   if (blocks < 1) blocks = 1;
-  hipLaunchKernelGGL(k_stream_read, dim3((unsigned)blocks), dim3(256), 0, (hipStream_t)stream,
-                     (const uint4 *)src, n16, sink);
-  return hipGetLastError() == hipSuccess ? EGT_OK : EGT_ERR_HIP;
+  return done(egt::launch(k_stream_read, dim3((unsigned)blocks), dim3(256), 0, (hipStream_t)stream,
+                          (const uint4 *)src, n16, sink));
 }
 
 }  // extern "C"

@@ -10,11 +10,30 @@
 
 namespace egt {
 
+// Launch through hipLaunchKernel so that the status is the launch's own return
+// value (hipGetLastError may carry a stale, unrelated code of the calling thread).
+template <typename... P, typename... A>
+inline hipError_t launch(void (*kernel)(P...), dim3 grid, dim3 block, size_t lds, hipStream_t stream,
+                         A... args) {
+  auto pack = [&](P... p) {
+    void *argv[] = {(void *)&p...};
+    return hipLaunchKernel((const void *)kernel, grid, block, argv, lds, stream);
+  };
+  return pack(static_cast<P>(args)...);
+}
+
+// code of the most recent failing HIP call made by this library on this thread
+void note_hip_error(hipError_t e);
+
 // generic, slot-by-slot kernels (any shape the format allows)
 hipError_t launch_sparse_generic(const egt_2bitcsr &w, const uint16_t *X, int64_t ldx, uint16_t *Y,
                                  int64_t ldy, int M, hipStream_t stream);
 hipError_t launch_int4_generic(const uint8_t *q, const uint16_t *qparams, int rows, int cols,
                                int group, const uint16_t *x, uint16_t *y, hipStream_t stream);
+
+// M = 1 kernels on the sparse matrix cores (2:4 only; see sparse_m1_supported)
+bool sparse_m1_supported(const egt_2bitcsr &w);
+hipError_t launch_sparse_m1(const egt_2bitcsr &w, const uint16_t *x, uint16_t *y, hipStream_t stream);
 
 // dispatchers: pick the tuned kernel for the shape, else the generic one
 hipError_t launch_sparse(const egt_2bitcsr &w, const uint16_t *X, int64_t ldx, uint16_t *Y,

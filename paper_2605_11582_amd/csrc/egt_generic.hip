@@ -95,21 +95,19 @@ hipError_t launch_sparse_generic(const egt_2bitcsr &w, const uint16_t *X, int64_
   const int mt = M == 1 ? 1 : 4;
   const dim3 grid((w.rows + 3) / 4, (M + mt - 1) / mt);
 #define EGT_GO(KIND, MT)                                                                        \
-  hipLaunchKernelGGL((k_sparse_generic<KIND, MT>), grid, block, 0, stream, w.row_ptr,          \
-                     (const uint8_t *)w.values, w.idx, w.qparams, w.rows, w.cols, w.n_keep,     \
-                     w.group_size, (const __half *)X, ldx, (__half *)Y, ldy, M)
-  if (w.val_kind == EGT_VAL_INT4) { if (mt == 1) EGT_GO(EGT_VAL_INT4, 1); else EGT_GO(EGT_VAL_INT4, 4); }
-  else { if (mt == 1) EGT_GO(EGT_VAL_FP16, 1); else EGT_GO(EGT_VAL_FP16, 4); }
+  launch(k_sparse_generic<KIND, MT>, grid, block, 0, stream, w.row_ptr, (const uint8_t *)w.values, \
+         w.idx, w.qparams, w.rows, w.cols, w.n_keep, w.group_size, (const __half *)X, ldx,       \
+         (__half *)Y, ldy, M)
+  if (w.val_kind == EGT_VAL_INT4) return mt == 1 ? EGT_GO(EGT_VAL_INT4, 1) : EGT_GO(EGT_VAL_INT4, 4);
+  return mt == 1 ? EGT_GO(EGT_VAL_FP16, 1) : EGT_GO(EGT_VAL_FP16, 4);
 #undef EGT_GO
-  return hipGetLastError();
 }
 
 hipError_t launch_int4_generic(const uint8_t *q, const uint16_t *qparams, int rows, int cols,
                                int group, const uint16_t *x, uint16_t *y, hipStream_t stream) {
   if (rows == 0) return hipSuccess;
-  hipLaunchKernelGGL(k_int4_generic, dim3((rows + 3) / 4), dim3(256), 0, stream, q, qparams, rows,
-                     cols, group, (const __half *)x, (__half *)y);
-  return hipGetLastError();
+  return launch(k_int4_generic, dim3((rows + 3) / 4), dim3(256), 0, stream, q, qparams, rows, cols,
+                group, (const __half *)x, (__half *)y);
 }
 
 }  // namespace egt

@@ -1,0 +1,179 @@
+"""GPU parity: the HIP path, called through the C ABI, against the float64 oracle."""
+import numpy as np
+import pytest
+
+from oracle import egt_oracle as O
+from paper_2605_11582_amd import binding as B, synth
+import gpu_common as G
+
+pytestmark = pytest.mark.gpu
+
+
+def _small_case(rows, cols, n, g, kind, seed, drop=0.0):
+    rng = np.random.default_rng(seed)
+    w = synth.weights(rows, cols, seed)
+    mask = O.prune_n4_magnitude(w, n)
+    if drop:
+        mask = (mask & (rng.random(mask.shape) >= drop)).astype(np.uint8)
+    o = O.pack_2bitcsr(w, mask, n, g, kind)
+    p = B.pack_2bitcsr(w, mask, n, g, kind)
+    for k in ("row_ptr", "values", "idx"):
+        assert np.array_equal(getattr(p, k), o[k])
+    return p, o
+
+
+# ---------------------------------------------------------------- element by element, small
+@pytest.mark.parametrize("rows,cols,n,g,kind", [
+    (37, 96, 2, 32, 0), (5, 32, 1, 16, 0), (64, 160, 3, 32, 0), (33, 128, 4, 64, 0),
+    (19, 224, 2, 0, 1), (7, 64, 1, 0, 1), (130, 1056, 2, 96, 0), (3, 4128, 2, 4128, 0),
+    (257, 1024, 2, 128, 0), (100, 1024, 1, 128, 0), (70, 2048, 2, 64, 0), (70, 2048, 2, 256, 0),
+    (45, 4096, 2, 128, 0), (45, 4096, 2, 0, 1), (21, 11008, 2, 128, 0), (21, 11008, 1, 128, 0),
+    (21, 11008, 2, 0, 1), (50, 320, 2, 64, 0),
+])
+def test_sparse_gemv_small(rows, cols, n, g, kind):
+    print(f"case sparse_gemv {rows}x{cols} n={n} g={g} kind={kind}", flush=True)
+    p, o = _small_case(rows, cols, n, g, kind, seed=1000 + rows + cols + n, drop=0.1)
+    x = synth.activations(cols, 77 + rows)
+    y_ref, a_ref = O.gemv(o, x)
+    y = G.run_sparse_gemv(p, x)
+    G.assert_close(y, y_ref, a_ref, "sparse_gemv")
+
+
+def test_config1_full_parity_and_determinism():
+    seed = synth.seed_for(1)
+    w = synth.weights(1024, 1024, seed)
+    x = synth.activations(1024, seed)
+    mask = B.prune_n4(w, 2)
+    p = B.pack_2bitcsr(w, mask, 2, 128, 0)
+    o = O.pack_2bitcsr(w, O.prune_n4_magnitude(w, 2), 2, 128, 0)
+    for k in ("row_ptr", "values", "idx", "qparams"):
+        assert np.array_equal(getattr(p, k), o[k])
+    y_ref, a_ref = O.gemv(o, x)
+    y = G.run_sparse_gemv(p, x)
+    G.assert_close(y, y_ref, a_ref, "config 1")
+    # no atomics anywhere: two runs give the same bits
+    assert np.array_equal(y.view(np.uint16), G.run_sparse_gemv(p, x).view(np.uint16))
+
+
+@pytest.mark.parametrize("kind,g", [(0, 128), (1, 0)])
+def test_one_hot_x_returns_decoded_column_bit_exact(kind, g):
+    p, o = _small_case(96, 4096, 2, g, kind, seed=4242)
+    W = O.dense_from_packed(o)
+    for j in (0, 5, 2049, 4095):
+        e = np.zeros(4096, dtype=np.float16)
+        e[j] = 1
+        y = G.run_sparse_gemv(p, e)
+        assert np.array_equal(y.view(np.uint16), W[:, j].astype(np.float16).view(np.uint16)), f"column {j}"
+
+
+def test_zero_mask_and_empty_matrix():
+    w = synth.weights(64, 4096, 9)
+    x = synth.activations(4096, 9)
+    for kind, g in [(0, 128), (1, 0)]:
+        p = B.pack_2bitcsr(w, np.zeros_like(w, dtype=np.uint8), 2, g, kind)
+        y = G.run_sparse_gemv(p, x)
+        assert np.all(y.view(np.uint16) & 0x7FFF == 0)
+    p0 = B.pack_2bitcsr(np.zeros((0, 4096), dtype=np.float16), np.zeros((0, 4096), dtype=np.uint8), 2, 128, 0)
+    assert G.run_sparse_gemv(p0, x).size == 0
+
+
+def test_broken_row_ptr_yields_nan_not_a_fault():
+    p, o = _small_case(64, 4096, 2, 128, 0, seed=31)
+    x = synth.activations(4096, 31)
+    good = G.run_sparse_gemv(p, x)
+    p.row_ptr[7] += 8
+    p.row_ptr[40] = 0xFFFFFFF8
+    torch = G.torch_mod()
+    pd = p.to("cuda")
+    y = torch.zeros(64, dtype=torch.float16, device="cuda")
+    B.sparse_gemv(pd, G.to_dev(x.view(np.uint16)).view(torch.float16), y)
+    torch.cuda.synchronize()
+    y = y.cpu().numpy()
+    assert np.isnan(y[7]) and np.isnan(y[40])
+    keep = np.ones(64, dtype=bool)
+    keep[[7, 40]] = False
+    assert np.array_equal(y[keep].view(np.uint16), good[keep].view(np.uint16))
+
+
+# ---------------------------------------------------------------- dense INT4
+@pytest.mark.parametrize("rows,cols,g", [(37, 64, 8), (130, 1024, 128), (21, 11008, 128), (50, 4096, 64),
+                                         (9, 4096, 4096), (66, 2048, 32), (33, 320, 64)])
+def test_int4_gemv_small(rows, cols, g):
+    print(f"case int4_gemv {rows}x{cols} g={g}", flush=True)
+    w = synth.weights(rows, cols, 500 + rows)
+    x = synth.activations(cols, 500 + rows)
+    q, qp = B.quant_int4(w, g)
+    oq, oqp = O.quant_int4_dense(w, g)
+    assert np.array_equal(q, oq) and np.array_equal(qp, oqp)
+    y_ref, a_ref = O.int4_gemv(oq, oqp, g, x)
+    G.assert_close(G.run_int4_gemv(q, qp, g, x), y_ref, a_ref, "int4_gemv")
+
+
+def test_config2_dense_int4_full():
+    seed = synth.seed_for(2)
+    w = synth.weights(4096, 4096, seed)
+    x = synth.activations(4096, seed)
+    q, qp = B.quant_int4(w, 128)
+    oq, oqp = O.quant_int4_dense(w, 128)
+    assert np.array_equal(q, oq) and np.array_equal(qp, oqp)
+    y_ref, a_ref = O.int4_gemv(oq, oqp, 128, x)
+    G.assert_close(G.run_int4_gemv(q, qp, 128, x), y_ref, a_ref, "config 2")
+
+
+# ---------------------------------------------------------------- full sizes, sampled rows
+@pytest.mark.parametrize("name,rows,cols,kind,g,cfg", [
+    ("headline", 11008, 4096, 0, 128, synth.HEADLINE), ("config3", 11008, 4096, 1, 0, 3),
+    ("down", 4096, 11008, 0, 128, 5),
+])
+def test_full_size_sampled_rows(name, rows, cols, kind, g, cfg):
+    print(f"case full-size {name}", flush=True)
+    seed = synth.seed_for(cfg)
+    w, mask, p = G.packed_full(rows, cols, 2, g, kind, seed)
+    x = synth.activations(cols, seed)
+    y = G.run_sparse_gemv(p, x)
+    pick = G.sample_rows(rows, 192, seed)
+    # the oracle packs the sampled rows on its own: bytes must match the library's rows
+    o = O.pack_2bitcsr(w[pick], O.prune_n4_magnitude(w[pick], 2), 2, g, kind)
+    sub = G.row_subset(p, pick)
+    for k in ("values", "idx", "qparams"):
+        assert (o[k] is None and sub[k] is None) or np.array_equal(o[k], sub[k]), k
+    y_ref, a_ref = O.gemv(o, x)
+    G.assert_close(y[pick], y_ref, a_ref, name)
+    # property that holds at any size: every other row, decoded by the oracle from the
+    # library's bytes in slabs, also agrees
+    for r0 in range(0, rows, 2048):
+        rr = np.arange(r0, min(rows, r0 + 2048))
+        yr, ar = O.gemv(G.row_subset(p, rr), x)
+        G.assert_close(y[rr], yr, ar, f"{name} rows {r0}..")
+
+
+# ---------------------------------------------------------------- small M
+@pytest.mark.parametrize("M", [1, 2, 3, 4, 5, 16, 33, 64])
+def test_smallm_small_shapes(M):
+    print(f"case smallm M={M}", flush=True)
+    for rows, cols, n, g, kind in [(70, 1024, 2, 128, 0), (33, 96, 1, 32, 0), (40, 4096, 2, 0, 1), (18, 11008, 2, 128, 0)]:
+        p, o = _small_case(rows, cols, n, g, kind, seed=900 + M + rows)
+        X = synth.activation_rows(M, cols, 900 + M)
+        Y_ref, A_ref = O.gemm_smallm(o, X)
+        Y = G.run_sparse_gemm(p, X, ldx_pad=8 if M % 2 else 0, ldy_pad=6 if M % 2 else 0)
+        G.assert_close(Y, Y_ref, A_ref, f"smallm {rows}x{cols} M={M}")
+
+
+@pytest.mark.parametrize("rows,cols", [(11008, 4096), (4096, 11008)])
+@pytest.mark.parametrize("M", [4, 16, 64])
+def test_config5_smallm_full_size(rows, cols, M):
+    print(f"case config5 {rows}x{cols} M={M}", flush=True)
+    seed = synth.seed_for(5, 0 if rows == 11008 else 1)
+    w, mask, p = G.packed_full(rows, cols, 2, 128, 0, seed)
+    X = synth.activation_rows(M, cols, seed + M)
+    Y = G.run_sparse_gemm(p, X)
+    pick = G.sample_rows(rows, 96, seed + M)
+    o = O.pack_2bitcsr(w[pick], O.prune_n4_magnitude(w[pick], 2), 2, 128, 0)
+    sub = G.row_subset(p, pick)
+    for k in ("values", "idx", "qparams"):
+        assert np.array_equal(o[k], sub[k]), k
+    Y_ref, A_ref = O.gemm_smallm(o, X)
+    G.assert_close(Y[:, pick], Y_ref, A_ref, f"config 5 M={M}")
+    # M-row product equals M independent GEMVs on the same device path (within tolerance)
+    y0 = G.run_sparse_gemv(p, np.ascontiguousarray(X[0]))
+    G.assert_close(y0[pick], Y_ref[0], A_ref[0], "row 0 as a GEMV")
