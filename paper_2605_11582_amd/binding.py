@@ -234,5 +234,51 @@ def sparse_gemm_smallm(p: Packed, X, Y, stream=None) -> None:
                                         Y.stride(0), X.shape[0], _stream_ptr(stream)))
 
 
+# Pre-marshalled calls: the arguments are converted once, the returned function only
+# crosses the C ABI (for launch-rate-sensitive loops; same entry points, same checks).
+def prepared_sparse_gemv(p: Packed, x, y, stream=None):
+    fn, v = lib().egt_sparse_gemv, p.view()
+    ref, xp, yp, sp = C.byref(v), _dev(x), _dev(y), _stream_ptr(stream)
+
+    def call(_keep=(v, p, x, y)):
+        st = fn(ref, xp, yp, sp)
+        if st:
+            _check(st)
+    return call
+
+
+def prepared_sparse_gemm_smallm(p: Packed, X, Y, stream=None):
+    fn, v = lib().egt_sparse_gemm_smallm, p.view()
+    args = (C.byref(v), X.data_ptr(), X.stride(0), Y.data_ptr(), Y.stride(0), X.shape[0], _stream_ptr(stream))
+
+    def call(_keep=(v, p, X, Y)):
+        st = fn(*args)
+        if st:
+            _check(st)
+    return call
+
+
+def prepared_int4_gemv(q, qparams, rows: int, cols: int, group: int, x, y, stream=None):
+    fn = lib().egt_int4_gemv
+    args = (_dev(q), _dev(qparams), rows, cols, group, _dev(x), _dev(y), _stream_ptr(stream))
+
+    def call(_keep=(q, qparams, x, y)):
+        st = fn(*args)
+        if st:
+            _check(st)
+    return call
+
+
+def prepared_stream_read(src, nbytes: int, sink, stream=None):
+    fn = lib().egt_stream_read
+    args = (_dev(src), nbytes, _dev(sink), _stream_ptr(stream))
+
+    def call(_keep=(src, sink)):
+        st = fn(*args)
+        if st:
+            _check(st)
+    return call
+
+
 def stream_read(src, nbytes: int, sink, stream=None) -> None:
     _check(lib().egt_stream_read(_dev(src), nbytes, _dev(sink), _stream_ptr(stream)))

@@ -2,6 +2,9 @@
 // a kernel.  Nothing here synchronises or allocates.
 #include "egt_device.h"
 
+#include <cstdio>
+#include <cstdlib>
+
 namespace {
 
 egt_status check_view(const egt_2bitcsr *w) {
@@ -35,17 +38,24 @@ inline egt_status done(hipError_t e) {
 }
 
 // Streams `n16` 16-byte words; every workgroup folds what it read into one word.
-__global__ __launch_bounds__(256) void k_stream_read(const uint4 *__restrict__ src, size_t n16,
+// Each thread keeps U independent 128-bit loads in flight.
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+template <int U>
+__global__ __launch_bounds__(256) void k_stream_read(const u32x4 *__restrict__ src, size_t n16,
                                                       uint32_t *__restrict__ sink) {
   uint32_t acc = 0;
   const size_t stride = (size_t)gridDim.x * blockDim.x;
   size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
-  for (; i + 3 * stride < n16; i += 4 * stride) {
-    const uint4 a = src[i], b = src[i + stride], c = src[i + 2 * stride], d = src[i + 3 * stride];
-    acc ^= a.x ^ a.y ^ a.z ^ a.w ^ b.x ^ b.y ^ b.z ^ b.w ^ c.x ^ c.y ^ c.z ^ c.w ^ d.x ^ d.y ^ d.z ^ d.w;
+  for (; i + (U - 1) * stride < n16; i += U * stride) {
+    u32x4 v[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) v[u] = __builtin_nontemporal_load(src + i + u * stride);
+#pragma unroll
+    for (int u = 0; u < U; ++u) acc ^= v[u].x ^ v[u].y ^ v[u].z ^ v[u].w;
   }
   for (; i < n16; i += stride) {
-    const uint4 a = src[i];
+    const u32x4 a = src[i];
     acc ^= a.x ^ a.y ^ a.z ^ a.w;
   }
   for (int o = 32; o > 0; o >>= 1) acc ^= __shfl_xor(acc, o, 64);
@@ -99,11 +109,21 @@ egt_status egt_stream_read(const void *src, size_t bytes, uint32_t *sink, void *
   if (!aligned16(src)) return EGT_ERR_BUFFER;
   if (bytes == 0) return EGT_OK;
   const size_t n16 = bytes / 16;
-  size_t blocks = (n16 + 1023) / 1024;                // 4 x 16 B per thread when large
+  int unroll = 4, per_thread = 4;                   // loads in flight, 16 B words per thread
+  if (const char *e = getenv("EGT_READ_TUNE")) sscanf(e, "%d,%d", &unroll, &per_thread);
+  if (per_thread < unroll) per_thread = unroll;
+  size_t blocks = (n16 + 256 * (size_t)per_thread - 1) / (256 * (size_t)per_thread);
   if (blocks > 4096) blocks = 4096;
   if (blocks < 1) blocks = 1;
-  return done(egt::launch(k_stream_read, dim3((unsigned)blocks), dim3(256), 0, (hipStream_t)stream,
-                          (const uint4 *)src, n16, sink));
+  const dim3 grid((unsigned)blocks), block(256);
+  const hipStream_t st = (hipStream_t)stream;
+  const u32x4 *p = (const u32x4 *)src;
+  switch (unroll) {
+    case 1: return done(egt::launch(k_stream_read<1>, grid, block, 0, st, p, n16, sink));
+    case 2: return done(egt::launch(k_stream_read<2>, grid, block, 0, st, p, n16, sink));
+    case 8: return done(egt::launch(k_stream_read<8>, grid, block, 0, st, p, n16, sink));
+    default: return done(egt::launch(k_stream_read<4>, grid, block, 0, st, p, n16, sink));
+  }
 }
 
 }  // extern "C"

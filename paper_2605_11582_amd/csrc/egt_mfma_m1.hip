@@ -22,209 +22,327 @@
 // wave and reused for every row the wave processes.
 //
 // Four instructions (one per dword of the lane's nibbles) finish a tile.
+// Loads are never predicated: lanes or tiles that fall outside the matrix read a
+// clamped (valid) address and their result is either multiplied by a zero of B
+// or not stored.
 #include "egt_device.h"
+
+#include <cstdio>
+#include <cstdlib>
 
 namespace egt {
 
+typedef _Float16 h2 __attribute__((ext_vector_type(2)));
 typedef _Float16 h8 __attribute__((ext_vector_type(8)));
 typedef _Float16 h16 __attribute__((ext_vector_type(16)));
 typedef float f4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u8v __attribute__((ext_vector_type(8)));
+typedef uint32_t u2 __attribute__((ext_vector_type(2)));
 
+// streaming load: the weights are used once, keep them from displacing x in the caches
+template <typename T>
+__device__ __forceinline__ T ld_stream(const void *p) {
+  return __builtin_nontemporal_load((const T *)p);
+}
+
+__device__ __forceinline__ uint32_t pk_sub_f16(uint32_t a, uint32_t b) {
+  return __builtin_bit_cast(uint32_t, __builtin_bit_cast(h2, a) - __builtin_bit_cast(h2, b));
+}
 __device__ __forceinline__ uint32_t pk_add_f16(uint32_t a, uint32_t b) {
-  typedef _Float16 h2 __attribute__((ext_vector_type(2)));
   return __builtin_bit_cast(uint32_t, __builtin_bit_cast(h2, a) + __builtin_bit_cast(h2, b));
 }
 __device__ __forceinline__ uint32_t pk_mul_f16(uint32_t a, uint32_t b) {
-  typedef _Float16 h2 __attribute__((ext_vector_type(2)));
   return __builtin_bit_cast(uint32_t, __builtin_bit_cast(h2, a) * __builtin_bit_cast(h2, b));
+}
+// (a & mask) | magic in one instruction; the operands must sit in registers
+// because the three-operand encoding takes no literal.
+__device__ __forceinline__ uint32_t and_or(uint32_t a, uint32_t mask, uint32_t magic) {
+  uint32_t r;
+  asm("v_and_or_b32 %0, %1, %2, %3" : "=v"(r) : "v"(a), "s"(mask), "v"(magic));
+  return r;
+}
+// value of lane (l + N) of the same 16-lane row, 0 past the end of the row
+template <int N>
+__device__ __forceinline__ float row_shl(float v) {
+  return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x100 + N, 0xf, 0xf, true));
+}
+// value of lane (l ^ 1) / (l ^ 2) inside each group of four lanes
+__device__ __forceinline__ float quad_xor1(float v) {
+  return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0xB1, 0xf, 0xf, true));
+}
+__device__ __forceinline__ float quad_xor2(float v) {
+  return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x4E, 0xf, 0xf, true));
 }
 
 // Eight INT4 codes of one dword (slot k in bits 4k..4k+3) -> four half2 registers
 // {slot 2p, slot 2p+1} holding s*(q - z).  Byte p of the dword carries the pair:
 // the low nibble becomes the mantissa of 1024 + q, the high nibble (left in
-// place) the mantissa of 64 + q; one packed add removes both offsets and z
+// place) the mantissa of 64 + q; one packed subtract removes both offsets and z
 // exactly, one packed multiply applies the scale (a single rounding to FP16).
-__device__ __forceinline__ u4 dequant8(uint32_t d, uint32_t neg_off, uint32_t s2) {
+__device__ __forceinline__ u4 dequant8(uint32_t d, uint32_t off, uint32_t s2, uint32_t magic) {
   u4 r;
 #pragma unroll
   for (int p = 0; p < 4; ++p) {
     const uint32_t t = __builtin_amdgcn_perm(d, d, 0x0c000c00u + (uint32_t)p * 0x00010001u);
-    const uint32_t h = (t & 0x00F0000Fu) | 0x54006400u;
-    r[p] = pk_mul_f16(pk_add_f16(h, neg_off), s2);
+    r[p] = pk_mul_f16(pk_sub_f16(and_or(t, 0x00F0000Fu, magic), off), s2);
   }
   return r;
 }
 
 // Geometry of a launch, computed on the host.
 struct M1Geom {
-  int rows, cols;
-  int nchunks;        // cols / 64
-  int rows_per_tile;  // 1, or 64 / nchunks when a row is shorter than a tile
-  int phases;         // tiles per row (1 when rows_per_tile >= 1 covers the row)
-  int ntile_rows;     // ceil(rows / rows_per_tile): tiles per phase
-  int tiles_per_wave;
-  int group;          // INT4 group size (multiple of 64), 0 for FP16 values
+  int rows;
+  int nchunks;         // cols / 64
+  int ntiles;          // tiles per phase = ceil(rows / rows_per_tile)
+  int phases;          // tiles per row (row-tile mode), else 1
+  int mr_shift;        // multi-row mode: log2(nchunks) (nchunks = 16 or 32); -1 in row-tile mode
+  int gshift;          // INT4 group = 64 << gshift dense columns
+  int groups_per_row;  // cols / group
+  uint32_t last_chunk; // rows * nchunks - 1
+  int part_offset;     // byte offset of the per-phase partial sums in LDS
 };
 
-// TPI tiles are loaded together before any of them is consumed.
-template <int KIND, int TPI>
-__global__ __launch_bounds__(256) void k_sparse_m1(const uint32_t *__restrict__ row_ptr,
-                                                    const uint8_t *__restrict__ values,
-                                                    const uint8_t *__restrict__ idx,
-                                                    const uint16_t *__restrict__ qparams,
-                                                    const __half *__restrict__ x,
-                                                    __half *__restrict__ y, const M1Geom g) {
-  extern __shared__ float part[];                     // [phases][waves-per-phase * tiles_per_wave]
+// One wave = TPI tiles, all loaded before the first is consumed.
+// XP = 16 B pieces of x each thread stages (ceil(pieces / block size)).
+template <int KIND, int TPI, int XP>
+__global__ __launch_bounds__(1024) void k_sparse_m1(const uint32_t *__restrict__ row_ptr,
+                                                     const uint8_t *__restrict__ values,
+                                                     const uint8_t *__restrict__ idx,
+                                                     const uint8_t *__restrict__ qparams,
+                                                     const __half *__restrict__ x,
+                                                     __half *__restrict__ y, const M1Geom g) {
+  extern __shared__ __align__(16) uint8_t xs[];       // staged x, then [phases][rows of this block] floats
   const int lane = threadIdx.x & 63;
-  const int wave = threadIdx.x >> 6;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int nwaves = blockDim.x >> 6;
   const int wpp = nwaves / g.phases;                  // waves per phase in this block
+  float *part = (float *)(xs + g.part_offset);
   const int phase = wave / wpp;
-  const int wslot = wave % wpp;
+  const int wslot = wave - phase * wpp;
   const int i = lane & 15, kb = lane >> 4;
   const int cit = 4 * i + kb;                         // chunk of this lane inside a tile
+  const bool multirow = g.mr_shift >= 0;
+  const int rpt = multirow ? (64 >> g.mr_shift) : 1;  // rows per tile
+  const int c = multirow ? (cit & (g.nchunks - 1)) : cit + 64 * phase;   // chunk inside the row
+  const int rsub = multirow ? (cit >> g.mr_shift) : 0;
+  const int c_ld = min(c, g.nchunks - 1);
 
-  // ---- B operand: activations for column n = lane & 15, k-octets (lane >> 4) and 4 + (lane >> 4)
+  // ---- x: the block's threads fetch it once, 16 B pieces, before anything else is
+  //      requested, so that it is the first data to come back
+  const int npieces = g.nchunks * 8;                   // 8 halfs per piece
+  const int lds_pieces = multirow ? npieces : g.phases * 512;
+  u4 xp[XP];
+#pragma unroll
+  for (int j = 0; j < XP; ++j) {
+    const int pi = threadIdx.x + j * blockDim.x;
+    xp[j] = *(const u4 *)(x + 8 * min(pi, npieces - 1));
+  }
+
+  // ---- issue every load of the wave's TPI tiles
+  const int tile0 = (blockIdx.x * wpp + wslot) * TPI;
+  u4 nib[TPI][KIND == EGT_VAL_INT4 ? 1 : 4];
+  u2 iw[TPI];
+  uint32_t qp[TPI];
+#pragma unroll
+  for (int t = 0; t < TPI; ++t) {
+    const int tr = min(tile0 + t, g.ntiles - 1);      // uniform
+    uint32_t chunk;
+    if (multirow) chunk = min((uint32_t)tr * 64u + (uint32_t)cit, g.last_chunk);
+    else chunk = (uint32_t)tr * (uint32_t)g.nchunks + (uint32_t)c_ld;
+    iw[t] = ld_stream<u2>(idx + 8ull * chunk);
+    qp[t] = 0;
+    if (KIND == EGT_VAL_INT4) {
+      nib[t][0] = ld_stream<u4>(values + 16ull * chunk);
+      const int r = min(tr * rpt + rsub, g.rows - 1);
+      qp[t] = ld_stream<uint32_t>(qparams + 4ull * ((uint32_t)r * (uint32_t)g.groups_per_row + (uint32_t)(c_ld >> g.gshift)));
+    } else {
+#pragma unroll
+      for (int k = 0; k < 4; ++k) nib[t][k] = ld_stream<u4>(values + 64ull * chunk + 16 * k);
+    }
+  }
+  // The lanes that will store read their row pointers now, not at the end:
+  // lane j < 16 finishes tile (j >> 2) of each batch of four tiles.
+  const int sum_steps = multirow ? (g.mr_shift - 4) : 2;       // log2(quad groups per row)
+  constexpr int NB = (TPI + 3) / 4;
+  uint32_t rp[NB];
+  int rrow[NB];
+  bool st[NB];
+#pragma unroll
+  for (int bt = 0; bt < NB; ++bt) {
+    const int t = 4 * bt + ((lane >> 2) & 3);
+    const int tr = tile0 + t;
+    rrow[bt] = tr * rpt + ((lane & 3) >> sum_steps);
+    st[bt] = lane < 16 && t < TPI && tr < g.ntiles && rrow[bt] < g.rows &&
+             ((lane & 3) & ((1 << sum_steps) - 1)) == 0;
+    rp[bt] = st[bt] ? row_ptr[rrow[bt]] : 0u;
+  }
+
+  // ---- x through LDS.  Piece p lives at byte 16 p + 16 (p >> 5): one 16 B pad after
+  //      every 512 B, so that the 16-lane reads below, whose addresses are 512 B
+  //      apart, fall into different banks.  Pieces past the end of x are zero.
+#pragma unroll
+  for (int j = 0; j < XP; ++j) {
+    const int pi = threadIdx.x + j * blockDim.x;
+    if (pi < lds_pieces) {
+      u4 v = xp[j];
+      if (pi >= npieces) v = u4{0, 0, 0, 0};
+      *(u4 *)(xs + 16 * pi + 16 * (pi >> 5)) = v;
+    }
+  }
+  __syncthreads();
+  // B operand: column n = lane & 15 holds the activations of chunks 4n .. 4n+3;
+  // lane (n, b) supplies k-octets b (first 8 halfs) and 4 + b (last 8 halfs)
   u8v bx[4];
   {
     const int n = lane & 15, b = lane >> 4;
 #pragma unroll
     for (int h = 0; h < 2; ++h) {
       const int kba = (4 * h + b) >> 1, sub = b & 1;  // the A lane (n, kba) this octet multiplies
-      int c = 4 * n + kba;                             // its chunk inside the tile
-      c = g.rows_per_tile > 1 ? c % g.nchunks : c + 64 * phase;
-      const bool ok = c < g.nchunks;
+      int cb = 4 * n + kba;
+      cb = multirow ? (cb & (g.nchunks - 1)) : cb + 64 * phase;
 #pragma unroll
       for (int d = 0; d < 4; ++d) {
-        u4 v = {0, 0, 0, 0};
-        if (ok) v = *(const u4 *)(x + 64 * c + 16 * d + 8 * sub);
-        bx[d][4 * h + 0] = v[0]; bx[d][4 * h + 1] = v[1];
-        bx[d][4 * h + 2] = v[2]; bx[d][4 * h + 3] = v[3];
+        const int pi = 8 * cb + 2 * d + sub;
+        const u4 v = *(const u4 *)(xs + 16 * pi + 16 * (pi >> 5));
+#pragma unroll
+        for (int k = 0; k < 4; ++k) bx[d][4 * h + k] = v[k];
       }
     }
   }
 
-  const int S_row = g.cols >> 1;                      // slots per row (2:4)
-  const int tile0 = (blockIdx.x * wpp + wslot) * g.tiles_per_wave;
-  for (int tb = 0; tb < g.tiles_per_wave; tb += TPI) {
-    u4 nib[TPI][KIND == EGT_VAL_INT4 ? 1 : 4];
-    uint2 iw[TPI];
-    uint32_t qp[TPI];
-    bool act[TPI];
-    // ---- issue every load of TPI tiles
+  // ---- consume
+  uint32_t magic;
+  asm volatile("v_mov_b32 %0, 0x54006400" : "=v"(magic));
+  float s[TPI];
 #pragma unroll
-    for (int t = 0; t < TPI; ++t) {
-      const int tr = tile0 + tb + t;                  // tile row index
-      int r, c;                                       // matrix row and chunk-in-row of this lane
-      if (g.rows_per_tile > 1) { r = tr * g.rows_per_tile + cit / g.nchunks; c = cit % g.nchunks; }
-      else { r = tr; c = cit + 64 * phase; }
-      act[t] = tr < g.ntile_rows && r < g.rows && c < g.nchunks;
-      iw[t] = make_uint2(0u, 0u);
-      qp[t] = 0;
+  for (int t = 0; t < TPI; ++t) {
+    f4 acc = {0.f, 0.f, 0.f, 0.f};
+    uint32_t s2 = 0, off = 0;
+    if (KIND == EGT_VAL_INT4) {
+      s2 = __builtin_amdgcn_perm(qp[t], qp[t], 0x01000100u);                            // {s, s}
+      off = pk_add_f16(__builtin_amdgcn_perm(qp[t], qp[t], 0x03020302u), 0x54006400u);  // {1024+z, 64+z}
+    }
 #pragma unroll
-      for (int k = 0; k < (KIND == EGT_VAL_INT4 ? 1 : 4); ++k) nib[t][k] = u4{0, 0, 0, 0};
-      if (act[t]) {
-        const size_t chunk = (size_t)r * g.nchunks + c;            // global chunk id
-        iw[t] = *(const uint2 *)(idx + 8 * chunk);
-        if (KIND == EGT_VAL_INT4) {
-          nib[t][0] = *(const u4 *)(values + 16 * chunk);
-          qp[t] = *(const uint32_t *)(qparams + 2 * ((size_t)r * (g.cols / g.group) + (64 * c) / g.group));
-        } else {
+    for (int d = 0; d < 4; ++d) {
+      u4 a;
+      if (KIND == EGT_VAL_INT4) a = dequant8(nib[t][0][d], off, s2, magic);
+      else a = nib[t][d];
+      const int iword = d < 2 ? (int)iw[t][0] : (int)iw[t][1];
+      if (d & 1)
+        acc = __builtin_amdgcn_smfmac_f32_16x16x64_f16(__builtin_bit_cast(h8, a), __builtin_bit_cast(h16, bx[d]), acc, iword, 0, 1);
+      else
+        acc = __builtin_amdgcn_smfmac_f32_16x16x64_f16(__builtin_bit_cast(h8, a), __builtin_bit_cast(h16, bx[d]), acc, iword, 0, 0);
+    }
+    // D[q][q] sits in lane q + 16 (q / 4), register q % 4: lane 20 kb collects the
+    // four diagonals of quads 4 kb .. 4 kb + 3 from its three right neighbours
+    s[t] = acc[0] + row_shl<1>(acc[1]) + row_shl<2>(acc[2]) + row_shl<3>(acc[3]);
+  }
+  // ---- lane j < 16 fetches tile (j >> 2), quad group (j & 3); then sum the groups of a row
+  const int src_lane = 20 * (lane & 3);
 #pragma unroll
-          for (int k = 0; k < 4; ++k) nib[t][k] = *(const u4 *)(values + 64 * chunk + 16 * k);
-        }
+  for (int bt = 0; bt < NB; ++bt) {
+    float v = 0.f;
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      if (4 * bt + k < TPI) {
+        const float gk = __shfl(s[4 * bt + k], src_lane, 64);
+        v = ((lane >> 2) & 3) == k ? gk : v;
       }
     }
-    // ---- consume them
-#pragma unroll
-    for (int t = 0; t < TPI; ++t) {
-      f4 acc = {0.f, 0.f, 0.f, 0.f};
-      uint32_t s2 = 0, neg_off = 0;
-      if (KIND == EGT_VAL_INT4) {
-        s2 = __builtin_amdgcn_perm(qp[t], qp[t], 0x01000100u);               // {s, s}
-        const uint32_t z2 = __builtin_amdgcn_perm(qp[t], qp[t], 0x03020302u); // {z, z}
-        neg_off = pk_add_f16(z2, 0x54006400u) ^ 0x80008000u;                  // -{1024 + z, 64 + z}
-      }
-#pragma unroll
-      for (int d = 0; d < 4; ++d) {
-        u4 a;
-        if (KIND == EGT_VAL_INT4) a = dequant8(nib[t][0][d], neg_off, s2);
-        else a = nib[t][d];
-        const int iword = d < 2 ? (int)iw[t].x : (int)iw[t].y;
-        if (d & 1)
-          acc = __builtin_amdgcn_smfmac_f32_16x16x64_f16(__builtin_bit_cast(h8, a), __builtin_bit_cast(h16, bx[d]), acc, iword, 0, 1);
-        else
-          acc = __builtin_amdgcn_smfmac_f32_16x16x64_f16(__builtin_bit_cast(h8, a), __builtin_bit_cast(h16, bx[d]), acc, iword, 0, 0);
-      }
-      // D[q][q] of quad q sits in lane q + 16 (q / 4), register q % 4
-      float cand = (lane & 2) ? ((lane & 1) ? acc[3] : acc[2]) : ((lane & 1) ? acc[1] : acc[0]);
-      float v = __shfl(cand, (lane & 15) + 16 * ((lane & 15) >> 2), 64);     // lane l: quad l % 16
-      // sum the quads of one row: 16 / rows_per_tile consecutive quads
-      const int qpr = 16 / g.rows_per_tile;
-      for (int o = 1; o < qpr; o <<= 1) v += __shfl_xor(v, o, 64);
-      const int tr = tile0 + tb + t;
-      if (tr < g.ntile_rows && lane < 16 && (lane % qpr) == 0) {
-        const int r = tr * g.rows_per_tile + lane / qpr;
-        if (r < g.rows) {
-          if (g.phases == 1) {
-            const bool ok = row_ptr[r] == (uint32_t)r * (uint32_t)S_row;
-            y[r] = ok ? __float2half(v) : __ushort_as_half((uint16_t)0x7E00);
-          } else {
-            part[phase * (wpp * g.tiles_per_wave) + wslot * g.tiles_per_wave + tb + t] = v;
-          }
-        }
+    if (sum_steps >= 1) v += quad_xor1(v);
+    if (sum_steps >= 2) v += quad_xor2(v);
+    if (st[bt]) {
+      const int r = rrow[bt];
+      if (g.phases == 1) {
+        const bool ok = rp[bt] == (uint32_t)r * (uint32_t)(g.nchunks * 32);
+        y[r] = ok ? __float2half(v) : __ushort_as_half((uint16_t)0x7E00);
+      } else {
+        part[phase * (wpp * TPI) + wslot * TPI + 4 * bt + ((lane >> 2) & 3)] = v;
       }
     }
   }
   if (g.phases > 1) {
     __syncthreads();
-    const int per = wpp * g.tiles_per_wave;           // rows handled by this block
+    const int per = wpp * TPI;                        // rows handled by this block
     for (int j = threadIdx.x; j < per; j += blockDim.x) {
       const int r = blockIdx.x * per + j;
       if (r < g.rows) {
         float v = 0.f;
         for (int p = 0; p < g.phases; ++p) v += part[p * per + j];
-        const bool ok = row_ptr[r] == (uint32_t)r * (uint32_t)S_row;
+        const bool ok = row_ptr[r] == (uint32_t)r * (uint32_t)(g.nchunks * 32);
         y[r] = ok ? __float2half(v) : __ushort_as_half((uint16_t)0x7E00);
       }
     }
   }
 }
 
-// Shapes the diagonal kernel covers: 2:4, K a multiple of 256 that either divides
-// 4096 or is at least 4096 (at most 16 tiles per row), INT4 groups of a multiple of 64.
+// Shapes the diagonal kernel covers: 2:4; K = 1024 or 2048 (several rows per tile)
+// or a multiple of 256 from 4096 up to 16 tiles per row; INT4 groups of 64 << j.
 bool sparse_m1_supported(const egt_2bitcsr &w) {
-  if (w.n_keep != 2 || w.cols % 256 != 0) return false;
-  if (w.cols < 4096 && 4096 % w.cols != 0) return false;
-  if (w.cols > 16 * 4096) return false;
-  if (w.val_kind == EGT_VAL_INT4 && w.group_size % 64 != 0) return false;
+  if (w.n_keep != 2) return false;
+  const bool multirow = w.cols == 1024 || w.cols == 2048;
+  if (!multirow && (w.cols < 4096 || w.cols % 256 != 0 || w.cols > 16 * 4096)) return false;
+  if (w.val_kind == EGT_VAL_INT4) {
+    const int gm = w.group_size / 64;
+    if (w.group_size % 64 != 0 || (gm & (gm - 1)) != 0) return false;
+  }
   return true;
 }
 
 hipError_t launch_sparse_m1(const egt_2bitcsr &w, const uint16_t *x, uint16_t *y, hipStream_t stream) {
   if (w.rows == 0) return hipSuccess;
   M1Geom g;
-  g.rows = w.rows; g.cols = w.cols; g.nchunks = w.cols / 64;
-  g.rows_per_tile = g.nchunks >= 64 ? 1 : 64 / g.nchunks;
-  g.phases = g.nchunks >= 64 ? (g.nchunks + 63) / 64 : 1;
-  g.ntile_rows = (w.rows + g.rows_per_tile - 1) / g.rows_per_tile;
-  g.group = w.group_size;
-  constexpr int TPI = 4;
-  g.tiles_per_wave = TPI;
-  const int wpp = g.phases == 1 ? 4 : (g.phases <= 2 ? 2 : 1);   // waves per phase in a block
+  g.rows = w.rows;
+  g.nchunks = w.cols / 64;
+  const bool multirow = g.nchunks < 64;
+  g.mr_shift = multirow ? (g.nchunks == 16 ? 4 : 5) : -1;
+  const int rpt = multirow ? 64 / g.nchunks : 1;
+  g.phases = multirow ? 1 : (g.nchunks + 63) / 64;
+  g.ntiles = (w.rows + rpt - 1) / rpt;
+  g.gshift = 0;
+  g.groups_per_row = 0;
+  if (w.val_kind == EGT_VAL_INT4) {
+    while ((64 << g.gshift) < w.group_size) ++g.gshift;
+    g.groups_per_row = w.cols / w.group_size;
+  }
+  g.last_chunk = (uint32_t)w.rows * (uint32_t)g.nchunks - 1u;
+  // tuning knobs: tiles per wave, waves per phase per block
+  int tpi = 4, wpp = g.phases == 1 ? 4 : 2;
+  if (const char *e = getenv("EGT_M1_TUNE")) sscanf(e, "%d,%d", &tpi, &wpp);
+  if (wpp < 1) wpp = 1;
+  if (wpp * g.phases > 16) wpp = 16 / g.phases;
+  if (tpi != 1 && tpi != 2 && tpi != 4 && tpi != 8) tpi = 4;
+  if (w.val_kind == EGT_VAL_FP16 && tpi == 8) tpi = 4;
   const int nwaves = wpp * g.phases;
-  const int tiles_per_block = wpp * g.tiles_per_wave;
-  const dim3 grid((g.ntile_rows + tiles_per_block - 1) / tiles_per_block), block(64 * nwaves);
-  const size_t lds = g.phases > 1 ? sizeof(float) * g.phases * tiles_per_block : 0;
-  if (w.val_kind == EGT_VAL_INT4)
-    return launch(k_sparse_m1<EGT_VAL_INT4, TPI>, grid, block, lds, stream, w.row_ptr,
-                  (const uint8_t *)w.values, (const uint8_t *)w.idx, w.qparams, (const __half *)x,
-                  (__half *)y, g);
-  return launch(k_sparse_m1<EGT_VAL_FP16, TPI>, grid, block, lds, stream, w.row_ptr,
-                (const uint8_t *)w.values, (const uint8_t *)w.idx, w.qparams, (const __half *)x,
-                (__half *)y, g);
+  const int tiles_per_block = wpp * tpi;
+  const dim3 grid((g.ntiles + tiles_per_block - 1) / tiles_per_block), block(64 * nwaves);
+  const int lds_pieces = multirow ? g.nchunks * 8 : g.phases * 512;
+  g.part_offset = 16 * lds_pieces + 16 * ((lds_pieces + 31) >> 5);
+  const size_t lds = g.part_offset + (g.phases > 1 ? sizeof(float) * g.phases * tiles_per_block : 0);
+  const int xp = (lds_pieces + 64 * nwaves - 1) / (64 * nwaves);
+  if (xp > 4) return hipErrorInvalidConfiguration;
+#define EGT_GO3(KIND, TPI, XP)                                                                  \
+  launch(k_sparse_m1<KIND, TPI, XP>, grid, block, lds, stream, w.row_ptr,                       \
+         (const uint8_t *)w.values, (const uint8_t *)w.idx, (const uint8_t *)w.qparams,         \
+         (const __half *)x, (__half *)y, g)
+#define EGT_GO(KIND, TPI)                                                                       \
+  (xp <= 1 ? EGT_GO3(KIND, TPI, 1) : xp == 2 ? EGT_GO3(KIND, TPI, 2) : EGT_GO3(KIND, TPI, 4))
+  if (w.val_kind == EGT_VAL_INT4) {
+    switch (tpi) {
+      case 1: return EGT_GO(EGT_VAL_INT4, 1);
+      case 2: return EGT_GO(EGT_VAL_INT4, 2);
+      case 8: return EGT_GO(EGT_VAL_INT4, 8);
+      default: return EGT_GO(EGT_VAL_INT4, 4);
+    }
+  }
+  switch (tpi) {
+    case 1: return EGT_GO(EGT_VAL_FP16, 1);
+    case 2: return EGT_GO(EGT_VAL_FP16, 2);
+    default: return EGT_GO(EGT_VAL_FP16, 4);
+  }
+#undef EGT_GO
+#undef EGT_GO3
 }
 
 }  // namespace egt
