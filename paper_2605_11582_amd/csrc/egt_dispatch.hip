@@ -11,6 +11,7 @@ hipError_t launch_sparse(const egt_2bitcsr &w, const uint16_t *X, int64_t ldx, u
 
 hipError_t launch_int4(const uint8_t *q, const uint16_t *qparams, int rows, int cols, int group,
                        const uint16_t *x, uint16_t *y, hipStream_t stream) {
+  if (int4_m1_supported(cols, group)) return launch_int4_m1(q, qparams, rows, cols, x, y, stream);
   return launch_int4_generic(q, qparams, rows, cols, group, x, y, stream);
 }
 

@@ -1,0 +1,67 @@
+// Register-level helpers shared by the matrix-core kernels.
+#ifndef EGT_MFMA_COMMON_H
+#define EGT_MFMA_COMMON_H
+
+#include "egt_device.h"
+
+namespace egt {
+
+typedef _Float16 h2 __attribute__((ext_vector_type(2)));
+typedef _Float16 h8 __attribute__((ext_vector_type(8)));
+typedef _Float16 h16 __attribute__((ext_vector_type(16)));
+typedef float f4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u8v __attribute__((ext_vector_type(8)));
+typedef uint32_t u2 __attribute__((ext_vector_type(2)));
+
+// streaming load: the weights are used once, keep them from displacing x in the caches
+template <typename T>
+__device__ __forceinline__ T ld_stream(const void *p) {
+  return __builtin_nontemporal_load((const T *)p);
+}
+
+__device__ __forceinline__ uint32_t pk_sub_f16(uint32_t a, uint32_t b) {
+  return __builtin_bit_cast(uint32_t, __builtin_bit_cast(h2, a) - __builtin_bit_cast(h2, b));
+}
+__device__ __forceinline__ uint32_t pk_add_f16(uint32_t a, uint32_t b) {
+  return __builtin_bit_cast(uint32_t, __builtin_bit_cast(h2, a) + __builtin_bit_cast(h2, b));
+}
+__device__ __forceinline__ uint32_t pk_mul_f16(uint32_t a, uint32_t b) {
+  return __builtin_bit_cast(uint32_t, __builtin_bit_cast(h2, a) * __builtin_bit_cast(h2, b));
+}
+// (a & mask) | magic.  The compiler fuses this into one v_and_or_b32 only when mask
+// and magic are register values: the three-operand encoding takes no literal, so
+// callers pass them in from kernel arguments instead of writing constants.  (Inline
+// assembly is not an option here: results that feed a matrix instruction need wait
+// states the compiler only inserts for instructions it emitted itself.)
+__device__ __forceinline__ uint32_t and_or(uint32_t a, uint32_t mask, uint32_t magic) {
+  return (a & mask) | magic;
+}
+// Pins a wave-uniform value into a vector register (an empty statement for the
+// assembler): with the mask in a scalar and the magic in a vector register the
+// fused and-or respects the one-scalar-operand limit of the encoding.
+__device__ __forceinline__ uint32_t in_vgpr(uint32_t v) {
+  asm volatile("" : "+v"(v));
+  return v;
+}
+// value of lane (l + N) of the same 16-lane row, 0 past the end of the row
+template <int N>
+__device__ __forceinline__ float row_shl(float v) {
+  return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x100 + N, 0xf, 0xf, true));
+}
+// value of lane (l ^ 1) / (l ^ 2) inside each group of four lanes
+__device__ __forceinline__ float quad_xor1(float v) {
+  return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0xB1, 0xf, 0xf, true));
+}
+__device__ __forceinline__ float quad_xor2(float v) {
+  return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x4E, 0xf, 0xf, true));
+}
+
+
+// Index of the four-lane group, (lane >> 2) & 3, selects among four values.
+__device__ __forceinline__ float select4(int k, float a0, float a1, float a2, float a3) {
+  return (k & 2) ? ((k & 1) ? a3 : a2) : ((k & 1) ? a1 : a0);
+}
+
+}  // namespace egt
+#endif

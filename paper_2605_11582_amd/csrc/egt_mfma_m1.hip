@@ -25,67 +25,24 @@
 // Loads are never predicated: lanes or tiles that fall outside the matrix read a
 // clamped (valid) address and their result is either multiplied by a zero of B
 // or not stored.
-#include "egt_device.h"
+#include "egt_mfma_common.h"
 
 #include <cstdio>
 #include <cstdlib>
 
 namespace egt {
 
-typedef _Float16 h2 __attribute__((ext_vector_type(2)));
-typedef _Float16 h8 __attribute__((ext_vector_type(8)));
-typedef _Float16 h16 __attribute__((ext_vector_type(16)));
-typedef float f4 __attribute__((ext_vector_type(4)));
-typedef uint32_t u4 __attribute__((ext_vector_type(4)));
-typedef uint32_t u8v __attribute__((ext_vector_type(8)));
-typedef uint32_t u2 __attribute__((ext_vector_type(2)));
-
-// streaming load: the weights are used once, keep them from displacing x in the caches
-template <typename T>
-__device__ __forceinline__ T ld_stream(const void *p) {
-  return __builtin_nontemporal_load((const T *)p);
-}
-
-__device__ __forceinline__ uint32_t pk_sub_f16(uint32_t a, uint32_t b) {
-  return __builtin_bit_cast(uint32_t, __builtin_bit_cast(h2, a) - __builtin_bit_cast(h2, b));
-}
-__device__ __forceinline__ uint32_t pk_add_f16(uint32_t a, uint32_t b) {
-  return __builtin_bit_cast(uint32_t, __builtin_bit_cast(h2, a) + __builtin_bit_cast(h2, b));
-}
-__device__ __forceinline__ uint32_t pk_mul_f16(uint32_t a, uint32_t b) {
-  return __builtin_bit_cast(uint32_t, __builtin_bit_cast(h2, a) * __builtin_bit_cast(h2, b));
-}
-// (a & mask) | magic in one instruction; the operands must sit in registers
-// because the three-operand encoding takes no literal.
-__device__ __forceinline__ uint32_t and_or(uint32_t a, uint32_t mask, uint32_t magic) {
-  uint32_t r;
-  asm("v_and_or_b32 %0, %1, %2, %3" : "=v"(r) : "v"(a), "s"(mask), "v"(magic));
-  return r;
-}
-// value of lane (l + N) of the same 16-lane row, 0 past the end of the row
-template <int N>
-__device__ __forceinline__ float row_shl(float v) {
-  return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x100 + N, 0xf, 0xf, true));
-}
-// value of lane (l ^ 1) / (l ^ 2) inside each group of four lanes
-__device__ __forceinline__ float quad_xor1(float v) {
-  return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0xB1, 0xf, 0xf, true));
-}
-__device__ __forceinline__ float quad_xor2(float v) {
-  return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x4E, 0xf, 0xf, true));
-}
-
 // Eight INT4 codes of one dword (slot k in bits 4k..4k+3) -> four half2 registers
 // {slot 2p, slot 2p+1} holding s*(q - z).  Byte p of the dword carries the pair:
 // the low nibble becomes the mantissa of 1024 + q, the high nibble (left in
 // place) the mantissa of 64 + q; one packed subtract removes both offsets and z
 // exactly, one packed multiply applies the scale (a single rounding to FP16).
-__device__ __forceinline__ u4 dequant8(uint32_t d, uint32_t off, uint32_t s2, uint32_t magic) {
+__device__ __forceinline__ u4 dequant8(uint32_t d, uint32_t off, uint32_t s2, uint32_t mask, uint32_t magic) {
   u4 r;
 #pragma unroll
   for (int p = 0; p < 4; ++p) {
     const uint32_t t = __builtin_amdgcn_perm(d, d, 0x0c000c00u + (uint32_t)p * 0x00010001u);
-    r[p] = pk_mul_f16(pk_sub_f16(and_or(t, 0x00F0000Fu, magic), off), s2);
+    r[p] = pk_mul_f16(pk_sub_f16(and_or(t, mask, magic), off), s2);
   }
   return r;
 }
@@ -101,6 +58,8 @@ struct M1Geom {
   int groups_per_row;  // cols / group
   uint32_t last_chunk; // rows * nchunks - 1
   int part_offset;     // byte offset of the per-phase partial sums in LDS
+  uint32_t nib_mask;   // 0x00F0000F: low nibble of the low half, high nibble of the high half
+  uint32_t nib_magic;  // 0x54006400: FP16 {1024.0, 64.0}
 };
 
 // One wave = TPI tiles, all loaded before the first is consumed.
@@ -212,8 +171,7 @@ __global__ __launch_bounds__(1024) void k_sparse_m1(const uint32_t *__restrict__
   }
 
   // ---- consume
-  uint32_t magic;
-  asm volatile("v_mov_b32 %0, 0x54006400" : "=v"(magic));
+  const uint32_t magic = in_vgpr(g.nib_magic);
   float s[TPI];
 #pragma unroll
   for (int t = 0; t < TPI; ++t) {
@@ -221,12 +179,12 @@ __global__ __launch_bounds__(1024) void k_sparse_m1(const uint32_t *__restrict__
     uint32_t s2 = 0, off = 0;
     if (KIND == EGT_VAL_INT4) {
       s2 = __builtin_amdgcn_perm(qp[t], qp[t], 0x01000100u);                            // {s, s}
-      off = pk_add_f16(__builtin_amdgcn_perm(qp[t], qp[t], 0x03020302u), 0x54006400u);  // {1024+z, 64+z}
+      off = pk_add_f16(__builtin_amdgcn_perm(qp[t], qp[t], 0x03020302u), g.nib_magic);  // {1024+z, 64+z}
     }
 #pragma unroll
     for (int d = 0; d < 4; ++d) {
       u4 a;
-      if (KIND == EGT_VAL_INT4) a = dequant8(nib[t][0][d], off, s2, magic);
+      if (KIND == EGT_VAL_INT4) a = dequant8(nib[t][0][d], off, s2, g.nib_mask, magic);
       else a = nib[t][d];
       const int iword = d < 2 ? (int)iw[t][0] : (int)iw[t][1];
       if (d & 1)
@@ -307,6 +265,8 @@ hipError_t launch_sparse_m1(const egt_2bitcsr &w, const uint16_t *x, uint16_t *y
     g.groups_per_row = w.cols / w.group_size;
   }
   g.last_chunk = (uint32_t)w.rows * (uint32_t)g.nchunks - 1u;
+  g.nib_mask = 0x00F0000Fu;
+  g.nib_magic = 0x54006400u;
   // tuning knobs: tiles per wave, waves per phase per block
   int tpi = 4, wpp = g.phases == 1 ? 4 : 2;
   if (const char *e = getenv("EGT_M1_TUNE")) sscanf(e, "%d,%d", &tpi, &wpp);

@@ -97,7 +97,9 @@ def test_broken_row_ptr_yields_nan_not_a_fault():
 
 # ---------------------------------------------------------------- dense INT4
 @pytest.mark.parametrize("rows,cols,g", [(37, 64, 8), (130, 1024, 128), (21, 11008, 128), (50, 4096, 64),
-                                         (9, 4096, 4096), (66, 2048, 32), (33, 320, 64)])
+                                         (9, 4096, 4096), (66, 2048, 32), (33, 320, 64), (45, 4096, 128),
+                                         (7, 512, 128), (70, 2048, 128), (33, 8192, 128), (19, 2176, 128),
+                                         (1, 4096, 128), (131, 1024, 128)])
 def test_int4_gemv_small(rows, cols, g):
     print(f"case int4_gemv {rows}x{cols} g={g}", flush=True)
     w = synth.weights(rows, cols, 500 + rows)
@@ -107,6 +109,17 @@ def test_int4_gemv_small(rows, cols, g):
     assert np.array_equal(q, oq) and np.array_equal(qp, oqp)
     y_ref, a_ref = O.int4_gemv(oq, oqp, g, x)
     G.assert_close(G.run_int4_gemv(q, qp, g, x), y_ref, a_ref, "int4_gemv")
+
+
+def test_int4_one_hot_x_returns_decoded_column_bit_exact():
+    w = synth.weights(64, 4096, 77)
+    q, qp = B.quant_int4(w, 128)
+    Wd = O.dequant_int4_dense(q, qp, 128)
+    for j in (0, 1, 130, 4095):
+        e = np.zeros(4096, dtype=np.float16)
+        e[j] = 1
+        y = G.run_int4_gemv(q, qp, 128, e)
+        assert np.array_equal(y.view(np.uint16), Wd[:, j].astype(np.float16).view(np.uint16)), f"column {j}"
 
 
 def test_config2_dense_int4_full():
