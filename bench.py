@@ -192,6 +192,23 @@ def main():
                 extra[f"config5_{r5}x{k5}_M{M}"] = {"us": round(t5 * 1e6, 3), "gbps": round(b5 / t5 / 1e9, 1),
                                                    "bytes": b5, "tflops": round(2 * M * r5 * k5 / 2 / t5 / 1e12, 2)}
             del pk5
+        # config 4: the 32-layer stack, 224 launches, plain and as a HIP graph
+        from paper_2605_11582_amd import stack as S
+        del packed, calls
+        torch.cuda.empty_cache()
+        stk = S.LayerStack.build(dev, distinct_layers=1)
+        t4, _ = time_loop(torch, lambda i: stk.run(), 20, 3)
+        side = torch.cuda.Stream()
+        with torch.cuda.stream(side):
+            stk.run(side.cuda_stream)
+            torch.cuda.synchronize()
+            graph = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(graph, stream=side):
+                stk.run(torch.cuda.current_stream().cuda_stream)
+            t4g, _ = time_loop(torch, lambda i: graph.replay(), 20, 3)
+        extra["config4_stack_224_launches"] = {"us_plain": round(t4 * 1e6, 1), "us_graph": round(t4g * 1e6, 1),
+                                               "bytes": stk.nbytes, "gbps_plain": round(stk.nbytes / t4 / 1e9, 1),
+                                               "gbps_graph": round(stk.nbytes / t4g / 1e9, 1)}
         result["extra"] = extra
 
     if not args.no_cpu_baseline:

@@ -236,12 +236,14 @@ def sparse_gemm_smallm(p: Packed, X, Y, stream=None) -> None:
 
 # Pre-marshalled calls: the arguments are converted once, the returned function only
 # crosses the C ABI (for launch-rate-sensitive loops; same entry points, same checks).
+# The stream defaults to the one current at preparation; pass `stream_ptr` (an int)
+# to launch elsewhere, e.g. on a capturing stream.
 def prepared_sparse_gemv(p: Packed, x, y, stream=None):
     fn, v = lib().egt_sparse_gemv, p.view()
     ref, xp, yp, sp = C.byref(v), _dev(x), _dev(y), _stream_ptr(stream)
 
-    def call(_keep=(v, p, x, y)):
-        st = fn(ref, xp, yp, sp)
+    def call(stream_ptr=sp, _keep=(v, p, x, y)):
+        st = fn(ref, xp, yp, stream_ptr)
         if st:
             _check(st)
     return call
@@ -249,10 +251,11 @@ def prepared_sparse_gemv(p: Packed, x, y, stream=None):
 
 def prepared_sparse_gemm_smallm(p: Packed, X, Y, stream=None):
     fn, v = lib().egt_sparse_gemm_smallm, p.view()
-    args = (C.byref(v), X.data_ptr(), X.stride(0), Y.data_ptr(), Y.stride(0), X.shape[0], _stream_ptr(stream))
+    args = (C.byref(v), X.data_ptr(), X.stride(0), Y.data_ptr(), Y.stride(0), X.shape[0])
+    sp = _stream_ptr(stream)
 
-    def call(_keep=(v, p, X, Y)):
-        st = fn(*args)
+    def call(stream_ptr=sp, _keep=(v, p, X, Y)):
+        st = fn(*args, stream_ptr)
         if st:
             _check(st)
     return call
@@ -260,10 +263,11 @@ def prepared_sparse_gemm_smallm(p: Packed, X, Y, stream=None):
 
 def prepared_int4_gemv(q, qparams, rows: int, cols: int, group: int, x, y, stream=None):
     fn = lib().egt_int4_gemv
-    args = (_dev(q), _dev(qparams), rows, cols, group, _dev(x), _dev(y), _stream_ptr(stream))
+    args = (_dev(q), _dev(qparams), rows, cols, group, _dev(x), _dev(y))
+    sp = _stream_ptr(stream)
 
-    def call(_keep=(q, qparams, x, y)):
-        st = fn(*args)
+    def call(stream_ptr=sp, _keep=(q, qparams, x, y)):
+        st = fn(*args, stream_ptr)
         if st:
             _check(st)
     return call

@@ -1,0 +1,70 @@
+"""Config 4: the 32-layer 7B-shaped stack, 224 GEMV launches (16 layers 2:4-sparse INT4 in
+2bit-CSR, 16 dense INT4), plain and replayed from a HIP graph."""
+import numpy as np
+import pytest
+
+from oracle import egt_oracle as O
+from paper_2605_11582_amd import binding as B, stack as S, synth
+import gpu_common as G
+
+pytestmark = pytest.mark.gpu
+
+
+def test_layer_plan():
+    ids = synth.sparse_layers()
+    assert len(ids) == 16 and len(set(ids.tolist())) == 16 and ids.min() >= 0 and ids.max() < 32
+    total = sum(S.algorithmic_bytes(r, c, True) for _, r, c in synth.LAYER_MATRICES) * 16 + \
+        sum(S.algorithmic_bytes(r, c, False) for _, r, c in synth.LAYER_MATRICES) * 16
+    assert total == 3043344832                    # closed form of the byte model for this stack
+
+
+def test_stack_parity_and_graph_replay():
+    torch = G.torch_mod()
+    print("building the stack (2 layers with their own weights, 30 reuse their bytes)", flush=True)
+    st = S.LayerStack.build("cuda:0", distinct_layers=1, progress=lambda l: print(f"  layer {l} uploaded", flush=True) if l % 8 == 7 else None)
+    assert len(st.matrices) == 224 and st.nbytes == 3043344832
+    st.run()
+    torch.cuda.synchronize()
+    eager = [m.y.cpu().numpy().copy() for m in st.matrices]
+    sparse_ids = set(int(v) for v in synth.sparse_layers())
+    first = {True: min(sparse_ids), False: min(set(range(32)) - sparse_ids)}
+    nm = len(synth.LAYER_MATRICES)
+    # the two layers with their own weights: the oracle packs sampled rows itself and multiplies
+    for sparse, layer in first.items():
+        for mi, (name, rows, cols) in enumerate(synth.LAYER_MATRICES):
+            print(f"  oracle check layer {layer} ({'sparse' if sparse else 'dense'}) {name}", flush=True)
+            w, x, packed = S.pack_layer_matrix(layer, mi, sparse)
+            pick = G.sample_rows(rows, 48, layer * nm + mi)
+            y = eager[layer * nm + mi]
+            if sparse:
+                o = O.pack_2bitcsr(w[pick], O.prune_n4_magnitude(w[pick], 2), 2, 128, O.VAL_INT4)
+                sub = G.row_subset(packed, pick)
+                for k in ("values", "idx", "qparams"):
+                    assert np.array_equal(o[k], sub[k]), k
+                y_ref, a_ref = O.gemv(o, x)
+            else:
+                oq, oqp = O.quant_int4_dense(w[pick], 128)
+                assert np.array_equal(oq, packed[0][pick]) and np.array_equal(oqp, packed[1][pick])
+                y_ref, a_ref = O.int4_gemv(oq, oqp, 128, x)
+            G.assert_close(y[pick], y_ref, a_ref, f"layer {layer} {name}")
+    # layers that reuse those bytes must reproduce the same outputs bit for bit
+    for m_i, m in enumerate(st.matrices):
+        src = first[m.sparse] * nm + m_i % nm
+        assert np.array_equal(eager[m_i].view(np.uint16), eager[src].view(np.uint16)), (m.layer, m.name)
+    # HIP graph of the 224 launches: several replays, with eager work between them
+    side = torch.cuda.Stream()
+    with torch.cuda.stream(side):
+        st.run(side.cuda_stream)
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=side):
+            st.run(torch.cuda.current_stream().cuda_stream)
+    for rep in range(3):
+        for m in st.matrices:
+            m.y.fill_(7.0)                          # eager work between replays
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for m_i, m in enumerate(st.matrices):
+            assert np.array_equal(m.y.cpu().numpy().view(np.uint16), eager[m_i].view(np.uint16)), (rep, m.layer, m.name)
+        print(f"  graph replay {rep} matches the eager run", flush=True)
