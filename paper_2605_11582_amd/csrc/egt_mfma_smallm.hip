@@ -21,6 +21,14 @@
 
 namespace egt {
 
+// Here a wave-wide load touches 16 rows x 64 B, i.e. half cache lines whose other half
+// is read by a neighbouring wave a moment later: ordinary (cached) loads, not
+// streaming ones, or the line is dropped and fetched twice.
+template <typename T>
+__device__ __forceinline__ T ld_plain(const void *p) {
+  return *(const T *)p;
+}
+
 __device__ __forceinline__ u4 dequant8_sm(uint32_t d, uint32_t off, uint32_t s2, uint32_t mask, uint32_t magic) {
   u4 r;
 #pragma unroll
@@ -100,15 +108,15 @@ __global__ __launch_bounds__(256) void k_sparse_smallm(const uint32_t *__restric
   auto load_a = [&](int slot, int step) {
     const int s = min(step, g.nsteps - 1);
     const uint32_t chunk = row_chunk0 + (uint32_t)(4 * s + kb);
-    iw[slot] = ld_stream<u2>(idx + 8ull * chunk);
+    iw[slot] = ld_plain<u2>(idx + 8ull * chunk);
     qp[slot] = 0;
     if (KIND == EGT_VAL_INT4) {
-      nib[slot][0] = ld_stream<u4>(values + 16ull * chunk);
-      qp[slot] = ld_stream<uint32_t>(qparams + 4ull * ((uint32_t)r_ld * (uint32_t)g.groups_per_row +
+      nib[slot][0] = ld_plain<u4>(values + 16ull * chunk);
+      qp[slot] = ld_plain<uint32_t>(qparams + 4ull * ((uint32_t)r_ld * (uint32_t)g.groups_per_row +
                                                         (uint32_t)((4 * s + kb) >> g.gshift)));
     } else {
 #pragma unroll
-      for (int k = 0; k < VW; ++k) nib[slot][k] = ld_stream<u4>(values + 64ull * chunk + 16 * k);
+      for (int k = 0; k < VW; ++k) nib[slot][k] = ld_plain<u4>(values + 64ull * chunk + 16 * k);
     }
   };
 
@@ -180,6 +188,180 @@ __global__ __launch_bounds__(256) void k_sparse_smallm(const uint32_t *__restric
   }
 }
 
+// ---------------------------------------------------------------------------------
+// K-split form.  The waves of a workgroup split K between them: in phase p, wave w
+// owns K-step p * waves + w (256 dense columns).  It fetches its slice of X
+// (16 tokens x 256 columns) with fully coalesced loads, turns it into the B operand
+// layout through a private LDS region (token rows padded against bank conflicts, no
+// workgroup barrier involved) and keeps B in registers while the workgroup walks over
+// its (at most four) row tiles, whose A operands are all requested up front.  Each
+// wave leaves its partial 16 x 16 products in its own region; after one barrier 256
+// threads add them over the waves into running sums, and Y is stored after the last
+// phase.  K <= 4096 is one phase.  Groups of 16 tokens are handled one after the other.
+struct SmallMKsGeom {
+  int rows, M;
+  int nchunks;         // cols / 64
+  int nsteps;          // cols / 256
+  int ntiles;          // ceil(rows / 16)
+  int gshift;
+  int groups_per_row;
+  int64_t ldx, ldy;
+  uint32_t nib_mask, nib_magic;
+};
+
+template <int KIND>
+struct ATile {                        // A operand of one row tile, one K-step
+  u4 nib[KIND == EGT_VAL_INT4 ? 1 : 4];
+  u2 iw;
+  uint32_t qp;
+};
+
+constexpr int KS_MAX_ITEMS = 4;                    // row tiles per workgroup
+constexpr int KS_REGION = 16 * TOKEN_STRIDE;       // LDS bytes per wave
+
+template <int KIND>
+__global__ __launch_bounds__(1024) void k_sparse_smallm_ks(const uint32_t *__restrict__ row_ptr,
+                                                            const uint8_t *__restrict__ values,
+                                                            const uint8_t *__restrict__ idx,
+                                                            const uint8_t *__restrict__ qparams,
+                                                            const __half *__restrict__ X,
+                                                            __half *__restrict__ Y,
+                                                            const SmallMKsGeom g) {
+  extern __shared__ __align__(16) uint8_t xs[];       // [waves][KS_REGION]
+  constexpr int VW = KIND == EGT_VAL_INT4 ? 1 : 4;
+  constexpr int INFL = KIND == EGT_VAL_INT4 ? 3 : 2;  // row tiles whose A operand is in flight together
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int nw = blockDim.x >> 6;
+  const int i = lane & 15, kb = lane >> 4;
+  const int nit = (g.ntiles - (int)blockIdx.x + (int)gridDim.x - 1) / (int)gridDim.x;   // <= KS_MAX_ITEMS
+  const int phases = (g.nsteps + nw - 1) / nw;
+  const uint32_t magic = in_vgpr(g.nib_magic);
+  const uint32_t S_row = (uint32_t)g.nchunks * 32u;
+  uint8_t *region = xs + wave * KS_REGION;
+  // role of this thread in the cross-wave sum: row tile rit, register sv of lane sl
+  const int rit = threadIdx.x >> 8, sv = (threadIdx.x >> 6) & 3, sl = threadIdx.x & 63;
+  const int srow = 16 * ((int)blockIdx.x + rit * (int)gridDim.x) + 4 * (sl >> 4) + sv;
+  const bool summing = rit < nit && srow < g.rows;
+
+  auto load_a = [&](ATile<KIND> &a, int it, int step) {
+    const int rt = min((int)blockIdx.x + it * (int)gridDim.x, g.ntiles - 1);
+    const int r = min(16 * rt + i, g.rows - 1);
+    const int s = min(step, g.nsteps - 1);
+    const uint32_t chunk = (uint32_t)r * (uint32_t)g.nchunks + (uint32_t)(4 * s + kb);
+    a.iw = ld_plain<u2>(idx + 8ull * chunk);
+    a.qp = 0;
+    if (KIND == EGT_VAL_INT4) {
+      a.nib[0] = ld_plain<u4>(values + 16ull * chunk);
+      a.qp = ld_plain<uint32_t>(qparams + 4ull * ((uint32_t)r * (uint32_t)g.groups_per_row +
+                                                   (uint32_t)((4 * s + kb) >> g.gshift)));
+    } else {
+#pragma unroll
+      for (int k = 0; k < VW; ++k) a.nib[k] = ld_plain<u4>(values + 64ull * chunk + 16 * k);
+    }
+  };
+
+  const int ngroups = (g.M + 15) >> 4;
+  bool first = true;
+  for (int j = 0; j < ngroups; ++j) {
+    float run = 0.f;
+    const uint32_t rp = summing ? row_ptr[srow] : 0u;
+    for (int p = 0; p < phases; ++p) {
+      const int step = p * nw + wave;
+      // ---- this wave's slice of X: 8 coalesced loads of two token rows each
+      u4 xr[8];
+      const bool step_ok = step < g.nsteps;
+#pragma unroll
+      for (int u = 0; u < 8; ++u) {
+        const int tok = 16 * j + 2 * u + (lane >> 5);
+        xr[u] = *(const u4 *)(X + (int64_t)min(tok, g.M - 1) * g.ldx + 256 * min(step, g.nsteps - 1) + 8 * (lane & 31));
+      }
+      ATile<KIND> a[INFL];
+#pragma unroll
+      for (int it = 0; it < INFL; ++it)
+        if (it < nit) load_a(a[it], it, step);
+      // the regions are read by the summing threads of the previous round: wait for them
+      if (!first) __syncthreads();
+      first = false;
+#pragma unroll
+      for (int u = 0; u < 8; ++u) {
+        const int tl = 2 * u + (lane >> 5);
+        u4 v = xr[u];
+        if (16 * j + tl >= g.M || !step_ok) v = u4{0, 0, 0, 0};
+        *(u4 *)(region + tl * TOKEN_STRIDE + 16 * (lane & 31)) = v;
+      }
+      // B operand: lane (n, b) reads token n, k-octets b and 4 + b of each 16-column group d
+      u8v bx[4];
+      {
+        const int n = lane & 15, b = lane >> 4;
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+          const int kba = (4 * h + b) >> 1, sub = b & 1;
+#pragma unroll
+          for (int d = 0; d < 4; ++d) {
+            const u4 v = *(const u4 *)(region + n * TOKEN_STRIDE + 16 * (8 * kba + 2 * d + sub));
+#pragma unroll
+            for (int k = 0; k < 4; ++k) bx[d][4 * h + k] = v[k];
+          }
+        }
+      }
+
+      auto compute = [&](const ATile<KIND> &at, int it) {
+        f4 acc = {0.f, 0.f, 0.f, 0.f};
+        uint32_t s2 = 0, off = 0;
+        if (KIND == EGT_VAL_INT4) {
+          s2 = __builtin_amdgcn_perm(at.qp, at.qp, 0x01000100u);
+          off = pk_add_f16(__builtin_amdgcn_perm(at.qp, at.qp, 0x03020302u), g.nib_magic);
+        }
+#pragma unroll
+        for (int d = 0; d < 4; ++d) {
+          u4 av;
+          if (KIND == EGT_VAL_INT4) av = dequant8_sm(at.nib[0][d], off, s2, g.nib_mask, magic);
+          else av = at.nib[d];
+          const int iword = d < 2 ? (int)at.iw[0] : (int)at.iw[1];
+          if (d & 1)
+            acc = __builtin_amdgcn_smfmac_f32_16x16x64_f16(__builtin_bit_cast(h8, av), __builtin_bit_cast(h16, bx[d]), acc, iword, 0, 1);
+          else
+            acc = __builtin_amdgcn_smfmac_f32_16x16x64_f16(__builtin_bit_cast(h8, av), __builtin_bit_cast(h16, bx[d]), acc, iword, 0, 0);
+        }
+        float *out = (float *)(region + it * 1024);   // B has been read: the region is free
+#pragma unroll
+        for (int v = 0; v < 4; ++v) out[v * 64 + lane] = acc[v];
+      };
+#pragma unroll
+      for (int it0 = 0; it0 < KS_MAX_ITEMS; it0 += INFL) {
+        if (it0 < nit) {
+          if (it0 > 0) {
+#pragma unroll
+            for (int it = 0; it < INFL; ++it)
+              if (it0 + it < nit) load_a(a[it], it0 + it, step);
+          }
+#pragma unroll
+          for (int it = 0; it < INFL; ++it)
+            if (it0 + it < nit) compute(a[it], it0 + it);
+        }
+      }
+      __syncthreads();
+      if (summing) {                                  // all reads issued together, then added in wave order
+        const float *src = (const float *)(xs + rit * 1024) + (threadIdx.x & 255);
+        float part[16];
+#pragma unroll
+        for (int w = 0; w < 16; ++w) part[w] = w < nw ? src[w * (KS_REGION / 4)] : 0.f;
+        float sum = 0.f;
+#pragma unroll
+        for (int w = 0; w < 16; ++w) sum += part[w];
+        run += sum;
+      }
+    }
+    // ---- store: thread (rit, sv, sl) owns D[row 4 (sl >> 4) + sv][token sl & 15] of row tile rit
+    const int tok = 16 * j + (sl & 15);
+    if (summing && tok < g.M) {
+      const bool ok = rp == (uint32_t)srow * S_row;
+      Y[(int64_t)tok * g.ldy + srow] = ok ? __float2half(run) : __ushort_as_half((uint16_t)0x7E00);
+    }
+  }
+}
+
 // Shapes covered: 2:4, K a multiple of 256, INT4 groups of 64 << j.
 bool sparse_smallm_supported(const egt_2bitcsr &w) {
   if (w.n_keep != 2 || w.cols % 256 != 0 || w.cols < 256) return false;
@@ -190,7 +372,46 @@ bool sparse_smallm_supported(const egt_2bitcsr &w) {
   return true;
 }
 
+static hipError_t launch_sparse_smallm_steps(const egt_2bitcsr &w, const uint16_t *X, int64_t ldx,
+                                             uint16_t *Y, int64_t ldy, int M, hipStream_t stream);
+
 hipError_t launch_sparse_smallm(const egt_2bitcsr &w, const uint16_t *X, int64_t ldx, uint16_t *Y,
+                                int64_t ldy, int M, hipStream_t stream) {
+  if (w.rows == 0) return hipSuccess;
+  const int nsteps = w.cols / 256;
+  int nw = nsteps < 16 ? nsteps : 16;                 // waves per workgroup
+  int blocks_per_cu = 1;
+  if (const char *e = getenv("EGT_SM_TUNE")) sscanf(e, "%d,%d", &nw, &blocks_per_cu);
+  if (nw < 1 || nw > 16) return launch_sparse_smallm_steps(w, X, ldx, Y, ldy, M, stream);
+  SmallMKsGeom g;
+  g.rows = w.rows; g.M = M;
+  g.nchunks = w.cols / 64;
+  g.nsteps = nsteps;
+  g.ntiles = (w.rows + 15) / 16;
+  g.gshift = 0; g.groups_per_row = 0;
+  if (w.val_kind == EGT_VAL_INT4) {
+    while ((64 << g.gshift) < w.group_size) ++g.gshift;
+    g.groups_per_row = w.cols / w.group_size;
+  }
+  g.ldx = ldx; g.ldy = ldy;
+  g.nib_mask = 0x00F0000Fu; g.nib_magic = 0x54006400u;
+  int nblocks = 256 * blocks_per_cu;                  // one (or more) workgroup per compute unit
+  if (nblocks * KS_MAX_ITEMS < g.ntiles) nblocks = (g.ntiles + KS_MAX_ITEMS - 1) / KS_MAX_ITEMS;
+  if (nblocks > g.ntiles) nblocks = g.ntiles;
+  const dim3 grid(nblocks), block(64 * nw);
+  const size_t lds = (size_t)nw * KS_REGION;
+  if (w.val_kind == EGT_VAL_INT4)
+    return launch(k_sparse_smallm_ks<EGT_VAL_INT4>, grid, block, lds, stream, w.row_ptr,
+                  (const uint8_t *)w.values, (const uint8_t *)w.idx, (const uint8_t *)w.qparams,
+                  (const __half *)X, (__half *)Y, g);
+  return launch(k_sparse_smallm_ks<EGT_VAL_FP16>, grid, block, lds, stream, w.row_ptr,
+                (const uint8_t *)w.values, (const uint8_t *)w.idx, (const uint8_t *)w.qparams,
+                (const __half *)X, (__half *)Y, g);
+}
+
+// K-step form (any K that is a multiple of 256): used when K is too wide for one
+// workgroup to cover it with 16 waves.
+static hipError_t launch_sparse_smallm_steps(const egt_2bitcsr &w, const uint16_t *X, int64_t ldx, uint16_t *Y,
                                 int64_t ldy, int M, hipStream_t stream) {
   if (w.rows == 0) return hipSuccess;
   SmallMGeom g;
@@ -206,9 +427,7 @@ hipError_t launch_sparse_smallm(const egt_2bitcsr &w, const uint16_t *X, int64_t
   g.nib_mask = 0x00F0000Fu; g.nib_magic = 0x54006400u;
   const int nt = M <= 16 ? 1 : (M <= 32 ? 2 : 4);
   const int row_tiles = (w.rows + 15) / 16;
-  int nw = row_tiles >= 512 ? 2 : 1;                  // waves (row tiles) per workgroup
-  if (const char *e = getenv("EGT_SM_TUNE")) sscanf(e, "%d", &nw);
-  if (nw != 1 && nw != 2 && nw != 4) nw = 2;
+  const int nw = row_tiles >= 512 ? 2 : 1;            // waves (row tiles) per workgroup
   // 16 B pieces per thread per step = 16 nt tokens * 32 pieces / (64 nw threads)
   const int xpt = 8 * nt / nw;
   const dim3 grid((row_tiles + nw - 1) / nw), block(64 * nw);
