@@ -190,3 +190,18 @@ def test_config5_smallm_full_size(rows, cols, M):
     # M-row product equals M independent GEMVs on the same device path (within tolerance)
     y0 = G.run_sparse_gemv(p, np.ascontiguousarray(X[0]))
     G.assert_close(y0[pick], Y_ref[0], A_ref[0], "row 0 as a GEMV")
+
+
+# ---------------------------------------------------------------- measurement aid
+def test_stream_read_folds_every_word_once():
+    torch = G.torch_mod()
+    rng = np.random.default_rng(3)
+    for nbytes in (16, 4096 + 16, 1 << 20, (1 << 20) + 48):
+        data = rng.integers(0, 256, size=nbytes, dtype=np.uint8)
+        src = torch.from_numpy(data).cuda()
+        sink = torch.zeros(4096, dtype=torch.int32, device="cuda")
+        B.stream_read(src, nbytes, sink)
+        torch.cuda.synchronize()
+        got = np.bitwise_xor.reduce(sink.cpu().numpy().view(np.uint32))
+        want = np.bitwise_xor.reduce(data.view(np.uint32))
+        assert got == want, nbytes
