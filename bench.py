@@ -192,6 +192,15 @@ def main():
                 extra[f"config5_{r5}x{k5}_M{M}"] = {"us": round(t5 * 1e6, 3), "gbps": round(b5 / t5 / 1e9, 1),
                                                    "bytes": b5, "tflops": round(2 * M * r5 * k5 / 2 / t5 / 1e12, 2)}
             del pk5
+        # 1:4 sparsity (the sparser layer-adaptive setting), same shape as the headline
+        p14 = B.pack_2bitcsr(w, B.prune_n4(w, 1), 1, GRP, B.VAL_INT4)
+        c14 = max(2, -(-2 * LLC_BYTES // p14.nbytes()))
+        pk14 = [p14.to(dev) for _ in range(c14)]
+        f14 = [B.prepared_sparse_gemv(pk14[i], xd, ys[0]) for i in range(c14)]
+        t14, _ = time_loop(torch, lambda i: f14[i % c14](), 2000, 200)
+        b14 = algorithmic_bytes(R, K, 1, GRP, 0)
+        extra["sparse_int4_1to4_11008x4096"] = {"us": round(t14 * 1e6, 3), "gbps": round(b14 / t14 / 1e9, 1), "bytes": b14}
+        del pk14, f14
         # config 4: the 32-layer stack, 224 launches, plain and as a HIP graph
         from paper_2605_11582_amd import stack as S
         del packed, calls
@@ -209,6 +218,13 @@ def main():
         extra["config4_stack_224_launches"] = {"us_plain": round(t4 * 1e6, 1), "us_graph": round(t4g * 1e6, 1),
                                                "bytes": stk.nbytes, "gbps_plain": round(stk.nbytes / t4 / 1e9, 1),
                                                "gbps_graph": round(stk.nbytes / t4g / 1e9, 1)}
+        del stk, graph
+        torch.cuda.empty_cache()
+        # the three-way layer-adaptive mix (2:4, 1:4 and dense layers)
+        stk3 = S.LayerStack.build(dev, distinct_layers=1, plan="mix3")
+        t43, _ = time_loop(torch, lambda i: stk3.run(), 20, 3)
+        extra["stack_mix3_224_launches"] = {"us_plain": round(t43 * 1e6, 1), "bytes": stk3.nbytes,
+                                            "gbps_plain": round(stk3.nbytes / t43 / 1e9, 1)}
         result["extra"] = extra
 
     if not args.no_cpu_baseline:

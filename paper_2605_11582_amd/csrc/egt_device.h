@@ -35,6 +35,10 @@ hipError_t launch_int4_generic(const uint8_t *q, const uint16_t *qparams, int ro
 bool sparse_m1_supported(const egt_2bitcsr &w);
 hipError_t launch_sparse_m1(const egt_2bitcsr &w, const uint16_t *x, uint16_t *y, hipStream_t stream);
 
+// M = 1, 1:4 sparsity (see sparse_m1_n1_supported)
+bool sparse_m1_n1_supported(const egt_2bitcsr &w);
+hipError_t launch_sparse_m1_n1(const egt_2bitcsr &w, const uint16_t *x, uint16_t *y, hipStream_t stream);
+
 // 2 <= M <= 64 on the sparse matrix cores (2:4 only; see sparse_smallm_supported)
 bool sparse_smallm_supported(const egt_2bitcsr &w);
 hipError_t launch_sparse_smallm(const egt_2bitcsr &w, const uint16_t *X, int64_t ldx, uint16_t *Y,

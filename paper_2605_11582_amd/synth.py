@@ -49,3 +49,21 @@ def sparse_layers(seed: int = SEED_BASE + 400000) -> np.ndarray:
     stored 2:4-sparse INT4; the other 16 are dense INT4."""
     rng = np.random.Generator(np.random.PCG64(seed))
     return np.sort(rng.permutation(N_LAYERS)[: N_LAYERS // 2])
+
+
+def layer_kinds(plan: str = "config4") -> list:
+    """Per-layer storage of the 32-layer stack: "s24" (2:4 sparse INT4), "s14" (1:4 sparse
+    INT4) or "d" (dense INT4).  "config4": the seeded half/half mix of 2:4 and dense;
+    "mix3": a seeded three-way mix (11 x 2:4, 11 x 1:4, 10 x dense), the layer-adaptive
+    setting with both sparsities in use."""
+    if plan == "config4":
+        sp = set(int(v) for v in sparse_layers())
+        return ["s24" if l in sp else "d" for l in range(N_LAYERS)]
+    if plan == "mix3":
+        rng = np.random.Generator(np.random.PCG64(SEED_BASE + 410000))
+        order = rng.permutation(N_LAYERS)
+        kinds = [""] * N_LAYERS
+        for pos, layer in enumerate(order):
+            kinds[int(layer)] = "s24" if pos < 11 else ("s14" if pos < 22 else "d")
+        return kinds
+    raise ValueError(plan)

@@ -29,6 +29,8 @@ def _small_case(rows, cols, n, g, kind, seed, drop=0.0):
     (257, 1024, 2, 128, 0), (100, 1024, 1, 128, 0), (70, 2048, 2, 64, 0), (70, 2048, 2, 256, 0),
     (45, 4096, 2, 128, 0), (45, 4096, 2, 0, 1), (21, 11008, 2, 128, 0), (21, 11008, 1, 128, 0),
     (21, 11008, 2, 0, 1), (50, 320, 2, 64, 0),
+    (45, 4096, 1, 128, 0), (33, 8192, 1, 256, 0), (19, 2048, 1, 128, 0), (30, 4096, 1, 0, 1),
+    (21, 11008, 1, 0, 1), (130, 4096, 1, 256, 0), (9, 12288, 1, 128, 0), (41, 4160, 2, 64, 0),
 ])
 def test_sparse_gemv_small(rows, cols, n, g, kind):
     print(f"case sparse_gemv {rows}x{cols} n={n} g={g} kind={kind}", flush=True)

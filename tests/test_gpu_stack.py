@@ -18,6 +18,12 @@ def test_layer_plan():
     assert total == 3043344832                    # closed form of the byte model for this stack
 
 
+def test_three_way_plan():
+    kinds = synth.layer_kinds("mix3")
+    assert sorted(set(kinds)) == ["d", "s14", "s24"]
+    assert (kinds.count("s24"), kinds.count("s14"), kinds.count("d")) == (11, 11, 10)
+
+
 def test_stack_parity_and_graph_replay():
     torch = G.torch_mod()
     print("building the stack (2 layers with their own weights, 30 reuse their bytes)", flush=True)
@@ -28,6 +34,7 @@ def test_stack_parity_and_graph_replay():
     eager = [m.y.cpu().numpy().copy() for m in st.matrices]
     sparse_ids = set(int(v) for v in synth.sparse_layers())
     first = {True: min(sparse_ids), False: min(set(range(32)) - sparse_ids)}
+    assert [k != "d" for k in synth.layer_kinds("config4")] == [l in sparse_ids for l in range(32)]
     nm = len(synth.LAYER_MATRICES)
     # the two layers with their own weights: the oracle packs sampled rows itself and multiplies
     for sparse, layer in first.items():
