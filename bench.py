@@ -215,6 +215,14 @@ def main():
             with torch.cuda.graph(graph, stream=side):
                 stk.run(torch.cuda.current_stream().cuda_stream)
             t4g, _ = time_loop(torch, lambda i: graph.replay(), 20, 3)
+        fused = stk.fuse()
+
+        def run_fused(i):
+            for c in fused:
+                c()
+        t4f, _ = time_loop(torch, run_fused, 20, 3)
+        extra["config4_stack_fused_128_launches"] = {"us_plain": round(t4f * 1e6, 1),
+                                                     "gbps_plain": round(stk.nbytes / t4f / 1e9, 1)}
         extra["config4_stack_224_launches"] = {"us_plain": round(t4 * 1e6, 1), "us_graph": round(t4g * 1e6, 1),
                                                "bytes": stk.nbytes, "gbps_plain": round(stk.nbytes / t4 / 1e9, 1),
                                                "gbps_graph": round(stk.nbytes / t4g / 1e9, 1)}

@@ -150,6 +150,19 @@ egt_status egt_sparse_gemv(const egt_2bitcsr *w, const uint16_t *x, uint16_t *y,
 egt_status egt_sparse_gemm_smallm(const egt_2bitcsr *w, const uint16_t *X, int64_t ldx,
                                   uint16_t *Y, int64_t ldy, int M, void *stream);
 
+/* DEVICE.  `count` (1..4) independent products y[k] = W[k].x[k] of identically shaped
+ * matrices (same rows, cols, n_keep, group_size, val_kind; else EGT_ERR_SHAPE) in one
+ * launch: the q/k/v or gate/up projections of a decoder layer.  Sec. 3.3 starts from
+ * one kernel per linear layer; fusing the launches removes the fixed cost a short
+ * kernel cannot amortise.  w: array of `count` views; x, y: arrays of `count` device
+ * pointers (host arrays of device pointers).  Results equal those of `count` separate
+ * egt_sparse_gemv / egt_int4_gemv calls bit for bit. */
+egt_status egt_sparse_gemv_batch(const egt_2bitcsr *w, const uint16_t *const *x, uint16_t *const *y,
+                                 int count, void *stream);
+egt_status egt_int4_gemv_batch(const uint8_t *const *q, const uint16_t *const *qparams, int rows,
+                               int cols, int group, const uint16_t *const *x, uint16_t *const *y,
+                               int count, void *stream);
+
 /* DEVICE.  Measurement aid: streams `bytes` (a multiple of 16) from `src` with
  * 128-bit loads and folds them into one 32-bit word per workgroup written to
  * `sink` (at least 4096 words).  Gives the read bandwidth a kernel of that size

@@ -21,7 +21,7 @@ VAL_FP16 = 1
 SYMBOLS = (
     "egt_status_str", "egt_last_hip_error", "egt_2bitcsr_sizes", "egt_prune_n4", "egt_pack_2bitcsr",
     "egt_unpack_2bitcsr", "egt_quant_int4", "egt_int4_gemv", "egt_sparse_gemv",
-    "egt_sparse_gemm_smallm", "egt_stream_read",
+    "egt_sparse_gemm_smallm", "egt_stream_read", "egt_sparse_gemv_batch", "egt_int4_gemv_batch",
 )
 
 
@@ -70,6 +70,10 @@ def lib() -> C.CDLL:
         L.egt_sparse_gemm_smallm.argtypes = [C.POINTER(View), C.c_void_p, C.c_int64, C.c_void_p,
                                              C.c_int64, C.c_int, C.c_void_p]
         L.egt_stream_read.argtypes = [C.c_void_p, C.c_size_t, C.c_void_p, C.c_void_p]
+        L.egt_sparse_gemv_batch.argtypes = [C.POINTER(View), C.POINTER(C.c_void_p), C.POINTER(C.c_void_p),
+                                            C.c_int, C.c_void_p]
+        L.egt_int4_gemv_batch.argtypes = [C.POINTER(C.c_void_p), C.POINTER(C.c_void_p), C.c_int, C.c_int, C.c_int,
+                                          C.POINTER(C.c_void_p), C.POINTER(C.c_void_p), C.c_int, C.c_void_p]
         for name in SYMBOLS:
             if name not in ("egt_status_str", "egt_last_hip_error"):
                 getattr(L, name).restype = C.c_int
@@ -271,6 +275,43 @@ def prepared_int4_gemv(q, qparams, rows: int, cols: int, group: int, x, y, strea
         if st:
             _check(st)
     return call
+
+
+def _ptr_array(tensors):
+    return (C.c_void_p * len(tensors))(*[_dev(t) for t in tensors])
+
+
+def prepared_sparse_gemv_batch(ps, xs, ys, stream=None):
+    """One launch for len(ps) identically shaped matrices: ys[k] = W[k].xs[k]."""
+    fn = lib().egt_sparse_gemv_batch
+    views = (View * len(ps))(*[p.view() for p in ps])
+    xa, ya, n, sp = _ptr_array(xs), _ptr_array(ys), len(ps), _stream_ptr(stream)
+
+    def call(stream_ptr=sp, _keep=(views, ps, xs, ys, xa, ya)):
+        st = fn(views, xa, ya, n, stream_ptr)
+        if st:
+            _check(st)
+    return call
+
+
+def prepared_int4_gemv_batch(qs, qparams, rows: int, cols: int, group: int, xs, ys, stream=None):
+    fn = lib().egt_int4_gemv_batch
+    qa, pa, xa, ya = _ptr_array(qs), _ptr_array(qparams), _ptr_array(xs), _ptr_array(ys)
+    n, sp = len(qs), _stream_ptr(stream)
+
+    def call(stream_ptr=sp, _keep=(qs, qparams, xs, ys, qa, pa, xa, ya)):
+        st = fn(qa, pa, rows, cols, group, xa, ya, n, stream_ptr)
+        if st:
+            _check(st)
+    return call
+
+
+def sparse_gemv_batch(ps, xs, ys, stream=None) -> None:
+    prepared_sparse_gemv_batch(ps, xs, ys, stream)()
+
+
+def int4_gemv_batch(qs, qparams, rows: int, cols: int, group: int, xs, ys, stream=None) -> None:
+    prepared_int4_gemv_batch(qs, qparams, rows, cols, group, xs, ys, stream)()
 
 
 def prepared_stream_read(src, nbytes: int, sink, stream=None):

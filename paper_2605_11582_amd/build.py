@@ -9,6 +9,7 @@ import subprocess
 PKG = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG)
 LIB = os.path.join(PKG, "libegt.so")
+EXTRA_FLAGS = os.environ.get("EGT_EXTRA_HIPCC_FLAGS", "").split()
 
 
 def hipcc_path() -> str:
@@ -23,7 +24,7 @@ def build(verbose: bool = False) -> str:
     srcs = sorted(glob.glob(os.path.join(csrc, "*.cpp")) + glob.glob(os.path.join(csrc, "*.hip")))
     cmd = [hipcc_path(), "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
            "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-           "-Wno-unused-command-line-argument", "-pthread",
+           "-Wno-unused-command-line-argument", "-pthread", *EXTRA_FLAGS,
            "-I" + os.path.join(ROOT, "include"), "-I" + csrc, *srcs, "-o", LIB + ".tmp"]
     if verbose:
         print(" ".join(cmd), flush=True)

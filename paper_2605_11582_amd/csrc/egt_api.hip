@@ -103,6 +103,42 @@ egt_status egt_sparse_gemv(const egt_2bitcsr *w, const uint16_t *x, uint16_t *y,
   return egt_sparse_gemm_smallm(w, x, w->cols, y, w->rows, 1, stream);
 }
 
+egt_status egt_sparse_gemv_batch(const egt_2bitcsr *w, const uint16_t *const *x, uint16_t *const *y,
+                                 int count, void *stream) {
+  if (!w || !x || !y) return EGT_ERR_NULL;
+  if (count < 1 || count > 4) return EGT_ERR_SHAPE;
+  for (int k = 0; k < count; ++k) {
+    const egt_status st = check_view(&w[k]);
+    if (st != EGT_OK) return st;
+    if (w[k].rows != w[0].rows || w[k].cols != w[0].cols || w[k].n_keep != w[0].n_keep ||
+        w[k].group_size != w[0].group_size || w[k].val_kind != w[0].val_kind)
+      return EGT_ERR_SHAPE;
+  }
+  if (w[0].rows == 0) return EGT_OK;
+  for (int k = 0; k < count; ++k) {
+    if (!x[k] || !y[k]) return EGT_ERR_NULL;
+    if (!aligned16(w[k].row_ptr) || !aligned16(w[k].values) || !aligned16(w[k].idx) ||
+        (w[k].qparams && !aligned16(w[k].qparams)) || !aligned16(x[k]))
+      return EGT_ERR_BUFFER;
+  }
+  return done(egt::launch_sparse_batch(w, x, y, count, (hipStream_t)stream));
+}
+
+egt_status egt_int4_gemv_batch(const uint8_t *const *q, const uint16_t *const *qparams, int rows,
+                               int cols, int group, const uint16_t *const *x, uint16_t *const *y,
+                               int count, void *stream) {
+  if (!q || !qparams || !x || !y) return EGT_ERR_NULL;
+  if (count < 1 || count > 4) return EGT_ERR_SHAPE;
+  if (rows < 0 || cols < 0 || group <= 0 || group % 8 != 0 || cols % group != 0)
+    return EGT_ERR_SHAPE;
+  if (rows == 0) return EGT_OK;
+  for (int k = 0; k < count; ++k) {
+    if (!q[k] || !qparams[k] || !x[k] || !y[k]) return EGT_ERR_NULL;
+    if (!aligned16(q[k]) || !aligned16(qparams[k]) || !aligned16(x[k])) return EGT_ERR_BUFFER;
+  }
+  return done(egt::launch_int4_batch(q, qparams, rows, cols, group, x, y, count, (hipStream_t)stream));
+}
+
 egt_status egt_stream_read(const void *src, size_t bytes, uint32_t *sink, void *stream) {
   if (!src || !sink) return EGT_ERR_NULL;
   if (bytes % 16 != 0) return EGT_ERR_SHAPE;

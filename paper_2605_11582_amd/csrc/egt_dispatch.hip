@@ -17,4 +17,26 @@ hipError_t launch_int4(const uint8_t *q, const uint16_t *qparams, int rows, int 
   return launch_int4_generic(q, qparams, rows, cols, group, x, y, stream);
 }
 
+hipError_t launch_sparse_batch(const egt_2bitcsr *ws, const uint16_t *const *xs, uint16_t *const *ys,
+                               int count, hipStream_t stream) {
+  if (sparse_m1_supported(ws[0])) return launch_sparse_m1_batch(ws, xs, ys, count, stream);
+  if (sparse_m1_n1_supported(ws[0])) return launch_sparse_m1_n1_batch(ws, xs, ys, count, stream);
+  for (int k = 0; k < count; ++k) {                   // shapes without a tuned kernel: one launch each
+    const hipError_t e = launch_sparse_generic(ws[k], xs[k], ws[k].cols, ys[k], ws[k].rows, 1, stream);
+    if (e != hipSuccess) return e;
+  }
+  return hipSuccess;
+}
+
+hipError_t launch_int4_batch(const uint8_t *const *qs, const uint16_t *const *qps, int rows, int cols,
+                             int group, const uint16_t *const *xs, uint16_t *const *ys, int count,
+                             hipStream_t stream) {
+  if (int4_m1_supported(cols, group)) return launch_int4_m1_batch(qs, qps, rows, cols, xs, ys, count, stream);
+  for (int k = 0; k < count; ++k) {
+    const hipError_t e = launch_int4_generic(qs[k], qps[k], rows, cols, group, xs[k], ys[k], stream);
+    if (e != hipSuccess) return e;
+  }
+  return hipSuccess;
+}
+
 }  // namespace egt

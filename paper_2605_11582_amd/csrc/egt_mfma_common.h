@@ -58,6 +58,27 @@ __device__ __forceinline__ float quad_xor2(float v) {
 }
 
 
+// Pointer table of a batched launch: up to EGT_MAX_BATCH identically shaped matrices,
+// selected by blockIdx.y (a single product is a batch of one).
+constexpr int EGT_MAX_BATCH = 4;
+struct GemvBatch {
+  const uint32_t *row_ptr[EGT_MAX_BATCH];
+  const uint8_t *values[EGT_MAX_BATCH];
+  const uint8_t *idx[EGT_MAX_BATCH];
+  const uint8_t *qparams[EGT_MAX_BATCH];
+  const __half *x[EGT_MAX_BATCH];
+  __half *y[EGT_MAX_BATCH];
+};
+
+// Member `i` of a pointer table by scalar selects: all four entries arrive with the
+// kernel arguments, so no load depends on the index.
+template <typename T>
+__device__ __forceinline__ T pick4(T const (&a)[EGT_MAX_BATCH], unsigned i) {
+  const T lo = (i & 1) ? a[1] : a[0];
+  const T hi = (i & 1) ? a[3] : a[2];
+  return (i & 2) ? hi : lo;
+}
+
 // Index of the four-lane group, (lane >> 2) & 3, selects among four values.
 __device__ __forceinline__ float select4(int k, float a0, float a1, float a2, float a3) {
   return (k & 2) ? ((k & 1) ? a3 : a2) : ((k & 1) ? a1 : a0);

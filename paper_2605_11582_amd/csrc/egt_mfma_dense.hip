@@ -48,10 +48,8 @@ struct DenseGeom {
 };
 
 template <int TPI, int XP>
-__global__ __launch_bounds__(1024) void k_int4_m1(const uint8_t *__restrict__ q,
-                                                   const uint8_t *__restrict__ qparams,
-                                                   const __half *__restrict__ x,
-                                                   __half *__restrict__ y, const DenseGeom g) {
+__device__ __forceinline__ void k_int4_m1_body(const uint8_t *__restrict__ q, const uint8_t *__restrict__ qparams,
+    const __half *__restrict__ x, __half *__restrict__ y, const DenseGeom &g) {
   extern __shared__ __align__(16) uint8_t xs[];       // staged x, then [phases][rows of this block] floats
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -190,6 +188,20 @@ __global__ __launch_bounds__(1024) void k_int4_m1(const uint8_t *__restrict__ q,
   }
 }
 
+template <int TPI, int XP>
+__global__ __launch_bounds__(1024) void k_int4_m1(const uint8_t *__restrict__ q,
+                                                   const uint8_t *__restrict__ qparams,
+                                                   const __half *__restrict__ x,
+                                                   __half *__restrict__ y, const DenseGeom g) {
+  k_int4_m1_body<TPI, XP>(q, qparams, x, y, g);
+}
+
+template <int TPI, int XP>
+__global__ __launch_bounds__(1024) void k_int4_m1_batch(const GemvBatch b, const DenseGeom g) {
+  k_int4_m1_body<TPI, XP>(pick4(b.values, blockIdx.y), pick4(b.qparams, blockIdx.y),
+                          pick4(b.x, blockIdx.y), pick4(b.y, blockIdx.y), g);
+}
+
 // Shapes covered: group size 128; K = 512 or 1024 (several rows per tile) or a
 // multiple of 128 from 2048 up to 16 tiles per row.
 bool int4_m1_supported(int cols, int group) {
@@ -198,9 +210,15 @@ bool int4_m1_supported(int cols, int group) {
   return cols >= 2048 && cols % 128 == 0 && cols <= 16 * 2048;
 }
 
-hipError_t launch_int4_m1(const uint8_t *q, const uint16_t *qparams, int rows, int cols,
-                          const uint16_t *x, uint16_t *y, hipStream_t stream) {
-  if (rows == 0) return hipSuccess;
+hipError_t launch_int4_m1_batch(const uint8_t *const *qs, const uint16_t *const *qps, int rows, int cols,
+                                const uint16_t *const *xs, uint16_t *const *ys, int count,
+                                hipStream_t stream) {
+  if (rows == 0 || count == 0) return hipSuccess;
+  GemvBatch b = {};
+  for (int k = 0; k < count; ++k) {
+    b.values[k] = qs[k]; b.qparams[k] = (const uint8_t *)qps[k];
+    b.x[k] = (const __half *)xs[k]; b.y[k] = (__half *)ys[k];
+  }
   DenseGeom g;
   g.rows = rows;
   g.nchunks = cols / 32;
@@ -220,15 +238,16 @@ hipError_t launch_int4_m1(const uint8_t *q, const uint16_t *qparams, int rows, i
   if (tpi != 1 && tpi != 2 && tpi != 4 && tpi != 8) tpi = 4;
   const int nwaves = wpp * g.phases;
   const int tiles_per_block = wpp * tpi;
-  const dim3 grid((g.ntiles + tiles_per_block - 1) / tiles_per_block), block(64 * nwaves);
+  const dim3 grid((g.ntiles + tiles_per_block - 1) / tiles_per_block, count), block(64 * nwaves);
   const int lds_pieces = multirow ? g.nchunks * 4 : g.phases * 256;
   g.part_offset = 16 * lds_pieces + 16 * ((lds_pieces + 15) >> 4);
   const size_t lds = g.part_offset + (g.phases > 1 ? sizeof(float) * g.phases * tiles_per_block : 0);
   const int xp = (lds_pieces + 64 * nwaves - 1) / (64 * nwaves);
   if (xp > 4) return hipErrorInvalidConfiguration;
 #define EGT_GO3(TPI, XP)                                                                         \
-  launch(k_int4_m1<TPI, XP>, grid, block, lds, stream, q, (const uint8_t *)qparams,             \
-         (const __half *)x, (__half *)y, g)
+  (count > 1 ? launch(k_int4_m1_batch<TPI, XP>, grid, block, lds, stream, b, g)                    \
+             : launch(k_int4_m1<TPI, XP>, grid, block, lds, stream, b.values[0], b.qparams[0],    \
+                      b.x[0], b.y[0], g))
 #define EGT_GO(TPI) (xp <= 1 ? EGT_GO3(TPI, 1) : xp == 2 ? EGT_GO3(TPI, 2) : EGT_GO3(TPI, 4))
   switch (tpi) {
     case 1: return EGT_GO(1);
@@ -238,6 +257,11 @@ hipError_t launch_int4_m1(const uint8_t *q, const uint16_t *qparams, int rows, i
   }
 #undef EGT_GO
 #undef EGT_GO3
+}
+
+hipError_t launch_int4_m1(const uint8_t *q, const uint16_t *qparams, int rows, int cols,
+                          const uint16_t *x, uint16_t *y, hipStream_t stream) {
+  return launch_int4_m1_batch(&q, &qparams, rows, cols, &x, &y, 1, stream);
 }
 
 }  // namespace egt

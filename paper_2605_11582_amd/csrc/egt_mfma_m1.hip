@@ -65,12 +65,9 @@ struct M1Geom {
 // One wave = TPI tiles, all loaded before the first is consumed.
 // XP = 16 B pieces of x each thread stages (ceil(pieces / block size)).
 template <int KIND, int TPI, int XP>
-__global__ __launch_bounds__(1024) void k_sparse_m1(const uint32_t *__restrict__ row_ptr,
-                                                     const uint8_t *__restrict__ values,
-                                                     const uint8_t *__restrict__ idx,
-                                                     const uint8_t *__restrict__ qparams,
-                                                     const __half *__restrict__ x,
-                                                     __half *__restrict__ y, const M1Geom g) {
+__device__ __forceinline__ void k_sparse_m1_body(const uint32_t *__restrict__ row_ptr, const uint8_t *__restrict__ values,
+    const uint8_t *__restrict__ idx, const uint8_t *__restrict__ qparams, const __half *__restrict__ x,
+    __half *__restrict__ y, const M1Geom &g) {
   extern __shared__ __align__(16) uint8_t xs[];       // staged x, then [phases][rows of this block] floats
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -235,6 +232,25 @@ __global__ __launch_bounds__(1024) void k_sparse_m1(const uint32_t *__restrict__
   }
 }
 
+// One matrix per launch: the pointers are plain kernel arguments.
+template <int KIND, int TPI, int XP>
+__global__ __launch_bounds__(1024) void k_sparse_m1(const uint32_t *__restrict__ row_ptr,
+                                                     const uint8_t *__restrict__ values,
+                                                     const uint8_t *__restrict__ idx,
+                                                     const uint8_t *__restrict__ qparams,
+                                                     const __half *__restrict__ x,
+                                                     __half *__restrict__ y, const M1Geom g) {
+  k_sparse_m1_body<KIND, TPI, XP>(row_ptr, values, idx, qparams, x, y, g);
+}
+
+// Several identically shaped matrices per launch, selected by blockIdx.y.
+template <int KIND, int TPI, int XP>
+__global__ __launch_bounds__(1024) void k_sparse_m1_batch(const GemvBatch b, const M1Geom g) {
+  k_sparse_m1_body<KIND, TPI, XP>(pick4(b.row_ptr, blockIdx.y), pick4(b.values, blockIdx.y),
+                                  pick4(b.idx, blockIdx.y), pick4(b.qparams, blockIdx.y),
+                                  pick4(b.x, blockIdx.y), pick4(b.y, blockIdx.y), g);
+}
+
 // Shapes the diagonal kernel covers: 2:4; K = 1024 or 2048 (several rows per tile)
 // or a multiple of 64 from 4096 up to 16 tiles per row; INT4 groups of 64 << j.
 bool sparse_m1_supported(const egt_2bitcsr &w) {
@@ -248,8 +264,16 @@ bool sparse_m1_supported(const egt_2bitcsr &w) {
   return true;
 }
 
-hipError_t launch_sparse_m1(const egt_2bitcsr &w, const uint16_t *x, uint16_t *y, hipStream_t stream) {
-  if (w.rows == 0) return hipSuccess;
+hipError_t launch_sparse_m1_batch(const egt_2bitcsr *ws, const uint16_t *const *xs, uint16_t *const *ys,
+                                  int count, hipStream_t stream) {
+  const egt_2bitcsr &w = ws[0];
+  if (w.rows == 0 || count == 0) return hipSuccess;
+  GemvBatch b = {};
+  for (int k = 0; k < count; ++k) {
+    b.row_ptr[k] = ws[k].row_ptr; b.values[k] = (const uint8_t *)ws[k].values;
+    b.idx[k] = (const uint8_t *)ws[k].idx; b.qparams[k] = (const uint8_t *)ws[k].qparams;
+    b.x[k] = (const __half *)xs[k]; b.y[k] = (__half *)ys[k];
+  }
   M1Geom g;
   g.rows = w.rows;
   g.nchunks = w.cols / 64;
@@ -276,16 +300,16 @@ hipError_t launch_sparse_m1(const egt_2bitcsr &w, const uint16_t *x, uint16_t *y
   if (w.val_kind == EGT_VAL_FP16 && tpi == 8) tpi = 4;
   const int nwaves = wpp * g.phases;
   const int tiles_per_block = wpp * tpi;
-  const dim3 grid((g.ntiles + tiles_per_block - 1) / tiles_per_block), block(64 * nwaves);
+  const dim3 grid((g.ntiles + tiles_per_block - 1) / tiles_per_block, count), block(64 * nwaves);
   const int lds_pieces = multirow ? g.nchunks * 8 : g.phases * 512;
   g.part_offset = 16 * lds_pieces + 16 * ((lds_pieces + 31) >> 5);
   const size_t lds = g.part_offset + (g.phases > 1 ? sizeof(float) * g.phases * tiles_per_block : 0);
   const int xp = (lds_pieces + 64 * nwaves - 1) / (64 * nwaves);
   if (xp > 4) return hipErrorInvalidConfiguration;
 #define EGT_GO3(KIND, TPI, XP)                                                                  \
-  launch(k_sparse_m1<KIND, TPI, XP>, grid, block, lds, stream, w.row_ptr,                       \
-         (const uint8_t *)w.values, (const uint8_t *)w.idx, (const uint8_t *)w.qparams,         \
-         (const __half *)x, (__half *)y, g)
+  (count > 1 ? launch(k_sparse_m1_batch<KIND, TPI, XP>, grid, block, lds, stream, b, g)             \
+             : launch(k_sparse_m1<KIND, TPI, XP>, grid, block, lds, stream, b.row_ptr[0],          \
+                      b.values[0], b.idx[0], b.qparams[0], b.x[0], b.y[0], g))
 #define EGT_GO(KIND, TPI)                                                                       \
   (xp <= 1 ? EGT_GO3(KIND, TPI, 1) : xp == 2 ? EGT_GO3(KIND, TPI, 2) : EGT_GO3(KIND, TPI, 4))
   if (w.val_kind == EGT_VAL_INT4) {
@@ -303,6 +327,10 @@ hipError_t launch_sparse_m1(const egt_2bitcsr &w, const uint16_t *x, uint16_t *y
   }
 #undef EGT_GO
 #undef EGT_GO3
+}
+
+hipError_t launch_sparse_m1(const egt_2bitcsr &w, const uint16_t *x, uint16_t *y, hipStream_t stream) {
+  return launch_sparse_m1_batch(&w, &x, &y, 1, stream);
 }
 
 }  // namespace egt

@@ -83,6 +83,27 @@ class LayerStack:
             for m in self.matrices:
                 m.call(stream_ptr)
 
+    def fuse(self) -> list:
+        """Pre-marshalled launches with the q/k/v and the gate/up projections of every
+        layer fused into one launch each: 4 launches per layer instead of 7."""
+        calls = []
+        nm = len(synth.LAYER_MATRICES)
+        for l0 in range(0, len(self.matrices), nm):
+            layer = self.matrices[l0:l0 + nm]
+            by_name = {m.name: m for m in layer}
+            for group in (("q", "k", "v"), ("o",), ("gate", "up"), ("down",)):
+                ms = [by_name[n] for n in group]
+                if len(ms) == 1:
+                    calls.append(ms[0].call)
+                elif ms[0].kind != "d":
+                    calls.append(B.prepared_sparse_gemv_batch([m.keep[0] for m in ms], [m.keep[1] for m in ms],
+                                                              [m.y for m in ms]))
+                else:
+                    calls.append(B.prepared_int4_gemv_batch([m.keep[0] for m in ms], [m.keep[1] for m in ms],
+                                                            ms[0].rows, ms[0].cols, GROUP,
+                                                            [m.keep[2] for m in ms], [m.y for m in ms]))
+        return calls
+
     @staticmethod
     def build(device="cuda:0", distinct_layers=None, progress=None, plan="config4") -> "LayerStack":
         """Uploads the whole stack.  `distinct_layers`: how many layers of each kind get

@@ -207,3 +207,46 @@ def test_stream_read_folds_every_word_once():
         got = np.bitwise_xor.reduce(sink.cpu().numpy().view(np.uint32))
         want = np.bitwise_xor.reduce(data.view(np.uint32))
         assert got == want, nbytes
+
+
+# ---------------------------------------------------------------- batched launches
+@pytest.mark.parametrize("rows,cols,n,g,kind,count", [(70, 4096, 2, 128, 0, 3), (33, 11008, 2, 128, 0, 2),
+                                                      (40, 4096, 1, 128, 0, 4), (21, 4096, 2, 0, 1, 2),
+                                                      (19, 96, 3, 32, 0, 3)])
+def test_sparse_gemv_batch_equals_separate_calls(rows, cols, n, g, kind, count):
+    torch = G.torch_mod()
+    ps, xs, refs = [], [], []
+    for k in range(count):
+        p, o = _small_case(rows, cols, n, g, kind, seed=7000 + 13 * k + rows)
+        x = synth.activations(cols, 7000 + k)
+        ps.append(p); xs.append(x); refs.append(O.gemv(o, x))
+    pds = [p.to("cuda") for p in ps]
+    xds = [G.to_dev(x.view(np.uint16)).view(torch.float16) for x in xs]
+    ys = [torch.full((rows,), 9.0, dtype=torch.float16, device="cuda") for _ in range(count)]
+    B.sparse_gemv_batch(pds, xds, ys)
+    torch.cuda.synchronize()
+    for k in range(count):
+        y = ys[k].cpu().numpy()
+        G.assert_close(y, refs[k][0], refs[k][1], f"batch member {k}")
+        assert np.array_equal(y.view(np.uint16), G.run_sparse_gemv(ps[k], xs[k]).view(np.uint16))
+
+
+@pytest.mark.parametrize("rows,cols,g,count", [(50, 4096, 128, 3), (21, 11008, 128, 2), (30, 320, 64, 2)])
+def test_int4_gemv_batch_equals_separate_calls(rows, cols, g, count):
+    torch = G.torch_mod()
+    qs, qps, xs = [], [], []
+    for k in range(count):
+        w = synth.weights(rows, cols, 8000 + k + rows)
+        q, qp = B.quant_int4(w, g)
+        qs.append(q); qps.append(qp); xs.append(synth.activations(cols, 8000 + k))
+    qd = [G.to_dev(q) for q in qs]
+    qpd = [G.to_dev(qp) for qp in qps]
+    xd = [G.to_dev(x.view(np.uint16)).view(torch.float16) for x in xs]
+    ys = [torch.full((rows,), 9.0, dtype=torch.float16, device="cuda") for _ in range(count)]
+    B.int4_gemv_batch(qd, qpd, rows, cols, g, xd, ys)
+    torch.cuda.synchronize()
+    for k in range(count):
+        y_ref, a_ref = O.int4_gemv(*O.quant_int4_dense(synth.weights(rows, cols, 8000 + k + rows), g), g, xs[k])
+        y = ys[k].cpu().numpy()
+        G.assert_close(y, y_ref, a_ref, f"batch member {k}")
+        assert np.array_equal(y.view(np.uint16), G.run_int4_gemv(qs[k], qps[k], g, xs[k]).view(np.uint16))

@@ -58,6 +58,17 @@ def test_stack_parity_and_graph_replay():
     for m_i, m in enumerate(st.matrices):
         src = first[m.sparse] * nm + m_i % nm
         assert np.array_equal(eager[m_i].view(np.uint16), eager[src].view(np.uint16)), (m.layer, m.name)
+    # fused launches (q/k/v and gate/up in one launch each): same bits as the separate launches
+    fused = st.fuse()
+    assert len(fused) == 32 * 4
+    for m in st.matrices:
+        m.y.fill_(3.0)
+    for c in fused:
+        c()
+    torch.cuda.synchronize()
+    for m_i, m in enumerate(st.matrices):
+        assert np.array_equal(m.y.cpu().numpy().view(np.uint16), eager[m_i].view(np.uint16)), ("fused", m.layer, m.name)
+    print("  fused launches match the separate ones", flush=True)
     # HIP graph of the 224 launches: several replays, with eager work between them
     side = torch.cuda.Stream()
     with torch.cuda.stream(side):

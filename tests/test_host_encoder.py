@@ -201,4 +201,10 @@ def test_device_entry_points_reject_bad_arguments_without_a_gpu():
     assert L.egt_int4_gemv(None, 16, 8, 64, 32, 16, 16, None) == 1
     assert L.egt_int4_gemv(16, 16, 8, 64, 12, 16, 16, None) == 2
     assert L.egt_stream_read(16, 24, 16, None) == 2
+    views = (B.View * 2)(v, B.View(8, 64, 2, 16, 0, 16, 16, 16, 16))       # second view differs in group size
+    ptrs = (ctypes.c_void_p * 2)(16, 16)
+    assert L.egt_sparse_gemv_batch(views, ptrs, ptrs, 2, None) == 2
+    assert L.egt_sparse_gemv_batch(views, ptrs, ptrs, 5, None) == 2
+    assert L.egt_sparse_gemv_batch(None, ptrs, ptrs, 1, None) == 1
+    assert L.egt_int4_gemv_batch(ptrs, ptrs, 8, 64, 32, ptrs, ptrs, 0, None) == 2
     assert L.egt_stream_read(None, 32, 16, None) == 1
