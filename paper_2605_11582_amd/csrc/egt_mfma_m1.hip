@@ -95,8 +95,26 @@ __device__ __forceinline__ void k_sparse_m1_body(const uint32_t *__restrict__ ro
     xp[j] = *(const u4 *)(x + 8 * min(pi, npieces - 1));
   }
 
-  // ---- issue every load of the wave's TPI tiles
   const int tile0 = (blockIdx.x * wpp + wslot) * TPI;
+  // The lanes that will store read their row pointers before the tiles are requested (loads
+  // return in order, so the small ones go first and never make the wave wait for a tile):
+  // lane j < 16 finishes tile (j >> 2) of each batch of four tiles.
+  const int sum_steps = multirow ? (g.mr_shift - 4) : 2;       // log2(quad groups per row)
+  constexpr int NB = (TPI + 3) / 4;
+  uint32_t rp[NB];
+  int rrow[NB];
+  bool st[NB];
+#pragma unroll
+  for (int bt = 0; bt < NB; ++bt) {
+    const int t = 4 * bt + ((lane >> 2) & 3);
+    const int tr = tile0 + t;
+    rrow[bt] = tr * rpt + ((lane & 3) >> sum_steps);
+    st[bt] = lane < 16 && t < TPI && tr < g.ntiles && rrow[bt] < g.rows &&
+             ((lane & 3) & ((1 << sum_steps) - 1)) == 0;
+    rp[bt] = st[bt] ? row_ptr[rrow[bt]] : 0u;
+  }
+
+  // ---- issue every load of the wave's TPI tiles
   u4 nib[TPI][KIND == EGT_VAL_INT4 ? 1 : 4];
   u2 iw[TPI];
   uint32_t qp[TPI];
@@ -117,23 +135,6 @@ __device__ __forceinline__ void k_sparse_m1_body(const uint32_t *__restrict__ ro
       for (int k = 0; k < 4; ++k) nib[t][k] = ld_stream<u4>(values + 64ull * chunk + 16 * k);
     }
   }
-  // The lanes that will store read their row pointers now, not at the end:
-  // lane j < 16 finishes tile (j >> 2) of each batch of four tiles.
-  const int sum_steps = multirow ? (g.mr_shift - 4) : 2;       // log2(quad groups per row)
-  constexpr int NB = (TPI + 3) / 4;
-  uint32_t rp[NB];
-  int rrow[NB];
-  bool st[NB];
-#pragma unroll
-  for (int bt = 0; bt < NB; ++bt) {
-    const int t = 4 * bt + ((lane >> 2) & 3);
-    const int tr = tile0 + t;
-    rrow[bt] = tr * rpt + ((lane & 3) >> sum_steps);
-    st[bt] = lane < 16 && t < TPI && tr < g.ntiles && rrow[bt] < g.rows &&
-             ((lane & 3) & ((1 << sum_steps) - 1)) == 0;
-    rp[bt] = st[bt] ? row_ptr[rrow[bt]] : 0u;
-  }
-
   // ---- x through LDS.  Piece p lives at byte 16 p + 16 (p >> 5): one 16 B pad after
   //      every 512 B, so that the 16-lane reads below, whose addresses are 512 B
   //      apart, fall into different banks.  Pieces past the end of x are zero.
