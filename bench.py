@@ -192,6 +192,30 @@ def main():
                 extra[f"config5_{r5}x{k5}_M{M}"] = {"us": round(t5 * 1e6, 3), "gbps": round(b5 / t5 / 1e9, 1),
                                                    "bytes": b5, "tflops": round(2 * M * r5 * k5 / 2 / t5 / 1e12, 2)}
             del pk5
+        # M-sweep through an all-2:4 layer (q/k/v/o, gate/up, down) and the trigger cost model of
+        # Sec. 3.4: verification cost ~ a + b*M, autoregressive step = t(1)
+        sweep_m = (1, 2, 4, 8, 16, 32, 64)
+        layer_us = {m: 0.0 for m in sweep_m}
+        for (r5, k5, reps) in ((4096, 4096, 4), (11008, 4096, 2), (4096, 11008, 1)):
+            w5 = synth.weights(r5, k5, synth.seed_for(5, 7))
+            p5 = B.pack_2bitcsr(w5, B.prune_n4(w5, 2), 2, 128, B.VAL_INT4)
+            c5 = max(2, -(-2 * LLC_BYTES // p5.nbytes()))
+            pk5 = [p5.to(dev) for _ in range(c5)]
+            for M in sweep_m:
+                X = torch.from_numpy(synth.activation_rows(M, k5, 5).view(np.int16)).to(dev).view(torch.float16)
+                Y = torch.empty((M, r5), dtype=torch.float16, device=dev)
+                f5 = [B.prepared_sparse_gemm_smallm(pk5[i], X, Y) for i in range(c5)]
+                t5, _ = time_loop(torch, lambda i: f5[i % c5](), 300, 30)
+                layer_us[M] += reps * t5 * 1e6
+            del pk5
+        fit_a, fit_b = B.fit_verify_cost(list(sweep_m[1:]), [layer_us[m] for m in sweep_m[1:]])
+        cand = [64, 24, 9, 4, 2, 1]                      # candidates left per trie depth (wide top, narrow bottom)
+        rem = [6, 5, 4, 3, 2, 1]                         # tokens still to generate (average ID length 6)
+        depth, gain = B.trigger_depth(layer_us[1], fit_a, fit_b, cand, rem)
+        extra["trigger_model"] = {"layer_us_by_M": {str(m): round(v, 2) for m, v in layer_us.items()},
+                                  "fit_a_us": round(fit_a, 3), "fit_b_us_per_token": round(fit_b, 4),
+                                  "t_ar_us": round(layer_us[1], 2), "candidates": cand, "remaining": rem,
+                                  "trigger_depth": depth, "benefit_us_per_layer": round(gain, 2)}
         # 1:4 sparsity (the sparser layer-adaptive setting), same shape as the headline
         p14 = B.pack_2bitcsr(w, B.prune_n4(w, 1), 1, GRP, B.VAL_INT4)
         c14 = max(2, -(-2 * LLC_BYTES // p14.nbytes()))

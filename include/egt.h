@@ -163,6 +163,19 @@ egt_status egt_int4_gemv_batch(const uint8_t *const *q, const uint16_t *const *q
                                int cols, int group, const uint16_t *const *x, uint16_t *const *y,
                                int count, void *stream);
 
+/* HOST.  Cost model of the parallel-verification trigger (Sec. 3.4 "Parallel
+ * Verification Trigger"): the paper observes that the cost of a verification step grows
+ * linearly with the number of candidate tokens while an autoregressive step costs a
+ * constant.  egt_fit_verify_cost fits t(M) ~ a + b*M by least squares to n >= 2 measured
+ * points (m[i] >= 1, not all equal).  egt_trigger_depth returns in *best the depth d in
+ * [0, depth) that maximises  remaining[d] * t_ar - (a + b * cand[d])  - the time of
+ * generating the remaining tokens one by one minus the time of verifying cand[d]
+ * candidates in one step - and that maximum in *benefit; *best = -1 and *benefit = 0 when
+ * no depth has a positive benefit (never trigger).  Equal benefits: the smaller depth. */
+egt_status egt_fit_verify_cost(const int *m, const double *t, int n, double *a, double *b);
+egt_status egt_trigger_depth(double t_ar, double a, double b, const int *cand, const int *remaining,
+                             int depth, int *best, double *benefit);
+
 /* DEVICE.  Measurement aid: streams `bytes` (a multiple of 16) from `src` with
  * 128-bit loads and folds them into one 32-bit word per workgroup written to
  * `sink` (at least 4096 words).  Gives the read bandwidth a kernel of that size

@@ -383,3 +383,27 @@ def size_model(rows: int, cols: int, n_keep: int, value_bits: int, csr_index_bit
     csr = nnz * (csr_value_bits + csr_index_bits) / 8.0
     return dict(nnz=nnz, bytes_2bitcsr=ours, bytes_csr=csr, ratio=ours / csr,
                 bytes_row_ptr=4 * (rows + 1))
+
+
+# --------------------------------------------------------------------------
+# O9  trigger cost model (Sec. 3.4 "Parallel Verification Trigger": verification cost
+#     linear in the number of candidates, autoregressive step constant; trigger where
+#     "time to generate the remaining tokens minus time to verify them" is largest)
+# --------------------------------------------------------------------------
+def fit_verify_cost(m, t):
+    """Least-squares line t ~ a + b*m (normal equations via numpy.linalg.lstsq)."""
+    m = np.asarray(m, dtype=np.float64)
+    t = np.asarray(t, dtype=np.float64)
+    A = np.stack([np.ones_like(m), m], axis=1)
+    (a, b), *_ = np.linalg.lstsq(A, t, rcond=None)
+    return float(a), float(b)
+
+
+def trigger_depth(t_ar, a, b, cand, remaining):
+    """Depth with the largest positive benefit remaining*t_ar - (a + b*cand), else -1."""
+    best, top = -1, 0.0
+    for d, (c, r) in enumerate(zip(cand, remaining)):
+        gain = r * t_ar - (a + b * c)
+        if gain > top:
+            best, top = d, gain
+    return best, top

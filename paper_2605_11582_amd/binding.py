@@ -22,6 +22,7 @@ SYMBOLS = (
     "egt_status_str", "egt_last_hip_error", "egt_2bitcsr_sizes", "egt_prune_n4", "egt_pack_2bitcsr",
     "egt_unpack_2bitcsr", "egt_quant_int4", "egt_int4_gemv", "egt_sparse_gemv",
     "egt_sparse_gemm_smallm", "egt_stream_read", "egt_sparse_gemv_batch", "egt_int4_gemv_batch",
+    "egt_fit_verify_cost", "egt_trigger_depth",
 )
 
 
@@ -74,6 +75,9 @@ def lib() -> C.CDLL:
                                             C.c_int, C.c_void_p]
         L.egt_int4_gemv_batch.argtypes = [C.POINTER(C.c_void_p), C.POINTER(C.c_void_p), C.c_int, C.c_int, C.c_int,
                                           C.POINTER(C.c_void_p), C.POINTER(C.c_void_p), C.c_int, C.c_void_p]
+        L.egt_fit_verify_cost.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.POINTER(C.c_double), C.POINTER(C.c_double)]
+        L.egt_trigger_depth.argtypes = [C.c_double, C.c_double, C.c_double, C.c_void_p, C.c_void_p, C.c_int,
+                                        C.POINTER(C.c_int), C.POINTER(C.c_double)]
         for name in SYMBOLS:
             if name not in ("egt_status_str", "egt_last_hip_error"):
                 getattr(L, name).restype = C.c_int
@@ -203,6 +207,22 @@ def quant_int4(w: np.ndarray, group: int):
     qparams = np.empty((rows, cols // group, 2), dtype=np.uint16)
     _check(lib().egt_quant_int4(_np_ptr(w), _ld(w), rows, cols, group, _np_ptr(q), _np_ptr(qparams)))
     return q, qparams
+
+
+def fit_verify_cost(m, t):
+    m = np.ascontiguousarray(m, dtype=np.int32)
+    t = np.ascontiguousarray(t, dtype=np.float64)
+    a, b = C.c_double(), C.c_double()
+    _check(lib().egt_fit_verify_cost(_np_ptr(m), _np_ptr(t), len(m), C.byref(a), C.byref(b)))
+    return a.value, b.value
+
+
+def trigger_depth(t_ar: float, a: float, b: float, cand, remaining):
+    cand = np.ascontiguousarray(cand, dtype=np.int32)
+    remaining = np.ascontiguousarray(remaining, dtype=np.int32)
+    best, gain = C.c_int(), C.c_double()
+    _check(lib().egt_trigger_depth(t_ar, a, b, _np_ptr(cand), _np_ptr(remaining), len(cand), C.byref(best), C.byref(gain)))
+    return best.value, gain.value
 
 
 # ------------------------------------------------------------------ device calls

@@ -347,4 +347,35 @@ egt_status egt_quant_int4(const uint16_t *w, int64_t ldw, int rows, int cols, in
   return EGT_OK;
 }
 
+egt_status egt_fit_verify_cost(const int *m, const double *t, int n, double *a, double *b) {
+  if (!m || !t || !a || !b) return EGT_ERR_NULL;
+  if (n < 2) return EGT_ERR_SHAPE;
+  double sm = 0, st = 0, smm = 0, smt = 0;
+  for (int i = 0; i < n; ++i) {
+    if (m[i] < 1 || !std::isfinite(t[i])) return EGT_ERR_SHAPE;
+    sm += m[i]; st += t[i]; smm += (double)m[i] * m[i]; smt += (double)m[i] * t[i];
+  }
+  const double den = n * smm - sm * sm;
+  if (den == 0.0) return EGT_ERR_SHAPE;               // all M equal: no slope
+  *b = (n * smt - sm * st) / den;
+  *a = (st - *b * sm) / n;
+  return EGT_OK;
+}
+
+egt_status egt_trigger_depth(double t_ar, double a, double b, const int *cand, const int *remaining,
+                             int depth, int *best, double *benefit) {
+  if (!cand || !remaining || !best || !benefit) return EGT_ERR_NULL;
+  if (depth < 1) return EGT_ERR_SHAPE;
+  int arg = -1;
+  double top = 0.0;
+  for (int d = 0; d < depth; ++d) {
+    if (cand[d] < 0 || remaining[d] < 0) return EGT_ERR_SHAPE;
+    const double gain = remaining[d] * t_ar - (a + b * cand[d]);
+    if (gain > top) { top = gain; arg = d; }          // first depth wins among equal gains
+  }
+  *best = arg;
+  *benefit = top;
+  return EGT_OK;
+}
+
 }  // extern "C"

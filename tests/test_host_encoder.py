@@ -208,3 +208,27 @@ def test_device_entry_points_reject_bad_arguments_without_a_gpu():
     assert L.egt_sparse_gemv_batch(None, ptrs, ptrs, 1, None) == 1
     assert L.egt_int4_gemv_batch(ptrs, ptrs, 8, 64, 32, ptrs, ptrs, 0, None) == 2
     assert L.egt_stream_read(None, 32, 16, None) == 1
+
+
+def test_trigger_cost_model():
+    # exact line is recovered; noisy points match the oracle's least squares
+    m = [1, 2, 4, 8, 16, 32, 64]
+    a, b = B.fit_verify_cost(m, [3.0 + 0.25 * v for v in m])
+    assert a == pytest.approx(3.0) and b == pytest.approx(0.25)
+    rng = np.random.default_rng(4)
+    t = [5.0 + 0.4 * v + rng.normal(0, 0.3) for v in m]
+    assert B.fit_verify_cost(m, t) == pytest.approx(O.fit_verify_cost(m, t))
+    with pytest.raises(B.EgtError):
+        B.fit_verify_cost([4, 4], [1.0, 2.0])
+    # trie wide at the top, narrow at the bottom: candidates shrink with depth
+    cand = [64, 24, 9, 4, 2, 1]
+    rem = [6, 5, 4, 3, 2, 1]
+    for t_ar, aa, bb in [(10.0, 8.0, 0.5), (10.0, 8.0, 2.0), (1.0, 50.0, 1.0), (10.0, 0.0, 0.0)]:
+        assert B.trigger_depth(t_ar, aa, bb, cand, rem) == pytest.approx(O.trigger_depth(t_ar, aa, bb, cand, rem))
+    # closed form: with a flat verification cost (b = 0) the earliest depth wins;
+    # when verifying never pays, the answer is "never" (-1)
+    assert B.trigger_depth(10.0, 8.0, 0.0, cand, rem)[0] == 0
+    assert B.trigger_depth(1.0, 50.0, 1.0, cand, rem) == (-1, 0.0)
+    # brute force over all depths
+    gains = [r * 10.0 - (8.0 + 2.0 * c) for c, r in zip(cand, rem)]
+    assert B.trigger_depth(10.0, 8.0, 2.0, cand, rem)[0] == int(np.argmax(gains))
