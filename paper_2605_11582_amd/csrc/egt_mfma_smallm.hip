@@ -1,33 +1,20 @@
 // Small-M SparseGemm (2 <= M <= 64 activation rows) on the gfx950 sparse matrix
 // cores: the parallel-verification form of the product, Y[m][r] = sum_k W[r][k] X[m][k].
 //
-// Mapping.  Here the 16 rows of the A operand of v_smfmac_f32_16x16x64_f16 are 16
-// matrix rows and the 16 columns of B are 16 activation rows (tokens), so all 256
-// outputs of an instruction are used.  A wave owns one row tile (16 rows) and
-// walks K in steps of 256 dense columns.  In a step, lane (i, kb) = i + 16 kb loads
-// the chunk (64 dense columns = 16 B of nibbles + 8 B of idx words) number kb of
-// row i; its four dwords feed four instructions.  Instruction d therefore sees,
-// as its k-range [16 kb, 16 kb + 16), the dense columns 64 kb + 16 d .. + 15 of the
-// step - any fixed permutation of k is fine as long as B follows it, and B is
-// read from LDS with exactly that permutation.
-// The activations of a step (M tokens x 256 columns) are staged in LDS once per
-// workgroup and shared by its waves; token rows are padded by 16 B so that the
-// 16 lanes of a B read, one token each, fall into different banks.
-// The dequantised A registers of a step are reused for every group of 16 tokens.
+// Mapping.  The 16 rows of the A operand of v_smfmac_f32_16x16x64_f16 are 16 matrix
+// rows (a row tile) and the 16 columns of B are 16 activation rows (a token group), so
+// all 256 outputs of an instruction are used.  K is walked in steps of 256 dense
+// columns.  In a step, lane (i, kb) = i + 16 kb holds chunk kb of row i (a chunk is 64
+// dense columns = 16 B of nibbles + 8 B of idx words); its four dwords feed four
+// instructions.  Instruction d therefore sees, as its k-range [16 kb, 16 kb + 16), the
+// dense columns 64 kb + 16 d .. + 15 of the step: any fixed permutation of k is fine
+// as long as B follows it, and B is read from LDS with exactly that permutation.
 #include "egt_mfma_common.h"
 
 #include <cstdio>
 #include <cstdlib>
 
 namespace egt {
-
-// Here a wave-wide load touches 16 rows x 64 B, i.e. half cache lines whose other half
-// is read by a neighbouring wave a moment later: ordinary (cached) loads, not
-// streaming ones, or the line is dropped and fetched twice.
-template <typename T>
-__device__ __forceinline__ T ld_plain(const void *p) {
-  return *(const T *)p;
-}
 
 __device__ __forceinline__ u4 dequant8_sm(uint32_t d, uint32_t off, uint32_t s2, uint32_t mask, uint32_t magic) {
   u4 r;
@@ -39,165 +26,25 @@ __device__ __forceinline__ u4 dequant8_sm(uint32_t d, uint32_t off, uint32_t s2,
   return r;
 }
 
-struct SmallMGeom {
-  int rows, M;
-  int nchunks;         // cols / 64
-  int nsteps;          // cols / 256
-  int gshift;          // INT4 group = 64 << gshift
-  int groups_per_row;
-  int64_t ldx, ldy;
-  uint32_t nib_mask, nib_magic;
-};
-
-constexpr int TOKEN_STRIDE = 528;     // 256 halfs + 16 B pad
-
-// NT = groups of 16 tokens, PF = K-steps of A kept in flight, XPT = 16 B pieces of X
-// each thread stages per step.
-template <int KIND, int NT, int PF, int XPT>
-__global__ __launch_bounds__(256) void k_sparse_smallm(const uint32_t *__restrict__ row_ptr,
-                                                        const uint8_t *__restrict__ values,
-                                                        const uint8_t *__restrict__ idx,
-                                                        const uint8_t *__restrict__ qparams,
-                                                        const __half *__restrict__ X,
-                                                        __half *__restrict__ Y, const SmallMGeom g) {
-  extern __shared__ __align__(16) uint8_t xs[];       // two buffers of 16 NT tokens
-  constexpr int VW = KIND == EGT_VAL_INT4 ? 1 : 4;    // dwordx4 loads of values per chunk
-  const int lane = threadIdx.x & 63;
-  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-  const int nthreads = blockDim.x;
-  const int i = lane & 15, kb = lane >> 4;
-  const int r0 = (blockIdx.x * (nthreads >> 6) + wave) * 16;
-  const int r_ld = min(r0 + i, g.rows - 1);           // row this lane loads (clamped)
-  const uint32_t row_chunk0 = (uint32_t)r_ld * (uint32_t)g.nchunks;
-  const int buf_bytes = 16 * NT * TOKEN_STRIDE;
-
-  // row pointers of the four rows this lane will store
-  uint32_t rp[4];
-#pragma unroll
-  for (int v = 0; v < 4; ++v) rp[v] = row_ptr[min(r0 + 4 * kb + v, g.rows - 1)];
-
-  // ---- staging of X: linear piece index e -> (token, piece)
-  u4 xr[XPT];
-  auto load_x = [&](int step) {
-    const int s = min(step, g.nsteps - 1);
-#pragma unroll
-    for (int j = 0; j < XPT; ++j) {
-      const int e = threadIdx.x + j * nthreads;
-      const int tok = min(e >> 5, g.M - 1), piece = e & 31;
-      xr[j] = *(const u4 *)(X + (int64_t)tok * g.ldx + 256 * s + 8 * piece);
-    }
-  };
-  auto store_x = [&](int step) {
-    uint8_t *buf = xs + (step & 1) * buf_bytes;
-#pragma unroll
-    for (int j = 0; j < XPT; ++j) {
-      const int e = threadIdx.x + j * nthreads;
-      const int tok = e >> 5, piece = e & 31;
-      if (tok < 16 * NT) {
-        u4 v = xr[j];
-        if (tok >= g.M) v = u4{0, 0, 0, 0};
-        *(u4 *)(buf + tok * TOKEN_STRIDE + 16 * piece) = v;
-      }
-    }
-  };
-
-  // ---- A operand of a step
-  u4 nib[PF][VW];
-  u2 iw[PF];
-  uint32_t qp[PF];
-  auto load_a = [&](int slot, int step) {
-    const int s = min(step, g.nsteps - 1);
-    const uint32_t chunk = row_chunk0 + (uint32_t)(4 * s + kb);
-    iw[slot] = ld_plain<u2>(idx + 8ull * chunk);
-    qp[slot] = 0;
-    if (KIND == EGT_VAL_INT4) {
-      nib[slot][0] = ld_plain<u4>(values + 16ull * chunk);
-      qp[slot] = ld_plain<uint32_t>(qparams + 4ull * ((uint32_t)r_ld * (uint32_t)g.groups_per_row +
-                                                        (uint32_t)((4 * s + kb) >> g.gshift)));
-    } else {
-#pragma unroll
-      for (int k = 0; k < VW; ++k) nib[slot][k] = ld_plain<u4>(values + 64ull * chunk + 16 * k);
-    }
-  };
-
-  load_x(0);
-#pragma unroll
-  for (int u = 0; u < PF; ++u) load_a(u, u);
-
-  f4 acc[NT];
-#pragma unroll
-  for (int j = 0; j < NT; ++j) acc[j] = f4{0.f, 0.f, 0.f, 0.f};
-  const uint32_t magic = in_vgpr(g.nib_magic);
-  // LDS byte offset of this lane's B reads: token (lane & 15), octets b and 4 + b
-  const int n = lane & 15, b = lane >> 4;
-  const int boff0 = n * TOKEN_STRIDE + 16 * (8 * (b >> 1) + (b & 1));              // h = 0
-  const int boff1 = n * TOKEN_STRIDE + 16 * (8 * ((4 + b) >> 1) + (b & 1));        // h = 1
-
-  for (int s0 = 0; s0 < g.nsteps; s0 += PF) {
-#pragma unroll
-    for (int u = 0; u < PF; ++u) {
-      const int s = s0 + u;
-      if (s < g.nsteps) {                              // uniform
-        store_x(s);
-        __syncthreads();
-        load_x(s + 1);
-        const uint8_t *buf = xs + (s & 1) * buf_bytes;
-        uint32_t s2 = 0, off = 0;
-        if (KIND == EGT_VAL_INT4) {
-          s2 = __builtin_amdgcn_perm(qp[u], qp[u], 0x01000100u);
-          off = pk_add_f16(__builtin_amdgcn_perm(qp[u], qp[u], 0x03020302u), g.nib_magic);
-        }
-#pragma unroll
-        for (int d = 0; d < 4; ++d) {
-          u4 a;
-          if (KIND == EGT_VAL_INT4) a = dequant8_sm(nib[u][0][d], off, s2, g.nib_mask, magic);
-          else a = nib[u][d];
-          const int iword = d < 2 ? (int)iw[u][0] : (int)iw[u][1];
-#pragma unroll
-          for (int j = 0; j < NT; ++j) {
-            const uint8_t *tb = buf + 16 * j * TOKEN_STRIDE + 32 * d;
-            const u4 lo = *(const u4 *)(tb + boff0);
-            const u4 hi = *(const u4 *)(tb + boff1);
-            const u8v bv = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
-            if (d & 1)
-              acc[j] = __builtin_amdgcn_smfmac_f32_16x16x64_f16(__builtin_bit_cast(h8, a), __builtin_bit_cast(h16, bv), acc[j], iword, 0, 1);
-            else
-              acc[j] = __builtin_amdgcn_smfmac_f32_16x16x64_f16(__builtin_bit_cast(h8, a), __builtin_bit_cast(h16, bv), acc[j], iword, 0, 0);
-          }
-        }
-        load_a(u, s + PF);
-      }
-    }
-  }
-
-  // ---- D[row 4 kb + v][token n] of tile j -> Y[16 j + n][r0 + 4 kb + v]
-  const uint32_t S_row = (uint32_t)g.nchunks * 32u;
-#pragma unroll
-  for (int j = 0; j < NT; ++j) {
-    const int tok = 16 * j + n;
-    if (tok < g.M) {
-#pragma unroll
-      for (int v = 0; v < 4; ++v) {
-        const int r = r0 + 4 * kb + v;
-        if (r < g.rows) {
-          const bool ok = rp[v] == (uint32_t)r * S_row;
-          Y[(int64_t)tok * g.ldy + r] = ok ? __float2half(acc[j][v]) : __ushort_as_half((uint16_t)0x7E00);
-        }
-      }
-    }
-  }
-}
-
-// ---------------------------------------------------------------------------------
-// K-split form.  The waves of a workgroup split K between them: in phase p, wave w
-// owns K-step p * waves + w (256 dense columns).  It fetches its slice of X
-// (16 tokens x 256 columns) with fully coalesced loads, turns it into the B operand
-// layout through a private LDS region (token rows padded against bank conflicts, no
-// workgroup barrier involved) and keeps B in registers while the workgroup walks over
-// its (at most four) row tiles, whose A operands are all requested up front.  Each
-// wave leaves its partial 16 x 16 products in its own region; after one barrier 256
-// threads add them over the waves into running sums, and Y is stored after the last
-// phase.  K <= 4096 is one phase.  Groups of 16 tokens are handled one after the other.
+// The waves of a workgroup split K between them: in phase p, wave w
+// owns K-step p * waves + w (256 dense columns) of every row tile of the workgroup
+// (at most NIT of them, 16 rows each) and keeps its 16 x 16 sums in registers over
+// the phases.  Its slice of X (16 tokens x 256 columns per token group) is fetched
+// with fully coalesced loads and turned into the B operand layout through a private
+// LDS region (token rows padded against bank conflicts; no workgroup barrier).
+// A operand, INT4: lane 4 r + c fetches chunk c of row r of the step, so that four
+// neighbouring lanes read 64 contiguous bytes, and a lane permutation (ds_bpermute)
+// hands the chunk to lane (i, kb) = (r, c) of the matrix instruction.  FP16 values
+// are fetched by lane (i, kb) directly (64 B per lane).
+// The loads of phase p + 1 (A and the first token group of X) are requested while
+// phase p is computed.  Loads return in the order of their requests, so a request
+// for X that follows a request for A waits for A: with NT = 2 token groups the second
+// group of a phase is requested before the A tiles of the next phase and nothing
+// needed soon queues behind the long latency of A.  More than 16 NT tokens are
+// handled in passes over the same rows (the weights of the later passes come from
+// the caches).  After the last phase the waves leave their sums in LDS, one barrier
+// later 4-lane groups add them up over the waves in wave order (a fixed order: the
+// result does not depend on timing) and store four consecutive rows of a token.
 struct SmallMKsGeom {
   int rows, M;
   int nchunks;         // cols / 64
@@ -205,6 +52,8 @@ struct SmallMKsGeom {
   int ntiles;          // ceil(rows / 16)
   int gshift;
   int groups_per_row;
+  int vec_store;       // Y and ldy allow 8-byte stores of four rows
+  uint32_t val_bytes, idx_bytes, qp_bytes, x_bytes;   // extents of the arrays
   int64_t ldx, ldy;
   uint32_t nib_mask, nib_magic;
 };
@@ -216,149 +65,267 @@ struct ATile {                        // A operand of one row tile, one K-step
   uint32_t qp;
 };
 
-constexpr int KS_MAX_ITEMS = 4;                    // row tiles per workgroup
-constexpr int KS_REGION = 16 * TOKEN_STRIDE;       // LDS bytes per wave
+constexpr int KS_PAIR = 1024 + 32;                 // LDS bytes of a pair of tokens
+constexpr int KS_REGION = 8 * KS_PAIR;             // LDS bytes per wave for X
 
-template <int KIND>
-__global__ __launch_bounds__(1024) void k_sparse_smallm_ks(const uint32_t *__restrict__ row_ptr,
-                                                            const uint8_t *__restrict__ values,
-                                                            const uint8_t *__restrict__ idx,
-                                                            const uint8_t *__restrict__ qparams,
-                                                            const __half *__restrict__ X,
-                                                            __half *__restrict__ Y,
-                                                            const SmallMKsGeom g) {
-  extern __shared__ __align__(16) uint8_t xs[];       // [waves][KS_REGION]
-  constexpr int VW = KIND == EGT_VAL_INT4 ? 1 : 4;
-  constexpr int INFL = KIND == EGT_VAL_INT4 ? 3 : 2;  // row tiles whose A operand is in flight together
+__device__ __forceinline__ uint32_t lane_perm(int byte_addr, uint32_t v) {
+  return (uint32_t)__builtin_amdgcn_ds_bpermute(byte_addr, (int)v);
+}
+// Buffer resource over `bytes` bytes at p: loads through it take a 32-bit lane offset
+// plus a 32-bit wave-uniform offset (scalar registers, scalar arithmetic) and return
+// zero past the end instead of faulting.
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void *p, uint32_t bytes) {
+  return __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(p), 0, (int)bytes, 0x00020000);
+}
+// Explicit waits around the loads that write LDS directly: they count as vector-memory
+// operations, return in request order with the register loads, and nothing else tells a
+// following LDS read that their data has landed (or a following load of that kind that
+// the reads of the data it replaces are done).  The statements also keep the compiler
+// from moving memory operations across them.
+template <int N>
+__device__ __forceinline__ void wait_vmem() {       // at most N vector-memory operations still pending
+  asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
+}
+__device__ __forceinline__ void wait_lds() {
+  asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+}
+template <int N>
+__device__ __forceinline__ uint32_t quad_bcast(uint32_t v) {     // value of lane N of the 4-lane group
+  return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, N * 0x55, 0xf, 0xf, true);
+}
+
+template <int KIND, int NT, int NIT, int NWMAX>
+__global__ __launch_bounds__(64 * NWMAX) void k_sparse_smallm_ks(const uint32_t *__restrict__ row_ptr,
+                                                                  const uint8_t *__restrict__ values,
+                                                                  const uint8_t *__restrict__ idx,
+                                                                  const uint8_t *__restrict__ qparams,
+                                                                  const __half *__restrict__ X,
+                                                                  __half *__restrict__ Y,
+                                                                  const SmallMKsGeom g) {
+  extern __shared__ __align__(16) uint8_t xs[];       // X regions, later the partial sums
+  constexpr bool INT4 = KIND == EGT_VAL_INT4;
+  constexpr int VW = INT4 ? 1 : 4;
+  constexpr bool HOLD = NT > 1;                       // A operands of a phase are kept for all token groups
+  constexpr int PART = NIT * NT * 1024;               // bytes of partial sums per wave
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int nw = blockDim.x >> 6;
   const int i = lane & 15, kb = lane >> 4;
-  const int nit = (g.ntiles - (int)blockIdx.x + (int)gridDim.x - 1) / (int)gridDim.x;   // <= KS_MAX_ITEMS
+  const int li = INT4 ? (lane >> 2) : i, lc = INT4 ? (lane & 3) : kb;   // row, chunk this lane fetches
+  const int from = 4 * (4 * i + kb);                  // lane that fetched the chunk of lane (i, kb), as a byte address
+  const int nit = (g.ntiles - (int)blockIdx.x + (int)gridDim.x - 1) / (int)gridDim.x;   // <= NIT
   const int phases = (g.nsteps + nw - 1) / nw;
   const uint32_t magic = in_vgpr(g.nib_magic);
   const uint32_t S_row = (uint32_t)g.nchunks * 32u;
   uint8_t *region = xs + wave * KS_REGION;
-  // role of this thread in the cross-wave sum: row tile rit, register sv of lane sl
-  const int rit = threadIdx.x >> 8, sv = (threadIdx.x >> 6) & 3, sl = threadIdx.x & 63;
-  const int srow = 16 * ((int)blockIdx.x + rit * (int)gridDim.x) + 4 * (sl >> 4) + sv;
-  const bool summing = rit < nit && srow < g.rows;
+  const int ngroups = (g.M + 15) >> 4;
+  // Row pointers of the workgroup's rows are requested first and checked at the end
+  // (flags in LDS behind the regions): a row whose pointer is not r * S yields NaN.
+  uint32_t *flags = (uint32_t *)(xs + nw * (KS_REGION > PART ? KS_REGION : PART));
+  const int frow = 16 * ((int)blockIdx.x + (int)(threadIdx.x >> 4) * (int)gridDim.x) + (int)(threadIdx.x & 15);
+  const bool fcheck = (int)threadIdx.x < 16 * nit && frow < g.rows;
+  const uint32_t frp = fcheck ? row_ptr[frow] : 0u;
 
+  const __amdgpu_buffer_rsrc_t r_val = make_rsrc(values, g.val_bytes), r_idx = make_rsrc(idx, g.idx_bytes);
+  const __amdgpu_buffer_rsrc_t r_qp = make_rsrc(qparams, g.qp_bytes), r_x = make_rsrc(X, g.x_bytes);
   auto load_a = [&](ATile<KIND> &a, int it, int step) {
-    const int rt = min((int)blockIdx.x + it * (int)gridDim.x, g.ntiles - 1);
-    const int r = min(16 * rt + i, g.rows - 1);
+    const int rt = (int)blockIdx.x + min(it, nit - 1) * (int)gridDim.x;       // a tile past the end repeats the last one
     const int s = min(step, g.nsteps - 1);
-    const uint32_t chunk = (uint32_t)r * (uint32_t)g.nchunks + (uint32_t)(4 * s + kb);
-    a.iw = ld_plain<u2>(idx + 8ull * chunk);
+    const uint32_t rel = (uint32_t)min(li, g.rows - 1 - 16 * rt);            // row inside the tile (clamped)
+    const uint32_t cl = rel * (uint32_t)g.nchunks + (uint32_t)lc;             // lane part of the chunk number
+    const uint32_t cu = (uint32_t)(16 * rt) * (uint32_t)g.nchunks + (uint32_t)(4 * s);   // uniform part
+    a.iw = __builtin_amdgcn_raw_buffer_load_b64(r_idx, 8u * cl, 8u * cu, 0);
     a.qp = 0;
-    if (KIND == EGT_VAL_INT4) {
-      a.nib[0] = ld_plain<u4>(values + 16ull * chunk);
-      a.qp = ld_plain<uint32_t>(qparams + 4ull * ((uint32_t)r * (uint32_t)g.groups_per_row +
-                                                   (uint32_t)((4 * s + kb) >> g.gshift)));
+    if (INT4) {
+      a.nib[0] = __builtin_amdgcn_raw_buffer_load_b128(r_val, 16u * cl, 16u * cu, 0);
+      const uint32_t qu = (uint32_t)(16 * rt) * (uint32_t)g.groups_per_row + (uint32_t)((4 * s) >> g.gshift);
+      a.qp = __builtin_amdgcn_raw_buffer_load_b32(
+          r_qp, 4u * (rel * (uint32_t)g.groups_per_row + (uint32_t)(lc >> g.gshift)), 4u * qu, 0);
     } else {
 #pragma unroll
-      for (int k = 0; k < VW; ++k) a.nib[k] = ld_plain<u4>(values + 64ull * chunk + 16 * k);
+      for (int k = 0; k < VW; ++k)
+        a.nib[k] = __builtin_amdgcn_raw_buffer_load_b128(r_val, 64u * cl + 16u * k, 64u * cu, 0);
+    }
+  };
+  // fetched form -> operand form: lane (i, kb) takes what lane 4 i + kb fetched
+  auto to_operand = [&](ATile<KIND> &a) {
+    if (INT4) {
+#pragma unroll
+      for (int d = 0; d < 4; ++d) a.nib[0][d] = lane_perm(from, a.nib[0][d]);
+      a.iw[0] = lane_perm(from, a.iw[0]);
+      a.iw[1] = lane_perm(from, a.iw[1]);
+      a.qp = lane_perm(from, a.qp);
+    }
+  };
+  // This wave's slice of X for token group j (16 tokens x 512 B) goes from global memory
+  // straight into its LDS region, no registers in between: instruction u covers tokens
+  // 2 u and 2 u + 1, lane l delivers to byte 16 l of the kilobyte at 1056 u.  The odd token
+  // of a pair has neighbouring 16-byte pieces swapped (piece q at slot q ^ 1) and pairs are
+  // 32 B apart modulo the bank cycle, so the sixteen lanes of a B read (one token each, same
+  // piece) fall into different banks.
+  // Pairs of tokens past M are not fetched and the odd token past an odd M repeats token
+  // M - 1: whatever LDS holds there only reaches columns of the products that are never
+  // stored.
+  const int xtl = lane >> 5;
+  const uint32_t xoff_lo = 16u * (uint32_t)((lane & 31) ^ xtl);               // both halves read the same token
+  const uint32_t xoff_hi = xoff_lo + (uint32_t)xtl * (uint32_t)(2 * g.ldx);
+  auto dma_x = [&](int j, int step) {
+    const uint32_t xs0 = 512u * (uint32_t)min(step, g.nsteps - 1);
+    asm volatile("" ::: "memory");                    // the eight requests stay together, in program order
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      const int t0 = 16 * j + 2 * u;
+      if (t0 < g.M)                                   // uniform
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(r_x, (__attribute__((address_space(3))) void *)(region + KS_PAIR * u),
+                                                 16, t0 + 1 < g.M ? xoff_hi : xoff_lo,
+                                                 xs0 + (uint32_t)t0 * (uint32_t)(2 * g.ldx), 0, 0);
+    }
+    asm volatile("" ::: "memory");
+  };
+  // B operand: lane (n, b) holds token n, k-octets b and 4 + b of each 16-column group d,
+  // i.e. piece q = 16 h + 8 (b >> 1) + 2 d + (b & 1) for h = 0, 1
+  auto read_b = [&](u8v (&bx)[4]) {
+    const int n = lane & 15, b = lane >> 4;
+    const uint8_t *base0 = region + KS_PAIR * (n >> 1) + 512 * (n & 1) + 16 * (8 * (b >> 1) + ((b ^ n) & 1));
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+#pragma unroll
+      for (int d = 0; d < 4; ++d) {
+        const u4 v = *(const u4 *)(base0 + 256 * h + 32 * d);
+#pragma unroll
+        for (int k = 0; k < 4; ++k) bx[d][4 * h + k] = v[k];
+      }
+    }
+  };
+  auto dequant = [&](const ATile<KIND> &t, u4 (&av)[4]) {
+    uint32_t s2 = 0, off = 0;
+    if (INT4) {
+      s2 = __builtin_amdgcn_perm(t.qp, t.qp, 0x01000100u);
+      off = pk_add_f16(__builtin_amdgcn_perm(t.qp, t.qp, 0x03020302u), g.nib_magic);
+    }
+#pragma unroll
+    for (int d = 0; d < 4; ++d) {
+      if (INT4) av[d] = dequant8_sm(t.nib[0][d], off, s2, g.nib_mask, magic);
+      else av[d] = t.nib[d];
+    }
+  };
+  auto mfma4 = [&](const u4 (&av)[4], const u2 iw, const u8v (&bx)[4], f4 &acc) {
+#pragma unroll
+    for (int d = 0; d < 4; ++d) {
+      const int iword = d < 2 ? (int)iw[0] : (int)iw[1];
+      if (d & 1)
+        acc = __builtin_amdgcn_smfmac_f32_16x16x64_f16(__builtin_bit_cast(h8, av[d]), __builtin_bit_cast(h16, bx[d]), acc, iword, 0, 1);
+      else
+        acc = __builtin_amdgcn_smfmac_f32_16x16x64_f16(__builtin_bit_cast(h8, av[d]), __builtin_bit_cast(h16, bx[d]), acc, iword, 0, 0);
     }
   };
 
-  const int ngroups = (g.M + 15) >> 4;
-  bool first = true;
-  for (int j = 0; j < ngroups; ++j) {
-    float run = 0.f;
-    const uint32_t rp = summing ? row_ptr[srow] : 0u;
-    for (int p = 0; p < phases; ++p) {
-      const int step = p * nw + wave;
-      // ---- this wave's slice of X: 8 coalesced loads of two token rows each
-      u4 xr[8];
-      const bool step_ok = step < g.nsteps;
+  for (int j0 = 0; j0 < ngroups; j0 += NT) {          // passes of NT token groups
+    ATile<KIND> raw[NIT];
+    f4 acc[NIT][NT];
 #pragma unroll
-      for (int u = 0; u < 8; ++u) {
-        const int tok = 16 * j + 2 * u + (lane >> 5);
-        xr[u] = *(const u4 *)(X + (int64_t)min(tok, g.M - 1) * g.ldx + 256 * min(step, g.nsteps - 1) + 8 * (lane & 31));
-      }
-      ATile<KIND> a[INFL];
+    for (int it = 0; it < NIT; ++it)
 #pragma unroll
-      for (int it = 0; it < INFL; ++it)
-        if (it < nit) load_a(a[it], it, step);
-      // the regions are read by the summing threads of the previous round: wait for them
-      if (!first) __syncthreads();
-      first = false;
+      for (int jj = 0; jj < NT; ++jj) acc[it][jj] = f4{0.f, 0.f, 0.f, 0.f};
+    dma_x(j0, wave);
 #pragma unroll
-      for (int u = 0; u < 8; ++u) {
-        const int tl = 2 * u + (lane >> 5);
-        u4 v = xr[u];
-        if (16 * j + tl >= g.M || !step_ok) v = u4{0, 0, 0, 0};
-        *(u4 *)(region + tl * TOKEN_STRIDE + 16 * (lane & 31)) = v;
-      }
-      // B operand: lane (n, b) reads token n, k-octets b and 4 + b of each 16-column group d
-      u8v bx[4];
-      {
-        const int n = lane & 15, b = lane >> 4;
-#pragma unroll
-        for (int h = 0; h < 2; ++h) {
-          const int kba = (4 * h + b) >> 1, sub = b & 1;
-#pragma unroll
-          for (int d = 0; d < 4; ++d) {
-            const u4 v = *(const u4 *)(region + n * TOKEN_STRIDE + 16 * (8 * kba + 2 * d + sub));
-#pragma unroll
-            for (int k = 0; k < 4; ++k) bx[d][4 * h + k] = v[k];
-          }
-        }
-      }
+    for (int it = 0; it < NIT; ++it) load_a(raw[it], it, wave);
 
-      auto compute = [&](const ATile<KIND> &at, int it) {
-        f4 acc = {0.f, 0.f, 0.f, 0.f};
-        uint32_t s2 = 0, off = 0;
-        if (KIND == EGT_VAL_INT4) {
-          s2 = __builtin_amdgcn_perm(at.qp, at.qp, 0x01000100u);
-          off = pk_add_f16(__builtin_amdgcn_perm(at.qp, at.qp, 0x03020302u), g.nib_magic);
+    // A wave whose last step lies past K (K-steps not a multiple of the waves) skips
+    // that phase; it is the last one, nothing is requested in it.
+    for (int p = 0; p < phases && p * nw + wave < g.nsteps; ++p) {
+      const int step = p * nw + wave;
+      const bool more = p + 1 < phases;
+      constexpr int NA = NIT * (INT4 ? 3 : 5);         // loads of the A tiles of one phase
+      u8v bx[4];
+      ATile<KIND> t[NIT];
+      wait_vmem<0>();                                 // X and the A tiles of this phase have arrived
+      read_b(bx);
+#pragma unroll
+      for (int it = 0; it < NIT; ++it) {
+        t[it] = raw[it];
+        to_operand(t[it]);
+      }
+      wait_lds();                                     // the region and the fetch registers are free again
+      if (HOLD) {
+        // requests, in this order: X of the second token group, then the A tiles of the
+        // next phase; X of the next phase follows after the second group has been read
+        if (j0 + 1 < ngroups) dma_x(j0 + 1, step);
+        else if (more) dma_x(j0, step + nw);
+        if (more) {
+#pragma unroll
+          for (int it = 0; it < NIT; ++it) load_a(raw[it], it, step + nw);
         }
+        u4 held[NIT][4];
 #pragma unroll
-        for (int d = 0; d < 4; ++d) {
-          u4 av;
-          if (KIND == EGT_VAL_INT4) av = dequant8_sm(at.nib[0][d], off, s2, g.nib_mask, magic);
-          else av = at.nib[d];
-          const int iword = d < 2 ? (int)at.iw[0] : (int)at.iw[1];
-          if (d & 1)
-            acc = __builtin_amdgcn_smfmac_f32_16x16x64_f16(__builtin_bit_cast(h8, av), __builtin_bit_cast(h16, bx[d]), acc, iword, 0, 1);
-          else
-            acc = __builtin_amdgcn_smfmac_f32_16x16x64_f16(__builtin_bit_cast(h8, av), __builtin_bit_cast(h16, bx[d]), acc, iword, 0, 0);
-        }
-        float *out = (float *)(region + it * 1024);   // B has been read: the region is free
+        for (int it = 0; it < NIT; ++it) dequant(t[it], held[it]);
 #pragma unroll
-        for (int v = 0; v < 4; ++v) out[v * 64 + lane] = acc[v];
-      };
+        for (int jj = 0; jj < NT; ++jj) {
+          if (j0 + jj < ngroups) {                    // uniform
+            if (jj > 0) {
+              if (more) wait_vmem<NA>(); else wait_vmem<0>();
+              read_b(bx);
+              wait_lds();
+              if (jj + 1 < NT && j0 + jj + 1 < ngroups) dma_x(j0 + jj + 1, step);
+              else if (more) dma_x(j0, step + nw);
+            }
 #pragma unroll
-      for (int it0 = 0; it0 < KS_MAX_ITEMS; it0 += INFL) {
-        if (it0 < nit) {
-          if (it0 > 0) {
-#pragma unroll
-            for (int it = 0; it < INFL; ++it)
-              if (it0 + it < nit) load_a(a[it], it0 + it, step);
+            for (int it = 0; it < NIT; ++it)
+              if (it < nit) mfma4(held[it], t[it].iw, bx, acc[it][jj]);
           }
+        }
+      } else {
+        if (more) dma_x(j0, step + nw);
 #pragma unroll
-          for (int it = 0; it < INFL; ++it)
-            if (it0 + it < nit) compute(a[it], it0 + it);
+        for (int it = 0; it < NIT; ++it) {
+          if (it < nit) {
+            u4 av[4];
+            dequant(t[it], av);
+            mfma4(av, t[it].iw, bx, acc[it][0]);
+          }
+          if (more) load_a(raw[it], it, step + nw);  // into the registers this tile has just left
         }
       }
-      __syncthreads();
-      if (summing) {                                  // all reads issued together, then added in wave order
-        const float *src = (const float *)(xs + rit * 1024) + (threadIdx.x & 255);
-        float part[16];
+    }
+    wait_vmem<0>();                                   // a wave that left early may still have X on its way
+
+    // ---- partial sums to LDS: tile (it, jj) of wave w at w * PART + (it * NT + jj) * 1024,
+    //      float 4 * lane + v = D[row 4 (lane >> 4) + v][token lane & 15]
+    __syncthreads();                                  // every wave is done with its X region
+    if (threadIdx.x < 16 * NIT) flags[threadIdx.x] = (fcheck && frp == (uint32_t)frow * S_row) ? 1u : 0u;
 #pragma unroll
-        for (int w = 0; w < 16; ++w) part[w] = w < nw ? src[w * (KS_REGION / 4)] : 0.f;
-        float sum = 0.f;
+    for (int it = 0; it < NIT; ++it)
 #pragma unroll
-        for (int w = 0; w < 16; ++w) sum += part[w];
-        run += sum;
+      for (int jj = 0; jj < NT; ++jj)
+        if (it < nit) *(f4 *)(xs + wave * PART + (it * NT + jj) * 1024 + 16 * lane) = acc[it][jj];
+    __syncthreads();
+    for (int unit = threadIdx.x; unit < NIT * NT * 256; unit += (int)blockDim.x) {
+      const int tj = unit >> 8, it = tj / NT, jj = tj % NT;
+      if (it >= nit || j0 + jj >= ngroups) continue;  // uniform over a wave
+      const int v = unit & 3, sl = (unit >> 2) & 63;  // register v of lane sl of the tile
+      const float *src = (const float *)xs + unit;
+      float part[NWMAX];
+#pragma unroll
+      for (int w = 0; w < NWMAX; ++w) part[w] = src[min(w, nw - 1) * (PART / 4)];
+      float sum = 0.f;
+#pragma unroll
+      for (int w = 0; w < NWMAX; ++w) sum += w < nw ? part[w] : 0.f;
+      const int row0 = 16 * ((int)blockIdx.x + it * (int)gridDim.x) + 4 * (sl >> 4);
+      const int row = row0 + v;
+      const int tok = 16 * (j0 + jj) + (sl & 15);
+      uint32_t hv = 0x7E00u;
+      if (flags[16 * it + 4 * (sl >> 4) + v]) hv = __half_as_ushort(__float2half(sum));
+      const uint32_t h1 = quad_bcast<1>(hv), h2 = quad_bcast<2>(hv), h3 = quad_bcast<3>(hv);
+      if (tok < g.M) {
+        __half *dst = Y + (int64_t)tok * g.ldy + row;
+        if (g.vec_store && row0 + 3 < g.rows) {
+          if (v == 0) *(u2 *)dst = u2{hv | (h1 << 16), h2 | (h3 << 16)};
+        } else if (row < g.rows) {
+          *dst = __ushort_as_half((uint16_t)hv);
+        }
       }
     }
-    // ---- store: thread (rit, sv, sl) owns D[row 4 (sl >> 4) + sv][token sl & 15] of row tile rit
-    const int tok = 16 * j + (sl & 15);
-    if (summing && tok < g.M) {
-      const bool ok = rp == (uint32_t)srow * S_row;
-      Y[(int64_t)tok * g.ldy + srow] = ok ? __float2half(run) : __ushort_as_half((uint16_t)0x7E00);
-    }
+    __syncthreads();                                  // the next pass writes X regions again
   }
 }
 
@@ -372,83 +339,60 @@ bool sparse_smallm_supported(const egt_2bitcsr &w) {
   return true;
 }
 
-static hipError_t launch_sparse_smallm_steps(const egt_2bitcsr &w, const uint16_t *X, int64_t ldx,
-                                             uint16_t *Y, int64_t ldy, int M, hipStream_t stream);
-
-hipError_t launch_sparse_smallm(const egt_2bitcsr &w, const uint16_t *X, int64_t ldx, uint16_t *Y,
-                                int64_t ldy, int M, hipStream_t stream) {
-  if (w.rows == 0) return hipSuccess;
-  const int nsteps = w.cols / 256;
-  int nw = nsteps < 16 ? nsteps : 16;                 // waves per workgroup
-  int blocks_per_cu = 1;
-  if (const char *e = getenv("EGT_SM_TUNE")) sscanf(e, "%d,%d", &nw, &blocks_per_cu);
-  if (nw < 1 || nw > 16) return launch_sparse_smallm_steps(w, X, ldx, Y, ldy, M, stream);
-  SmallMKsGeom g;
-  g.rows = w.rows; g.M = M;
-  g.nchunks = w.cols / 64;
-  g.nsteps = nsteps;
-  g.ntiles = (w.rows + 15) / 16;
-  g.gshift = 0; g.groups_per_row = 0;
-  if (w.val_kind == EGT_VAL_INT4) {
-    while ((64 << g.gshift) < w.group_size) ++g.gshift;
-    g.groups_per_row = w.cols / w.group_size;
-  }
-  g.ldx = ldx; g.ldy = ldy;
-  g.nib_mask = 0x00F0000Fu; g.nib_magic = 0x54006400u;
-  int nblocks = 256 * blocks_per_cu;                  // one (or more) workgroup per compute unit
-  if (nblocks * KS_MAX_ITEMS < g.ntiles) nblocks = (g.ntiles + KS_MAX_ITEMS - 1) / KS_MAX_ITEMS;
-  if (nblocks > g.ntiles) nblocks = g.ntiles;
-  const dim3 grid(nblocks), block(64 * nw);
-  const size_t lds = (size_t)nw * KS_REGION;
-  if (w.val_kind == EGT_VAL_INT4)
-    return launch(k_sparse_smallm_ks<EGT_VAL_INT4>, grid, block, lds, stream, w.row_ptr,
-                  (const uint8_t *)w.values, (const uint8_t *)w.idx, (const uint8_t *)w.qparams,
-                  (const __half *)X, (__half *)Y, g);
-  return launch(k_sparse_smallm_ks<EGT_VAL_FP16>, grid, block, lds, stream, w.row_ptr,
+template <int KIND, int NT, int NIT, int NWMAX>
+static hipError_t go_ks(const egt_2bitcsr &w, const uint16_t *X, uint16_t *Y, const SmallMKsGeom &g, int nw,
+                        int nblocks, hipStream_t stream) {
+  const size_t x_bytes = (size_t)nw * KS_REGION, p_bytes = (size_t)nw * NIT * NT * 1024;
+  const size_t lds = (x_bytes > p_bytes ? x_bytes : p_bytes) + 64 * NIT;   // + row-pointer flags
+  return launch(k_sparse_smallm_ks<KIND, NT, NIT, NWMAX>, dim3(nblocks), dim3(64 * nw), lds, stream, w.row_ptr,
                 (const uint8_t *)w.values, (const uint8_t *)w.idx, (const uint8_t *)w.qparams,
                 (const __half *)X, (__half *)Y, g);
 }
 
-// K-step form (any K that is a multiple of 256): used when K is too wide for one
-// workgroup to cover it with 16 waves.
-static hipError_t launch_sparse_smallm_steps(const egt_2bitcsr &w, const uint16_t *X, int64_t ldx, uint16_t *Y,
+hipError_t launch_sparse_smallm(const egt_2bitcsr &w, const uint16_t *X, int64_t ldx, uint16_t *Y,
                                 int64_t ldy, int M, hipStream_t stream) {
   if (w.rows == 0) return hipSuccess;
-  SmallMGeom g;
+  const bool int4 = w.val_kind == EGT_VAL_INT4;
+  SmallMKsGeom g;
   g.rows = w.rows; g.M = M;
   g.nchunks = w.cols / 64;
   g.nsteps = w.cols / 256;
+  g.ntiles = (w.rows + 15) / 16;
   g.gshift = 0; g.groups_per_row = 0;
-  if (w.val_kind == EGT_VAL_INT4) {
+  if (int4) {
     while ((64 << g.gshift) < w.group_size) ++g.gshift;
     g.groups_per_row = w.cols / w.group_size;
   }
   g.ldx = ldx; g.ldy = ldy;
+  g.vec_store = ((uintptr_t)Y % 8 == 0 && ldy % 4 == 0) ? 1 : 0;
+  const uint64_t chunks = (uint64_t)w.rows * g.nchunks;
+  const uint64_t vb = chunks * (int4 ? 16 : 64), xb = ((uint64_t)(M - 1) * ldx + w.cols) * 2;
+  if (vb >= (1ull << 32) || xb >= (1ull << 32)) return hipErrorInvalidValue;   // 32-bit offsets
+  g.val_bytes = (uint32_t)vb; g.idx_bytes = (uint32_t)(chunks * 8);
+  g.qp_bytes = (uint32_t)((uint64_t)w.rows * g.groups_per_row * 4); g.x_bytes = (uint32_t)xb;
   g.nib_mask = 0x00F0000Fu; g.nib_magic = 0x54006400u;
-  const int nt = M <= 16 ? 1 : (M <= 32 ? 2 : 4);
-  const int row_tiles = (w.rows + 15) / 16;
-  const int nw = row_tiles >= 512 ? 2 : 1;            // waves (row tiles) per workgroup
-  // 16 B pieces per thread per step = 16 nt tokens * 32 pieces / (64 nw threads)
-  const int xpt = 8 * nt / nw;
-  const dim3 grid((row_tiles + nw - 1) / nw), block(64 * nw);
-  const size_t lds = 2 * 16 * nt * TOKEN_STRIDE;
-#define EGT_GO(KIND, NT, PF, XPT)                                                               \
-  launch(k_sparse_smallm<KIND, NT, PF, XPT>, grid, block, lds, stream, w.row_ptr,                \
-         (const uint8_t *)w.values, (const uint8_t *)w.idx, (const uint8_t *)w.qparams,          \
-         (const __half *)X, (__half *)Y, g)
-#define EGT_PICK(KIND, PF)                                                                       \
-  switch (xpt) {                                                                                 \
-    case 2: return EGT_GO(KIND, 1, PF, 2);   /* nt 1, nw 4 */                                    \
-    case 4: return nt == 1 ? EGT_GO(KIND, 1, PF, 4) : EGT_GO(KIND, 2, PF, 4);                    \
-    case 8: return nt == 1 ? EGT_GO(KIND, 1, PF, 8) : nt == 2 ? EGT_GO(KIND, 2, PF, 8)           \
-                                                               : EGT_GO(KIND, 4, PF, 8);         \
-    case 16: return nt == 2 ? EGT_GO(KIND, 2, PF, 16) : EGT_GO(KIND, 4, PF, 16);                 \
-    default: return EGT_GO(KIND, 4, PF, 32); /* nt 4, nw 1 */                                    \
+  // One workgroup per compute unit while its row tiles fit the registers (NIT of them);
+  // up to 16 tokens with 16 waves of 128 registers, more with 8 waves of 256.
+  const bool wide = M > 16 || !int4;                  // 8 waves, two token groups per pass
+  const int nit_max = wide ? 4 : 3;
+  int nwmax = wide ? 8 : 16, blocks_per_cu = 1;
+  if (const char *e = getenv("EGT_SM_TUNE")) sscanf(e, "%d,%d", &nwmax, &blocks_per_cu);
+  if (nwmax < 1 || nwmax > (wide ? 8 : 16)) return hipErrorInvalidValue;
+  const int nw = g.nsteps < nwmax ? g.nsteps : nwmax;
+  int nblocks = 256 * blocks_per_cu;
+  if (nblocks * nit_max < g.ntiles) nblocks = (g.ntiles + nit_max - 1) / nit_max;
+  if (nblocks > g.ntiles) nblocks = g.ntiles;
+  const bool one = nblocks == g.ntiles;               // one row tile per workgroup
+  if (int4) {
+    if (!wide) return one ? go_ks<EGT_VAL_INT4, 1, 1, 16>(w, X, Y, g, nw, nblocks, stream)
+                          : go_ks<EGT_VAL_INT4, 1, 3, 16>(w, X, Y, g, nw, nblocks, stream);
+    return one ? go_ks<EGT_VAL_INT4, 2, 1, 8>(w, X, Y, g, nw, nblocks, stream)
+               : go_ks<EGT_VAL_INT4, 2, 4, 8>(w, X, Y, g, nw, nblocks, stream);
   }
-  if (w.val_kind == EGT_VAL_INT4) { EGT_PICK(EGT_VAL_INT4, 4) }
-  EGT_PICK(EGT_VAL_FP16, 2)
-#undef EGT_PICK
-#undef EGT_GO
+  if (M <= 16) return one ? go_ks<EGT_VAL_FP16, 1, 1, 8>(w, X, Y, g, nw, nblocks, stream)
+                          : go_ks<EGT_VAL_FP16, 1, 4, 8>(w, X, Y, g, nw, nblocks, stream);
+  return one ? go_ks<EGT_VAL_FP16, 2, 1, 8>(w, X, Y, g, nw, nblocks, stream)
+             : go_ks<EGT_VAL_FP16, 2, 4, 8>(w, X, Y, g, nw, nblocks, stream);
 }
 
 }  // namespace egt

@@ -174,8 +174,29 @@ def test_smallm_small_shapes(M):
         G.assert_close(Y, Y_ref, A_ref, f"smallm {rows}x{cols} M={M}")
 
 
+@pytest.mark.parametrize("rows,cols,g,kind,M", [
+    (4200, 256, 128, 0, 7),      # one K-step (one wave), several row tiles per workgroup, ragged last tile
+    (5000, 768, 64, 0, 16),      # three waves, groups of 64
+    (5000, 768, 256, 0, 40),     # two token groups per pass, second pass half empty
+    (4130, 1280, 128, 0, 17),    # five waves, M just past one token group
+    (300, 8704, 128, 0, 32),     # 34 K-steps: phases with idle waves at the end
+    (300, 8704, 128, 0, 9),
+    (4100, 512, 0, 1, 5),        # FP16 values
+    (4100, 512, 0, 1, 48),
+    (13000, 256, 128, 0, 3),     # more row tiles than three per workgroup on 256 workgroups
+])
+def test_smallm_tile_and_wave_shapes(rows, cols, g, kind, M):
+    print(f"case smallm shapes {rows}x{cols} g={g} kind={kind} M={M}", flush=True)
+    p, o = _small_case(rows, cols, 2, g, kind, seed=1300 + M + rows)
+    X = synth.activation_rows(M, cols, 1300 + M)
+    Y_ref, A_ref = O.gemm_smallm(o, X)
+    for pad in (0, 6):           # 8-byte stores of four rows, and the 2-byte fallback
+        Y = G.run_sparse_gemm(p, X, ldx_pad=pad, ldy_pad=pad)
+        G.assert_close(Y, Y_ref, A_ref, f"smallm {rows}x{cols} M={M} pad={pad}")
+
+
 @pytest.mark.parametrize("rows,cols", [(11008, 4096), (4096, 11008)])
-@pytest.mark.parametrize("M", [4, 16, 64])
+@pytest.mark.parametrize("M", [4, 16, 24, 64])
 def test_config5_smallm_full_size(rows, cols, M):
     print(f"case config5 {rows}x{cols} M={M}", flush=True)
     seed = synth.seed_for(5, 0 if rows == 11008 else 1)
