@@ -108,6 +108,18 @@ egt_status egt_2bitcsr_sizes(int rows, int cols, int n_keep, int group, int val_
 egt_status egt_prune_n4(const uint16_t *w, int64_t ldw, int rows, int cols, int n_keep,
                         uint8_t *mask, int64_t ldm);
 
+/* HOST.  N:4 pruning mask by the importance score of Eq. (3) (Sec. 3.2
+ * "Sparsification"): I_ij = |W_ij| * ||X_j||_2 + |W_ij| * |dE/dW_ij|, evaluated in
+ * float64 as written (two products, one sum, no fused multiply-add).  act_norm: cols
+ * floats, the activation norm of every input feature; grad_abs: rows x cols floats,
+ * row stride ldg, the gradient magnitudes, or NULL for a zero gradient term.  The
+ * n_keep entries of largest score of every 4-group are kept (equal scores: lower column
+ * wins).  EGT_ERR_NONFINITE if a weight, norm or gradient is NaN or infinite or a norm
+ * or gradient is negative; the mask is untouched then. */
+egt_status egt_prune_n4_importance(const uint16_t *w, int64_t ldw, const float *act_norm,
+                                   const float *grad_abs, int64_t ldg, int rows, int cols,
+                                   int n_keep, uint8_t *mask, int64_t ldm);
+
 /* HOST.  Encoder of Sec. 3.3 "Sparse Index Structure" fused with the quantiser of
  * Sec. 3.2: dense FP16 W + 0/1 mask + group size -> 2bit-CSR.  `out` has its five
  * scalars ignored on input and filled on success; its four buffers are

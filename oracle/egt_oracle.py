@@ -114,6 +114,28 @@ def importance_eq3(w, act_norm, grad_abs) -> np.ndarray:
     return a * np.asarray(act_norm, dtype=np.float64)[None, :] + a * np.asarray(grad_abs, dtype=np.float64)
 
 
+def prune_n4_importance(w, act_norm, grad_abs, n_keep: int) -> np.ndarray:
+    """Mask keeping, in every 4-group, the n_keep entries of largest Eq. (3) score;
+    equal scores: the lower column wins (Sec. 3.2 "Sparsification")."""
+    w16 = _as_f16(w)
+    R, K = w16.shape
+    if grad_abs is None:
+        grad_abs = np.zeros((R, K))
+    score = importance_eq3(w16, act_norm, grad_abs).reshape(R, K // 4, 4)
+    mask = np.zeros((R, K // 4, 4), dtype=np.uint8)
+    for j in range(4):
+        beats = np.zeros((R, K // 4), dtype=np.int64)
+        for i in range(4):
+            if i == j:
+                continue
+            if i < j:
+                beats += score[:, :, i] >= score[:, :, j]
+            else:
+                beats += score[:, :, i] > score[:, :, j]
+        mask[:, :, j] = beats < n_keep
+    return mask.reshape(R, K)
+
+
 # --------------------------------------------------------------------------
 # O2  slot selection
 # --------------------------------------------------------------------------

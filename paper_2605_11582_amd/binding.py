@@ -22,7 +22,7 @@ SYMBOLS = (
     "egt_status_str", "egt_last_hip_error", "egt_2bitcsr_sizes", "egt_prune_n4", "egt_pack_2bitcsr",
     "egt_unpack_2bitcsr", "egt_quant_int4", "egt_int4_gemv", "egt_sparse_gemv",
     "egt_sparse_gemm_smallm", "egt_stream_read", "egt_sparse_gemv_batch", "egt_int4_gemv_batch",
-    "egt_fit_verify_cost", "egt_trigger_depth",
+    "egt_fit_verify_cost", "egt_trigger_depth", "egt_prune_n4_importance",
 )
 
 
@@ -61,6 +61,8 @@ def lib() -> C.CDLL:
         L.egt_last_hip_error.argtypes = []
         L.egt_2bitcsr_sizes.argtypes = [C.c_int] * 5 + [C.POINTER(C.c_size_t)]
         L.egt_prune_n4.argtypes = [C.c_void_p, C.c_int64, C.c_int, C.c_int, C.c_int, C.c_void_p, C.c_int64]
+        L.egt_prune_n4_importance.argtypes = [C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p, C.c_int64, C.c_int,
+                                              C.c_int, C.c_int, C.c_void_p, C.c_int64]
         L.egt_pack_2bitcsr.argtypes = [C.c_void_p, C.c_int64, C.c_void_p, C.c_int64, C.c_int, C.c_int,
                                        C.c_int, C.c_int, C.c_int, C.POINTER(View)]
         L.egt_unpack_2bitcsr.argtypes = [C.POINTER(View), C.c_void_p, C.c_int64, C.c_void_p, C.c_int64]
@@ -133,6 +135,21 @@ def prune_n4(w: np.ndarray, n_keep: int) -> np.ndarray:
     rows, cols = w.shape
     mask = np.empty((rows, cols), dtype=np.uint8)
     _check(lib().egt_prune_n4(_np_ptr(w), _ld(w), rows, cols, n_keep, _np_ptr(mask), cols))
+    return mask
+
+
+def prune_n4_importance(w: np.ndarray, act_norm: np.ndarray, grad_abs, n_keep: int) -> np.ndarray:
+    w = _row_major(_f16_bits(w))
+    rows, cols = w.shape
+    norm = np.ascontiguousarray(act_norm, dtype=np.float32)
+    if norm.shape != (cols,):
+        raise ValueError("act_norm must have one entry per column")
+    grad = None if grad_abs is None else np.ascontiguousarray(grad_abs, dtype=np.float32)
+    if grad is not None and grad.shape != (rows, cols):
+        raise ValueError("grad_abs must have the shape of w")
+    mask = np.empty((rows, cols), dtype=np.uint8)
+    _check(lib().egt_prune_n4_importance(_np_ptr(w), _ld(w), _np_ptr(norm), None if grad is None else _np_ptr(grad),
+                                         cols, rows, cols, n_keep, _np_ptr(mask), cols))
     return mask
 
 

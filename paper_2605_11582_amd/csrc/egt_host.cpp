@@ -161,6 +161,55 @@ egt_status egt_prune_n4(const uint16_t *w, int64_t ldw, int rows, int cols, int 
   return EGT_OK;
 }
 
+egt_status egt_prune_n4_importance(const uint16_t *w, int64_t ldw, const float *act_norm,
+                                   const float *grad_abs, int64_t ldg, int rows, int cols,
+                                   int n_keep, uint8_t *mask, int64_t ldm) {
+  if (!w || !act_norm || !mask) return EGT_ERR_NULL;
+  if (rows < 0 || cols < 0 || cols % 4 != 0 || n_keep < 1 || n_keep > 4 || ldw < cols || ldm < cols ||
+      (grad_abs && ldg < cols))
+    return EGT_ERR_SHAPE;
+  for (int c = 0; c < cols; ++c)
+    if (!(act_norm[c] >= 0.0f) || std::isinf(act_norm[c])) return EGT_ERR_NONFINITE;
+  std::atomic<int> err(EGT_OK);
+  parallel_rows(rows, [&](int r0, int r1) {
+    for (int r = r0; r < r1; ++r) {
+      for (int c = 0; c < cols; ++c) {
+        if ((w[(int64_t)r * ldw + c] & 0x7C00) == 0x7C00) err.store(EGT_ERR_NONFINITE);
+        if (grad_abs) {
+          const float gv = grad_abs[(int64_t)r * ldg + c];
+          if (!(gv >= 0.0f) || std::isinf(gv)) err.store(EGT_ERR_NONFINITE);
+        }
+      }
+    }
+  });
+  if (err.load() != EGT_OK) return (egt_status)err.load();
+  parallel_rows(rows, [=](int r0, int r1) {
+#pragma clang fp contract(off)
+    for (int r = r0; r < r1; ++r) {
+      const uint16_t *wr = w + (int64_t)r * ldw;
+      uint8_t *mr = mask + (int64_t)r * ldm;
+      for (int c = 0; c < cols; c += 4) {
+        double score[4];
+        for (int j = 0; j < 4; ++j) {
+          const double a = std::fabs(half_to_double(wr[c + j]));
+          const double p1 = a * (double)act_norm[c + j];
+          const double p2 = grad_abs ? a * (double)grad_abs[(int64_t)r * ldg + c + j] : 0.0;
+          score[j] = p1 + p2;
+        }
+        for (int j = 0; j < 4; ++j) {
+          int beats = 0;
+          for (int i = 0; i < 4; ++i) {
+            if (i == j) continue;
+            beats += i < j ? (score[i] >= score[j]) : (score[i] > score[j]);
+          }
+          mr[c + j] = beats < n_keep ? 1 : 0;
+        }
+      }
+    }
+  });
+  return EGT_OK;
+}
+
 egt_status egt_pack_2bitcsr(const uint16_t *w, int64_t ldw, const uint8_t *mask, int64_t ldm,
                             int rows, int cols, int n_keep, int group, int val_kind,
                             egt_2bitcsr *out) {

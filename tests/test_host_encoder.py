@@ -59,6 +59,45 @@ def test_prune_matches_oracle(n):
     assert np.array_equal(B.prune_n4(w, n), O.prune_n4_magnitude(w, n))
 
 
+@pytest.mark.parametrize("n", [1, 2, 3])
+def test_importance_prune_matches_oracle(n):
+    rng = np.random.default_rng(300 + n)
+    w = synth.weights(200, 256, 300 + n)
+    w[0, :16] = np.float16(0.25)                              # ties inside groups
+    w[1, :8] = [0.0, -0.0, 0.5, -0.5, -0.0, 0.0, 0.0, -0.0]
+    norm = np.abs(rng.standard_normal(256)).astype(np.float32) * 3
+    norm[5] = 0.0
+    grad = np.abs(rng.standard_normal((200, 256))).astype(np.float32) * 0.01
+    assert np.array_equal(B.prune_n4_importance(w, norm, grad, n), O.prune_n4_importance(w, norm, grad, n))
+    assert np.array_equal(B.prune_n4_importance(w, norm, None, n), O.prune_n4_importance(w, norm, None, n))
+    # constant statistics reduce to magnitude pruning
+    assert np.array_equal(B.prune_n4_importance(w, np.full(256, 2.0, np.float32), None, n), B.prune_n4(w, n))
+
+
+def test_importance_prune_rejects_bad_statistics():
+    w = synth.weights(8, 32, 1)
+    norm = np.ones(32, np.float32)
+    for bad in (-1.0, np.nan, np.inf):
+        nb = norm.copy()
+        nb[7] = bad
+        with pytest.raises(B.EgtError) as e:
+            B.prune_n4_importance(w, nb, None, 2)
+        assert e.value.status == 4
+    g = np.zeros((8, 32), np.float32)
+    g[3, 3] = -0.5
+    with pytest.raises(B.EgtError) as e:
+        B.prune_n4_importance(w, norm, g, 2)
+    assert e.value.status == 4
+    wn = w.copy()
+    wn[2, 2] = np.float16(np.inf)
+    with pytest.raises(B.EgtError) as e:
+        B.prune_n4_importance(wn, norm, None, 2)
+    assert e.value.status == 4
+    with pytest.raises(B.EgtError) as e:
+        B.prune_n4_importance(w, norm, None, 5)
+    assert e.value.status == 2
+
+
 @pytest.mark.parametrize("n,g,kind", [(2, 128, 0), (1, 128, 0), (2, 0, 1), (1, 0, 1), (3, 64, 0), (4, 32, 0), (2, 4, 0)])
 def test_pack_bit_exact_config_like(n, g, kind):
     w = synth.weights(96, 512, 777 + 10 * n + kind)

@@ -109,6 +109,48 @@ def test_prune_equals_eq3_ranking_with_constant_statistics():
     assert np.array_equal(mask, expect.reshape(8, 32))
 
 
+@pytest.mark.parametrize("n", [1, 2, 3])
+def test_importance_pruning_is_top_n_of_eq3_by_exact_arithmetic(n):
+    # brute force with exact rationals: score = |w| * norm + |w| * grad, largest n per
+    # 4-group, ties to the lower column.  Inputs are small dyadic numbers so the float64
+    # evaluation in the oracle is exact and must agree with the rational one.
+    from fractions import Fraction
+    rng = np.random.default_rng(40 + n)
+    w = (rng.integers(-8, 9, size=(6, 16)) / 8.0).astype(np.float16)      # many ties, zeros
+    norm = rng.integers(0, 5, size=16) / 4.0
+    grad = rng.integers(0, 3, size=(6, 16)) / 2.0
+    mask = O.prune_n4_importance(w, norm, grad, n)
+    for r in range(6):
+        for c in range(0, 16, 4):
+            sc = [abs(Fraction(float(w[r, c + j]))) * Fraction(float(norm[c + j])) +
+                  abs(Fraction(float(w[r, c + j]))) * Fraction(float(grad[r, c + j])) for j in range(4)]
+            order = sorted(range(4), key=lambda j: (-sc[j], j))
+            expect = np.zeros(4, dtype=np.uint8)
+            expect[order[:n]] = 1
+            assert np.array_equal(mask[r, c:c + 4], expect), (r, c)
+
+
+def test_importance_pruning_special_cases():
+    w = _rand_w(8, 32, 5)
+    # constant statistics: the magnitude mask
+    assert np.array_equal(O.prune_n4_importance(w, np.full(32, 0.75), None, 2), O.prune_n4_magnitude(w, 2))
+    # all scores zero: the lower columns win
+    m = O.prune_n4_importance(w, np.zeros(32), None, 2)
+    assert np.array_equal(m.reshape(8, 8, 4), np.broadcast_to(np.array([1, 1, 0, 0], np.uint8), (8, 8, 4)))
+    # a huge activation norm on column 4c+3 forces that column in (unless its weight is 0)
+    norm = np.ones(32)
+    norm[3::4] = 1e6
+    m = O.prune_n4_importance(w, norm, None, 1)
+    nz = np.asarray(w, dtype=np.float16)[:, 3::4] != 0
+    assert np.all(m[:, 3::4][nz] == 1)
+    # the gradient term alone can decide: zero norms, gradient only on column 4c+2
+    grad = np.zeros((8, 32))
+    grad[:, 2::4] = 1.0
+    m = O.prune_n4_importance(w, np.zeros(32), grad, 1)
+    nz = np.asarray(w, dtype=np.float16)[:, 2::4] != 0
+    assert np.all(m[:, 2::4][nz] == 1)
+
+
 # ----------------------------------------------------------------- structure
 @pytest.mark.parametrize("n,kind,g", [(2, 0, 32), (1, 0, 32), (2, 1, 0), (3, 0, 16), (4, 0, 64)])
 def test_structure_invariants(n, kind, g):
