@@ -44,9 +44,9 @@ bool sparse_smallm_supported(const egt_2bitcsr &w);
 hipError_t launch_sparse_smallm(const egt_2bitcsr &w, const uint16_t *X, int64_t ldx, uint16_t *Y,
                                 int64_t ldy, int M, hipStream_t stream);
 
-// dense INT4, M = 1, on the matrix cores (group size 128; see int4_m1_supported)
+// dense INT4, M = 1, on the matrix cores (group sizes 32 << j; see int4_m1_supported)
 bool int4_m1_supported(int cols, int group);
-hipError_t launch_int4_m1(const uint8_t *q, const uint16_t *qparams, int rows, int cols,
+hipError_t launch_int4_m1(const uint8_t *q, const uint16_t *qparams, int rows, int cols, int group,
                           const uint16_t *x, uint16_t *y, hipStream_t stream);
 
 // batched forms: `count` identically shaped matrices in one launch (count <= 4)
@@ -55,7 +55,7 @@ hipError_t launch_sparse_m1_batch(const egt_2bitcsr *ws, const uint16_t *const *
 hipError_t launch_sparse_m1_n1_batch(const egt_2bitcsr *ws, const uint16_t *const *xs, uint16_t *const *ys,
                                      int count, hipStream_t stream);
 hipError_t launch_int4_m1_batch(const uint8_t *const *qs, const uint16_t *const *qps, int rows, int cols,
-                                const uint16_t *const *xs, uint16_t *const *ys, int count,
+                                int group, const uint16_t *const *xs, uint16_t *const *ys, int count,
                                 hipStream_t stream);
 
 // dispatchers: pick the tuned kernel for the shape, else the generic one

@@ -13,7 +13,7 @@ hipError_t launch_sparse(const egt_2bitcsr &w, const uint16_t *X, int64_t ldx, u
 
 hipError_t launch_int4(const uint8_t *q, const uint16_t *qparams, int rows, int cols, int group,
                        const uint16_t *x, uint16_t *y, hipStream_t stream) {
-  if (int4_m1_supported(cols, group)) return launch_int4_m1(q, qparams, rows, cols, x, y, stream);
+  if (int4_m1_supported(cols, group)) return launch_int4_m1(q, qparams, rows, cols, group, x, y, stream);
   return launch_int4_generic(q, qparams, rows, cols, group, x, y, stream);
 }
 
@@ -31,7 +31,7 @@ hipError_t launch_sparse_batch(const egt_2bitcsr *ws, const uint16_t *const *xs,
 hipError_t launch_int4_batch(const uint8_t *const *qs, const uint16_t *const *qps, int rows, int cols,
                              int group, const uint16_t *const *xs, uint16_t *const *ys, int count,
                              hipStream_t stream) {
-  if (int4_m1_supported(cols, group)) return launch_int4_m1_batch(qs, qps, rows, cols, xs, ys, count, stream);
+  if (int4_m1_supported(cols, group)) return launch_int4_m1_batch(qs, qps, rows, cols, group, xs, ys, count, stream);
   for (int k = 0; k < count; ++k) {
     const hipError_t e = launch_int4_generic(qs[k], qps[k], rows, cols, group, xs[k], ys[k], stream);
     if (e != hipSuccess) return e;

@@ -12,7 +12,11 @@
 // permute and one and-or per pair, exact), and the kernel finishes a group as
 //   s * ( sum (64 + q) x  -  (64 + z) * sum x ),
 // where sum x over the group does not depend on the row: it is computed once per
-// wave by the same instruction with an all-ones A operand.
+// wave by the same instruction with an all-ones A operand.  Groups of 256, 512, ...
+// columns work the same way (neighbouring quads share their parameters).
+// Groups of 32 or 64 columns are narrower than a quad; there a lane's chunk lies in
+// one group and the lane applies zero point and scale to its values before the
+// matrix instruction (template parameter PRE), two more packed operations per pair.
 #include "egt_mfma_common.h"
 
 #include <cstdio>
@@ -40,14 +44,15 @@ struct DenseGeom {
   int ntiles;          // tiles per phase = ceil(rows / rows_per_tile)
   int phases;          // tiles per row (row-tile mode), else 1
   int mr_shift;        // multi-row mode: log2(nchunks) (16 or 32 chunks per row); else -1
-  int groups_per_row;  // cols / 128
+  int groups_per_row;  // cols / group
+  int gs;              // group = 128 << gs columns (scaled after the instruction) or 32 << gs (before)
   uint32_t last_chunk; // rows * nchunks - 1
   int part_offset;     // byte offset of the per-phase partial sums in LDS
   uint32_t nib_mask;   // 0x00F000F0: the nibble of each half that becomes a mantissa
   uint32_t nib_magic;  // 0x54005400: FP16 64.0 in both halves
 };
 
-template <int TPI, int XP>
+template <int TPI, int XP, bool PRE>
 __device__ __forceinline__ void k_int4_m1_body(const uint8_t *__restrict__ q, const uint8_t *__restrict__ qparams,
     const __half *__restrict__ x, __half *__restrict__ y, const DenseGeom &g) {
   extern __shared__ __align__(16) uint8_t xs[];       // staged x, then [phases][rows of this block] floats
@@ -80,7 +85,10 @@ __device__ __forceinline__ void k_int4_m1_body(const uint8_t *__restrict__ q, co
   const int tile0 = (blockIdx.x * wpp + wslot) * TPI;
   const int ql = lane & 15;
   const int qrow = multirow ? ((4 * ql) >> g.mr_shift) : 0;
-  const int qgrp = multirow ? (((4 * ql) & (g.nchunks - 1)) >> 2) : min(16 * phase + ql, g.groups_per_row - 1);
+  const int rsub = multirow ? (cit >> g.mr_shift) : 0;
+  const int qgrp = PRE ? (c_ld >> g.gs)
+                       : multirow ? ((((4 * ql) & (g.nchunks - 1)) >> 2) >> g.gs)
+                                  : min((16 * phase + ql) >> g.gs, g.groups_per_row - 1);
   u4 nib[TPI];
   uint32_t qp[TPI];
 #pragma unroll
@@ -90,7 +98,7 @@ __device__ __forceinline__ void k_int4_m1_body(const uint8_t *__restrict__ q, co
     if (multirow) chunk = min((uint32_t)tr * 64u + (uint32_t)cit, g.last_chunk);
     else chunk = (uint32_t)tr * (uint32_t)g.nchunks + (uint32_t)c_ld;
     nib[t] = ld_stream<u4>(q + 16ull * chunk);
-    const int r = min(tr * rpt + qrow, g.rows - 1);
+    const int r = min(tr * rpt + (PRE ? rsub : qrow), g.rows - 1);
     qp[t] = ld_stream<uint32_t>(qparams + 4ull * ((uint32_t)r * (uint32_t)g.groups_per_row + (uint32_t)qgrp));
   }
   const int sum_steps = multirow ? (g.mr_shift - 4) : 2;       // log2(quad groups per row)
@@ -130,7 +138,7 @@ __device__ __forceinline__ void k_int4_m1_body(const uint8_t *__restrict__ q, co
   }
   // sum of x over each quad: every row of D gets the column sums of B
   f4 xsum = {0.f, 0.f, 0.f, 0.f};
-  {
+  if (!PRE) {
     const u4 ones = {0x3C003C00u, 0x3C003C00u, 0x3C003C00u, 0x3C003C00u};
 #pragma unroll
     for (int d = 0; d < 4; ++d)
@@ -144,16 +152,28 @@ __device__ __forceinline__ void k_int4_m1_body(const uint8_t *__restrict__ q, co
 #pragma unroll
   for (int t = 0; t < TPI; ++t) {
     f4 acc = {0.f, 0.f, 0.f, 0.f};
+    uint32_t s2 = 0, off = 0;
+    if (PRE) {
+      s2 = __builtin_amdgcn_perm(qp[t], qp[t], 0x01000100u);                            // {s, s}
+      off = pk_add_f16(__builtin_amdgcn_perm(qp[t], qp[t], 0x03020302u), g.nib_magic);  // {64 + z, 64 + z}
+    }
 #pragma unroll
     for (int d = 0; d < 4; ++d) {
-      const u4 a = nibbles_to_f16(nib[t][d], g.nib_mask, magic);
+      u4 a = nibbles_to_f16(nib[t][d], g.nib_mask, magic);
+      if (PRE) {
+#pragma unroll
+        for (int p = 0; p < 4; ++p) a[p] = pk_mul_f16(pk_sub_f16(a[p], off), s2);
+      }
       acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(h8, a), __builtin_bit_cast(h8, bx[d]), acc, 0, 0, 0);
     }
     // lane 20 kb + v holds D[4 kb + v][4 kb + v] in register v = lane & 3
     const float diag = select4(lane & 3, acc[0], acc[1], acc[2], acc[3]);
-    const float sc = __half2float(__ushort_as_half((uint16_t)(qp[t] & 0xFFFFu)));
-    const float zp = __half2float(__ushort_as_half((uint16_t)(qp[t] >> 16)));
-    const float val = sc * (diag - (64.f + zp) * xq);
+    float val = diag;
+    if (!PRE) {
+      const float sc = __half2float(__ushort_as_half((uint16_t)(qp[t] & 0xFFFFu)));
+      const float zp = __half2float(__ushort_as_half((uint16_t)(qp[t] >> 16)));
+      val = sc * (diag - (64.f + zp) * xq);
+    }
     s[t] = val + row_shl<1>(val) + row_shl<2>(val) + row_shl<3>(val);   // valid in lanes 20 kb
   }
   const int src_lane = 20 * (lane & 3);
@@ -188,30 +208,31 @@ __device__ __forceinline__ void k_int4_m1_body(const uint8_t *__restrict__ q, co
   }
 }
 
-template <int TPI, int XP>
+template <int TPI, int XP, bool PRE>
 __global__ __launch_bounds__(1024) void k_int4_m1(const uint8_t *__restrict__ q,
                                                    const uint8_t *__restrict__ qparams,
                                                    const __half *__restrict__ x,
                                                    __half *__restrict__ y, const DenseGeom g) {
-  k_int4_m1_body<TPI, XP>(q, qparams, x, y, g);
+  k_int4_m1_body<TPI, XP, PRE>(q, qparams, x, y, g);
 }
 
-template <int TPI, int XP>
+template <int TPI, int XP, bool PRE>
 __global__ __launch_bounds__(1024) void k_int4_m1_batch(const GemvBatch b, const DenseGeom g) {
-  k_int4_m1_body<TPI, XP>(pick4(b.values, blockIdx.y), pick4(b.qparams, blockIdx.y),
+  k_int4_m1_body<TPI, XP, PRE>(pick4(b.values, blockIdx.y), pick4(b.qparams, blockIdx.y),
                           pick4(b.x, blockIdx.y), pick4(b.y, blockIdx.y), g);
 }
 
-// Shapes covered: group size 128; K = 512 or 1024 (several rows per tile) or a
+// Shapes covered: group size 32 << j; K = 512 or 1024 (several rows per tile) or a
 // multiple of 128 from 2048 up to 16 tiles per row.
 bool int4_m1_supported(int cols, int group) {
-  if (group != 128) return false;
+  const int gm = group / 32;
+  if (group % 32 != 0 || (gm & (gm - 1)) != 0 || cols % group != 0) return false;
   if (cols == 512 || cols == 1024) return true;
   return cols >= 2048 && cols % 128 == 0 && cols <= 16 * 2048;
 }
 
 hipError_t launch_int4_m1_batch(const uint8_t *const *qs, const uint16_t *const *qps, int rows, int cols,
-                                const uint16_t *const *xs, uint16_t *const *ys, int count,
+                                int group, const uint16_t *const *xs, uint16_t *const *ys, int count,
                                 hipStream_t stream) {
   if (rows == 0 || count == 0) return hipSuccess;
   GemvBatch b = {};
@@ -227,7 +248,10 @@ hipError_t launch_int4_m1_batch(const uint8_t *const *qs, const uint16_t *const 
   const int rpt = multirow ? 64 / g.nchunks : 1;
   g.phases = multirow ? 1 : (g.nchunks + 63) / 64;
   g.ntiles = (rows + rpt - 1) / rpt;
-  g.groups_per_row = cols / 128;
+  g.groups_per_row = cols / group;
+  const bool pre = group < 128;
+  g.gs = 0;
+  while (((pre ? 32 : 128) << g.gs) < group) ++g.gs;
   g.last_chunk = (uint32_t)rows * (uint32_t)g.nchunks - 1u;
   g.nib_mask = 0x00F000F0u;
   g.nib_magic = 0x54005400u;
@@ -244,10 +268,11 @@ hipError_t launch_int4_m1_batch(const uint8_t *const *qs, const uint16_t *const 
   const size_t lds = g.part_offset + (g.phases > 1 ? sizeof(float) * g.phases * tiles_per_block : 0);
   const int xp = (lds_pieces + 64 * nwaves - 1) / (64 * nwaves);
   if (xp > 4) return hipErrorInvalidConfiguration;
-#define EGT_GO3(TPI, XP)                                                                         \
-  (count > 1 ? launch(k_int4_m1_batch<TPI, XP>, grid, block, lds, stream, b, g)                    \
-             : launch(k_int4_m1<TPI, XP>, grid, block, lds, stream, b.values[0], b.qparams[0],    \
-                      b.x[0], b.y[0], g))
+#define EGT_GO4(TPI, XP, PRE)                                                                    \
+  (count > 1 ? launch(k_int4_m1_batch<TPI, XP, PRE>, grid, block, lds, stream, b, g)               \
+             : launch(k_int4_m1<TPI, XP, PRE>, grid, block, lds, stream, b.values[0],             \
+                      b.qparams[0], b.x[0], b.y[0], g))
+#define EGT_GO3(TPI, XP) (pre ? EGT_GO4(TPI, XP, true) : EGT_GO4(TPI, XP, false))
 #define EGT_GO(TPI) (xp <= 1 ? EGT_GO3(TPI, 1) : xp == 2 ? EGT_GO3(TPI, 2) : EGT_GO3(TPI, 4))
   switch (tpi) {
     case 1: return EGT_GO(1);
@@ -257,11 +282,12 @@ hipError_t launch_int4_m1_batch(const uint8_t *const *qs, const uint16_t *const 
   }
 #undef EGT_GO
 #undef EGT_GO3
+#undef EGT_GO4
 }
 
-hipError_t launch_int4_m1(const uint8_t *q, const uint16_t *qparams, int rows, int cols,
+hipError_t launch_int4_m1(const uint8_t *q, const uint16_t *qparams, int rows, int cols, int group,
                           const uint16_t *x, uint16_t *y, hipStream_t stream) {
-  return launch_int4_m1_batch(&q, &qparams, rows, cols, &x, &y, 1, stream);
+  return launch_int4_m1_batch(&q, &qparams, rows, cols, group, &x, &y, 1, stream);
 }
 
 }  // namespace egt

@@ -64,7 +64,9 @@ struct M1Geom {
 
 // One wave = TPI tiles, all loaded before the first is consumed.
 // XP = 16 B pieces of x each thread stages (ceil(pieces / block size)).
-template <int KIND, int TPI, int XP>
+// QW = {scale, zero} pairs per chunk: 1 for groups of 64 columns and more, 2 for groups
+// of 32 (dwords 0, 1 of a chunk then belong to the first group, 2, 3 to the second).
+template <int KIND, int TPI, int XP, int QW>
 __device__ __forceinline__ void k_sparse_m1_body(const uint32_t *__restrict__ row_ptr, const uint8_t *__restrict__ values,
     const uint8_t *__restrict__ idx, const uint8_t *__restrict__ qparams, const __half *__restrict__ x,
     __half *__restrict__ y, const M1Geom &g) {
@@ -117,7 +119,7 @@ __device__ __forceinline__ void k_sparse_m1_body(const uint32_t *__restrict__ ro
   // ---- issue every load of the wave's TPI tiles
   u4 nib[TPI][KIND == EGT_VAL_INT4 ? 1 : 4];
   u2 iw[TPI];
-  uint32_t qp[TPI];
+  uint32_t qp[TPI][QW];
 #pragma unroll
   for (int t = 0; t < TPI; ++t) {
     const int tr = min(tile0 + t, g.ntiles - 1);      // uniform
@@ -125,11 +127,17 @@ __device__ __forceinline__ void k_sparse_m1_body(const uint32_t *__restrict__ ro
     if (multirow) chunk = min((uint32_t)tr * 64u + (uint32_t)cit, g.last_chunk);
     else chunk = (uint32_t)tr * (uint32_t)g.nchunks + (uint32_t)c_ld;
     iw[t] = ld_stream<u2>(idx + 8ull * chunk);
-    qp[t] = 0;
+    qp[t][0] = 0;
     if (KIND == EGT_VAL_INT4) {
       nib[t][0] = ld_stream<u4>(values + 16ull * chunk);
       const int r = min(tr * rpt + rsub, g.rows - 1);
-      qp[t] = ld_stream<uint32_t>(qparams + 4ull * ((uint32_t)r * (uint32_t)g.groups_per_row + (uint32_t)(c_ld >> g.gshift)));
+      if (QW == 2) {
+        const u2 v = ld_stream<u2>(qparams + 4ull * ((uint32_t)r * (uint32_t)g.groups_per_row + 2u * (uint32_t)c_ld));
+        qp[t][0] = v[0];
+        qp[t][QW - 1] = v[1];
+      } else {
+        qp[t][0] = ld_stream<uint32_t>(qparams + 4ull * ((uint32_t)r * (uint32_t)g.groups_per_row + (uint32_t)(c_ld >> g.gshift)));
+      }
     } else {
 #pragma unroll
       for (int k = 0; k < 4; ++k) nib[t][k] = ld_stream<u4>(values + 64ull * chunk + 16 * k);
@@ -174,15 +182,19 @@ __device__ __forceinline__ void k_sparse_m1_body(const uint32_t *__restrict__ ro
 #pragma unroll
   for (int t = 0; t < TPI; ++t) {
     f4 acc = {0.f, 0.f, 0.f, 0.f};
-    uint32_t s2 = 0, off = 0;
-    if (KIND == EGT_VAL_INT4) {
-      s2 = __builtin_amdgcn_perm(qp[t], qp[t], 0x01000100u);                            // {s, s}
-      off = pk_add_f16(__builtin_amdgcn_perm(qp[t], qp[t], 0x03020302u), g.nib_magic);  // {1024+z, 64+z}
+    uint32_t s2[QW], off[QW];
+#pragma unroll
+    for (int k = 0; k < QW; ++k) {
+      s2[k] = off[k] = 0;
+      if (KIND == EGT_VAL_INT4) {
+        s2[k] = __builtin_amdgcn_perm(qp[t][k], qp[t][k], 0x01000100u);                            // {s, s}
+        off[k] = pk_add_f16(__builtin_amdgcn_perm(qp[t][k], qp[t][k], 0x03020302u), g.nib_magic);  // {1024+z, 64+z}
+      }
     }
 #pragma unroll
     for (int d = 0; d < 4; ++d) {
       u4 a;
-      if (KIND == EGT_VAL_INT4) a = dequant8(nib[t][0][d], off, s2, g.nib_mask, magic);
+      if (KIND == EGT_VAL_INT4) a = dequant8(nib[t][0][d], off[d * QW / 4], s2[d * QW / 4], g.nib_mask, magic);
       else a = nib[t][d];
       const int iword = d < 2 ? (int)iw[t][0] : (int)iw[t][1];
       if (d & 1)
@@ -234,33 +246,33 @@ __device__ __forceinline__ void k_sparse_m1_body(const uint32_t *__restrict__ ro
 }
 
 // One matrix per launch: the pointers are plain kernel arguments.
-template <int KIND, int TPI, int XP>
+template <int KIND, int TPI, int XP, int QW>
 __global__ __launch_bounds__(1024) void k_sparse_m1(const uint32_t *__restrict__ row_ptr,
                                                      const uint8_t *__restrict__ values,
                                                      const uint8_t *__restrict__ idx,
                                                      const uint8_t *__restrict__ qparams,
                                                      const __half *__restrict__ x,
                                                      __half *__restrict__ y, const M1Geom g) {
-  k_sparse_m1_body<KIND, TPI, XP>(row_ptr, values, idx, qparams, x, y, g);
+  k_sparse_m1_body<KIND, TPI, XP, QW>(row_ptr, values, idx, qparams, x, y, g);
 }
 
 // Several identically shaped matrices per launch, selected by blockIdx.y.
-template <int KIND, int TPI, int XP>
+template <int KIND, int TPI, int XP, int QW>
 __global__ __launch_bounds__(1024) void k_sparse_m1_batch(const GemvBatch b, const M1Geom g) {
-  k_sparse_m1_body<KIND, TPI, XP>(pick4(b.row_ptr, blockIdx.y), pick4(b.values, blockIdx.y),
+  k_sparse_m1_body<KIND, TPI, XP, QW>(pick4(b.row_ptr, blockIdx.y), pick4(b.values, blockIdx.y),
                                   pick4(b.idx, blockIdx.y), pick4(b.qparams, blockIdx.y),
                                   pick4(b.x, blockIdx.y), pick4(b.y, blockIdx.y), g);
 }
 
 // Shapes the diagonal kernel covers: 2:4; K = 1024 or 2048 (several rows per tile)
-// or a multiple of 64 from 4096 up to 16 tiles per row; INT4 groups of 64 << j.
+// or a multiple of 64 from 4096 up to 16 tiles per row; INT4 groups of 32 << j.
 bool sparse_m1_supported(const egt_2bitcsr &w) {
   if (w.n_keep != 2) return false;
   const bool multirow = w.cols == 1024 || w.cols == 2048;
   if (!multirow && (w.cols < 4096 || w.cols % 64 != 0 || w.cols > 16 * 4096)) return false;
   if (w.val_kind == EGT_VAL_INT4) {
-    const int gm = w.group_size / 64;
-    if (w.group_size % 64 != 0 || (gm & (gm - 1)) != 0) return false;
+    const int gm = w.group_size / 32;
+    if (w.group_size % 32 != 0 || (gm & (gm - 1)) != 0) return false;
   }
   return true;
 }
@@ -285,6 +297,7 @@ hipError_t launch_sparse_m1_batch(const egt_2bitcsr *ws, const uint16_t *const *
   g.ntiles = (w.rows + rpt - 1) / rpt;
   g.gshift = 0;
   g.groups_per_row = 0;
+  const bool g32 = w.val_kind == EGT_VAL_INT4 && w.group_size == 32;
   if (w.val_kind == EGT_VAL_INT4) {
     while ((64 << g.gshift) < w.group_size) ++g.gshift;
     g.groups_per_row = w.cols / w.group_size;
@@ -299,6 +312,7 @@ hipError_t launch_sparse_m1_batch(const egt_2bitcsr *ws, const uint16_t *const *
   if (wpp * g.phases > 16) wpp = 16 / g.phases;
   if (tpi != 1 && tpi != 2 && tpi != 4 && tpi != 8) tpi = 4;
   if (w.val_kind == EGT_VAL_FP16 && tpi == 8) tpi = 4;
+  if (g32) tpi = 4;
   const int nwaves = wpp * g.phases;
   const int tiles_per_block = wpp * tpi;
   const dim3 grid((g.ntiles + tiles_per_block - 1) / tiles_per_block, count), block(64 * nwaves);
@@ -307,12 +321,16 @@ hipError_t launch_sparse_m1_batch(const egt_2bitcsr *ws, const uint16_t *const *
   const size_t lds = g.part_offset + (g.phases > 1 ? sizeof(float) * g.phases * tiles_per_block : 0);
   const int xp = (lds_pieces + 64 * nwaves - 1) / (64 * nwaves);
   if (xp > 4) return hipErrorInvalidConfiguration;
-#define EGT_GO3(KIND, TPI, XP)                                                                  \
-  (count > 1 ? launch(k_sparse_m1_batch<KIND, TPI, XP>, grid, block, lds, stream, b, g)             \
-             : launch(k_sparse_m1<KIND, TPI, XP>, grid, block, lds, stream, b.row_ptr[0],          \
+#define EGT_GO4(KIND, TPI, XP, QW)                                                              \
+  (count > 1 ? launch(k_sparse_m1_batch<KIND, TPI, XP, QW>, grid, block, lds, stream, b, g)         \
+             : launch(k_sparse_m1<KIND, TPI, XP, QW>, grid, block, lds, stream, b.row_ptr[0],      \
                       b.values[0], b.idx[0], b.qparams[0], b.x[0], b.y[0], g))
+#define EGT_GO3(KIND, TPI, XP) EGT_GO4(KIND, TPI, XP, 1)
 #define EGT_GO(KIND, TPI)                                                                       \
   (xp <= 1 ? EGT_GO3(KIND, TPI, 1) : xp == 2 ? EGT_GO3(KIND, TPI, 2) : EGT_GO3(KIND, TPI, 4))
+  if (g32)                                             // groups of 32: one launch shape
+    return xp <= 1 ? EGT_GO4(EGT_VAL_INT4, 4, 1, 2) : xp == 2 ? EGT_GO4(EGT_VAL_INT4, 4, 2, 2)
+                                                              : EGT_GO4(EGT_VAL_INT4, 4, 4, 2);
   if (w.val_kind == EGT_VAL_INT4) {
     switch (tpi) {
       case 1: return EGT_GO(EGT_VAL_INT4, 1);
@@ -328,6 +346,7 @@ hipError_t launch_sparse_m1_batch(const egt_2bitcsr *ws, const uint16_t *const *
   }
 #undef EGT_GO
 #undef EGT_GO3
+#undef EGT_GO4
 }
 
 hipError_t launch_sparse_m1(const egt_2bitcsr &w, const uint16_t *x, uint16_t *y, hipStream_t stream) {

@@ -39,7 +39,9 @@ struct M1N1Geom {
   uint32_t nib_magic;  // 0x54006400: FP16 {1024.0, 64.0}
 };
 
-template <int KIND, int TPI, int XP>
+// QW = {scale, zero} pairs per chunk of 128 dense columns: 1 for groups of 128 and more,
+// 2 for groups of 64, 4 for groups of 32.
+template <int KIND, int TPI, int XP, int QW>
 __device__ __forceinline__ void k_sparse_m1_n1_body(const uint32_t *__restrict__ row_ptr, const uint8_t *__restrict__ values,
     const uint8_t *__restrict__ idx, const uint8_t *__restrict__ qparams, const __half *__restrict__ x,
     __half *__restrict__ y, const M1N1Geom &g) {
@@ -72,7 +74,7 @@ __device__ __forceinline__ void k_sparse_m1_n1_body(const uint32_t *__restrict__
   const int tile0 = (blockIdx.x * wpp + wslot) * TPI;
   u4 nib[TPI][KIND == EGT_VAL_INT4 ? 1 : 4];
   u2 iw[TPI];
-  uint32_t qp[TPI];
+  uint32_t qp[TPI][QW];
 #pragma unroll
   for (int t = 0; t < TPI; ++t) {
     const int tr = min(tile0 + t, g.ntiles - 1);
@@ -80,11 +82,22 @@ __device__ __forceinline__ void k_sparse_m1_n1_body(const uint32_t *__restrict__
     if (multirow) chunk = min((uint32_t)tr * 64u + (uint32_t)cit, g.last_chunk);
     else chunk = (uint32_t)tr * (uint32_t)g.nchunks + (uint32_t)c_ld;
     iw[t] = ld_stream<u2>(idx + 8ull * chunk);
-    qp[t] = 0;
+    qp[t][0] = 0;
     if (KIND == EGT_VAL_INT4) {
       nib[t][0] = ld_stream<u4>(values + 16ull * chunk);
       const int r = min(tr * rpt + rsub, g.rows - 1);
-      qp[t] = ld_stream<uint32_t>(qparams + 4ull * ((uint32_t)r * (uint32_t)g.groups_per_row + (uint32_t)(c_ld >> g.gshift)));
+      const uint8_t *qrow = qparams + 4ull * ((uint32_t)r * (uint32_t)g.groups_per_row);
+      if (QW == 4) {
+        const u4 v = ld_stream<u4>(qrow + 16u * (uint32_t)c_ld);
+#pragma unroll
+        for (int k = 0; k < QW; ++k) qp[t][k] = v[k & 3];
+      } else if (QW == 2) {
+        const u2 v = ld_stream<u2>(qrow + 8u * (uint32_t)c_ld);
+#pragma unroll
+        for (int k = 0; k < QW; ++k) qp[t][k] = v[k & 1];
+      } else {
+        qp[t][0] = ld_stream<uint32_t>(qrow + 4u * (uint32_t)(c_ld >> g.gshift));
+      }
     } else {
 #pragma unroll
       for (int k = 0; k < 4; ++k) nib[t][k] = ld_stream<u4>(values + 64ull * chunk + 16 * k);
@@ -142,10 +155,14 @@ __device__ __forceinline__ void k_sparse_m1_n1_body(const uint32_t *__restrict__
 #pragma unroll
   for (int t = 0; t < TPI; ++t) {
     f4 acc = {0.f, 0.f, 0.f, 0.f};
-    uint32_t s2 = 0, off = 0;
-    if (KIND == EGT_VAL_INT4) {
-      s2 = __builtin_amdgcn_perm(qp[t], qp[t], 0x01000100u);                            // {s, s}
-      off = pk_add_f16(__builtin_amdgcn_perm(qp[t], qp[t], 0x03020302u), g.nib_magic);  // {1024+z, 64+z}
+    uint32_t s2[QW], off[QW];
+#pragma unroll
+    for (int k = 0; k < QW; ++k) {
+      s2[k] = off[k] = 0;
+      if (KIND == EGT_VAL_INT4) {
+        s2[k] = __builtin_amdgcn_perm(qp[t][k], qp[t][k], 0x01000100u);                            // {s, s}
+        off[k] = pk_add_f16(__builtin_amdgcn_perm(qp[t][k], qp[t][k], 0x03020302u), g.nib_magic);  // {1024+z, 64+z}
+      }
     }
     const uint32_t sp[4] = {spread_idx(iw[t][0] & 0xFFFFu, g.m8, g.m4, g.m2), spread_idx(iw[t][0] >> 16, g.m8, g.m4, g.m2),
                             spread_idx(iw[t][1] & 0xFFFFu, g.m8, g.m4, g.m2), spread_idx(iw[t][1] >> 16, g.m8, g.m4, g.m2)};
@@ -159,7 +176,7 @@ __device__ __forceinline__ void k_sparse_m1_n1_body(const uint32_t *__restrict__
         for (int p = 0; p < 2; ++p) {
           // the two slots of a byte are dequantised as a pair, then split into {w, 0} registers
           const uint32_t t2 = __builtin_amdgcn_perm(d, d, 0x0c000c00u + (uint32_t)(2 * (m & 1) + p) * 0x00010001u);
-          const uint32_t pair = pk_mul_f16(pk_sub_f16(and_or(t2, g.nib_mask, magic), off), s2);
+          const uint32_t pair = pk_mul_f16(pk_sub_f16(and_or(t2, g.nib_mask, magic), off[m * QW / 8]), s2[m * QW / 8]);
           a[2 * p] = pair & 0xFFFFu;
           a[2 * p + 1] = pair >> 16;
         }
@@ -214,32 +231,32 @@ __device__ __forceinline__ void k_sparse_m1_n1_body(const uint32_t *__restrict__
   }
 }
 
-template <int KIND, int TPI, int XP>
+template <int KIND, int TPI, int XP, int QW>
 __global__ __launch_bounds__(1024) void k_sparse_m1_n1(const uint32_t *__restrict__ row_ptr,
                                                         const uint8_t *__restrict__ values,
                                                         const uint8_t *__restrict__ idx,
                                                         const uint8_t *__restrict__ qparams,
                                                         const __half *__restrict__ x,
                                                         __half *__restrict__ y, const M1N1Geom g) {
-  k_sparse_m1_n1_body<KIND, TPI, XP>(row_ptr, values, idx, qparams, x, y, g);
+  k_sparse_m1_n1_body<KIND, TPI, XP, QW>(row_ptr, values, idx, qparams, x, y, g);
 }
 
-template <int KIND, int TPI, int XP>
+template <int KIND, int TPI, int XP, int QW>
 __global__ __launch_bounds__(1024) void k_sparse_m1_n1_batch(const GemvBatch b, const M1N1Geom g) {
-  k_sparse_m1_n1_body<KIND, TPI, XP>(pick4(b.row_ptr, blockIdx.y), pick4(b.values, blockIdx.y),
+  k_sparse_m1_n1_body<KIND, TPI, XP, QW>(pick4(b.row_ptr, blockIdx.y), pick4(b.values, blockIdx.y),
                                      pick4(b.idx, blockIdx.y), pick4(b.qparams, blockIdx.y),
                                      pick4(b.x, blockIdx.y), pick4(b.y, blockIdx.y), g);
 }
 
 // Shapes covered: 1:4; K = 2048 or 4096 (several rows per tile) or a multiple of 128
-// from 8192 up to 8 tiles per row; INT4 groups of 128 << j.
+// from 8192 up to 8 tiles per row; INT4 groups of 32 << j.
 bool sparse_m1_n1_supported(const egt_2bitcsr &w) {
   if (w.n_keep != 1) return false;
   const bool multirow = w.cols == 2048 || w.cols == 4096;
   if (!multirow && (w.cols < 8192 || w.cols % 128 != 0 || w.cols > 8 * 8192)) return false;
   if (w.val_kind == EGT_VAL_INT4) {
-    const int gm = w.group_size / 128;
-    if (w.group_size % 128 != 0 || (gm & (gm - 1)) != 0) return false;
+    const int gm = w.group_size / 32;
+    if (w.group_size % 32 != 0 || (gm & (gm - 1)) != 0) return false;
   }
   return true;
 }
@@ -277,6 +294,7 @@ hipError_t launch_sparse_m1_n1_batch(const egt_2bitcsr *ws, const uint16_t *cons
   if (wpp * g.phases > 16) wpp = 16 / g.phases;
   if (tpi != 1 && tpi != 2 && tpi != 4) tpi = 2;
   if (w.val_kind == EGT_VAL_FP16 && tpi == 4) tpi = 2;   // 64 B of values per lane and tile
+  if (w.val_kind == EGT_VAL_INT4 && w.group_size < 128) tpi = 2;
   const int nwaves = wpp * g.phases;
   const int tiles_per_block = wpp * tpi;
   const dim3 grid((g.ntiles + tiles_per_block - 1) / tiles_per_block, count), block(64 * nwaves);
@@ -285,12 +303,20 @@ hipError_t launch_sparse_m1_n1_batch(const egt_2bitcsr *ws, const uint16_t *cons
   const size_t lds = g.part_offset + (g.phases > 1 ? sizeof(float) * g.phases * tiles_per_block : 0);
   const int xp = (lds_pieces + 64 * nwaves - 1) / (64 * nwaves);
   if (xp > 4) return hipErrorInvalidConfiguration;
-#define EGT_GO3(KIND, TPI, XP)                                                                  \
-  (count > 1 ? launch(k_sparse_m1_n1_batch<KIND, TPI, XP>, grid, block, lds, stream, b, g)          \
-             : launch(k_sparse_m1_n1<KIND, TPI, XP>, grid, block, lds, stream, b.row_ptr[0],       \
+#define EGT_GO4(KIND, TPI, XP, QW)                                                              \
+  (count > 1 ? launch(k_sparse_m1_n1_batch<KIND, TPI, XP, QW>, grid, block, lds, stream, b, g)      \
+             : launch(k_sparse_m1_n1<KIND, TPI, XP, QW>, grid, block, lds, stream, b.row_ptr[0],   \
                       b.values[0], b.idx[0], b.qparams[0], b.x[0], b.y[0], g))
+#define EGT_GO3(KIND, TPI, XP) EGT_GO4(KIND, TPI, XP, 1)
 #define EGT_GO(KIND, TPI)                                                                       \
   (xp <= 1 ? EGT_GO3(KIND, TPI, 1) : xp == 2 ? EGT_GO3(KIND, TPI, 2) : EGT_GO3(KIND, TPI, 4))
+  if (w.val_kind == EGT_VAL_INT4 && w.group_size < 128) {   // narrow groups: one launch shape each
+    if (w.group_size == 64)
+      return xp <= 1 ? EGT_GO4(EGT_VAL_INT4, 2, 1, 2) : xp == 2 ? EGT_GO4(EGT_VAL_INT4, 2, 2, 2)
+                                                                : EGT_GO4(EGT_VAL_INT4, 2, 4, 2);
+    return xp <= 1 ? EGT_GO4(EGT_VAL_INT4, 2, 1, 4) : xp == 2 ? EGT_GO4(EGT_VAL_INT4, 2, 2, 4)
+                                                              : EGT_GO4(EGT_VAL_INT4, 2, 4, 4);
+  }
   if (w.val_kind == EGT_VAL_INT4) {
     switch (tpi) {
       case 1: return EGT_GO(EGT_VAL_INT4, 1);
@@ -304,6 +330,7 @@ hipError_t launch_sparse_m1_n1_batch(const egt_2bitcsr *ws, const uint16_t *cons
   }
 #undef EGT_GO
 #undef EGT_GO3
+#undef EGT_GO4
 }
 
 hipError_t launch_sparse_m1_n1(const egt_2bitcsr &w, const uint16_t *x, uint16_t *y, hipStream_t stream) {

@@ -58,11 +58,11 @@ struct SmallMKsGeom {
   uint32_t nib_mask, nib_magic;
 };
 
-template <int KIND>
+template <int KIND, int QW>
 struct ATile {                        // A operand of one row tile, one K-step
   u4 nib[KIND == EGT_VAL_INT4 ? 1 : 4];
   u2 iw;
-  uint32_t qp;
+  uint32_t qp[QW];                    // {scale, zero} of the chunk; two for groups of 32 columns
 };
 
 constexpr int KS_PAIR = 1024 + 32;                 // LDS bytes of a pair of tokens
@@ -94,7 +94,7 @@ __device__ __forceinline__ uint32_t quad_bcast(uint32_t v) {     // value of lan
   return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, N * 0x55, 0xf, 0xf, true);
 }
 
-template <int KIND, int NT, int NIT, int NWMAX>
+template <int KIND, int NT, int NIT, int NWMAX, int QW>
 __global__ __launch_bounds__(64 * NWMAX) void k_sparse_smallm_ks(const uint32_t *__restrict__ row_ptr,
                                                                   const uint8_t *__restrict__ values,
                                                                   const uint8_t *__restrict__ idx,
@@ -128,19 +128,27 @@ __global__ __launch_bounds__(64 * NWMAX) void k_sparse_smallm_ks(const uint32_t 
 
   const __amdgpu_buffer_rsrc_t r_val = make_rsrc(values, g.val_bytes), r_idx = make_rsrc(idx, g.idx_bytes);
   const __amdgpu_buffer_rsrc_t r_qp = make_rsrc(qparams, g.qp_bytes), r_x = make_rsrc(X, g.x_bytes);
-  auto load_a = [&](ATile<KIND> &a, int it, int step) {
+  auto load_a = [&](ATile<KIND, QW> &a, int it, int step) {
     const int rt = (int)blockIdx.x + min(it, nit - 1) * (int)gridDim.x;       // a tile past the end repeats the last one
     const int s = min(step, g.nsteps - 1);
     const uint32_t rel = (uint32_t)min(li, g.rows - 1 - 16 * rt);            // row inside the tile (clamped)
     const uint32_t cl = rel * (uint32_t)g.nchunks + (uint32_t)lc;             // lane part of the chunk number
     const uint32_t cu = (uint32_t)(16 * rt) * (uint32_t)g.nchunks + (uint32_t)(4 * s);   // uniform part
     a.iw = __builtin_amdgcn_raw_buffer_load_b64(r_idx, 8u * cl, 8u * cu, 0);
-    a.qp = 0;
+    a.qp[0] = 0;
     if (INT4) {
       a.nib[0] = __builtin_amdgcn_raw_buffer_load_b128(r_val, 16u * cl, 16u * cu, 0);
-      const uint32_t qu = (uint32_t)(16 * rt) * (uint32_t)g.groups_per_row + (uint32_t)((4 * s) >> g.gshift);
-      a.qp = __builtin_amdgcn_raw_buffer_load_b32(
-          r_qp, 4u * (rel * (uint32_t)g.groups_per_row + (uint32_t)(lc >> g.gshift)), 4u * qu, 0);
+      if (QW == 2) {                                  // groups 8 s + 2 lc and the next one
+        const uint32_t qu = (uint32_t)(16 * rt) * (uint32_t)g.groups_per_row + (uint32_t)(8 * s);
+        const u2 v = __builtin_amdgcn_raw_buffer_load_b64(
+            r_qp, 4u * (rel * (uint32_t)g.groups_per_row + 2u * (uint32_t)lc), 4u * qu, 0);
+        a.qp[0] = v[0];
+        a.qp[QW - 1] = v[1];
+      } else {
+        const uint32_t qu = (uint32_t)(16 * rt) * (uint32_t)g.groups_per_row + (uint32_t)((4 * s) >> g.gshift);
+        a.qp[0] = __builtin_amdgcn_raw_buffer_load_b32(
+            r_qp, 4u * (rel * (uint32_t)g.groups_per_row + (uint32_t)(lc >> g.gshift)), 4u * qu, 0);
+      }
     } else {
 #pragma unroll
       for (int k = 0; k < VW; ++k)
@@ -148,13 +156,14 @@ __global__ __launch_bounds__(64 * NWMAX) void k_sparse_smallm_ks(const uint32_t 
     }
   };
   // fetched form -> operand form: lane (i, kb) takes what lane 4 i + kb fetched
-  auto to_operand = [&](ATile<KIND> &a) {
+  auto to_operand = [&](ATile<KIND, QW> &a) {
     if (INT4) {
 #pragma unroll
       for (int d = 0; d < 4; ++d) a.nib[0][d] = lane_perm(from, a.nib[0][d]);
       a.iw[0] = lane_perm(from, a.iw[0]);
       a.iw[1] = lane_perm(from, a.iw[1]);
-      a.qp = lane_perm(from, a.qp);
+#pragma unroll
+      for (int k = 0; k < QW; ++k) a.qp[k] = lane_perm(from, a.qp[k]);
     }
   };
   // This wave's slice of X for token group j (16 tokens x 512 B) goes from global memory
@@ -197,15 +206,19 @@ __global__ __launch_bounds__(64 * NWMAX) void k_sparse_smallm_ks(const uint32_t 
       }
     }
   };
-  auto dequant = [&](const ATile<KIND> &t, u4 (&av)[4]) {
-    uint32_t s2 = 0, off = 0;
-    if (INT4) {
-      s2 = __builtin_amdgcn_perm(t.qp, t.qp, 0x01000100u);
-      off = pk_add_f16(__builtin_amdgcn_perm(t.qp, t.qp, 0x03020302u), g.nib_magic);
+  auto dequant = [&](const ATile<KIND, QW> &t, u4 (&av)[4]) {
+    uint32_t s2[QW], off[QW];
+#pragma unroll
+    for (int k = 0; k < QW; ++k) {
+      s2[k] = off[k] = 0;
+      if (INT4) {
+        s2[k] = __builtin_amdgcn_perm(t.qp[k], t.qp[k], 0x01000100u);
+        off[k] = pk_add_f16(__builtin_amdgcn_perm(t.qp[k], t.qp[k], 0x03020302u), g.nib_magic);
+      }
     }
 #pragma unroll
     for (int d = 0; d < 4; ++d) {
-      if (INT4) av[d] = dequant8_sm(t.nib[0][d], off, s2, g.nib_mask, magic);
+      if (INT4) av[d] = dequant8_sm(t.nib[0][d], off[d * QW / 4], s2[d * QW / 4], g.nib_mask, magic);
       else av[d] = t.nib[d];
     }
   };
@@ -221,7 +234,7 @@ __global__ __launch_bounds__(64 * NWMAX) void k_sparse_smallm_ks(const uint32_t 
   };
 
   for (int j0 = 0; j0 < ngroups; j0 += NT) {          // passes of NT token groups
-    ATile<KIND> raw[NIT];
+    ATile<KIND, QW> raw[NIT];
     f4 acc[NIT][NT];
 #pragma unroll
     for (int it = 0; it < NIT; ++it)
@@ -236,9 +249,9 @@ __global__ __launch_bounds__(64 * NWMAX) void k_sparse_smallm_ks(const uint32_t 
     for (int p = 0; p < phases && p * nw + wave < g.nsteps; ++p) {
       const int step = p * nw + wave;
       const bool more = p + 1 < phases;
-      constexpr int NA = NIT * (INT4 ? 3 : 5);         // loads of the A tiles of one phase
+      constexpr int NA = NIT * (INT4 ? 3 : 5);         // loads of the A tiles of one phase (any QW)
       u8v bx[4];
-      ATile<KIND> t[NIT];
+      ATile<KIND, QW> t[NIT];
       wait_vmem<0>();                                 // X and the A tiles of this phase have arrived
       read_b(bx);
 #pragma unroll
@@ -329,22 +342,22 @@ __global__ __launch_bounds__(64 * NWMAX) void k_sparse_smallm_ks(const uint32_t 
   }
 }
 
-// Shapes covered: 2:4, K a multiple of 256, INT4 groups of 64 << j.
+// Shapes covered: 2:4, K a multiple of 256, INT4 groups of 32 << j.
 bool sparse_smallm_supported(const egt_2bitcsr &w) {
   if (w.n_keep != 2 || w.cols % 256 != 0 || w.cols < 256) return false;
   if (w.val_kind == EGT_VAL_INT4) {
-    const int gm = w.group_size / 64;
-    if (w.group_size % 64 != 0 || (gm & (gm - 1)) != 0) return false;
+    const int gm = w.group_size / 32;
+    if (w.group_size % 32 != 0 || (gm & (gm - 1)) != 0) return false;
   }
   return true;
 }
 
-template <int KIND, int NT, int NIT, int NWMAX>
+template <int KIND, int NT, int NIT, int NWMAX, int QW = 1>
 static hipError_t go_ks(const egt_2bitcsr &w, const uint16_t *X, uint16_t *Y, const SmallMKsGeom &g, int nw,
                         int nblocks, hipStream_t stream) {
   const size_t x_bytes = (size_t)nw * KS_REGION, p_bytes = (size_t)nw * NIT * NT * 1024;
   const size_t lds = (x_bytes > p_bytes ? x_bytes : p_bytes) + 64 * NIT;   // + row-pointer flags
-  return launch(k_sparse_smallm_ks<KIND, NT, NIT, NWMAX>, dim3(nblocks), dim3(64 * nw), lds, stream, w.row_ptr,
+  return launch(k_sparse_smallm_ks<KIND, NT, NIT, NWMAX, QW>, dim3(nblocks), dim3(64 * nw), lds, stream, w.row_ptr,
                 (const uint8_t *)w.values, (const uint8_t *)w.idx, (const uint8_t *)w.qparams,
                 (const __half *)X, (__half *)Y, g);
 }
@@ -383,6 +396,12 @@ hipError_t launch_sparse_smallm(const egt_2bitcsr &w, const uint16_t *X, int64_t
   if (nblocks * nit_max < g.ntiles) nblocks = (g.ntiles + nit_max - 1) / nit_max;
   if (nblocks > g.ntiles) nblocks = g.ntiles;
   const bool one = nblocks == g.ntiles;               // one row tile per workgroup
+  if (int4 && w.group_size == 32) {
+    if (!wide) return one ? go_ks<EGT_VAL_INT4, 1, 1, 16, 2>(w, X, Y, g, nw, nblocks, stream)
+                          : go_ks<EGT_VAL_INT4, 1, 3, 16, 2>(w, X, Y, g, nw, nblocks, stream);
+    return one ? go_ks<EGT_VAL_INT4, 2, 1, 8, 2>(w, X, Y, g, nw, nblocks, stream)
+               : go_ks<EGT_VAL_INT4, 2, 4, 8, 2>(w, X, Y, g, nw, nblocks, stream);
+  }
   if (int4) {
     if (!wide) return one ? go_ks<EGT_VAL_INT4, 1, 1, 16>(w, X, Y, g, nw, nblocks, stream)
                           : go_ks<EGT_VAL_INT4, 1, 3, 16>(w, X, Y, g, nw, nblocks, stream);

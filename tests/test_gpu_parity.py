@@ -31,6 +31,9 @@ def _small_case(rows, cols, n, g, kind, seed, drop=0.0):
     (21, 11008, 2, 0, 1), (50, 320, 2, 64, 0),
     (45, 4096, 1, 128, 0), (33, 8192, 1, 256, 0), (19, 2048, 1, 128, 0), (30, 4096, 1, 0, 1),
     (21, 11008, 1, 0, 1), (130, 4096, 1, 256, 0), (9, 12288, 1, 128, 0), (41, 4160, 2, 64, 0),
+    # narrow quantisation groups on the matrix-core paths
+    (45, 4096, 2, 32, 0), (70, 1024, 2, 32, 0), (21, 11008, 2, 32, 0), (33, 2048, 2, 32, 0),
+    (45, 4096, 1, 32, 0), (45, 4096, 1, 64, 0), (21, 11008, 1, 64, 0), (19, 2048, 1, 32, 0), (9, 12288, 1, 32, 0),
 ])
 def test_sparse_gemv_small(rows, cols, n, g, kind):
     print(f"case sparse_gemv {rows}x{cols} n={n} g={g} kind={kind}", flush=True)
@@ -101,7 +104,10 @@ def test_broken_row_ptr_yields_nan_not_a_fault():
 @pytest.mark.parametrize("rows,cols,g", [(37, 64, 8), (130, 1024, 128), (21, 11008, 128), (50, 4096, 64),
                                          (9, 4096, 4096), (66, 2048, 32), (33, 320, 64), (45, 4096, 128),
                                          (7, 512, 128), (70, 2048, 128), (33, 8192, 128), (19, 2176, 128),
-                                         (1, 4096, 128), (131, 1024, 128)])
+                                         (1, 4096, 128), (131, 1024, 128),
+                                         # other group sizes on the matrix-core path
+                                         (70, 4096, 256), (33, 1024, 32), (20, 512, 64), (40, 1024, 512),
+                                         (21, 11008, 256), (21, 11008, 64), (35, 2048, 2048), (18, 6144, 32)])
 def test_int4_gemv_small(rows, cols, g):
     print(f"case int4_gemv {rows}x{cols} g={g}", flush=True)
     w = synth.weights(rows, cols, 500 + rows)
@@ -113,14 +119,15 @@ def test_int4_gemv_small(rows, cols, g):
     G.assert_close(G.run_int4_gemv(q, qp, g, x), y_ref, a_ref, "int4_gemv")
 
 
-def test_int4_one_hot_x_returns_decoded_column_bit_exact():
+@pytest.mark.parametrize("g", [128, 32, 64, 256])
+def test_int4_one_hot_x_returns_decoded_column_bit_exact(g):
     w = synth.weights(64, 4096, 77)
-    q, qp = B.quant_int4(w, 128)
-    Wd = O.dequant_int4_dense(q, qp, 128)
+    q, qp = B.quant_int4(w, g)
+    Wd = O.dequant_int4_dense(q, qp, g)
     for j in (0, 1, 130, 4095):
         e = np.zeros(4096, dtype=np.float16)
         e[j] = 1
-        y = G.run_int4_gemv(q, qp, 128, e)
+        y = G.run_int4_gemv(q, qp, g, e)
         assert np.array_equal(y.view(np.uint16), Wd[:, j].astype(np.float16).view(np.uint16)), f"column {j}"
 
 
@@ -184,6 +191,9 @@ def test_smallm_small_shapes(M):
     (4100, 512, 0, 1, 5),        # FP16 values
     (4100, 512, 0, 1, 48),
     (13000, 256, 128, 0, 3),     # more row tiles than three per workgroup on 256 workgroups
+    (4200, 512, 32, 0, 6),       # groups of 32 columns: two {scale, zero} pairs per chunk
+    (4200, 512, 32, 0, 30),
+    (50, 8704, 32, 0, 16),
 ])
 def test_smallm_tile_and_wave_shapes(rows, cols, g, kind, M):
     print(f"case smallm shapes {rows}x{cols} g={g} kind={kind} M={M}", flush=True)
@@ -252,7 +262,8 @@ def test_sparse_gemv_batch_equals_separate_calls(rows, cols, n, g, kind, count):
         assert np.array_equal(y.view(np.uint16), G.run_sparse_gemv(ps[k], xs[k]).view(np.uint16))
 
 
-@pytest.mark.parametrize("rows,cols,g,count", [(50, 4096, 128, 3), (21, 11008, 128, 2), (30, 320, 64, 2)])
+@pytest.mark.parametrize("rows,cols,g,count", [(50, 4096, 128, 3), (21, 11008, 128, 2), (30, 320, 64, 2),
+                                               (40, 4096, 64, 4), (40, 4096, 256, 2)])
 def test_int4_gemv_batch_equals_separate_calls(rows, cols, g, count):
     torch = G.torch_mod()
     qs, qps, xs = [], [], []
