@@ -200,7 +200,7 @@ def test_smallm_tile_and_wave_shapes(rows, cols, g, kind, M):
     p, o = _small_case(rows, cols, 2, g, kind, seed=1300 + M + rows)
     X = synth.activation_rows(M, cols, 1300 + M)
     Y_ref, A_ref = O.gemm_smallm(o, X)
-    for pad in (0, 6):           # 8-byte stores of four rows, and the 2-byte fallback
+    for pad in (0, 6, 7):        # 8-byte stores of four rows, the 2-byte fallback, odd strides
         Y = G.run_sparse_gemm(p, X, ldx_pad=pad, ldy_pad=pad)
         G.assert_close(Y, Y_ref, A_ref, f"smallm {rows}x{cols} M={M} pad={pad}")
 
