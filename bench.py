@@ -28,7 +28,7 @@ HBM_PEAK_GBPS = 8000.0
 LLC_BYTES = 256 << 20
 # HBM bytes per launch of the headline kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
 # (profiles/sparse_m1_headline_hbm_traffic.txt): 9062.2 * 2 KiB read + 21.5 KiB written.
-MEASURED_TRAFFIC_BYTES = int(9062.2 * 2048 + 21.5 * 1024)
+MEASURED_TRAFFIC_BYTES = round(9062.2 * 2048 + 21.5 * 1024)
 
 
 def algorithmic_bytes(rows, cols, n_keep, group, kind, m=1):
