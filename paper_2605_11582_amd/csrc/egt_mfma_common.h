@@ -58,6 +58,15 @@ __device__ __forceinline__ float quad_xor2(float v) {
 }
 
 
+// 16-bit index word (8 fields of 2 bits) -> 32 bits with field j at bits [4j, 4j+1]: the
+// index operand of an instruction whose compressed values are {value, 0} pairs (1:4).
+// The masks 0x00FF00FF, 0x0F0F0F0F, 0x33333333 are passed in so that they live in registers.
+__device__ __forceinline__ uint32_t spread_idx(uint32_t w, uint32_t m8, uint32_t m4, uint32_t m2) {
+  uint32_t t = (w | (w << 8)) & m8;
+  t = (t | (t << 4)) & m4;
+  return (t | (t << 2)) & m2;
+}
+
 // Pointer table of a batched launch: up to EGT_MAX_BATCH identically shaped matrices,
 // selected by blockIdx.y (a single product is a batch of one).
 constexpr int EGT_MAX_BATCH = 4;

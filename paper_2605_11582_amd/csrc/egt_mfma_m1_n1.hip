@@ -17,13 +17,6 @@
 
 namespace egt {
 
-// 16-bit index word (8 fields of 2 bits) -> 32 bits with field j at bits [4j, 4j+1]
-__device__ __forceinline__ uint32_t spread_idx(uint32_t w, uint32_t m8, uint32_t m4, uint32_t m2) {
-  uint32_t t = (w | (w << 8)) & m8;      // 0x00FF00FF
-  t = (t | (t << 4)) & m4;               // 0x0F0F0F0F
-  return (t | (t << 2)) & m2;            // 0x33333333
-}
-
 struct M1N1Geom {
   int rows;
   int nchunks;         // cols / 128

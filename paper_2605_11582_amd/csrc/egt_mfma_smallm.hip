@@ -3,12 +3,39 @@
 //
 // Mapping.  The 16 rows of the A operand of v_smfmac_f32_16x16x64_f16 are 16 matrix
 // rows (a row tile) and the 16 columns of B are 16 activation rows (a token group), so
-// all 256 outputs of an instruction are used.  K is walked in steps of 256 dense
-// columns.  In a step, lane (i, kb) = i + 16 kb holds chunk kb of row i (a chunk is 64
-// dense columns = 16 B of nibbles + 8 B of idx words); its four dwords feed four
-// instructions.  Instruction d therefore sees, as its k-range [16 kb, 16 kb + 16), the
-// dense columns 64 kb + 16 d .. + 15 of the step: any fixed permutation of k is fine
-// as long as B follows it, and B is read from LDS with exactly that permutation.
+// all 256 outputs of an instruction are used.  K is walked in steps of four chunks; a
+// chunk is 16 B of nibbles (or 64 B of FP16 values) + 8 B of idx words = 32 slots, i.e.
+// 64 dense columns at 2:4 and 128 at 1:4.  In a step, lane (i, kb) = i + 16 kb holds
+// chunk kb of row i.
+//   2:4: its four dwords feed four instructions; instruction d sees, as its k-range
+//        [16 kb, 16 kb + 16), the dense columns 64 kb + 16 d .. + 15 of the step.
+//   1:4: the instruction wants two values per four columns, so every slot becomes the
+//        pair {value, 0} with its offset in the even index field (spread_idx); eight
+//        instructions finish the step, instruction m takes slots 4 m .. 4 m + 3 of the
+//        chunk = the dense columns 128 kb + 16 m .. + 15.
+// Any fixed permutation of k is fine as long as B follows it, and B is read from LDS
+// with exactly that permutation.
+//
+// The waves of a workgroup split K between them: in phase p, wave w owns K-step
+// p * waves + w of every row tile of the workgroup (at most NIT of them) and keeps its
+// 16 x 16 sums in registers over the phases.  Its slice of X goes from global memory
+// straight into a private LDS region (no registers in between, no workgroup barrier).
+// A operand, INT4: lane 4 r + c fetches chunk c of row r of the step, so that four
+// neighbouring lanes read 64 contiguous bytes, and a lane permutation (ds_bpermute)
+// hands the chunk to lane (i, kb) = (r, c) of the matrix instruction.  FP16 values are
+// fetched by lane (i, kb) directly (64 B per lane).
+// The loads of phase p + 1 are requested while phase p is computed.  Loads return in
+// the order of their requests, so a request for X that follows a request for A waits
+// for A: with NT = 2 token groups the second group of a phase is requested before the
+// A tiles of the next phase and nothing needed soon queues behind the long latency of
+// A.  More than 16 NT tokens are handled in passes over the same rows (the weights of
+// the later passes come from the caches).  After the last phase the waves leave their
+// sums in LDS, one barrier later 4-lane groups add them up over the waves in wave
+// order (a fixed order: the result does not depend on timing) and store four
+// consecutive rows of a token.
+// A last step that K fills only partly: chunks past the end are fetched from a clamped
+// (valid) address and enter with scale 0 (FP16: value 0), the pieces of X past the end
+// are overwritten with zeros in LDS.
 #include "egt_mfma_common.h"
 
 #include <cstdio>
@@ -26,54 +53,36 @@ __device__ __forceinline__ u4 dequant8_sm(uint32_t d, uint32_t off, uint32_t s2,
   return r;
 }
 
-// The waves of a workgroup split K between them: in phase p, wave w
-// owns K-step p * waves + w (256 dense columns) of every row tile of the workgroup
-// (at most NIT of them, 16 rows each) and keeps its 16 x 16 sums in registers over
-// the phases.  Its slice of X (16 tokens x 256 columns per token group) is fetched
-// with fully coalesced loads and turned into the B operand layout through a private
-// LDS region (token rows padded against bank conflicts; no workgroup barrier).
-// A operand, INT4: lane 4 r + c fetches chunk c of row r of the step, so that four
-// neighbouring lanes read 64 contiguous bytes, and a lane permutation (ds_bpermute)
-// hands the chunk to lane (i, kb) = (r, c) of the matrix instruction.  FP16 values
-// are fetched by lane (i, kb) directly (64 B per lane).
-// The loads of phase p + 1 (A and the first token group of X) are requested while
-// phase p is computed.  Loads return in the order of their requests, so a request
-// for X that follows a request for A waits for A: with NT = 2 token groups the second
-// group of a phase is requested before the A tiles of the next phase and nothing
-// needed soon queues behind the long latency of A.  More than 16 NT tokens are
-// handled in passes over the same rows (the weights of the later passes come from
-// the caches).  After the last phase the waves leave their sums in LDS, one barrier
-// later 4-lane groups add them up over the waves in wave order (a fixed order: the
-// result does not depend on timing) and store four consecutive rows of a token.
 struct SmallMKsGeom {
   int rows, M;
-  int nchunks;         // cols / 64
-  int nsteps;          // cols / 256
+  int nchunks;         // cols / 64 (2:4) or cols / 128 (1:4)
+  int nsteps;          // ceil(nchunks / 4)
+  int kpieces;         // cols / 8: 16-byte pieces of a row of X
   int ntiles;          // ceil(rows / 16)
-  int gshift;
+  int gshift;          // one {scale, zero} pair per chunk: group = chunk << gshift columns
   int groups_per_row;
   int vec_store;       // Y and ldy allow 8-byte stores of four rows
   uint32_t val_bytes, idx_bytes, qp_bytes, x_bytes;   // extents of the arrays
   int64_t ldx, ldy;
-  uint32_t nib_mask, nib_magic;
+  uint32_t nib_mask, nib_magic;                        // 0x00F0000F, FP16 {1024.0, 64.0}
+  uint32_t m8, m4, m2;                                 // masks of spread_idx
 };
 
 template <int KIND, int QW>
 struct ATile {                        // A operand of one row tile, one K-step
   u4 nib[KIND == EGT_VAL_INT4 ? 1 : 4];
   u2 iw;
-  uint32_t qp[QW];                    // {scale, zero} of the chunk; two for groups of 32 columns
+  uint32_t qp[QW];                    // {scale, zero} pairs of the chunk (QW > 1: groups narrower than a chunk)
 };
 
-constexpr int KS_PAIR = 1024 + 32;                 // LDS bytes of a pair of tokens
-constexpr int KS_REGION = 8 * KS_PAIR;             // LDS bytes per wave for X
+constexpr int KS_PAIR = 1024 + 32;                 // 2:4: LDS bytes of a pair of tokens (512 B each)
+constexpr int KS_TOKEN_N1 = 1024 + 16;             // 1:4: LDS bytes of a token (1 KiB)
 
 __device__ __forceinline__ uint32_t lane_perm(int byte_addr, uint32_t v) {
   return (uint32_t)__builtin_amdgcn_ds_bpermute(byte_addr, (int)v);
 }
 // Buffer resource over `bytes` bytes at p: loads through it take a 32-bit lane offset
-// plus a 32-bit wave-uniform offset (scalar registers, scalar arithmetic) and return
-// zero past the end instead of faulting.
+// plus a 32-bit wave-uniform offset (scalar registers, scalar arithmetic).
 __device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void *p, uint32_t bytes) {
   return __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(p), 0, (int)bytes, 0x00020000);
 }
@@ -94,7 +103,9 @@ __device__ __forceinline__ uint32_t quad_bcast(uint32_t v) {     // value of lan
   return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, N * 0x55, 0xf, 0xf, true);
 }
 
-template <int KIND, int NT, int NIT, int NWMAX, int QW>
+// KIND: INT4 or FP16 values.  NT: token groups per pass.  NIT: row tiles per workgroup.
+// NWMAX: waves per workgroup at most.  QW: {scale, zero} pairs per chunk.  N1: 1:4.
+template <int KIND, int NT, int NIT, int NWMAX, int QW, bool N1>
 __global__ __launch_bounds__(64 * NWMAX) void k_sparse_smallm_ks(const uint32_t *__restrict__ row_ptr,
                                                                   const uint8_t *__restrict__ values,
                                                                   const uint8_t *__restrict__ idx,
@@ -103,9 +114,13 @@ __global__ __launch_bounds__(64 * NWMAX) void k_sparse_smallm_ks(const uint32_t 
                                                                   __half *__restrict__ Y,
                                                                   const SmallMKsGeom g) {
   extern __shared__ __align__(16) uint8_t xs[];       // X regions, later the partial sums
+  static_assert(!(N1 && NT > 1), "1:4 runs one token group per pass");
   constexpr bool INT4 = KIND == EGT_VAL_INT4;
   constexpr int VW = INT4 ? 1 : 4;
   constexpr bool HOLD = NT > 1;                       // A operands of a phase are kept for all token groups
+  constexpr int NM = N1 ? 8 : 4;                      // matrix instructions per step
+  constexpr int PIECES = N1 ? 64 : 32;                // 16-byte pieces of a token row in a step
+  constexpr int REGION = N1 ? 16 * KS_TOKEN_N1 : 8 * KS_PAIR;   // LDS bytes per wave for X
   constexpr int PART = NIT * NT * 1024;               // bytes of partial sums per wave
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -117,11 +132,11 @@ __global__ __launch_bounds__(64 * NWMAX) void k_sparse_smallm_ks(const uint32_t 
   const int phases = (g.nsteps + nw - 1) / nw;
   const uint32_t magic = in_vgpr(g.nib_magic);
   const uint32_t S_row = (uint32_t)g.nchunks * 32u;
-  uint8_t *region = xs + wave * KS_REGION;
+  uint8_t *region = xs + wave * REGION;
   const int ngroups = (g.M + 15) >> 4;
   // Row pointers of the workgroup's rows are requested first and checked at the end
   // (flags in LDS behind the regions): a row whose pointer is not r * S yields NaN.
-  uint32_t *flags = (uint32_t *)(xs + nw * (KS_REGION > PART ? KS_REGION : PART));
+  uint32_t *flags = (uint32_t *)(xs + nw * (REGION > PART ? REGION : PART));
   const int frow = 16 * ((int)blockIdx.x + (int)(threadIdx.x >> 4) * (int)gridDim.x) + (int)(threadIdx.x & 15);
   const bool fcheck = (int)threadIdx.x < 16 * nit && frow < g.rows;
   const uint32_t frp = fcheck ? row_ptr[frow] : 0u;
@@ -131,23 +146,28 @@ __global__ __launch_bounds__(64 * NWMAX) void k_sparse_smallm_ks(const uint32_t 
   auto load_a = [&](ATile<KIND, QW> &a, int it, int step) {
     const int rt = (int)blockIdx.x + min(it, nit - 1) * (int)gridDim.x;       // a tile past the end repeats the last one
     const int s = min(step, g.nsteps - 1);
-    const uint32_t rel = (uint32_t)min(li, g.rows - 1 - 16 * rt);            // row inside the tile (clamped)
-    const uint32_t cl = rel * (uint32_t)g.nchunks + (uint32_t)lc;             // lane part of the chunk number
+    // (the lane offsets are recomputed at every request: kept across the loops they would
+    //  occupy a dozen registers)
+    const uint32_t rel = (uint32_t)min((int)in_vgpr((uint32_t)li), g.rows - 1 - 16 * rt);   // row inside the tile (clamped)
+    const uint32_t lcc = (uint32_t)min((int)in_vgpr((uint32_t)lc), g.nchunks - 1 - 4 * s);  // chunk inside the step (clamped)
+    const uint32_t cl = rel * (uint32_t)g.nchunks + lcc;                      // lane part of the chunk number
     const uint32_t cu = (uint32_t)(16 * rt) * (uint32_t)g.nchunks + (uint32_t)(4 * s);   // uniform part
     a.iw = __builtin_amdgcn_raw_buffer_load_b64(r_idx, 8u * cl, 8u * cu, 0);
     a.qp[0] = 0;
     if (INT4) {
       a.nib[0] = __builtin_amdgcn_raw_buffer_load_b128(r_val, 16u * cl, 16u * cu, 0);
-      if (QW == 2) {                                  // groups 8 s + 2 lc and the next one
-        const uint32_t qu = (uint32_t)(16 * rt) * (uint32_t)g.groups_per_row + (uint32_t)(8 * s);
-        const u2 v = __builtin_amdgcn_raw_buffer_load_b64(
-            r_qp, 4u * (rel * (uint32_t)g.groups_per_row + 2u * (uint32_t)lc), 4u * qu, 0);
-        a.qp[0] = v[0];
-        a.qp[QW - 1] = v[1];
+      const uint32_t qrow_l = rel * (uint32_t)g.groups_per_row, qrow_u = (uint32_t)(16 * rt) * (uint32_t)g.groups_per_row;
+      if (QW == 4) {
+        const u4 v = __builtin_amdgcn_raw_buffer_load_b128(r_qp, 4u * (qrow_l + 4u * lcc), 4u * (qrow_u + 16u * (uint32_t)s), 0);
+#pragma unroll
+        for (int k = 0; k < QW; ++k) a.qp[k] = v[k & 3];
+      } else if (QW == 2) {
+        const u2 v = __builtin_amdgcn_raw_buffer_load_b64(r_qp, 4u * (qrow_l + 2u * lcc), 4u * (qrow_u + 8u * (uint32_t)s), 0);
+#pragma unroll
+        for (int k = 0; k < QW; ++k) a.qp[k] = v[k & 1];
       } else {
-        const uint32_t qu = (uint32_t)(16 * rt) * (uint32_t)g.groups_per_row + (uint32_t)((4 * s) >> g.gshift);
-        a.qp[0] = __builtin_amdgcn_raw_buffer_load_b32(
-            r_qp, 4u * (rel * (uint32_t)g.groups_per_row + (uint32_t)(lc >> g.gshift)), 4u * qu, 0);
+        a.qp[0] = __builtin_amdgcn_raw_buffer_load_b32(r_qp, 4u * (qrow_l + (lcc >> g.gshift)),
+                                                       4u * (qrow_u + (uint32_t)((4 * s) >> g.gshift)), 0);
       }
     } else {
 #pragma unroll
@@ -166,70 +186,127 @@ __global__ __launch_bounds__(64 * NWMAX) void k_sparse_smallm_ks(const uint32_t 
       for (int k = 0; k < QW; ++k) a.qp[k] = lane_perm(from, a.qp[k]);
     }
   };
-  // This wave's slice of X for token group j (16 tokens x 512 B) goes from global memory
-  // straight into its LDS region, no registers in between: instruction u covers tokens
-  // 2 u and 2 u + 1, lane l delivers to byte 16 l of the kilobyte at 1056 u.  The odd token
-  // of a pair has neighbouring 16-byte pieces swapped (piece q at slot q ^ 1) and pairs are
-  // 32 B apart modulo the bank cycle, so the sixteen lanes of a B read (one token each, same
-  // piece) fall into different banks.
-  // Pairs of tokens past M are not fetched and the odd token past an odd M repeats token
+  // This wave's slice of X for token group j goes from global memory straight into its
+  // LDS region: lane l of a request delivers to byte 16 l of one kilobyte.
+  //   2:4 (512 B per token): request u covers tokens 2 u and 2 u + 1 and lands at
+  //     1056 u.  The odd token of a pair has neighbouring 16-byte pieces swapped (piece
+  //     q at slot q ^ 1) and pairs are 32 B apart modulo the bank cycle, so the sixteen
+  //     lanes of a B read (one token each, same piece) fall into different banks.
+  //   1:4 (1 KiB per token): request u is token u and lands at 1040 u.
+  // Pairs (tokens) past M are not fetched and the odd token past an odd M repeats token
   // M - 1: whatever LDS holds there only reaches columns of the products that are never
-  // stored.
+  // stored.  Pieces past the end of a row of X repeat the last one (and are zeroed later).
   const int xtl = lane >> 5;
-  const uint32_t xoff_lo = 16u * (uint32_t)((lane & 31) ^ xtl);               // both halves read the same token
-  const uint32_t xoff_hi = xoff_lo + (uint32_t)xtl * (uint32_t)(2 * g.ldx);
+  const int slot_piece = N1 ? lane : ((lane & 31) ^ xtl);      // piece of X this lane delivers
   auto dma_x = [&](int j, int step) {
-    const uint32_t xs0 = 512u * (uint32_t)min(step, g.nsteps - 1);
-    asm volatile("" ::: "memory");                    // the eight requests stay together, in program order
+    const int s = min(step, g.nsteps - 1);
+    const int vp = min(PIECES, g.kpieces - PIECES * s);         // pieces of the step inside K
+    const uint32_t xs0 = (uint32_t)(16 * PIECES) * (uint32_t)s;
+    const uint32_t off_lo = 16u * (uint32_t)min(slot_piece, vp - 1);
+    const uint32_t off_hi = off_lo + (uint32_t)xtl * (uint32_t)(2 * g.ldx);
+    asm volatile("" ::: "memory");                    // the requests stay together, in program order
+    if (N1) {
 #pragma unroll
-    for (int u = 0; u < 8; ++u) {
-      const int t0 = 16 * j + 2 * u;
-      if (t0 < g.M)                                   // uniform
-        __builtin_amdgcn_raw_ptr_buffer_load_lds(r_x, (__attribute__((address_space(3))) void *)(region + KS_PAIR * u),
-                                                 16, t0 + 1 < g.M ? xoff_hi : xoff_lo,
-                                                 xs0 + (uint32_t)t0 * (uint32_t)(2 * g.ldx), 0, 0);
+      for (int u = 0; u < 16; ++u) {
+        const int t0 = 16 * j + u;
+        if (t0 < g.M)                                 // uniform
+          __builtin_amdgcn_raw_ptr_buffer_load_lds(r_x, (__attribute__((address_space(3))) void *)(region + KS_TOKEN_N1 * u),
+                                                   16, off_lo, xs0 + (uint32_t)t0 * (uint32_t)(2 * g.ldx), 0, 0);
+      }
+    } else {
+#pragma unroll
+      for (int u = 0; u < 8; ++u) {
+        const int t0 = 16 * j + 2 * u;
+        if (t0 < g.M)                                 // uniform
+          __builtin_amdgcn_raw_ptr_buffer_load_lds(r_x, (__attribute__((address_space(3))) void *)(region + KS_PAIR * u),
+                                                   16, t0 + 1 < g.M ? off_hi : off_lo,
+                                                   xs0 + (uint32_t)t0 * (uint32_t)(2 * g.ldx), 0, 0);
+      }
     }
     asm volatile("" ::: "memory");
   };
-  // B operand: lane (n, b) holds token n, k-octets b and 4 + b of each 16-column group d,
-  // i.e. piece q = 16 h + 8 (b >> 1) + 2 d + (b & 1) for h = 0, 1
-  auto read_b = [&](u8v (&bx)[4]) {
+  // the pieces of a partly filled step that lie past K become zeros
+  auto zero_tail = [&](int step) {
+    const int vp = g.kpieces - PIECES * step;
+    if (vp < PIECES && slot_piece >= vp) {
+#pragma unroll
+      for (int u = 0; u < (N1 ? 16 : 8); ++u)
+        *(u4 *)(region + (N1 ? KS_TOKEN_N1 : KS_PAIR) * u + 16 * lane) = u4{0, 0, 0, 0};
+    }
+  };
+  // B operand: lane (n, b) holds token n, k-octets b and 4 + b of the 16-column group of
+  // each instruction, i.e. the pieces 16 h + 8 (b >> 1) + 2 d + (b & 1) of the step at 2:4
+  // and 32 h + 16 (b >> 1) + 2 m + (b & 1) at 1:4, for h = 0, 1
+  auto read_b = [&](u8v (&bx)[NM]) {
     const int n = lane & 15, b = lane >> 4;
-    const uint8_t *base0 = region + KS_PAIR * (n >> 1) + 512 * (n & 1) + 16 * (8 * (b >> 1) + ((b ^ n) & 1));
+    const uint8_t *base0 = N1 ? region + KS_TOKEN_N1 * n + 16 * (16 * (b >> 1) + (b & 1))
+                              : region + KS_PAIR * (n >> 1) + 512 * (n & 1) + 16 * (8 * (b >> 1) + ((b ^ n) & 1));
 #pragma unroll
     for (int h = 0; h < 2; ++h) {
 #pragma unroll
-      for (int d = 0; d < 4; ++d) {
-        const u4 v = *(const u4 *)(base0 + 256 * h + 32 * d);
+      for (int m = 0; m < NM; ++m) {
+        const u4 v = *(const u4 *)(base0 + (N1 ? 512 : 256) * h + 32 * m);
 #pragma unroll
-        for (int k = 0; k < 4; ++k) bx[d][4 * h + k] = v[k];
+        for (int k = 0; k < 4; ++k) bx[m][4 * h + k] = v[k];
       }
     }
   };
-  auto dequant = [&](const ATile<KIND, QW> &t, u4 (&av)[4]) {
+  // operands of the NM instructions of a step: values av[m], index words iwv[m >> 1]
+  // (instruction m takes the low half of its word for even m, the high half for odd m)
+  auto operands = [&](const ATile<KIND, QW> &t, int step, u4 (&av)[NM], uint32_t (&iwv)[NM / 2]) {
+    const bool live = 4 * step + kb < g.nchunks;      // false: a chunk past the end of K
     uint32_t s2[QW], off[QW];
 #pragma unroll
     for (int k = 0; k < QW; ++k) {
       s2[k] = off[k] = 0;
       if (INT4) {
         s2[k] = __builtin_amdgcn_perm(t.qp[k], t.qp[k], 0x01000100u);
+        if (!live) s2[k] = 0;
         off[k] = pk_add_f16(__builtin_amdgcn_perm(t.qp[k], t.qp[k], 0x03020302u), g.nib_magic);
       }
     }
+    if (N1) {
+      iwv[0] = spread_idx(t.iw[0] & 0xFFFFu, g.m8, g.m4, g.m2);
+      iwv[1] = spread_idx(t.iw[0] >> 16, g.m8, g.m4, g.m2);
+      iwv[NM / 2 - 2] = spread_idx(t.iw[1] & 0xFFFFu, g.m8, g.m4, g.m2);
+      iwv[NM / 2 - 1] = spread_idx(t.iw[1] >> 16, g.m8, g.m4, g.m2);
 #pragma unroll
-    for (int d = 0; d < 4; ++d) {
-      if (INT4) av[d] = dequant8_sm(t.nib[0][d], off[d * QW / 4], s2[d * QW / 4], g.nib_mask, magic);
-      else av[d] = t.nib[d];
+      for (int m = 0; m < NM; ++m) {
+        if constexpr (INT4) {
+          // slots 4 m .. 4 m + 3 = bytes 2 (m & 1), 2 (m & 1) + 1 of dword m >> 1; the two
+          // slots of a byte are dequantised as a pair, then split into {w, 0} registers
+          const uint32_t d = t.nib[0][(m >> 1) & 3];
+#pragma unroll
+          for (int p = 0; p < 2; ++p) {
+            const uint32_t t2 = __builtin_amdgcn_perm(d, d, 0x0c000c00u + (uint32_t)(2 * (m & 1) + p) * 0x00010001u);
+            const uint32_t pair = pk_mul_f16(pk_sub_f16(and_or(t2, g.nib_mask, magic), off[m * QW / 8]), s2[m * QW / 8]);
+            av[m][2 * p] = pair & 0xFFFFu;
+            av[m][2 * p + 1] = pair >> 16;
+          }
+        } else {
+          const uint32_t v0 = live ? t.nib[(m >> 1) & 3][2 * (m & 1)] : 0u;
+          const uint32_t v1 = live ? t.nib[(m >> 1) & 3][2 * (m & 1) + 1] : 0u;
+          av[m] = u4{v0 & 0xFFFFu, v0 >> 16, v1 & 0xFFFFu, v1 >> 16};
+        }
+      }
+    } else {
+      iwv[0] = t.iw[0];
+      iwv[NM / 2 - 1] = t.iw[1];
+#pragma unroll
+      for (int d = 0; d < NM; ++d) {
+        if constexpr (INT4) av[d] = dequant8_sm(t.nib[0][d & 3], off[(d & 3) * QW / 4], s2[(d & 3) * QW / 4], g.nib_mask, magic);
+        else av[d] = live ? t.nib[d & 3] : u4{0, 0, 0, 0};
+      }
     }
   };
-  auto mfma4 = [&](const u4 (&av)[4], const u2 iw, const u8v (&bx)[4], f4 &acc) {
+  auto mfma_step = [&](const u4 (&av)[NM], const uint32_t (&iwv)[NM / 2], const u8v (&bx)[NM], f4 &acc) {
 #pragma unroll
-    for (int d = 0; d < 4; ++d) {
-      const int iword = d < 2 ? (int)iw[0] : (int)iw[1];
-      if (d & 1)
-        acc = __builtin_amdgcn_smfmac_f32_16x16x64_f16(__builtin_bit_cast(h8, av[d]), __builtin_bit_cast(h16, bx[d]), acc, iword, 0, 1);
+    for (int m = 0; m < NM; ++m) {
+      const int iword = (int)iwv[m >> 1];
+      if (m & 1)
+        acc = __builtin_amdgcn_smfmac_f32_16x16x64_f16(__builtin_bit_cast(h8, av[m]), __builtin_bit_cast(h16, bx[m]), acc, iword, 0, 1);
       else
-        acc = __builtin_amdgcn_smfmac_f32_16x16x64_f16(__builtin_bit_cast(h8, av[d]), __builtin_bit_cast(h16, bx[d]), acc, iword, 0, 0);
+        acc = __builtin_amdgcn_smfmac_f32_16x16x64_f16(__builtin_bit_cast(h8, av[m]), __builtin_bit_cast(h16, bx[m]), acc, iword, 0, 0);
     }
   };
 
@@ -250,9 +327,10 @@ __global__ __launch_bounds__(64 * NWMAX) void k_sparse_smallm_ks(const uint32_t 
       const int step = p * nw + wave;
       const bool more = p + 1 < phases;
       constexpr int NA = NIT * (INT4 ? 3 : 5);         // loads of the A tiles of one phase (any QW)
-      u8v bx[4];
+      u8v bx[NM];
       ATile<KIND, QW> t[NIT];
       wait_vmem<0>();                                 // X and the A tiles of this phase have arrived
+      zero_tail(step);
       read_b(bx);
 #pragma unroll
       for (int it = 0; it < NIT; ++it) {
@@ -269,14 +347,16 @@ __global__ __launch_bounds__(64 * NWMAX) void k_sparse_smallm_ks(const uint32_t 
 #pragma unroll
           for (int it = 0; it < NIT; ++it) load_a(raw[it], it, step + nw);
         }
-        u4 held[NIT][4];
+        u4 held[NIT][NM];
+        uint32_t hiw[NIT][NM / 2];
 #pragma unroll
-        for (int it = 0; it < NIT; ++it) dequant(t[it], held[it]);
+        for (int it = 0; it < NIT; ++it) operands(t[it], step, held[it], hiw[it]);
 #pragma unroll
         for (int jj = 0; jj < NT; ++jj) {
           if (j0 + jj < ngroups) {                    // uniform
             if (jj > 0) {
               if (more) wait_vmem<NA>(); else wait_vmem<0>();
+              zero_tail(step);
               read_b(bx);
               wait_lds();
               if (jj + 1 < NT && j0 + jj + 1 < ngroups) dma_x(j0 + jj + 1, step);
@@ -284,7 +364,7 @@ __global__ __launch_bounds__(64 * NWMAX) void k_sparse_smallm_ks(const uint32_t 
             }
 #pragma unroll
             for (int it = 0; it < NIT; ++it)
-              if (it < nit) mfma4(held[it], t[it].iw, bx, acc[it][jj]);
+              if (it < nit) mfma_step(held[it], hiw[it], bx, acc[it][jj]);
           }
         }
       } else {
@@ -292,9 +372,10 @@ __global__ __launch_bounds__(64 * NWMAX) void k_sparse_smallm_ks(const uint32_t 
 #pragma unroll
         for (int it = 0; it < NIT; ++it) {
           if (it < nit) {
-            u4 av[4];
-            dequant(t[it], av);
-            mfma4(av, t[it].iw, bx, acc[it][0]);
+            u4 av[NM];
+            uint32_t iwv[NM / 2];
+            operands(t[it], step, av, iwv);
+            mfma_step(av, iwv, bx, acc[it][0]);
           }
           if (more) load_a(raw[it], it, step + nw);  // into the registers this tile has just left
         }
@@ -342,9 +423,12 @@ __global__ __launch_bounds__(64 * NWMAX) void k_sparse_smallm_ks(const uint32_t 
   }
 }
 
-// Shapes covered: 2:4, K a multiple of 256, INT4 groups of 32 << j.
+// Shapes covered: 2:4 with K a multiple of 64, 1:4 with K a multiple of 128; INT4 groups
+// of 32 << j.
 bool sparse_smallm_supported(const egt_2bitcsr &w) {
-  if (w.n_keep != 2 || w.cols % 256 != 0 || w.cols < 256) return false;
+  if (w.n_keep != 1 && w.n_keep != 2) return false;
+  const int chunk = w.n_keep == 1 ? 128 : 64;
+  if (w.cols % chunk != 0 || w.cols < chunk) return false;
   if (w.val_kind == EGT_VAL_INT4) {
     const int gm = w.group_size / 32;
     if (w.group_size % 32 != 0 || (gm & (gm - 1)) != 0) return false;
@@ -352,28 +436,33 @@ bool sparse_smallm_supported(const egt_2bitcsr &w) {
   return true;
 }
 
-template <int KIND, int NT, int NIT, int NWMAX, int QW = 1>
+template <int KIND, int NT, int NIT, int NWMAX, int QW, bool N1>
 static hipError_t go_ks(const egt_2bitcsr &w, const uint16_t *X, uint16_t *Y, const SmallMKsGeom &g, int nw,
                         int nblocks, hipStream_t stream) {
-  const size_t x_bytes = (size_t)nw * KS_REGION, p_bytes = (size_t)nw * NIT * NT * 1024;
+  const size_t region = N1 ? 16 * KS_TOKEN_N1 : 8 * KS_PAIR;
+  const size_t x_bytes = (size_t)nw * region, p_bytes = (size_t)nw * NIT * NT * 1024;
   const size_t lds = (x_bytes > p_bytes ? x_bytes : p_bytes) + 64 * NIT;   // + row-pointer flags
-  return launch(k_sparse_smallm_ks<KIND, NT, NIT, NWMAX, QW>, dim3(nblocks), dim3(64 * nw), lds, stream, w.row_ptr,
-                (const uint8_t *)w.values, (const uint8_t *)w.idx, (const uint8_t *)w.qparams,
+  return launch(k_sparse_smallm_ks<KIND, NT, NIT, NWMAX, QW, N1>, dim3(nblocks), dim3(64 * nw), lds, stream,
+                w.row_ptr, (const uint8_t *)w.values, (const uint8_t *)w.idx, (const uint8_t *)w.qparams,
                 (const __half *)X, (__half *)Y, g);
 }
 
 hipError_t launch_sparse_smallm(const egt_2bitcsr &w, const uint16_t *X, int64_t ldx, uint16_t *Y,
                                 int64_t ldy, int M, hipStream_t stream) {
   if (w.rows == 0) return hipSuccess;
-  const bool int4 = w.val_kind == EGT_VAL_INT4;
+  const bool int4 = w.val_kind == EGT_VAL_INT4, n1 = w.n_keep == 1;
+  const int chunk = n1 ? 128 : 64;
   SmallMKsGeom g;
   g.rows = w.rows; g.M = M;
-  g.nchunks = w.cols / 64;
-  g.nsteps = w.cols / 256;
+  g.nchunks = w.cols / chunk;
+  g.nsteps = (g.nchunks + 3) / 4;
+  g.kpieces = w.cols / 8;
   g.ntiles = (w.rows + 15) / 16;
   g.gshift = 0; g.groups_per_row = 0;
+  int qw = 1;                                         // {scale, zero} pairs per chunk
   if (int4) {
-    while ((64 << g.gshift) < w.group_size) ++g.gshift;
+    if (w.group_size < chunk) qw = chunk / w.group_size;
+    while ((chunk << g.gshift) < w.group_size) ++g.gshift;
     g.groups_per_row = w.cols / w.group_size;
   }
   g.ldx = ldx; g.ldy = ldy;
@@ -384,9 +473,11 @@ hipError_t launch_sparse_smallm(const egt_2bitcsr &w, const uint16_t *X, int64_t
   g.val_bytes = (uint32_t)vb; g.idx_bytes = (uint32_t)(chunks * 8);
   g.qp_bytes = (uint32_t)((uint64_t)w.rows * g.groups_per_row * 4); g.x_bytes = (uint32_t)xb;
   g.nib_mask = 0x00F0000Fu; g.nib_magic = 0x54006400u;
-  // One workgroup per compute unit while its row tiles fit the registers (NIT of them);
-  // up to 16 tokens with 16 waves of 128 registers, more with 8 waves of 256.
-  const bool wide = M > 16 || !int4;                  // 8 waves, two token groups per pass
+  g.m8 = 0x00FF00FFu; g.m4 = 0x0F0F0F0Fu; g.m2 = 0x33333333u;
+  // One workgroup per compute unit while its row tiles fit the registers (NIT of them).
+  // 2:4 INT4, up to 16 tokens: 16 waves of 128 registers; everything else 8 waves of 256
+  // (more than 16 tokens at 2:4: two token groups per pass).
+  const bool wide = n1 || M > 16 || !int4;
   const int nit_max = wide ? 4 : 3;
   int nwmax = wide ? 8 : 16, blocks_per_cu = 1;
   if (const char *e = getenv("EGT_SM_TUNE")) sscanf(e, "%d,%d", &nwmax, &blocks_per_cu);
@@ -396,22 +487,24 @@ hipError_t launch_sparse_smallm(const egt_2bitcsr &w, const uint16_t *X, int64_t
   if (nblocks * nit_max < g.ntiles) nblocks = (g.ntiles + nit_max - 1) / nit_max;
   if (nblocks > g.ntiles) nblocks = g.ntiles;
   const bool one = nblocks == g.ntiles;               // one row tile per workgroup
-  if (int4 && w.group_size == 32) {
-    if (!wide) return one ? go_ks<EGT_VAL_INT4, 1, 1, 16, 2>(w, X, Y, g, nw, nblocks, stream)
-                          : go_ks<EGT_VAL_INT4, 1, 3, 16, 2>(w, X, Y, g, nw, nblocks, stream);
-    return one ? go_ks<EGT_VAL_INT4, 2, 1, 8, 2>(w, X, Y, g, nw, nblocks, stream)
-               : go_ks<EGT_VAL_INT4, 2, 4, 8, 2>(w, X, Y, g, nw, nblocks, stream);
+#define EGT_KS(KIND, NT, NIT, NWMAX, QW, N1) go_ks<KIND, NT, NIT, NWMAX, QW, N1>(w, X, Y, g, nw, nblocks, stream)
+  if (n1) {
+    if (!int4) return one ? EGT_KS(EGT_VAL_FP16, 1, 1, 8, 1, true) : EGT_KS(EGT_VAL_FP16, 1, 4, 8, 1, true);
+    if (qw == 4) return one ? EGT_KS(EGT_VAL_INT4, 1, 1, 8, 4, true) : EGT_KS(EGT_VAL_INT4, 1, 4, 8, 4, true);
+    if (qw == 2) return one ? EGT_KS(EGT_VAL_INT4, 1, 1, 8, 2, true) : EGT_KS(EGT_VAL_INT4, 1, 4, 8, 2, true);
+    return one ? EGT_KS(EGT_VAL_INT4, 1, 1, 8, 1, true) : EGT_KS(EGT_VAL_INT4, 1, 4, 8, 1, true);
+  }
+  if (int4 && qw == 2) {
+    if (!wide) return one ? EGT_KS(EGT_VAL_INT4, 1, 1, 16, 2, false) : EGT_KS(EGT_VAL_INT4, 1, 3, 16, 2, false);
+    return one ? EGT_KS(EGT_VAL_INT4, 2, 1, 8, 2, false) : EGT_KS(EGT_VAL_INT4, 2, 4, 8, 2, false);
   }
   if (int4) {
-    if (!wide) return one ? go_ks<EGT_VAL_INT4, 1, 1, 16>(w, X, Y, g, nw, nblocks, stream)
-                          : go_ks<EGT_VAL_INT4, 1, 3, 16>(w, X, Y, g, nw, nblocks, stream);
-    return one ? go_ks<EGT_VAL_INT4, 2, 1, 8>(w, X, Y, g, nw, nblocks, stream)
-               : go_ks<EGT_VAL_INT4, 2, 4, 8>(w, X, Y, g, nw, nblocks, stream);
+    if (!wide) return one ? EGT_KS(EGT_VAL_INT4, 1, 1, 16, 1, false) : EGT_KS(EGT_VAL_INT4, 1, 3, 16, 1, false);
+    return one ? EGT_KS(EGT_VAL_INT4, 2, 1, 8, 1, false) : EGT_KS(EGT_VAL_INT4, 2, 4, 8, 1, false);
   }
-  if (M <= 16) return one ? go_ks<EGT_VAL_FP16, 1, 1, 8>(w, X, Y, g, nw, nblocks, stream)
-                          : go_ks<EGT_VAL_FP16, 1, 4, 8>(w, X, Y, g, nw, nblocks, stream);
-  return one ? go_ks<EGT_VAL_FP16, 2, 1, 8>(w, X, Y, g, nw, nblocks, stream)
-             : go_ks<EGT_VAL_FP16, 2, 4, 8>(w, X, Y, g, nw, nblocks, stream);
+  if (M <= 16) return one ? EGT_KS(EGT_VAL_FP16, 1, 1, 8, 1, false) : EGT_KS(EGT_VAL_FP16, 1, 4, 8, 1, false);
+  return one ? EGT_KS(EGT_VAL_FP16, 2, 1, 8, 1, false) : EGT_KS(EGT_VAL_FP16, 2, 4, 8, 1, false);
+#undef EGT_KS
 }
 
 }  // namespace egt

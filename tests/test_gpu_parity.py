@@ -181,23 +181,34 @@ def test_smallm_small_shapes(M):
         G.assert_close(Y, Y_ref, A_ref, f"smallm {rows}x{cols} M={M}")
 
 
-@pytest.mark.parametrize("rows,cols,g,kind,M", [
-    (4200, 256, 128, 0, 7),      # one K-step (one wave), several row tiles per workgroup, ragged last tile
-    (5000, 768, 64, 0, 16),      # three waves, groups of 64
-    (5000, 768, 256, 0, 40),     # two token groups per pass, second pass half empty
-    (4130, 1280, 128, 0, 17),    # five waves, M just past one token group
-    (300, 8704, 128, 0, 32),     # 34 K-steps: phases with idle waves at the end
-    (300, 8704, 128, 0, 9),
-    (4100, 512, 0, 1, 5),        # FP16 values
-    (4100, 512, 0, 1, 48),
-    (13000, 256, 128, 0, 3),     # more row tiles than three per workgroup on 256 workgroups
-    (4200, 512, 32, 0, 6),       # groups of 32 columns: two {scale, zero} pairs per chunk
-    (4200, 512, 32, 0, 30),
-    (50, 8704, 32, 0, 16),
+@pytest.mark.parametrize("rows,cols,n,g,kind,M", [
+    (4200, 256, 2, 128, 0, 7),      # one K-step (one wave), several row tiles per workgroup, ragged last tile
+    (5000, 768, 2, 64, 0, 16),      # three waves, groups of 64
+    (5000, 768, 2, 256, 0, 40),     # two token groups per pass, second pass half empty
+    (4130, 1280, 2, 128, 0, 17),    # five waves, M just past one token group
+    (300, 8704, 2, 128, 0, 32),     # 34 K-steps: phases with idle waves at the end
+    (300, 8704, 2, 128, 0, 9),
+    (4100, 512, 2, 0, 1, 5),        # FP16 values
+    (4100, 512, 2, 0, 1, 48),
+    (13000, 256, 2, 128, 0, 3),     # more row tiles than three per workgroup on 256 workgroups
+    (4200, 512, 2, 32, 0, 6),       # groups of 32 columns: two {scale, zero} pairs per chunk
+    (4200, 512, 2, 32, 0, 30),
+    (50, 8704, 2, 32, 0, 16),
+    (70, 4160, 2, 64, 0, 5),        # K not a multiple of the K-step: a partly filled last step
+    (70, 4160, 2, 64, 0, 20),
+    (40, 320, 2, 0, 1, 33),         # the same with FP16 values
+    (4200, 1024, 1, 128, 0, 6),     # 1:4: {value, 0} pairs, eight instructions per step
+    (300, 4096, 1, 128, 0, 16),
+    (300, 4096, 1, 256, 0, 40),     # 1:4 runs its token groups one after the other
+    (60, 11008, 1, 128, 0, 4),      # 86 chunks: a half-filled last step
+    (60, 11008, 1, 64, 0, 16),      # 1:4 with two and four {scale, zero} pairs per chunk
+    (60, 2176, 1, 32, 0, 7),
+    (4100, 640, 1, 0, 1, 12),       # 1:4, FP16 values, partly filled last step
+    (90, 4096, 1, 0, 1, 64),
 ])
-def test_smallm_tile_and_wave_shapes(rows, cols, g, kind, M):
-    print(f"case smallm shapes {rows}x{cols} g={g} kind={kind} M={M}", flush=True)
-    p, o = _small_case(rows, cols, 2, g, kind, seed=1300 + M + rows)
+def test_smallm_tile_and_wave_shapes(rows, cols, n, g, kind, M):
+    print(f"case smallm shapes {rows}x{cols} n={n} g={g} kind={kind} M={M}", flush=True)
+    p, o = _small_case(rows, cols, n, g, kind, seed=1300 + M + rows)
     X = synth.activation_rows(M, cols, 1300 + M)
     Y_ref, A_ref = O.gemm_smallm(o, X)
     for pad in (0, 6, 7):        # 8-byte stores of four rows, the 2-byte fallback, odd strides
