@@ -66,7 +66,12 @@ struct M1Geom {
 // XP = 16 B pieces of x each thread stages (ceil(pieces / block size)).
 // QW = {scale, zero} pairs per chunk: 1 for groups of 64 columns and more, 2 for groups
 // of 32 (dwords 0, 1 of a chunk then belong to the first group, 2, 3 to the second).
-template <int KIND, int TPI, int XP, int QW>
+// LIN (FP16 values, one row per tile): every load instruction of a wave reads one
+// contiguous kilobyte of values - instruction k takes the 16-byte piece 64 k + lane of the
+// tile (8 slots = 16 dense columns = one idx word) - instead of each lane reading its own
+// chunk of 64 B.  Lane (i, kb) then multiplies pieces i + 16 kb + 64 k, k = 0..3, and
+// column n of B carries the activations of the pieces n + 16 kb + 64 k.
+template <int KIND, int TPI, int XP, int QW, bool LIN>
 __device__ __forceinline__ void k_sparse_m1_body(const uint32_t *__restrict__ row_ptr, const uint8_t *__restrict__ values,
     const uint8_t *__restrict__ idx, const uint8_t *__restrict__ qparams, const __half *__restrict__ x,
     __half *__restrict__ y, const M1Geom &g) {
@@ -97,6 +102,7 @@ __device__ __forceinline__ void k_sparse_m1_body(const uint32_t *__restrict__ ro
     xp[j] = *(const u4 *)(x + 8 * min(pi, npieces - 1));
   }
 
+  constexpr int XSH = LIN ? 4 : 5;                    // x in LDS: one 16 B pad per 2^XSH pieces
   const int tile0 = (blockIdx.x * wpp + wslot) * TPI;
   // The lanes that will store read their row pointers before the tiles are requested (loads
   // return in order, so the small ones go first and never make the wave wait for a tile):
@@ -119,10 +125,21 @@ __device__ __forceinline__ void k_sparse_m1_body(const uint32_t *__restrict__ ro
   // ---- issue every load of the wave's TPI tiles
   u4 nib[TPI][KIND == EGT_VAL_INT4 ? 1 : 4];
   u2 iw[TPI];
+  uint32_t iwl[LIN ? TPI : 1][4];                     // LIN: the idx word of each piece
   uint32_t qp[TPI][QW];
 #pragma unroll
   for (int t = 0; t < TPI; ++t) {
     const int tr = min(tile0 + t, g.ntiles - 1);      // uniform
+    if constexpr (LIN) {
+#pragma unroll
+      for (int k = 0; k < 4; ++k) {
+        const uint32_t piece = (uint32_t)min(256 * phase + 64 * k + lane, 4 * g.nchunks - 1);   // inside the row (clamped)
+        const uint32_t gp = (uint32_t)tr * (uint32_t)(4 * g.nchunks) + piece;
+        nib[t][k] = ld_stream<u4>(values + 16ull * gp);
+        iwl[t][k] = ld_stream<uint16_t>(idx + 2ull * gp);
+      }
+      continue;
+    }
     uint32_t chunk;
     if (multirow) chunk = min((uint32_t)tr * 64u + (uint32_t)cit, g.last_chunk);
     else chunk = (uint32_t)tr * (uint32_t)g.nchunks + (uint32_t)c_ld;
@@ -152,14 +169,27 @@ __device__ __forceinline__ void k_sparse_m1_body(const uint32_t *__restrict__ ro
     if (pi < lds_pieces) {
       u4 v = xp[j];
       if (pi >= npieces) v = u4{0, 0, 0, 0};
-      *(u4 *)(xs + 16 * pi + 16 * (pi >> 5)) = v;
+      *(u4 *)(xs + 16 * pi + 16 * (pi >> XSH)) = v;
     }
   }
   __syncthreads();
   // B operand: column n = lane & 15 holds the activations of chunks 4n .. 4n+3;
   // lane (n, b) supplies k-octets b (first 8 halfs) and 4 + b (last 8 halfs)
   u8v bx[4];
-  {
+  if constexpr (LIN) {
+    const int n = lane & 15, b = lane >> 4;
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+      const int kba = 2 * h + (b >> 1), sub = b & 1;  // the A lane (n, kba) this octet multiplies
+#pragma unroll
+      for (int k = 0; k < 4; ++k) {
+        const int pi = 2 * (256 * phase + 64 * k + n + 16 * kba) + sub;
+        const u4 v = *(const u4 *)(xs + 16 * pi + 16 * (pi >> XSH));
+#pragma unroll
+        for (int j = 0; j < 4; ++j) bx[k][4 * h + j] = v[j];
+      }
+    }
+  } else {
     const int n = lane & 15, b = lane >> 4;
 #pragma unroll
     for (int h = 0; h < 2; ++h) {
@@ -196,6 +226,10 @@ __device__ __forceinline__ void k_sparse_m1_body(const uint32_t *__restrict__ ro
       u4 a;
       if (KIND == EGT_VAL_INT4) a = dequant8(nib[t][0][d], off[d * QW / 4], s2[d * QW / 4], g.nib_mask, magic);
       else a = nib[t][d];
+      if constexpr (LIN) {
+        acc = __builtin_amdgcn_smfmac_f32_16x16x64_f16(__builtin_bit_cast(h8, a), __builtin_bit_cast(h16, bx[d]), acc, (int)iwl[t][d], 0, 0);
+        continue;
+      }
       const int iword = d < 2 ? (int)iw[t][0] : (int)iw[t][1];
       if (d & 1)
         acc = __builtin_amdgcn_smfmac_f32_16x16x64_f16(__builtin_bit_cast(h8, a), __builtin_bit_cast(h16, bx[d]), acc, iword, 0, 1);
@@ -246,20 +280,20 @@ __device__ __forceinline__ void k_sparse_m1_body(const uint32_t *__restrict__ ro
 }
 
 // One matrix per launch: the pointers are plain kernel arguments.
-template <int KIND, int TPI, int XP, int QW>
+template <int KIND, int TPI, int XP, int QW, bool LIN>
 __global__ __launch_bounds__(1024) void k_sparse_m1(const uint32_t *__restrict__ row_ptr,
                                                      const uint8_t *__restrict__ values,
                                                      const uint8_t *__restrict__ idx,
                                                      const uint8_t *__restrict__ qparams,
                                                      const __half *__restrict__ x,
                                                      __half *__restrict__ y, const M1Geom g) {
-  k_sparse_m1_body<KIND, TPI, XP, QW>(row_ptr, values, idx, qparams, x, y, g);
+  k_sparse_m1_body<KIND, TPI, XP, QW, LIN>(row_ptr, values, idx, qparams, x, y, g);
 }
 
 // Several identically shaped matrices per launch, selected by blockIdx.y.
-template <int KIND, int TPI, int XP, int QW>
+template <int KIND, int TPI, int XP, int QW, bool LIN>
 __global__ __launch_bounds__(1024) void k_sparse_m1_batch(const GemvBatch b, const M1Geom g) {
-  k_sparse_m1_body<KIND, TPI, XP, QW>(pick4(b.row_ptr, blockIdx.y), pick4(b.values, blockIdx.y),
+  k_sparse_m1_body<KIND, TPI, XP, QW, LIN>(pick4(b.row_ptr, blockIdx.y), pick4(b.values, blockIdx.y),
                                   pick4(b.idx, blockIdx.y), pick4(b.qparams, blockIdx.y),
                                   pick4(b.x, blockIdx.y), pick4(b.y, blockIdx.y), g);
 }
@@ -317,15 +351,19 @@ hipError_t launch_sparse_m1_batch(const egt_2bitcsr *ws, const uint16_t *const *
   const int tiles_per_block = wpp * tpi;
   const dim3 grid((g.ntiles + tiles_per_block - 1) / tiles_per_block, count), block(64 * nwaves);
   const int lds_pieces = multirow ? g.nchunks * 8 : g.phases * 512;
-  g.part_offset = 16 * lds_pieces + 16 * ((lds_pieces + 31) >> 5);
+  const bool lin = w.val_kind == EGT_VAL_FP16 && !multirow && getenv("EGT_M1_NOLIN") == nullptr;
+  g.part_offset = lin ? 16 * lds_pieces + 16 * ((lds_pieces + 15) >> 4) : 16 * lds_pieces + 16 * ((lds_pieces + 31) >> 5);
   const size_t lds = g.part_offset + (g.phases > 1 ? sizeof(float) * g.phases * tiles_per_block : 0);
   const int xp = (lds_pieces + 64 * nwaves - 1) / (64 * nwaves);
   if (xp > 4) return hipErrorInvalidConfiguration;
-#define EGT_GO4(KIND, TPI, XP, QW)                                                              \
-  (count > 1 ? launch(k_sparse_m1_batch<KIND, TPI, XP, QW>, grid, block, lds, stream, b, g)         \
-             : launch(k_sparse_m1<KIND, TPI, XP, QW>, grid, block, lds, stream, b.row_ptr[0],      \
+#define EGT_GO5(KIND, TPI, XP, QW, LIN)                                                         \
+  (count > 1 ? launch(k_sparse_m1_batch<KIND, TPI, XP, QW, LIN>, grid, block, lds, stream, b, g)    \
+             : launch(k_sparse_m1<KIND, TPI, XP, QW, LIN>, grid, block, lds, stream, b.row_ptr[0], \
                       b.values[0], b.idx[0], b.qparams[0], b.x[0], b.y[0], g))
+#define EGT_GO4(KIND, TPI, XP, QW) EGT_GO5(KIND, TPI, XP, QW, false)
 #define EGT_GO3(KIND, TPI, XP) EGT_GO4(KIND, TPI, XP, 1)
+#define EGT_GOL(TPI) (xp <= 1 ? EGT_GO5(EGT_VAL_FP16, TPI, 1, 1, true) : xp == 2 ? EGT_GO5(EGT_VAL_FP16, TPI, 2, 1, true) \
+                                                                                  : EGT_GO5(EGT_VAL_FP16, TPI, 4, 1, true))
 #define EGT_GO(KIND, TPI)                                                                       \
   (xp <= 1 ? EGT_GO3(KIND, TPI, 1) : xp == 2 ? EGT_GO3(KIND, TPI, 2) : EGT_GO3(KIND, TPI, 4))
   if (g32)                                             // groups of 32: one launch shape
@@ -339,6 +377,13 @@ hipError_t launch_sparse_m1_batch(const egt_2bitcsr *ws, const uint16_t *const *
       default: return EGT_GO(EGT_VAL_INT4, 4);
     }
   }
+  if (lin) {
+    switch (tpi) {
+      case 1: return EGT_GOL(1);
+      case 2: return EGT_GOL(2);
+      default: return EGT_GOL(4);
+    }
+  }
   switch (tpi) {
     case 1: return EGT_GO(EGT_VAL_FP16, 1);
     case 2: return EGT_GO(EGT_VAL_FP16, 2);
@@ -347,6 +392,8 @@ hipError_t launch_sparse_m1_batch(const egt_2bitcsr *ws, const uint16_t *const *
 #undef EGT_GO
 #undef EGT_GO3
 #undef EGT_GO4
+#undef EGT_GO5
+#undef EGT_GOL
 }
 
 hipError_t launch_sparse_m1(const egt_2bitcsr &w, const uint16_t *x, uint16_t *y, hipStream_t stream) {
