@@ -201,12 +201,13 @@ def main():
             p5 = B.pack_2bitcsr(w5, B.prune_n4(w5, 2), 2, 128, B.VAL_INT4)
             c5 = max(2, -(-2 * LLC_BYTES // p5.nbytes()))
             pk5 = [p5.to(dev) for _ in range(c5)]
-            for M in sweep_m:
+            for pass_no, M in enumerate((sweep_m[0],) + sweep_m):   # the first pass only settles clocks and caches
                 X = torch.from_numpy(synth.activation_rows(M, k5, 5).view(np.int16)).to(dev).view(torch.float16)
                 Y = torch.empty((M, r5), dtype=torch.float16, device=dev)
                 f5 = [B.prepared_sparse_gemm_smallm(pk5[i], X, Y) for i in range(c5)]
-                t5, _ = time_loop(torch, lambda i: f5[i % c5](), 300, 30)
-                layer_us[M] += reps * t5 * 1e6
+                t5, _ = time_loop(torch, lambda i: f5[i % c5](), 600, 60)
+                if pass_no > 0:
+                    layer_us[M] += reps * t5 * 1e6
             del pk5
         fit_a, fit_b = B.fit_verify_cost(list(sweep_m[1:]), [layer_us[m] for m in sweep_m[1:]])
         cand = [64, 24, 9, 4, 2, 1]                      # candidates left per trie depth (wide top, narrow bottom)

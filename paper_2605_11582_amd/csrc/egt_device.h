@@ -49,6 +49,11 @@ bool int4_m1_supported(int cols, int group);
 hipError_t launch_int4_m1(const uint8_t *q, const uint16_t *qparams, int rows, int cols, int group,
                           const uint16_t *x, uint16_t *y, hipStream_t stream);
 
+// 2:4 INT4, 2..4 activation rows on the M = 1 kernel's row-per-wave mapping
+bool sparse_m1_tokens_supported(const egt_2bitcsr &w, int M);
+hipError_t launch_sparse_m1_tokens(const egt_2bitcsr &w, const uint16_t *X, int64_t ldx, uint16_t *Y,
+                                   int64_t ldy, int M, hipStream_t stream);
+
 // batched forms: `count` identically shaped matrices in one launch (count <= 4)
 hipError_t launch_sparse_m1_batch(const egt_2bitcsr *ws, const uint16_t *const *xs, uint16_t *const *ys,
                                   int count, hipStream_t stream);

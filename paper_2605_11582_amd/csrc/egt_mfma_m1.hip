@@ -58,6 +58,9 @@ struct M1Geom {
   int groups_per_row;  // cols / group
   uint32_t last_chunk; // rows * nchunks - 1
   int part_offset;     // byte offset of the per-phase partial sums in LDS
+  int xtok;            // LDS bytes of the staged activations of one token
+  int M;               // tokens (activation rows): 1, or up to MT in the several-token form
+  int64_t ldx, ldy;    // row strides of X and Y in elements (several-token form)
   uint32_t nib_mask;   // 0x00F0000F: low nibble of the low half, high nibble of the high half
   uint32_t nib_magic;  // 0x54006400: FP16 {1024.0, 64.0}
 };
@@ -71,7 +74,11 @@ struct M1Geom {
 // tile (8 slots = 16 dense columns = one idx word) - instead of each lane reading its own
 // chunk of 64 B.  Lane (i, kb) then multiplies pieces i + 16 kb + 64 k, k = 0..3, and
 // column n of B carries the activations of the pieces n + 16 kb + 64 k.
-template <int KIND, int TPI, int XP, int QW, bool LIN>
+// MT > 1: the several-token form (2 <= M <= MT activation rows).  The dequantised A
+// registers of a tile feed MT instructions, one per token, each with the B operand of
+// its own token (32 registers per token, loaded once per wave); everything about the
+// weights - the loads, the dequantisation - is done once, as for one token.
+template <int KIND, int TPI, int XP, int QW, bool LIN, int MT>
 __device__ __forceinline__ void k_sparse_m1_body(const uint32_t *__restrict__ row_ptr, const uint8_t *__restrict__ values,
     const uint8_t *__restrict__ idx, const uint8_t *__restrict__ qparams, const __half *__restrict__ x,
     __half *__restrict__ y, const M1Geom &g) {
@@ -95,11 +102,15 @@ __device__ __forceinline__ void k_sparse_m1_body(const uint32_t *__restrict__ ro
   //      requested, so that it is the first data to come back
   const int npieces = g.nchunks * 8;                   // 8 halfs per piece
   const int lds_pieces = multirow ? npieces : g.phases * 512;
-  u4 xp[XP];
+  u4 xp[MT][XP];
 #pragma unroll
-  for (int j = 0; j < XP; ++j) {
-    const int pi = threadIdx.x + j * blockDim.x;
-    xp[j] = *(const u4 *)(x + 8 * min(pi, npieces - 1));
+  for (int m = 0; m < MT; ++m) {
+    const __half *xm = MT == 1 ? x : x + (int64_t)min(m, g.M - 1) * g.ldx;   // a token past M repeats the last one
+#pragma unroll
+    for (int j = 0; j < XP; ++j) {
+      const int pi = threadIdx.x + j * blockDim.x;
+      xp[m][j] = *(const u4 *)(xm + 8 * min(pi, npieces - 1));
+    }
   }
 
   constexpr int XSH = LIN ? 4 : 5;                    // x in LDS: one 16 B pad per 2^XSH pieces
@@ -164,18 +175,21 @@ __device__ __forceinline__ void k_sparse_m1_body(const uint32_t *__restrict__ ro
   //      every 512 B, so that the 16-lane reads below, whose addresses are 512 B
   //      apart, fall into different banks.  Pieces past the end of x are zero.
 #pragma unroll
-  for (int j = 0; j < XP; ++j) {
-    const int pi = threadIdx.x + j * blockDim.x;
-    if (pi < lds_pieces) {
-      u4 v = xp[j];
-      if (pi >= npieces) v = u4{0, 0, 0, 0};
-      *(u4 *)(xs + 16 * pi + 16 * (pi >> XSH)) = v;
+  for (int m = 0; m < MT; ++m) {
+#pragma unroll
+    for (int j = 0; j < XP; ++j) {
+      const int pi = threadIdx.x + j * blockDim.x;
+      if (pi < lds_pieces) {
+        u4 v = xp[m][j];
+        if (pi >= npieces) v = u4{0, 0, 0, 0};
+        *(u4 *)(xs + m * g.xtok + 16 * pi + 16 * (pi >> XSH)) = v;
+      }
     }
   }
   __syncthreads();
   // B operand: column n = lane & 15 holds the activations of chunks 4n .. 4n+3;
   // lane (n, b) supplies k-octets b (first 8 halfs) and 4 + b (last 8 halfs)
-  u8v bx[4];
+  u8v bx[MT][4];
   if constexpr (LIN) {
     const int n = lane & 15, b = lane >> 4;
 #pragma unroll
@@ -186,7 +200,7 @@ __device__ __forceinline__ void k_sparse_m1_body(const uint32_t *__restrict__ ro
         const int pi = 2 * (256 * phase + 64 * k + n + 16 * kba) + sub;
         const u4 v = *(const u4 *)(xs + 16 * pi + 16 * (pi >> XSH));
 #pragma unroll
-        for (int j = 0; j < 4; ++j) bx[k][4 * h + j] = v[j];
+        for (int j = 0; j < 4; ++j) bx[0][k][4 * h + j] = v[j];
       }
     }
   } else {
@@ -199,19 +213,24 @@ __device__ __forceinline__ void k_sparse_m1_body(const uint32_t *__restrict__ ro
 #pragma unroll
       for (int d = 0; d < 4; ++d) {
         const int pi = 8 * cb + 2 * d + sub;
-        const u4 v = *(const u4 *)(xs + 16 * pi + 16 * (pi >> 5));
 #pragma unroll
-        for (int k = 0; k < 4; ++k) bx[d][4 * h + k] = v[k];
+        for (int m = 0; m < MT; ++m) {
+          const u4 v = *(const u4 *)(xs + m * g.xtok + 16 * pi + 16 * (pi >> 5));
+#pragma unroll
+          for (int k = 0; k < 4; ++k) bx[m][d][4 * h + k] = v[k];
+        }
       }
     }
   }
 
   // ---- consume
   const uint32_t magic = in_vgpr(g.nib_magic);
-  float s[TPI];
+  float s[TPI][MT];
 #pragma unroll
   for (int t = 0; t < TPI; ++t) {
-    f4 acc = {0.f, 0.f, 0.f, 0.f};
+    f4 acc[MT];
+#pragma unroll
+    for (int m = 0; m < MT; ++m) acc[m] = f4{0.f, 0.f, 0.f, 0.f};
     uint32_t s2[QW], off[QW];
 #pragma unroll
     for (int k = 0; k < QW; ++k) {
@@ -227,53 +246,62 @@ __device__ __forceinline__ void k_sparse_m1_body(const uint32_t *__restrict__ ro
       if (KIND == EGT_VAL_INT4) a = dequant8(nib[t][0][d], off[d * QW / 4], s2[d * QW / 4], g.nib_mask, magic);
       else a = nib[t][d];
       if constexpr (LIN) {
-        acc = __builtin_amdgcn_smfmac_f32_16x16x64_f16(__builtin_bit_cast(h8, a), __builtin_bit_cast(h16, bx[d]), acc, (int)iwl[t][d], 0, 0);
+        acc[0] = __builtin_amdgcn_smfmac_f32_16x16x64_f16(__builtin_bit_cast(h8, a), __builtin_bit_cast(h16, bx[0][d]), acc[0], (int)iwl[t][d], 0, 0);
         continue;
       }
       const int iword = d < 2 ? (int)iw[t][0] : (int)iw[t][1];
-      if (d & 1)
-        acc = __builtin_amdgcn_smfmac_f32_16x16x64_f16(__builtin_bit_cast(h8, a), __builtin_bit_cast(h16, bx[d]), acc, iword, 0, 1);
-      else
-        acc = __builtin_amdgcn_smfmac_f32_16x16x64_f16(__builtin_bit_cast(h8, a), __builtin_bit_cast(h16, bx[d]), acc, iword, 0, 0);
+#pragma unroll
+      for (int m = 0; m < MT; ++m) {
+        if (d & 1)
+          acc[m] = __builtin_amdgcn_smfmac_f32_16x16x64_f16(__builtin_bit_cast(h8, a), __builtin_bit_cast(h16, bx[m][d]), acc[m], iword, 0, 1);
+        else
+          acc[m] = __builtin_amdgcn_smfmac_f32_16x16x64_f16(__builtin_bit_cast(h8, a), __builtin_bit_cast(h16, bx[m][d]), acc[m], iword, 0, 0);
+      }
     }
     // D[q][q] sits in lane q + 16 (q / 4), register q % 4: lane 20 kb collects the
     // four diagonals of quads 4 kb .. 4 kb + 3 from its three right neighbours
-    s[t] = acc[0] + row_shl<1>(acc[1]) + row_shl<2>(acc[2]) + row_shl<3>(acc[3]);
+#pragma unroll
+    for (int m = 0; m < MT; ++m)
+      s[t][m] = acc[m][0] + row_shl<1>(acc[m][1]) + row_shl<2>(acc[m][2]) + row_shl<3>(acc[m][3]);
   }
   // ---- lane j < 16 fetches tile (j >> 2), quad group (j & 3); then sum the groups of a row
   const int src_lane = 20 * (lane & 3);
 #pragma unroll
-  for (int bt = 0; bt < NB; ++bt) {
-    float v = 0.f;
+  for (int m = 0; m < MT; ++m) {
 #pragma unroll
-    for (int k = 0; k < 4; ++k) {
-      if (4 * bt + k < TPI) {
-        const float gk = __shfl(s[4 * bt + k], src_lane, 64);
-        v = ((lane >> 2) & 3) == k ? gk : v;
+    for (int bt = 0; bt < NB; ++bt) {
+      float v = 0.f;
+#pragma unroll
+      for (int k = 0; k < 4; ++k) {
+        if (4 * bt + k < TPI) {
+          const float gk = __shfl(s[4 * bt + k][m], src_lane, 64);
+          v = ((lane >> 2) & 3) == k ? gk : v;
+        }
       }
-    }
-    if (sum_steps >= 1) v += quad_xor1(v);
-    if (sum_steps >= 2) v += quad_xor2(v);
-    if (st[bt]) {
-      const int r = rrow[bt];
-      if (g.phases == 1) {
-        const bool ok = rp[bt] == (uint32_t)r * (uint32_t)(g.nchunks * 32);
-        y[r] = ok ? __float2half(v) : __ushort_as_half((uint16_t)0x7E00);
-      } else {
-        part[phase * (wpp * TPI) + wslot * TPI + 4 * bt + ((lane >> 2) & 3)] = v;
+      if (sum_steps >= 1) v += quad_xor1(v);
+      if (sum_steps >= 2) v += quad_xor2(v);
+      if (st[bt] && (MT == 1 || m < g.M)) {
+        const int r = rrow[bt];
+        if (g.phases == 1) {
+          const bool ok = rp[bt] == (uint32_t)r * (uint32_t)(g.nchunks * 32);
+          y[(int64_t)m * g.ldy + r] = ok ? __float2half(v) : __ushort_as_half((uint16_t)0x7E00);
+        } else {
+          part[(phase * (wpp * TPI) + wslot * TPI + 4 * bt + ((lane >> 2) & 3)) * MT + m] = v;
+        }
       }
     }
   }
   if (g.phases > 1) {
     __syncthreads();
     const int per = wpp * TPI;                        // rows handled by this block
-    for (int j = threadIdx.x; j < per; j += blockDim.x) {
-      const int r = blockIdx.x * per + j;
-      if (r < g.rows) {
+    for (int j = threadIdx.x; j < per * MT; j += blockDim.x) {
+      const int jr = j / MT, m = j - jr * MT;
+      const int r = blockIdx.x * per + jr;
+      if (r < g.rows && (MT == 1 || m < g.M)) {
         float v = 0.f;
-        for (int p = 0; p < g.phases; ++p) v += part[p * per + j];
+        for (int p = 0; p < g.phases; ++p) v += part[(p * per + jr) * MT + m];
         const bool ok = row_ptr[r] == (uint32_t)r * (uint32_t)(g.nchunks * 32);
-        y[r] = ok ? __float2half(v) : __ushort_as_half((uint16_t)0x7E00);
+        y[(int64_t)m * g.ldy + r] = ok ? __float2half(v) : __ushort_as_half((uint16_t)0x7E00);
       }
     }
   }
@@ -287,13 +315,24 @@ __global__ __launch_bounds__(1024) void k_sparse_m1(const uint32_t *__restrict__
                                                      const uint8_t *__restrict__ qparams,
                                                      const __half *__restrict__ x,
                                                      __half *__restrict__ y, const M1Geom g) {
-  k_sparse_m1_body<KIND, TPI, XP, QW, LIN>(row_ptr, values, idx, qparams, x, y, g);
+  k_sparse_m1_body<KIND, TPI, XP, QW, LIN, 1>(row_ptr, values, idx, qparams, x, y, g);
+}
+
+// Several tokens (2 <= M <= MT), one matrix.
+template <int TPI, int XP, int MT>
+__global__ __launch_bounds__(MT > 2 ? 512 : 1024) void k_sparse_m1_tokens(const uint32_t *__restrict__ row_ptr,
+                                                                           const uint8_t *__restrict__ values,
+                                                                           const uint8_t *__restrict__ idx,
+                                                                           const uint8_t *__restrict__ qparams,
+                                                                           const __half *__restrict__ x,
+                                                                           __half *__restrict__ y, const M1Geom g) {
+  k_sparse_m1_body<EGT_VAL_INT4, TPI, XP, 1, false, MT>(row_ptr, values, idx, qparams, x, y, g);
 }
 
 // Several identically shaped matrices per launch, selected by blockIdx.y.
 template <int KIND, int TPI, int XP, int QW, bool LIN>
 __global__ __launch_bounds__(1024) void k_sparse_m1_batch(const GemvBatch b, const M1Geom g) {
-  k_sparse_m1_body<KIND, TPI, XP, QW, LIN>(pick4(b.row_ptr, blockIdx.y), pick4(b.values, blockIdx.y),
+  k_sparse_m1_body<KIND, TPI, XP, QW, LIN, 1>(pick4(b.row_ptr, blockIdx.y), pick4(b.values, blockIdx.y),
                                   pick4(b.idx, blockIdx.y), pick4(b.qparams, blockIdx.y),
                                   pick4(b.x, blockIdx.y), pick4(b.y, blockIdx.y), g);
 }
@@ -353,6 +392,7 @@ hipError_t launch_sparse_m1_batch(const egt_2bitcsr *ws, const uint16_t *const *
   const int lds_pieces = multirow ? g.nchunks * 8 : g.phases * 512;
   const bool lin = w.val_kind == EGT_VAL_FP16 && !multirow && getenv("EGT_M1_NOLIN") == nullptr;
   g.part_offset = lin ? 16 * lds_pieces + 16 * ((lds_pieces + 15) >> 4) : 16 * lds_pieces + 16 * ((lds_pieces + 31) >> 5);
+  g.xtok = g.part_offset; g.M = 1; g.ldx = 0; g.ldy = 0;
   const size_t lds = g.part_offset + (g.phases > 1 ? sizeof(float) * g.phases * tiles_per_block : 0);
   const int xp = (lds_pieces + 64 * nwaves - 1) / (64 * nwaves);
   if (xp > 4) return hipErrorInvalidConfiguration;
@@ -394,6 +434,62 @@ hipError_t launch_sparse_m1_batch(const egt_2bitcsr *ws, const uint16_t *const *
 #undef EGT_GO4
 #undef EGT_GO5
 #undef EGT_GOL
+}
+
+// Several-token form: 2:4 INT4, groups of 64 << j, M = 2..4.  Used where it is the faster
+// one: a row is one tile (K = 4096; with more tiles per row the K-split kernel wins), and for
+// three or four tokens (about 220 registers, two waves per SIMD) all workgroups must be
+// resident at once (at most 8192 rows).
+bool sparse_m1_tokens_supported(const egt_2bitcsr &w, int M) {
+  if (M < 2 || M > 4 || w.n_keep != 2 || w.val_kind != EGT_VAL_INT4) return false;
+  if (w.cols != 4096) return false;
+  if (M > 2 && w.rows > 8192) return false;
+  const int gm = w.group_size / 64;
+  return w.group_size % 64 == 0 && (gm & (gm - 1)) == 0;
+}
+
+hipError_t launch_sparse_m1_tokens(const egt_2bitcsr &w, const uint16_t *X, int64_t ldx, uint16_t *Y,
+                                   int64_t ldy, int M, hipStream_t stream) {
+  if (w.rows == 0) return hipSuccess;
+  M1Geom g;
+  g.rows = w.rows;
+  g.nchunks = w.cols / 64;
+  g.mr_shift = -1;
+  g.phases = (g.nchunks + 63) / 64;
+  g.ntiles = w.rows;
+  g.gshift = 0;
+  while ((64 << g.gshift) < w.group_size) ++g.gshift;
+  g.groups_per_row = w.cols / w.group_size;
+  g.last_chunk = (uint32_t)w.rows * (uint32_t)g.nchunks - 1u;
+  g.nib_mask = 0x00F0000Fu;
+  g.nib_magic = 0x54006400u;
+  g.M = M; g.ldx = ldx; g.ldy = ldy;
+  const int mt = M == 2 ? 2 : 4;
+  // four tokens take about 200 registers: two waves per SIMD, workgroups of at most 8 waves
+  int tpi = 4, wpp = g.phases == 1 ? 4 : 2;
+  if (const char *e = getenv("EGT_M1T_TUNE")) sscanf(e, "%d,%d", &tpi, &wpp);
+  if (wpp < 1) wpp = 1;
+  const int max_waves = mt > 2 ? 8 : 16;
+  if (wpp * g.phases > max_waves) wpp = max_waves / g.phases;
+  if (wpp < 1) return hipErrorInvalidConfiguration;
+  if (tpi != 2 && tpi != 4) tpi = 4;
+  const int nwaves = wpp * g.phases;
+  const int tiles_per_block = wpp * tpi;
+  const dim3 grid((g.ntiles + tiles_per_block - 1) / tiles_per_block), block(64 * nwaves);
+  const int lds_pieces = g.phases * 512;
+  g.xtok = 16 * lds_pieces + 16 * ((lds_pieces + 31) >> 5);
+  g.part_offset = mt * g.xtok;
+  const size_t lds = g.part_offset + (g.phases > 1 ? sizeof(float) * g.phases * tiles_per_block * mt : 0);
+  const int xp = (lds_pieces + 64 * nwaves - 1) / (64 * nwaves);
+  if (xp > 4) return hipErrorInvalidConfiguration;
+#define EGT_T3(TPI, XP, MT)                                                                     \
+  launch(k_sparse_m1_tokens<TPI, XP, MT>, grid, block, lds, stream, w.row_ptr, (const uint8_t *)w.values, \
+         (const uint8_t *)w.idx, (const uint8_t *)w.qparams, (const __half *)X, (__half *)Y, g)
+#define EGT_T2(TPI, MT) (xp <= 1 ? EGT_T3(TPI, 1, MT) : xp == 2 ? EGT_T3(TPI, 2, MT) : EGT_T3(TPI, 4, MT))
+  if (mt == 2) return tpi == 2 ? EGT_T2(2, 2) : EGT_T2(4, 2);
+  return tpi == 2 ? EGT_T2(2, 4) : EGT_T2(4, 4);
+#undef EGT_T2
+#undef EGT_T3
 }
 
 hipError_t launch_sparse_m1(const egt_2bitcsr &w, const uint16_t *x, uint16_t *y, hipStream_t stream) {

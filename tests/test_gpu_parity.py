@@ -216,8 +216,29 @@ def test_smallm_tile_and_wave_shapes(rows, cols, n, g, kind, M):
         G.assert_close(Y, Y_ref, A_ref, f"smallm {rows}x{cols} M={M} pad={pad}")
 
 
+@pytest.mark.parametrize("rows,cols,g,M", [
+    (70, 4096, 128, 2), (70, 4096, 128, 3), (70, 4096, 128, 4),
+    (33, 4096, 64, 2), (33, 4096, 256, 4), (19, 4096, 4096, 3),      # other group sizes
+    (1000, 4096, 128, 4), (1003, 4096, 128, 2),                      # many workgroups, ragged rows
+    (9000, 4096, 128, 2),                                            # more rows than the four-token form takes
+])
+def test_few_tokens_on_the_row_per_wave_mapping(rows, cols, g, M):
+    # M = 2..4 at 2:4 INT4 with K >= 4096 runs on the M = 1 kernel's mapping (the weights are
+    # dequantised once and multiplied with one B operand per token)
+    print(f"case few tokens {rows}x{cols} g={g} M={M}", flush=True)
+    p, o = _small_case(rows, cols, 2, g, 0, seed=1700 + M + rows)
+    X = synth.activation_rows(M, cols, 1700 + M)
+    Y_ref, A_ref = O.gemm_smallm(o, X)
+    for pad in (0, 8):
+        Y = G.run_sparse_gemm(p, X, ldx_pad=pad, ldy_pad=pad // 2)
+        G.assert_close(Y, Y_ref, A_ref, f"few tokens {rows}x{cols} M={M} pad={pad}")
+    # token 0 alone is the M = 1 product: the same instructions in the same order
+    y0 = G.run_sparse_gemv(p, np.ascontiguousarray(X[0]))
+    assert np.array_equal(Y[0].view(np.uint16), y0.view(np.uint16))
+
+
 @pytest.mark.parametrize("rows,cols", [(11008, 4096), (4096, 11008)])
-@pytest.mark.parametrize("M", [4, 16, 24, 64])
+@pytest.mark.parametrize("M", [2, 4, 16, 24, 64])
 def test_config5_smallm_full_size(rows, cols, M):
     print(f"case config5 {rows}x{cols} M={M}", flush=True)
     seed = synth.seed_for(5, 0 if rows == 11008 else 1)
