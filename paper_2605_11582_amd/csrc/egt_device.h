@@ -39,8 +39,8 @@ hipError_t launch_sparse_m1(const egt_2bitcsr &w, const uint16_t *x, uint16_t *y
 bool sparse_m1_n1_supported(const egt_2bitcsr &w);
 hipError_t launch_sparse_m1_n1(const egt_2bitcsr &w, const uint16_t *x, uint16_t *y, hipStream_t stream);
 
-// 2 <= M <= 64 on the sparse matrix cores (2:4 only; see sparse_smallm_supported)
-bool sparse_smallm_supported(const egt_2bitcsr &w);
+// 2 <= M <= 64 on the sparse matrix cores (2:4 and 1:4; see sparse_smallm_supported)
+bool sparse_smallm_supported(const egt_2bitcsr &w, int64_t ldx, int M);
 hipError_t launch_sparse_smallm(const egt_2bitcsr &w, const uint16_t *X, int64_t ldx, uint16_t *Y,
                                 int64_t ldy, int M, hipStream_t stream);
 

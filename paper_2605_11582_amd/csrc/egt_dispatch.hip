@@ -12,8 +12,7 @@ hipError_t launch_sparse(const egt_2bitcsr &w, const uint16_t *X, int64_t ldx, u
   // 16-byte loads of X: token rows must start on a 16-byte boundary there
   if (M >= 2 && ldx % 8 == 0 && sparse_m1_tokens_supported(w, M) && getenv("EGT_NO_M1T") == nullptr)
     return launch_sparse_m1_tokens(w, X, ldx, Y, ldy, M, stream);
-  // the matrix-core path fetches X in 16-byte pieces: token rows must start on a dword
-  if (M >= 2 && ldx % 2 == 0 && sparse_smallm_supported(w)) return launch_sparse_smallm(w, X, ldx, Y, ldy, M, stream);
+  if (M >= 2 && sparse_smallm_supported(w, ldx, M)) return launch_sparse_smallm(w, X, ldx, Y, ldy, M, stream);
   return launch_sparse_generic(w, X, ldx, Y, ldy, M, stream);
 }
 

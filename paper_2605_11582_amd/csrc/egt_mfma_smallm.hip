@@ -424,11 +424,15 @@ __global__ __launch_bounds__(64 * NWMAX) void k_sparse_smallm_ks(const uint32_t 
 }
 
 // Shapes covered: 2:4 with K a multiple of 64, 1:4 with K a multiple of 128; INT4 groups
-// of 32 << j.
-bool sparse_smallm_supported(const egt_2bitcsr &w) {
+// of 32 << j; token rows of X on a dword boundary; values and X below 4 GiB each (the
+// loads take 32-bit offsets).
+bool sparse_smallm_supported(const egt_2bitcsr &w, int64_t ldx, int M) {
   if (w.n_keep != 1 && w.n_keep != 2) return false;
   const int chunk = w.n_keep == 1 ? 128 : 64;
-  if (w.cols % chunk != 0 || w.cols < chunk) return false;
+  if (w.cols % chunk != 0 || w.cols < chunk || ldx % 2 != 0) return false;
+  const uint64_t vbytes = (uint64_t)w.rows * (w.cols / chunk) * (w.val_kind == EGT_VAL_INT4 ? 16 : 64);
+  const uint64_t xbytes = ((uint64_t)(M - 1) * ldx + w.cols) * 2;
+  if (vbytes >= (1ull << 32) || xbytes >= (1ull << 32)) return false;
   if (w.val_kind == EGT_VAL_INT4) {
     const int gm = w.group_size / 32;
     if (w.group_size % 32 != 0 || (gm & (gm - 1)) != 0) return false;

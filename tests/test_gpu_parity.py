@@ -100,6 +100,22 @@ def test_broken_row_ptr_yields_nan_not_a_fault():
     assert np.array_equal(y[keep].view(np.uint16), good[keep].view(np.uint16))
 
 
+@pytest.mark.parametrize("cols,n,M", [(4096, 2, 2), (4096, 2, 4), (4096, 2, 9), (4096, 2, 40), (1024, 2, 5),
+                                      (4096, 1, 3), (11008, 1, 20)])
+def test_broken_row_ptr_yields_nan_for_every_token(cols, n, M):
+    # the several-token path, the K-split kernel (one and two token groups per pass) and 1:4
+    p, o = _small_case(64, cols, n, 128, 0, seed=4300 + M)
+    X = synth.activation_rows(M, cols, 4300 + M)
+    good = G.run_sparse_gemm(p, X)
+    p.row_ptr[7] += 8
+    p.row_ptr[40] = 0xFFFFFFF8
+    Y = G.run_sparse_gemm(p, X)
+    assert np.all(np.isnan(Y[:, 7])) and np.all(np.isnan(Y[:, 40]))
+    keep = np.ones(64, dtype=bool)
+    keep[[7, 40]] = False
+    assert np.array_equal(Y[:, keep].view(np.uint16), good[:, keep].view(np.uint16))
+
+
 # ---------------------------------------------------------------- dense INT4
 @pytest.mark.parametrize("rows,cols,g", [(37, 64, 8), (130, 1024, 128), (21, 11008, 128), (50, 4096, 64),
                                          (9, 4096, 4096), (66, 2048, 32), (33, 320, 64), (45, 4096, 128),
