@@ -100,6 +100,19 @@ def test_broken_row_ptr_yields_nan_not_a_fault():
     assert np.array_equal(y[keep].view(np.uint16), good[keep].view(np.uint16))
 
 
+@pytest.mark.parametrize("rows,cols,n,g,kind", [(1, 64, 2, 32, 0), (3, 128, 2, 64, 0), (2, 192, 2, 0, 1), (17, 64, 2, 64, 0),
+                                                (1, 128, 1, 32, 0), (5, 384, 1, 128, 0), (16, 256, 1, 0, 1),
+                                                (31, 4096, 2, 128, 0), (1, 4096, 2, 128, 0)])
+@pytest.mark.parametrize("M", [2, 17, 64])
+def test_smallm_tiny_matrices(rows, cols, n, g, kind, M):
+    # fewer rows than a row tile, one or two chunks per row, every token count class
+    print(f"case smallm tiny {rows}x{cols} n={n} g={g} kind={kind} M={M}", flush=True)
+    p, o = _small_case(rows, cols, n, g, kind, seed=5100 + M + rows + cols)
+    X = synth.activation_rows(M, cols, 5100 + M)
+    Y_ref, A_ref = O.gemm_smallm(o, X)
+    G.assert_close(G.run_sparse_gemm(p, X), Y_ref, A_ref, f"smallm tiny {rows}x{cols} M={M}")
+
+
 @pytest.mark.parametrize("cols,n,M", [(4096, 2, 2), (4096, 2, 4), (4096, 2, 9), (4096, 2, 40), (1024, 2, 5),
                                       (4096, 1, 3), (11008, 1, 20)])
 def test_broken_row_ptr_yields_nan_for_every_token(cols, n, M):
