@@ -122,6 +122,10 @@ __global__ __launch_bounds__(64 * NWMAX) void k_sparse_smallm_ks(const uint32_t 
   constexpr int PIECES = N1 ? 64 : 32;                // 16-byte pieces of a token row in a step
   constexpr int REGION = N1 ? 16 * KS_TOKEN_N1 : 8 * KS_PAIR;   // LDS bytes per wave for X
   constexpr int PART = NIT * NT * 1024;               // bytes of partial sums per wave
+  // SEP: the partial sums have LDS of their own behind the X regions, so the first loads
+  // of the next pass can be requested before the sums of this pass are added up and
+  // stored (8-wave forms with two token groups per pass; the others share the memory)
+  constexpr bool SEP = HOLD;
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int nw = blockDim.x >> 6;
@@ -136,7 +140,8 @@ __global__ __launch_bounds__(64 * NWMAX) void k_sparse_smallm_ks(const uint32_t 
   const int ngroups = (g.M + 15) >> 4;
   // Row pointers of the workgroup's rows are requested first and checked at the end
   // (flags in LDS behind the regions): a row whose pointer is not r * S yields NaN.
-  uint32_t *flags = (uint32_t *)(xs + nw * (REGION > PART ? REGION : PART));
+  uint8_t *parts = SEP ? xs + nw * REGION : xs;
+  uint32_t *flags = (uint32_t *)(xs + nw * (SEP ? REGION + PART : (REGION > PART ? REGION : PART)));
   const int frow = 16 * ((int)blockIdx.x + (int)(threadIdx.x >> 4) * (int)gridDim.x) + (int)(threadIdx.x & 15);
   const bool fcheck = (int)threadIdx.x < 16 * nit && frow < g.rows;
   const uint32_t frp = fcheck ? row_ptr[frow] : 0u;
@@ -310,16 +315,16 @@ __global__ __launch_bounds__(64 * NWMAX) void k_sparse_smallm_ks(const uint32_t 
     }
   };
 
+  ATile<KIND, QW> raw[NIT];
+  dma_x(0, wave);
+#pragma unroll
+  for (int it = 0; it < NIT; ++it) load_a(raw[it], it, wave);
   for (int j0 = 0; j0 < ngroups; j0 += NT) {          // passes of NT token groups
-    ATile<KIND, QW> raw[NIT];
     f4 acc[NIT][NT];
 #pragma unroll
     for (int it = 0; it < NIT; ++it)
 #pragma unroll
       for (int jj = 0; jj < NT; ++jj) acc[it][jj] = f4{0.f, 0.f, 0.f, 0.f};
-    dma_x(j0, wave);
-#pragma unroll
-    for (int it = 0; it < NIT; ++it) load_a(raw[it], it, wave);
 
     // A wave whose last step lies past K (K-steps not a multiple of the waves) skips
     // that phase; it is the last one, nothing is requested in it.
@@ -381,23 +386,32 @@ __global__ __launch_bounds__(64 * NWMAX) void k_sparse_smallm_ks(const uint32_t 
         }
       }
     }
-    wait_vmem<0>();                                   // a wave that left early may still have X on its way
+    const bool next_pass = j0 + NT < ngroups;
+    if (SEP) {
+      if (next_pass) {                                // first requests of the next pass (the region is free)
+        dma_x(j0 + NT, wave);
+#pragma unroll
+        for (int it = 0; it < NIT; ++it) load_a(raw[it], it, wave);
+      }
+    } else {
+      wait_vmem<0>();                                 // a wave that left early may still have X on its way
+      __syncthreads();                                // every wave is done with its X region
+    }
 
     // ---- partial sums to LDS: tile (it, jj) of wave w at w * PART + (it * NT + jj) * 1024,
     //      float 4 * lane + v = D[row 4 (lane >> 4) + v][token lane & 15]
-    __syncthreads();                                  // every wave is done with its X region
     if (threadIdx.x < 16 * NIT) flags[threadIdx.x] = (fcheck && frp == (uint32_t)frow * S_row) ? 1u : 0u;
 #pragma unroll
     for (int it = 0; it < NIT; ++it)
 #pragma unroll
       for (int jj = 0; jj < NT; ++jj)
-        if (it < nit) *(f4 *)(xs + wave * PART + (it * NT + jj) * 1024 + 16 * lane) = acc[it][jj];
+        if (it < nit) *(f4 *)(parts + wave * PART + (it * NT + jj) * 1024 + 16 * lane) = acc[it][jj];
     __syncthreads();
     for (int unit = threadIdx.x; unit < NIT * NT * 256; unit += (int)blockDim.x) {
       const int tj = unit >> 8, it = tj / NT, jj = tj % NT;
       if (it >= nit || j0 + jj >= ngroups) continue;  // uniform over a wave
       const int v = unit & 3, sl = (unit >> 2) & 63;  // register v of lane sl of the tile
-      const float *src = (const float *)xs + unit;
+      const float *src = (const float *)parts + unit;
       float part[NWMAX];
 #pragma unroll
       for (int w = 0; w < NWMAX; ++w) part[w] = src[min(w, nw - 1) * (PART / 4)];
@@ -419,7 +433,12 @@ __global__ __launch_bounds__(64 * NWMAX) void k_sparse_smallm_ks(const uint32_t 
         }
       }
     }
-    __syncthreads();                                  // the next pass writes X regions again
+    __syncthreads();                                  // the next pass writes the partial sums (and X regions) again
+    if (!SEP && next_pass) {
+      dma_x(j0 + NT, wave);
+#pragma unroll
+      for (int it = 0; it < NIT; ++it) load_a(raw[it], it, wave);
+    }
   }
 }
 
@@ -445,7 +464,9 @@ static hipError_t go_ks(const egt_2bitcsr &w, const uint16_t *X, uint16_t *Y, co
                         int nblocks, hipStream_t stream) {
   const size_t region = N1 ? 16 * KS_TOKEN_N1 : 8 * KS_PAIR;
   const size_t x_bytes = (size_t)nw * region, p_bytes = (size_t)nw * NIT * NT * 1024;
-  const size_t lds = (x_bytes > p_bytes ? x_bytes : p_bytes) + 64 * NIT;   // + row-pointer flags
+  // partial sums behind the X regions where the kernel keeps them apart (NT > 1), else in
+  // the same memory; + row-pointer flags
+  const size_t lds = (NT > 1 ? x_bytes + p_bytes : (x_bytes > p_bytes ? x_bytes : p_bytes)) + 64 * NIT;
   return launch(k_sparse_smallm_ks<KIND, NT, NIT, NWMAX, QW, N1>, dim3(nblocks), dim3(64 * nw), lds, stream,
                 w.row_ptr, (const uint8_t *)w.values, (const uint8_t *)w.idx, (const uint8_t *)w.qparams,
                 (const __half *)X, (__half *)Y, g);
