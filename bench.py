@@ -27,8 +27,8 @@ if ROOT not in sys.path:
 HBM_PEAK_GBPS = 8000.0
 LLC_BYTES = 256 << 20
 # HBM bytes per launch of the headline kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
-# (profiles/sparse_m1_headline_hbm_traffic.txt): 9062.2 * 2 KiB read + 21.5 KiB written.
-MEASURED_TRAFFIC_BYTES = round(9062.2 * 2048 + 21.5 * 1024)
+# (profiles/sparse_m1_headline_hbm_traffic.txt): 9066.7 * 2 KiB read + 21.5 KiB written.
+MEASURED_TRAFFIC_BYTES = round(9066.7 * 2048 + 21.5 * 1024)
 
 
 def algorithmic_bytes(rows, cols, n_keep, group, kind, m=1):
