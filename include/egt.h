@@ -130,6 +130,18 @@ egt_status egt_pack_2bitcsr(const uint16_t *w, int64_t ldw, const uint8_t *mask,
                             int rows, int cols, int n_keep, int group, int val_kind,
                             egt_2bitcsr *out);
 
+/* HOST.  The same encoder with a group size per row (Sec. 3.2 "Adaptive Group-Wise
+ * Quantization": channels found sensitive get more, smaller groups, robust ones fewer).
+ * row_group: rows entries, each a multiple of `group` that divides cols (else
+ * EGT_ERR_SHAPE); NULL means `group` for every row.  Row r is quantised in groups of
+ * row_group[r] columns.  The stored parameters keep the granularity `group`
+ * (out->group_size = group): a coarser group repeats its {scale, zero} pair, so the
+ * device kernels and egt_unpack_2bitcsr read the result like any other matrix; the
+ * bytes moved are those of the finest group size.  INT4 values only. */
+egt_status egt_pack_2bitcsr_rowgroups(const uint16_t *w, int64_t ldw, const uint8_t *mask, int64_t ldm,
+                                      int rows, int cols, int n_keep, int group, int val_kind,
+                                      const int32_t *row_group, egt_2bitcsr *out);
+
 /* HOST.  Inverse of the encoder: writes the decoded matrix (FP16 bits; s*(q-z)
  * rounded once to FP16 for INT4 values; 0 where no slot exists) and the mask of
  * positions that own a slot.  Either output may be NULL.  EGT_ERR_BUFFER when

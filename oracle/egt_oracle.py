@@ -188,11 +188,16 @@ def quant_codes(v: np.ndarray, s: np.ndarray, z: np.ndarray) -> np.ndarray:
 # --------------------------------------------------------------------------
 # O4  pack
 # --------------------------------------------------------------------------
-def pack_2bitcsr(w, mask, n_keep: int, group: int, val_kind: int) -> dict:
+def pack_2bitcsr(w, mask, n_keep: int, group: int, val_kind: int, row_group=None) -> dict:
     """Dense FP16 W (R x K) + 0/1 mask + n_keep + group size -> 2bit-CSR.
 
     Returns a dict of numpy arrays: row_ptr (uint32), values (uint8 bytes),
-    idx (uint16), qparams (uint16 (R, K/g, 2) or None) plus the scalars."""
+    idx (uint16), qparams (uint16 (R, K/g, 2) or None) plus the scalars.
+
+    row_group (INT4 only): per-row group sizes (Sec. 3.2 "Adaptive Group-Wise
+    Quantization": sensitive channels get more, smaller groups).  Row r is quantised in
+    groups of row_group[r] columns, a multiple of `group` that divides K; the stored
+    parameters keep the granularity `group`, every coarse group repeating its pair."""
     w = _as_f16(w)
     R, K = w.shape
     check_shape(R, K, n_keep, group, val_kind)
@@ -240,6 +245,16 @@ def pack_2bitcsr(w, mask, n_keep: int, group: int, val_kind: int) -> dict:
     mk = kept.reshape(R, G, group)
     vmin = np.where(mk, wk, np.inf).min(axis=2)
     vmax = np.where(mk, wk, -np.inf).max(axis=2)
+    if row_group is not None:
+        rg = np.asarray(row_group, dtype=np.int64)
+        if rg.shape != (R,) or np.any(rg <= 0) or np.any(rg % group != 0) or np.any(K % rg != 0):
+            raise ValueError("row_group entries must be multiples of group that divide cols")
+        for m in np.unique(rg // group):                   # rows whose groups span m stored groups
+            sel = np.nonzero(rg // group == m)[0]
+            lo = vmin[sel].reshape(len(sel), G // m, m).min(axis=2)
+            hi = vmax[sel].reshape(len(sel), G // m, m).max(axis=2)
+            vmin[sel] = np.repeat(lo, m, axis=1)
+            vmax[sel] = np.repeat(hi, m, axis=1)
     vmin = np.where(np.isfinite(vmin), vmin, 0.0)          # group with nothing kept
     vmax = np.where(np.isfinite(vmax), vmax, 0.0)
     s16, z = quant_params(vmin, vmax)                      # (R, G)

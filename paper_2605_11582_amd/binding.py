@@ -22,7 +22,7 @@ SYMBOLS = (
     "egt_status_str", "egt_last_hip_error", "egt_2bitcsr_sizes", "egt_prune_n4", "egt_pack_2bitcsr",
     "egt_unpack_2bitcsr", "egt_quant_int4", "egt_int4_gemv", "egt_sparse_gemv",
     "egt_sparse_gemm_smallm", "egt_stream_read", "egt_sparse_gemv_batch", "egt_int4_gemv_batch",
-    "egt_fit_verify_cost", "egt_trigger_depth", "egt_prune_n4_importance",
+    "egt_fit_verify_cost", "egt_trigger_depth", "egt_prune_n4_importance", "egt_pack_2bitcsr_rowgroups",
 )
 
 
@@ -65,6 +65,8 @@ def lib() -> C.CDLL:
                                               C.c_int, C.c_int, C.c_void_p, C.c_int64]
         L.egt_pack_2bitcsr.argtypes = [C.c_void_p, C.c_int64, C.c_void_p, C.c_int64, C.c_int, C.c_int,
                                        C.c_int, C.c_int, C.c_int, C.POINTER(View)]
+        L.egt_pack_2bitcsr_rowgroups.argtypes = [C.c_void_p, C.c_int64, C.c_void_p, C.c_int64, C.c_int, C.c_int,
+                                                 C.c_int, C.c_int, C.c_int, C.c_void_p, C.POINTER(View)]
         L.egt_unpack_2bitcsr.argtypes = [C.POINTER(View), C.c_void_p, C.c_int64, C.c_void_p, C.c_int64]
         L.egt_quant_int4.argtypes = [C.c_void_p, C.c_int64, C.c_int, C.c_int, C.c_int, C.c_void_p, C.c_void_p]
         L.egt_int4_gemv.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_void_p,
@@ -189,7 +191,8 @@ class Packed:
                       up(self.row_ptr), up(self.values), up(self.idx), up(self.qparams))
 
 
-def pack_2bitcsr(w: np.ndarray, mask: np.ndarray, n_keep: int, group: int, val_kind: int) -> Packed:
+def pack_2bitcsr(w: np.ndarray, mask: np.ndarray, n_keep: int, group: int, val_kind: int,
+                 row_group=None) -> Packed:
     w = _row_major(_f16_bits(w))
     mask = _row_major(np.asarray(mask, dtype=np.uint8))
     rows, cols = w.shape
@@ -202,8 +205,15 @@ def pack_2bitcsr(w: np.ndarray, mask: np.ndarray, n_keep: int, group: int, val_k
     qparams = np.empty((rows, cols // group, 2), dtype=np.uint16) if val_kind == VAL_INT4 else None
     p = Packed(rows, cols, n_keep, group, val_kind, row_ptr, values, idx, qparams)
     v = p.view()
-    _check(lib().egt_pack_2bitcsr(_np_ptr(w), _ld(w), _np_ptr(mask), _ld(mask),
-                                  rows, cols, n_keep, group, val_kind, C.byref(v)))
+    if row_group is None:
+        _check(lib().egt_pack_2bitcsr(_np_ptr(w), _ld(w), _np_ptr(mask), _ld(mask),
+                                      rows, cols, n_keep, group, val_kind, C.byref(v)))
+    else:
+        rg = np.ascontiguousarray(row_group, dtype=np.int32)
+        if rg.shape != (rows,):
+            raise ValueError("row_group must have one entry per row")
+        _check(lib().egt_pack_2bitcsr_rowgroups(_np_ptr(w), _ld(w), _np_ptr(mask), _ld(mask), rows, cols, n_keep,
+                                                group, val_kind, _np_ptr(rg), C.byref(v)))
     return p
 
 

@@ -213,12 +213,23 @@ egt_status egt_prune_n4_importance(const uint16_t *w, int64_t ldw, const float *
 egt_status egt_pack_2bitcsr(const uint16_t *w, int64_t ldw, const uint8_t *mask, int64_t ldm,
                             int rows, int cols, int n_keep, int group, int val_kind,
                             egt_2bitcsr *out) {
+  return egt_pack_2bitcsr_rowgroups(w, ldw, mask, ldm, rows, cols, n_keep, group, val_kind, nullptr, out);
+}
+
+egt_status egt_pack_2bitcsr_rowgroups(const uint16_t *w, int64_t ldw, const uint8_t *mask, int64_t ldm,
+                                      int rows, int cols, int n_keep, int group, int val_kind,
+                                      const int32_t *row_group, egt_2bitcsr *out) {
   if (!w || !mask || !out) return EGT_ERR_NULL;
   egt_status st = check_shape(rows, cols, n_keep, group, val_kind);
   if (st != EGT_OK) return st;
   if (ldw < cols || ldm < cols) return EGT_ERR_SHAPE;
   if (!out->row_ptr || !out->values || !out->idx) return EGT_ERR_NULL;
   if (val_kind == EGT_VAL_INT4 && !out->qparams) return EGT_ERR_NULL;
+  if (row_group) {
+    if (val_kind != EGT_VAL_INT4) return EGT_ERR_SHAPE;
+    for (int r = 0; r < rows; ++r)
+      if (row_group[r] <= 0 || row_group[r] % group != 0 || cols % row_group[r] != 0) return EGT_ERR_SHAPE;
+  }
 
   // pass 1: validate everything before a single output byte is written
   std::atomic<int> err(EGT_OK);
@@ -253,19 +264,24 @@ egt_status egt_pack_2bitcsr(const uint16_t *w, int64_t ldw, const uint8_t *mask,
       const uint8_t *mr = mask + (int64_t)r * ldm;
       row_ptr[r] = (uint32_t)((int64_t)r * S);
       if (val_kind == EGT_VAL_INT4) {
-        for (int g = 0; g < G; ++g) {
+        // the row's own group size; its parameters are stored once per `group` columns
+        const int gr = row_group ? row_group[r] : group, rep = gr / group;
+        for (int g0 = 0; g0 < G; g0 += rep) {
           double vmin = INFINITY, vmax = -INFINITY;
-          for (int c = g * group; c < (g + 1) * group; ++c) {
+          for (int c = g0 * group; c < g0 * group + gr; ++c) {
             if (!mr[c]) continue;
             const double v = half_to_double(wr[c]);
             vmin = std::min(vmin, v);
             vmax = std::max(vmax, v);
           }
           if (vmin > vmax) { vmin = 0.0; vmax = 0.0; }          // nothing kept
-          qp[g] = make_qparam(vmin, vmax);
-          uint16_t *o = qparams + ((int64_t)r * G + g) * 2;
-          o[0] = qp[g].s_bits;
-          o[1] = double_to_half((double)qp[g].z);
+          const QParam p = make_qparam(vmin, vmax);
+          for (int g = g0; g < g0 + rep; ++g) {
+            qp[g] = p;
+            uint16_t *o = qparams + ((int64_t)r * G + g) * 2;
+            o[0] = p.s_bits;
+            o[1] = double_to_half((double)p.z);
+          }
         }
       }
       int64_t t = (int64_t)r * S;                                 // global slot id

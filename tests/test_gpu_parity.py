@@ -44,6 +44,23 @@ def test_sparse_gemv_small(rows, cols, n, g, kind):
     G.assert_close(y, y_ref, a_ref, "sparse_gemv")
 
 
+@pytest.mark.parametrize("rows,cols,n,g,M", [(70, 4096, 2, 64, 1), (70, 4096, 1, 32, 1), (300, 1024, 2, 128, 6)])
+def test_row_group_sizes_run_on_the_ordinary_kernels(rows, cols, n, g, M):
+    # rows quantised with group sizes of their own are stored at the finest granularity
+    rng = np.random.default_rng(rows + cols + g)
+    w = synth.weights(rows, cols, 6100 + g)
+    mask = O.prune_n4_magnitude(w, n)
+    rg = rng.choice([g, 2 * g, 4 * g, cols], size=rows)
+    p = B.pack_2bitcsr(w, mask, n, g, 0, row_group=rg)
+    o = O.pack_2bitcsr(w, mask, n, g, 0, row_group=rg)
+    for k in ("values", "idx", "qparams"):
+        assert np.array_equal(getattr(p, k), o[k]), k
+    X = synth.activation_rows(M, cols, 6100 + g)
+    Y_ref, A_ref = O.gemm_smallm(o, X)
+    Y = G.run_sparse_gemm(p, X) if M > 1 else G.run_sparse_gemv(p, np.ascontiguousarray(X[0]))[None, :]
+    G.assert_close(Y, Y_ref, A_ref, "row groups")
+
+
 def test_config1_full_parity_and_determinism():
     seed = synth.seed_for(1)
     w = synth.weights(1024, 1024, seed)

@@ -107,6 +107,29 @@ def test_pack_bit_exact_config_like(n, g, kind):
     _same_packed(B.pack_2bitcsr(w, mask, n, g, kind), O.pack_2bitcsr(w, mask, n, g, kind))
 
 
+@pytest.mark.parametrize("n,g", [(2, 32), (1, 64), (2, 128)])
+def test_pack_with_row_groups_bit_exact(n, g):
+    rng = np.random.default_rng(600 + n + g)
+    w = synth.weights(150, 1024, 600 + n + g)
+    mask = O.prune_n4_magnitude(w, n)
+    mask[3, 64:192] = 0
+    rg = rng.choice([g, 2 * g, 4 * g, 1024], size=150)
+    _same_packed(B.pack_2bitcsr(w, mask, n, g, 0, row_group=rg), O.pack_2bitcsr(w, mask, n, g, 0, row_group=rg))
+    # every row at the stored granularity = the plain encoder
+    a, b = B.pack_2bitcsr(w, mask, n, g, 0, row_group=np.full(150, g)), B.pack_2bitcsr(w, mask, n, g, 0)
+    for k in ("row_ptr", "values", "idx", "qparams"):
+        assert np.array_equal(getattr(a, k), getattr(b, k)), k
+    for bad in (g + 4, 3 * g if 1024 % (3 * g) else 5 * g, 0, -g):
+        rb = rg.copy()
+        rb[17] = bad
+        with pytest.raises(B.EgtError) as e:
+            B.pack_2bitcsr(w, mask, n, g, 0, row_group=rb)
+        assert e.value.status == 2
+    with pytest.raises(B.EgtError) as e:                   # FP16 values have no groups
+        B.pack_2bitcsr(w, mask, n, 0, 1, row_group=np.full(150, 64))
+    assert e.value.status == 2
+
+
 def test_pack_bit_exact_config1():
     seed = synth.seed_for(1)
     w = synth.weights(1024, 1024, seed)

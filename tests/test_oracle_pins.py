@@ -151,6 +151,33 @@ def test_importance_pruning_special_cases():
     assert np.all(m[:, 2::4][nz] == 1)
 
 
+def test_row_groups_reduce_to_separate_packs_of_each_class():
+    # rows quantised with their own group size = the rows of a pack with that group size,
+    # its parameters repeated down to the stored granularity; decode sees no difference
+    rng = np.random.default_rng(77)
+    R, K, g = 12, 256, 32
+    w = _rand_w(R, K, 77)
+    mask = O.prune_n4_magnitude(w, 2)
+    rg = rng.choice([32, 64, 128, 256], size=R)
+    p = O.pack_2bitcsr(w, mask, 2, g, 0, row_group=rg)
+    assert p["qparams"].shape == (R, K // g, 2) and p["group"] == g
+    W = O.dense_from_packed(p)
+    for gr in (32, 64, 128, 256):
+        sel = np.nonzero(rg == gr)[0]
+        if len(sel) == 0:
+            continue
+        ref = O.pack_2bitcsr(w[sel], mask[sel], 2, gr, 0)
+        assert np.array_equal(np.repeat(ref["qparams"], gr // g, axis=1), p["qparams"][sel])
+        assert np.array_equal(O.dense_from_packed(ref), W[sel])
+    # a coarser group can only widen the range: its scale is at least the finer group's
+    fine = O.pack_2bitcsr(w, mask, 2, g, 0)
+    s_f = fine["qparams"][:, :, 0].view(np.float16).astype(np.float64)
+    s_c = p["qparams"][:, :, 0].view(np.float16).astype(np.float64)
+    assert np.all(s_c >= s_f)
+    with pytest.raises(ValueError):
+        O.pack_2bitcsr(w, mask, 2, g, 0, row_group=np.full(R, 48))
+
+
 # ----------------------------------------------------------------- structure
 @pytest.mark.parametrize("n,kind,g", [(2, 0, 32), (1, 0, 32), (2, 1, 0), (3, 0, 16), (4, 0, 64)])
 def test_structure_invariants(n, kind, g):
