@@ -133,6 +133,14 @@ __device__ __forceinline__ void k_sparse_m1_body(const uint32_t *__restrict__ ro
     rp[bt] = st[bt] ? row_ptr[rrow[bt]] : 0u;
   }
 
+  // several tiles per row: the threads that add the phases up at the end fetch the row
+  // pointer of their row now (wpp * TPI * MT <= 64 <= blockDim: one output per thread)
+  uint32_t rp_fin = 0;
+  if (g.phases > 1 && (int)threadIdx.x < wpp * TPI * MT) {
+    const int r = blockIdx.x * (wpp * TPI) + (int)threadIdx.x / MT;
+    if (r < g.rows) rp_fin = row_ptr[r];
+  }
+
   // ---- issue every load of the wave's TPI tiles
   u4 nib[TPI][KIND == EGT_VAL_INT4 ? 1 : 4];
   u2 iw[TPI];
@@ -294,13 +302,14 @@ __device__ __forceinline__ void k_sparse_m1_body(const uint32_t *__restrict__ ro
   if (g.phases > 1) {
     __syncthreads();
     const int per = wpp * TPI;                        // rows handled by this block
-    for (int j = threadIdx.x; j < per * MT; j += blockDim.x) {
+    const int j = threadIdx.x;
+    if (j < per * MT) {
       const int jr = j / MT, m = j - jr * MT;
       const int r = blockIdx.x * per + jr;
       if (r < g.rows && (MT == 1 || m < g.M)) {
         float v = 0.f;
         for (int p = 0; p < g.phases; ++p) v += part[(p * per + jr) * MT + m];
-        const bool ok = row_ptr[r] == (uint32_t)r * (uint32_t)(g.nchunks * 32);
+        const bool ok = rp_fin == (uint32_t)r * (uint32_t)(g.nchunks * 32);
         y[(int64_t)m * g.ldy + r] = ok ? __float2half(v) : __ushort_as_half((uint16_t)0x7E00);
       }
     }
@@ -379,7 +388,9 @@ hipError_t launch_sparse_m1_batch(const egt_2bitcsr *ws, const uint16_t *const *
   g.nib_mask = 0x00F0000Fu;
   g.nib_magic = 0x54006400u;
   // tuning knobs: tiles per wave, waves per phase per block
-  int tpi = 4, wpp = g.phases == 1 ? 4 : 2;
+  // measured optima: 4 tiles per wave and 4 waves per phase for one phase, 2 waves per phase
+  // for several - except three phases (K = 11008: 6.97 against 7.30 us with 2 and 4)
+  int tpi = g.phases == 3 ? 2 : 4, wpp = (g.phases == 1 || g.phases == 3) ? 4 : 2;
   if (const char *e = getenv("EGT_M1_TUNE")) sscanf(e, "%d,%d", &tpi, &wpp);
   if (wpp < 1) wpp = 1;
   if (wpp * g.phases > 16) wpp = 16 / g.phases;

@@ -65,6 +65,13 @@ __device__ __forceinline__ void k_sparse_m1_n1_body(const uint32_t *__restrict__
   }
 
   const int tile0 = (blockIdx.x * wpp + wslot) * TPI;
+  // several tiles per row: the threads that add the phases up at the end fetch the row
+  // pointer of their row now (wpp * TPI <= 64 <= blockDim: one output per thread)
+  uint32_t rp_fin = 0;
+  if (g.phases > 1 && (int)threadIdx.x < wpp * TPI) {
+    const int r = blockIdx.x * (wpp * TPI) + (int)threadIdx.x;
+    if (r < g.rows) rp_fin = row_ptr[r];
+  }
   u4 nib[TPI][KIND == EGT_VAL_INT4 ? 1 : 4];
   u2 iw[TPI];
   uint32_t qp[TPI][QW];
@@ -212,12 +219,13 @@ __device__ __forceinline__ void k_sparse_m1_n1_body(const uint32_t *__restrict__
   if (g.phases > 1) {
     __syncthreads();
     const int per = wpp * TPI;
-    for (int j = threadIdx.x; j < per; j += blockDim.x) {
+    const int j = threadIdx.x;
+    if (j < per) {
       const int r = blockIdx.x * per + j;
       if (r < g.rows) {
         float v = 0.f;
         for (int p = 0; p < g.phases; ++p) v += part[p * per + j];
-        const bool ok = row_ptr[r] == (uint32_t)r * (uint32_t)(g.nchunks * 32);
+        const bool ok = rp_fin == (uint32_t)r * (uint32_t)(g.nchunks * 32);
         y[r] = ok ? __float2half(v) : __ushort_as_half((uint16_t)0x7E00);
       }
     }
