@@ -67,6 +67,15 @@ __device__ __forceinline__ uint32_t spread_idx(uint32_t w, uint32_t m8, uint32_t
   return (t | (t << 2)) & m2;
 }
 
+// Workgroup barrier that orders LDS traffic only.  __syncthreads() also waits for every
+// outstanding global load and store of the wave; where loads for later work are in flight
+// across the barrier on purpose, that wait would give the overlap away.
+__device__ __forceinline__ void lds_barrier() {
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+  __builtin_amdgcn_s_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+}
+
 // Pointer table of a batched launch: up to EGT_MAX_BATCH identically shaped matrices,
 // selected by blockIdx.y (a single product is a batch of one).
 constexpr int EGT_MAX_BATCH = 4;

@@ -395,7 +395,7 @@ __global__ __launch_bounds__(64 * NWMAX) void k_sparse_smallm_ks(const uint32_t 
       }
     } else {
       wait_vmem<0>();                                 // a wave that left early may still have X on its way
-      __syncthreads();                                // every wave is done with its X region
+      lds_barrier();                                    // every wave is done with its X region
     }
 
     // ---- partial sums to LDS: tile (it, jj) of wave w at w * PART + (it * NT + jj) * 1024,
@@ -406,7 +406,7 @@ __global__ __launch_bounds__(64 * NWMAX) void k_sparse_smallm_ks(const uint32_t 
 #pragma unroll
       for (int jj = 0; jj < NT; ++jj)
         if (it < nit) *(f4 *)(parts + wave * PART + (it * NT + jj) * 1024 + 16 * lane) = acc[it][jj];
-    __syncthreads();
+    lds_barrier();
     for (int unit = threadIdx.x; unit < NIT * NT * 256; unit += (int)blockDim.x) {
       const int tj = unit >> 8, it = tj / NT, jj = tj % NT;
       if (it >= nit || j0 + jj >= ngroups) continue;  // uniform over a wave
@@ -433,7 +433,7 @@ __global__ __launch_bounds__(64 * NWMAX) void k_sparse_smallm_ks(const uint32_t 
         }
       }
     }
-    __syncthreads();                                  // the next pass writes the partial sums (and X regions) again
+    lds_barrier();                                    // the next pass writes the partial sums (and X regions) again
     if (!SEP && next_pass) {
       dma_x(j0 + NT, wave);
 #pragma unroll
