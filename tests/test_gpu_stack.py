@@ -86,3 +86,39 @@ def test_stack_parity_and_graph_replay():
         for m_i, m in enumerate(st.matrices):
             assert np.array_equal(m.y.cpu().numpy().view(np.uint16), eager[m_i].view(np.uint16)), (rep, m.layer, m.name)
         print(f"  graph replay {rep} matches the eager run", flush=True)
+
+
+def test_smallm_kernels_replay_in_a_hip_graph():
+    # the several-token path, the K-split kernel with one and two token groups per pass
+    # and its 1:4 form, captured together; every replay must reproduce the eager bits
+    torch = G.torch_mod()
+    cases = []
+    for (rows, cols, n, M) in ((300, 4096, 2, 2), (300, 4096, 2, 12), (300, 4096, 2, 40), (200, 11008, 1, 20),
+                               (90, 2048, 2, 64)):
+        w = synth.weights(rows, cols, 9000 + rows + M)
+        p = B.pack_2bitcsr(w, B.prune_n4(w, n), n, 128, B.VAL_INT4).to("cuda:0")
+        X = G.to_dev(synth.activation_rows(M, cols, 9000 + M).view(np.uint16)).view(torch.float16)
+        Y = torch.zeros((M, rows), dtype=torch.float16, device="cuda:0")
+        cases.append((B.prepared_sparse_gemm_smallm(p, X, Y), Y))
+    for call, _ in cases:
+        call()
+    torch.cuda.synchronize()
+    eager = [Y.cpu().numpy().copy() for _, Y in cases]
+    side = torch.cuda.Stream()
+    with torch.cuda.stream(side):
+        for call, _ in cases:
+            call(side.cuda_stream)
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=side):
+            sp = torch.cuda.current_stream().cuda_stream
+            for call, _ in cases:
+                call(sp)
+    for rep in range(3):
+        for _, Y in cases:
+            Y.fill_(5.0)                            # eager work between replays
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for k, (_, Y) in enumerate(cases):
+            assert np.array_equal(Y.cpu().numpy().view(np.uint16), eager[k].view(np.uint16)), (rep, k)
