@@ -433,8 +433,9 @@ __global__ __launch_bounds__(64 * NWMAX) void k_sparse_smallm_ks(const uint32_t 
         }
       }
     }
+    if (!next_pass) break;
     lds_barrier();                                    // the next pass writes the partial sums (and X regions) again
-    if (!SEP && next_pass) {
+    if (!SEP) {
       dma_x(j0 + NT, wave);
 #pragma unroll
       for (int it = 0; it < NIT; ++it) load_a(raw[it], it, wave);
