@@ -118,6 +118,13 @@ __global__ __launch_bounds__(64 * NWMAX) void k_sparse_smallm_ks(const uint32_t 
   constexpr bool INT4 = KIND == EGT_VAL_INT4;
   constexpr int VW = INT4 ? 1 : 4;
   constexpr bool HOLD = NT > 1;                       // A operands of a phase are kept for all token groups
+  // FP16 values at 2:4: instruction k of a step takes chunk k, lane (i, kb) its 16-byte
+  // piece kb, so the four lanes of a row fetch 64 contiguous bytes and what a lane
+  // fetches is its operand.  (Otherwise lane (i, kb) owns chunk kb for all instructions.)
+  constexpr bool LINA = !INT4 && !N1;
+  // DEEP: the A tiles are requested two phases ahead (two sets of fetch registers); X,
+  // which has one LDS region per wave, stays one phase ahead.
+  constexpr bool DEEP = LINA && !HOLD;
   constexpr int NM = N1 ? 8 : 4;                      // matrix instructions per step
   constexpr int PIECES = N1 ? 64 : 32;                // 16-byte pieces of a token row in a step
   constexpr int REGION = N1 ? 16 * KS_TOKEN_N1 : 8 * KS_PAIR;   // LDS bytes per wave for X
@@ -130,7 +137,8 @@ __global__ __launch_bounds__(64 * NWMAX) void k_sparse_smallm_ks(const uint32_t 
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int nw = blockDim.x >> 6;
   const int i = lane & 15, kb = lane >> 4;
-  const int li = INT4 ? (lane >> 2) : i, lc = INT4 ? (lane & 3) : kb;   // row, chunk this lane fetches
+  // row, chunk this lane fetches (LINA: of the index words only)
+  const int li = (INT4 || LINA) ? (lane >> 2) : i, lc = (INT4 || LINA) ? (lane & 3) : kb;
   const int from = 4 * (4 * i + kb);                  // lane that fetched the chunk of lane (i, kb), as a byte address
   const int nit = (g.ntiles - (int)blockIdx.x + (int)gridDim.x - 1) / (int)gridDim.x;   // <= NIT
   const int phases = (g.nsteps + nw - 1) / nw;
@@ -149,35 +157,48 @@ __global__ __launch_bounds__(64 * NWMAX) void k_sparse_smallm_ks(const uint32_t 
   const __amdgpu_buffer_rsrc_t r_val = make_rsrc(values, g.val_bytes), r_idx = make_rsrc(idx, g.idx_bytes);
   const __amdgpu_buffer_rsrc_t r_qp = make_rsrc(qparams, g.qp_bytes), r_x = make_rsrc(X, g.x_bytes);
   auto load_a = [&](ATile<KIND, QW> &a, int it, int step) {
-    const int rt = (int)blockIdx.x + min(it, nit - 1) * (int)gridDim.x;       // a tile past the end repeats the last one
+    // A tile past the workgroup's last one is requested out of range of the buffers: such a
+    // request returns zeros and moves no data (the count of requests per phase stays fixed).
+    const bool on = it < nit;                                                 // uniform
+    const uint32_t off_range = 0xFFFFFFF0u;
+    const int rt = (int)blockIdx.x + min(it, nit - 1) * (int)gridDim.x;
     const int s = min(step, g.nsteps - 1);
     // (the lane offsets are recomputed at every request: kept across the loops they would
     //  occupy a dozen registers)
     const uint32_t rel = (uint32_t)min((int)in_vgpr((uint32_t)li), g.rows - 1 - 16 * rt);   // row inside the tile (clamped)
     const uint32_t lcc = (uint32_t)min((int)in_vgpr((uint32_t)lc), g.nchunks - 1 - 4 * s);  // chunk inside the step (clamped)
     const uint32_t cl = rel * (uint32_t)g.nchunks + lcc;                      // lane part of the chunk number
-    const uint32_t cu = (uint32_t)(16 * rt) * (uint32_t)g.nchunks + (uint32_t)(4 * s);   // uniform part
-    a.iw = __builtin_amdgcn_raw_buffer_load_b64(r_idx, 8u * cl, 8u * cu, 0);
+    const uint32_t cu = on ? (uint32_t)(16 * rt) * (uint32_t)g.nchunks + (uint32_t)(4 * s) : 0u;   // uniform part
+    a.iw = __builtin_amdgcn_raw_buffer_load_b64(r_idx, on ? 8u * cl : off_range, 8u * cu, 0);
     a.qp[0] = 0;
     if (INT4) {
-      a.nib[0] = __builtin_amdgcn_raw_buffer_load_b128(r_val, 16u * cl, 16u * cu, 0);
-      const uint32_t qrow_l = rel * (uint32_t)g.groups_per_row, qrow_u = (uint32_t)(16 * rt) * (uint32_t)g.groups_per_row;
+      a.nib[0] = __builtin_amdgcn_raw_buffer_load_b128(r_val, on ? 16u * cl : off_range, 16u * cu, 0);
+      const uint32_t qrow_l = rel * (uint32_t)g.groups_per_row;
+      const uint32_t qrow_u = on ? (uint32_t)(16 * rt) * (uint32_t)g.groups_per_row : 0u;
       if (QW == 4) {
-        const u4 v = __builtin_amdgcn_raw_buffer_load_b128(r_qp, 4u * (qrow_l + 4u * lcc), 4u * (qrow_u + 16u * (uint32_t)s), 0);
+        const u4 v = __builtin_amdgcn_raw_buffer_load_b128(r_qp, on ? 4u * (qrow_l + 4u * lcc) : off_range,
+                                                           on ? 4u * (qrow_u + 16u * (uint32_t)s) : 0u, 0);
 #pragma unroll
         for (int k = 0; k < QW; ++k) a.qp[k] = v[k & 3];
       } else if (QW == 2) {
-        const u2 v = __builtin_amdgcn_raw_buffer_load_b64(r_qp, 4u * (qrow_l + 2u * lcc), 4u * (qrow_u + 8u * (uint32_t)s), 0);
+        const u2 v = __builtin_amdgcn_raw_buffer_load_b64(r_qp, on ? 4u * (qrow_l + 2u * lcc) : off_range,
+                                                          on ? 4u * (qrow_u + 8u * (uint32_t)s) : 0u, 0);
 #pragma unroll
         for (int k = 0; k < QW; ++k) a.qp[k] = v[k & 1];
       } else {
-        a.qp[0] = __builtin_amdgcn_raw_buffer_load_b32(r_qp, 4u * (qrow_l + (lcc >> g.gshift)),
-                                                       4u * (qrow_u + (uint32_t)((4 * s) >> g.gshift)), 0);
+        a.qp[0] = __builtin_amdgcn_raw_buffer_load_b32(r_qp, on ? 4u * (qrow_l + (lcc >> g.gshift)) : off_range,
+                                                       on ? 4u * (qrow_u + (uint32_t)((4 * s) >> g.gshift)) : 0u, 0);
       }
+    } else if (LINA) {
+      const uint32_t vrow = (uint32_t)min((int)in_vgpr((uint32_t)i), g.rows - 1 - 16 * rt);
+      const uint32_t vl = on ? 64u * vrow * (uint32_t)g.nchunks + 16u * (uint32_t)kb : off_range;
+#pragma unroll
+      for (int k = 0; k < VW; ++k)                    // chunk k of the step (clamped: uniform)
+        a.nib[k] = __builtin_amdgcn_raw_buffer_load_b128(r_val, vl, on ? 64u * (cu + (uint32_t)min(k, g.nchunks - 1 - 4 * s)) : 0u, 0);
     } else {
 #pragma unroll
       for (int k = 0; k < VW; ++k)
-        a.nib[k] = __builtin_amdgcn_raw_buffer_load_b128(r_val, 64u * cl + 16u * k, 64u * cu, 0);
+        a.nib[k] = __builtin_amdgcn_raw_buffer_load_b128(r_val, on ? 64u * cl + 16u * k : off_range, 64u * cu, 0);
     }
   };
   // fetched form -> operand form: lane (i, kb) takes what lane 4 i + kb fetched
@@ -189,6 +210,20 @@ __global__ __launch_bounds__(64 * NWMAX) void k_sparse_smallm_ks(const uint32_t 
       a.iw[1] = lane_perm(from, a.iw[1]);
 #pragma unroll
       for (int k = 0; k < QW; ++k) a.qp[k] = lane_perm(from, a.qp[k]);
+    } else if (LINA) {
+      // The index word of chunk c (four 16-bit fields, one per piece) was fetched by lane
+      // 4 r + c; instruction k wants field kb of the word of chunk k in lane (i, kb):
+      // a 4 x 4 transpose over the four lanes of the row, then the lane exchange.
+      const uint32_t c = (uint32_t)(lane & 3);
+      const uint32_t lo_sel = 0x0c0c0100u + c * 0x0202u, hi_sel = 0x01000c0cu + c * 0x02020000u;
+      const uint32_t a0 = quad_bcast<0>(a.iw[0]), b0 = quad_bcast<0>(a.iw[1]);
+      const uint32_t a1 = quad_bcast<1>(a.iw[0]), b1 = quad_bcast<1>(a.iw[1]);
+      const uint32_t a2 = quad_bcast<2>(a.iw[0]), b2 = quad_bcast<2>(a.iw[1]);
+      const uint32_t a3 = quad_bcast<3>(a.iw[0]), b3 = quad_bcast<3>(a.iw[1]);
+      const uint32_t w01 = __builtin_amdgcn_perm(b0, a0, lo_sel) | __builtin_amdgcn_perm(b1, a1, hi_sel);
+      const uint32_t w23 = __builtin_amdgcn_perm(b2, a2, lo_sel) | __builtin_amdgcn_perm(b3, a3, hi_sel);
+      a.iw[0] = lane_perm(from, w01);
+      a.iw[1] = lane_perm(from, w23);
     }
   };
   // This wave's slice of X for token group j goes from global memory straight into its
@@ -244,13 +279,15 @@ __global__ __launch_bounds__(64 * NWMAX) void k_sparse_smallm_ks(const uint32_t 
   // and 32 h + 16 (b >> 1) + 2 m + (b & 1) at 1:4, for h = 0, 1
   auto read_b = [&](u8v (&bx)[NM]) {
     const int n = lane & 15, b = lane >> 4;
-    const uint8_t *base0 = N1 ? region + KS_TOKEN_N1 * n + 16 * (16 * (b >> 1) + (b & 1))
-                              : region + KS_PAIR * (n >> 1) + 512 * (n & 1) + 16 * (8 * (b >> 1) + ((b ^ n) & 1));
+    // (LINA: pieces 8 m + b and 8 m + 4 + b, instruction m being chunk m of the step)
+    const uint8_t *base0 = N1     ? region + KS_TOKEN_N1 * n + 16 * (16 * (b >> 1) + (b & 1))
+                           : LINA ? region + KS_PAIR * (n >> 1) + 512 * (n & 1) + 16 * (b ^ (n & 1))
+                                  : region + KS_PAIR * (n >> 1) + 512 * (n & 1) + 16 * (8 * (b >> 1) + ((b ^ n) & 1));
 #pragma unroll
     for (int h = 0; h < 2; ++h) {
 #pragma unroll
       for (int m = 0; m < NM; ++m) {
-        const u4 v = *(const u4 *)(base0 + (N1 ? 512 : 256) * h + 32 * m);
+        const u4 v = *(const u4 *)(base0 + (N1 ? 512 : LINA ? 64 : 256) * h + (LINA ? 128 : 32) * m);
 #pragma unroll
         for (int k = 0; k < 4; ++k) bx[m][4 * h + k] = v[k];
       }
@@ -294,6 +331,11 @@ __global__ __launch_bounds__(64 * NWMAX) void k_sparse_smallm_ks(const uint32_t 
           av[m] = u4{v0 & 0xFFFFu, v0 >> 16, v1 & 0xFFFFu, v1 >> 16};
         }
       }
+    } else if constexpr (LINA) {
+      iwv[0] = t.iw[0];
+      iwv[NM / 2 - 1] = t.iw[1];
+#pragma unroll
+      for (int d = 0; d < NM; ++d) av[d] = 4 * step + d < g.nchunks ? t.nib[d & 3] : u4{0, 0, 0, 0};   // uniform
     } else {
       iwv[0] = t.iw[0];
       iwv[NM / 2 - 1] = t.iw[1];
@@ -315,10 +357,18 @@ __global__ __launch_bounds__(64 * NWMAX) void k_sparse_smallm_ks(const uint32_t 
     }
   };
 
-  ATile<KIND, QW> raw[NIT];
-  dma_x(0, wave);
+  ATile<KIND, QW> raw[NIT], raw2[DEEP ? NIT : 1];
+  // first requests of a pass: X and the A tiles of phase 0 (DEEP: and the tiles of phase 1)
+  auto start_pass = [&](int j) {
+    dma_x(j, wave);
 #pragma unroll
-  for (int it = 0; it < NIT; ++it) load_a(raw[it], it, wave);
+    for (int it = 0; it < NIT; ++it) load_a(raw[it], it, wave);
+    if (DEEP && phases > 1) {
+#pragma unroll
+      for (int it = 0; it < NIT; ++it) load_a(raw2[it], it, wave + nw);
+    }
+  };
+  start_pass(0);
   for (int j0 = 0; j0 < ngroups; j0 += NT) {          // passes of NT token groups
     f4 acc[NIT][NT];
 #pragma unroll
@@ -328,7 +378,40 @@ __global__ __launch_bounds__(64 * NWMAX) void k_sparse_smallm_ks(const uint32_t 
 
     // A wave whose last step lies past K (K-steps not a multiple of the waves) skips
     // that phase; it is the last one, nothing is requested in it.
-    for (int p = 0; p < phases && p * nw + wave < g.nsteps; ++p) {
+    // DEEP: pending at the top of phase p are, in request order, A(p), X(p), A(p + 1)
+    auto deep_phase = [&](ATile<KIND, QW> (&cur)[NIT], int p) {
+      constexpr int NA = NIT * 5;
+      const int step = p * nw + wave;
+      u8v bx[NM];
+      ATile<KIND, QW> t[NIT];
+      if (p + 1 < phases) wait_vmem<NA>(); else wait_vmem<0>();
+      zero_tail(step);
+      read_b(bx);
+#pragma unroll
+      for (int it = 0; it < NIT; ++it) {
+        t[it] = cur[it];
+        to_operand(t[it]);
+      }
+      wait_lds();
+      if (p + 1 < phases) dma_x(j0, step + nw);
+#pragma unroll
+      for (int it = 0; it < NIT; ++it) {
+        if (it < nit) {
+          u4 av[NM];
+          uint32_t iwv[NM / 2];
+          operands(t[it], step, av, iwv);
+          mfma_step(av, iwv, bx, acc[it][0]);
+        }
+        if (p + 2 < phases) load_a(cur[it], it, step + 2 * nw);
+      }
+    };
+    if constexpr (DEEP) {
+      for (int p = 0; p < phases && p * nw + wave < g.nsteps; p += 2) {
+        deep_phase(raw, p);
+        if (p + 1 < phases && (p + 1) * nw + wave < g.nsteps) deep_phase(raw2, p + 1);
+      }
+    }
+    for (int p = 0; !DEEP && p < phases && p * nw + wave < g.nsteps; ++p) {
       const int step = p * nw + wave;
       const bool more = p + 1 < phases;
       constexpr int NA = NIT * (INT4 ? 3 : 5);         // loads of the A tiles of one phase (any QW)
@@ -388,11 +471,7 @@ __global__ __launch_bounds__(64 * NWMAX) void k_sparse_smallm_ks(const uint32_t 
     }
     const bool next_pass = j0 + NT < ngroups;
     if (SEP) {
-      if (next_pass) {                                // first requests of the next pass (the region is free)
-        dma_x(j0 + NT, wave);
-#pragma unroll
-        for (int it = 0; it < NIT; ++it) load_a(raw[it], it, wave);
-      }
+      if (next_pass) start_pass(j0 + NT);             // (the region is free)
     } else {
       wait_vmem<0>();                                 // a wave that left early may still have X on its way
       lds_barrier();                                    // every wave is done with its X region
@@ -435,11 +514,7 @@ __global__ __launch_bounds__(64 * NWMAX) void k_sparse_smallm_ks(const uint32_t 
     }
     if (!next_pass) break;
     lds_barrier();                                    // the next pass writes the partial sums (and X regions) again
-    if (!SEP) {
-      dma_x(j0 + NT, wave);
-#pragma unroll
-      for (int it = 0; it < NIT; ++it) load_a(raw[it], it, wave);
-    }
+    if (!SEP) start_pass(j0 + NT);
   }
 }
 
@@ -504,10 +579,12 @@ hipError_t launch_sparse_smallm(const egt_2bitcsr &w, const uint16_t *X, int64_t
   // 2:4 INT4, up to 16 tokens: 16 waves of 128 registers; everything else 8 waves of 256
   // (more than 16 tokens at 2:4: two token groups per pass).
   const bool wide = n1 || M > 16 || !int4;
+  const bool f16x = !int4 && !n1 && M <= 16;          // FP16 values at 2:4, one token group
   const int nit_max = wide ? 4 : 3;
   int nwmax = wide ? 8 : 16, blocks_per_cu = 1;
+  if (f16x && g.ntiles <= 256) nwmax = 16;            // one tile per workgroup: 16 waves of 128 registers
   if (const char *e = getenv("EGT_SM_TUNE")) sscanf(e, "%d,%d", &nwmax, &blocks_per_cu);
-  if (nwmax < 1 || nwmax > (wide ? 8 : 16)) return hipErrorInvalidValue;
+  if (nwmax < 1 || nwmax > ((wide && !f16x) ? 8 : 16)) return hipErrorInvalidValue;
   const int nw = g.nsteps < nwmax ? g.nsteps : nwmax;
   int nblocks = 256 * blocks_per_cu;
   if (nblocks * nit_max < g.ntiles) nblocks = (g.ntiles + nit_max - 1) / nit_max;
@@ -528,7 +605,11 @@ hipError_t launch_sparse_smallm(const egt_2bitcsr &w, const uint16_t *X, int64_t
     if (!wide) return one ? EGT_KS(EGT_VAL_INT4, 1, 1, 16, 1, false) : EGT_KS(EGT_VAL_INT4, 1, 3, 16, 1, false);
     return one ? EGT_KS(EGT_VAL_INT4, 2, 1, 8, 1, false) : EGT_KS(EGT_VAL_INT4, 2, 4, 8, 1, false);
   }
-  if (M <= 16) return one ? EGT_KS(EGT_VAL_FP16, 1, 1, 8, 1, false) : EGT_KS(EGT_VAL_FP16, 1, 4, 8, 1, false);
+  if (M <= 16) {
+    if (one) return nw > 8 ? EGT_KS(EGT_VAL_FP16, 1, 1, 16, 1, false) : EGT_KS(EGT_VAL_FP16, 1, 1, 8, 1, false);
+    if (nw > 8) return hipErrorInvalidValue;
+    return EGT_KS(EGT_VAL_FP16, 1, 4, 8, 1, false);
+  }
   return one ? EGT_KS(EGT_VAL_FP16, 2, 1, 8, 1, false) : EGT_KS(EGT_VAL_FP16, 2, 4, 8, 1, false);
 #undef EGT_KS
 }

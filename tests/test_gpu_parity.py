@@ -243,6 +243,10 @@ def test_smallm_small_shapes(M):
     (70, 4160, 2, 64, 0, 5),        # K not a multiple of the K-step: a partly filled last step
     (70, 4160, 2, 64, 0, 20),
     (40, 320, 2, 0, 1, 33),         # the same with FP16 values
+    (4100, 6464, 2, 0, 1, 9),       # FP16 values, tiles requested two phases ahead: four phases of 8 waves,
+    (4100, 2304, 2, 0, 1, 16),      #   a partly filled last step; two phases, the second with one wave
+    (60, 11072, 2, 0, 1, 3),        # one tile per workgroup: three phases of 16 waves, the last partly filled
+    (200, 4352, 2, 0, 1, 13),       # 17 steps on 16 waves
     (4200, 1024, 1, 128, 0, 6),     # 1:4: {value, 0} pairs, eight instructions per step
     (300, 4096, 1, 128, 0, 16),
     (300, 4096, 1, 256, 0, 40),     # 1:4 runs its token groups one after the other
