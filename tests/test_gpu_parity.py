@@ -364,3 +364,58 @@ def test_int4_gemv_batch_equals_separate_calls(rows, cols, g, count):
         y = ys[k].cpu().numpy()
         G.assert_close(y, y_ref, a_ref, f"batch member {k}")
         assert np.array_equal(y.view(np.uint16), G.run_int4_gemv(qs[k], qps[k], g, xs[k]).view(np.uint16))
+
+
+# ---------------------------------------------------------------- seeded sweep over shapes
+def _random_sparse_case(rng):
+    big = rng.random() < 0.1
+    rows = int(rng.integers(4000, 5200)) if big else int(rng.integers(1, 400))
+    cols = 32 * int(rng.integers(1, 41 if big else 361))
+    if rng.random() < 0.3:
+        cols = int(rng.choice([4096, 11008, 8192, 1024, 2048, 4160, 12288]))
+    if big and cols > 2048:
+        cols = 1024
+    n = int(rng.choice([1, 2, 2, 2, 1, 3, 4]))
+    kind = int(rng.random() < 0.25)
+    g = 0 if kind else int(rng.choice([g for g in (32, 64, 128, 256, 512, cols, 96, 16) if cols % g == 0]))
+    M = 1 if rng.random() < 0.35 else int(rng.choice([2, 3, 4, 5, 7, 8, 15, 16, 17, 31, 32, 33, 48, 57, 63, 64]))
+    if big and M > 20:
+        M = int(rng.integers(2, 20))
+    return rows, cols, n, g, kind, M, int(rng.choice([0, 0, 2, 6, 7, 8])), 0.3 if rng.random() < 0.3 else 0.0
+
+
+@pytest.mark.parametrize("block", range(4))
+def test_seeded_sweep_of_sparse_shapes(block):
+    # shapes nobody picked by hand: every kernel form and the dispatch between them
+    rng = np.random.default_rng(4400 + block)
+    for case in range(25):
+        rows, cols, n, g, kind, M, pad, drop = _random_sparse_case(rng)
+        what = f"sweep {block}/{case}: {rows}x{cols} n={n} g={g} kind={kind} M={M} pad={pad} drop={drop}"
+        print("case " + what, flush=True)
+        p, o = _small_case(rows, cols, n, g, kind, seed=4400 + 100 * block + case, drop=drop)
+        if M == 1:
+            x = synth.activations(cols, 4400 + case)
+            y_ref, a_ref = O.gemv(o, x)
+            G.assert_close(G.run_sparse_gemv(p, x), y_ref, a_ref, what)
+        else:
+            X = synth.activation_rows(M, cols, 4400 + case)
+            Y_ref, A_ref = O.gemm_smallm(o, X)
+            G.assert_close(G.run_sparse_gemm(p, X, ldx_pad=pad, ldy_pad=pad), Y_ref, A_ref, what)
+
+
+def test_seeded_sweep_of_dense_shapes():
+    rng = np.random.default_rng(4500)
+    for case in range(40):
+        rows = int(rng.integers(1, 400))
+        cols = 8 * int(rng.integers(1, 1500))
+        if rng.random() < 0.4:
+            cols = int(rng.choice([4096, 11008, 8192, 1024, 2048, 4160, 12288, 512]))
+        g = int(rng.choice([g for g in (8, 16, 32, 64, 128, 256, 512, cols, 96) if cols % g == 0]))
+        print(f"case dense sweep {case}: {rows}x{cols} g={g}", flush=True)
+        w = synth.weights(rows, cols, 4500 + case)
+        x = synth.activations(cols, 4500 + case)
+        q, qp = B.quant_int4(w, g)
+        oq, oqp = O.quant_int4_dense(w, g)
+        assert np.array_equal(q, oq) and np.array_equal(qp, oqp)
+        y_ref, a_ref = O.int4_gemv(oq, oqp, g, x)
+        G.assert_close(G.run_int4_gemv(q, qp, g, x), y_ref, a_ref, f"dense sweep {rows}x{cols} g={g}")
