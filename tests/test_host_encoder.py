@@ -34,6 +34,39 @@ def test_library_exports_every_declared_symbol():
         assert getattr(L, name) is not None
 
 
+def test_library_packs_the_handworked_rows():
+    # the hand-worked fixtures pin the library directly, not only through the oracle
+    from helpers import read_fixture
+    fx = read_fixture("handworked_1x32.txt")
+    w = np.array([float(v) for v in fx["w"]], dtype=np.float16)[None, :]
+    mask = np.array([int(v) for v in fx["mask"]], dtype=np.uint8)[None, :]
+    p = B.pack_2bitcsr(w, mask, 2, 32, B.VAL_INT4)
+    assert p.idx.tolist() == [int(v, 16) for v in fx["idx_words"]]
+    assert p.values.tolist() == [int(v, 16) for v in fx["value_bytes"]]
+    assert np.asarray(p.qparams).reshape(-1).tolist() == [int(v, 16) for v in fx["qparams"]]
+    pf = B.pack_2bitcsr(w, mask, 2, 0, B.VAL_FP16)
+    assert np.asarray(pf.values).view(np.uint16).tolist() == [int(v, 16) for v in fx["fp16_bits"]]
+    fq = read_fixture("handworked_quantiser.txt")
+    w = np.zeros((1, 32), dtype=np.float16)
+    mask = np.zeros((1, 32), dtype=np.uint8)
+    w[0, :4] = [float(v) for v in fq["row_w"]]
+    mask[0, :4] = [int(v) for v in fq["row_mask"]]
+    p = B.pack_2bitcsr(w, mask, 2, 32, B.VAL_INT4)
+    assert np.asarray(p.qparams).reshape(-1).tolist() == [int(v, 16) for v in fq["row_qparams"]]
+    assert p.values.tolist() == [int(v, 16) for v in fq["row_value_bytes"]]
+    assert p.idx.tolist() == [int(v, 16) for v in fq["row_idx_words"]]
+    # the quantiser cases as one-group rows: kept values vmin and vmax (and a zero)
+    for name in ("all_positive", "all_negative", "rounded_scale_up", "rounded_scale_dn"):
+        vmin, vmax, bits, zero = fq[name]
+        w = np.zeros((1, 32), dtype=np.float16)
+        mask = np.zeros((1, 32), dtype=np.uint8)
+        w[0, 0], w[0, 4] = float(vmin), float(vmax)
+        mask[0, 0] = mask[0, 4] = 1
+        qp = np.asarray(B.pack_2bitcsr(w, mask, 2, 32, B.VAL_INT4).qparams).reshape(-1)
+        assert int(qp[0]) == int(bits, 16), name
+        assert float(qp[1:2].view(np.float16)[0]) == float(zero), name
+
+
 def test_status_strings():
     assert B.status_str(0) == "ok"
     assert len({B.status_str(i) for i in range(8)}) == 8

@@ -53,6 +53,47 @@ def test_handworked_fp16_bytes():
     assert y[0] == float(fx["y_fp16"][0])
 
 
+def test_handworked_quantiser_cases():
+    fx = read_fixture("handworked_quantiser.txt")
+    for name in ("all_positive", "all_negative", "rounded_scale_up", "rounded_scale_dn", "nothing_kept"):
+        vmin, vmax, bits, zero = fx[name]
+        s16, z = O.quant_params(np.array([float(vmin)]), np.array([float(vmax)]))
+        assert int(s16.view(np.uint16)[0]) == int(bits, 16), name
+        assert float(z[0]) == float(zero), name
+    # an entry the mask drops does not widen the range of its group
+    w = np.zeros((1, 32), dtype=np.float16)
+    mask = np.zeros((1, 32), dtype=np.uint8)
+    w[0, :4] = [float(v) for v in fx["row_w"]]
+    mask[0, :4] = [int(v) for v in fx["row_mask"]]
+    p = O.pack_2bitcsr(w, mask, 2, 32, O.VAL_INT4)
+    assert p["qparams"].reshape(-1).tolist() == [int(v, 16) for v in fx["row_qparams"]]
+    assert p["values"].tolist() == [int(v, 16) for v in fx["row_value_bytes"]]
+    assert p["idx"].tolist() == [int(v, 16) for v in fx["row_idx_words"]]
+
+
+# ----------------------------------------------------------------- trigger cost model
+def test_fit_of_an_exact_line_and_against_polyfit():
+    m = [1, 2, 4, 8, 16, 32, 64]
+    a, b = O.fit_verify_cost(m, [3.0 + 0.25 * v for v in m])
+    assert a == pytest.approx(3.0) and b == pytest.approx(0.25)
+    t = [34.0, 38.5, 45.0, 49.5, 55.0, 71.0, 115.0]
+    slope, icpt = np.polyfit(np.array(m, dtype=np.float64), np.array(t), 1)     # library least squares
+    a, b = O.fit_verify_cost(m, t)
+    assert a == pytest.approx(icpt) and b == pytest.approx(slope)
+
+
+def test_trigger_depth_worked_by_hand():
+    # t_ar = 10, a = 8, b = 2: gains per depth are
+    #   6*10-(8+2*64) = -76, 5*10-(8+48) = -6, 4*10-(8+18) = 14, 3*10-(8+8) = 14, 2*10-(8+4) = 8, 10-(8+2) = 0
+    # the largest gain, 14, is reached first at depth 2
+    cand, rem = [64, 24, 9, 4, 2, 1], [6, 5, 4, 3, 2, 1]
+    assert O.trigger_depth(10.0, 8.0, 2.0, cand, rem) == (2, 14.0)
+    # a flat cost (b = 0): the depth with the most tokens left wins, gain 60 - 8
+    assert O.trigger_depth(10.0, 8.0, 0.0, cand, rem) == (0, 52.0)
+    # verification dearer than everything it saves: never trigger
+    assert O.trigger_depth(1.0, 50.0, 1.0, cand, rem) == (-1, 0.0)
+
+
 # ----------------------------------------------------------------- size model
 def test_size_ratio_30_percent():
     # the paper's figure: index + weights = 30 % of the original CSR
