@@ -206,9 +206,12 @@ __device__ __forceinline__ void k_sparse_m1_body(const uint32_t *__restrict__ ro
 #pragma unroll
       for (int k = 0; k < 4; ++k) {
         const int pi = 2 * (256 * phase + 64 * k + n + 16 * kba) + sub;
-        const u4 v = *(const u4 *)(xs + 16 * pi + 16 * (pi >> XSH));
 #pragma unroll
-        for (int j = 0; j < 4; ++j) bx[0][k][4 * h + j] = v[j];
+        for (int m = 0; m < MT; ++m) {
+          const u4 v = *(const u4 *)(xs + m * g.xtok + 16 * pi + 16 * (pi >> XSH));
+#pragma unroll
+          for (int j = 0; j < 4; ++j) bx[m][k][4 * h + j] = v[j];
+        }
       }
     }
   } else {
@@ -254,7 +257,9 @@ __device__ __forceinline__ void k_sparse_m1_body(const uint32_t *__restrict__ ro
       if (KIND == EGT_VAL_INT4) a = dequant8(nib[t][0][d], off[d * QW / 4], s2[d * QW / 4], g.nib_mask, magic);
       else a = nib[t][d];
       if constexpr (LIN) {
-        acc[0] = __builtin_amdgcn_smfmac_f32_16x16x64_f16(__builtin_bit_cast(h8, a), __builtin_bit_cast(h16, bx[0][d]), acc[0], (int)iwl[t][d], 0, 0);
+#pragma unroll
+        for (int m = 0; m < MT; ++m)
+          acc[m] = __builtin_amdgcn_smfmac_f32_16x16x64_f16(__builtin_bit_cast(h8, a), __builtin_bit_cast(h16, bx[m][d]), acc[m], (int)iwl[t][d], 0, 0);
         continue;
       }
       const int iword = d < 2 ? (int)iw[t][0] : (int)iw[t][1];
@@ -328,14 +333,14 @@ __global__ __launch_bounds__(1024) void k_sparse_m1(const uint32_t *__restrict__
 }
 
 // Several tokens (2 <= M <= MT), one matrix.
-template <int TPI, int XP, int MT>
-__global__ __launch_bounds__(MT > 2 ? 512 : 1024) void k_sparse_m1_tokens(const uint32_t *__restrict__ row_ptr,
+template <int KIND, int TPI, int XP, int MT>
+__global__ __launch_bounds__((MT > 2 || KIND == EGT_VAL_FP16) ? 512 : 1024) void k_sparse_m1_tokens(const uint32_t *__restrict__ row_ptr,
                                                                            const uint8_t *__restrict__ values,
                                                                            const uint8_t *__restrict__ idx,
                                                                            const uint8_t *__restrict__ qparams,
                                                                            const __half *__restrict__ x,
                                                                            __half *__restrict__ y, const M1Geom g) {
-  k_sparse_m1_body<EGT_VAL_INT4, TPI, XP, 1, false, MT>(row_ptr, values, idx, qparams, x, y, g);
+  k_sparse_m1_body<KIND, TPI, XP, 1, KIND == EGT_VAL_FP16, MT>(row_ptr, values, idx, qparams, x, y, g);
 }
 
 // Several identically shaped matrices per launch, selected by blockIdx.y.
@@ -447,13 +452,18 @@ hipError_t launch_sparse_m1_batch(const egt_2bitcsr *ws, const uint16_t *const *
 #undef EGT_GOL
 }
 
-// Several-token form: 2:4 INT4, groups of 64 << j, M = 2..4.  Used where it is the faster
-// one: a row is one tile (K = 4096; with more tiles per row the K-split kernel wins), and for
-// three or four tokens (about 220 registers, two waves per SIMD) all workgroups must be
-// resident at once (at most 8192 rows).
+// Several-token form: 2:4, M = 2..4, INT4 values (groups of 64 << j) or FP16 values.  Used
+// where it is the faster one: a row is one tile (K = 4096; with more tiles per row the
+// K-split kernel wins, except for two tokens with FP16 values), and for three or four tokens
+// with INT4 values (about 220 registers, two waves per SIMD) all workgroups must be resident
+// at once (at most 8192 rows).
 bool sparse_m1_tokens_supported(const egt_2bitcsr &w, int M) {
-  if (M < 2 || M > 4 || w.n_keep != 2 || w.val_kind != EGT_VAL_INT4) return false;
+  if (M < 2 || M > 4 || w.n_keep != 2) return false;
+  // FP16 values, two tokens: also up to four tiles per row (12.3 against 14.0 us on
+  // 4096 x 11008, 8.7 against 11.0 us on 4096 x 8192)
+  if (w.val_kind == EGT_VAL_FP16 && M == 2 && w.cols % 64 == 0 && w.cols > 4096 && w.cols <= 16384) return true;
   if (w.cols != 4096) return false;
+  if (w.val_kind == EGT_VAL_FP16) return true;
   if (M > 2 && w.rows > 8192) return false;
   const int gm = w.group_size / 64;
   return w.group_size % 64 == 0 && (gm & (gm - 1)) == 0;
@@ -468,37 +478,45 @@ hipError_t launch_sparse_m1_tokens(const egt_2bitcsr &w, const uint16_t *X, int6
   g.mr_shift = -1;
   g.phases = (g.nchunks + 63) / 64;
   g.ntiles = w.rows;
-  g.gshift = 0;
-  while ((64 << g.gshift) < w.group_size) ++g.gshift;
-  g.groups_per_row = w.cols / w.group_size;
+  const bool f16 = w.val_kind == EGT_VAL_FP16;
+  g.gshift = 0; g.groups_per_row = 0;
+  if (!f16) {
+    while ((64 << g.gshift) < w.group_size) ++g.gshift;
+    g.groups_per_row = w.cols / w.group_size;
+  }
   g.last_chunk = (uint32_t)w.rows * (uint32_t)g.nchunks - 1u;
   g.nib_mask = 0x00F0000Fu;
   g.nib_magic = 0x54006400u;
   g.M = M; g.ldx = ldx; g.ldy = ldy;
   const int mt = M == 2 ? 2 : 4;
-  // four tokens take about 200 registers: two waves per SIMD, workgroups of at most 8 waves
-  int tpi = 4, wpp = g.phases == 1 ? 4 : 2;
+  // four tokens take about 200 registers: two waves per SIMD, workgroups of at most 8 waves;
+  // FP16 values (64 B per lane and tile): two tiles per wave
+  int tpi = (f16 && g.phases < 3) ? 2 : 4, wpp = g.phases == 1 ? 4 : 2;
   if (const char *e = getenv("EGT_M1T_TUNE")) sscanf(e, "%d,%d", &tpi, &wpp);
+  if (f16 && mt == 4) tpi = 2;                        // the only four-token form with FP16 values
   if (wpp < 1) wpp = 1;
-  const int max_waves = mt > 2 ? 8 : 16;
+  const int max_waves = (mt > 2 || f16) ? 8 : 16;
   if (wpp * g.phases > max_waves) wpp = max_waves / g.phases;
   if (wpp < 1) return hipErrorInvalidConfiguration;
-  if (tpi != 2 && tpi != 4) tpi = 4;
+  if (tpi != 2 && tpi != 4) tpi = f16 ? 2 : 4;
   const int nwaves = wpp * g.phases;
   const int tiles_per_block = wpp * tpi;
   const dim3 grid((g.ntiles + tiles_per_block - 1) / tiles_per_block), block(64 * nwaves);
   const int lds_pieces = g.phases * 512;
-  g.xtok = 16 * lds_pieces + 16 * ((lds_pieces + 31) >> 5);
+  // (x in LDS is padded once per 16 pieces for the contiguous-kilobyte form, else once per 32)
+  g.xtok = f16 ? 16 * lds_pieces + 16 * ((lds_pieces + 15) >> 4) : 16 * lds_pieces + 16 * ((lds_pieces + 31) >> 5);
   g.part_offset = mt * g.xtok;
   const size_t lds = g.part_offset + (g.phases > 1 ? sizeof(float) * g.phases * tiles_per_block * mt : 0);
   const int xp = (lds_pieces + 64 * nwaves - 1) / (64 * nwaves);
   if (xp > 4) return hipErrorInvalidConfiguration;
-#define EGT_T3(TPI, XP, MT)                                                                     \
-  launch(k_sparse_m1_tokens<TPI, XP, MT>, grid, block, lds, stream, w.row_ptr, (const uint8_t *)w.values, \
+#define EGT_T3(KIND, TPI, XP, MT)                                                               \
+  launch(k_sparse_m1_tokens<KIND, TPI, XP, MT>, grid, block, lds, stream, w.row_ptr, (const uint8_t *)w.values, \
          (const uint8_t *)w.idx, (const uint8_t *)w.qparams, (const __half *)X, (__half *)Y, g)
-#define EGT_T2(TPI, MT) (xp <= 1 ? EGT_T3(TPI, 1, MT) : xp == 2 ? EGT_T3(TPI, 2, MT) : EGT_T3(TPI, 4, MT))
-  if (mt == 2) return tpi == 2 ? EGT_T2(2, 2) : EGT_T2(4, 2);
-  return tpi == 2 ? EGT_T2(2, 4) : EGT_T2(4, 4);
+#define EGT_T2(KIND, TPI, MT) (xp <= 1 ? EGT_T3(KIND, TPI, 1, MT) : xp == 2 ? EGT_T3(KIND, TPI, 2, MT) : EGT_T3(KIND, TPI, 4, MT))
+  if (f16 && mt == 4) return EGT_T2(EGT_VAL_FP16, 2, 4);
+  if (f16) return tpi == 2 ? EGT_T2(EGT_VAL_FP16, 2, 2) : EGT_T2(EGT_VAL_FP16, 4, 2);
+  if (mt == 2) return tpi == 2 ? EGT_T2(EGT_VAL_INT4, 2, 2) : EGT_T2(EGT_VAL_INT4, 4, 2);
+  return tpi == 2 ? EGT_T2(EGT_VAL_INT4, 2, 4) : EGT_T2(EGT_VAL_INT4, 4, 4);
 #undef EGT_T2
 #undef EGT_T3
 }

@@ -287,6 +287,26 @@ def test_few_tokens_on_the_row_per_wave_mapping(rows, cols, g, M):
     assert np.array_equal(Y[0].view(np.uint16), y0.view(np.uint16))
 
 
+@pytest.mark.parametrize("rows,cols,M", [(70, 4096, 2), (1003, 4096, 2), (9000, 4096, 2), (70, 4096, 3), (1003, 4096, 4),
+                                         (9000, 4096, 3), (11008, 4096, 4),
+                                         # two tokens, several tiles per row (the last one partly filled)
+                                         (300, 11008, 2), (70, 8192, 2), (41, 4160, 2), (33, 16384, 2), (1030, 5120, 2)])
+def test_few_tokens_with_fp16_values_on_the_row_per_wave_mapping(rows, cols, M):
+    # FP16 values, M = 2..4: the M = 1 kernel's contiguous-kilobyte loads with one B operand per token
+    print(f"case few tokens fp16 {rows}x{cols} M={M}", flush=True)
+    p, o = _small_case(rows, cols, 2, 0, 1, seed=1900 + rows, drop=0.1)
+    X = synth.activation_rows(M, cols, 1900 + rows)
+    Y_ref, A_ref = O.gemm_smallm(o, X)
+    for pad in (0, 8):
+        Y = G.run_sparse_gemm(p, X, ldx_pad=pad, ldy_pad=pad // 2)
+        G.assert_close(Y, Y_ref, A_ref, f"few tokens fp16 {rows} M={M} pad={pad}")
+    for m in range(M):            # each token alone is the M = 1 product: same instructions, same order
+        y1 = G.run_sparse_gemv(p, np.ascontiguousarray(X[m]))
+        assert np.array_equal(Y[m].view(np.uint16), y1.view(np.uint16))
+    Y6 = G.run_sparse_gemm(p, X, ldx_pad=6)          # token rows not 16-byte aligned: the K-split kernel
+    G.assert_close(Y6, Y_ref, A_ref, "few tokens fp16, unaligned rows of X")
+
+
 @pytest.mark.parametrize("rows,cols", [(11008, 4096), (4096, 11008)])
 @pytest.mark.parametrize("M", [2, 4, 16, 24, 64])
 def test_config5_smallm_full_size(rows, cols, M):
