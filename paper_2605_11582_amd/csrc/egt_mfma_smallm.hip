@@ -98,6 +98,16 @@ __device__ __forceinline__ void wait_vmem() {       // at most N vector-memory o
 __device__ __forceinline__ void wait_lds() {
   asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
 }
+// f(IC<0>), f(IC<1>), ... f(IC<N - 1>): a loop whose index is a compile-time constant
+template <int V>
+struct IC { static constexpr int v = V; };
+template <int I, int N, class F>
+__device__ __forceinline__ void static_for(F &&f) {
+  if constexpr (I < N) {
+    f(IC<I>{});
+    static_for<I + 1, N>(f);
+  }
+}
 template <int N>
 __device__ __forceinline__ uint32_t quad_bcast(uint32_t v) {     // value of lane N of the 4-lane group
   return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, N * 0x55, 0xf, 0xf, true);
@@ -384,7 +394,26 @@ __global__ __launch_bounds__(64 * NWMAX) void k_sparse_smallm_ks(const uint32_t 
       const int step = p * nw + wave;
       u8v bx[NM];
       ATile<KIND, QW> t[NIT];
-      if (p + 1 < phases) wait_vmem<NA>(); else wait_vmem<0>();
+      if (p + 1 >= phases) {
+        // last phase: the tiles are consumed as they arrive
+        wait_vmem<(NIT - 1) * 5>();
+        zero_tail(step);
+        read_b(bx);
+        static_for<0, NIT>([&](auto ic) {
+          constexpr int it = decltype(ic)::v;
+          if constexpr (it > 0) wait_vmem<(NIT - 1 - it) * 5>();
+          if (it < nit) {
+            ATile<KIND, QW> tl = cur[it];
+            to_operand(tl);
+            u4 av[NM];
+            uint32_t iwv[NM / 2];
+            operands(tl, step, av, iwv);
+            mfma_step(av, iwv, bx, acc[it][0]);
+          }
+        });
+        return;
+      }
+      wait_vmem<NA>();
       zero_tail(step);
       read_b(bx);
 #pragma unroll
@@ -417,6 +446,29 @@ __global__ __launch_bounds__(64 * NWMAX) void k_sparse_smallm_ks(const uint32_t 
       constexpr int NA = NIT * (INT4 ? 3 : 5);         // loads of the A tiles of one phase (any QW)
       u8v bx[NM];
       ATile<KIND, QW> t[NIT];
+      if constexpr (!HOLD) {
+        if (!more) {
+          // Last phase: nothing more is requested, so the tiles are consumed as they arrive
+          // (loads return in request order: X first, then tile 0, 1, ...).
+          constexpr int LPT = INT4 ? 3 : 5;           // loads per tile
+          wait_vmem<(NIT - 1) * LPT>();
+          zero_tail(step);
+          read_b(bx);
+          static_for<0, NIT>([&](auto ic) {
+            constexpr int it = decltype(ic)::v;
+            if constexpr (it > 0) wait_vmem<(NIT - 1 - it) * LPT>();
+            if (it < nit) {
+              ATile<KIND, QW> tl = raw[it];
+              to_operand(tl);
+              u4 av[NM];
+              uint32_t iwv[NM / 2];
+              operands(tl, step, av, iwv);
+              mfma_step(av, iwv, bx, acc[it][0]);
+            }
+          });
+          continue;
+        }
+      }
       wait_vmem<0>();                                 // X and the A tiles of this phase have arrived
       zero_tail(step);
       read_b(bx);
