@@ -158,8 +158,12 @@ __global__ __launch_bounds__(64 * NWMAX) void k_sparse_smallm_ks(const uint32_t 
   const int ngroups = (g.M + 15) >> 4;
   // Row pointers of the workgroup's rows are requested first and checked at the end
   // (flags in LDS behind the regions): a row whose pointer is not r * S yields NaN.
+  // (not SEP: a wave's partial sums go to the start of its own X region, which no other
+  //  wave touches: no barrier between the last read of X and the sums)
+  static_assert(PART <= REGION, "partial sums of a wave fit its X region");
+  constexpr int PSTRIDE = SEP ? PART : REGION;        // bytes from one wave's partial sums to the next
   uint8_t *parts = SEP ? xs + nw * REGION : xs;
-  uint32_t *flags = (uint32_t *)(xs + nw * (SEP ? REGION + PART : (REGION > PART ? REGION : PART)));
+  uint32_t *flags = (uint32_t *)(xs + nw * (SEP ? REGION + PART : REGION));
   const int frow = 16 * ((int)blockIdx.x + (int)(threadIdx.x >> 4) * (int)gridDim.x) + (int)(threadIdx.x & 15);
   const bool fcheck = (int)threadIdx.x < 16 * nit && frow < g.rows;
   const uint32_t frp = fcheck ? row_ptr[frow] : 0u;
@@ -526,17 +530,16 @@ __global__ __launch_bounds__(64 * NWMAX) void k_sparse_smallm_ks(const uint32_t 
       if (next_pass) start_pass(j0 + NT);             // (the region is free)
     } else {
       wait_vmem<0>();                                 // a wave that left early may still have X on its way
-      lds_barrier();                                    // every wave is done with its X region
     }
 
-    // ---- partial sums to LDS: tile (it, jj) of wave w at w * PART + (it * NT + jj) * 1024,
+    // ---- partial sums to LDS: tile (it, jj) of wave w at w * PSTRIDE + (it * NT + jj) * 1024,
     //      float 4 * lane + v = D[row 4 (lane >> 4) + v][token lane & 15]
     if (threadIdx.x < 16 * NIT) flags[threadIdx.x] = (fcheck && frp == (uint32_t)frow * S_row) ? 1u : 0u;
 #pragma unroll
     for (int it = 0; it < NIT; ++it)
 #pragma unroll
       for (int jj = 0; jj < NT; ++jj)
-        if (it < nit) *(f4 *)(parts + wave * PART + (it * NT + jj) * 1024 + 16 * lane) = acc[it][jj];
+        if (it < nit) *(f4 *)(parts + wave * PSTRIDE + (it * NT + jj) * 1024 + 16 * lane) = acc[it][jj];
     lds_barrier();
     for (int unit = threadIdx.x; unit < NIT * NT * 256; unit += (int)blockDim.x) {
       const int tj = unit >> 8, it = tj / NT, jj = tj % NT;
@@ -545,7 +548,7 @@ __global__ __launch_bounds__(64 * NWMAX) void k_sparse_smallm_ks(const uint32_t 
       const float *src = (const float *)parts + unit;
       float part[NWMAX];
 #pragma unroll
-      for (int w = 0; w < NWMAX; ++w) part[w] = src[min(w, nw - 1) * (PART / 4)];
+      for (int w = 0; w < NWMAX; ++w) part[w] = src[min(w, nw - 1) * (PSTRIDE / 4)];
       float sum = 0.f;
 #pragma unroll
       for (int w = 0; w < NWMAX; ++w) sum += w < nw ? part[w] : 0.f;
@@ -592,9 +595,9 @@ static hipError_t go_ks(const egt_2bitcsr &w, const uint16_t *X, uint16_t *Y, co
                         int nblocks, hipStream_t stream) {
   const size_t region = N1 ? 16 * KS_TOKEN_N1 : 8 * KS_PAIR;
   const size_t x_bytes = (size_t)nw * region, p_bytes = (size_t)nw * NIT * NT * 1024;
-  // partial sums behind the X regions where the kernel keeps them apart (NT > 1), else in
-  // the same memory; + row-pointer flags
-  const size_t lds = (NT > 1 ? x_bytes + p_bytes : (x_bytes > p_bytes ? x_bytes : p_bytes)) + 64 * NIT;
+  // partial sums behind the X regions where the kernel keeps them apart (NT > 1), else at
+  // the start of each wave's own region; + row-pointer flags
+  const size_t lds = (NT > 1 ? x_bytes + p_bytes : x_bytes) + 64 * NIT;
   return launch(k_sparse_smallm_ks<KIND, NT, NIT, NWMAX, QW, N1>, dim3(nblocks), dim3(64 * nw), lds, stream,
                 w.row_ptr, (const uint8_t *)w.values, (const uint8_t *)w.idx, (const uint8_t *)w.qparams,
                 (const __half *)X, (__half *)Y, g);
