@@ -67,6 +67,28 @@ __device__ __forceinline__ uint32_t spread_idx(uint32_t w, uint32_t m8, uint32_t
   return (t | (t << 2)) & m2;
 }
 
+// Explicit waits around the loads that write LDS directly: they count as vector-memory
+// operations, return in request order with the register loads, and nothing else tells a
+// following LDS read that their data has landed (or a following load of that kind that
+// the reads of the data it replaces are done).  The statements also keep the compiler
+// from moving memory operations across them.
+template <int N>
+__device__ __forceinline__ void wait_vmem() {       // at most N vector-memory operations still pending
+  asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
+}
+__device__ __forceinline__ void wait_lds() {
+  asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+}
+// f(IC<0>), f(IC<1>), ... f(IC<N - 1>): a loop whose index is a compile-time constant
+template <int V>
+struct IC { static constexpr int v = V; };
+template <int I, int N, class F>
+__device__ __forceinline__ void static_for(F &&f) {
+  if constexpr (I < N) {
+    f(IC<I>{});
+    static_for<I + 1, N>(f);
+  }
+}
 // Workgroup barrier that orders LDS traffic only.  __syncthreads() also waits for every
 // outstanding global load and store of the wave; where loads for later work are in flight
 // across the barrier on purpose, that wait would give the overlap away.

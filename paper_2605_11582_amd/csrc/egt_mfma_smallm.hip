@@ -86,28 +86,6 @@ __device__ __forceinline__ uint32_t lane_perm(int byte_addr, uint32_t v) {
 __device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void *p, uint32_t bytes) {
   return __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(p), 0, (int)bytes, 0x00020000);
 }
-// Explicit waits around the loads that write LDS directly: they count as vector-memory
-// operations, return in request order with the register loads, and nothing else tells a
-// following LDS read that their data has landed (or a following load of that kind that
-// the reads of the data it replaces are done).  The statements also keep the compiler
-// from moving memory operations across them.
-template <int N>
-__device__ __forceinline__ void wait_vmem() {       // at most N vector-memory operations still pending
-  asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
-}
-__device__ __forceinline__ void wait_lds() {
-  asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-}
-// f(IC<0>), f(IC<1>), ... f(IC<N - 1>): a loop whose index is a compile-time constant
-template <int V>
-struct IC { static constexpr int v = V; };
-template <int I, int N, class F>
-__device__ __forceinline__ void static_for(F &&f) {
-  if constexpr (I < N) {
-    f(IC<I>{});
-    static_for<I + 1, N>(f);
-  }
-}
 template <int N>
 __device__ __forceinline__ uint32_t quad_bcast(uint32_t v) {     // value of lane N of the 4-lane group
   return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, N * 0x55, 0xf, 0xf, true);
