@@ -352,11 +352,12 @@ __global__ __launch_bounds__(1024) void k_sparse_m1_batch(const GemvBatch b, con
 }
 
 // Shapes the diagonal kernel covers: 2:4; K = 1024 or 2048 (several rows per tile)
-// or a multiple of 64 from 4096 up to 16 tiles per row; INT4 groups of 32 << j.
+// or a multiple of 64 from 4096 up to 8 tiles per row (more would not leave two waves per
+// phase in a 16-wave workgroup to stage x in four pieces per thread); INT4 groups of 32 << j.
 bool sparse_m1_supported(const egt_2bitcsr &w) {
   if (w.n_keep != 2) return false;
   const bool multirow = w.cols == 1024 || w.cols == 2048;
-  if (!multirow && (w.cols < 4096 || w.cols % 64 != 0 || w.cols > 16 * 4096)) return false;
+  if (!multirow && (w.cols < 4096 || w.cols % 64 != 0 || w.cols > 8 * 4096)) return false;
   if (w.val_kind == EGT_VAL_INT4) {
     const int gm = w.group_size / 32;
     if (w.group_size % 32 != 0 || (gm & (gm - 1)) != 0) return false;

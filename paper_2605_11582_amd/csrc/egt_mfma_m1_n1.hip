@@ -34,7 +34,13 @@ struct M1N1Geom {
 
 // QW = {scale, zero} pairs per chunk of 128 dense columns: 1 for groups of 128 and more,
 // 2 for groups of 64, 4 for groups of 32.
-template <int KIND, int TPI, int XP, int QW>
+// NI > 0 (FP16 values): a tile is one row (one phase of it: up to 64 NI pieces of 16 bytes,
+// a piece being 8 slots = 32 dense columns = one 16-bit index word) and load instruction k
+// of a wave reads the contiguous kilobyte of pieces 64 k + lane.  Lane (i, kb) then owns the
+// pieces 64 k + 16 kb + i, k < NI, each good for two matrix instructions (slots 0..3 and
+// 4..7), and column n of B carries the activations under the pieces 64 k + 16 kb + n.
+// NI = 0: every lane reads the 64 B of its own chunk.
+template <int KIND, int TPI, int XP, int QW, int NI>
 __device__ __forceinline__ void k_sparse_m1_n1_body(const uint32_t *__restrict__ row_ptr, const uint8_t *__restrict__ values,
     const uint8_t *__restrict__ idx, const uint8_t *__restrict__ qparams, const __half *__restrict__ x,
     __half *__restrict__ y, const M1N1Geom &g) {
@@ -56,7 +62,9 @@ __device__ __forceinline__ void k_sparse_m1_n1_body(const uint32_t *__restrict__
 
   // ---- x first (16 B pieces, 16 per chunk)
   const int npieces = g.nchunks * 16;
-  const int lds_pieces = multirow ? npieces : g.phases * 1024;
+  constexpr bool LIN = NI > 0;
+  constexpr int XSH = LIN ? 4 : 6;                    // x in LDS: one 16 B pad per 2^XSH pieces
+  const int lds_pieces = LIN ? g.phases * NI * 256 : multirow ? npieces : g.phases * 1024;
   u4 xp[XP];
 #pragma unroll
   for (int j = 0; j < XP; ++j) {
@@ -74,10 +82,21 @@ __device__ __forceinline__ void k_sparse_m1_n1_body(const uint32_t *__restrict__
   }
   u4 nib[TPI][KIND == EGT_VAL_INT4 ? 1 : 4];
   u2 iw[TPI];
+  uint32_t iwl[LIN ? TPI : 1][LIN ? NI : 1];          // LIN: the index word of each piece
   uint32_t qp[TPI][QW];
 #pragma unroll
   for (int t = 0; t < TPI; ++t) {
     const int tr = min(tile0 + t, g.ntiles - 1);
+    if constexpr (LIN) {
+#pragma unroll
+      for (int k = 0; k < NI; ++k) {
+        const uint32_t piece = (uint32_t)min(NI * 64 * phase + 64 * k + lane, 4 * g.nchunks - 1);   // inside the row (clamped)
+        const uint32_t gp = (uint32_t)tr * (uint32_t)(4 * g.nchunks) + piece;
+        nib[t][k] = ld_stream<u4>(values + 16ull * gp);
+        iwl[t][k] = ld_stream<uint16_t>(idx + 2ull * gp);
+      }
+      continue;
+    }
     uint32_t chunk;
     if (multirow) chunk = min((uint32_t)tr * 64u + (uint32_t)cit, g.last_chunk);
     else chunk = (uint32_t)tr * (uint32_t)g.nchunks + (uint32_t)c_ld;
@@ -126,13 +145,31 @@ __device__ __forceinline__ void k_sparse_m1_n1_body(const uint32_t *__restrict__
     if (pi < lds_pieces) {
       u4 v = xp[j];
       if (pi >= npieces) v = u4{0, 0, 0, 0};
-      *(u4 *)(xs + 16 * pi + 16 * (pi >> 6)) = v;
+      *(u4 *)(xs + 16 * pi + 16 * (pi >> XSH)) = v;
     }
   }
   __syncthreads();
   // B operand of instruction m: the 16 dense columns 16 m .. 16 m + 15 of each chunk
   u8v bx[8];
-  {
+  if constexpr (LIN) {
+    // instruction 2 k + e multiplies slots 4 e .. 4 e + 3 (16 dense columns) of the pieces
+    // 64 k + 16 kb + n: x pieces 4 P + 2 e and 4 P + 2 e + 1
+    const int n = lane & 15, b = lane >> 4;
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+      const int kba = 2 * h + (b >> 1), sub = b & 1;
+#pragma unroll
+      for (int k = 0; k < NI; ++k) {
+#pragma unroll
+        for (int e = 0; e < 2; ++e) {
+          const int pi = 4 * (NI * 64 * phase + 64 * k + 16 * kba + n) + 2 * e + sub;
+          const u4 v = *(const u4 *)(xs + 16 * pi + 16 * (pi >> XSH));
+#pragma unroll
+          for (int j = 0; j < 4; ++j) bx[2 * k + e][4 * h + j] = v[j];
+        }
+      }
+    }
+  } else {
     const int n = lane & 15, b = lane >> 4;
 #pragma unroll
     for (int h = 0; h < 2; ++h) {
@@ -163,6 +200,23 @@ __device__ __forceinline__ void k_sparse_m1_n1_body(const uint32_t *__restrict__
         s2[k] = __builtin_amdgcn_perm(qp[t][k], qp[t][k], 0x01000100u);                            // {s, s}
         off[k] = pk_add_f16(__builtin_amdgcn_perm(qp[t][k], qp[t][k], 0x03020302u), g.nib_magic);  // {1024+z, 64+z}
       }
+    }
+    if constexpr (LIN) {
+#pragma unroll
+      for (int k = 0; k < NI; ++k) {
+        const int iword = (int)spread_idx(iwl[t][k], g.m8, g.m4, g.m2);
+#pragma unroll
+        for (int e = 0; e < 2; ++e) {
+          const uint32_t v0 = nib[t][k][2 * e], v1 = nib[t][k][2 * e + 1];
+          const u4 a = {v0 & 0xFFFFu, v0 >> 16, v1 & 0xFFFFu, v1 >> 16};
+          if (e)
+            acc = __builtin_amdgcn_smfmac_f32_16x16x64_f16(__builtin_bit_cast(h8, a), __builtin_bit_cast(h16, bx[2 * k + e]), acc, iword, 0, 1);
+          else
+            acc = __builtin_amdgcn_smfmac_f32_16x16x64_f16(__builtin_bit_cast(h8, a), __builtin_bit_cast(h16, bx[2 * k + e]), acc, iword, 0, 0);
+        }
+      }
+      s[t] = acc[0] + row_shl<1>(acc[1]) + row_shl<2>(acc[2]) + row_shl<3>(acc[3]);
+      continue;
     }
     const uint32_t sp[4] = {spread_idx(iw[t][0] & 0xFFFFu, g.m8, g.m4, g.m2), spread_idx(iw[t][0] >> 16, g.m8, g.m4, g.m2),
                             spread_idx(iw[t][1] & 0xFFFFu, g.m8, g.m4, g.m2), spread_idx(iw[t][1] >> 16, g.m8, g.m4, g.m2)};
@@ -232,29 +286,29 @@ __device__ __forceinline__ void k_sparse_m1_n1_body(const uint32_t *__restrict__
   }
 }
 
-template <int KIND, int TPI, int XP, int QW>
+template <int KIND, int TPI, int XP, int QW, int NI>
 __global__ __launch_bounds__(1024) void k_sparse_m1_n1(const uint32_t *__restrict__ row_ptr,
                                                         const uint8_t *__restrict__ values,
                                                         const uint8_t *__restrict__ idx,
                                                         const uint8_t *__restrict__ qparams,
                                                         const __half *__restrict__ x,
                                                         __half *__restrict__ y, const M1N1Geom g) {
-  k_sparse_m1_n1_body<KIND, TPI, XP, QW>(row_ptr, values, idx, qparams, x, y, g);
+  k_sparse_m1_n1_body<KIND, TPI, XP, QW, NI>(row_ptr, values, idx, qparams, x, y, g);
 }
 
-template <int KIND, int TPI, int XP, int QW>
+template <int KIND, int TPI, int XP, int QW, int NI>
 __global__ __launch_bounds__(1024) void k_sparse_m1_n1_batch(const GemvBatch b, const M1N1Geom g) {
-  k_sparse_m1_n1_body<KIND, TPI, XP, QW>(pick4(b.row_ptr, blockIdx.y), pick4(b.values, blockIdx.y),
+  k_sparse_m1_n1_body<KIND, TPI, XP, QW, NI>(pick4(b.row_ptr, blockIdx.y), pick4(b.values, blockIdx.y),
                                      pick4(b.idx, blockIdx.y), pick4(b.qparams, blockIdx.y),
                                      pick4(b.x, blockIdx.y), pick4(b.y, blockIdx.y), g);
 }
 
 // Shapes covered: 1:4; K = 2048 or 4096 (several rows per tile) or a multiple of 128
-// from 8192 up to 8 tiles per row; INT4 groups of 32 << j.
+// from 8192 up to 4 tiles per row (four waves per phase stage x); INT4 groups of 32 << j.
 bool sparse_m1_n1_supported(const egt_2bitcsr &w) {
   if (w.n_keep != 1) return false;
   const bool multirow = w.cols == 2048 || w.cols == 4096;
-  if (!multirow && (w.cols < 8192 || w.cols % 128 != 0 || w.cols > 8 * 8192)) return false;
+  if (!multirow && (w.cols < 8192 || w.cols % 128 != 0 || w.cols > 4 * 8192)) return false;
   if (w.val_kind == EGT_VAL_INT4) {
     const int gm = w.group_size / 32;
     if (w.group_size % 32 != 0 || (gm & (gm - 1)) != 0) return false;
@@ -275,10 +329,13 @@ hipError_t launch_sparse_m1_n1_batch(const egt_2bitcsr *ws, const uint16_t *cons
   M1N1Geom g;
   g.rows = w.rows;
   g.nchunks = w.cols / 128;
-  const bool multirow = g.nchunks < 64;
+  // FP16 values: one row per tile, contiguous-kilobyte loads (NI load instructions per tile)
+  const bool lin = w.val_kind == EGT_VAL_FP16 && getenv("EGT_M1N1_NOLIN") == nullptr;
+  const int ni = !lin ? 0 : g.nchunks == 16 ? 1 : g.nchunks == 32 ? 2 : 4;
+  const bool multirow = !lin && g.nchunks < 64;
   g.mr_shift = multirow ? (g.nchunks == 16 ? 4 : 5) : -1;
   const int rpt = multirow ? 64 / g.nchunks : 1;
-  g.phases = multirow ? 1 : (g.nchunks + 63) / 64;
+  g.phases = (multirow || lin) ? (g.nchunks + 63) / 64 : (g.nchunks + 63) / 64;
   g.ntiles = (w.rows + rpt - 1) / rpt;
   g.gshift = 0;
   g.groups_per_row = 0;
@@ -290,27 +347,35 @@ hipError_t launch_sparse_m1_n1_batch(const egt_2bitcsr *ws, const uint16_t *cons
   g.m8 = 0x00FF00FFu; g.m4 = 0x0F0F0F0Fu; g.m2 = 0x33333333u;
   g.nib_mask = 0x00F0000Fu; g.nib_magic = 0x54006400u;
   int tpi = g.phases == 1 ? 2 : 4, wpp = 4;
+  if (lin) tpi = ni == 4 ? 2 : 4;
   if (const char *e = getenv("EGT_M1N1_TUNE")) sscanf(e, "%d,%d", &tpi, &wpp);
   if (wpp < 1) wpp = 1;
   if (wpp * g.phases > 16) wpp = 16 / g.phases;
   if (tpi != 1 && tpi != 2 && tpi != 4) tpi = 2;
-  if (w.val_kind == EGT_VAL_FP16 && tpi == 4) tpi = 2;   // 64 B of values per lane and tile
+  if (w.val_kind == EGT_VAL_FP16 && tpi == 4 && ni != 1 && ni != 2) tpi = 2;   // 64 B of values per lane and tile
+  if (lin && ni < 4) tpi = 4;
+  if (lin && ni == 4) tpi = 2;
   if (w.val_kind == EGT_VAL_INT4 && w.group_size < 128) tpi = 2;
   const int nwaves = wpp * g.phases;
   const int tiles_per_block = wpp * tpi;
   const dim3 grid((g.ntiles + tiles_per_block - 1) / tiles_per_block, count), block(64 * nwaves);
-  const int lds_pieces = multirow ? g.nchunks * 16 : g.phases * 1024;
-  g.part_offset = 16 * lds_pieces + 16 * ((lds_pieces + 63) >> 6);
+  const int lds_pieces = lin ? g.phases * ni * 256 : multirow ? g.nchunks * 16 : g.phases * 1024;
+  g.part_offset = lin ? 16 * lds_pieces + 16 * ((lds_pieces + 15) >> 4) : 16 * lds_pieces + 16 * ((lds_pieces + 63) >> 6);
   const size_t lds = g.part_offset + (g.phases > 1 ? sizeof(float) * g.phases * tiles_per_block : 0);
   const int xp = (lds_pieces + 64 * nwaves - 1) / (64 * nwaves);
   if (xp > 4) return hipErrorInvalidConfiguration;
-#define EGT_GO4(KIND, TPI, XP, QW)                                                              \
-  (count > 1 ? launch(k_sparse_m1_n1_batch<KIND, TPI, XP, QW>, grid, block, lds, stream, b, g)      \
-             : launch(k_sparse_m1_n1<KIND, TPI, XP, QW>, grid, block, lds, stream, b.row_ptr[0],   \
+#define EGT_GO5(KIND, TPI, XP, QW, NI)                                                          \
+  (count > 1 ? launch(k_sparse_m1_n1_batch<KIND, TPI, XP, QW, NI>, grid, block, lds, stream, b, g)  \
+             : launch(k_sparse_m1_n1<KIND, TPI, XP, QW, NI>, grid, block, lds, stream, b.row_ptr[0], \
                       b.values[0], b.idx[0], b.qparams[0], b.x[0], b.y[0], g))
+#define EGT_GO4(KIND, TPI, XP, QW) EGT_GO5(KIND, TPI, XP, QW, 0)
 #define EGT_GO3(KIND, TPI, XP) EGT_GO4(KIND, TPI, XP, 1)
 #define EGT_GO(KIND, TPI)                                                                       \
   (xp <= 1 ? EGT_GO3(KIND, TPI, 1) : xp == 2 ? EGT_GO3(KIND, TPI, 2) : EGT_GO3(KIND, TPI, 4))
+#define EGT_GOL(TPI, NI)                                                                        \
+  (xp <= 1 ? EGT_GO5(EGT_VAL_FP16, TPI, 1, 1, NI) : xp == 2 ? EGT_GO5(EGT_VAL_FP16, TPI, 2, 1, NI) \
+                                                            : EGT_GO5(EGT_VAL_FP16, TPI, 4, 1, NI))
+  if (lin) return ni == 1 ? EGT_GOL(4, 1) : ni == 2 ? EGT_GOL(4, 2) : EGT_GOL(2, 4);
   if (w.val_kind == EGT_VAL_INT4 && w.group_size < 128) {   // narrow groups: one launch shape each
     if (w.group_size == 64)
       return xp <= 1 ? EGT_GO4(EGT_VAL_INT4, 2, 1, 2) : xp == 2 ? EGT_GO4(EGT_VAL_INT4, 2, 2, 2)
@@ -332,6 +397,8 @@ hipError_t launch_sparse_m1_n1_batch(const egt_2bitcsr *ws, const uint16_t *cons
 #undef EGT_GO
 #undef EGT_GO3
 #undef EGT_GO4
+#undef EGT_GO5
+#undef EGT_GOL
 }
 
 hipError_t launch_sparse_m1_n1(const egt_2bitcsr &w, const uint16_t *x, uint16_t *y, hipStream_t stream) {

@@ -34,6 +34,11 @@ def _small_case(rows, cols, n, g, kind, seed, drop=0.0):
     # narrow quantisation groups on the matrix-core paths
     (45, 4096, 2, 32, 0), (70, 1024, 2, 32, 0), (21, 11008, 2, 32, 0), (33, 2048, 2, 32, 0),
     (45, 4096, 1, 32, 0), (45, 4096, 1, 64, 0), (21, 11008, 1, 64, 0), (19, 2048, 1, 32, 0), (9, 12288, 1, 32, 0),
+    # the widest rows the tuned kernels take, and wider ones (the generic kernels)
+    (4, 32768, 2, 128, 0), (4, 32768, 1, 128, 0), (3, 32768, 2, 0, 1), (3, 32768, 1, 0, 1),
+    (3, 40960, 2, 128, 0), (3, 36864, 1, 128, 0), (2, 65536, 2, 0, 1),
+    # 1:4 with FP16 values: one, two and four load instructions per row, two phases, a partly filled one
+    (70, 2048, 1, 0, 1), (133, 4096, 1, 0, 1), (40, 8192, 1, 0, 1), (37, 11008, 1, 0, 1), (18, 16384, 1, 0, 1), (9, 20608, 1, 0, 1),
 ])
 def test_sparse_gemv_small(rows, cols, n, g, kind):
     print(f"case sparse_gemv {rows}x{cols} n={n} g={g} kind={kind}", flush=True)
