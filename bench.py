@@ -163,7 +163,23 @@ def main():
         t3, _ = time_loop(torch, lambda i: f3[i % c3](), 1000, 100)
         b3 = algorithmic_bytes(R, K, N, 0, 1)
         extra["config3_sparse_fp16_11008x4096"] = {"us": round(t3 * 1e6, 3), "gbps": round(b3 / t3 / 1e9, 1), "bytes": b3}
+        for M in (2, 4, 16):                          # the same matrix under parallel verification
+            Xm = torch.from_numpy(synth.activation_rows(M, K, synth.seed_for(3) + M).view(np.int16)).to(dev).view(torch.float16)
+            Ym = torch.empty((M, R), dtype=torch.float16, device=dev)
+            fm = [B.prepared_sparse_gemm_smallm(pk3[i], Xm, Ym) for i in range(c3)]
+            tm, _ = time_loop(torch, lambda i: fm[i % c3](), 600, 60)
+            bm = algorithmic_bytes(R, K, N, 0, 1, m=M)
+            extra[f"sparse_fp16_11008x4096_M{M}"] = {"us": round(tm * 1e6, 3), "gbps": round(bm / tm / 1e9, 1), "bytes": bm}
+            del fm
         del pk3
+        p3n = B.pack_2bitcsr(w, B.prune_n4(w, 1), 1, 0, B.VAL_FP16)     # 1:4 with FP16 values
+        c3n = max(2, -(-2 * LLC_BYTES // p3n.nbytes()))
+        pk3n = [p3n.to(dev) for _ in range(c3n)]
+        f3n = [B.prepared_sparse_gemv(pk3n[i], xd, ys[0]) for i in range(c3n)]
+        t3n, _ = time_loop(torch, lambda i: f3n[i % c3n](), 1000, 100)
+        b3n = algorithmic_bytes(R, K, 1, 0, 1)
+        extra["sparse_fp16_1to4_11008x4096"] = {"us": round(t3n * 1e6, 3), "gbps": round(b3n / t3n / 1e9, 1), "bytes": b3n}
+        del pk3n, f3n
         # config 2: dense INT4 4096x4096
         w2 = synth.weights(4096, 4096, synth.seed_for(2))
         q2, qp2 = B.quant_int4(w2, 128)
