@@ -69,6 +69,9 @@ def main():
     ap.add_argument("--extra", action="store_true", help="also time the other configurations")
     ap.add_argument("--calibrate", action="store_true",
                     help="also run a 64 MiB device copy ten times (known traffic, for scaling rocprofv3 counters)")
+    ap.add_argument("--counter-workloads", action="store_true",
+                    help="also launch the other kernels 40 times each on the 11008x4096 shape, untimed "
+                         "(FP16 values, 1:4, M > 1), for rocprofv3 counter runs")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no sharding, no collectives); use --gpus 1",
@@ -122,6 +125,23 @@ def main():
             dst.copy_(src)
         torch.cuda.synchronize()
         del src, dst
+
+    if args.counter_workloads:
+        def launches(pk_host, Ms):
+            n = max(2, -(-2 * LLC_BYTES // pk_host.nbytes()))
+            pks = [pk_host.to(dev) for _ in range(n)]
+            for M in Ms:
+                Xm = torch.from_numpy(synth.activation_rows(M, K, seed + M).view(np.int16)).to(dev).view(torch.float16)
+                Ym = torch.empty((M, R), dtype=torch.float16, device=dev)
+                fs = [B.prepared_sparse_gemv(pks[i], Xm[0], Ym[0]) if M == 1 else
+                      B.prepared_sparse_gemm_smallm(pks[i], Xm, Ym) for i in range(n)]
+                for i in range(40):
+                    fs[i % n]()
+                torch.cuda.synchronize()
+        launches(B.pack_2bitcsr(w, mask, N, 0, B.VAL_FP16), (1, 2, 4, 16))
+        launches(B.pack_2bitcsr(w, B.prune_n4(w, 1), 1, 0, B.VAL_FP16), (1,))
+        launches(p, (2, 16, 64))
+        launches(B.pack_2bitcsr(w, B.prune_n4(w, 1), 1, GRP, B.VAL_INT4), (1, 16))
 
     gbps = nbytes / t_dev / 1e9
     result = {
