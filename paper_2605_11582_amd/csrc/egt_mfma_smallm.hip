@@ -22,17 +22,21 @@
 // straight into a private LDS region (no registers in between, no workgroup barrier).
 // A operand, INT4: lane 4 r + c fetches chunk c of row r of the step, so that four
 // neighbouring lanes read 64 contiguous bytes, and a lane permutation (ds_bpermute)
-// hands the chunk to lane (i, kb) = (r, c) of the matrix instruction.  FP16 values are
-// fetched by lane (i, kb) directly (64 B per lane).
+// hands the chunk to lane (i, kb) = (r, c) of the matrix instruction.  FP16 values at
+// 2:4 use another assignment (LINA below): instruction k takes chunk k and lane (i, kb)
+// its piece kb, what a lane fetches is its operand; at 1:4 lane (i, kb) fetches the 64 B
+// of its chunk.
 // The loads of phase p + 1 are requested while phase p is computed.  Loads return in
 // the order of their requests, so a request for X that follows a request for A waits
 // for A: with NT = 2 token groups the second group of a phase is requested before the
 // A tiles of the next phase and nothing needed soon queues behind the long latency of
 // A.  More than 16 NT tokens are handled in passes over the same rows (the weights of
-// the later passes come from the caches).  After the last phase the waves leave their
-// sums in LDS, one barrier later 4-lane groups add them up over the waves in wave
-// order (a fixed order: the result does not depend on timing) and store four
-// consecutive rows of a token.
+// the later passes come from the caches).  In the last phase nothing is requested any
+// more and the row tiles are consumed as they arrive.  Then the waves leave their sums
+// in LDS, one barrier later 4-lane groups add them up over the waves in wave order (a
+// fixed order: the result does not depend on timing) and store four consecutive rows of
+// a token.  Row tiles past the last one of a workgroup are requested out of range of the
+// buffer resources (zeros, no traffic), so every wave issues the same number of loads.
 // A last step that K fills only partly: chunks past the end are fetched from a clamped
 // (valid) address and enter with scale 0 (FP16: value 0), the pieces of X past the end
 // are overwritten with zeros in LDS.
@@ -119,7 +123,7 @@ __global__ __launch_bounds__(64 * NWMAX) void k_sparse_smallm_ks(const uint32_t 
   constexpr int PART = NIT * NT * 1024;               // bytes of partial sums per wave
   // SEP: the partial sums have LDS of their own behind the X regions, so the first loads
   // of the next pass can be requested before the sums of this pass are added up and
-  // stored (8-wave forms with two token groups per pass; the others share the memory)
+  // stored (8-wave forms with two token groups per pass; the others put them over the X regions)
   constexpr bool SEP = HOLD;
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
