@@ -122,3 +122,44 @@ def test_smallm_kernels_replay_in_a_hip_graph():
         torch.cuda.synchronize()
         for k, (_, Y) in enumerate(cases):
             assert np.array_equal(Y.cpu().numpy().view(np.uint16), eager[k].view(np.uint16)), (rep, k)
+
+
+def test_two_streams_at_once_give_the_serial_results():
+    # the library keeps no state between calls: products enqueued on two streams (default
+    # priority) at the same time equal the ones computed one after the other, bit for bit
+    torch = G.torch_mod()
+    w = synth.weights(3000, 4096, 8800)
+    p = B.pack_2bitcsr(w, B.prune_n4(w, 2), 2, 128, B.VAL_INT4).to("cuda")
+    pf = B.pack_2bitcsr(w, B.prune_n4(w, 2), 2, 0, B.VAL_FP16).to("cuda")
+    q, qp = B.quant_int4(w, 128)
+    qd, qpd = G.to_dev(q), G.to_dev(qp)
+    x = G.to_dev(synth.activations(4096, 8801).view(np.uint16)).view(torch.float16)
+    X = G.to_dev(synth.activation_rows(16, 4096, 8802).view(np.uint16)).view(torch.float16)
+
+    def work(tag, stream, out):
+        for rep in range(8):
+            B.sparse_gemv(p, x, out["a"], stream=stream)
+            B.sparse_gemm_smallm(p, X, out["b"], stream=stream)
+            B.sparse_gemv(pf, x, out["c"], stream=stream)
+            B.int4_gemv(qd, qpd, 3000, 4096, 128, x, out["d"], stream=stream)
+            B.sparse_gemm_smallm(pf, X[:3], out["e"], stream=stream)
+
+    def outputs():
+        return {"a": torch.empty(3000, dtype=torch.float16, device="cuda"),
+                "b": torch.empty((16, 3000), dtype=torch.float16, device="cuda"),
+                "c": torch.empty(3000, dtype=torch.float16, device="cuda"),
+                "d": torch.empty(3000, dtype=torch.float16, device="cuda"),
+                "e": torch.empty((3, 3000), dtype=torch.float16, device="cuda")}
+
+    serial = outputs()
+    work("serial", None, serial)
+    torch.cuda.synchronize()
+    s1, s2 = torch.cuda.Stream(), torch.cuda.Stream()
+    o1, o2 = outputs(), outputs()
+    print("case two streams", flush=True)
+    work("s1", s1, o1)
+    work("s2", s2, o2)
+    s1.synchronize()
+    s2.synchronize()
+    for k in serial:
+        assert torch.equal(serial[k], o1[k]) and torch.equal(serial[k], o2[k]), k
