@@ -132,7 +132,11 @@ __global__ __launch_bounds__(64 * NWMAX) void k_sparse_smallm_ks(const uint32_t 
   // row, chunk this lane fetches (LINA: of the index words only)
   const int li = (INT4 || LINA) ? (lane >> 2) : i, lc = (INT4 || LINA) ? (lane & 3) : kb;
   const int from = 4 * (4 * i + kb);                  // lane that fetched the chunk of lane (i, kb), as a byte address
-  const int nit = (g.ntiles - (int)blockIdx.x + (int)gridDim.x - 1) / (int)gridDim.x;   // <= NIT
+  // Row tiles of this workgroup: blockIdx.x + k * gridDim.x, k < mytiles, taken NIT at a time
+  // (rounds); round rr holds tiles_of(rr) of them.
+  const int mytiles = (g.ntiles - (int)blockIdx.x + (int)gridDim.x - 1) / (int)gridDim.x;
+  const int rounds = (mytiles + NIT - 1) / NIT;
+  auto tiles_of = [&](int rr) { return min(NIT, mytiles - rr * NIT); };
   const int phases = (g.nsteps + nw - 1) / nw;
   const uint32_t magic = in_vgpr(g.nib_magic);
   const uint32_t S_row = (uint32_t)g.nchunks * 32u;
@@ -146,18 +150,22 @@ __global__ __launch_bounds__(64 * NWMAX) void k_sparse_smallm_ks(const uint32_t 
   constexpr int PSTRIDE = SEP ? PART : REGION;        // bytes from one wave's partial sums to the next
   uint8_t *parts = SEP ? xs + nw * REGION : xs;
   uint32_t *flags = (uint32_t *)(xs + nw * (SEP ? REGION + PART : REGION));
-  const int frow = 16 * ((int)blockIdx.x + (int)(threadIdx.x >> 4) * (int)gridDim.x) + (int)(threadIdx.x & 15);
-  const bool fcheck = (int)threadIdx.x < 16 * nit && frow < g.rows;
-  const uint32_t frp = fcheck ? row_ptr[frow] : 0u;
+  auto flag_row = [&](int rr) {                       // the row whose pointer this thread checks in round rr
+    return 16 * ((int)blockIdx.x + (rr * NIT + (int)(threadIdx.x >> 4)) * (int)gridDim.x) + (int)(threadIdx.x & 15);
+  };
+  auto flag_checked = [&](int rr) { return (int)threadIdx.x < 16 * tiles_of(rr) && flag_row(rr) < g.rows; };
+  auto load_rp = [&](int rr) { return flag_checked(rr) ? row_ptr[flag_row(rr)] : 0u; };
+  uint32_t frp = load_rp(0), frp_next = 0;
 
   const __amdgpu_buffer_rsrc_t r_val = make_rsrc(values, g.val_bytes), r_idx = make_rsrc(idx, g.idx_bytes);
   const __amdgpu_buffer_rsrc_t r_qp = make_rsrc(qparams, g.qp_bytes), r_x = make_rsrc(X, g.x_bytes);
-  auto load_a = [&](ATile<KIND, QW> &a, int it, int step) {
-    // A tile past the workgroup's last one is requested out of range of the buffers: such a
+  auto load_a = [&](ATile<KIND, QW> &a, int it, int step, int rr) {
+    // A tile past the last one of the round is requested out of range of the buffers: such a
     // request returns zeros and moves no data (the count of requests per phase stays fixed).
-    const bool on = it < nit;                                                 // uniform
+    const int nit_r = tiles_of(rr);
+    const bool on = it < nit_r;                                               // uniform
     const uint32_t off_range = 0xFFFFFFF0u;
-    const int rt = (int)blockIdx.x + min(it, nit - 1) * (int)gridDim.x;
+    const int rt = (int)blockIdx.x + (rr * NIT + min(it, nit_r - 1)) * (int)gridDim.x;
     const int s = min(step, g.nsteps - 1);
     // (the lane offsets are recomputed at every request: kept across the loops they would
     //  occupy a dozen registers)
@@ -355,17 +363,19 @@ __global__ __launch_bounds__(64 * NWMAX) void k_sparse_smallm_ks(const uint32_t 
 
   ATile<KIND, QW> raw[NIT], raw2[DEEP ? NIT : 1];
   // first requests of a pass: X and the A tiles of phase 0 (DEEP: and the tiles of phase 1)
-  auto start_pass = [&](int j) {
+  auto start_pass = [&](int rr, int j) {
     dma_x(j, wave);
 #pragma unroll
-    for (int it = 0; it < NIT; ++it) load_a(raw[it], it, wave);
+    for (int it = 0; it < NIT; ++it) load_a(raw[it], it, wave, rr);
     if (DEEP && phases > 1) {
 #pragma unroll
-      for (int it = 0; it < NIT; ++it) load_a(raw2[it], it, wave + nw);
+      for (int it = 0; it < NIT; ++it) load_a(raw2[it], it, wave + nw, rr);
     }
   };
-  start_pass(0);
-  for (int j0 = 0; j0 < ngroups; j0 += NT) {          // passes of NT token groups
+  start_pass(0, 0);
+  int r = 0;                                          // the round being computed
+  for (int j0 = 0;;) {                                // work items: (round r, pass of NT token groups from j0)
+    const int nit = tiles_of(r);
     f4 acc[NIT][NT];
 #pragma unroll
     for (int it = 0; it < NIT; ++it)
@@ -417,7 +427,7 @@ __global__ __launch_bounds__(64 * NWMAX) void k_sparse_smallm_ks(const uint32_t 
           operands(t[it], step, av, iwv);
           mfma_step(av, iwv, bx, acc[it][0]);
         }
-        if (p + 2 < phases) load_a(cur[it], it, step + 2 * nw);
+        if (p + 2 < phases) load_a(cur[it], it, step + 2 * nw, r);
       }
     };
     if constexpr (DEEP) {
@@ -471,7 +481,7 @@ __global__ __launch_bounds__(64 * NWMAX) void k_sparse_smallm_ks(const uint32_t 
         else if (more) dma_x(j0, step + nw);
         if (more) {
 #pragma unroll
-          for (int it = 0; it < NIT; ++it) load_a(raw[it], it, step + nw);
+          for (int it = 0; it < NIT; ++it) load_a(raw[it], it, step + nw, r);
         }
         u4 held[NIT][NM];
         uint32_t hiw[NIT][NM / 2];
@@ -503,20 +513,26 @@ __global__ __launch_bounds__(64 * NWMAX) void k_sparse_smallm_ks(const uint32_t 
             operands(t[it], step, av, iwv);
             mfma_step(av, iwv, bx, acc[it][0]);
           }
-          if (more) load_a(raw[it], it, step + nw);  // into the registers this tile has just left
+          if (more) load_a(raw[it], it, step + nw, r);  // into the registers this tile has just left
         }
       }
     }
-    const bool next_pass = j0 + NT < ngroups;
+    // the next work item: the next pass over the same row tiles, else the next round
+    const bool same_round = j0 + NT < ngroups;
+    const int rn = same_round ? r : r + 1, jn = same_round ? j0 + NT : 0;
+    const bool more_work = rn < rounds;                // uniform over the workgroup
     if (SEP) {
-      if (next_pass) start_pass(j0 + NT);             // (the region is free)
+      if (more_work) {                                // (the region is free)
+        if (!same_round) frp_next = load_rp(rn);
+        start_pass(rn, jn);
+      }
     } else {
       wait_vmem<0>();                                 // a wave that left early may still have X on its way
     }
 
     // ---- partial sums to LDS: tile (it, jj) of wave w at w * PSTRIDE + (it * NT + jj) * 1024,
     //      float 4 * lane + v = D[row 4 (lane >> 4) + v][token lane & 15]
-    if (threadIdx.x < 16 * NIT) flags[threadIdx.x] = (fcheck && frp == (uint32_t)frow * S_row) ? 1u : 0u;
+    if (threadIdx.x < 16 * NIT) flags[threadIdx.x] = (flag_checked(r) && frp == (uint32_t)flag_row(r) * S_row) ? 1u : 0u;
 #pragma unroll
     for (int it = 0; it < NIT; ++it)
 #pragma unroll
@@ -534,7 +550,7 @@ __global__ __launch_bounds__(64 * NWMAX) void k_sparse_smallm_ks(const uint32_t 
       float sum = 0.f;
 #pragma unroll
       for (int w = 0; w < NWMAX; ++w) sum += w < nw ? part[w] : 0.f;
-      const int row0 = 16 * ((int)blockIdx.x + it * (int)gridDim.x) + 4 * (sl >> 4);
+      const int row0 = 16 * ((int)blockIdx.x + (r * NIT + it) * (int)gridDim.x) + 4 * (sl >> 4);
       const int row = row0 + v;
       const int tok = 16 * (j0 + jj) + (sl & 15);
       uint32_t hv = 0x7E00u;
@@ -549,9 +565,15 @@ __global__ __launch_bounds__(64 * NWMAX) void k_sparse_smallm_ks(const uint32_t 
         }
       }
     }
-    if (!next_pass) break;
-    lds_barrier();                                    // the next pass writes the partial sums (and X regions) again
-    if (!SEP) start_pass(j0 + NT);
+    if (!more_work) break;
+    lds_barrier();                                    // the next work item writes the partial sums (and X regions) again
+    if (!SEP) {
+      if (!same_round) frp_next = load_rp(rn);
+      start_pass(rn, jn);
+    }
+    if (!same_round) frp = frp_next;
+    r = rn;
+    j0 = jn;
   }
 }
 
@@ -617,14 +639,12 @@ hipError_t launch_sparse_smallm(const egt_2bitcsr &w, const uint16_t *X, int64_t
   // (more than 16 tokens at 2:4: two token groups per pass).
   const bool wide = n1 || M > 16 || !int4;
   const bool f16x = !int4 && !n1 && M <= 16;          // FP16 values at 2:4, one token group
-  const int nit_max = wide ? 4 : 3;
   int nwmax = wide ? 8 : 16, blocks_per_cu = 1;
   if (f16x && g.ntiles <= 256) nwmax = 16;            // one tile per workgroup: 16 waves of 128 registers
   if (const char *e = getenv("EGT_SM_TUNE")) sscanf(e, "%d,%d", &nwmax, &blocks_per_cu);
   if (nwmax < 1 || nwmax > ((wide && !f16x) ? 8 : 16)) return hipErrorInvalidValue;
   const int nw = g.nsteps < nwmax ? g.nsteps : nwmax;
-  int nblocks = 256 * blocks_per_cu;
-  if (nblocks * nit_max < g.ntiles) nblocks = (g.ntiles + nit_max - 1) / nit_max;
+  int nblocks = 256 * blocks_per_cu;                  // more row tiles than nblocks * NIT: rounds in the kernel
   if (nblocks > g.ntiles) nblocks = g.ntiles;
   const bool one = nblocks == g.ntiles;               // one row tile per workgroup
 #define EGT_KS(KIND, NT, NIT, NWMAX, QW, N1) go_ks<KIND, NT, NIT, NWMAX, QW, N1>(w, X, Y, g, nw, nblocks, stream)

@@ -241,7 +241,12 @@ def test_smallm_small_shapes(M):
     (300, 8704, 2, 128, 0, 9),
     (4100, 512, 2, 0, 1, 5),        # FP16 values
     (4100, 512, 2, 0, 1, 48),
-    (13000, 256, 2, 128, 0, 3),     # more row tiles than three per workgroup on 256 workgroups
+    (13000, 256, 2, 128, 0, 3),     # more row tiles than three per workgroup on 256 workgroups: two rounds
+    (20000, 512, 2, 128, 0, 40),    # rounds x passes: 1250 row tiles, three token groups, two per pass
+    (17000, 640, 1, 128, 0, 20),    # the same at 1:4 (one token group per pass), partly filled last step
+    (20000, 2304, 2, 0, 1, 9),      # rounds with FP16 values (tiles requested two phases ahead)
+    (13000, 320, 2, 64, 0, 16),     # rounds with a partly filled last step
+    (33000, 128, 2, 128, 0, 5),     # nine row tiles per workgroup: three rounds, one wave
     (4200, 512, 2, 32, 0, 6),       # groups of 32 columns: two {scale, zero} pairs per chunk
     (4200, 512, 2, 32, 0, 30),
     (50, 8704, 2, 32, 0, 16),
