@@ -97,7 +97,8 @@ __device__ __forceinline__ uint32_t quad_bcast(uint32_t v) {     // value of lan
 
 // KIND: INT4 or FP16 values.  NT: token groups per pass.  NIT: row tiles per workgroup.
 // NWMAX: waves per workgroup at most.  QW: {scale, zero} pairs per chunk.  N1: 1:4.
-template <int KIND, int NT, int NIT, int NWMAX, int QW, bool N1>
+// RND: a workgroup may own more than NIT row tiles and takes them in rounds.
+template <int KIND, int NT, int NIT, int NWMAX, int QW, bool N1, bool RND>
 __global__ __launch_bounds__(64 * NWMAX) void k_sparse_smallm_ks(const uint32_t *__restrict__ row_ptr,
                                                                   const uint8_t *__restrict__ values,
                                                                   const uint8_t *__restrict__ idx,
@@ -135,8 +136,8 @@ __global__ __launch_bounds__(64 * NWMAX) void k_sparse_smallm_ks(const uint32_t 
   // Row tiles of this workgroup: blockIdx.x + k * gridDim.x, k < mytiles, taken NIT at a time
   // (rounds); round rr holds tiles_of(rr) of them.
   const int mytiles = (g.ntiles - (int)blockIdx.x + (int)gridDim.x - 1) / (int)gridDim.x;
-  const int rounds = (mytiles + NIT - 1) / NIT;
-  auto tiles_of = [&](int rr) { return min(NIT, mytiles - rr * NIT); };
+  const int rounds = RND ? (mytiles + NIT - 1) / NIT : 1;
+  auto tiles_of = [&](int rr) { return RND ? min(NIT, mytiles - rr * NIT) : mytiles; };
   const int phases = (g.nsteps + nw - 1) / nw;
   const uint32_t magic = in_vgpr(g.nib_magic);
   const uint32_t S_row = (uint32_t)g.nchunks * 32u;
@@ -150,22 +151,24 @@ __global__ __launch_bounds__(64 * NWMAX) void k_sparse_smallm_ks(const uint32_t 
   constexpr int PSTRIDE = SEP ? PART : REGION;        // bytes from one wave's partial sums to the next
   uint8_t *parts = SEP ? xs + nw * REGION : xs;
   uint32_t *flags = (uint32_t *)(xs + nw * (SEP ? REGION + PART : REGION));
+  const int frow0 = 16 * ((int)blockIdx.x + (int)(threadIdx.x >> 4) * (int)gridDim.x) + (int)(threadIdx.x & 15);
   auto flag_row = [&](int rr) {                       // the row whose pointer this thread checks in round rr
-    return 16 * ((int)blockIdx.x + (rr * NIT + (int)(threadIdx.x >> 4)) * (int)gridDim.x) + (int)(threadIdx.x & 15);
+    return RND ? frow0 + 16 * rr * NIT * (int)gridDim.x : frow0;
   };
   auto flag_checked = [&](int rr) { return (int)threadIdx.x < 16 * tiles_of(rr) && flag_row(rr) < g.rows; };
   auto load_rp = [&](int rr) { return flag_checked(rr) ? row_ptr[flag_row(rr)] : 0u; };
-  uint32_t frp = load_rp(0), frp_next = 0;
+  const bool fcheck0 = flag_checked(0);
+  uint32_t frp = fcheck0 ? row_ptr[frow0] : 0u, frp_next = 0;
 
   const __amdgpu_buffer_rsrc_t r_val = make_rsrc(values, g.val_bytes), r_idx = make_rsrc(idx, g.idx_bytes);
   const __amdgpu_buffer_rsrc_t r_qp = make_rsrc(qparams, g.qp_bytes), r_x = make_rsrc(X, g.x_bytes);
   auto load_a = [&](ATile<KIND, QW> &a, int it, int step, int rr) {
     // A tile past the last one of the round is requested out of range of the buffers: such a
     // request returns zeros and moves no data (the count of requests per phase stays fixed).
-    const int nit_r = tiles_of(rr);
+    const int nit_r = RND ? tiles_of(rr) : mytiles;
     const bool on = it < nit_r;                                               // uniform
     const uint32_t off_range = 0xFFFFFFF0u;
-    const int rt = (int)blockIdx.x + (rr * NIT + min(it, nit_r - 1)) * (int)gridDim.x;
+    const int rt = (int)blockIdx.x + ((RND ? rr * NIT : 0) + min(it, nit_r - 1)) * (int)gridDim.x;
     const int s = min(step, g.nsteps - 1);
     // (the lane offsets are recomputed at every request: kept across the loops they would
     //  occupy a dozen registers)
@@ -374,7 +377,7 @@ __global__ __launch_bounds__(64 * NWMAX) void k_sparse_smallm_ks(const uint32_t 
   };
   start_pass(0, 0);
   int r = 0;                                          // the round being computed
-  for (int j0 = 0;;) {                                // work items: (round r, pass of NT token groups from j0)
+  for (int j0 = 0; RND || j0 < ngroups;) {            // work items: (round r, pass of NT token groups from j0)
     const int nit = tiles_of(r);
     f4 acc[NIT][NT];
 #pragma unroll
@@ -519,8 +522,8 @@ __global__ __launch_bounds__(64 * NWMAX) void k_sparse_smallm_ks(const uint32_t 
     }
     // the next work item: the next pass over the same row tiles, else the next round
     const bool same_round = j0 + NT < ngroups;
-    const int rn = same_round ? r : r + 1, jn = same_round ? j0 + NT : 0;
-    const bool more_work = rn < rounds;                // uniform over the workgroup
+    const int rn = (!RND || same_round) ? r : r + 1, jn = same_round ? j0 + NT : 0;
+    const bool more_work = RND ? rn < rounds : same_round;   // uniform over the workgroup
     if (SEP) {
       if (more_work) {                                // (the region is free)
         if (!same_round) frp_next = load_rp(rn);
@@ -532,7 +535,8 @@ __global__ __launch_bounds__(64 * NWMAX) void k_sparse_smallm_ks(const uint32_t 
 
     // ---- partial sums to LDS: tile (it, jj) of wave w at w * PSTRIDE + (it * NT + jj) * 1024,
     //      float 4 * lane + v = D[row 4 (lane >> 4) + v][token lane & 15]
-    if (threadIdx.x < 16 * NIT) flags[threadIdx.x] = (flag_checked(r) && frp == (uint32_t)flag_row(r) * S_row) ? 1u : 0u;
+    if (threadIdx.x < 16 * NIT)
+      flags[threadIdx.x] = ((RND ? flag_checked(r) : fcheck0) && frp == (uint32_t)flag_row(r) * S_row) ? 1u : 0u;
 #pragma unroll
     for (int it = 0; it < NIT; ++it)
 #pragma unroll
@@ -594,7 +598,7 @@ bool sparse_smallm_supported(const egt_2bitcsr &w, int64_t ldx, int M) {
   return true;
 }
 
-template <int KIND, int NT, int NIT, int NWMAX, int QW, bool N1>
+template <int KIND, int NT, int NIT, int NWMAX, int QW, bool N1, bool RND>
 static hipError_t go_ks(const egt_2bitcsr &w, const uint16_t *X, uint16_t *Y, const SmallMKsGeom &g, int nw,
                         int nblocks, hipStream_t stream) {
   const size_t region = N1 ? 16 * KS_TOKEN_N1 : 8 * KS_PAIR;
@@ -602,7 +606,7 @@ static hipError_t go_ks(const egt_2bitcsr &w, const uint16_t *X, uint16_t *Y, co
   // partial sums behind the X regions where the kernel keeps them apart (NT > 1), else at
   // the start of each wave's own region; + row-pointer flags
   const size_t lds = (NT > 1 ? x_bytes + p_bytes : x_bytes) + 64 * NIT;
-  return launch(k_sparse_smallm_ks<KIND, NT, NIT, NWMAX, QW, N1>, dim3(nblocks), dim3(64 * nw), lds, stream,
+  return launch(k_sparse_smallm_ks<KIND, NT, NIT, NWMAX, QW, N1, RND>, dim3(nblocks), dim3(64 * nw), lds, stream,
                 w.row_ptr, (const uint8_t *)w.values, (const uint8_t *)w.idx, (const uint8_t *)w.qparams,
                 (const __half *)X, (__half *)Y, g);
 }
@@ -647,7 +651,10 @@ hipError_t launch_sparse_smallm(const egt_2bitcsr &w, const uint16_t *X, int64_t
   int nblocks = 256 * blocks_per_cu;                  // more row tiles than nblocks * NIT: rounds in the kernel
   if (nblocks > g.ntiles) nblocks = g.ntiles;
   const bool one = nblocks == g.ntiles;               // one row tile per workgroup
-#define EGT_KS(KIND, NT, NIT, NWMAX, QW, N1) go_ks<KIND, NT, NIT, NWMAX, QW, N1>(w, X, Y, g, nw, nblocks, stream)
+  // (NIT > 1: the form with rounds only where a workgroup owns more than NIT row tiles)
+#define EGT_KS(KIND, NT, NIT, NWMAX, QW, N1)                                                     \
+  ((NIT > 1 && (int64_t)nblocks * NIT < g.ntiles) ? go_ks<KIND, NT, NIT, NWMAX, QW, N1, (NIT > 1)>(w, X, Y, g, nw, nblocks, stream) \
+                                                  : go_ks<KIND, NT, NIT, NWMAX, QW, N1, false>(w, X, Y, g, nw, nblocks, stream))
   if (n1) {
     if (!int4) return one ? EGT_KS(EGT_VAL_FP16, 1, 1, 8, 1, true) : EGT_KS(EGT_VAL_FP16, 1, 4, 8, 1, true);
     if (qw == 4) return one ? EGT_KS(EGT_VAL_INT4, 1, 1, 8, 4, true) : EGT_KS(EGT_VAL_INT4, 1, 4, 8, 4, true);
