@@ -281,6 +281,7 @@ def test_smallm_tile_and_wave_shapes(rows, cols, n, g, kind, M):
     (33, 4096, 64, 2), (33, 4096, 256, 4), (19, 4096, 4096, 3),      # other group sizes
     (1000, 4096, 128, 4), (1003, 4096, 128, 2),                      # many workgroups, ragged rows
     (9000, 4096, 128, 2),                                            # more rows than the four-token form takes
+    (300, 8192, 128, 2), (77, 4160, 64, 2), (1000, 6144, 256, 2),    # two tokens, two tiles per row (the second partly filled)
 ])
 def test_few_tokens_on_the_row_per_wave_mapping(rows, cols, g, M):
     # M = 2..4 at 2:4 INT4 with K >= 4096 runs on the M = 1 kernel's mapping (the weights are
