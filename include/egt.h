@@ -87,7 +87,7 @@ typedef struct {
 } egt_2bitcsr;
 
 /* Text for a status code (static storage, never NULL). */
-const char *egt_status_str(int status);
+const char *egt_status_str(egt_status status);
 
 /* Text of the HIP error behind the most recent EGT_ERR_HIP returned to the
  * calling thread ("no error" if there was none).  Diagnostic aid. */
@@ -152,7 +152,7 @@ egt_status egt_unpack_2bitcsr(const egt_2bitcsr *in, uint16_t *w_dense, int64_t 
 /* HOST.  Dense group-wise INT4 quantiser of the earlier "Gemv" kernel that
  * Sec. 3.3 starts from: every column kept, same quantiser as above.
  * q: rows x cols/2 bytes (column c in byte c>>1, low nibble for even c);
- * qparams: [rows][cols/group][2] FP16 bits.  cols % group == 0, group % 8 == 0. */
+ * qparams: [rows][cols/group][2] FP16 bits.  cols % group == 0, group % 4 == 0. */
 egt_status egt_quant_int4(const uint16_t *w, int64_t ldw, int rows, int cols, int group,
                           uint8_t *q, uint16_t *qparams);
 

@@ -329,6 +329,12 @@ def gemv(p: dict, x):
     if x.shape != (p["cols"],):
         raise ValueError("x length")
     col, w_hat, _ = decode_2bitcsr(p)
+    return gemv_decoded(col, w_hat, x)
+
+
+def gemv_decoded(col, w_hat, x):
+    """The product step of `gemv` alone, on an already decoded matrix (per-slot dense
+    column and weight, as `decode_2bitcsr` returns them); x is float64."""
     prod = w_hat * x[col]
     return prod.sum(axis=1), np.abs(prod).sum(axis=1)
 

@@ -229,7 +229,7 @@ def quant_int4(w: np.ndarray, group: int):
     w = _row_major(_f16_bits(w))
     rows, cols = w.shape
     if cols % 2 or group <= 0 or cols % group:
-        _check(2)
+        _check(2)                                        # EGT_ERR_SHAPE, before the buffers are sized
     q = np.empty((rows, cols // 2), dtype=np.uint8)
     qparams = np.empty((rows, cols // group, 2), dtype=np.uint16)
     _check(lib().egt_quant_int4(_np_ptr(w), _ld(w), rows, cols, group, _np_ptr(q), _np_ptr(qparams)))
@@ -265,21 +265,63 @@ def _dev(t):
     return t.data_ptr()
 
 
+# The C ABI sees pointers only: a tensor of the wrong type or too short would become an
+# out-of-bounds access on the device, so sizes and types are checked here, on the host.
+def _need(t, nbytes: int, what: str, f16: bool = False):
+    import torch
+    if f16 and t.dtype != torch.float16:
+        raise ValueError(f"{what}: expected a float16 tensor, got {t.dtype}")
+    if t.numel() * t.element_size() < nbytes:
+        raise ValueError(f"{what}: {t.numel() * t.element_size()} bytes, needs {nbytes}")
+    return _dev(t)
+
+
+def _check_packed_dev(p: "Packed") -> None:
+    b = sizes(p.rows, p.cols, p.n_keep, p.group, p.val_kind)
+    for name, nb in zip(("row_ptr", "values", "idx", "qparams"), b):
+        t = getattr(p, name)
+        if t is None:
+            if nb and name != "qparams":
+                raise ValueError(f"packed matrix: {name} is missing")
+            continue
+        _need(t, nb, "packed matrix " + name)
+
+
+def _check_int4_dev(q, qparams, rows: int, cols: int, group: int) -> None:
+    if rows < 0 or cols < 0 or group <= 0 or cols % group:
+        return                                           # the library reports the shape error
+    _need(q, rows * (cols // 2), "q")
+    _need(qparams, 4 * rows * (cols // group), "qparams")
+
+
 def int4_gemv(q, qparams, rows: int, cols: int, group: int, x, y, stream=None) -> None:
     """q, qparams, x, y: device tensors (uint8 / int16-viewable / float16 / float16)."""
-    _check(lib().egt_int4_gemv(_dev(q), _dev(qparams), rows, cols, group, _dev(x), _dev(y),
-                               _stream_ptr(stream)))
+    _check_int4_dev(q, qparams, rows, cols, group)
+    _check(lib().egt_int4_gemv(_dev(q), _dev(qparams), rows, cols, group, _need(x, 2 * cols, "x", True),
+                               _need(y, 2 * rows, "y", True), _stream_ptr(stream)))
 
 
 def sparse_gemv(p: Packed, x, y, stream=None) -> None:
     v = p.view()
-    _check(lib().egt_sparse_gemv(C.byref(v), _dev(x), _dev(y), _stream_ptr(stream)))
+    _check_packed_dev(p)
+    _check(lib().egt_sparse_gemv(C.byref(v), _need(x, 2 * p.cols, "x", True), _need(y, 2 * p.rows, "y", True),
+                                 _stream_ptr(stream)))
+
+
+def _check_xy(p: "Packed", X, Y) -> None:
+    import torch
+    if X.dim() != 2 or Y.dim() != 2 or (X.shape[1] > 1 and X.stride(1) != 1) or (Y.shape[1] > 1 and Y.stride(1) != 1):
+        raise ValueError("X and Y must be row-major 2-D tensors")
+    if not (X.is_cuda and Y.is_cuda) or X.dtype != torch.float16 or Y.dtype != torch.float16:
+        raise ValueError("X and Y must be float16 device tensors")
+    if X.shape[1] != p.cols or tuple(Y.shape) != (X.shape[0], p.rows):
+        raise ValueError(f"X must be (M, {p.cols}) and Y (M, {p.rows}); got {tuple(X.shape)} and {tuple(Y.shape)}")
+    _check_packed_dev(p)
 
 
 def sparse_gemm_smallm(p: Packed, X, Y, stream=None) -> None:
     """X: (M, K) float16 device tensor, Y: (M, R) float16 device tensor; rows may be strided."""
-    if X.dim() != 2 or Y.dim() != 2 or X.stride(1) != 1 or Y.stride(1) != 1:
-        raise ValueError("X and Y must be row-major 2-D tensors")
+    _check_xy(p, X, Y)
     v = p.view()
     _check(lib().egt_sparse_gemm_smallm(C.byref(v), X.data_ptr(), X.stride(0), Y.data_ptr(),
                                         Y.stride(0), X.shape[0], _stream_ptr(stream)))
@@ -291,7 +333,8 @@ def sparse_gemm_smallm(p: Packed, X, Y, stream=None) -> None:
 # to launch elsewhere, e.g. on a capturing stream.
 def prepared_sparse_gemv(p: Packed, x, y, stream=None):
     fn, v = lib().egt_sparse_gemv, p.view()
-    ref, xp, yp, sp = C.byref(v), _dev(x), _dev(y), _stream_ptr(stream)
+    _check_packed_dev(p)
+    ref, xp, yp, sp = C.byref(v), _need(x, 2 * p.cols, "x", True), _need(y, 2 * p.rows, "y", True), _stream_ptr(stream)
 
     def call(stream_ptr=sp, _keep=(v, p, x, y)):
         st = fn(ref, xp, yp, stream_ptr)
@@ -302,6 +345,7 @@ def prepared_sparse_gemv(p: Packed, x, y, stream=None):
 
 def prepared_sparse_gemm_smallm(p: Packed, X, Y, stream=None):
     fn, v = lib().egt_sparse_gemm_smallm, p.view()
+    _check_xy(p, X, Y)
     args = (C.byref(v), X.data_ptr(), X.stride(0), Y.data_ptr(), Y.stride(0), X.shape[0])
     sp = _stream_ptr(stream)
 
@@ -314,7 +358,8 @@ def prepared_sparse_gemm_smallm(p: Packed, X, Y, stream=None):
 
 def prepared_int4_gemv(q, qparams, rows: int, cols: int, group: int, x, y, stream=None):
     fn = lib().egt_int4_gemv
-    args = (_dev(q), _dev(qparams), rows, cols, group, _dev(x), _dev(y))
+    _check_int4_dev(q, qparams, rows, cols, group)
+    args = (_dev(q), _dev(qparams), rows, cols, group, _need(x, 2 * cols, "x", True), _need(y, 2 * rows, "y", True))
     sp = _stream_ptr(stream)
 
     def call(stream_ptr=sp, _keep=(q, qparams, x, y)):
@@ -331,6 +376,10 @@ def _ptr_array(tensors):
 def prepared_sparse_gemv_batch(ps, xs, ys, stream=None):
     """One launch for len(ps) identically shaped matrices: ys[k] = W[k].xs[k]."""
     fn = lib().egt_sparse_gemv_batch
+    for p, x, y in zip(ps, xs, ys):
+        _check_packed_dev(p)
+        _need(x, 2 * p.cols, "x", True)
+        _need(y, 2 * p.rows, "y", True)
     views = (View * len(ps))(*[p.view() for p in ps])
     xa, ya, n, sp = _ptr_array(xs), _ptr_array(ys), len(ps), _stream_ptr(stream)
 
@@ -343,6 +392,10 @@ def prepared_sparse_gemv_batch(ps, xs, ys, stream=None):
 
 def prepared_int4_gemv_batch(qs, qparams, rows: int, cols: int, group: int, xs, ys, stream=None):
     fn = lib().egt_int4_gemv_batch
+    for q, qp, x, y in zip(qs, qparams, xs, ys):
+        _check_int4_dev(q, qp, rows, cols, group)
+        _need(x, 2 * cols, "x", True)
+        _need(y, 2 * rows, "y", True)
     qa, pa, xa, ya = _ptr_array(qs), _ptr_array(qparams), _ptr_array(xs), _ptr_array(ys)
     n, sp = len(qs), _stream_ptr(stream)
 

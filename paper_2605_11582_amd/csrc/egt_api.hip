@@ -77,7 +77,7 @@ const char *egt_last_hip_error(void) { return hipGetErrorString(g_last_hip_error
 
 egt_status egt_int4_gemv(const uint8_t *q, const uint16_t *qparams, int rows, int cols, int group,
                          const uint16_t *x, uint16_t *y, void *stream) {
-  if (rows < 0 || cols < 0 || group <= 0 || group % 8 != 0 || cols % group != 0)
+  if (rows < 0 || cols < 0 || group <= 0 || group % 4 != 0 || cols % group != 0)
     return EGT_ERR_SHAPE;
   if (rows == 0) return EGT_OK;                     // nothing to compute, pointers not examined
   if (!q || !qparams || !x || !y) return EGT_ERR_NULL;
@@ -129,7 +129,7 @@ egt_status egt_int4_gemv_batch(const uint8_t *const *q, const uint16_t *const *q
                                int count, void *stream) {
   if (!q || !qparams || !x || !y) return EGT_ERR_NULL;
   if (count < 1 || count > 4) return EGT_ERR_SHAPE;
-  if (rows < 0 || cols < 0 || group <= 0 || group % 8 != 0 || cols % group != 0)
+  if (rows < 0 || cols < 0 || group <= 0 || group % 4 != 0 || cols % group != 0)
     return EGT_ERR_SHAPE;
   if (rows == 0) return EGT_OK;
   for (int k = 0; k < count; ++k) {

@@ -1,7 +1,7 @@
 // Kernel selection for the device entry points.
 #include "egt_device.h"
 
-#include <cstdlib>
+#include "egt_tune.h"
 
 namespace egt {
 
@@ -10,7 +10,7 @@ hipError_t launch_sparse(const egt_2bitcsr &w, const uint16_t *X, int64_t ldx, u
   if (M == 1 && sparse_m1_supported(w)) return launch_sparse_m1(w, X, Y, stream);
   if (M == 1 && sparse_m1_n1_supported(w)) return launch_sparse_m1_n1(w, X, Y, stream);
   // 16-byte loads of X: token rows must start on a 16-byte boundary there
-  if (M >= 2 && ldx % 8 == 0 && sparse_m1_tokens_supported(w, M) && getenv("EGT_NO_M1T") == nullptr)
+  if (M >= 2 && ldx % 8 == 0 && sparse_m1_tokens_supported(w, M) && !tune_flag("EGT_NO_M1T"))
     return launch_sparse_m1_tokens(w, X, ldx, Y, ldy, M, stream);
   if (M >= 2 && sparse_smallm_supported(w, ldx, M)) return launch_sparse_smallm(w, X, ldx, Y, ldy, M, stream);
   return launch_sparse_generic(w, X, ldx, Y, ldy, M, stream);

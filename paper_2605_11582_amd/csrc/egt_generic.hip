@@ -88,6 +88,34 @@ __global__ __launch_bounds__(256) void k_int4_generic(const uint8_t *__restrict_
   if (lane == 0) y[r] = __float2half(acc);
 }
 
+// The same product in units of four columns (two bytes of codes): serves groups that are a
+// multiple of 4 but not of 8 columns, where an 8-column word would straddle two groups.
+__global__ __launch_bounds__(256) void k_int4_generic4(const uint8_t *__restrict__ q,
+                                                        const uint16_t *__restrict__ qparams,
+                                                        int rows, int cols, int group,
+                                                        const __half *__restrict__ x,
+                                                        __half *__restrict__ y) {
+  const int lane = threadIdx.x & 63;
+  const int r = blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
+  if (r >= rows) return;
+  const int G = cols / group;
+  const uint16_t *qr = (const uint16_t *)(q + (size_t)r * (cols >> 1));
+  float acc = 0.f;
+  for (int u = lane; u < (cols >> 2); u += 64) {
+    const uint32_t nib = qr[u];
+    const int c0 = 4 * u;                                   // group % 4 == 0: one group per unit
+    const uint16_t *p = qparams + ((size_t)r * G + c0 / group) * 2;
+    const float s = __half2float(__ushort_as_half(p[0])), z = __half2float(__ushort_as_half(p[1]));
+    float part = 0.f;
+#pragma unroll
+    for (int k = 0; k < 4; ++k)
+      part = fmaf((float)((nib >> (4 * k)) & 15) - z, __half2float(x[c0 + k]), part);
+    acc = fmaf(s, part, acc);
+  }
+  for (int o = 32; o > 0; o >>= 1) acc += __shfl_xor(acc, o, 64);
+  if (lane == 0) y[r] = __float2half(acc);
+}
+
 hipError_t launch_sparse_generic(const egt_2bitcsr &w, const uint16_t *X, int64_t ldx, uint16_t *Y,
                                  int64_t ldy, int M, hipStream_t stream) {
   if (w.rows == 0) return hipSuccess;
@@ -106,6 +134,9 @@ hipError_t launch_sparse_generic(const egt_2bitcsr &w, const uint16_t *X, int64_
 hipError_t launch_int4_generic(const uint8_t *q, const uint16_t *qparams, int rows, int cols,
                                int group, const uint16_t *x, uint16_t *y, hipStream_t stream) {
   if (rows == 0) return hipSuccess;
+  if (group % 8 != 0)
+    return launch(k_int4_generic4, dim3((rows + 3) / 4), dim3(256), 0, stream, q, qparams, rows, cols,
+                  group, (const __half *)x, (__half *)y);
   return launch(k_int4_generic, dim3((rows + 3) / 4), dim3(256), 0, stream, q, qparams, rows, cols,
                 group, (const __half *)x, (__half *)y);
 }

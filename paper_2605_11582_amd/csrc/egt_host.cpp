@@ -6,6 +6,7 @@
 #include <algorithm>
 #include <atomic>
 #include <cmath>
+#include <cstdint>
 #include <cstring>
 #include <thread>
 #include <vector>
@@ -107,7 +108,7 @@ inline int choose4(const uint8_t *m, int n) {
 
 extern "C" {
 
-const char *egt_status_str(int status) {
+const char *egt_status_str(egt_status status) {
   switch (status) {
     case EGT_OK: return "ok";
     case EGT_ERR_NULL: return "null pointer";
@@ -231,24 +232,34 @@ egt_status egt_pack_2bitcsr_rowgroups(const uint16_t *w, int64_t ldw, const uint
       if (row_group[r] <= 0 || row_group[r] % group != 0 || cols % row_group[r] != 0) return EGT_ERR_SHAPE;
   }
 
-  // pass 1: validate everything before a single output byte is written
-  std::atomic<int> err(EGT_OK);
+  // pass 1: validate everything before a single output byte is written.  The error reported
+  // is that of the first offending 4-group in row-major order, whatever the thread timing; a
+  // group that is both over-full and holds a non-finite kept weight reports the mask.
+  std::atomic<int64_t> first(INT64_MAX);             // (index of the 4-group in the matrix) * 8 + code
+  const int64_t gpr = cols / 4;
   parallel_rows(rows, [&](int r0, int r1) {
-    for (int r = r0; r < r1 && err.load(std::memory_order_relaxed) == EGT_OK; ++r) {
+    for (int r = r0; r < r1; ++r) {
+      if ((int64_t)r * gpr * 8 > first.load(std::memory_order_relaxed)) break;
       const uint16_t *wr = w + (int64_t)r * ldw;
       const uint8_t *mr = mask + (int64_t)r * ldm;
       for (int c = 0; c < cols; c += 4) {
         int cnt = 0;
+        bool nonfinite = false;
         for (int j = 0; j < 4; ++j) {
           if (!mr[c + j]) continue;
           ++cnt;
-          if (!half_is_finite(wr[c + j])) { int e = EGT_OK; err.compare_exchange_strong(e, EGT_ERR_NONFINITE); }
+          nonfinite |= !half_is_finite(wr[c + j]);
         }
-        if (cnt > n_keep) { err.store(EGT_ERR_MASK); }
+        if (cnt <= n_keep && !nonfinite) continue;
+        const int64_t key = ((int64_t)r * gpr + (c >> 2)) * 8 + (cnt > n_keep ? EGT_ERR_MASK : EGT_ERR_NONFINITE);
+        int64_t seen = first.load();
+        while (key < seen && !first.compare_exchange_weak(seen, key)) {}
+        r = r1;                                         // later rows of this range cannot come first
+        break;
       }
     }
   });
-  if (err.load() != EGT_OK) return (egt_status)err.load();
+  if (first.load() != INT64_MAX) return (egt_status)(first.load() & 7);
 
   const int64_t S = (int64_t)n_keep * (cols / 4);
   const int G = val_kind == EGT_VAL_INT4 ? cols / group : 0;
@@ -377,7 +388,7 @@ egt_status egt_unpack_2bitcsr(const egt_2bitcsr *in, uint16_t *w_dense, int64_t 
 egt_status egt_quant_int4(const uint16_t *w, int64_t ldw, int rows, int cols, int group,
                           uint8_t *q, uint16_t *qparams) {
   if (!w || !q || !qparams) return EGT_ERR_NULL;
-  if (rows < 0 || cols < 0 || group <= 0 || group % 8 != 0 || cols % group != 0 || ldw < cols)
+  if (rows < 0 || cols < 0 || group <= 0 || group % 4 != 0 || cols % group != 0 || ldw < cols)
     return EGT_ERR_SHAPE;
   std::atomic<int> err(EGT_OK);
   parallel_rows(rows, [&](int r0, int r1) {

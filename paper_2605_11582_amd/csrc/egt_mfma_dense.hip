@@ -19,8 +19,7 @@
 // matrix instruction (template parameter PRE), two more packed operations per pair.
 #include "egt_mfma_common.h"
 
-#include <cstdio>
-#include <cstdlib>
+#include "egt_tune.h"
 
 namespace egt {
 
@@ -256,7 +255,7 @@ hipError_t launch_int4_m1_batch(const uint8_t *const *qs, const uint16_t *const 
   g.nib_mask = 0x00F000F0u;
   g.nib_magic = 0x54005400u;
   int tpi = 4, wpp = g.phases == 1 ? 4 : (g.phases <= 8 ? 2 : 1);   // measured; K = 11008 (6 phases): 7.65 us with 2, 8.24 with 1
-  if (const char *e = getenv("EGT_DENSE_TUNE")) sscanf(e, "%d,%d", &tpi, &wpp);
+  tune_pair("EGT_DENSE_TUNE", tpi, wpp);
   if (wpp < 1) wpp = 1;
   if (wpp * g.phases > 16) wpp = 16 / g.phases;
   if (tpi != 1 && tpi != 2 && tpi != 4 && tpi != 8) tpi = 4;

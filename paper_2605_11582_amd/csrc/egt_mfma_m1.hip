@@ -27,8 +27,7 @@
 // or not stored.
 #include "egt_mfma_common.h"
 
-#include <cstdio>
-#include <cstdlib>
+#include "egt_tune.h"
 
 namespace egt {
 
@@ -397,7 +396,7 @@ hipError_t launch_sparse_m1_batch(const egt_2bitcsr *ws, const uint16_t *const *
   // measured optima: 4 tiles per wave and 4 waves per phase for one phase, 2 waves per phase
   // for several - except three phases (K = 11008: 6.97 against 7.30 us with 2 and 4)
   int tpi = g.phases == 3 ? 2 : 4, wpp = (g.phases == 1 || g.phases == 3) ? 4 : 2;
-  if (const char *e = getenv("EGT_M1_TUNE")) sscanf(e, "%d,%d", &tpi, &wpp);
+  tune_pair("EGT_M1_TUNE", tpi, wpp);
   if (wpp < 1) wpp = 1;
   if (wpp * g.phases > 16) wpp = 16 / g.phases;
   if (tpi != 1 && tpi != 2 && tpi != 4 && tpi != 8) tpi = 4;
@@ -407,7 +406,7 @@ hipError_t launch_sparse_m1_batch(const egt_2bitcsr *ws, const uint16_t *const *
   const int tiles_per_block = wpp * tpi;
   const dim3 grid((g.ntiles + tiles_per_block - 1) / tiles_per_block, count), block(64 * nwaves);
   const int lds_pieces = multirow ? g.nchunks * 8 : g.phases * 512;
-  const bool lin = w.val_kind == EGT_VAL_FP16 && !multirow && getenv("EGT_M1_NOLIN") == nullptr;
+  const bool lin = w.val_kind == EGT_VAL_FP16 && !multirow && !tune_flag("EGT_M1_NOLIN");
   g.part_offset = lin ? 16 * lds_pieces + 16 * ((lds_pieces + 15) >> 4) : 16 * lds_pieces + 16 * ((lds_pieces + 31) >> 5);
   g.xtok = g.part_offset; g.M = 1; g.ldx = 0; g.ldy = 0;
   const size_t lds = g.part_offset + (g.phases > 1 ? sizeof(float) * g.phases * tiles_per_block : 0);
@@ -496,7 +495,7 @@ hipError_t launch_sparse_m1_tokens(const egt_2bitcsr &w, const uint16_t *X, int6
   // four tokens take about 200 registers: two waves per SIMD, workgroups of at most 8 waves;
   // FP16 values (64 B per lane and tile): two tiles per wave
   int tpi = (f16 && g.phases < 3) ? 2 : 4, wpp = g.phases == 1 ? 4 : 2;
-  if (const char *e = getenv("EGT_M1T_TUNE")) sscanf(e, "%d,%d", &tpi, &wpp);
+  tune_pair("EGT_M1T_TUNE", tpi, wpp);
   if (f16 && mt == 4) tpi = 2;                        // the only four-token form with FP16 values
   if (wpp < 1) wpp = 1;
   const int max_waves = (mt > 2 || f16) ? 8 : 16;

@@ -12,8 +12,7 @@
 // instructions (four slots each) finish a chunk.
 #include "egt_mfma_common.h"
 
-#include <cstdio>
-#include <cstdlib>
+#include "egt_tune.h"
 
 namespace egt {
 
@@ -330,7 +329,7 @@ hipError_t launch_sparse_m1_n1_batch(const egt_2bitcsr *ws, const uint16_t *cons
   g.rows = w.rows;
   g.nchunks = w.cols / 128;
   // FP16 values: one row per tile, contiguous-kilobyte loads (NI load instructions per tile)
-  const bool lin = w.val_kind == EGT_VAL_FP16 && getenv("EGT_M1N1_NOLIN") == nullptr;
+  const bool lin = w.val_kind == EGT_VAL_FP16 && !tune_flag("EGT_M1N1_NOLIN");
   const int ni = !lin ? 0 : g.nchunks == 16 ? 1 : g.nchunks == 32 ? 2 : 4;
   const bool multirow = !lin && g.nchunks < 64;
   g.mr_shift = multirow ? (g.nchunks == 16 ? 4 : 5) : -1;
@@ -348,7 +347,7 @@ hipError_t launch_sparse_m1_n1_batch(const egt_2bitcsr *ws, const uint16_t *cons
   g.nib_mask = 0x00F0000Fu; g.nib_magic = 0x54006400u;
   int tpi = g.phases == 1 ? 2 : 4, wpp = 4;
   if (lin) tpi = ni == 4 ? 2 : 4;
-  if (const char *e = getenv("EGT_M1N1_TUNE")) sscanf(e, "%d,%d", &tpi, &wpp);
+  tune_pair("EGT_M1N1_TUNE", tpi, wpp);
   if (wpp < 1) wpp = 1;
   if (wpp * g.phases > 16) wpp = 16 / g.phases;
   if (tpi != 1 && tpi != 2 && tpi != 4) tpi = 2;

@@ -42,8 +42,7 @@
 // are overwritten with zeros in LDS.
 #include "egt_mfma_common.h"
 
-#include <cstdio>
-#include <cstdlib>
+#include "egt_tune.h"
 
 namespace egt {
 
@@ -645,12 +644,17 @@ hipError_t launch_sparse_smallm(const egt_2bitcsr &w, const uint16_t *X, int64_t
   const bool f16x = !int4 && !n1 && M <= 16;          // FP16 values at 2:4, one token group
   int nwmax = wide ? 8 : 16, blocks_per_cu = 1;
   if (f16x && g.ntiles <= 256) nwmax = 16;            // one tile per workgroup: 16 waves of 128 registers
-  if (const char *e = getenv("EGT_SM_TUNE")) sscanf(e, "%d,%d", &nwmax, &blocks_per_cu);
-  if (nwmax < 1 || nwmax > ((wide && !f16x) ? 8 : 16)) return hipErrorInvalidValue;
-  const int nw = g.nsteps < nwmax ? g.nsteps : nwmax;
+  {
+    const int nwcap = (wide && !f16x) ? 8 : 16;
+    tune_pair("EGT_SM_TUNE", nwmax, blocks_per_cu);
+    nwmax = nwmax < 1 ? 1 : nwmax > nwcap ? nwcap : nwmax;
+    blocks_per_cu = blocks_per_cu < 1 ? 1 : blocks_per_cu > 4 ? 4 : blocks_per_cu;
+  }
   int nblocks = 256 * blocks_per_cu;                  // more row tiles than nblocks * NIT: rounds in the kernel
   if (nblocks > g.ntiles) nblocks = g.ntiles;
   const bool one = nblocks == g.ntiles;               // one row tile per workgroup
+  if (f16x && !one && nwmax > 8) nwmax = 8;           // several tiles with FP16 values: 8 waves of 256 registers
+  const int nw = g.nsteps < nwmax ? g.nsteps : nwmax;
   // (NIT > 1: the form with rounds only where a workgroup owns more than NIT row tiles)
 #define EGT_KS(KIND, NT, NIT, NWMAX, QW, N1)                                                     \
   ((NIT > 1 && (int64_t)nblocks * NIT < g.ntiles) ? go_ks<KIND, NT, NIT, NWMAX, QW, N1, (NIT > 1)>(w, X, Y, g, nw, nblocks, stream) \
@@ -671,7 +675,6 @@ hipError_t launch_sparse_smallm(const egt_2bitcsr &w, const uint16_t *X, int64_t
   }
   if (M <= 16) {
     if (one) return nw > 8 ? EGT_KS(EGT_VAL_FP16, 1, 1, 16, 1, false) : EGT_KS(EGT_VAL_FP16, 1, 1, 8, 1, false);
-    if (nw > 8) return hipErrorInvalidValue;
     return EGT_KS(EGT_VAL_FP16, 1, 4, 8, 1, false);
   }
   return one ? EGT_KS(EGT_VAL_FP16, 2, 1, 8, 1, false) : EGT_KS(EGT_VAL_FP16, 2, 4, 8, 1, false);

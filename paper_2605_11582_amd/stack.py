@@ -105,23 +105,34 @@ class LayerStack:
         return calls
 
     @staticmethod
-    def build(device="cuda:0", distinct_layers=None, progress=None, plan="config4") -> "LayerStack":
+    def build(device="cuda:0", distinct_layers=None, progress=None, plan="config4", on_matrix=None) -> "LayerStack":
         """Uploads the whole stack.  `distinct_layers`: how many layers of each kind get
-        their own seeded weights (None = all); the remaining layers reuse the packed
-        bytes of an earlier layer of the same kind in freshly allocated device memory
-        (same traffic, same launches; only the numbers repeat)."""
+        their own seeded weights (None = all 32, the configuration as stated); the
+        remaining layers reuse the packed bytes of an earlier layer of the same kind in
+        freshly allocated device memory (same traffic, same launches; only the numbers
+        repeat).  `on_matrix(layer, mi, kind, w, x, packed)` is called for every matrix
+        with weights of its own while its host data is alive (the dense weights are not
+        kept afterwards)."""
         import torch
         kinds = synth.layer_kinds(plan)
         st = LayerStack()
         cache = {"s24": [], "s14": [], "d": []}
+        nm = len(synth.LAYER_MATRICES)
         for layer in range(synth.N_LAYERS):
             kind = kinds[layer]
             reuse = distinct_layers is not None and len(cache[kind]) >= distinct_layers
             if reuse:
                 host = cache[kind][layer % len(cache[kind])]
             else:
-                host = [pack_layer_matrix(layer, mi, kind) for mi in range(len(synth.LAYER_MATRICES))]
-                cache[kind].append(host)
+                host = []
+                for mi in range(nm):
+                    w, x, packed = pack_layer_matrix(layer, mi, kind)
+                    if on_matrix:
+                        on_matrix(layer, mi, kind, w, x, packed)
+                    host.append((None, x, packed))
+                    del w
+                if distinct_layers is not None:
+                    cache[kind].append(host)
             for mi, (name, rows, cols) in enumerate(synth.LAYER_MATRICES):
                 _, x, packed = host[mi]
                 xd = torch.from_numpy(x.view(np.int16)).to(device).view(torch.float16)

@@ -158,7 +158,9 @@ def test_broken_row_ptr_yields_nan_for_every_token(cols, n, M):
                                          (1, 4096, 128), (131, 1024, 128),
                                          # other group sizes on the matrix-core path
                                          (70, 4096, 256), (33, 1024, 32), (20, 512, 64), (40, 1024, 512),
-                                         (21, 11008, 256), (21, 11008, 64), (35, 2048, 2048), (18, 6144, 32)])
+                                         (21, 11008, 256), (21, 11008, 64), (35, 2048, 2048), (18, 6144, 32),
+                                         # groups that are a multiple of 4 but not of 8 columns
+                                         (37, 96, 12), (9, 160, 20), (70, 64, 4), (5, 1092, 84)])
 def test_int4_gemv_small(rows, cols, g):
     print(f"case int4_gemv {rows}x{cols} g={g}", flush=True)
     w = synth.weights(rows, cols, 500 + rows)

@@ -1,5 +1,6 @@
 """Config 4: the 32-layer 7B-shaped stack, 224 GEMV launches (16 layers 2:4-sparse INT4 in
-2bit-CSR, 16 dense INT4), plain and replayed from a HIP graph."""
+2bit-CSR, 16 dense INT4), plain and replayed from a HIP graph; the three-way layer mix;
+the trigger cost model on a measured M-sweep."""
 import numpy as np
 import pytest
 
@@ -24,40 +25,67 @@ def test_three_way_plan():
     assert (kinds.count("s24"), kinds.count("s14"), kinds.count("d")) == (11, 11, 10)
 
 
+class _OracleSamples:
+    """Collects, while a stack is built, the oracle's result on sampled rows of every matrix
+    that has weights of its own: the oracle prunes, quantises and packs those rows itself
+    (bit-compared with the library's bytes) and multiplies them with x in float64."""
+
+    def __init__(self, per_matrix=32):
+        self.per_matrix = per_matrix
+        self.ref = {}                                   # (layer, mi) -> (rows, y_ref, a_ref)
+
+    def __call__(self, layer, mi, kind, w, x, packed):
+        name, rows, cols = synth.LAYER_MATRICES[mi]
+        pick = G.sample_rows(rows, self.per_matrix, layer * len(synth.LAYER_MATRICES) + mi)
+        if kind != "d":
+            n = S.N_KEEP[kind]
+            o = O.pack_2bitcsr(w[pick], O.prune_n4_magnitude(w[pick], n), n, 128, O.VAL_INT4)
+            sub = G.row_subset(packed, pick)
+            for k in ("values", "idx", "qparams"):
+                assert np.array_equal(o[k], sub[k]), (layer, name, k)
+            y_ref, a_ref = O.gemv(o, x)
+        else:
+            oq, oqp = O.quant_int4_dense(w[pick], 128)
+            assert np.array_equal(oq, packed[0][pick]) and np.array_equal(oqp, packed[1][pick]), (layer, name)
+            y_ref, a_ref = O.int4_gemv(oq, oqp, 128, x)
+        self.ref[(layer, mi)] = (pick, y_ref, a_ref)
+
+    def check(self, outputs, what):
+        nm = len(synth.LAYER_MATRICES)
+        worst = 0.0
+        for (layer, mi), (pick, y_ref, a_ref) in self.ref.items():
+            worst = max(worst, G.assert_close(outputs[layer * nm + mi][pick], y_ref, a_ref,
+                                              f"{what} layer {layer} {synth.LAYER_MATRICES[mi][0]}"))
+        return worst
+
+
+def _progress(layer):
+    if layer % 4 == 3:
+        print(f"  layer {layer} packed, checked and uploaded", flush=True)
+
+
 def test_stack_parity_and_graph_replay():
+    # config 4 as stated: all 32 layers carry their own seeded weights (224 distinct matrices);
+    # the oracle re-encodes sampled rows of every one of them
     torch = G.torch_mod()
-    print("building the stack (2 layers with their own weights, 30 reuse their bytes)", flush=True)
-    st = S.LayerStack.build("cuda:0", distinct_layers=1, progress=lambda l: print(f"  layer {l} uploaded", flush=True) if l % 8 == 7 else None)
-    assert len(st.matrices) == 224 and st.nbytes == 3043344832
+    print("building the 32-layer stack, every layer with its own weights", flush=True)
+    samples = _OracleSamples()
+    st = S.LayerStack.build("cuda:0", distinct_layers=None, progress=_progress, on_matrix=samples)
+    assert len(st.matrices) == 224 and st.nbytes == 3043344832 and len(samples.ref) == 224
+    sparse_ids = set(int(v) for v in synth.sparse_layers())
+    assert [k != "d" for k in synth.layer_kinds("config4")] == [l in sparse_ids for l in range(32)]
     st.run()
     torch.cuda.synchronize()
     eager = [m.y.cpu().numpy().copy() for m in st.matrices]
-    sparse_ids = set(int(v) for v in synth.sparse_layers())
-    first = {True: min(sparse_ids), False: min(set(range(32)) - sparse_ids)}
-    assert [k != "d" for k in synth.layer_kinds("config4")] == [l in sparse_ids for l in range(32)]
+    worst = samples.check(eager, "config 4")
+    print(f"  224 matrices match the oracle on sampled rows (max err / bound {worst:.4f})", flush=True)
+    # distinct seeds give distinct results: no layer repeats another layer's output
     nm = len(synth.LAYER_MATRICES)
-    # the two layers with their own weights: the oracle packs sampled rows itself and multiplies
-    for sparse, layer in first.items():
-        for mi, (name, rows, cols) in enumerate(synth.LAYER_MATRICES):
-            print(f"  oracle check layer {layer} ({'sparse' if sparse else 'dense'}) {name}", flush=True)
-            w, x, packed = S.pack_layer_matrix(layer, mi, sparse)
-            pick = G.sample_rows(rows, 48, layer * nm + mi)
-            y = eager[layer * nm + mi]
-            if sparse:
-                o = O.pack_2bitcsr(w[pick], O.prune_n4_magnitude(w[pick], 2), 2, 128, O.VAL_INT4)
-                sub = G.row_subset(packed, pick)
-                for k in ("values", "idx", "qparams"):
-                    assert np.array_equal(o[k], sub[k]), k
-                y_ref, a_ref = O.gemv(o, x)
-            else:
-                oq, oqp = O.quant_int4_dense(w[pick], 128)
-                assert np.array_equal(oq, packed[0][pick]) and np.array_equal(oqp, packed[1][pick])
-                y_ref, a_ref = O.int4_gemv(oq, oqp, 128, x)
-            G.assert_close(y[pick], y_ref, a_ref, f"layer {layer} {name}")
-    # layers that reuse those bytes must reproduce the same outputs bit for bit
-    for m_i, m in enumerate(st.matrices):
-        src = first[m.sparse] * nm + m_i % nm
-        assert np.array_equal(eager[m_i].view(np.uint16), eager[src].view(np.uint16)), (m.layer, m.name)
+    seen = set()
+    for m_i in range(0, 224, nm):
+        key = eager[m_i].tobytes()
+        assert key not in seen
+        seen.add(key)
     # fused launches (q/k/v and gate/up in one launch each): same bits as the separate launches
     fused = st.fuse()
     assert len(fused) == 32 * 4
@@ -86,6 +114,82 @@ def test_stack_parity_and_graph_replay():
         for m_i, m in enumerate(st.matrices):
             assert np.array_equal(m.y.cpu().numpy().view(np.uint16), eager[m_i].view(np.uint16)), (rep, m.layer, m.name)
         print(f"  graph replay {rep} matches the eager run", flush=True)
+
+
+def test_three_way_mix_stack_parity():
+    # the layer-adaptive mix with both sparsities in use (2:4, 1:4 and dense layers, Sec. 3.2):
+    # two layers of each kind carry their own weights and are checked against the oracle; the
+    # other layers reuse those bytes in their own device memory and must reproduce the bits
+    torch = G.torch_mod()
+    samples = _OracleSamples(per_matrix=48)
+    st = S.LayerStack.build("cuda:0", distinct_layers=2, progress=_progress, plan="mix3", on_matrix=samples)
+    kinds = synth.layer_kinds("mix3")
+    nm = len(synth.LAYER_MATRICES)
+    assert len(st.matrices) == 224 and len(samples.ref) == 6 * nm
+    assert sorted(set(kinds[l] for (l, _) in samples.ref)) == ["d", "s14", "s24"]
+    assert st.nbytes == sum(S.algorithmic_bytes(r, c, kinds[l]) for l in range(32) for _, r, c in synth.LAYER_MATRICES)
+    st.run()
+    torch.cuda.synchronize()
+    eager = [m.y.cpu().numpy().copy() for m in st.matrices]
+    worst = samples.check(eager, "mix3")
+    print(f"  {len(samples.ref)} matrices of the three kinds match the oracle (max err / bound {worst:.4f})", flush=True)
+    own = {}                                            # kind -> layers with their own weights, in order
+    for (l, _) in samples.ref:
+        if l not in own.setdefault(kinds[l], []):
+            own[kinds[l]].append(l)
+    for m_i, m in enumerate(st.matrices):
+        src_layer = own[m.kind][m.layer % len(own[m.kind])] if m.layer not in own[m.kind] else m.layer
+        src = src_layer * nm + m_i % nm
+        assert np.array_equal(eager[m_i].view(np.uint16), eager[src].view(np.uint16)), (m.layer, m.name)
+    # fused launches on the mixed stack: q/k/v and gate/up of a 1:4 layer in one launch too
+    fused = st.fuse()
+    for m in st.matrices:
+        m.y.fill_(3.0)
+    for c in fused:
+        c()
+    torch.cuda.synchronize()
+    for m_i, m in enumerate(st.matrices):
+        assert np.array_equal(m.y.cpu().numpy().view(np.uint16), eager[m_i].view(np.uint16)), ("fused", m.layer, m.name)
+
+
+def test_trigger_model_on_a_measured_sweep():
+    # Sec. 3.4: time one all-2:4 layer (q/k/v/o, gate/up, down) for M = 1..64 on the GPU, fit
+    # the verification cost with the library and compare fit and trigger point with the
+    # oracle on the very same measured points
+    torch = G.torch_mod()
+    shapes = ((4096, 4096, 4), (11008, 4096, 2), (4096, 11008, 1))
+    sweep = (1, 2, 3, 4, 6, 8, 12, 16, 24, 32, 48, 64)
+    layer_us = {m: 0.0 for m in sweep}
+    for rows, cols, reps in shapes:
+        _, _, p = G.packed_full(rows, cols, 2, 128, 0, synth.seed_for(5, 7))
+        pd = p.to("cuda:0")
+        for M in sweep:
+            X = G.to_dev(synth.activation_rows(M, cols, 5).view(np.uint16)).view(torch.float16)
+            Y = torch.empty((M, rows), dtype=torch.float16, device="cuda:0")
+            call = B.prepared_sparse_gemm_smallm(pd, X, Y)
+            for _ in range(20):
+                call()
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(100):
+                call()
+            e1.record()
+            torch.cuda.synchronize()
+            layer_us[M] += reps * e0.elapsed_time(e1) * 10.0          # ms per 100 calls -> us per call
+    print("  layer time by M (us):", {m: round(v, 1) for m, v in layer_us.items()}, flush=True)
+    ms, ts = list(sweep[1:]), [layer_us[m] for m in sweep[1:]]
+    a, b = B.fit_verify_cost(ms, ts)
+    oa, ob = O.fit_verify_cost(ms, ts)
+    assert a == pytest.approx(oa, rel=1e-9, abs=1e-9) and b == pytest.approx(ob, rel=1e-9, abs=1e-12)
+    assert b > 0 and all(v > 0 for v in ts)             # more candidates cost more, as the paper observes
+    assert layer_us[64] > layer_us[1]
+    for cand, rem in (([64, 24, 9, 4, 2, 1], [6, 5, 4, 3, 2, 1]), ([48, 48, 12, 3], [4, 3, 2, 1]), ([64], [1])):
+        got = B.trigger_depth(layer_us[1], a, b, cand, rem)
+        want = O.trigger_depth(layer_us[1], oa, ob, cand, rem)
+        assert got[0] == want[0] and got[1] == pytest.approx(want[1], rel=1e-9, abs=1e-9), (cand, rem)
+        gains = [r * layer_us[1] - (a + b * c) for c, r in zip(cand, rem)]
+        assert got[0] == (int(np.argmax(gains)) if max(gains) > 0 else -1)
 
 
 def test_smallm_kernels_replay_in_a_hip_graph():

@@ -230,6 +230,33 @@ def test_pack_errors_leave_outputs_untouched():
     assert B.lib().egt_pack_2bitcsr(w.ctypes.data, 32, bad.ctypes.data, 64, 8, 64, 2, 32, 0, ctypes.byref(v)) == 2
 
 
+def test_pack_reports_the_first_offending_group_whatever_the_thread_timing():
+    # several errors in one matrix: the one of the first offending 4-group in row-major order
+    # is returned, every time; a group with both faults reports the mask
+    w = synth.weights(600, 64, 6)
+    mask = O.prune_n4_magnitude(w, 2)
+    overfull = mask.copy()
+    overfull[500, 8:12] = 1                    # EGT_ERR_MASK late in the matrix
+    wn = w.copy()
+    r, c = 20, int(np.argwhere(mask[20] == 1)[3][0])
+    wn[r, c] = np.float16(np.inf)              # EGT_ERR_NONFINITE early
+    for _ in range(20):
+        with pytest.raises(B.EgtError) as e:
+            B.pack_2bitcsr(wn, overfull, 2, 32, 0)
+        assert e.value.status == 4
+    overfull2 = mask.copy()
+    overfull2[3, 0:4] = 1
+    for _ in range(20):
+        with pytest.raises(B.EgtError) as e:
+            B.pack_2bitcsr(wn, overfull2, 2, 32, 0)
+        assert e.value.status == 3
+    both = mask.copy()
+    both[r, 4 * (c // 4):4 * (c // 4) + 4] = 1
+    with pytest.raises(B.EgtError) as e:
+        B.pack_2bitcsr(wn, both, 2, 32, 0)
+    assert e.value.status == 3
+
+
 def test_strided_inputs():
     big = synth.weights(16, 256, 11)
     w = big[:, 64:192]                         # row stride 256, 128 columns
@@ -270,9 +297,9 @@ def test_unpack_rejects_broken_buffers():
     assert e.value.status == 5
 
 
-@pytest.mark.parametrize("g", [8, 32, 128])
-def test_quant_int4_dense_bit_exact(g):
-    w = synth.weights(48, 512, 55 + g)
+@pytest.mark.parametrize("g,cols", [(8, 512), (32, 512), (128, 512), (4, 64), (12, 96), (20, 160)])
+def test_quant_int4_dense_bit_exact(g, cols):
+    w = synth.weights(48, cols, 55 + g)
     q, qp = B.quant_int4(w, g)
     oq, oqp = O.quant_int4_dense(w, g)
     assert np.array_equal(q, oq) and np.array_equal(qp, oqp)
@@ -294,7 +321,9 @@ def test_device_entry_points_reject_bad_arguments_without_a_gpu():
     v4 = B.View(8, 64, 2, 32, 0, 16, 24, 16, 16)         # misaligned values pointer
     assert L.egt_sparse_gemv(ctypes.byref(v4), 16, 16, None) == 5
     assert L.egt_int4_gemv(None, 16, 8, 64, 32, 16, 16, None) == 1
-    assert L.egt_int4_gemv(16, 16, 8, 64, 12, 16, 16, None) == 2
+    assert L.egt_int4_gemv(16, 16, 8, 64, 12, 16, 16, None) == 2       # 64 % 12 != 0
+    assert L.egt_int4_gemv(16, 16, 8, 60, 6, 16, 16, None) == 2        # group % 4 != 0
+    assert L.egt_int4_gemv(16, 16, 0, 60, 12, 16, 16, None) == 0       # group % 4 == 0 is accepted (empty matrix)
     assert L.egt_stream_read(16, 24, 16, None) == 2
     views = (B.View * 2)(v, B.View(8, 64, 2, 16, 0, 16, 16, 16, 16))       # second view differs in group size
     ptrs = (ctypes.c_void_p * 2)(16, 16)
