@@ -86,7 +86,7 @@ class Timer:
         for _ in range(REPEATS):
             torch.cuda.synchronize()
             e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            self.filler()                          # keeps the GPU busy while the queue fills
+            self.filler(torch.cuda.current_stream().cuda_stream)   # keeps the GPU busy while the queue fills
             t0 = time.perf_counter()
             e0.record()
             for i in range(steps):
@@ -236,7 +236,7 @@ def main():
     ys = [torch.empty(R, dtype=torch.float16, device=dev) for _ in range(copies)]
     calls = [B.prepared_sparse_gemv(packed[i], xd, ys[i]) for i in range(copies)]
 
-    sink = torch.zeros(8192, dtype=torch.int32, device=dev)
+    sink = torch.zeros(4096, dtype=torch.int32, device=dev)
     big = torch.empty(1 << 30, dtype=torch.uint8, device=dev).random_(0, 255)
     filler = B.prepared_stream_read(big, 1 << 30, sink)
     timer = Timer(torch, filler)
@@ -441,6 +441,14 @@ def table(torch, B, synth, timer, dev, w, mask, xd, ys, calls, packed):
             for c in fused:
                 c()
         row["launches_128_fused_plain"] = entry(timer(run_fused, 10, 2), stk.nbytes)
+        layers = stk.per_layer()
+
+        def run_layers(i):
+            for c in layers:
+                c()
+        row["launches_32_one_per_layer"] = entry(timer(run_layers, 10, 2), stk.nbytes)
+        whole = stk.one_launch()
+        row["launches_1_whole_stack"] = entry(timer(lambda i: whole(), 10, 2), stk.nbytes)
         if plan == "config4":
             with torch.cuda.stream(side):
                 stk.run(side.cuda_stream)

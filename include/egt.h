@@ -187,6 +187,66 @@ egt_status egt_int4_gemv_batch(const uint8_t *const *q, const uint16_t *const *q
                                int cols, int group, const uint16_t *const *x, uint16_t *const *y,
                                int count, void *stream);
 
+/* Several products of different shapes and storage forms in one launch (Sec. 3.3 starts
+ * from one kernel per linear layer; Sec. 3.2 makes the stack a layer-adaptive mix of 2:4,
+ * 1:4 and dense INT4 layers): the fixed cost of a launch, about half the time of a GEMV of
+ * a few megabytes, is paid once per table instead of once per matrix.
+ *
+ * An item is one product y = W.x.  `sparse` != NULL: W is that 2bit-CSR view (INT4 values,
+ * n_keep 2 with group_size >= 64 or n_keep 1 with group_size >= 128; device buffers); the
+ * fields q .. group are ignored.  `sparse` == NULL: W is dense INT4 (q, qparams, rows, cols,
+ * group as for egt_int4_gemv, group >= 128).  x: cols FP16, y: rows FP16, device pointers.
+ * Shapes outside those of the matrix-core kernels give EGT_ERR_UNSUPPORTED. */
+typedef struct {
+  const egt_2bitcsr *sparse;
+  const uint8_t *q;
+  const uint16_t *qparams;
+  int32_t rows, cols, group;
+  const uint16_t *x;
+  uint16_t *y;
+} egt_gemv_item;
+
+#define EGT_STACK_ENTRY_BYTES 160 /* bytes of one descriptor in the table */
+enum { EGT_STACK_AUTO = 0, EGT_STACK_GRID = 1, EGT_STACK_RESIDENT = 2 };
+
+typedef struct {
+  int32_t count;         /* matrices in the table                                            */
+  int32_t mode;          /* 0: one grid of short-lived workgroups per matrix;
+                            1: resident workgroups that walk a list of row blocks            */
+  int32_t grid_x;        /* mode 0: workgroups of the largest matrix; mode 1: workgroups     */
+  int32_t block_threads; /* threads per workgroup (a multiple of 64)                         */
+  int32_t lds_bytes;     /* dynamic LDS per workgroup                                        */
+  int32_t x_pieces;      /* 16-byte pieces of x a thread stages: 2, 4 or 8                   */
+  int32_t forms;         /* storage forms in the table: bit 0 2:4, bit 1 1:4, bit 2 dense    */
+  int32_t nitems;        /* mode 1: row blocks in the list                                   */
+  int32_t part_offset;   /* mode 1: LDS offset of the partial sums                           */
+  int32_t reserved;
+  uint64_t table_bytes;  /* bytes of the table                                               */
+} egt_stack_plan;
+
+/* HOST.  Checks `count` (1..65535) items, chooses the launch form and writes the launch
+ * shape to *plan.  With table == NULL that is all (a size query: plan->table_bytes says how
+ * large the table is); otherwise the table - the matrix descriptors, EGT_STACK_ENTRY_BYTES
+ * each, followed in mode 1 by the list of row blocks - is written to `table`, HOST memory
+ * of the caller with room for `table_bytes` >= plan->table_bytes bytes (else EGT_ERR_SHAPE).
+ * The caller copies the table to 16-byte aligned device memory it owns (the library
+ * allocates nothing) and may run it any number of times.  Nothing is written when an
+ * error is returned.  Items with rows == 0 are legal and compute nothing.
+ * `form`: EGT_STACK_AUTO picks mode 1 for tables of 2:4 and dense INT4 matrices with at
+ * least 2048 (dense) or 4096 (2:4) columns that hold 256 MB or more (below that a workgroup
+ * would see too few rows to make staying resident pay) and mode 0 otherwise; EGT_STACK_GRID
+ * and EGT_STACK_RESIDENT ask for mode 0 or mode 1 (EGT_ERR_UNSUPPORTED if the shapes do not
+ * allow mode 1).  Mode 1 sizes the launch for the 256 compute units of an MI355X. */
+egt_status egt_gemv_stack_plan(const egt_gemv_item *items, int count, int form, void *table,
+                               size_t table_bytes, egt_stack_plan *plan);
+
+/* DEVICE.  Runs every product of a planned table in one launch on `stream`.  table_dev:
+ * the device copy of the table egt_gemv_stack_plan wrote; it and every buffer it names
+ * must stay valid until the launch has completed.  The products are independent: no y may
+ * alias an x or another y of the same table.  Each y[r] is computed by the same code as
+ * in egt_sparse_gemv / egt_int4_gemv (a broken row_ptr entry gives NaN in that row). */
+egt_status egt_gemv_stack_run(const void *table_dev, const egt_stack_plan *plan, void *stream);
+
 /* HOST.  Cost model of the parallel-verification trigger (Sec. 3.4 "Parallel
  * Verification Trigger"): the paper observes that the cost of a verification step grows
  * linearly with the number of candidate tokens while an autoregressive step costs a

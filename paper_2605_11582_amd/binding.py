@@ -23,6 +23,7 @@ SYMBOLS = (
     "egt_unpack_2bitcsr", "egt_quant_int4", "egt_int4_gemv", "egt_sparse_gemv",
     "egt_sparse_gemm_smallm", "egt_stream_read", "egt_sparse_gemv_batch", "egt_int4_gemv_batch",
     "egt_fit_verify_cost", "egt_trigger_depth", "egt_prune_n4_importance", "egt_pack_2bitcsr_rowgroups",
+    "egt_gemv_stack_plan", "egt_gemv_stack_run",
 )
 
 
@@ -39,6 +40,22 @@ class View(C.Structure):
                 ("row_ptr", C.c_void_p), ("values", C.c_void_p), ("idx", C.c_void_p),
                 ("qparams", C.c_void_p)]
 
+
+class GemvItem(C.Structure):
+    """Mirror of `egt_gemv_item`."""
+    _fields_ = [("sparse", C.POINTER(View)), ("q", C.c_void_p), ("qparams", C.c_void_p),
+                ("rows", C.c_int32), ("cols", C.c_int32), ("group", C.c_int32),
+                ("x", C.c_void_p), ("y", C.c_void_p)]
+
+
+class StackPlan(C.Structure):
+    """Mirror of `egt_stack_plan`."""
+    _fields_ = [("count", C.c_int32), ("mode", C.c_int32), ("grid_x", C.c_int32), ("block_threads", C.c_int32),
+                ("lds_bytes", C.c_int32), ("x_pieces", C.c_int32), ("forms", C.c_int32), ("nitems", C.c_int32),
+                ("part_offset", C.c_int32), ("reserved", C.c_int32), ("table_bytes", C.c_uint64)]
+
+
+STACK_ENTRY_BYTES = 160
 
 _lib = None
 
@@ -82,6 +99,8 @@ def lib() -> C.CDLL:
         L.egt_fit_verify_cost.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.POINTER(C.c_double), C.POINTER(C.c_double)]
         L.egt_trigger_depth.argtypes = [C.c_double, C.c_double, C.c_double, C.c_void_p, C.c_void_p, C.c_int,
                                         C.POINTER(C.c_int), C.POINTER(C.c_double)]
+        L.egt_gemv_stack_plan.argtypes = [C.POINTER(GemvItem), C.c_int, C.c_int, C.c_void_p, C.c_size_t, C.POINTER(StackPlan)]
+        L.egt_gemv_stack_run.argtypes = [C.c_void_p, C.POINTER(StackPlan), C.c_void_p]
         for name in SYMBOLS:
             if name not in ("egt_status_str", "egt_last_hip_error"):
                 getattr(L, name).restype = C.c_int
@@ -414,16 +433,64 @@ def int4_gemv_batch(qs, qparams, rows: int, cols: int, group: int, xs, ys, strea
     prepared_int4_gemv_batch(qs, qparams, rows, cols, group, xs, ys, stream)()
 
 
+STACK_AUTO, STACK_GRID, STACK_RESIDENT = 0, 1, 2
+
+
+def prepared_gemv_stack(items, stream=None, form=STACK_AUTO):
+    """One launch for a list of products of different shapes and storage forms.
+
+    items: tuples ("sparse", Packed, x, y) or ("dense", q, qparams, rows, cols, group, x, y)
+    with device tensors.  The descriptor table is planned by the library on the host and
+    uploaded here into a device tensor that the returned call keeps alive."""
+    import torch
+    n = len(items)
+    arr = (GemvItem * n)()
+    views, keep = [], []
+    for k, it in enumerate(items):
+        if it[0] == "sparse":
+            _, p, x, y = it
+            _check_packed_dev(p)
+            v = p.view()
+            views.append(v)
+            arr[k].sparse = C.pointer(v)
+            arr[k].x, arr[k].y = _need(x, 2 * p.cols, "x", True), _need(y, 2 * p.rows, "y", True)
+            keep.append((p, x, y))
+        else:
+            _, q, qp, rows, cols, group, x, y = it
+            _check_int4_dev(q, qp, rows, cols, group)
+            arr[k].q, arr[k].qparams = _dev(q), _dev(qp)
+            arr[k].rows, arr[k].cols, arr[k].group = rows, cols, group
+            arr[k].x, arr[k].y = _need(x, 2 * cols, "x", True), _need(y, 2 * rows, "y", True)
+            keep.append((q, qp, x, y))
+    plan = StackPlan()
+    _check(lib().egt_gemv_stack_plan(arr, n, form, None, 0, C.byref(plan)))    # size query
+    table = np.zeros(int(plan.table_bytes), dtype=np.uint8)
+    _check(lib().egt_gemv_stack_plan(arr, n, form, _np_ptr(table), table.nbytes, C.byref(plan)))
+    dev = keep[0][-1].device
+    table_dev = torch.from_numpy(table).to(dev)
+    fn, tp, ref, sp = lib().egt_gemv_stack_run, table_dev.data_ptr(), C.byref(plan), _stream_ptr(stream)
+
+    def call(stream_ptr=sp, _keep=(table_dev, plan, keep, views, arr)):
+        st = fn(tp, ref, stream_ptr)
+        if st:
+            _check(st)
+    call.plan = plan
+    return call
+
+
 def prepared_stream_read(src, nbytes: int, sink, stream=None):
     fn = lib().egt_stream_read
-    args = (_dev(src), nbytes, _dev(sink), _stream_ptr(stream))
+    if src.numel() * src.element_size() < nbytes or sink.numel() * sink.element_size() < 4 * 4096:
+        raise ValueError("stream_read: src shorter than nbytes, or sink shorter than 4096 words")
+    args = (_dev(src), nbytes, _dev(sink))
+    sp = _stream_ptr(stream)
 
-    def call(_keep=(src, sink)):
-        st = fn(*args)
+    def call(stream_ptr=sp, _keep=(src, sink)):
+        st = fn(*args, stream_ptr)
         if st:
             _check(st)
     return call
 
 
 def stream_read(src, nbytes: int, sink, stream=None) -> None:
-    _check(lib().egt_stream_read(_dev(src), nbytes, _dev(sink), _stream_ptr(stream)))
+    prepared_stream_read(src, nbytes, sink, stream)()

@@ -31,7 +31,9 @@ def hipcc_path() -> str:
 
 
 def _flags(csrc: str) -> list:
-    return ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
+    # -ffp-contract=off: a multiply is fused with an add only where the source says fmaf, so
+    # the same expression gives the same bits in every kernel that contains it
+    return ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-ffp-contract=off",
             "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
             "-Wno-unused-command-line-argument", "-pthread", *EXTRA_FLAGS,
             "-I" + os.path.join(ROOT, "include"), "-I" + csrc]

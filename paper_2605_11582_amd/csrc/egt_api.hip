@@ -2,8 +2,7 @@
 // a kernel.  Nothing here synchronises or allocates.
 #include "egt_device.h"
 
-#include <cstdio>
-#include <cstdlib>
+#include "egt_tune.h"
 
 namespace {
 
@@ -41,6 +40,15 @@ inline egt_status done(hipError_t e) {
 // Each thread keeps U independent 128-bit loads in flight.
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
+__device__ __forceinline__ void fold_and_store(uint32_t acc, uint32_t *__restrict__ sink) {
+  for (int o = 32; o > 0; o >>= 1) acc ^= __shfl_xor(acc, o, 64);
+  __shared__ uint32_t part[4];
+  if ((threadIdx.x & 63) == 0) part[threadIdx.x >> 6] = acc;
+  __syncthreads();
+  if (threadIdx.x == 0) sink[blockIdx.x] = part[0] ^ part[1] ^ part[2] ^ part[3];
+}
+
+// Grid-stride form for large buffers: a fixed number of workgroups walks the buffer.
 template <int U>
 __global__ __launch_bounds__(256) void k_stream_read(const u32x4 *__restrict__ src, size_t n16,
                                                       uint32_t *__restrict__ sink) {
@@ -58,11 +66,30 @@ __global__ __launch_bounds__(256) void k_stream_read(const u32x4 *__restrict__ s
     const u32x4 a = src[i];
     acc ^= a.x ^ a.y ^ a.z ^ a.w;
   }
-  for (int o = 32; o > 0; o >>= 1) acc ^= __shfl_xor(acc, o, 64);
-  __shared__ uint32_t part[4];
-  if ((threadIdx.x & 63) == 0) part[threadIdx.x >> 6] = acc;
-  __syncthreads();
-  if (threadIdx.x == 0) sink[blockIdx.x] = part[0] ^ part[1] ^ part[2] ^ part[3];
+  fold_and_store(acc, sink);
+}
+
+// One-shot form, the launch shape of the M = 1 kernels: every workgroup owns U consecutive
+// 4 KB pieces and each of its threads requests its U words before it looks at any of them,
+// so the whole buffer is requested within the first moments of the kernel.  Words past the
+// end are read from a clamped address and do not enter the fold.
+template <int U>
+__global__ __launch_bounds__(256) void k_stream_read_shot(const u32x4 *__restrict__ src, size_t n16,
+                                                           uint32_t *__restrict__ sink) {
+  const size_t base = (size_t)blockIdx.x * (256 * U) + threadIdx.x;
+  u32x4 v[U];
+#pragma unroll
+  for (int u = 0; u < U; ++u) {
+    const size_t i = base + 256 * u;
+    v[u] = __builtin_nontemporal_load(src + (i < n16 ? i : n16 - 1));
+  }
+  uint32_t acc = 0;
+#pragma unroll
+  for (int u = 0; u < U; ++u) {
+    const uint32_t f = v[u].x ^ v[u].y ^ v[u].z ^ v[u].w;
+    acc ^= base + 256 * u < n16 ? f : 0u;
+  }
+  fold_and_store(acc, sink);
 }
 
 }  // namespace
@@ -145,20 +172,31 @@ egt_status egt_stream_read(const void *src, size_t bytes, uint32_t *sink, void *
   if (!aligned16(src)) return EGT_ERR_BUFFER;
   if (bytes == 0) return EGT_OK;
   const size_t n16 = bytes / 16;
-  int unroll = 4, per_thread = 4;                   // loads in flight, 16 B words per thread
-  if (const char *e = getenv("EGT_READ_TUNE")) sscanf(e, "%d,%d", &unroll, &per_thread);
-  if (per_thread < unroll) per_thread = unroll;
-  size_t blocks = (n16 + 256 * (size_t)per_thread - 1) / (256 * (size_t)per_thread);
-  if (blocks > 4096) blocks = 4096;
-  if (blocks < 1) blocks = 1;
-  const dim3 grid((unsigned)blocks), block(256);
+  // loads in flight per thread; shape 0 = one-shot (one workgroup per U * 4 KB, at most 4096
+  // of them), shape k > 0 = k * 256 workgroups walking the buffer
+  int unroll = 8, shape = 0;
+  egt::tune_pair("EGT_READ_TUNE", unroll, shape);
+  if (unroll != 4 && unroll != 8 && unroll != 16) unroll = 8;
+  shape = shape < 0 ? 0 : shape > 16 ? 16 : shape;
   const hipStream_t st = (hipStream_t)stream;
   const u32x4 *p = (const u32x4 *)src;
+  const size_t shot_blocks = (n16 + 256 * (size_t)unroll - 1) / (256 * (size_t)unroll);
+  if (shape == 0 && shot_blocks <= 4096) {
+    const dim3 grid((unsigned)shot_blocks), block(256);
+    switch (unroll) {
+      case 4: return done(egt::launch(k_stream_read_shot<4>, grid, block, 0, st, p, n16, sink));
+      case 16: return done(egt::launch(k_stream_read_shot<16>, grid, block, 0, st, p, n16, sink));
+      default: return done(egt::launch(k_stream_read_shot<8>, grid, block, 0, st, p, n16, sink));
+    }
+  }
+  if (shape == 0) shape = 8;
+  size_t blocks = (n16 + 255) / 256;
+  if (blocks > 256 * (size_t)shape) blocks = 256 * (size_t)shape;
+  const dim3 grid((unsigned)blocks), block(256);
   switch (unroll) {
-    case 1: return done(egt::launch(k_stream_read<1>, grid, block, 0, st, p, n16, sink));
-    case 2: return done(egt::launch(k_stream_read<2>, grid, block, 0, st, p, n16, sink));
-    case 8: return done(egt::launch(k_stream_read<8>, grid, block, 0, st, p, n16, sink));
-    default: return done(egt::launch(k_stream_read<4>, grid, block, 0, st, p, n16, sink));
+    case 4: return done(egt::launch(k_stream_read<4>, grid, block, 0, st, p, n16, sink));
+    case 16: return done(egt::launch(k_stream_read<16>, grid, block, 0, st, p, n16, sink));
+    default: return done(egt::launch(k_stream_read<8>, grid, block, 0, st, p, n16, sink));
   }
 }
 

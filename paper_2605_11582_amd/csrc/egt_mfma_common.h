@@ -98,6 +98,16 @@ __device__ __forceinline__ void lds_barrier() {
   __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
 }
 
+// Block shape of a launch of one of the M = 1 kernels, derived on the host from the matrix
+// geometry, the waves per workgroup and the tiles per wave.
+struct LaunchShape {
+  int nblocks;   // workgroups along x
+  int nwaves;    // waves per workgroup
+  int tpi;       // tiles per wave
+  int xp;        // 16-byte pieces of x each thread stages
+  size_t lds;    // dynamic LDS bytes
+};
+
 // Pointer table of a batched launch: up to EGT_MAX_BATCH identically shaped matrices,
 // selected by blockIdx.y (a single product is a batch of one).
 constexpr int EGT_MAX_BATCH = 4;

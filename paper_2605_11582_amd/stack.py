@@ -9,6 +9,7 @@ bookkeeping live here: all arithmetic runs in libegt.so.
 """
 from __future__ import annotations
 
+import os
 from dataclasses import dataclass, field
 
 import numpy as np
@@ -104,6 +105,21 @@ class LayerStack:
                                                             [m.keep[2] for m in ms], [m.y for m in ms]))
         return calls
 
+    def _item(self, m):
+        if m.kind != "d":
+            return ("sparse", m.keep[0], m.keep[1], m.y)
+        return ("dense", m.keep[0], m.keep[1], m.rows, m.cols, GROUP, m.keep[2], m.y)
+
+    def per_layer(self) -> list:
+        """One launch per decoder layer: its seven products, of three shapes, in one table."""
+        nm = len(synth.LAYER_MATRICES)
+        return [B.prepared_gemv_stack([self._item(m) for m in self.matrices[l0:l0 + nm]])
+                for l0 in range(0, len(self.matrices), nm)]
+
+    def one_launch(self):
+        """The whole stack - 224 products of mixed storage forms - in a single launch."""
+        return B.prepared_gemv_stack([self._item(m) for m in self.matrices])
+
     @staticmethod
     def build(device="cuda:0", distinct_layers=None, progress=None, plan="config4", on_matrix=None) -> "LayerStack":
         """Uploads the whole stack.  `distinct_layers`: how many layers of each kind get
@@ -114,19 +130,36 @@ class LayerStack:
         with weights of its own while its host data is alive (the dense weights are not
         kept afterwards)."""
         import torch
+        from concurrent.futures import ThreadPoolExecutor
         kinds = synth.layer_kinds(plan)
         st = LayerStack()
         cache = {"s24": [], "s14": [], "d": []}
         nm = len(synth.LAYER_MATRICES)
+        # which layers get weights of their own is known up front, so their matrices are
+        # drawn and packed by a few host threads ahead of the upload (numpy's generator and
+        # the encoder both release the interpreter lock)
+        own, count = [], {"s24": 0, "s14": 0, "d": 0}
+        for layer in range(synth.N_LAYERS):
+            if distinct_layers is None or count[kinds[layer]] < distinct_layers:
+                own.append(layer)
+                count[kinds[layer]] += 1
+        pool = ThreadPoolExecutor(max_workers=max(1, min(6, (os.cpu_count() or 2) // 2)))
+        pending, ahead = {}, 10                         # at most `ahead` matrices in flight
+        todo = [(layer, mi) for layer in own for mi in range(nm)]
+
+        def refill():
+            while todo and len(pending) < ahead:
+                key = todo.pop(0)
+                pending[key] = pool.submit(pack_layer_matrix, key[0], key[1], kinds[key[0]])
         for layer in range(synth.N_LAYERS):
             kind = kinds[layer]
-            reuse = distinct_layers is not None and len(cache[kind]) >= distinct_layers
-            if reuse:
+            if layer not in own:
                 host = cache[kind][layer % len(cache[kind])]
             else:
                 host = []
                 for mi in range(nm):
-                    w, x, packed = pack_layer_matrix(layer, mi, kind)
+                    refill()
+                    w, x, packed = pending.pop((layer, mi)).result()
                     if on_matrix:
                         on_matrix(layer, mi, kind, w, x, packed)
                     host.append((None, x, packed))
@@ -151,4 +184,5 @@ class LayerStack:
                 st.matrices.append(m)
             if progress:
                 progress(layer)
+        pool.shutdown()
         return st

@@ -97,6 +97,18 @@ def test_stack_parity_and_graph_replay():
     for m_i, m in enumerate(st.matrices):
         assert np.array_equal(m.y.cpu().numpy().view(np.uint16), eager[m_i].view(np.uint16)), ("fused", m.layer, m.name)
     print("  fused launches match the separate ones", flush=True)
+    # one launch per layer (seven products of three shapes), and the whole stack in one launch
+    for what, launches in (("one launch per layer", st.per_layer()), ("one launch per stack", [st.one_launch()])):
+        for m in st.matrices:
+            m.y.fill_(3.0)
+        for c in launches:
+            c()
+        torch.cuda.synchronize()
+        outs = [m.y.cpu().numpy() for m in st.matrices]
+        samples.check(outs, what)
+        for m_i, m in enumerate(st.matrices):
+            assert np.array_equal(outs[m_i].view(np.uint16), eager[m_i].view(np.uint16)), (what, m.layer, m.name)
+        print(f"  {what}: {len(launches)} launches match the oracle and the separate launches bit for bit", flush=True)
     # HIP graph of the 224 launches: several replays, with eager work between them
     side = torch.cuda.Stream()
     with torch.cuda.stream(side):
@@ -150,6 +162,131 @@ def test_three_way_mix_stack_parity():
     torch.cuda.synchronize()
     for m_i, m in enumerate(st.matrices):
         assert np.array_equal(m.y.cpu().numpy().view(np.uint16), eager[m_i].view(np.uint16)), ("fused", m.layer, m.name)
+
+
+def test_mixed_table_in_one_launch_small_shapes():
+    # egt_gemv_stack_run on a table of small matrices of every storage form and of several
+    # shapes (ragged row counts, one and several tiles per row, several rows per tile, an empty
+    # matrix): element by element against the oracle and bit for bit against separate calls
+    torch = G.torch_mod()
+    specs = [("s24", 37, 4096), ("d", 50, 4096), ("s14", 45, 4096), ("s24", 21, 11008), ("d", 19, 11008),
+             ("s14", 21, 11008), ("s24", 70, 2048), ("s24", 0, 4096), ("d", 33, 8192), ("s24", 300, 8192),
+             ("s14", 19, 2048), ("d", 131, 1024), ("s24", 257, 1024), ("s24", 1003, 4096)]
+    items, refs, singles = [], [], []
+    for k, (kind, rows, cols) in enumerate(specs):
+        w = synth.weights(rows, cols, 4400 + k)
+        x = synth.activations(cols, 4400 + k)
+        xd = G.to_dev(x.view(np.uint16)).view(torch.float16)
+        ybuf = torch.full((rows + 128,), G.CANARY, dtype=torch.int16, device="cuda")
+        y = ybuf[64:64 + rows].view(torch.float16)
+        y1 = torch.empty(rows, dtype=torch.float16, device="cuda")
+        if kind == "d":
+            q, qp = B.quant_int4(w, 128)
+            qd, qpd = G.to_dev(q), G.to_dev(qp)
+            items.append(("dense", qd, qpd, rows, cols, 128, xd, y))
+            oq, oqp = O.quant_int4_dense(w, 128)
+            refs.append(O.int4_gemv(oq, oqp, 128, x))
+            B.int4_gemv(qd, qpd, rows, cols, 128, xd, y1)
+        else:
+            n = S.N_KEEP[kind]
+            mask = O.prune_n4_magnitude(w, n)
+            p = B.pack_2bitcsr(w, mask, n, 128, 0).to("cuda")
+            items.append(("sparse", p, xd, y))
+            refs.append(O.gemv(O.pack_2bitcsr(w, mask, n, 128, 0), x))
+            B.sparse_gemv(p, xd, y1)
+        singles.append((ybuf, y1))
+    call = B.prepared_gemv_stack(items)
+    assert call.plan.count == len(specs) and call.plan.block_threads == 768 and call.plan.mode == 0   # 1, 2, 3, 4 and 6 tiles per row
+    for rep in range(2):
+        call()
+        torch.cuda.synchronize()
+        for k, (kind, rows, cols) in enumerate(specs):
+            ybuf, y1 = singles[k]
+            host = ybuf.cpu().numpy().view(np.uint16)
+            assert np.all(host[:64] == G.CANARY) and np.all(host[64 + rows:] == G.CANARY), ("write outside y", k)
+            y = host[64:64 + rows].view(np.float16)
+            G.assert_close(y, refs[k][0], refs[k][1], f"table item {k} {kind} {rows}x{cols}")
+            assert np.array_equal(y.view(np.uint16), y1.cpu().numpy().view(np.uint16)), (k, kind, rows, cols)
+            ybuf[64:64 + rows].fill_(0)
+    # other wave counts: one tile per row everywhere -> 4 waves; four tiles per row -> 4 waves too
+    small = B.prepared_gemv_stack([items[0], items[2]])
+    assert small.plan.block_threads == 256
+    small()
+    torch.cuda.synchronize()
+    for k in (0, 2):
+        y = items[k][-1].cpu().numpy()
+        G.assert_close(y, refs[k][0], refs[k][1], f"4-wave table item {k}")
+
+
+def test_row_block_list_on_ragged_shapes():
+    # the resident-workgroup form on a table with row counts that are
+    # no multiple of a row block, one, two and six tiles per row, a matrix shorter than one row
+    # block and an empty one: sampled rows against the oracle (which re-encodes them), all
+    # rows bit for bit against the separate calls, and nothing written outside y
+    torch = G.torch_mod()
+    specs = [("s24", 11008, 4096), ("d", 4099, 11008), ("s24", 4097, 8192), ("d", 1001, 4096), ("s24", 0, 4096),
+             ("s24", 37, 4096), ("d", 5, 4096), ("s24", 145, 11008)]
+    items, checks = [], []
+    for k, (kind, rows, cols) in enumerate(specs):
+        print(f"  packing {kind} {rows}x{cols}", flush=True)
+        w = synth.weights(rows, cols, 4700 + k)
+        x = synth.activations(cols, 4700 + k)
+        xd = G.to_dev(x.view(np.uint16)).view(torch.float16)
+        ybuf = torch.full((rows + 128,), G.CANARY, dtype=torch.int16, device="cuda")
+        y = ybuf[64:64 + rows].view(torch.float16)
+        y1 = torch.empty(rows, dtype=torch.float16, device="cuda")
+        pick = G.sample_rows(rows, 40, k) if rows else np.zeros(0, dtype=np.int64)
+        if kind == "d":
+            q, qp = B.quant_int4(w, 128)
+            qd, qpd = G.to_dev(q), G.to_dev(qp)
+            items.append(("dense", qd, qpd, rows, cols, 128, xd, y))
+            oq, oqp = O.quant_int4_dense(w[pick], 128)
+            assert np.array_equal(oq, q[pick]) and np.array_equal(oqp, qp[pick])
+            ref = O.int4_gemv(oq, oqp, 128, x)
+            B.int4_gemv(qd, qpd, rows, cols, 128, xd, y1)
+        else:
+            ph = B.pack_2bitcsr(w, B.prune_n4(w, 2), 2, 128, 0)
+            if rows:
+                o = O.pack_2bitcsr(w[pick], O.prune_n4_magnitude(w[pick], 2), 2, 128, 0)
+                sub = G.row_subset(ph, pick)
+                for name in ("values", "idx", "qparams"):
+                    assert np.array_equal(o[name], sub[name]), name
+                ref = O.gemv(o, x)
+            else:
+                ref = (np.zeros(0), np.zeros(0))
+            p = ph.to("cuda")
+            items.append(("sparse", p, xd, y))
+            B.sparse_gemv(p, xd, y1)
+        checks.append((ybuf, y1, pick, ref))
+    call = B.prepared_gemv_stack(items, form=B.STACK_RESIDENT)
+    assert (call.plan.mode, call.plan.block_threads) == (1, 768) and call.plan.nitems > 0
+    for rep in range(3):
+        call()
+        torch.cuda.synchronize()
+        for k, (kind, rows, cols) in enumerate(specs):
+            ybuf, y1, pick, ref = checks[k]
+            host = ybuf.cpu().numpy().view(np.uint16)
+            assert np.all(host[:64] == G.CANARY) and np.all(host[64 + rows:] == G.CANARY), ("write outside y", k)
+            y = host[64:64 + rows].view(np.float16)
+            if rows:
+                G.assert_close(y[pick], ref[0], ref[1], f"row blocks item {k} {kind} {rows}x{cols}")
+            assert np.array_equal(y.view(np.uint16), y1.cpu().numpy().view(np.uint16)), (k, kind, rows, cols)
+            ybuf[64:64 + rows].fill_(0)
+    # a broken row pointer gives NaN in that row and leaves the other rows alone
+    p0 = items[0][1]
+    rp = p0.row_ptr.view(torch.int32)
+    saved = rp[[7, 4000]].clone()
+    rp[7] += 8
+    rp[4000] = 0
+    call()
+    torch.cuda.synchronize()
+    y = checks[0][0].cpu().numpy().view(np.uint16)[64:64 + 11008].view(np.float16)
+    good = checks[0][1].cpu().numpy()
+    assert np.isnan(y[7]) and np.isnan(y[4000])
+    keep = np.ones(11008, dtype=bool)
+    keep[[7, 4000]] = False
+    assert np.array_equal(y[keep].view(np.uint16), good[keep].view(np.uint16))
+    rp[[7, 4000]] = saved
 
 
 def test_trigger_model_on_a_measured_sweep():

@@ -334,6 +334,124 @@ def test_device_entry_points_reject_bad_arguments_without_a_gpu():
     assert L.egt_stream_read(None, 32, 16, None) == 1
 
 
+def _fake_items(views, dense=()):
+    """Items over fake, aligned, never dereferenced device pointers."""
+    n = len(views) + len(dense)
+    items = (B.GemvItem * n)()
+    for k, v in enumerate(views):
+        items[k].sparse = ctypes.pointer(v)
+    for k, (rows, cols, group) in enumerate(dense, start=len(views)):
+        items[k].q, items[k].qparams, items[k].rows, items[k].cols, items[k].group = 16, 16, rows, cols, group
+    for it in items:
+        it.x, it.y = 16, 16
+    return items
+
+
+def test_stack_plan_checks_items_and_reports_the_launch_shape():
+    L = B.lib()
+    view = B.View(4096, 4096, 2, 128, 0, 16, 16, 16, 16)          # fake aligned device pointers, never used
+    down = B.View(4096, 11008, 2, 128, 0, 16, 16, 16, 16)
+    one4 = B.View(4096, 11008, 1, 128, 0, 16, 16, 16, 16)
+    items = _fake_items([view, down, one4], [(4096, 11008, 128)])
+    plan = B.StackPlan()
+    assert L.egt_gemv_stack_plan(items, 4, 0, None, 0, ctypes.byref(plan)) == 0          # size query
+    # tiles per row 1, 3, 2 and 6: six waves; a 1:4 matrix: short-lived workgroups, every body;
+    # the widest x (1:4, K = 11008: 2048 pieces) needs 6 -> 8 pieces per thread
+    assert (plan.count, plan.mode, plan.block_threads, plan.x_pieces, plan.forms) == (4, 0, 384, 8, 7)
+    assert plan.table_bytes == 4 * B.STACK_ENTRY_BYTES and plan.grid_x == 512 and 0 < plan.lds_bytes <= 65536
+    table = np.full(4 * B.STACK_ENTRY_BYTES, 0xA5, dtype=np.uint8)
+    assert L.egt_gemv_stack_plan(items, 4, 0, table.ctypes.data, table.nbytes - 1, ctypes.byref(plan)) == 2
+    assert np.all(table == 0xA5)
+    assert L.egt_gemv_stack_plan(items, 4, 0, table.ctypes.data, table.nbytes, ctypes.byref(plan)) == 0
+    assert not np.all(table == 0xA5)
+    # errors leave table and plan untouched
+    table[:] = 0xA5
+    plan2 = B.StackPlan(-1)
+    bad = B.View(4096, 4096, 2, 0, 1, 16, 16, 16, None)                # FP16 values: no multi-matrix form
+    items[1].sparse = ctypes.pointer(bad)
+    assert L.egt_gemv_stack_plan(items, 4, 0, table.ctypes.data, table.nbytes, ctypes.byref(plan2)) == 6
+    assert np.all(table == 0xA5) and plan2.count == -1
+    items[1].sparse = ctypes.pointer(down)
+    items[3].group = 96                                                # 11008 % 96 != 0
+    assert L.egt_gemv_stack_plan(items, 4, 0, table.ctypes.data, table.nbytes, ctypes.byref(plan2)) == 2
+    items[3].group = 64                                                # dense groups below 128: not in this form
+    assert L.egt_gemv_stack_plan(items, 4, 0, table.ctypes.data, table.nbytes, ctypes.byref(plan2)) == 6
+    items[3].group = 128
+    items[2].x = 24
+    assert L.egt_gemv_stack_plan(items, 4, 0, table.ctypes.data, table.nbytes, ctypes.byref(plan2)) == 5
+    items[2].x = None
+    assert L.egt_gemv_stack_plan(items, 4, 0, table.ctypes.data, table.nbytes, ctypes.byref(plan2)) == 1
+    items[2].x = 16
+    assert L.egt_gemv_stack_plan(items, 0, 0, table.ctypes.data, table.nbytes, ctypes.byref(plan2)) == 2
+    assert L.egt_gemv_stack_plan(None, 4, 0, table.ctypes.data, table.nbytes, ctypes.byref(plan2)) == 1
+    wide = B.View(64, 16384, 2, 128, 0, 16, 16, 16, 16)                # four tiles per row beside three: twelve waves
+    items[0].sparse = ctypes.pointer(wide)
+    assert L.egt_gemv_stack_plan(items, 4, 0, None, 0, ctypes.byref(plan2)) == 0 and plan2.block_threads == 768
+    # the run call checks the plan before anything is launched
+    assert L.egt_gemv_stack_run(None, ctypes.byref(plan), None) == 1
+    assert L.egt_gemv_stack_run(24, ctypes.byref(plan), None) == 5
+    for field, value in (("count", 0), ("block_threads", 100), ("block_threads", 2048), ("lds_bytes", 1 << 20), ("x_pieces", 3),
+                         ("forms", 0), ("forms", 8), ("mode", 2)):
+        broken = B.StackPlan.from_buffer_copy(plan)
+        setattr(broken, field, value)
+        assert L.egt_gemv_stack_run(16, ctypes.byref(broken), None) == 2, field
+    empty = B.StackPlan.from_buffer_copy(plan)
+    empty.grid_x = 0
+    assert L.egt_gemv_stack_run(16, ctypes.byref(empty), None) == 0       # all matrices empty: nothing to launch
+
+
+def test_stack_plan_cuts_a_large_table_into_row_blocks():
+    # three decoder layers of 2:4 and dense INT4 matrices (more than 256 MB): resident
+    # workgroups walk a list of row blocks; the list covers every row of every matrix exactly once
+    L = B.lib()
+    layer = [B.View(r, c, 2, 128, 0, 16, 16, 16, 16) for (_, r, c) in synth.LAYER_MATRICES]
+    dense = [(r, c, 128) for (_, r, c) in synth.LAYER_MATRICES]
+    items = _fake_items(layer + layer, dense)
+    plan = B.StackPlan()
+    assert L.egt_gemv_stack_plan(items, 21, B.STACK_AUTO, None, 0, ctypes.byref(plan)) == 0
+    assert (plan.mode, plan.block_threads, plan.forms) == (1, 768, 5)      # tiles per row 1, 2, 3, 6: twelve waves
+    assert plan.grid_x == 512 and plan.nitems >= plan.grid_x
+    first_bytes = (4 * (plan.grid_x + 1) + 15) // 16 * 16
+    assert plan.table_bytes == 21 * B.STACK_ENTRY_BYTES + first_bytes + 16 * plan.nitems
+    table = np.zeros(plan.table_bytes, dtype=np.uint8)
+    assert L.egt_gemv_stack_plan(items, 21, B.STACK_AUTO, table.ctypes.data, table.nbytes, ctypes.byref(plan)) == 0
+    off = 21 * B.STACK_ENTRY_BYTES
+    first = table[off:off + 4 * (plan.grid_x + 1)].view(np.uint32)
+    work = table[off + first_bytes:].view(np.uint32).reshape(-1, 4)
+    assert first[0] == 0 and first[-1] == plan.nitems and np.all(np.diff(first.astype(np.int64)) >= 0)
+    rows = [r for (_, r, _) in synth.LAYER_MATRICES] * 3
+    cols = [c for (_, _, c) in synth.LAYER_MATRICES] * 3
+    row_bytes = [c // 4 + c // 8 + 4 * (c // 128) if k < 14 else c // 2 + 4 * (c // 128) for k, c in enumerate(cols)]
+    covered = [np.zeros(r, dtype=np.int32) for r in rows]
+    per_block = np.zeros(plan.grid_x, dtype=np.int64)
+    for b in range(plan.grid_x):
+        for m, r0, n, _ in work[first[b]:first[b + 1]]:
+            desc = table[m * B.STACK_ENTRY_BYTES:(m + 1) * B.STACK_ENTRY_BYTES].view(np.int32)
+            item_rows = int(desc[21])                   # six pointers, form, rows, nchunks, phases, gshift, groups, 3 extents, item_rows
+            assert 0 < n <= item_rows <= 2048 and 16 * int(desc[15]) * item_rows <= 24 * 1024
+            covered[m][r0:r0 + n] += 1
+            per_block[b] += int(n) * row_bytes[m]
+    assert all(np.all(c == 1) for c in covered)         # every row of every matrix exactly once
+    # every workgroup streams the same number of bytes, to within one row, and a contiguous stretch
+    assert per_block.max() - per_block.min() <= 2 * max(row_bytes)
+    flat = [(int(m), int(r0)) for m, r0, _, _ in work]
+    assert flat == sorted(flat)
+    # a smaller table keeps the short-lived workgroups unless the caller asks otherwise
+    one = _fake_items(layer[:4])
+    assert L.egt_gemv_stack_plan(one, 4, B.STACK_AUTO, None, 0, ctypes.byref(plan)) == 0 and plan.mode == 0
+    assert L.egt_gemv_stack_plan(one, 4, B.STACK_RESIDENT, None, 0, ctypes.byref(plan)) == 0 and plan.mode == 1
+    assert L.egt_gemv_stack_plan(items, 21, B.STACK_GRID, None, 0, ctypes.byref(plan)) == 0 and plan.mode == 0
+    assert L.egt_gemv_stack_plan(items, 21, 3, None, 0, ctypes.byref(plan)) == 2
+    narrow = _fake_items([B.View(4096, 1024, 2, 128, 0, 16, 16, 16, 16)])      # several rows per tile: no resident form
+    assert L.egt_gemv_stack_plan(narrow, 1, B.STACK_RESIDENT, None, 0, ctypes.byref(plan)) == 6
+    # inconsistent mode-1 plans are refused
+    assert L.egt_gemv_stack_plan(items, 21, B.STACK_AUTO, None, 0, ctypes.byref(plan)) == 0
+    for field, value in (("nitems", 0), ("grid_x", plan.nitems + 1), ("table_bytes", 5), ("part_offset", 1 << 20)):
+        broken = B.StackPlan.from_buffer_copy(plan)
+        setattr(broken, field, value)
+        assert L.egt_gemv_stack_run(16, ctypes.byref(broken), None) == 2, field
+
+
 def test_trigger_cost_model():
     # exact line is recovered; noisy points match the oracle's least squares
     m = [1, 2, 4, 8, 16, 32, 64]
