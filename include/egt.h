@@ -174,6 +174,25 @@ egt_status egt_sparse_gemv(const egt_2bitcsr *w, const uint16_t *x, uint16_t *y,
 egt_status egt_sparse_gemm_smallm(const egt_2bitcsr *w, const uint16_t *X, int64_t ldx,
                                   uint16_t *Y, int64_t ldy, int M, void *stream);
 
+/* The same product with K split over workgroups (Sec. 3.4: the cost of a verification step
+ * grows with the number of candidates; from about five candidates on, what grows is the
+ * traffic of X, which every compute unit of the one-launch form reads in full).  The grid is
+ * cut into row blocks x K slices, a workgroup reads only its slice of X, the FP32 partial
+ * sums of the slices pass through `workspace` (DEVICE memory of the caller, 16-byte
+ * aligned) and a second kernel adds them in slice order, so results are reproducible
+ * run to run; they differ from egt_sparse_gemm_smallm's in the order of the FP32 additions
+ * only.  The workspace is dead after the call's kernels have run; calls that share one
+ * must not overlap.
+ * egt_sparse_gemm_smallm_ws_bytes (HOST): the bytes this matrix and M need; 0 where the
+ * split form is not the faster one (it is for 2:4 INT4 with groups of 64 columns and more,
+ * M > 16, K >= 8192 and at most 4096 rows: the down projection under verification), in
+ * which case egt_sparse_gemm_smallm_ws ignores the workspace and is the one-launch call.
+ * EGT_ERR_SHAPE when workspace_bytes is smaller than required. */
+egt_status egt_sparse_gemm_smallm_ws_bytes(const egt_2bitcsr *w, int64_t ldx, int M, size_t *bytes);
+egt_status egt_sparse_gemm_smallm_ws(const egt_2bitcsr *w, const uint16_t *X, int64_t ldx,
+                                     uint16_t *Y, int64_t ldy, int M, void *workspace,
+                                     size_t workspace_bytes, void *stream);
+
 /* DEVICE.  `count` (1..4) independent products y[k] = W[k].x[k] of identically shaped
  * matrices (same rows, cols, n_keep, group_size, val_kind; else EGT_ERR_SHAPE) in one
  * launch: the q/k/v or gate/up projections of a decoder layer.  Sec. 3.3 starts from

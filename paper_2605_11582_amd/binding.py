@@ -23,7 +23,7 @@ SYMBOLS = (
     "egt_unpack_2bitcsr", "egt_quant_int4", "egt_int4_gemv", "egt_sparse_gemv",
     "egt_sparse_gemm_smallm", "egt_stream_read", "egt_sparse_gemv_batch", "egt_int4_gemv_batch",
     "egt_fit_verify_cost", "egt_trigger_depth", "egt_prune_n4_importance", "egt_pack_2bitcsr_rowgroups",
-    "egt_gemv_stack_plan", "egt_gemv_stack_run",
+    "egt_gemv_stack_plan", "egt_gemv_stack_run", "egt_sparse_gemm_smallm_ws_bytes", "egt_sparse_gemm_smallm_ws",
 )
 
 
@@ -101,6 +101,9 @@ def lib() -> C.CDLL:
                                         C.POINTER(C.c_int), C.POINTER(C.c_double)]
         L.egt_gemv_stack_plan.argtypes = [C.POINTER(GemvItem), C.c_int, C.c_int, C.c_void_p, C.c_size_t, C.POINTER(StackPlan)]
         L.egt_gemv_stack_run.argtypes = [C.c_void_p, C.POINTER(StackPlan), C.c_void_p]
+        L.egt_sparse_gemm_smallm_ws_bytes.argtypes = [C.POINTER(View), C.c_int64, C.c_int, C.POINTER(C.c_size_t)]
+        L.egt_sparse_gemm_smallm_ws.argtypes = [C.POINTER(View), C.c_void_p, C.c_int64, C.c_void_p, C.c_int64, C.c_int,
+                                                C.c_void_p, C.c_size_t, C.c_void_p]
         for name in SYMBOLS:
             if name not in ("egt_status_str", "egt_last_hip_error"):
                 getattr(L, name).restype = C.c_int
@@ -373,6 +376,38 @@ def prepared_sparse_gemm_smallm(p: Packed, X, Y, stream=None):
         if st:
             _check(st)
     return call
+
+
+def smallm_ws_bytes(p: Packed, M: int, ldx=None) -> int:
+    """Bytes of device workspace `sparse_gemm_smallm_ws` needs (0: none)."""
+    out = C.c_size_t()
+    v = p.view()
+    _check(lib().egt_sparse_gemm_smallm_ws_bytes(C.byref(v), p.cols if ldx is None else ldx, M, C.byref(out)))
+    return int(out.value)
+
+
+def prepared_sparse_gemm_smallm_ws(p: Packed, X, Y, workspace, stream=None):
+    """The K-split form; `workspace`: a device tensor of at least smallm_ws_bytes bytes (or None
+    when that is 0)."""
+    fn, v = lib().egt_sparse_gemm_smallm_ws, p.view()
+    _check_xy(p, X, Y)
+    need = smallm_ws_bytes(p, X.shape[0], X.stride(0))
+    if need and (workspace is None or workspace.numel() * workspace.element_size() < need):
+        raise ValueError(f"workspace of {need} bytes required")
+    wp = 0 if workspace is None else _dev(workspace)
+    wb = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    args = (C.byref(v), X.data_ptr(), X.stride(0), Y.data_ptr(), Y.stride(0), X.shape[0], wp, wb)
+    sp = _stream_ptr(stream)
+
+    def call(stream_ptr=sp, _keep=(v, p, X, Y, workspace)):
+        st = fn(*args, stream_ptr)
+        if st:
+            _check(st)
+    return call
+
+
+def sparse_gemm_smallm_ws(p: Packed, X, Y, workspace, stream=None) -> None:
+    prepared_sparse_gemm_smallm_ws(p, X, Y, workspace, stream)()
 
 
 def prepared_int4_gemv(q, qparams, rows: int, cols: int, group: int, x, y, stream=None):

@@ -6,14 +6,15 @@
 
 namespace {
 
-egt_status check_view(const egt_2bitcsr *w) {
+// `pointers`: also require the buffers (a size query looks at the shape only)
+egt_status check_view(const egt_2bitcsr *w, bool pointers = true) {
   if (!w) return EGT_ERR_NULL;
   if (w->rows < 0 || w->cols < 0 || w->cols % 32 != 0) return EGT_ERR_SHAPE;
   if (w->n_keep < 1 || w->n_keep > 4) return EGT_ERR_SHAPE;
   if (w->val_kind == EGT_VAL_INT4) {
     if (w->group_size <= 0 || w->group_size % 4 != 0 || w->cols % w->group_size != 0)
       return EGT_ERR_SHAPE;
-    if (!w->qparams && w->rows != 0) return EGT_ERR_NULL;
+    if (pointers && !w->qparams && w->rows != 0) return EGT_ERR_NULL;
   } else if (w->val_kind == EGT_VAL_FP16) {
     if (w->group_size != 0) return EGT_ERR_SHAPE;
   } else {
@@ -21,7 +22,7 @@ egt_status check_view(const egt_2bitcsr *w) {
   }
   if ((uint64_t)w->rows * (uint64_t)w->n_keep * (uint64_t)(w->cols / 4) >= (1ull << 32))
     return EGT_ERR_SHAPE;
-  if (w->rows == 0) return EGT_OK;                  // empty matrix: its buffers may be NULL
+  if (w->rows == 0 || !pointers) return EGT_OK;     // empty matrix: its buffers may be NULL
   if (!w->row_ptr || !w->values || !w->idx) return EGT_ERR_NULL;
   return EGT_OK;
 }
@@ -123,6 +124,34 @@ egt_status egt_sparse_gemm_smallm(const egt_2bitcsr *w, const uint16_t *X, int64
       (w->qparams && !aligned16(w->qparams)) || !aligned16(X))
     return EGT_ERR_BUFFER;
   return done(egt::launch_sparse(*w, X, ldx, Y, ldy, M, (hipStream_t)stream));
+}
+
+egt_status egt_sparse_gemm_smallm_ws_bytes(const egt_2bitcsr *w, int64_t ldx, int M, size_t *bytes) {
+  if (!bytes) return EGT_ERR_NULL;
+  const egt_status st = check_view(w, false);
+  if (st != EGT_OK) return st;
+  if (M < 1 || M > 64 || ldx < w->cols) return EGT_ERR_SHAPE;
+  size_t need = 0;
+  if (w->rows > 0) egt::sparse_smallm_split_bytes(*w, ldx, M, need);
+  *bytes = need;
+  return EGT_OK;
+}
+
+egt_status egt_sparse_gemm_smallm_ws(const egt_2bitcsr *w, const uint16_t *X, int64_t ldx, uint16_t *Y,
+                                     int64_t ldy, int M, void *workspace, size_t workspace_bytes, void *stream) {
+  const egt_status st = check_view(w);
+  if (st != EGT_OK) return st;
+  if (M < 1 || M > 64 || ldx < w->cols || ldy < w->rows) return EGT_ERR_SHAPE;
+  if (w->rows == 0) return EGT_OK;
+  size_t need = 0;
+  const bool split = egt::sparse_smallm_split_bytes(*w, ldx, M, need) && ldx % 8 == 0;
+  if (!split) return egt_sparse_gemm_smallm(w, X, ldx, Y, ldy, M, stream);   // no workspace needed: the one-launch form
+  if (!X || !Y || !workspace) return EGT_ERR_NULL;
+  if (workspace_bytes < need) return EGT_ERR_SHAPE;
+  if (!aligned16(w->row_ptr) || !aligned16(w->values) || !aligned16(w->idx) || (w->qparams && !aligned16(w->qparams)) ||
+      !aligned16(X) || !aligned16(workspace))
+    return EGT_ERR_BUFFER;
+  return done(egt::launch_sparse_smallm_split(*w, X, ldx, Y, ldy, M, (float *)workspace, (hipStream_t)stream));
 }
 
 egt_status egt_sparse_gemv(const egt_2bitcsr *w, const uint16_t *x, uint16_t *y, void *stream) {

@@ -44,6 +44,12 @@ bool sparse_smallm_supported(const egt_2bitcsr &w, int64_t ldx, int M);
 hipError_t launch_sparse_smallm(const egt_2bitcsr &w, const uint16_t *X, int64_t ldx, uint16_t *Y,
                                 int64_t ldy, int M, hipStream_t stream);
 
+// the same with K split over workgroups and FP32 partial sums in a workspace of the caller
+// (sparse_smallm_split_bytes: false if this shape and M do not use the split form)
+bool sparse_smallm_split_bytes(const egt_2bitcsr &w, int64_t ldx, int M, size_t &bytes);
+hipError_t launch_sparse_smallm_split(const egt_2bitcsr &w, const uint16_t *X, int64_t ldx, uint16_t *Y,
+                                      int64_t ldy, int M, float *ws, hipStream_t stream);
+
 // dense INT4, M = 1, on the matrix cores (group sizes 32 << j; see int4_m1_supported)
 bool int4_m1_supported(int cols, int group);
 hipError_t launch_int4_m1(const uint8_t *q, const uint16_t *qparams, int rows, int cols, int group,

@@ -69,6 +69,12 @@ struct SmallMKsGeom {
   int64_t ldx, ldy;
   uint32_t nib_mask, nib_magic;                        // 0x00F0000F, FP16 {1024.0, 64.0}
   uint32_t m8, m4, m2;                                 // masks of spread_idx
+  // K split over workgroups (blockIdx.y = slice s of nslices: the K-steps
+  // [s * nsteps / nslices, (s + 1) * nsteps / nslices)), and where the FP32 partial sums of
+  // slice s, token m, row r go: ws[(s * M + m) * ws_ld + r]
+  int nslices;
+  int64_t ws_ld;
+  float *ws;
 };
 
 template <int KIND, int QW>
@@ -97,7 +103,9 @@ __device__ __forceinline__ uint32_t quad_bcast(uint32_t v) {     // value of lan
 // KIND: INT4 or FP16 values.  NT: token groups per pass.  NIT: row tiles per workgroup.
 // NWMAX: waves per workgroup at most.  QW: {scale, zero} pairs per chunk.  N1: 1:4.
 // RND: a workgroup may own more than NIT row tiles and takes them in rounds.
-template <int KIND, int NT, int NIT, int NWMAX, int QW, bool N1, bool RND>
+// KS: the grid's y dimension splits K; a workgroup walks only the K-steps of its slice and
+// leaves FP32 partial sums in the caller's workspace (k_smallm_sum_slices finishes them).
+template <int KIND, int NT, int NIT, int NWMAX, int QW, bool N1, bool RND, bool KS = false>
 __global__ __launch_bounds__(64 * NWMAX) void k_sparse_smallm_ks(const uint32_t *__restrict__ row_ptr,
                                                                   const uint8_t *__restrict__ values,
                                                                   const uint8_t *__restrict__ idx,
@@ -137,7 +145,10 @@ __global__ __launch_bounds__(64 * NWMAX) void k_sparse_smallm_ks(const uint32_t 
   const int mytiles = (g.ntiles - (int)blockIdx.x + (int)gridDim.x - 1) / (int)gridDim.x;
   const int rounds = RND ? (mytiles + NIT - 1) / NIT : 1;
   auto tiles_of = [&](int rr) { return RND ? min(NIT, mytiles - rr * NIT) : mytiles; };
-  const int phases = (g.nsteps + nw - 1) / nw;
+  // the K-steps of this workgroup: [step0, nsteps)
+  const int step0 = KS ? (int)blockIdx.y * g.nsteps / g.nslices : 0;
+  const int nsteps = KS ? ((int)blockIdx.y + 1) * g.nsteps / g.nslices : g.nsteps;
+  const int phases = (nsteps - step0 + nw - 1) / nw;
   const uint32_t magic = in_vgpr(g.nib_magic);
   const uint32_t S_row = (uint32_t)g.nchunks * 32u;
   uint8_t *region = xs + wave * REGION;
@@ -168,7 +179,7 @@ __global__ __launch_bounds__(64 * NWMAX) void k_sparse_smallm_ks(const uint32_t 
     const bool on = it < nit_r;                                               // uniform
     const uint32_t off_range = 0xFFFFFFF0u;
     const int rt = (int)blockIdx.x + ((RND ? rr * NIT : 0) + min(it, nit_r - 1)) * (int)gridDim.x;
-    const int s = min(step, g.nsteps - 1);
+    const int s = min(step, nsteps - 1);
     // (the lane offsets are recomputed at every request: kept across the loops they would
     //  occupy a dozen registers)
     const uint32_t rel = (uint32_t)min((int)in_vgpr((uint32_t)li), g.rows - 1 - 16 * rt);   // row inside the tile (clamped)
@@ -245,7 +256,7 @@ __global__ __launch_bounds__(64 * NWMAX) void k_sparse_smallm_ks(const uint32_t 
   const int xtl = lane >> 5;
   const int slot_piece = N1 ? lane : ((lane & 31) ^ xtl);      // piece of X this lane delivers
   auto dma_x = [&](int j, int step) {
-    const int s = min(step, g.nsteps - 1);
+    const int s = min(step, nsteps - 1);
     const int vp = min(PIECES, g.kpieces - PIECES * s);         // pieces of the step inside K
     const uint32_t xs0 = (uint32_t)(16 * PIECES) * (uint32_t)s;
     const uint32_t off_lo = 16u * (uint32_t)min(slot_piece, vp - 1);
@@ -366,12 +377,12 @@ __global__ __launch_bounds__(64 * NWMAX) void k_sparse_smallm_ks(const uint32_t 
   ATile<KIND, QW> raw[NIT], raw2[DEEP ? NIT : 1];
   // first requests of a pass: X and the A tiles of phase 0 (DEEP: and the tiles of phase 1)
   auto start_pass = [&](int rr, int j) {
-    dma_x(j, wave);
+    dma_x(j, step0 + wave);
 #pragma unroll
-    for (int it = 0; it < NIT; ++it) load_a(raw[it], it, wave, rr);
+    for (int it = 0; it < NIT; ++it) load_a(raw[it], it, step0 + wave, rr);
     if (DEEP && phases > 1) {
 #pragma unroll
-      for (int it = 0; it < NIT; ++it) load_a(raw2[it], it, wave + nw, rr);
+      for (int it = 0; it < NIT; ++it) load_a(raw2[it], it, step0 + wave + nw, rr);
     }
   };
   start_pass(0, 0);
@@ -389,7 +400,7 @@ __global__ __launch_bounds__(64 * NWMAX) void k_sparse_smallm_ks(const uint32_t 
     // DEEP: pending at the top of phase p are, in request order, A(p), X(p), A(p + 1)
     auto deep_phase = [&](ATile<KIND, QW> (&cur)[NIT], int p) {
       constexpr int NA = NIT * 5;
-      const int step = p * nw + wave;
+      const int step = step0 + p * nw + wave;
       u8v bx[NM];
       ATile<KIND, QW> t[NIT];
       if (p + 1 >= phases) {
@@ -433,13 +444,13 @@ __global__ __launch_bounds__(64 * NWMAX) void k_sparse_smallm_ks(const uint32_t 
       }
     };
     if constexpr (DEEP) {
-      for (int p = 0; p < phases && p * nw + wave < g.nsteps; p += 2) {
+      for (int p = 0; p < phases && step0 + p * nw + wave < nsteps; p += 2) {
         deep_phase(raw, p);
-        if (p + 1 < phases && (p + 1) * nw + wave < g.nsteps) deep_phase(raw2, p + 1);
+        if (p + 1 < phases && step0 + (p + 1) * nw + wave < nsteps) deep_phase(raw2, p + 1);
       }
     }
-    for (int p = 0; !DEEP && p < phases && p * nw + wave < g.nsteps; ++p) {
-      const int step = p * nw + wave;
+    for (int p = 0; !DEEP && p < phases && step0 + p * nw + wave < nsteps; ++p) {
+      const int step = step0 + p * nw + wave;
       const bool more = p + 1 < phases;
       constexpr int NA = NIT * (INT4 ? 3 : 5);         // loads of the A tiles of one phase (any QW)
       u8v bx[NM];
@@ -556,6 +567,12 @@ __global__ __launch_bounds__(64 * NWMAX) void k_sparse_smallm_ks(const uint32_t 
       const int row0 = 16 * ((int)blockIdx.x + (r * NIT + it) * (int)gridDim.x) + 4 * (sl >> 4);
       const int row = row0 + v;
       const int tok = 16 * (j0 + jj) + (sl & 15);
+      if constexpr (KS) {
+        // partial sum of this slice; a row with a broken pointer gets NaN from every slice
+        if (tok < g.M && row < g.rows)
+          g.ws[((int64_t)blockIdx.y * g.M + tok) * g.ws_ld + row] = flags[16 * it + 4 * (sl >> 4) + v] ? sum : __builtin_nanf("");
+        continue;
+      }
       uint32_t hv = 0x7E00u;
       if (flags[16 * it + 4 * (sl >> 4) + v]) hv = __half_as_ushort(__float2half(sum));
       const uint32_t h1 = quad_bcast<1>(hv), h2 = quad_bcast<2>(hv), h3 = quad_bcast<3>(hv);
@@ -597,7 +614,19 @@ bool sparse_smallm_supported(const egt_2bitcsr &w, int64_t ldx, int M) {
   return true;
 }
 
-template <int KIND, int NT, int NIT, int NWMAX, int QW, bool N1, bool RND>
+// Y[m][r] = FP16( sum over the K slices, in slice order, of the partial sums the split
+// kernel left in the workspace ).  One thread per output; a NaN partial (broken row
+// pointer) gives the library's NaN pattern.
+__global__ __launch_bounds__(256) void k_smallm_sum_slices(const float *__restrict__ ws, int64_t ws_ld, int nslices, int M,
+                                                           int rows, __half *__restrict__ Y, int64_t ldy) {
+  const int r = blockIdx.x * 256 + threadIdx.x, m = blockIdx.y;
+  if (r >= rows) return;
+  float sum = 0.f;
+  for (int s = 0; s < nslices; ++s) sum += ws[((int64_t)s * M + m) * ws_ld + r];
+  Y[(int64_t)m * ldy + r] = sum != sum ? __ushort_as_half((uint16_t)0x7E00) : __float2half(sum);
+}
+
+template <int KIND, int NT, int NIT, int NWMAX, int QW, bool N1, bool RND, bool KS = false>
 static hipError_t go_ks(const egt_2bitcsr &w, const uint16_t *X, uint16_t *Y, const SmallMKsGeom &g, int nw,
                         int nblocks, hipStream_t stream) {
   const size_t region = N1 ? 16 * KS_TOKEN_N1 : 8 * KS_PAIR;
@@ -605,24 +634,21 @@ static hipError_t go_ks(const egt_2bitcsr &w, const uint16_t *X, uint16_t *Y, co
   // partial sums behind the X regions where the kernel keeps them apart (NT > 1), else at
   // the start of each wave's own region; + row-pointer flags
   const size_t lds = (NT > 1 ? x_bytes + p_bytes : x_bytes) + 64 * NIT;
-  return launch(k_sparse_smallm_ks<KIND, NT, NIT, NWMAX, QW, N1, RND>, dim3(nblocks), dim3(64 * nw), lds, stream,
-                w.row_ptr, (const uint8_t *)w.values, (const uint8_t *)w.idx, (const uint8_t *)w.qparams,
+  return launch(k_sparse_smallm_ks<KIND, NT, NIT, NWMAX, QW, N1, RND, KS>, dim3(nblocks, KS ? g.nslices : 1), dim3(64 * nw),
+                lds, stream, w.row_ptr, (const uint8_t *)w.values, (const uint8_t *)w.idx, (const uint8_t *)w.qparams,
                 (const __half *)X, (__half *)Y, g);
 }
 
-hipError_t launch_sparse_smallm(const egt_2bitcsr &w, const uint16_t *X, int64_t ldx, uint16_t *Y,
-                                int64_t ldy, int M, hipStream_t stream) {
-  if (w.rows == 0) return hipSuccess;
+static void smallm_geometry(const egt_2bitcsr &w, int64_t ldx, uint16_t *Y, int64_t ldy, int M, SmallMKsGeom &g, int &qw) {
   const bool int4 = w.val_kind == EGT_VAL_INT4, n1 = w.n_keep == 1;
   const int chunk = n1 ? 128 : 64;
-  SmallMKsGeom g;
   g.rows = w.rows; g.M = M;
   g.nchunks = w.cols / chunk;
   g.nsteps = (g.nchunks + 3) / 4;
   g.kpieces = w.cols / 8;
   g.ntiles = (w.rows + 15) / 16;
   g.gshift = 0; g.groups_per_row = 0;
-  int qw = 1;                                         // {scale, zero} pairs per chunk
+  qw = 1;                                             // {scale, zero} pairs per chunk
   if (int4) {
     if (w.group_size < chunk) qw = chunk / w.group_size;
     while ((chunk << g.gshift) < w.group_size) ++g.gshift;
@@ -631,12 +657,88 @@ hipError_t launch_sparse_smallm(const egt_2bitcsr &w, const uint16_t *X, int64_t
   g.ldx = ldx; g.ldy = ldy;
   g.vec_store = ((uintptr_t)Y % 8 == 0 && ldy % 4 == 0) ? 1 : 0;
   const uint64_t chunks = (uint64_t)w.rows * g.nchunks;
-  const uint64_t vb = chunks * (int4 ? 16 : 64), xb = ((uint64_t)(M - 1) * ldx + w.cols) * 2;
-  if (vb >= (1ull << 32) || xb >= (1ull << 32)) return hipErrorInvalidValue;   // 32-bit offsets
-  g.val_bytes = (uint32_t)vb; g.idx_bytes = (uint32_t)(chunks * 8);
-  g.qp_bytes = (uint32_t)((uint64_t)w.rows * g.groups_per_row * 4); g.x_bytes = (uint32_t)xb;
+  g.val_bytes = (uint32_t)(chunks * (int4 ? 16 : 64)); g.idx_bytes = (uint32_t)(chunks * 8);
+  g.qp_bytes = (uint32_t)((uint64_t)w.rows * g.groups_per_row * 4);
+  g.x_bytes = (uint32_t)(((uint64_t)(M - 1) * ldx + w.cols) * 2);
   g.nib_mask = 0x00F0000Fu; g.nib_magic = 0x54006400u;
   g.m8 = 0x00FF00FFu; g.m4 = 0x0F0F0F0Fu; g.m2 = 0x33333333u;
+  g.nslices = 1; g.ws_ld = 0; g.ws = nullptr;
+}
+
+// K split over workgroups: at larger M every compute unit pulls the whole of X (M * K * 2
+// bytes) through its XCD's L2, which is what bounds the one-launch kernel when K is large
+// and the rows are few (the down projection: 4096 x 11008).  With the grid cut into row
+// blocks x K slices a workgroup needs only its slice of X, at the price of FP32 partial
+// sums that pass through a workspace and a second, small kernel that adds them in slice
+// order.  That price is only recovered where a workgroup still gets by with one round of
+// row tiles (a second round would fetch its X slice again), and measured it is: 2:4 INT4,
+// one {scale, zero} pair per chunk, more than 16 tokens, K >= 8192 and at most 256 row
+// tiles - four slices, a quarter of the row tiles per workgroup column (4096 x 11008:
+// 21.9 against 24.9 us at M = 64, 14.3 against 14.9 at M = 32; with more rows, e.g.
+// 11008 x 4096, every split measured was slower than the one-launch kernel).
+// Returns the number of slices (1: no split) and the row blocks.
+static int smallm_slices(const egt_2bitcsr &w, int M, int &row_blocks) {
+  row_blocks = 0;
+  if (w.val_kind != EGT_VAL_INT4 || w.n_keep != 2 || w.group_size < 64 || w.rows < 16) return 1;
+  const int nsteps = (w.cols / 64 + 3) / 4, ntiles = (w.rows + 15) / 16;
+  int s = (M > 16 && nsteps >= 32 && ntiles <= 256) ? 4 : 1;
+  int blocks = (ntiles + 3) / 4;
+  tune_pair("EGT_SM_KS", s, blocks);                   // developer build: any split, for timing
+  if (M < 5 || s < 2 || s > 16 || s > nsteps) return 1;
+  if (blocks < 1) blocks = 1;
+  if (blocks > ntiles) blocks = ntiles;
+  row_blocks = blocks;
+  return s;
+}
+
+bool sparse_smallm_split_bytes(const egt_2bitcsr &w, int64_t ldx, int M, size_t &bytes) {
+  int row_blocks;
+  bytes = 0;
+  if (!sparse_smallm_supported(w, ldx, M)) return false;
+  const int s = smallm_slices(w, M, row_blocks);
+  if (s < 2) return false;
+  bytes = sizeof(float) * (size_t)s * (size_t)M * (size_t)w.rows;
+  return true;
+}
+
+hipError_t launch_sparse_smallm_split(const egt_2bitcsr &w, const uint16_t *X, int64_t ldx, uint16_t *Y, int64_t ldy, int M,
+                                      float *ws, hipStream_t stream) {
+  if (w.rows == 0) return hipSuccess;
+  SmallMKsGeom g;
+  int qw, row_blocks;
+  smallm_geometry(w, ldx, Y, ldy, M, g, qw);
+  g.nslices = smallm_slices(w, M, row_blocks);
+  g.ws = ws; g.ws_ld = w.rows;
+  const bool wide = M > 16;
+  const int nwmax = wide ? 8 : 16;
+  const int min_steps = g.nsteps / g.nslices;          // the shortest slice
+  const int nw = min_steps < nwmax ? min_steps : nwmax;
+  const int nblocks = row_blocks;
+  const bool one = nblocks == g.ntiles;
+  hipError_t e;
+#define EGT_KSS(NT, NIT, NWMAX)                                                                              \
+  ((NIT > 1 && (int64_t)nblocks * NIT < g.ntiles) ? go_ks<EGT_VAL_INT4, NT, NIT, NWMAX, 1, false, (NIT > 1), true>(w, X, Y, g, nw, nblocks, stream) \
+                                                  : go_ks<EGT_VAL_INT4, NT, NIT, NWMAX, 1, false, false, true>(w, X, Y, g, nw, nblocks, stream))
+  if (!wide) e = one ? EGT_KSS(1, 1, 16) : EGT_KSS(1, 3, 16);
+  else e = one ? EGT_KSS(2, 1, 8) : EGT_KSS(2, 4, 8);
+#undef EGT_KSS
+  if (e != hipSuccess) return e;
+  return launch(k_smallm_sum_slices, dim3((w.rows + 255) / 256, M), dim3(256), 0, stream, (const float *)ws, g.ws_ld,
+                g.nslices, M, w.rows, (__half *)Y, ldy);
+}
+
+hipError_t launch_sparse_smallm(const egt_2bitcsr &w, const uint16_t *X, int64_t ldx, uint16_t *Y,
+                                int64_t ldy, int M, hipStream_t stream) {
+  if (w.rows == 0) return hipSuccess;
+  const bool int4 = w.val_kind == EGT_VAL_INT4, n1 = w.n_keep == 1;
+  SmallMKsGeom g;
+  int qw;
+  {
+    const uint64_t chunks = (uint64_t)w.rows * (uint64_t)(w.cols / (n1 ? 128 : 64));
+    const uint64_t vb = chunks * (int4 ? 16 : 64), xb = ((uint64_t)(M - 1) * ldx + w.cols) * 2;
+    if (vb >= (1ull << 32) || xb >= (1ull << 32)) return hipErrorInvalidValue;   // 32-bit offsets
+  }
+  smallm_geometry(w, ldx, Y, ldy, M, g, qw);
   // One workgroup per compute unit while its row tiles fit the registers (NIT of them).
   // 2:4 INT4, up to 16 tokens: 16 waves of 128 registers; everything else 8 waves of 256
   // (more than 16 tokens at 2:4: two token groups per pass).

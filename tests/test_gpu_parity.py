@@ -340,6 +340,82 @@ def test_config5_smallm_full_size(rows, cols, M):
     G.assert_close(y0[pick], Y_ref[0], A_ref[0], "row 0 as a GEMV")
 
 
+@pytest.mark.parametrize("rows,cols,M", [(4096, 11008, 64), (4096, 11008, 17), (2000, 8192, 33), (500, 12288, 40), (16, 8192, 64)])
+def test_smallm_split_over_k_with_a_workspace(rows, cols, M):
+    # K split over workgroups, FP32 partial sums through a caller-provided workspace: sampled
+    # rows against the oracle, every output close to the one-launch kernel's (same products,
+    # another order of the FP32 additions), identical bits on a second run, a canary behind the
+    # bytes the library said it needs, nothing written outside Y
+    torch = G.torch_mod()
+    print(f"case smallm split {rows}x{cols} M={M}", flush=True)
+    w, mask, p = G.packed_full(rows, cols, 2, 128, 0, 5200 + rows + cols)
+    X = synth.activation_rows(M, cols, 5200 + M)
+    pd = p.to("cuda")
+    need = B.smallm_ws_bytes(pd, M)
+    assert need == 4 * 4 * M * rows                      # four slices of FP32 partial sums
+    ws = torch.full((need + 4096,), 0x5A, dtype=torch.uint8, device="cuda")
+    Xd = G.to_dev(X.view(np.uint16)).view(torch.float16)
+    Ybuf = torch.full((M + 2, rows + 8), G.CANARY, dtype=torch.int16, device="cuda")
+    Y = Ybuf[1:M + 1, :rows].view(torch.float16)
+    B.sparse_gemm_smallm_ws(pd, Xd, Y, ws[:need])
+    torch.cuda.synchronize()
+    host = Ybuf.cpu().numpy().view(np.uint16)
+    assert np.all(host[0] == G.CANARY) and np.all(host[M + 1] == G.CANARY) and np.all(host[:, rows:] == G.CANARY)
+    assert torch.all(ws[need:] == 0x5A)
+    got = host[1:M + 1, :rows].view(np.float16)
+    pick = G.sample_rows(rows, 24, M)
+    o = O.pack_2bitcsr(w[pick], O.prune_n4_magnitude(w[pick], 2), 2, 128, 0)
+    Y_ref, A_ref = O.gemm_smallm(o, X)
+    G.assert_close(got[:, pick], Y_ref, A_ref, "split over K")
+    one = G.run_sparse_gemm(p, X)
+    diff = np.abs(got.astype(np.float64) - one.astype(np.float64))
+    assert np.all(diff <= 2e-3 * np.maximum(1.0, np.abs(one.astype(np.float64))))
+    first = got.copy()
+    ws.fill_(0x33)                                       # whatever the workspace holds before the call
+    Ybuf.fill_(G.CANARY)
+    B.sparse_gemm_smallm_ws(pd, Xd, Y, ws[:need])
+    torch.cuda.synchronize()
+    again = Ybuf.cpu().numpy().view(np.uint16)[1:M + 1, :rows]
+    assert np.array_equal(again, first.view(np.uint16))
+    # a broken row pointer: NaN for every token of that row, the other rows untouched
+    rp = pd.row_ptr.view(torch.int32)
+    keep_rp = rp[3].clone()
+    rp[3] += 8
+    B.sparse_gemm_smallm_ws(pd, Xd, Y, ws[:need])
+    torch.cuda.synchronize()
+    bad = Ybuf.cpu().numpy().view(np.uint16)[1:M + 1, :rows].view(np.float16)
+    assert np.all(np.isnan(bad[:, 3]))
+    others = np.ones(rows, dtype=bool)
+    others[3] = False
+    assert np.array_equal(bad[:, others].view(np.uint16), first[:, others].view(np.uint16))
+    rp[3] = keep_rp
+    # too small a workspace is refused on the host
+    with pytest.raises(B.EgtError) as e:
+        v = pd.view()
+        B._check(B.lib().egt_sparse_gemm_smallm_ws(__import__("ctypes").byref(v), Xd.data_ptr(), cols, Y.data_ptr(), Y.stride(0), M,
+                                                   ws.data_ptr(), need - 1, None))
+    assert e.value.status == 2
+
+
+def test_smallm_workspace_not_needed_where_the_split_does_not_pay():
+    torch = G.torch_mod()
+    for rows, cols, n, g, kind, M in ((11008, 4096, 2, 128, 0, 64), (4096, 11008, 2, 128, 0, 16), (300, 8192, 1, 128, 0, 40),
+                                      (300, 8192, 2, 0, 1, 40), (300, 8192, 2, 32, 0, 40)):
+        p = B.Packed(rows, cols, n, g, kind, None, None, None, None)
+        assert B.smallm_ws_bytes(p, M) == 0
+    # the workspace call is then the one-launch call
+    p, o = _small_case(300, 8192, 2, 32, 0, seed=77)
+    X = synth.activation_rows(40, 8192, 78)
+    pd = p.to("cuda")
+    Xd = G.to_dev(X.view(np.uint16)).view(torch.float16)
+    Y1 = torch.zeros((40, 300), dtype=torch.float16, device="cuda")
+    Y2 = torch.zeros((40, 300), dtype=torch.float16, device="cuda")
+    B.sparse_gemm_smallm(pd, Xd, Y1)
+    B.sparse_gemm_smallm_ws(pd, Xd, Y2, None)
+    torch.cuda.synchronize()
+    assert torch.equal(Y1, Y2)
+
+
 # ---------------------------------------------------------------- measurement aid
 def test_stream_read_folds_every_word_once():
     torch = G.torch_mod()

@@ -452,6 +452,25 @@ def test_stack_plan_cuts_a_large_table_into_row_blocks():
         assert L.egt_gemv_stack_run(16, ctypes.byref(broken), None) == 2, field
 
 
+def test_smallm_workspace_size_query():
+    L = B.lib()
+    out = ctypes.c_size_t(7)
+    down = B.View(4096, 11008, 2, 128, 0, 16, 16, 16, 16)
+    assert L.egt_sparse_gemm_smallm_ws_bytes(ctypes.byref(down), 11008, 64, ctypes.byref(out)) == 0 and out.value == 4 * 4 * 64 * 4096
+    assert L.egt_sparse_gemm_smallm_ws_bytes(ctypes.byref(down), 11008, 16, ctypes.byref(out)) == 0 and out.value == 0
+    gate = B.View(11008, 4096, 2, 128, 0, 16, 16, 16, 16)
+    assert L.egt_sparse_gemm_smallm_ws_bytes(ctypes.byref(gate), 4096, 64, ctypes.byref(out)) == 0 and out.value == 0
+    assert L.egt_sparse_gemm_smallm_ws_bytes(ctypes.byref(down), 11008, 65, ctypes.byref(out)) == 2
+    assert L.egt_sparse_gemm_smallm_ws_bytes(ctypes.byref(down), 100, 64, ctypes.byref(out)) == 2
+    assert L.egt_sparse_gemm_smallm_ws_bytes(ctypes.byref(down), 11008, 64, None) == 1
+    assert L.egt_sparse_gemm_smallm_ws_bytes(None, 11008, 64, ctypes.byref(out)) == 1
+    # the device call checks its arguments before anything is launched
+    assert L.egt_sparse_gemm_smallm_ws(ctypes.byref(down), 16, 11008, 16, 4096, 64, None, 0, None) == 1
+    assert L.egt_sparse_gemm_smallm_ws(ctypes.byref(down), 16, 11008, 16, 4096, 64, 16, 100, None) == 2
+    assert L.egt_sparse_gemm_smallm_ws(ctypes.byref(down), 16, 11008, 16, 4096, 64, 24, 1 << 30, None) == 5
+    assert L.egt_sparse_gemm_smallm_ws(ctypes.byref(down), 16, 11008, 16, 100, 64, 16, 1 << 30, None) == 2
+
+
 def test_trigger_cost_model():
     # exact line is recovered; noisy points match the oracle's least squares
     m = [1, 2, 4, 8, 16, 32, 64]
