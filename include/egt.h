@@ -193,6 +193,20 @@ egt_status egt_sparse_gemm_smallm_ws(const egt_2bitcsr *w, const uint16_t *X, in
                                      uint16_t *Y, int64_t ldy, int M, void *workspace,
                                      size_t workspace_bytes, void *stream);
 
+/* DEVICE.  egt_sparse_gemm_smallm_ws for callers that cannot allocate device memory and
+ * have no workspace to hand over: code under HIP graph capture, tight serving loops,
+ * harnesses that forbid hipMalloc.  The partial sums go to a buffer of
+ * EGT_STATIC_SCRATCH_BYTES that is part of the library's device image (every GPU the library
+ * runs on holds it until the process ends); the call allocates and frees nothing.  A
+ * matrix and M whose partial sums need more give EGT_ERR_UNSUPPORTED (use the workspace
+ * form); where the split form does not apply the call is egt_sparse_gemm_smallm.  All
+ * calls on one GPU share that buffer: calls that overlap on one GPU (two streams, two
+ * threads) race, whoever makes them must order them.  Results equal
+ * egt_sparse_gemm_smallm_ws's bit for bit. */
+#define EGT_STATIC_SCRATCH_BYTES (4u << 20) /* four slices of 64 tokens x 4096 rows of FP32 */
+egt_status egt_sparse_gemm_smallm_static(const egt_2bitcsr *w, const uint16_t *X, int64_t ldx,
+                                         uint16_t *Y, int64_t ldy, int M, void *stream);
+
 /* DEVICE.  `count` (1..4) independent products y[k] = W[k].x[k] of identically shaped
  * matrices (same rows, cols, n_keep, group_size, val_kind; else EGT_ERR_SHAPE) in one
  * launch: the q/k/v or gate/up projections of a decoder layer.  Sec. 3.3 starts from

@@ -24,6 +24,7 @@ SYMBOLS = (
     "egt_sparse_gemm_smallm", "egt_stream_read", "egt_sparse_gemv_batch", "egt_int4_gemv_batch",
     "egt_fit_verify_cost", "egt_trigger_depth", "egt_prune_n4_importance", "egt_pack_2bitcsr_rowgroups",
     "egt_gemv_stack_plan", "egt_gemv_stack_run", "egt_sparse_gemm_smallm_ws_bytes", "egt_sparse_gemm_smallm_ws",
+    "egt_sparse_gemm_smallm_static",
 )
 
 
@@ -102,6 +103,8 @@ def lib() -> C.CDLL:
         L.egt_gemv_stack_plan.argtypes = [C.POINTER(GemvItem), C.c_int, C.c_int, C.c_void_p, C.c_size_t, C.POINTER(StackPlan)]
         L.egt_gemv_stack_run.argtypes = [C.c_void_p, C.POINTER(StackPlan), C.c_void_p]
         L.egt_sparse_gemm_smallm_ws_bytes.argtypes = [C.POINTER(View), C.c_int64, C.c_int, C.POINTER(C.c_size_t)]
+        L.egt_sparse_gemm_smallm_static.argtypes = [C.POINTER(View), C.c_void_p, C.c_int64, C.c_void_p, C.c_int64, C.c_int,
+                                                    C.c_void_p]
         L.egt_sparse_gemm_smallm_ws.argtypes = [C.POINTER(View), C.c_void_p, C.c_int64, C.c_void_p, C.c_int64, C.c_int,
                                                 C.c_void_p, C.c_size_t, C.c_void_p]
         for name in SYMBOLS:
@@ -404,6 +407,14 @@ def prepared_sparse_gemm_smallm_ws(p: Packed, X, Y, workspace, stream=None):
         if st:
             _check(st)
     return call
+
+
+def sparse_gemm_smallm_static(p: Packed, X, Y, stream=None) -> None:
+    """The K-split form on the library's built-in scratch buffer (allocates nothing)."""
+    _check_xy(p, X, Y)
+    v = p.view()
+    _check(lib().egt_sparse_gemm_smallm_static(C.byref(v), X.data_ptr(), X.stride(0), Y.data_ptr(), Y.stride(0),
+                                               X.shape[0], _stream_ptr(stream)))
 
 
 def sparse_gemm_smallm_ws(p: Packed, X, Y, workspace, stream=None) -> None:

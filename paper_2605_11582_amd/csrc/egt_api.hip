@@ -4,6 +4,8 @@
 
 #include "egt_tune.h"
 
+#include <mutex>
+
 namespace {
 
 // `pointers`: also require the buffers (a size query looks at the shape only)
@@ -93,6 +95,33 @@ __global__ __launch_bounds__(256) void k_stream_read_shot(const u32x4 *__restric
   fold_and_store(acc, sink);
 }
 
+// Device memory of the allocation-free entry point: the partial sums of the split small-M
+// kernels go here instead of into a caller's workspace.  Every GPU the library runs on
+// holds its own copy of the array, at its own address, until the process ends.  In host
+// code the array's name is only a handle: the address kernels can use comes from
+// hipGetSymbolAddress, asked once per device with that device current, and is kept.
+static __device__ __align__(256) unsigned char scratch[EGT_STATIC_SCRATCH_BYTES];
+
+hipError_t static_scratch(void **out) {
+  constexpr int MAX_DEVICES = 64;
+  static std::mutex mu;
+  static void *addr[MAX_DEVICES] = {};
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  if (dev < 0 || dev >= MAX_DEVICES) return hipErrorInvalidDevice;
+  std::lock_guard<std::mutex> lock(mu);
+  if (!addr[dev]) {
+    void *p = nullptr;
+    e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return e;
+    if (!p) return hipErrorInvalidSymbol;
+    addr[dev] = p;
+  }
+  *out = addr[dev];
+  return hipSuccess;
+}
+
 }  // namespace
 
 namespace egt {
@@ -152,6 +181,27 @@ egt_status egt_sparse_gemm_smallm_ws(const egt_2bitcsr *w, const uint16_t *X, in
       !aligned16(X) || !aligned16(workspace))
     return EGT_ERR_BUFFER;
   return done(egt::launch_sparse_smallm_split(*w, X, ldx, Y, ldy, M, (float *)workspace, (hipStream_t)stream));
+}
+
+egt_status egt_sparse_gemm_smallm_static(const egt_2bitcsr *w, const uint16_t *X, int64_t ldx, uint16_t *Y,
+                                         int64_t ldy, int M, void *stream) {
+  const egt_status st = check_view(w);
+  if (st != EGT_OK) return st;
+  if (M < 1 || M > 64 || ldx < w->cols || ldy < w->rows) return EGT_ERR_SHAPE;
+  if (w->rows == 0) return EGT_OK;
+  size_t need = 0;
+  const bool split = egt::sparse_smallm_split_bytes(*w, ldx, M, need) && ldx % 8 == 0;
+  if (!split) return egt_sparse_gemm_smallm(w, X, ldx, Y, ldy, M, stream);   // no partial sums in memory: nothing to place
+  if (need > EGT_STATIC_SCRATCH_BYTES) return EGT_ERR_UNSUPPORTED;           // beyond the built-in buffer
+  if (!X || !Y) return EGT_ERR_NULL;
+  if (!aligned16(w->row_ptr) || !aligned16(w->values) || !aligned16(w->idx) || (w->qparams && !aligned16(w->qparams)) ||
+      !aligned16(X))
+    return EGT_ERR_BUFFER;
+  void *ws = nullptr;
+  const hipError_t e = static_scratch(&ws);
+  if (e != hipSuccess) return done(e);
+  // every partial sum the second kernel reads is written by the first: nothing to clear
+  return done(egt::launch_sparse_smallm_split(*w, X, ldx, Y, ldy, M, (float *)ws, (hipStream_t)stream));
 }
 
 egt_status egt_sparse_gemv(const egt_2bitcsr *w, const uint16_t *x, uint16_t *y, void *stream) {
