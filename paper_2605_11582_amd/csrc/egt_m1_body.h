@@ -35,6 +35,7 @@ struct M1Geom {
   int part_offset;     // byte offset of the per-phase partial sums in LDS
   int xtok;            // LDS bytes of the staged activations of one token
   int M;               // tokens (activation rows): 1, or up to MT in the several-token form
+  int hi_blocks;       // k_sparse_m1_one: workgroups [0, hi_blocks) take TPI tiles per wave, the others TPI - 1
   int64_t ldx, ldy;    // row strides of X and Y in elements (several-token form)
   uint32_t nib_mask;   // 0x00F0000F: low nibble of the low half, high nibble of the high half
   uint32_t nib_magic;  // 0x54006400: FP16 {1024.0, 64.0}
@@ -53,30 +54,35 @@ struct M1Geom {
 // registers of a tile feed MT instructions, one per token, each with the B operand of
 // its own token (32 registers per token, loaded once per wave); everything about the
 // weights - the loads, the dequantisation - is done once, as for one token.
-template <int KIND, int TPI, int XP, int QW, bool LIN, int MT>
+// ONE: the matrix has exactly one whole tile per row (K = 4096) - the shape of most
+// projections of a 7B decoder and of the headline workload; tiles per row, rows per tile
+// and chunks per row are then constants and the index arithmetic of the general form
+// (two integer divisions before the first request goes out) folds away.
+template <int KIND, int TPI, int XP, int QW, bool LIN, int MT, bool ONE = false>
 __device__ __forceinline__ void k_sparse_m1_body(const uint32_t *__restrict__ row_ptr, const uint8_t *__restrict__ values,
     const uint8_t *__restrict__ idx, const uint8_t *__restrict__ qparams, const __half *__restrict__ x,
-    __half *__restrict__ y, const M1Geom &g) {
+    __half *__restrict__ y, const M1Geom &g, int tile_base = -1) {
   extern __shared__ __align__(16) uint8_t xs[];       // staged x, then [phases][rows of this block] floats
+  const int g_phases = ONE ? 1 : g.phases, g_mr_shift = ONE ? -1 : g.mr_shift, g_nchunks = ONE ? 64 : g.nchunks;
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int nwaves = blockDim.x >> 6;
-  const int wpp = nwaves / g.phases;                  // waves per phase in this block
+  const int wpp = nwaves / g_phases;                  // waves per phase in this block
   float *part = (float *)(xs + g.part_offset);
-  const int phase = wave / wpp;
+  const int phase = ONE ? 0 : wave / wpp;
   const int wslot = wave - phase * wpp;
   const int i = lane & 15, kb = lane >> 4;
   const int cit = 4 * i + kb;                         // chunk of this lane inside a tile
-  const bool multirow = g.mr_shift >= 0;
-  const int rpt = multirow ? (64 >> g.mr_shift) : 1;  // rows per tile
-  const int c = multirow ? (cit & (g.nchunks - 1)) : cit + 64 * phase;   // chunk inside the row
-  const int rsub = multirow ? (cit >> g.mr_shift) : 0;
-  const int c_ld = min(c, g.nchunks - 1);
+  const bool multirow = g_mr_shift >= 0;
+  const int rpt = multirow ? (64 >> g_mr_shift) : 1;  // rows per tile
+  const int c = multirow ? (cit & (g_nchunks - 1)) : cit + 64 * phase;   // chunk inside the row
+  const int rsub = multirow ? (cit >> g_mr_shift) : 0;
+  const int c_ld = min(c, g_nchunks - 1);
 
   // ---- x: the block's threads fetch it once, 16 B pieces, before anything else is
   //      requested, so that it is the first data to come back
-  const int npieces = g.nchunks * 8;                   // 8 halfs per piece
-  const int lds_pieces = multirow ? npieces : g.phases * 512;
+  const int npieces = g_nchunks * 8;                   // 8 halfs per piece
+  const int lds_pieces = multirow ? npieces : g_phases * 512;
   u4 xp[MT][XP];
 #pragma unroll
   for (int m = 0; m < MT; ++m) {
@@ -89,11 +95,13 @@ __device__ __forceinline__ void k_sparse_m1_body(const uint32_t *__restrict__ ro
   }
 
   constexpr int XSH = LIN ? 4 : 5;                    // x in LDS: one 16 B pad per 2^XSH pieces
-  const int tile0 = (blockIdx.x * wpp + wslot) * TPI;
+  // first tile of this wave; tile_base >= 0: the caller says where the workgroup's tiles start
+  // (workgroups of one launch may differ in their tiles per wave)
+  const int tile0 = tile_base >= 0 ? tile_base + wslot * TPI : (blockIdx.x * wpp + wslot) * TPI;
   // The lanes that will store read their row pointers before the tiles are requested (loads
   // return in order, so the small ones go first and never make the wave wait for a tile):
   // lane j < 16 finishes tile (j >> 2) of each batch of four tiles.
-  const int sum_steps = multirow ? (g.mr_shift - 4) : 2;       // log2(quad groups per row)
+  const int sum_steps = multirow ? (g_mr_shift - 4) : 2;       // log2(quad groups per row)
   constexpr int NB = (TPI + 3) / 4;
   uint32_t rp[NB];
   int rrow[NB];
@@ -111,7 +119,7 @@ __device__ __forceinline__ void k_sparse_m1_body(const uint32_t *__restrict__ ro
   // several tiles per row: the threads that add the phases up at the end fetch the row
   // pointer of their row now (wpp * TPI * MT <= 64 <= blockDim: one output per thread)
   uint32_t rp_fin = 0;
-  if (g.phases > 1 && (int)threadIdx.x < wpp * TPI * MT) {
+  if (g_phases > 1 && (int)threadIdx.x < wpp * TPI * MT) {
     const int r = blockIdx.x * (wpp * TPI) + (int)threadIdx.x / MT;
     if (r < g.rows) rp_fin = row_ptr[r];
   }
@@ -127,8 +135,8 @@ __device__ __forceinline__ void k_sparse_m1_body(const uint32_t *__restrict__ ro
     if constexpr (LIN) {
 #pragma unroll
       for (int k = 0; k < 4; ++k) {
-        const uint32_t piece = (uint32_t)min(256 * phase + 64 * k + lane, 4 * g.nchunks - 1);   // inside the row (clamped)
-        const uint32_t gp = (uint32_t)tr * (uint32_t)(4 * g.nchunks) + piece;
+        const uint32_t piece = (uint32_t)min(256 * phase + 64 * k + lane, 4 * g_nchunks - 1);   // inside the row (clamped)
+        const uint32_t gp = (uint32_t)tr * (uint32_t)(4 * g_nchunks) + piece;
         nib[t][k] = ld_stream<u4>(values + 16ull * gp);
         iwl[t][k] = ld_stream<uint16_t>(idx + 2ull * gp);
       }
@@ -136,7 +144,7 @@ __device__ __forceinline__ void k_sparse_m1_body(const uint32_t *__restrict__ ro
     }
     uint32_t chunk;
     if (multirow) chunk = min((uint32_t)tr * 64u + (uint32_t)cit, g.last_chunk);
-    else chunk = (uint32_t)tr * (uint32_t)g.nchunks + (uint32_t)c_ld;
+    else chunk = (uint32_t)tr * (uint32_t)g_nchunks + (uint32_t)c_ld;
     iw[t] = ld_stream<u2>(idx + 8ull * chunk);
     qp[t][0] = 0;
     if (KIND == EGT_VAL_INT4) {
@@ -195,7 +203,7 @@ __device__ __forceinline__ void k_sparse_m1_body(const uint32_t *__restrict__ ro
     for (int h = 0; h < 2; ++h) {
       const int kba = (4 * h + b) >> 1, sub = b & 1;  // the A lane (n, kba) this octet multiplies
       int cb = 4 * n + kba;
-      cb = multirow ? (cb & (g.nchunks - 1)) : cb + 64 * phase;
+      cb = multirow ? (cb & (g_nchunks - 1)) : cb + 64 * phase;
 #pragma unroll
       for (int d = 0; d < 4; ++d) {
         const int pi = 8 * cb + 2 * d + sub;
@@ -270,8 +278,8 @@ __device__ __forceinline__ void k_sparse_m1_body(const uint32_t *__restrict__ ro
       if (sum_steps >= 2) v += quad_xor2(v);
       if (st[bt] && (MT == 1 || m < g.M)) {
         const int r = rrow[bt];
-        if (g.phases == 1) {
-          const bool ok = rp[bt] == (uint32_t)r * (uint32_t)(g.nchunks * 32);
+        if (g_phases == 1) {
+          const bool ok = rp[bt] == (uint32_t)r * (uint32_t)(g_nchunks * 32);
           y[(int64_t)m * g.ldy + r] = ok ? __float2half(v) : __ushort_as_half((uint16_t)0x7E00);
         } else {
           part[(phase * (wpp * TPI) + wslot * TPI + 4 * bt + ((lane >> 2) & 3)) * MT + m] = v;
@@ -279,7 +287,7 @@ __device__ __forceinline__ void k_sparse_m1_body(const uint32_t *__restrict__ ro
       }
     }
   }
-  if (g.phases > 1) {
+  if (g_phases > 1) {
     __syncthreads();
     const int per = wpp * TPI;                        // rows handled by this block
     const int j = threadIdx.x;
@@ -288,8 +296,8 @@ __device__ __forceinline__ void k_sparse_m1_body(const uint32_t *__restrict__ ro
       const int r = blockIdx.x * per + jr;
       if (r < g.rows && (MT == 1 || m < g.M)) {
         float v = 0.f;
-        for (int p = 0; p < g.phases; ++p) v += part[(p * per + jr) * MT + m];
-        const bool ok = rp_fin == (uint32_t)r * (uint32_t)(g.nchunks * 32);
+        for (int p = 0; p < g_phases; ++p) v += part[(p * per + jr) * MT + m];
+        const bool ok = rp_fin == (uint32_t)r * (uint32_t)(g_nchunks * 32);
         y[(int64_t)m * g.ldy + r] = ok ? __float2half(v) : __ushort_as_half((uint16_t)0x7E00);
       }
     }
@@ -316,6 +324,7 @@ inline void m1_geometry(const egt_2bitcsr &w, M1Geom &g) {
   g.nib_mask = 0x00F0000Fu;
   g.nib_magic = 0x54006400u;
   g.M = 1; g.ldx = 0; g.ldy = 0;
+  g.hi_blocks = 0;
 }
 
 // Block shape for `wpp` waves per phase and `tpi` tiles per wave, `mt` tokens; fills the

@@ -31,6 +31,29 @@
 
 namespace egt {
 
+// One matrix per launch, one whole tile per row (K = 4096), INT4 values: the headline shape.
+template <int TPI, int XP, int QW>
+__global__ __launch_bounds__(1024) void k_sparse_m1_one(const uint32_t *__restrict__ row_ptr,
+                                                         const uint8_t *__restrict__ values,
+                                                         const uint8_t *__restrict__ idx,
+                                                         const uint8_t *__restrict__ qparams,
+                                                         const __half *__restrict__ x,
+                                                         __half *__restrict__ y, const M1Geom g) {
+  // Workgroups [0, hi_blocks) take TPI tiles per wave, the rest TPI - 1: the launcher picks a
+  // workgroup count that is a multiple of the compute units and spreads the rows evenly
+  // (11008 rows in workgroups of 16 are 688 workgroups, 2.7 per compute unit: some units
+  // would get three, some two, and the kernel ends with the slowest).
+  const int nw = blockDim.x >> 6;
+  if constexpr (TPI > 1) {
+    if ((int)blockIdx.x >= g.hi_blocks) {
+      k_sparse_m1_body<EGT_VAL_INT4, TPI - 1, XP, QW, false, 1, true>(
+          row_ptr, values, idx, qparams, x, y, g, (g.hi_blocks * TPI + ((int)blockIdx.x - g.hi_blocks) * (TPI - 1)) * nw);
+      return;
+    }
+  }
+  k_sparse_m1_body<EGT_VAL_INT4, TPI, XP, QW, false, 1, true>(row_ptr, values, idx, qparams, x, y, g, (int)blockIdx.x * nw * TPI);
+}
+
 // One matrix per launch: the pointers are plain kernel arguments.
 template <int KIND, int TPI, int XP, int QW, bool LIN>
 __global__ __launch_bounds__(1024) void k_sparse_m1(const uint32_t *__restrict__ row_ptr,
@@ -115,6 +138,32 @@ hipError_t launch_sparse_m1_batch(const egt_2bitcsr *ws, const uint16_t *const *
                                                                                   : EGT_GO5(EGT_VAL_FP16, TPI, 4, 1, true))
 #define EGT_GO(KIND, TPI)                                                                       \
   (xp <= 1 ? EGT_GO3(KIND, TPI, 1) : xp == 2 ? EGT_GO3(KIND, TPI, 2) : EGT_GO3(KIND, TPI, 4))
+  if (count == 1 && w.val_kind == EGT_VAL_INT4 && !g32 && g.nchunks == 64 && !tune_flag("EGT_M1_NOONE")) {
+    // an even spread over the compute units while all workgroups are resident at once: the
+    // smallest multiple of 256 workgroups that covers the rows at tpi tiles per wave, a part
+    // of them with one tile less
+    int nb = ls.nblocks;
+    g.hi_blocks = nb;
+    const int per_hi = ls.nwaves * tpi, per_lo = ls.nwaves * (tpi - 1);
+    const int even = 256 * ((g.ntiles + 256 * per_hi - 1) / (256 * per_hi));
+    if (tpi > 1 && even <= 1024 && even * per_lo < g.ntiles && !tune_flag("EGT_M1_NOEVEN")) {
+      nb = even;
+      g.hi_blocks = (g.ntiles - nb * per_lo + ls.nwaves - 1) / ls.nwaves;
+    }
+    const dim3 grid(nb);
+#define EGT_ONE(TPI, XP)                                                                        \
+  launch(k_sparse_m1_one<TPI, XP, 1>, grid, block, lds, stream, b.row_ptr[0], b.values[0], b.idx[0], b.qparams[0], \
+         b.x[0], b.y[0], g)
+    if (xp <= 2) {                                     // (at least four waves: x in one or two pieces per thread)
+      switch (tpi) {
+        case 1: return xp <= 1 ? EGT_ONE(1, 1) : EGT_ONE(1, 2);
+        case 2: return xp <= 1 ? EGT_ONE(2, 1) : EGT_ONE(2, 2);
+        case 8: return xp <= 1 ? EGT_ONE(8, 1) : EGT_ONE(8, 2);
+        default: return xp <= 1 ? EGT_ONE(4, 1) : EGT_ONE(4, 2);
+      }
+    }
+#undef EGT_ONE
+  }
   if (g32)                                             // groups of 32: one launch shape
     return xp <= 1 ? EGT_GO4(EGT_VAL_INT4, 4, 1, 2) : xp == 2 ? EGT_GO4(EGT_VAL_INT4, 4, 2, 2)
                                                               : EGT_GO4(EGT_VAL_INT4, 4, 4, 2);

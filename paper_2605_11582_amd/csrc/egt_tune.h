@@ -8,7 +8,9 @@
 //   EGT_M1_TUNE=tpi,wpp      2:4 M = 1            EGT_M1N1_TUNE=tpi,wpp    1:4 M = 1
 //   EGT_M1T_TUNE=tpi,wpp     several-token form   EGT_DENSE_TUNE=tpi,wpp   dense INT4
 //   EGT_SM_TUNE=waves,blocks_per_cu   small M     EGT_READ_TUNE=unroll,blocks_per_cu  streaming read
-//   EGT_NO_M1T, EGT_M1_NOLIN, EGT_M1N1_NOLIN      (set = that path is not used)
+//   EGT_STACK_TUNE=waves,tpi_mode  EGT_STREAM_TUNE=force,blocks_per_cu  EGT_STREAM_WAVES=waves  EGT_STREAM_ITEM=kilobytes
+//   EGT_SM_KS=slices,row_blocks    (multi-matrix launches; K split at small M)
+//   EGT_NO_M1T, EGT_M1_NOLIN, EGT_M1N1_NOLIN, EGT_M1_NOONE   (set = that path is not used)
 #ifndef EGT_TUNE_H
 #define EGT_TUNE_H
 
