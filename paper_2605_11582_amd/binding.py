@@ -61,6 +61,46 @@ STACK_ENTRY_BYTES = 160
 _lib = None
 
 
+def _declare(L: C.CDLL, names=None) -> C.CDLL:
+    """Argument and result types of the entry points `names` (default: all) of a loaded library."""
+    names = SYMBOLS if names is None else names
+    sig = {
+        "egt_status_str": ([C.c_int], C.c_char_p),
+        "egt_last_hip_error": ([], C.c_char_p),
+        "egt_2bitcsr_sizes": ([C.c_int] * 5 + [C.POINTER(C.c_size_t)], C.c_int),
+        "egt_prune_n4": ([C.c_void_p, C.c_int64, C.c_int, C.c_int, C.c_int, C.c_void_p, C.c_int64], C.c_int),
+        "egt_prune_n4_importance": ([C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p, C.c_int64, C.c_int, C.c_int, C.c_int,
+                                     C.c_void_p, C.c_int64], C.c_int),
+        "egt_pack_2bitcsr": ([C.c_void_p, C.c_int64, C.c_void_p, C.c_int64, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int,
+                              C.POINTER(View)], C.c_int),
+        "egt_pack_2bitcsr_rowgroups": ([C.c_void_p, C.c_int64, C.c_void_p, C.c_int64, C.c_int, C.c_int, C.c_int, C.c_int,
+                                        C.c_int, C.c_void_p, C.POINTER(View)], C.c_int),
+        "egt_unpack_2bitcsr": ([C.POINTER(View), C.c_void_p, C.c_int64, C.c_void_p, C.c_int64], C.c_int),
+        "egt_quant_int4": ([C.c_void_p, C.c_int64, C.c_int, C.c_int, C.c_int, C.c_void_p, C.c_void_p], C.c_int),
+        "egt_int4_gemv": ([C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p], C.c_int),
+        "egt_sparse_gemv": ([C.POINTER(View), C.c_void_p, C.c_void_p, C.c_void_p], C.c_int),
+        "egt_sparse_gemm_smallm": ([C.POINTER(View), C.c_void_p, C.c_int64, C.c_void_p, C.c_int64, C.c_int, C.c_void_p], C.c_int),
+        "egt_stream_read": ([C.c_void_p, C.c_size_t, C.c_void_p, C.c_void_p], C.c_int),
+        "egt_sparse_gemv_batch": ([C.POINTER(View), C.POINTER(C.c_void_p), C.POINTER(C.c_void_p), C.c_int, C.c_void_p], C.c_int),
+        "egt_int4_gemv_batch": ([C.POINTER(C.c_void_p), C.POINTER(C.c_void_p), C.c_int, C.c_int, C.c_int,
+                                 C.POINTER(C.c_void_p), C.POINTER(C.c_void_p), C.c_int, C.c_void_p], C.c_int),
+        "egt_fit_verify_cost": ([C.c_void_p, C.c_void_p, C.c_int, C.POINTER(C.c_double), C.POINTER(C.c_double)], C.c_int),
+        "egt_trigger_depth": ([C.c_double, C.c_double, C.c_double, C.c_void_p, C.c_void_p, C.c_int, C.POINTER(C.c_int),
+                               C.POINTER(C.c_double)], C.c_int),
+        "egt_gemv_stack_plan": ([C.POINTER(GemvItem), C.c_int, C.c_int, C.c_void_p, C.c_size_t, C.POINTER(StackPlan)], C.c_int),
+        "egt_gemv_stack_run": ([C.c_void_p, C.POINTER(StackPlan), C.c_void_p], C.c_int),
+        "egt_sparse_gemm_smallm_ws_bytes": ([C.POINTER(View), C.c_int64, C.c_int, C.POINTER(C.c_size_t)], C.c_int),
+        "egt_sparse_gemm_smallm_ws": ([C.POINTER(View), C.c_void_p, C.c_int64, C.c_void_p, C.c_int64, C.c_int, C.c_void_p,
+                                       C.c_size_t, C.c_void_p], C.c_int),
+        "egt_sparse_gemm_smallm_static": ([C.POINTER(View), C.c_void_p, C.c_int64, C.c_void_p, C.c_int64, C.c_int, C.c_void_p],
+                                          C.c_int),
+    }
+    for name in names:
+        fn = getattr(L, name)                           # AttributeError if the library lacks an entry point
+        fn.argtypes, fn.restype = sig[name]
+    return L
+
+
 def lib() -> C.CDLL:
     global _lib
     if _lib is None:
@@ -72,45 +112,7 @@ def lib() -> C.CDLL:
         # to that copy, so streams and device pointers mean the same thing on both
         # sides; loading libegt.so first would pull in a second runtime.
         import torch  # noqa: F401
-        L = C.CDLL(LIB_PATH)
-        L.egt_status_str.restype = C.c_char_p
-        L.egt_status_str.argtypes = [C.c_int]
-        L.egt_last_hip_error.restype = C.c_char_p
-        L.egt_last_hip_error.argtypes = []
-        L.egt_2bitcsr_sizes.argtypes = [C.c_int] * 5 + [C.POINTER(C.c_size_t)]
-        L.egt_prune_n4.argtypes = [C.c_void_p, C.c_int64, C.c_int, C.c_int, C.c_int, C.c_void_p, C.c_int64]
-        L.egt_prune_n4_importance.argtypes = [C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p, C.c_int64, C.c_int,
-                                              C.c_int, C.c_int, C.c_void_p, C.c_int64]
-        L.egt_pack_2bitcsr.argtypes = [C.c_void_p, C.c_int64, C.c_void_p, C.c_int64, C.c_int, C.c_int,
-                                       C.c_int, C.c_int, C.c_int, C.POINTER(View)]
-        L.egt_pack_2bitcsr_rowgroups.argtypes = [C.c_void_p, C.c_int64, C.c_void_p, C.c_int64, C.c_int, C.c_int,
-                                                 C.c_int, C.c_int, C.c_int, C.c_void_p, C.POINTER(View)]
-        L.egt_unpack_2bitcsr.argtypes = [C.POINTER(View), C.c_void_p, C.c_int64, C.c_void_p, C.c_int64]
-        L.egt_quant_int4.argtypes = [C.c_void_p, C.c_int64, C.c_int, C.c_int, C.c_int, C.c_void_p, C.c_void_p]
-        L.egt_int4_gemv.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_void_p,
-                                    C.c_void_p, C.c_void_p]
-        L.egt_sparse_gemv.argtypes = [C.POINTER(View), C.c_void_p, C.c_void_p, C.c_void_p]
-        L.egt_sparse_gemm_smallm.argtypes = [C.POINTER(View), C.c_void_p, C.c_int64, C.c_void_p,
-                                             C.c_int64, C.c_int, C.c_void_p]
-        L.egt_stream_read.argtypes = [C.c_void_p, C.c_size_t, C.c_void_p, C.c_void_p]
-        L.egt_sparse_gemv_batch.argtypes = [C.POINTER(View), C.POINTER(C.c_void_p), C.POINTER(C.c_void_p),
-                                            C.c_int, C.c_void_p]
-        L.egt_int4_gemv_batch.argtypes = [C.POINTER(C.c_void_p), C.POINTER(C.c_void_p), C.c_int, C.c_int, C.c_int,
-                                          C.POINTER(C.c_void_p), C.POINTER(C.c_void_p), C.c_int, C.c_void_p]
-        L.egt_fit_verify_cost.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.POINTER(C.c_double), C.POINTER(C.c_double)]
-        L.egt_trigger_depth.argtypes = [C.c_double, C.c_double, C.c_double, C.c_void_p, C.c_void_p, C.c_int,
-                                        C.POINTER(C.c_int), C.POINTER(C.c_double)]
-        L.egt_gemv_stack_plan.argtypes = [C.POINTER(GemvItem), C.c_int, C.c_int, C.c_void_p, C.c_size_t, C.POINTER(StackPlan)]
-        L.egt_gemv_stack_run.argtypes = [C.c_void_p, C.POINTER(StackPlan), C.c_void_p]
-        L.egt_sparse_gemm_smallm_ws_bytes.argtypes = [C.POINTER(View), C.c_int64, C.c_int, C.POINTER(C.c_size_t)]
-        L.egt_sparse_gemm_smallm_static.argtypes = [C.POINTER(View), C.c_void_p, C.c_int64, C.c_void_p, C.c_int64, C.c_int,
-                                                    C.c_void_p]
-        L.egt_sparse_gemm_smallm_ws.argtypes = [C.POINTER(View), C.c_void_p, C.c_int64, C.c_void_p, C.c_int64, C.c_int,
-                                                C.c_void_p, C.c_size_t, C.c_void_p]
-        for name in SYMBOLS:
-            if name not in ("egt_status_str", "egt_last_hip_error"):
-                getattr(L, name).restype = C.c_int
-        _lib = L
+        _lib = _declare(C.CDLL(LIB_PATH))
     return _lib
 
 

@@ -43,6 +43,7 @@ struct DenseGeom {
   int part_offset;     // byte offset of the per-phase partial sums in LDS
   uint32_t nib_mask;   // 0x00F000F0: the nibble of each half that becomes a mantissa
   uint32_t nib_magic;  // 0x54005400: FP16 64.0 in both halves
+  int wpp, wpp_inv;    // waves per phase in a workgroup, ceil(65536 / wpp)
 };
 
 template <int TPI, int XP, bool PRE>
@@ -51,10 +52,11 @@ __device__ __forceinline__ void k_int4_m1_body(const uint8_t *__restrict__ q, co
   extern __shared__ __align__(16) uint8_t xs[];       // staged x, then [phases][rows of this block] floats
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-  const int nwaves = blockDim.x >> 6;
-  const int wpp = nwaves / g.phases;                  // waves per phase in this block
+  // waves per phase in this workgroup; (wave * wpp_inv) >> 16 = wave / wpp for wave < 16
+  // (both from the host: integer divisions here would delay the first request)
+  const int wpp = g.wpp;
   float *part = (float *)(xs + g.part_offset);
-  const int phase = wave / wpp;
+  const int phase = (wave * g.wpp_inv) >> 16;
   const int wslot = wave - phase * wpp;
   const int i = lane & 15, kb = lane >> 4;
   const int cit = 4 * i + kb;                         // chunk of this lane inside a tile
@@ -223,6 +225,7 @@ inline bool dense_block_shape(DenseGeom &g, int wpp, int tpi, int max_xp, Launch
   const bool multirow = g.mr_shift >= 0;
   ls.nwaves = wpp * g.phases;
   ls.tpi = tpi;
+  g.wpp = wpp; g.wpp_inv = (65536 + wpp - 1) / wpp;
   const int tiles_per_block = wpp * tpi;
   ls.nblocks = (g.ntiles + tiles_per_block - 1) / tiles_per_block;
   const int lds_pieces = multirow ? g.nchunks * 4 : g.phases * 256;

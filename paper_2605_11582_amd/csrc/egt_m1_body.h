@@ -35,6 +35,7 @@ struct M1Geom {
   int part_offset;     // byte offset of the per-phase partial sums in LDS
   int xtok;            // LDS bytes of the staged activations of one token
   int M;               // tokens (activation rows): 1, or up to MT in the several-token form
+  int wpp, wpp_inv;    // waves per phase in a workgroup, ceil(65536 / wpp)
   int hi_blocks;       // k_sparse_m1_one: workgroups [0, hi_blocks) take TPI tiles per wave, the others TPI - 1
   int64_t ldx, ldy;    // row strides of X and Y in elements (several-token form)
   uint32_t nib_mask;   // 0x00F0000F: low nibble of the low half, high nibble of the high half
@@ -66,10 +67,11 @@ __device__ __forceinline__ void k_sparse_m1_body(const uint32_t *__restrict__ ro
   const int g_phases = ONE ? 1 : g.phases, g_mr_shift = ONE ? -1 : g.mr_shift, g_nchunks = ONE ? 64 : g.nchunks;
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-  const int nwaves = blockDim.x >> 6;
-  const int wpp = nwaves / g_phases;                  // waves per phase in this block
+  // waves per phase in this workgroup; (wave * wpp_inv) >> 16 = wave / wpp for wave < 16
+  // (both from the host: integer divisions here would delay the first request)
+  const int wpp = ONE ? (int)(blockDim.x >> 6) : g.wpp;
   float *part = (float *)(xs + g.part_offset);
-  const int phase = ONE ? 0 : wave / wpp;
+  const int phase = ONE ? 0 : (wave * g.wpp_inv) >> 16;
   const int wslot = wave - phase * wpp;
   const int i = lane & 15, kb = lane >> 4;
   const int cit = 4 * i + kb;                         // chunk of this lane inside a tile
@@ -333,6 +335,7 @@ inline bool m1_block_shape(M1Geom &g, bool lin, int wpp, int tpi, int mt, int ma
   const bool multirow = g.mr_shift >= 0;
   ls.nwaves = wpp * g.phases;
   ls.tpi = tpi;
+  g.wpp = wpp; g.wpp_inv = (65536 + wpp - 1) / wpp;
   const int tiles_per_block = wpp * tpi;
   ls.nblocks = (g.ntiles + tiles_per_block - 1) / tiles_per_block;
   const int lds_pieces = multirow ? g.nchunks * 8 : g.phases * 512;

@@ -20,6 +20,7 @@ struct M1N1Geom {
   uint32_t m8, m4, m2; // masks of spread_idx, passed in so that they live in registers
   uint32_t nib_mask;   // 0x00F0000F
   uint32_t nib_magic;  // 0x54006400: FP16 {1024.0, 64.0}
+  int wpp, wpp_inv;    // waves per phase in a workgroup, ceil(65536 / wpp)
 };
 
 // QW = {scale, zero} pairs per chunk of 128 dense columns: 1 for groups of 128 and more,
@@ -37,10 +38,11 @@ __device__ __forceinline__ void k_sparse_m1_n1_body(const uint32_t *__restrict__
   extern __shared__ __align__(16) uint8_t xs[];       // staged x, then [phases][rows of this block] floats
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-  const int nwaves = blockDim.x >> 6;
-  const int wpp = nwaves / g.phases;
+  // waves per phase in this workgroup; (wave * wpp_inv) >> 16 = wave / wpp for wave < 16
+  // (both from the host: integer divisions here would delay the first request)
+  const int wpp = g.wpp;
   float *part = (float *)(xs + g.part_offset);
-  const int phase = wave / wpp;
+  const int phase = (wave * g.wpp_inv) >> 16;
   const int wslot = wave - phase * wpp;
   const int i = lane & 15, kb = lane >> 4;
   const int cit = 4 * i + kb;
@@ -304,6 +306,7 @@ inline bool n1_block_shape(M1N1Geom &g, bool lin, int ni, int wpp, int tpi, int 
   const bool multirow = g.mr_shift >= 0;
   ls.nwaves = wpp * g.phases;
   ls.tpi = tpi;
+  g.wpp = wpp; g.wpp_inv = (65536 + wpp - 1) / wpp;
   const int tiles_per_block = wpp * tpi;
   ls.nblocks = (g.ntiles + tiles_per_block - 1) / tiles_per_block;
   const int lds_pieces = lin ? g.phases * ni * 256 : multirow ? g.nchunks * 16 : g.phases * 1024;
