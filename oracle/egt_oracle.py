@@ -42,6 +42,14 @@ strictly ascending.
   values  : INT4 - byte t>>1, low nibble for even t;  FP16 - uint16[t] raw bits.
   qparams : INT4 only, uint16[R][K/g][2] = FP16 bits of {scale, zero}; the
             quantisation groups are ranges of g *dense* columns.
+
+Rows of different lengths (Sec. 3.2: N of N:4 is chosen adaptively; Sec. 3.3: the format is
+CSR-like, i.e. it has row pointers).  Row r keeps n_r in {1..4} entries per 4-group and has
+S_r = n_r*K/4 slots; row_ptr is the running sum of the S_r.  Since every row starts on a
+whole index word and a whole value byte (K % 32 == 0) and the quantiser works row by row,
+such a matrix is, by definition here, the row-by-row concatenation of the uniform encodings
+of its rows: that is how `pack_2bitcsr_rows` builds it, and `decode_row` / `gemv_rows` walk
+row_ptr as any CSR product does.  The dict says n_keep = 0 and carries row_n_keep.
 """
 from __future__ import annotations
 
@@ -352,6 +360,105 @@ def gemm_smallm(p: dict, X):
         Y[m] = prod.sum(axis=1)
         A[m] = np.abs(prod).sum(axis=1)
     return Y, A
+
+
+# --------------------------------------------------------------------------
+# O6b  rows of different lengths (Sec. 3.2 adaptive N:4, Sec. 3.3 CSR-like row pointers)
+# --------------------------------------------------------------------------
+def pack_2bitcsr_rows(w, mask, row_n_keep, group: int, val_kind: int) -> dict:
+    """Row r keeps row_n_keep[r] (1..4) entries per 4-group.  The result is the uniform
+    encoding of every row by itself, laid end to end; row_ptr is the running sum of the row
+    lengths."""
+    w = _as_f16(w)
+    R, K = w.shape
+    mask = np.asarray(mask)
+    if mask.shape != (R, K):
+        raise ValueError("mask shape")
+    nk = np.asarray(row_n_keep, dtype=np.int64)
+    if nk.shape != (R,) or np.any(nk < 1) or np.any(nk > 4):
+        raise ValueError("row_n_keep: one entry in 1..4 per row")
+    check_shape(R, K, 1, group, val_kind)
+    row_ptr = np.concatenate([[0], np.cumsum(nk * (K // 4))])
+    if row_ptr[-1] >= 2 ** 32:
+        raise ValueError("too many slots for uint32 row_ptr")
+    values, idx, qparams = [], [], []
+    for r in range(R):
+        one = pack_2bitcsr(w[r:r + 1], mask[r:r + 1], int(nk[r]), group, val_kind)
+        values.append(one["values"])
+        idx.append(one["idx"])
+        if val_kind == VAL_INT4:
+            qparams.append(one["qparams"])
+    cat = lambda parts, dt: np.concatenate(parts) if parts else np.zeros(0, dtype=dt)
+    return dict(rows=R, cols=K, n_keep=0, row_n_keep=nk.astype(np.int32), group=group, val_kind=val_kind,
+                row_ptr=row_ptr.astype(np.uint32), values=cat(values, np.uint8), idx=cat(idx, np.uint16),
+                qparams=(cat(qparams, np.uint16).reshape(R, K // group, 2) if val_kind == VAL_INT4 else None),
+                total_slots=int(row_ptr[-1]))
+
+
+def decode_row(p: dict, r: int):
+    """Dense columns and decoded weights (float64) of the slots of row r, read through
+    row_ptr: slots row_ptr[r] .. row_ptr[r+1]-1, n_r = (their number) / (K/4) per 4-group."""
+    K, g = p["cols"], p["group"]
+    t0, t1 = int(p["row_ptr"][r]), int(p["row_ptr"][r + 1])
+    S = t1 - t0
+    if S <= 0 or S % (K // 4) or S // (K // 4) > 4 or t0 % 8:
+        raise ValueError("row_ptr does not describe a whole row of 1..4 entries per 4-group")
+    n = S // (K // 4)
+    t = t0 + np.arange(S, dtype=np.int64)
+    offs = (p["idx"].astype(np.int64)[t >> 3] >> (2 * (t & 7))) & 3
+    col = 4 * (np.arange(S, dtype=np.int64) // n) + offs
+    if p["val_kind"] == VAL_FP16:
+        return col, p["values"].view(np.uint16)[t].view(np.float16).astype(np.float64)
+    q = (p["values"].astype(np.int64)[t >> 1] >> (4 * (t & 1))) & 15
+    s = p["qparams"][r, :, 0].view(np.float16).astype(np.float64)
+    z = p["qparams"][r, :, 1].view(np.float16).astype(np.float64)
+    return col, s[col // g] * (q.astype(np.float64) - z[col // g])
+
+
+def dense_from_packed_rows(p: dict) -> np.ndarray:
+    """Decoded matrix of a ragged encoding, dense float64; positions without a slot are 0."""
+    W = np.zeros((p["rows"], p["cols"]), dtype=np.float64)
+    for r in range(p["rows"]):
+        col, w_hat = decode_row(p, r)
+        W[r, col] = w_hat
+    return W
+
+
+def mask_from_packed_rows(p: dict) -> np.ndarray:
+    m = np.zeros((p["rows"], p["cols"]), dtype=np.uint8)
+    for r in range(p["rows"]):
+        m[r, decode_row(p, r)[0]] = 1
+    return m
+
+
+def gemm_rows(p: dict, X):
+    """Y_ref[m][r] = sum over the slots of row r of w_hat * X[m][col] and A = sum |.|,
+    the CSR product written out row by row (float64)."""
+    X = _as_f16(X).astype(np.float64)
+    if X.ndim != 2 or X.shape[1] != p["cols"]:
+        raise ValueError("X shape")
+    Y = np.zeros((X.shape[0], p["rows"]), dtype=np.float64)
+    A = np.zeros_like(Y)
+    for r in range(p["rows"]):
+        col, w_hat = decode_row(p, r)
+        prod = w_hat[None, :] * X[:, col]
+        Y[:, r] = prod.sum(axis=1)
+        A[:, r] = np.abs(prod).sum(axis=1)
+    return Y, A
+
+
+def gemv_rows(p: dict, x):
+    Y, A = gemm_rows(p, _as_f16(x)[None, :])
+    return Y[0], A[0]
+
+
+def buffer_sizes_rows(cols: int, row_n_keep, group: int, val_kind: int):
+    """Bytes of (row_ptr, values, idx, qparams) of a ragged encoding."""
+    nk = np.asarray(row_n_keep, dtype=np.int64)
+    T = int(nk.sum()) * (cols // 4)
+    R = len(nk)
+    return (4 * (R + 1), T // 2 if val_kind == VAL_INT4 else 2 * T, T // 4,
+            4 * R * (cols // group) if val_kind == VAL_INT4 else 0)
 
 
 # --------------------------------------------------------------------------

@@ -456,3 +456,144 @@ def test_synth_is_seeded():
     assert np.array_equal(a.view(np.uint16), b.view(np.uint16))
     assert abs(float(synth.weights(256, 256, 3).astype(np.float64).std()) - 0.02) < 0.001
     assert len(synth.sparse_layers()) == 16
+
+
+# ----------------------------------------------------------------- rows of different lengths
+def _ragged_fixture():
+    fx1, w1, mask1 = _fixture()
+    fx = read_fixture("handworked_ragged_2x32.txt")
+    w0 = np.array([float(v) for v in fx["w0"]], dtype=np.float16)[None, :]
+    mask0 = np.array([int(v) for v in fx["mask0"]], dtype=np.uint8)[None, :]
+    return fx, fx1, np.concatenate([w0, w1]), np.concatenate([mask0, mask1])
+
+
+def test_handworked_ragged_bytes():
+    fx, fx1, w, mask = _ragged_fixture()
+    p = O.pack_2bitcsr_rows(w, mask, [1, 2], 32, O.VAL_INT4)
+    assert p["n_keep"] == 0 and p["total_slots"] == 24
+    assert [int(v) for v in fx["row_ptr"]] == p["row_ptr"].tolist()
+    assert [int(v, 16) for v in fx["idx_words"]] == p["idx"].tolist()
+    assert [int(v, 16) for v in fx["value_bytes"]] == p["values"].tolist()
+    assert [int(v, 16) for v in fx["qparams"]] == p["qparams"].reshape(-1).tolist()
+    assert [int(v) for v in fx["sizes"]] == list(O.buffer_sizes_rows(32, [1, 2], 32, O.VAL_INT4))
+    col, w_hat = O.decode_row(p, 0)
+    assert [int(v) for v in fx["cols0"]] == col.tolist()
+    assert [0.5 * (int(q) - 4) for q in fx["q0"]] == w_hat.tolist()
+    x = np.arange(1, 33).astype(np.float16)
+    y, a = O.gemv_rows(p, x)
+    assert y.tolist() == [float(v) for v in fx["y"]] and a.tolist() == [float(v) for v in fx["abs_sum"]]
+    # FP16 values: raw bits of the kept weights, +0.0 in the padding slot
+    pf = O.pack_2bitcsr_rows(w, mask, [1, 2], 0, O.VAL_FP16)
+    bits = pf["values"].view(np.uint16).tolist()
+    assert bits == [int(v, 16) for v in fx["fp16_bits0"]] + [int(v, 16) for v in fx1["fp16_bits"]]
+    assert pf["idx"].tolist() == p["idx"].tolist() and pf["qparams"] is None
+    yf, _ = O.gemv_rows(pf, x)
+    assert yf.tolist() == [float(fx["y"][0]), float(fx1["y_fp16"][0])]
+
+
+@pytest.mark.parametrize("n,kind,g", [(1, 0, 32), (2, 0, 16), (3, 0, 64), (2, 1, 0), (4, 1, 0)])
+def test_equal_rows_reduce_to_the_uniform_format(n, kind, g):
+    R, K = 6, 64
+    w = _rand_w(R, K, 90 + n)
+    mask = O.prune_n4_magnitude(w, n)
+    u = O.pack_2bitcsr(w, mask, n, g, kind)
+    p = O.pack_2bitcsr_rows(w, mask, [n] * R, g, kind)
+    for key in ("row_ptr", "values", "idx"):
+        assert np.array_equal(u[key], p[key]), key
+    if kind == O.VAL_INT4:
+        assert np.array_equal(u["qparams"], p["qparams"])
+    x = _rand_x(K, 91)
+    assert np.array_equal(O.gemv(u, x)[0], O.gemv_rows(p, x)[0])
+    assert np.array_equal(O.dense_from_packed(u), O.dense_from_packed_rows(p))
+
+
+def _mixed_case(R, K, seed, choices=(1, 2)):
+    rng = np.random.default_rng(seed)
+    w = _rand_w(R, K, seed + 1)
+    nk = rng.choice(choices, size=R)
+    mask = np.zeros((R, K), dtype=np.uint8)
+    for n in np.unique(nk):
+        sel = nk == n
+        mask[sel] = O.prune_n4_magnitude(w[sel], int(n))
+    return w, mask, nk
+
+
+def test_ragged_fp16_is_the_masked_matrix_and_its_csr_product():
+    R, K = 24, 96
+    w, mask, nk = _mixed_case(R, K, 100, choices=(1, 2, 3, 4))
+    p = O.pack_2bitcsr_rows(w, mask, nk, 0, O.VAL_FP16)
+    want = np.where(mask != 0, w.astype(np.float64), 0.0)
+    assert np.array_equal(O.dense_from_packed_rows(p), want)          # decode(encode) = the kept entries
+    assert np.array_equal(O.mask_from_packed_rows(p), mask)           # top-n masks are full: no padding
+    assert np.array_equal(np.diff(p["row_ptr"].astype(np.int64)), nk * (K // 4))
+    X = np.stack([_rand_x(K, 101 + m) for m in range(3)])
+    Y, A = O.gemm_rows(p, X)
+    csr = scipy.sparse.csr_matrix(want)
+    assert csr.nnz <= int(nk.sum()) * (K // 4)
+    for m in range(3):
+        np.testing.assert_allclose(Y[m], csr @ X[m].astype(np.float64), rtol=0, atol=1e-12)
+        np.testing.assert_allclose(A[m], abs(csr) @ np.abs(X[m].astype(np.float64)), rtol=0, atol=1e-12)
+
+
+def test_ragged_int4_rows_against_brute_force_bit_reading():
+    """Every slot of every row read with Python integer arithmetic straight from the buffers."""
+    R, K, g = 10, 64, 16
+    w, mask, nk = _mixed_case(R, K, 110)
+    p = O.pack_2bitcsr_rows(w, mask, nk, g, O.VAL_INT4)
+    x = _rand_x(K, 111).astype(np.float64)
+    idx, vals, qp, row_ptr = p["idx"].tolist(), p["values"].tolist(), p["qparams"], p["row_ptr"].tolist()
+    y = []
+    for r in range(R):
+        acc, t, n = 0.0, row_ptr[r], int(nk[r])
+        assert row_ptr[r + 1] - row_ptr[r] == n * K // 4
+        for c4 in range(K // 4):
+            prev = -1
+            for _ in range(n):
+                off = (idx[t // 8] >> (2 * (t % 8))) & 3
+                assert off > prev
+                prev = off
+                q = (vals[t // 2] >> (4 * (t % 2))) & 15
+                c = 4 * c4 + off
+                s = float(qp[r, c // g, 0:1].view(np.float16)[0])
+                z = float(qp[r, c // g, 1:2].view(np.float16)[0])
+                acc += s * (q - z) * x[c]
+                t += 1
+        assert t == row_ptr[r + 1]
+        y.append(acc)
+    np.testing.assert_allclose(O.gemv_rows(p, x.astype(np.float16))[0], np.array(y), rtol=0, atol=1e-12)
+    # a 1:4 row is quantised from its own kept values: the same bytes as packing it alone
+    r1 = int(np.nonzero(nk == 1)[0][0])
+    alone = O.pack_2bitcsr(w[r1:r1 + 1], mask[r1:r1 + 1], 1, g, O.VAL_INT4)
+    t0 = row_ptr[r1]
+    assert np.array_equal(p["values"][t0 // 2: t0 // 2 + K // 8], alone["values"])
+    assert np.array_equal(p["qparams"][r1], alone["qparams"][0])
+
+
+def test_ragged_sizes_and_bytes_saved():
+    # half of the rows at 1:4 instead of 2:4: a quarter fewer value and index bytes
+    R, K, g = 64, 256, 128
+    nk = np.array([1, 2] * (R // 2))
+    b_mixed = O.buffer_sizes_rows(K, nk, g, O.VAL_INT4)
+    b_24 = O.buffer_sizes(R, K, 2, g, O.VAL_INT4)
+    assert b_mixed[0] == b_24[0] and b_mixed[3] == b_24[3]
+    assert 4 * (b_mixed[1] + b_mixed[2]) == 3 * (b_24[1] + b_24[2])
+    w, mask, _ = _mixed_case(R, K, 120)
+    mask = np.zeros_like(mask)
+    p = O.pack_2bitcsr_rows(w, mask, nk, g, O.VAL_INT4)
+    assert (p["row_ptr"].nbytes, p["values"].nbytes, p["idx"].nbytes, p["qparams"].nbytes) == b_mixed
+    assert not O.dense_from_packed_rows(p).any()                      # an empty mask: all padding, all zero
+
+
+def test_ragged_errors():
+    w, mask, nk = _mixed_case(4, 32, 130)
+    for bad in ([0, 1, 2, 1], [1, 2, 5, 1], [1, 2]):
+        with pytest.raises(ValueError):
+            O.pack_2bitcsr_rows(w, mask, bad, 32, O.VAL_INT4)
+    full = O.prune_n4_magnitude(w, 2)
+    with pytest.raises(ValueError):                                    # a 2:4 mask in a 1:4 row
+        O.pack_2bitcsr_rows(w, full, [2, 2, 1, 2], 32, O.VAL_INT4)
+    p = O.pack_2bitcsr_rows(w, mask, nk, 32, O.VAL_INT4)
+    p["row_ptr"] = p["row_ptr"].copy()
+    p["row_ptr"][1] += 4
+    with pytest.raises(ValueError):
+        O.decode_row(p, 1)
