@@ -199,6 +199,9 @@ def main():
     ap.add_argument("--counter-workloads", action="store_true",
                     help="also launch the other kernels 40 times each, untimed (dense INT4, FP16 values, 1:4, "
                          "M = 16 / 64), for rocprofv3 counter runs")
+    ap.add_argument("--counter-run", action="store_true",
+                    help="a short run for rocprofv3 --pmc: --steps headline launches without clock warm-up, read "
+                         "ceilings, table or oracle, then the --counter-workloads launches and five whole-stack launches")
     ap.add_argument("--cpu-worker", default=None, help=argparse.SUPPRESS)
     args = ap.parse_args()
     if args.cpu_worker:
@@ -214,6 +217,8 @@ def main():
     w = synth.weights(R, K, seed)
     x = synth.activations(K, seed)
 
+    if args.counter_run:
+        args.no_cpu_baseline = args.no_table = args.counter_workloads = True
     # the oracle on the host cores first: its worker processes start before this process
     # touches the GPU
     cpu = None if args.no_cpu_baseline else cpu_baseline(w, x)
@@ -240,6 +245,33 @@ def main():
     big = torch.empty(1 << 30, dtype=torch.uint8, device=dev).random_(0, 255)
     filler = B.prepared_stream_read(big, 1 << 30, sink)
     timer = Timer(torch, filler)
+
+    if args.counter_run:
+        for i in range(args.steps):
+            calls[i % copies]()
+        torch.cuda.synchronize()
+        reads = [B.prepared_stream_read(packed[i].values, packed[i].values.numel() // 16 * 16, sink) for i in range(copies)]
+        for i in range(40):
+            reads[i % copies]()
+        filler()
+        torch.cuda.synchronize()
+        if args.calibrate:
+            src = torch.empty(64 << 20, dtype=torch.uint8, device=dev).random_(0, 255)
+            dst = torch.empty_like(src)
+            for _ in range(10):
+                dst.copy_(src)
+            torch.cuda.synchronize()
+            del src, dst
+        counter_workloads(torch, B, synth, w, mask, p, dev)
+        from paper_2605_11582_amd import stack as S
+        del packed[:], calls[:]
+        stk = S.LayerStack.build(dev, distinct_layers=1)
+        whole = stk.one_launch()
+        for _ in range(5):
+            whole()
+        torch.cuda.synchronize()
+        print(json.dumps({"counter_run": True, "headline_launches": args.steps}))
+        return
 
     # clock warm-up: at least 0.3 s of back-to-back launches
     t_end = time.perf_counter() + 0.3

@@ -48,6 +48,13 @@
  *      all in binary64 with rint = ties-to-even.
  *    A 4-group whose mask keeps fewer than n entries is padded with the
  *    smallest unused offsets; padding slots hold an exact zero (q = z or +0.0).
+ *
+ * Rows of different lengths (Sec. 3.2 makes N of N:4 adaptive; Sec. 3.3 gives the format
+ * CSR-like row pointers): a matrix packed by egt_pack_2bitcsr_rows keeps n_r in 1..4
+ * entries per 4-group in row r, row r has S_r = n_r*K/4 slots, row_ptr is the running sum
+ * of the S_r and T = row_ptr[R].  Such a view has n_keep = 0 and says T in total_slots.
+ * Everything else (slot order, index words, nibbles, qparams per row and dense group) is
+ * as above; a row starts on a whole index word and a whole byte because K % 32 == 0.
  */
 #ifndef EGT_H
 #define EGT_H
@@ -84,6 +91,8 @@ typedef struct {
   void *values;          /* INT4: T/2 bytes; FP16: 2*T bytes                          */
   uint16_t *idx;         /* [T/8]                                                     */
   uint16_t *qparams;     /* INT4: [R][K/g][2]; FP16 values: NULL                      */
+  uint32_t total_slots;  /* rows of different lengths (n_keep == 0) only: T, the extent
+                            of values and idx that the caller vouches for                */
 } egt_2bitcsr;
 
 /* Text for a status code (static storage, never NULL). */
@@ -130,6 +139,17 @@ egt_status egt_pack_2bitcsr(const uint16_t *w, int64_t ldw, const uint8_t *mask,
                             int rows, int cols, int n_keep, int group, int val_kind,
                             egt_2bitcsr *out);
 
+/* HOST.  The encoder for rows of different lengths: row r keeps row_n_keep[r] in 1..4
+ * entries per 4-group (a 4-group of row r whose mask keeps more is EGT_ERR_MASK).  `out`
+ * gets n_keep = 0 and total_slots; its buffers have the sizes egt_2bitcsr_sizes_rows
+ * reports.  A 2:4 matrix in which half of the rows are 1:4 moves a quarter fewer bytes
+ * than the 2:4 matrix with those rows padded. */
+egt_status egt_2bitcsr_sizes_rows(int rows, int cols, const int32_t *row_n_keep, int group, int val_kind,
+                                  size_t bytes[4]);
+egt_status egt_pack_2bitcsr_rows(const uint16_t *w, int64_t ldw, const uint8_t *mask, int64_t ldm,
+                                 int rows, int cols, const int32_t *row_n_keep, int group, int val_kind,
+                                 egt_2bitcsr *out);
+
 /* HOST.  The same encoder with a group size per row (Sec. 3.2 "Adaptive Group-Wise
  * Quantization": channels found sensitive get more, smaller groups, robust ones fewer).
  * row_group: rows entries, each a multiple of `group` that divides cols (else
@@ -145,7 +165,8 @@ egt_status egt_pack_2bitcsr_rowgroups(const uint16_t *w, int64_t ldw, const uint
 /* HOST.  Inverse of the encoder: writes the decoded matrix (FP16 bits; s*(q-z)
  * rounded once to FP16 for INT4 values; 0 where no slot exists) and the mask of
  * positions that own a slot.  Either output may be NULL.  EGT_ERR_BUFFER when
- * row_ptr is not the uniform progression or offsets are not ascending. */
+ * row_ptr is not the uniform progression (n_keep = 0: not a running sum of whole rows of
+ * 1..4 entries per 4-group that ends at total_slots) or offsets are not ascending. */
 egt_status egt_unpack_2bitcsr(const egt_2bitcsr *in, uint16_t *w_dense, int64_t ldw,
                               uint8_t *mask, int64_t ldm);
 
@@ -164,7 +185,10 @@ egt_status egt_int4_gemv(const uint8_t *q, const uint16_t *qparams, int rows, in
 
 /* DEVICE.  SparseGemv (Sec. 3.3 "Computational Acceleration"): y = W.x for W in
  * 2bit-CSR with INT4 or FP16 values.  x: cols FP16, y: rows FP16.  A row whose
- * row_ptr entry is not r*S yields NaN in y[r] (the kernel checks it). */
+ * row_ptr entry is not r*S yields NaN in y[r] (the kernel checks it).  Rows of
+ * different lengths (n_keep = 0) are followed through row_ptr by a slot-by-slot kernel;
+ * a row whose pointers do not describe a whole row of 1..4 entries per 4-group that
+ * starts on an index word and ends inside total_slots yields NaN and is never read. */
 egt_status egt_sparse_gemv(const egt_2bitcsr *w, const uint16_t *x, uint16_t *y, void *stream);
 
 /* DEVICE.  Small-M form for tree-based parallel verification (Sec. 3.4): the M

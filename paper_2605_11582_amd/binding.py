@@ -23,6 +23,7 @@ SYMBOLS = (
     "egt_unpack_2bitcsr", "egt_quant_int4", "egt_int4_gemv", "egt_sparse_gemv",
     "egt_sparse_gemm_smallm", "egt_stream_read", "egt_sparse_gemv_batch", "egt_int4_gemv_batch",
     "egt_fit_verify_cost", "egt_trigger_depth", "egt_prune_n4_importance", "egt_pack_2bitcsr_rowgroups",
+    "egt_pack_2bitcsr_rows", "egt_2bitcsr_sizes_rows",
     "egt_gemv_stack_plan", "egt_gemv_stack_run", "egt_sparse_gemm_smallm_ws_bytes", "egt_sparse_gemm_smallm_ws",
     "egt_sparse_gemm_smallm_static",
 )
@@ -39,7 +40,7 @@ class View(C.Structure):
     _fields_ = [("rows", C.c_int32), ("cols", C.c_int32), ("n_keep", C.c_int32),
                 ("group_size", C.c_int32), ("val_kind", C.c_int32),
                 ("row_ptr", C.c_void_p), ("values", C.c_void_p), ("idx", C.c_void_p),
-                ("qparams", C.c_void_p)]
+                ("qparams", C.c_void_p), ("total_slots", C.c_uint32)]
 
 
 class GemvItem(C.Structure):
@@ -75,6 +76,9 @@ def _declare(L: C.CDLL, names=None) -> C.CDLL:
                               C.POINTER(View)], C.c_int),
         "egt_pack_2bitcsr_rowgroups": ([C.c_void_p, C.c_int64, C.c_void_p, C.c_int64, C.c_int, C.c_int, C.c_int, C.c_int,
                                         C.c_int, C.c_void_p, C.POINTER(View)], C.c_int),
+        "egt_2bitcsr_sizes_rows": ([C.c_int, C.c_int, C.c_void_p, C.c_int, C.c_int, C.POINTER(C.c_size_t)], C.c_int),
+        "egt_pack_2bitcsr_rows": ([C.c_void_p, C.c_int64, C.c_void_p, C.c_int64, C.c_int, C.c_int, C.c_void_p, C.c_int, C.c_int,
+                                   C.POINTER(View)], C.c_int),
         "egt_unpack_2bitcsr": ([C.POINTER(View), C.c_void_p, C.c_int64, C.c_void_p, C.c_int64], C.c_int),
         "egt_quant_int4": ([C.c_void_p, C.c_int64, C.c_int, C.c_int, C.c_int, C.c_void_p, C.c_void_p], C.c_int),
         "egt_int4_gemv": ([C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p], C.c_int),
@@ -194,6 +198,8 @@ class Packed:
     values: object
     idx: object
     qparams: object
+    total_slots: int = 0          # rows of different lengths (n_keep == 0): row_ptr[rows]
+    row_n_keep: object = None     # ... and the entries kept per 4-group in each row (host copy)
 
     def _ptr(self, b):
         if b is None:
@@ -203,10 +209,18 @@ class Packed:
     def view(self) -> View:
         return View(self.rows, self.cols, self.n_keep, self.group, self.val_kind,
                     self._ptr(self.row_ptr), self._ptr(self.values), self._ptr(self.idx),
-                    self._ptr(self.qparams))
+                    self._ptr(self.qparams), self.total_slots)
+
+    def sizes(self):
+        """Bytes of (row_ptr, values, idx, qparams) the view speaks for."""
+        if self.n_keep == 0:                             # total_slots is what the kernels trust
+            T, int4 = self.total_slots, self.val_kind == VAL_INT4
+            return (4 * (self.rows + 1), T // 2 if int4 else 2 * T, T // 4,
+                    4 * self.rows * (self.cols // self.group) if int4 else 0)
+        return sizes(self.rows, self.cols, self.n_keep, self.group, self.val_kind)
 
     def nbytes(self) -> int:
-        return sum(sizes(self.rows, self.cols, self.n_keep, self.group, self.val_kind))
+        return sum(self.sizes())
 
     def to(self, device) -> "Packed":
         import torch
@@ -215,7 +229,8 @@ class Packed:
                 return None
             return torch.from_numpy(np.ascontiguousarray(b).view(np.uint8).reshape(-1)).to(device)
         return Packed(self.rows, self.cols, self.n_keep, self.group, self.val_kind,
-                      up(self.row_ptr), up(self.values), up(self.idx), up(self.qparams))
+                      up(self.row_ptr), up(self.values), up(self.idx), up(self.qparams),
+                      self.total_slots, self.row_n_keep)
 
 
 def pack_2bitcsr(w: np.ndarray, mask: np.ndarray, n_keep: int, group: int, val_kind: int,
@@ -241,6 +256,36 @@ def pack_2bitcsr(w: np.ndarray, mask: np.ndarray, n_keep: int, group: int, val_k
             raise ValueError("row_group must have one entry per row")
         _check(lib().egt_pack_2bitcsr_rowgroups(_np_ptr(w), _ld(w), _np_ptr(mask), _ld(mask), rows, cols, n_keep,
                                                 group, val_kind, _np_ptr(rg), C.byref(v)))
+    return p
+
+
+def sizes_rows(rows: int, cols: int, row_n_keep, group: int, val_kind: int):
+    nk = np.ascontiguousarray(row_n_keep, dtype=np.int32)
+    if nk.shape != (rows,):
+        raise ValueError("row_n_keep must have one entry per row")
+    out = (C.c_size_t * 4)()
+    _check(lib().egt_2bitcsr_sizes_rows(rows, cols, _np_ptr(nk), group, val_kind, out))
+    return tuple(int(v) for v in out)
+
+
+def pack_2bitcsr_rows(w: np.ndarray, mask: np.ndarray, row_n_keep, group: int, val_kind: int) -> Packed:
+    """Rows of different lengths: row r keeps row_n_keep[r] entries per 4-group."""
+    w = _row_major(_f16_bits(w))
+    mask = _row_major(np.asarray(mask, dtype=np.uint8))
+    rows, cols = w.shape
+    if mask.shape != w.shape:
+        raise ValueError("mask shape")
+    nk = np.ascontiguousarray(row_n_keep, dtype=np.int32)
+    b = sizes_rows(rows, cols, nk, group, val_kind)
+    row_ptr = np.empty(b[0] // 4, dtype=np.uint32)
+    values = np.empty(b[1], dtype=np.uint8)
+    idx = np.empty(b[2] // 2, dtype=np.uint16)
+    qparams = np.empty((rows, cols // group, 2), dtype=np.uint16) if val_kind == VAL_INT4 else None
+    p = Packed(rows, cols, 0, group, val_kind, row_ptr, values, idx, qparams, 0, nk)
+    v = p.view()
+    _check(lib().egt_pack_2bitcsr_rows(_np_ptr(w), _ld(w), _np_ptr(mask), _ld(mask), rows, cols, _np_ptr(nk),
+                                       group, val_kind, C.byref(v)))
+    p.total_slots = int(v.total_slots)
     return p
 
 
@@ -304,7 +349,7 @@ def _need(t, nbytes: int, what: str, f16: bool = False):
 
 
 def _check_packed_dev(p: "Packed") -> None:
-    b = sizes(p.rows, p.cols, p.n_keep, p.group, p.val_kind)
+    b = p.sizes()
     for name, nb in zip(("row_ptr", "values", "idx", "qparams"), b):
         t = getattr(p, name)
         if t is None:

@@ -12,7 +12,10 @@ namespace {
 egt_status check_view(const egt_2bitcsr *w, bool pointers = true) {
   if (!w) return EGT_ERR_NULL;
   if (w->rows < 0 || w->cols < 0 || w->cols % 32 != 0) return EGT_ERR_SHAPE;
-  if (w->n_keep < 1 || w->n_keep > 4) return EGT_ERR_SHAPE;
+  if (w->n_keep < 0 || w->n_keep > 4) return EGT_ERR_SHAPE;
+  // n_keep == 0: rows of different lengths; the buffers hold total_slots whole index words
+  if (w->n_keep == 0 && (w->total_slots % 8 != 0 || (uint64_t)w->total_slots > (uint64_t)w->rows * (uint64_t)w->cols))
+    return EGT_ERR_SHAPE;
   if (w->val_kind == EGT_VAL_INT4) {
     if (w->group_size <= 0 || w->group_size % 4 != 0 || w->cols % w->group_size != 0)
       return EGT_ERR_SHAPE;

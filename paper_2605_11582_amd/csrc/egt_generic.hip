@@ -1,26 +1,41 @@
-// Generic (any n_keep, any group size, any K % 32 == 0) kernels of the SparseGemv
-// library.  They follow the format slot by slot with scalar FP32 arithmetic and
-// serve every shape the tuned kernels do not cover.  One wavefront per matrix
+// Generic (any n_keep, any group size, any K % 32 == 0, rows of different lengths) kernels
+// of the SparseGemv library.  They follow the format slot by slot with scalar FP32
+// arithmetic and serve every shape the tuned kernels do not cover.  One wavefront per matrix
 // row; lanes stride over the row's index words.
 #include "egt_device.h"
 
 namespace egt {
 
 // One wave per row, MT activation rows per pass (blockIdx.y selects the M-chunk).
-template <int VAL_KIND, int MT>
+// RAGGED: rows of different lengths (n_keep == 0 in the view).  The row's extent comes from
+// row_ptr[r] and row_ptr[r + 1]; it is followed only if it is a whole row of 1..4 entries per
+// 4-group that starts on an index word and ends inside `total_slots`, the extent of values
+// and idx the caller vouches for.  Otherwise the row is never read and reports NaN.
+template <int VAL_KIND, int MT, bool RAGGED>
 __global__ __launch_bounds__(256) void k_sparse_generic(
     const uint32_t *__restrict__ row_ptr, const uint8_t *__restrict__ values,
     const uint16_t *__restrict__ idx, const uint16_t *__restrict__ qparams, int rows, int cols,
-    int n_keep, int group, const __half *__restrict__ X, int64_t ldx, __half *__restrict__ Y,
-    int64_t ldy, int M) {
+    int n_keep, uint32_t total_slots, int group, const __half *__restrict__ X, int64_t ldx,
+    __half *__restrict__ Y, int64_t ldy, int M) {
   const int lane = threadIdx.x & 63;
   const int r = blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
   if (r >= rows) return;
   const int m0 = blockIdx.y * MT;
-  const uint32_t S = (uint32_t)n_keep * (uint32_t)(cols >> 2);
+  const uint32_t quarter = (uint32_t)(cols >> 2);
+  uint32_t S = (uint32_t)n_keep * quarter;
   const uint32_t t_row = row_ptr[r];
-  // the format has uniform rows: anything else is reported as NaN, never followed
-  const bool ok = t_row == (uint32_t)r * S;
+  bool ok;
+  if (RAGGED) {
+    const uint32_t t_end = row_ptr[r + 1];
+    S = t_end - t_row;
+    n_keep = quarter ? (int)(S / quarter) : 1;
+    ok = t_end >= t_row && t_end <= total_slots && (t_row & 7u) == 0 && n_keep >= 1 && n_keep <= 4 &&
+         (uint32_t)n_keep * quarter == S;
+    if (quarter == 0) ok = t_end == t_row;
+  } else {
+    // uniform rows: anything but the progression r*S is reported as NaN, never followed
+    ok = t_row == (uint32_t)r * S;
+  }
   float acc[MT];
 #pragma unroll
   for (int m = 0; m < MT; ++m) acc[m] = 0.f;
@@ -122,12 +137,15 @@ hipError_t launch_sparse_generic(const egt_2bitcsr &w, const uint16_t *X, int64_
   const dim3 block(256);
   const int mt = M == 1 ? 1 : 4;
   const dim3 grid((w.rows + 3) / 4, (M + mt - 1) / mt);
-#define EGT_GO(KIND, MT)                                                                        \
-  launch(k_sparse_generic<KIND, MT>, grid, block, 0, stream, w.row_ptr, (const uint8_t *)w.values, \
-         w.idx, w.qparams, w.rows, w.cols, w.n_keep, w.group_size, (const __half *)X, ldx,       \
+#define EGT_GO(KIND, MT, RAGGED)                                                                 \
+  launch(k_sparse_generic<KIND, MT, RAGGED>, grid, block, 0, stream, w.row_ptr, (const uint8_t *)w.values, \
+         w.idx, w.qparams, w.rows, w.cols, w.n_keep, w.total_slots, w.group_size, (const __half *)X, ldx, \
          (__half *)Y, ldy, M)
-  if (w.val_kind == EGT_VAL_INT4) return mt == 1 ? EGT_GO(EGT_VAL_INT4, 1) : EGT_GO(EGT_VAL_INT4, 4);
-  return mt == 1 ? EGT_GO(EGT_VAL_FP16, 1) : EGT_GO(EGT_VAL_FP16, 4);
+#define EGT_GO_MT(KIND, RAGGED) (mt == 1 ? EGT_GO(KIND, 1, RAGGED) : EGT_GO(KIND, 4, RAGGED))
+  if (w.n_keep == 0)                                  // rows of different lengths
+    return w.val_kind == EGT_VAL_INT4 ? EGT_GO_MT(EGT_VAL_INT4, true) : EGT_GO_MT(EGT_VAL_FP16, true);
+  return w.val_kind == EGT_VAL_INT4 ? EGT_GO_MT(EGT_VAL_INT4, false) : EGT_GO_MT(EGT_VAL_FP16, false);
+#undef EGT_GO_MT
 #undef EGT_GO
 }
 

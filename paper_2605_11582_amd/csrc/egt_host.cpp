@@ -77,6 +77,31 @@ egt_status check_shape(int rows, int cols, int n_keep, int group, int val_kind) 
   return EGT_OK;
 }
 
+// Shape rules of a matrix whose rows keep row_n_keep[r] (1..4) entries per 4-group each;
+// `slots`: the total number of slots.
+egt_status check_rows(int rows, int cols, const int32_t *row_n_keep, int group, int val_kind, uint64_t &slots) {
+  const egt_status st = check_shape(rows, cols, 1, group, val_kind);
+  if (st != EGT_OK) return st;
+  slots = 0;
+  for (int r = 0; r < rows; ++r) {
+    if (row_n_keep[r] < 1 || row_n_keep[r] > 4) return EGT_ERR_SHAPE;
+    slots += (uint64_t)row_n_keep[r] * (uint64_t)(cols / 4);
+  }
+  if (slots >= (1ull << 32)) return EGT_ERR_SHAPE;
+  return EGT_OK;
+}
+
+void fill_sizes(int rows, int cols, uint64_t slots, int group, int val_kind, size_t bytes[4]) {
+  bytes[0] = sizeof(uint32_t) * ((size_t)rows + 1);
+  bytes[1] = val_kind == EGT_VAL_INT4 ? (size_t)(slots / 2) : (size_t)(slots * 2);
+  bytes[2] = (size_t)(slots / 8) * sizeof(uint16_t);
+  bytes[3] = val_kind == EGT_VAL_INT4 ? sizeof(uint16_t) * 2 * (size_t)rows * (size_t)(cols / group) : 0;
+}
+
+egt_status pack_rows(const uint16_t *w, int64_t ldw, const uint8_t *mask, int64_t ldm, int rows, int cols,
+                     int n_keep, const int32_t *row_n_keep, int group, int val_kind, const int32_t *row_group,
+                     egt_2bitcsr *out);
+
 // Scale and zero point of one group from the extrema of its kept values.
 struct QParam { uint16_t s_bits; double s; int z; };
 inline QParam make_qparam(double vmin, double vmax) {
@@ -214,15 +239,48 @@ egt_status egt_prune_n4_importance(const uint16_t *w, int64_t ldw, const float *
 egt_status egt_pack_2bitcsr(const uint16_t *w, int64_t ldw, const uint8_t *mask, int64_t ldm,
                             int rows, int cols, int n_keep, int group, int val_kind,
                             egt_2bitcsr *out) {
-  return egt_pack_2bitcsr_rowgroups(w, ldw, mask, ldm, rows, cols, n_keep, group, val_kind, nullptr, out);
+  return pack_rows(w, ldw, mask, ldm, rows, cols, n_keep, nullptr, group, val_kind, nullptr, out);
 }
 
 egt_status egt_pack_2bitcsr_rowgroups(const uint16_t *w, int64_t ldw, const uint8_t *mask, int64_t ldm,
                                       int rows, int cols, int n_keep, int group, int val_kind,
                                       const int32_t *row_group, egt_2bitcsr *out) {
-  if (!w || !mask || !out) return EGT_ERR_NULL;
-  egt_status st = check_shape(rows, cols, n_keep, group, val_kind);
+  return pack_rows(w, ldw, mask, ldm, rows, cols, n_keep, nullptr, group, val_kind, row_group, out);
+}
+
+egt_status egt_pack_2bitcsr_rows(const uint16_t *w, int64_t ldw, const uint8_t *mask, int64_t ldm,
+                                 int rows, int cols, const int32_t *row_n_keep, int group, int val_kind,
+                                 egt_2bitcsr *out) {
+  if (!row_n_keep) return EGT_ERR_NULL;
+  return pack_rows(w, ldw, mask, ldm, rows, cols, 0, row_n_keep, group, val_kind, nullptr, out);
+}
+
+egt_status egt_2bitcsr_sizes_rows(int rows, int cols, const int32_t *row_n_keep, int group, int val_kind,
+                                  size_t bytes[4]) {
+  if (!bytes || !row_n_keep) return EGT_ERR_NULL;
+  uint64_t slots = 0;
+  const egt_status st = check_rows(rows, cols, row_n_keep, group, val_kind, slots);
   if (st != EGT_OK) return st;
+  fill_sizes(rows, cols, slots, group, val_kind, bytes);
+  return EGT_OK;
+}
+
+}  // extern "C"
+
+namespace {
+
+// The encoder.  row_n_keep == nullptr: n_keep entries per 4-group in every row; else row r
+// keeps row_n_keep[r] (rows of different lengths, row_ptr a true prefix sum, n_keep = 0
+// in the view).
+egt_status pack_rows(const uint16_t *w, int64_t ldw, const uint8_t *mask, int64_t ldm, int rows, int cols,
+                     int n_keep, const int32_t *row_n_keep, int group, int val_kind, const int32_t *row_group,
+                     egt_2bitcsr *out) {
+  if (!w || !mask || !out) return EGT_ERR_NULL;
+  uint64_t total_slots = 0;
+  egt_status st = row_n_keep ? check_rows(rows, cols, row_n_keep, group, val_kind, total_slots)
+                             : check_shape(rows, cols, n_keep, group, val_kind);
+  if (st != EGT_OK) return st;
+  auto n_of = [=](int r) { return row_n_keep ? (int)row_n_keep[r] : n_keep; };
   if (ldw < cols || ldm < cols) return EGT_ERR_SHAPE;
   if (!out->row_ptr || !out->values || !out->idx) return EGT_ERR_NULL;
   if (val_kind == EGT_VAL_INT4 && !out->qparams) return EGT_ERR_NULL;
@@ -242,6 +300,7 @@ egt_status egt_pack_2bitcsr_rowgroups(const uint16_t *w, int64_t ldw, const uint
       if ((int64_t)r * gpr * 8 > first.load(std::memory_order_relaxed)) break;
       const uint16_t *wr = w + (int64_t)r * ldw;
       const uint8_t *mr = mask + (int64_t)r * ldm;
+      const int n_row = n_of(r);
       for (int c = 0; c < cols; c += 4) {
         int cnt = 0;
         bool nonfinite = false;
@@ -250,8 +309,8 @@ egt_status egt_pack_2bitcsr_rowgroups(const uint16_t *w, int64_t ldw, const uint
           ++cnt;
           nonfinite |= !half_is_finite(wr[c + j]);
         }
-        if (cnt <= n_keep && !nonfinite) continue;
-        const int64_t key = ((int64_t)r * gpr + (c >> 2)) * 8 + (cnt > n_keep ? EGT_ERR_MASK : EGT_ERR_NONFINITE);
+        if (cnt <= n_row && !nonfinite) continue;
+        const int64_t key = ((int64_t)r * gpr + (c >> 2)) * 8 + (cnt > n_row ? EGT_ERR_MASK : EGT_ERR_NONFINITE);
         int64_t seen = first.load();
         while (key < seen && !first.compare_exchange_weak(seen, key)) {}
         r = r1;                                         // later rows of this range cannot come first
@@ -261,8 +320,12 @@ egt_status egt_pack_2bitcsr_rowgroups(const uint16_t *w, int64_t ldw, const uint
   });
   if (first.load() != INT64_MAX) return (egt_status)(first.load() & 7);
 
-  const int64_t S = (int64_t)n_keep * (cols / 4);
   const int G = val_kind == EGT_VAL_INT4 ? cols / group : 0;
+  // first slot of every row (uniform rows: r * S)
+  for (int64_t r = 0, t = 0; r <= rows; ++r) {
+    out->row_ptr[r] = (uint32_t)t;
+    if (r < rows) t += (int64_t)n_of((int)r) * (cols / 4);
+  }
   uint8_t *vals8 = (uint8_t *)out->values;
   uint16_t *vals16 = (uint16_t *)out->values;
   uint32_t *row_ptr = out->row_ptr;
@@ -273,7 +336,7 @@ egt_status egt_pack_2bitcsr_rowgroups(const uint16_t *w, int64_t ldw, const uint
     for (int r = r0; r < r1; ++r) {
       const uint16_t *wr = w + (int64_t)r * ldw;
       const uint8_t *mr = mask + (int64_t)r * ldm;
-      row_ptr[r] = (uint32_t)((int64_t)r * S);
+      const int n_row = n_of(r);
       if (val_kind == EGT_VAL_INT4) {
         // the row's own group size; its parameters are stored once per `group` columns
         const int gr = row_group ? row_group[r] : group, rep = gr / group;
@@ -295,11 +358,11 @@ egt_status egt_pack_2bitcsr_rowgroups(const uint16_t *w, int64_t ldw, const uint
           }
         }
       }
-      int64_t t = (int64_t)r * S;                                 // global slot id
+      int64_t t = (int64_t)row_ptr[r];                            // global slot id
       uint32_t word = 0;
       uint32_t byte = 0;
       for (int c = 0; c < cols; c += 4) {
-        const int set = choose4(mr + c, n_keep);
+        const int set = choose4(mr + c, n_row);
         for (int j = 0; j < 4; ++j) {
           if (!(set >> j & 1)) continue;
           word |= (uint32_t)j << (2 * (t & 7));
@@ -318,33 +381,51 @@ egt_status egt_pack_2bitcsr_rowgroups(const uint16_t *w, int64_t ldw, const uint
       }
     }
   });
-  row_ptr[rows] = (uint32_t)((int64_t)rows * S);
-  out->rows = rows; out->cols = cols; out->n_keep = n_keep;
+  out->rows = rows; out->cols = cols; out->n_keep = row_n_keep ? 0 : n_keep;
   out->group_size = group; out->val_kind = val_kind;
+  out->total_slots = row_ptr[rows];
   return EGT_OK;
 }
+
+}  // namespace
+
+extern "C" {
 
 egt_status egt_unpack_2bitcsr(const egt_2bitcsr *in, uint16_t *w_dense, int64_t ldw,
                               uint8_t *mask, int64_t ldm) {
   if (!in) return EGT_ERR_NULL;
-  const int rows = in->rows, cols = in->cols, n = in->n_keep, group = in->group_size;
-  egt_status st = check_shape(rows, cols, n, group, in->val_kind);
+  const int rows = in->rows, cols = in->cols, group = in->group_size;
+  const bool mixed = in->n_keep == 0;                  // rows of different lengths
+  egt_status st = check_shape(rows, cols, mixed ? 1 : in->n_keep, group, in->val_kind);
   if (st != EGT_OK) return st;
   if (!in->row_ptr || !in->values || !in->idx) return EGT_ERR_NULL;
   if (in->val_kind == EGT_VAL_INT4 && !in->qparams) return EGT_ERR_NULL;
   if ((w_dense && ldw < cols) || (mask && ldm < cols)) return EGT_ERR_SHAPE;
-  const int64_t S = (int64_t)n * (cols / 4);
-  for (int r = 0; r <= rows; ++r)
-    if (in->row_ptr[r] != (uint32_t)((int64_t)r * S)) return EGT_ERR_BUFFER;
+  // row_ptr: the uniform progression, or a running sum of whole rows that ends at total_slots
+  const int64_t quarter = cols / 4;
+  std::vector<int> n_row((size_t)rows);
+  for (int r = 0; r < rows; ++r) {
+    const int64_t len = (int64_t)in->row_ptr[r + 1] - (int64_t)in->row_ptr[r];
+    if (mixed) {
+      if (quarter == 0 || len % quarter != 0 || len / quarter < 1 || len / quarter > 4) return EGT_ERR_BUFFER;
+      n_row[r] = (int)(len / quarter);
+    } else {
+      if (in->row_ptr[r] != (uint32_t)((int64_t)r * in->n_keep * quarter) || len != in->n_keep * quarter) return EGT_ERR_BUFFER;
+      n_row[r] = in->n_keep;
+    }
+  }
+  if (rows > 0 && in->row_ptr[0] != 0) return EGT_ERR_BUFFER;
+  if (mixed && in->row_ptr[rows] != in->total_slots) return EGT_ERR_BUFFER;
   // offsets of a 4-group must ascend strictly
   std::atomic<int> err(EGT_OK);
   const uint16_t *idx = in->idx;
+  const uint32_t *row_ptr = in->row_ptr;
   parallel_rows(rows, [&](int r0, int r1) {
     for (int r = r0; r < r1; ++r) {
-      int64_t t = (int64_t)r * S;
+      int64_t t = (int64_t)row_ptr[r];
       for (int c = 0; c < cols; c += 4) {
         int prev = -1;
-        for (int k = 0; k < n; ++k, ++t) {
+        for (int k = 0; k < n_row[r]; ++k, ++t) {
           const int off = (idx[t >> 3] >> (2 * (t & 7))) & 3;
           if (off <= prev) err.store(EGT_ERR_BUFFER);
           prev = off;
@@ -359,13 +440,14 @@ egt_status egt_unpack_2bitcsr(const egt_2bitcsr *in, uint16_t *w_dense, int64_t 
   const uint16_t *qparams = in->qparams;
   const int val_kind = in->val_kind;
   const int G = val_kind == EGT_VAL_INT4 ? cols / group : 0;
+  const int *nr = n_row.data();
   parallel_rows(rows, [=](int r0, int r1) {
     for (int r = r0; r < r1; ++r) {
       if (w_dense) std::memset(w_dense + (int64_t)r * ldw, 0, sizeof(uint16_t) * (size_t)cols);
       if (mask) std::memset(mask + (int64_t)r * ldm, 0, (size_t)cols);
-      int64_t t = (int64_t)r * S;
+      int64_t t = (int64_t)row_ptr[r];
       for (int c = 0; c < cols; c += 4) {
-        for (int k = 0; k < n; ++k, ++t) {
+        for (int k = 0; k < nr[r]; ++k, ++t) {
           const int col = c + ((idx[t >> 3] >> (2 * (t & 7))) & 3);
           if (mask) mask[(int64_t)r * ldm + col] = 1;
           if (!w_dense) continue;

@@ -5,6 +5,18 @@
 
 #include "egt_mfma_common.h"
 
+// EGT_ABLATE (developer build, -DEGT_ABLATE=<bits>): stages of the 2:4 M = 1 kernel switched
+// off for timing; the results are then wrong on purpose.  The loads, their order and the
+// launch shape stay as they are, and every loaded register still reaches the stored value,
+// so nothing that is timed can be optimised away.
+//   bit 0: no dequantisation (the raw nibble dword goes to the instruction four times)
+//   bit 1: no matrix instructions (the operands are folded into the sum with an add)
+//   bit 2: no cross-lane reduction (each storing lane stores its own partial value)
+//   bit 3: x is not staged through LDS (no LDS write, no barrier, B operand = the raw pieces)
+#ifndef EGT_ABLATE
+#define EGT_ABLATE 0
+#endif
+
 namespace egt {
 
 // Eight INT4 codes of one dword (slot k in bits 4k..4k+3) -> four half2 registers
@@ -167,19 +179,21 @@ __device__ __forceinline__ void k_sparse_m1_body(const uint32_t *__restrict__ ro
   // ---- x through LDS.  Piece p lives at byte 16 p + 16 (p >> 5): one 16 B pad after
   //      every 512 B, so that the 16-lane reads below, whose addresses are 512 B
   //      apart, fall into different banks.  Pieces past the end of x are zero.
+  if (!(EGT_ABLATE & 8)) {
 #pragma unroll
-  for (int m = 0; m < MT; ++m) {
+    for (int m = 0; m < MT; ++m) {
 #pragma unroll
-    for (int j = 0; j < XP; ++j) {
-      const int pi = threadIdx.x + j * blockDim.x;
-      if (pi < lds_pieces) {
-        u4 v = xp[m][j];
-        if (pi >= npieces) v = u4{0, 0, 0, 0};
-        *(u4 *)(xs + m * g.xtok + 16 * pi + 16 * (pi >> XSH)) = v;
+      for (int j = 0; j < XP; ++j) {
+        const int pi = threadIdx.x + j * blockDim.x;
+        if (pi < lds_pieces) {
+          u4 v = xp[m][j];
+          if (pi >= npieces) v = u4{0, 0, 0, 0};
+          *(u4 *)(xs + m * g.xtok + 16 * pi + 16 * (pi >> XSH)) = v;
+        }
       }
     }
+    __syncthreads();
   }
-  __syncthreads();
   // B operand: column n = lane & 15 holds the activations of chunks 4n .. 4n+3;
   // lane (n, b) supplies k-octets b (first 8 halfs) and 4 + b (last 8 halfs)
   u8v bx[MT][4];
@@ -219,6 +233,15 @@ __device__ __forceinline__ void k_sparse_m1_body(const uint32_t *__restrict__ ro
     }
   }
 
+  if (EGT_ABLATE & 8) {
+#pragma unroll
+    for (int m = 0; m < MT; ++m)
+#pragma unroll
+      for (int d = 0; d < 4; ++d)
+#pragma unroll
+        for (int j = 0; j < 8; ++j) bx[m][d][j] = xp[m][(d + j) % XP][j & 3];
+  }
+
   // ---- consume
   const uint32_t magic = in_vgpr(g.nib_magic);
   float s[TPI][MT];
@@ -239,8 +262,19 @@ __device__ __forceinline__ void k_sparse_m1_body(const uint32_t *__restrict__ ro
 #pragma unroll
     for (int d = 0; d < 4; ++d) {
       u4 a;
-      if (KIND == EGT_VAL_INT4) a = dequant8(nib[t][0][d], off[d * QW / 4], s2[d * QW / 4], g.nib_mask, magic);
-      else a = nib[t][d];
+      if (KIND == EGT_VAL_INT4) {
+        if (EGT_ABLATE & 1) a = u4{nib[t][0][d], nib[t][0][d] ^ off[0], nib[t][0][d] ^ s2[0], nib[t][0][d]};
+        else a = dequant8(nib[t][0][d], off[d * QW / 4], s2[d * QW / 4], g.nib_mask, magic);
+      } else {
+        a = nib[t][d];
+      }
+      if (EGT_ABLATE & 2) {
+        const int iw_abl = LIN ? (int)iwl[t][d] : (d < 2 ? (int)iw[t][0] : (int)iw[t][1]);
+#pragma unroll
+        for (int m = 0; m < MT; ++m)
+          acc[m][0] += __builtin_bit_cast(float, a[0] ^ a[1] ^ a[2] ^ a[3] ^ bx[m][d][0] ^ (uint32_t)iw_abl);
+        continue;
+      }
       if constexpr (LIN) {
 #pragma unroll
         for (int m = 0; m < MT; ++m)
@@ -259,8 +293,10 @@ __device__ __forceinline__ void k_sparse_m1_body(const uint32_t *__restrict__ ro
     // D[q][q] sits in lane q + 16 (q / 4), register q % 4: lane 20 kb collects the
     // four diagonals of quads 4 kb .. 4 kb + 3 from its three right neighbours
 #pragma unroll
-    for (int m = 0; m < MT; ++m)
-      s[t][m] = acc[m][0] + row_shl<1>(acc[m][1]) + row_shl<2>(acc[m][2]) + row_shl<3>(acc[m][3]);
+    for (int m = 0; m < MT; ++m) {
+      if (EGT_ABLATE & 4) s[t][m] = acc[m][0] + acc[m][1] + acc[m][2] + acc[m][3];
+      else s[t][m] = acc[m][0] + row_shl<1>(acc[m][1]) + row_shl<2>(acc[m][2]) + row_shl<3>(acc[m][3]);
+    }
   }
   // ---- lane j < 16 fetches tile (j >> 2), quad group (j & 3); then sum the groups of a row
   const int src_lane = 20 * (lane & 3);
@@ -272,12 +308,14 @@ __device__ __forceinline__ void k_sparse_m1_body(const uint32_t *__restrict__ ro
 #pragma unroll
       for (int k = 0; k < 4; ++k) {
         if (4 * bt + k < TPI) {
-          const float gk = __shfl(s[4 * bt + k][m], src_lane, 64);
+          const float gk = (EGT_ABLATE & 4) ? s[4 * bt + k][m] : __shfl(s[4 * bt + k][m], src_lane, 64);
           v = ((lane >> 2) & 3) == k ? gk : v;
         }
       }
-      if (sum_steps >= 1) v += quad_xor1(v);
-      if (sum_steps >= 2) v += quad_xor2(v);
+      if (!(EGT_ABLATE & 4)) {
+        if (sum_steps >= 1) v += quad_xor1(v);
+        if (sum_steps >= 2) v += quad_xor2(v);
+      }
       if (st[bt] && (MT == 1 || m < g.M)) {
         const int r = rrow[bt];
         if (g_phases == 1) {

@@ -121,7 +121,7 @@ egt_status classify(const egt_gemv_item &it, ItemShape &s) {
     s.w = w;
     if (w.n_keep == 2 && sparse_m1_supported(w) && w.group_size >= 64) s.form = FORM_S24;
     else if (w.n_keep == 1 && sparse_m1_n1_supported(w) && w.group_size >= 128) s.form = FORM_S14;
-    else return (w.n_keep < 1 || w.n_keep > 4) ? EGT_ERR_SHAPE : EGT_ERR_UNSUPPORTED;
+    else return (w.n_keep < 0 || w.n_keep > 4) ? EGT_ERR_SHAPE : EGT_ERR_UNSUPPORTED;
     return EGT_OK;
   }
   if (it.rows < 0 || it.cols <= 0 || it.group <= 0 || it.group % 4 != 0 || it.cols % it.group != 0) return EGT_ERR_SHAPE;

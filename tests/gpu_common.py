@@ -87,7 +87,7 @@ def oracle_view(p: B.Packed) -> dict:
     """The library's packed bytes handed to the oracle's own decoder."""
     return dict(rows=p.rows, cols=p.cols, n_keep=p.n_keep, group=p.group, val_kind=p.val_kind,
                 row_ptr=np.asarray(p.row_ptr), values=np.asarray(p.values), idx=np.asarray(p.idx),
-                qparams=None if p.qparams is None else np.asarray(p.qparams))
+                qparams=None if p.qparams is None else np.asarray(p.qparams), total_slots=p.total_slots)
 
 
 def row_subset(p: B.Packed, rows: np.ndarray) -> dict:

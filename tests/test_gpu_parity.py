@@ -222,6 +222,100 @@ def test_full_size_sampled_rows(name, rows, cols, kind, g, cfg):
         G.assert_close(y[rr], yr, ar, f"{name} rows {r0}..")
 
 
+# ---------------------------------------------------------------- rows of different lengths
+def _ragged_case(rows, cols, g, kind, seed, choices=(1, 2), drop=0.0):
+    rng = np.random.default_rng(seed)
+    w = synth.weights(rows, cols, seed)
+    nk = rng.choice(choices, size=rows).astype(np.int32)
+    mask = np.zeros((rows, cols), dtype=np.uint8)
+    for n in np.unique(nk):
+        mask[nk == n] = B.prune_n4(np.ascontiguousarray(w[nk == n]), int(n))
+    if drop:
+        mask = (mask & (rng.random(mask.shape) >= drop)).astype(np.uint8)
+    return w, mask, nk
+
+
+@pytest.mark.parametrize("rows,cols,g,kind,choices", [
+    (37, 96, 32, 0, (1, 2)), (64, 4096, 128, 0, (1, 2)), (130, 1056, 96, 0, (1, 2, 3, 4)), (45, 4096, 0, 1, (1, 2)),
+    (21, 11008, 128, 0, (1, 2)), (9, 2112, 12, 0, (2, 4)), (3, 40960, 128, 0, (1, 2)), (1, 32, 32, 0, (1,)),
+])
+@pytest.mark.parametrize("M", [1, 5])
+def test_ragged_rows_small(rows, cols, g, kind, choices, M):
+    print(f"case ragged {rows}x{cols} g={g} kind={kind} rows keep {choices} M={M}", flush=True)
+    w, mask, nk = _ragged_case(rows, cols, g, kind, 7000 + rows + cols, choices, drop=0.1)
+    p = B.pack_2bitcsr_rows(w, mask, nk, g, kind)
+    o = O.pack_2bitcsr_rows(w, mask, nk, g, kind)
+    for k in ("row_ptr", "values", "idx"):
+        assert np.array_equal(getattr(p, k), o[k]), k
+    X = synth.activation_rows(M, cols, 7000 + rows)
+    Y_ref, A_ref = O.gemm_rows(o, X)
+    Y = G.run_sparse_gemm(p, X, ldx_pad=8, ldy_pad=3) if M > 1 else G.run_sparse_gemv(p, np.ascontiguousarray(X[0]))[None, :]
+    G.assert_close(Y, Y_ref, A_ref, "ragged rows")
+
+
+def test_ragged_rows_half_of_the_headline_matrix_at_one_in_four():
+    """Sec. 3.2's adaptive N:4 inside one matrix: every second row class keeps 1 of 4."""
+    rows, cols, g = 11008, 4096, 128
+    seed = synth.seed_for(synth.HEADLINE)
+    rng = np.random.default_rng(seed)
+    w = synth.weights(rows, cols, seed)
+    nk = rng.permutation(np.repeat([1, 2], rows // 2)).astype(np.int32)
+    mask = np.zeros((rows, cols), dtype=np.uint8)
+    for n in (1, 2):
+        mask[nk == n] = B.prune_n4(np.ascontiguousarray(w[nk == n]), n)
+    p = B.pack_2bitcsr_rows(w, mask, nk, g, 0)
+    uniform = sum(B.sizes(rows, cols, 2, g, 0))
+    saved = uniform - p.nbytes()
+    print(f"ragged 50/50 1:4 and 2:4: {p.nbytes()} bytes against {uniform} for 2:4 throughout, {saved} saved", flush=True)
+    assert saved == (rows // 2) * (cols // 4) * 6 // 8             # one slot (4 + 2 bits) per 4-group in half of the rows
+    x = synth.activations(cols, seed)
+    y = G.run_sparse_gemv(p, x)
+    pick = G.sample_rows(rows, 192, seed)
+    # sampled rows: the oracle packs them itself, its bytes must be the library's rows
+    o = O.pack_2bitcsr_rows(w[pick], mask[pick], nk[pick], g, 0)
+    for k, r in enumerate(pick):
+        t0, t1 = int(p.row_ptr[r]), int(p.row_ptr[r + 1])
+        u0, u1 = int(o["row_ptr"][k]), int(o["row_ptr"][k + 1])
+        assert t1 - t0 == u1 - u0
+        assert np.array_equal(p.values[t0 // 2:t1 // 2], o["values"][u0 // 2:u1 // 2])
+        assert np.array_equal(p.idx[t0 // 8:t1 // 8], o["idx"][u0 // 8:u1 // 8])
+    assert np.array_equal(p.qparams[pick], o["qparams"])
+    y_ref, a_ref = O.gemv_rows(o, x)
+    G.assert_close(y[pick], y_ref, a_ref, "ragged sampled rows")
+    # every row, decoded by the oracle from the library's bytes
+    y_all, a_all = O.gemv_rows(G.oracle_view(p), x)
+    G.assert_close(y, y_all, a_all, "ragged all rows")
+
+
+def test_ragged_broken_row_ptr_yields_nan_not_a_fault():
+    w, mask, nk = _ragged_case(64, 1024, 128, 0, 7100)
+    p = B.pack_2bitcsr_rows(w, mask, nk, 128, 0)
+    x = synth.activations(1024, 71)
+    good = G.run_sparse_gemv(p, x)
+    torch = G.torch_mod()
+    bad_rows = set()
+
+    def run(q):
+        y = torch.zeros(64, dtype=torch.float16, device="cuda")
+        B.sparse_gemv(q.to("cuda"), G.to_dev(x.view(np.uint16)).view(torch.float16), y)
+        torch.cuda.synchronize()
+        return y.cpu().numpy()
+
+    q = B.Packed(**{**p.__dict__, "row_ptr": p.row_ptr.copy()})
+    q.row_ptr[7] += 4                       # rows 6 and 7 are not whole rows, row 7 not on an index word
+    q.row_ptr[40] = 0xFFFFFFF8              # row 39 runs far past the buffers, row 40 has a negative length
+    y = run(q)
+    bad_rows = [6, 7, 39, 40]
+    assert np.all(np.isnan(y[bad_rows]))
+    keep = np.ones(64, dtype=bool)
+    keep[bad_rows] = False
+    assert np.array_equal(y[keep].view(np.uint16), good[keep].view(np.uint16))
+    # a view that vouches for fewer slots than row_ptr walks: the rows beyond are not read
+    q = B.Packed(**{**p.__dict__, "total_slots": int(p.row_ptr[50])})
+    y = run(q)
+    assert np.all(np.isnan(y[50:])) and np.array_equal(y[:50].view(np.uint16), good[:50].view(np.uint16))
+
+
 # ---------------------------------------------------------------- small M
 @pytest.mark.parametrize("M", [1, 2, 3, 4, 5, 16, 33, 64])
 def test_smallm_small_shapes(M):

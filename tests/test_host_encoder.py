@@ -297,6 +297,109 @@ def test_unpack_rejects_broken_buffers():
     assert e.value.status == 5
 
 
+# ----------------------------------------------------------------- rows of different lengths
+def _mixed(R, K, seed, choices=(1, 2), drop=False):
+    rng = np.random.default_rng(seed)
+    w = synth.weights(R, K, seed)
+    nk = rng.choice(choices, size=R).astype(np.int32)
+    mask = np.zeros((R, K), dtype=np.uint8)
+    for n in np.unique(nk):
+        mask[nk == n] = O.prune_n4_magnitude(w[nk == n], int(n))
+    if drop:                                   # some groups keep fewer than their row allows: padding slots
+        mask[rng.random((R, K)) < 0.1] = 0
+    return w, mask, nk
+
+
+def _same_ragged(p, o):
+    assert (p.rows, p.cols, p.n_keep, p.group, p.val_kind, p.total_slots) == \
+        (o["rows"], o["cols"], 0, o["group"], o["val_kind"], o["total_slots"])
+    for key in ("row_ptr", "idx", "values"):
+        assert np.array_equal(getattr(p, key), o[key]), key
+    assert (p.qparams is None) if o["qparams"] is None else np.array_equal(p.qparams, o["qparams"])
+
+
+def test_library_packs_the_handworked_ragged_matrix():
+    from helpers import read_fixture
+    fx, fx1 = read_fixture("handworked_ragged_2x32.txt"), read_fixture("handworked_1x32.txt")
+    w = np.array([[float(v) for v in fx["w0"]], [float(v) for v in fx1["w"]]], dtype=np.float16)
+    mask = np.array([[int(v) for v in fx["mask0"]], [int(v) for v in fx1["mask"]]], dtype=np.uint8)
+    p = B.pack_2bitcsr_rows(w, mask, [1, 2], 32, B.VAL_INT4)
+    assert p.n_keep == 0 and p.total_slots == 24
+    assert p.row_ptr.tolist() == [int(v) for v in fx["row_ptr"]]
+    assert p.idx.tolist() == [int(v, 16) for v in fx["idx_words"]]
+    assert p.values.tolist() == [int(v, 16) for v in fx["value_bytes"]]
+    assert np.asarray(p.qparams).reshape(-1).tolist() == [int(v, 16) for v in fx["qparams"]]
+    assert list(B.sizes_rows(2, 32, [1, 2], 32, B.VAL_INT4)) == [int(v) for v in fx["sizes"]]
+    pf = B.pack_2bitcsr_rows(w, mask, [1, 2], 0, B.VAL_FP16)
+    assert np.asarray(pf.values).view(np.uint16).tolist()[:8] == [int(v, 16) for v in fx["fp16_bits0"]]
+
+
+@pytest.mark.parametrize("choices,g,kind,drop", [((1, 2), 128, 0, False), ((1, 2), 32, 0, True), ((1, 2, 3, 4), 16, 0, True),
+                                                 ((1, 2), 0, 1, True), ((2, 4), 12, 0, False)])
+def test_ragged_pack_bit_exact_and_round_trip(choices, g, kind, drop):
+    R, K = 37, 384
+    w, mask, nk = _mixed(R, K, 400 + g, choices, drop)
+    p = B.pack_2bitcsr_rows(w, mask, nk, g, kind)
+    o = O.pack_2bitcsr_rows(w, mask, nk, g, kind)
+    _same_ragged(p, o)
+    assert B.sizes_rows(R, K, nk, g, kind) == O.buffer_sizes_rows(K, nk, g, kind) == \
+        (p.row_ptr.nbytes, p.values.nbytes, p.idx.nbytes, 0 if p.qparams is None else p.qparams.nbytes)
+    wd, md = B.unpack_2bitcsr(p)
+    assert np.array_equal(md, O.mask_from_packed_rows(o))
+    assert np.array_equal(wd.view(np.uint16), O.dense_from_packed_rows(o).astype(np.float16).view(np.uint16))
+
+
+def test_ragged_pack_of_equal_rows_is_the_uniform_pack():
+    w, mask, _ = _mixed(16, 128, 410, choices=(2,))
+    p = B.pack_2bitcsr_rows(w, mask, [2] * 16, 64, 0)
+    u = B.pack_2bitcsr(w, mask, 2, 64, 0)
+    for key in ("row_ptr", "values", "idx", "qparams"):
+        assert np.array_equal(getattr(p, key), getattr(u, key))
+    assert p.total_slots == 16 * 64
+
+
+def test_ragged_pack_and_unpack_errors():
+    w, mask, nk = _mixed(8, 64, 420)
+    for bad in ([0] + [1] * 7, [5] + [1] * 7):
+        with pytest.raises(B.EgtError) as e:
+            B.sizes_rows(8, 64, bad, 32, 0)
+        assert e.value.status == 2
+    with pytest.raises(ValueError):
+        B.sizes_rows(8, 64, [1, 2], 32, 0)
+    full = O.prune_n4_magnitude(w, 2)
+    one = np.array([2, 2, 2, 1, 2, 2, 2, 2], dtype=np.int32)
+    with pytest.raises(B.EgtError) as e:        # a 2:4 mask in a row that keeps one entry per 4-group
+        B.pack_2bitcsr_rows(w, full, one, 32, 0)
+    assert e.value.status == 3
+    L = B.lib()
+    assert L.egt_pack_2bitcsr_rows(16, 64, 16, 64, 8, 64, None, 32, 0, ctypes.byref(B.View())) == 1
+    assert L.egt_2bitcsr_sizes_rows(8, 64, None, 32, 0, (ctypes.c_size_t * 4)()) == 1
+    p = B.pack_2bitcsr_rows(w, mask, nk, 32, 0)
+    good = p.row_ptr.copy()
+    p.row_ptr[3] += 8                           # rows 2 and 3 are no longer whole rows
+    with pytest.raises(B.EgtError) as e:
+        B.unpack_2bitcsr(p)
+    assert e.value.status == 5
+    p.row_ptr[:] = good
+    p.total_slots += 8                          # the running sum does not end where the view says
+    with pytest.raises(B.EgtError) as e:
+        B.unpack_2bitcsr(p)
+    assert e.value.status == 5
+
+
+def test_device_entry_points_check_a_ragged_view_without_a_gpu():
+    L = B.lib()
+    ok = B.View(0, 64, 0, 32, 0, 16, 16, 16, 16, 0)                  # no rows: nothing runs
+    assert L.egt_sparse_gemv(ctypes.byref(ok), 16, 16, None) == 0
+    odd = B.View(8, 64, 0, 32, 0, 16, 16, 16, 16, 132)               # not whole index words
+    assert L.egt_sparse_gemv(ctypes.byref(odd), 16, 16, None) == 2
+    big = B.View(8, 64, 0, 32, 0, 16, 16, 16, 16, 8 * 64 + 8)        # more slots than the matrix has entries
+    assert L.egt_sparse_gemv(ctypes.byref(big), 16, 16, None) == 2
+    items = _fake_items([B.View(64, 4096, 0, 128, 0, 16, 16, 16, 16, 64 * 1024)])
+    plan = B.StackPlan()
+    assert L.egt_gemv_stack_plan(items, 1, B.STACK_AUTO, None, 0, ctypes.byref(plan)) == 6   # no table form for ragged rows
+
+
 @pytest.mark.parametrize("g,cols", [(8, 512), (32, 512), (128, 512), (4, 64), (12, 96), (20, 160)])
 def test_quant_int4_dense_bit_exact(g, cols):
     w = synth.weights(48, cols, 55 + g)

@@ -12,10 +12,10 @@ import pytest
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 CSRC = os.path.join(ROOT, "paper_2605_11582_amd", "csrc")
 HOST_SYMBOLS = ("egt_status_str", "egt_2bitcsr_sizes", "egt_prune_n4", "egt_prune_n4_importance", "egt_pack_2bitcsr",
-                "egt_pack_2bitcsr_rowgroups", "egt_unpack_2bitcsr", "egt_quant_int4", "egt_fit_verify_cost", "egt_trigger_depth")
+                "egt_pack_2bitcsr_rowgroups", "egt_pack_2bitcsr_rows", "egt_2bitcsr_sizes_rows", "egt_unpack_2bitcsr", "egt_quant_int4", "egt_fit_verify_cost", "egt_trigger_depth")
 HOST_TESTS = ("packs_the_handworked or status_strings or sizes_match or prune_matches or importance_prune or pack_bit_exact or "
               "row_groups or wide_value_ranges or pack_errors or first_offending or strided_inputs or unpack_ or quant_int4_dense or "
-              "trigger_cost_model")
+              "trigger_cost_model or ragged_pack")
 
 CHILD = r"""
 import ctypes, sys
