@@ -40,11 +40,10 @@ LLC_BYTES = 256 << 20
 REPEATS = 5
 R, K, N, GRP = 11008, 4096, 2, 128
 TRAFFIC_PROFILE = os.path.join("profiles", "sparse_m1_headline_hbm_traffic.txt")
-# vector-ALU instructions the headline kernel issues per tile (one row of 4096 columns per
-# wave) and per wave outside the tile loop, counted in the ISA of the shipped kernel
-# (profiles/sparse_m1_headline_isa_counts.txt); one wave64 instruction occupies its SIMD
-# for 4 cycles, the device has 1024 SIMDs at 2.4 GHz
-VALU_COUNTS_PROFILE = os.path.join("profiles", "sparse_m1_headline_isa_counts.txt")
+# vector-ALU instructions and matrix-core busy cycles of one headline launch, counted by
+# rocprofv3 (profiles/sparse_m1_headline_counters.txt); one wave64 vector instruction
+# occupies its 16-lane SIMD for 4 cycles, the device has 1024 SIMDs at 2.4 GHz
+COUNTERS_PROFILE = os.path.join("profiles", "sparse_m1_headline_counters.txt")
 SIMDS, CLOCK_HZ, CYCLES_PER_VALU = 1024, 2.4e9, 4
 
 
@@ -202,6 +201,8 @@ def main():
     ap.add_argument("--counter-run", action="store_true",
                     help="a short run for rocprofv3 --pmc: --steps headline launches without clock warm-up, read "
                          "ceilings, table or oracle, then the --counter-workloads launches and five whole-stack launches")
+    ap.add_argument("--only-stack", action="store_true",
+                    help="time the whole-stack launch of configuration 4 only (for sweeps of a tuning build)")
     ap.add_argument("--cpu-worker", default=None, help=argparse.SUPPRESS)
     args = ap.parse_args()
     if args.cpu_worker:
@@ -245,6 +246,17 @@ def main():
     big = torch.empty(1 << 30, dtype=torch.uint8, device=dev).random_(0, 255)
     filler = B.prepared_stream_read(big, 1 << 30, sink)
     timer = Timer(torch, filler)
+
+    if args.only_stack:
+        from paper_2605_11582_amd import stack as S
+        del packed[:], calls[:]
+        stk = S.LayerStack.build(dev, distinct_layers=1)     # the traffic of all 224 matrices; the numbers repeat
+        whole = stk.one_launch()
+        plan = whole.plan
+        row = entry(timer(lambda i: whole(), 10, 2), stk.nbytes)
+        row.update(mode=plan.mode, grid=plan.grid_x, block_threads=plan.block_threads, lds_bytes=plan.lds_bytes, items=plan.nitems)
+        print(json.dumps({"only_stack": True, "config4_whole_stack": row}))
+        return
 
     if args.counter_run:
         for i in range(args.steps):
@@ -309,8 +321,8 @@ def main():
 
     gbps = nbytes / t_dev / 1e9
     traffic = profile_number(TRAFFIC_PROFILE, "traffic_bytes_per_launch")
-    valu_per_tile = profile_number(VALU_COUNTS_PROFILE, "valu_per_tile")
-    valu_per_wave = profile_number(VALU_COUNTS_PROFILE, "valu_per_wave_outside_tiles")
+    valu_insts = profile_number(COUNTERS_PROFILE, "valu_insts_per_launch")
+    mfma_cycles = profile_number(COUNTERS_PROFILE, "mfma_busy_cycles_per_launch")
     result = {
         "metric": "SparseGemv achieved HBM GB/s, INT4 2:4 11008x4096, M=1",
         "value": round(gbps, 1),
@@ -344,13 +356,14 @@ def main():
                          "one_gib_gbps": round((1 << 30) / t_big["median"] / 1e9, 1),
                          "empty_kernel_us": round(t_tiny["median"] * 1e6, 3)},
     }
-    if valu_per_tile is not None and valu_per_wave is not None:
-        waves = -(-R // 16) * 4                           # 4 waves per workgroup, 4 rows (tiles) per wave
-        issue_s = (R * valu_per_tile + waves * valu_per_wave) * CYCLES_PER_VALU / (SIMDS * CLOCK_HZ)
-        result["valu_issue_bound"] = {"us": round(issue_s * 1e6, 3), "valu_per_tile": valu_per_tile,
-                                      "valu_per_wave_outside_tiles": valu_per_wave,
-                                      "model": "wave instructions x 4 cycles / (1024 SIMDs x 2.4 GHz), perfectly spread",
-                                      "source": VALU_COUNTS_PROFILE}
+    if valu_insts is not None and mfma_cycles is not None:
+        issue_s = (valu_insts * CYCLES_PER_VALU + mfma_cycles) / (SIMDS * CLOCK_HZ)
+        result["valu_issue_bound"] = {"us": round(issue_s * 1e6, 3), "valu_insts_per_launch": int(valu_insts),
+                                      "valu_insts_per_nnz": round(valu_insts / (R * N * K // 4), 4),
+                                      "mfma_busy_cycles_per_launch": int(mfma_cycles),
+                                      "model": "(vector instructions x 4 cycles + matrix busy cycles) / (1024 SIMDs x 2.4 GHz), "
+                                               "perfectly spread",
+                                      "source": COUNTERS_PROFILE + " (not re-measured by this run)"}
 
     if not args.no_table:
         result["table"] = table(torch, B, synth, timer, dev, w, mask, xd, ys, calls, packed)
@@ -395,6 +408,7 @@ def table(torch, B, synth, timer, dev, w, mask, xd, ys, calls, packed):
     """Every configuration of the benchmark spec, timed like the headline."""
     from paper_2605_11582_amd import stack as S
     t = {}
+    packed_bytes_24 = packed[0].nbytes()
     up16 = lambda a: torch.from_numpy(a.view(np.int16)).to(dev).view(torch.float16)
     # the headline launch on one copy only (weights stay in the last-level cache)
     t["headline_hot_cache"] = entry(timer(lambda i: calls[0](), 1000), algorithmic_bytes(R, K, N, GRP, 0))
@@ -432,6 +446,19 @@ def table(torch, B, synth, timer, dev, w, mask, xd, ys, calls, packed):
     f14 = [B.prepared_sparse_gemv(pk14[i], xd, ys[0]) for i in range(c14)]
     t["sparse_int4_1to4_11008x4096"] = entry(timer(lambda i: f14[i % c14](), 1000), algorithmic_bytes(R, K, 1, GRP, 0))
     del pk14, f14
+    # rows of different lengths: half of the rows keep 1 of 4 (Sec. 3.2's adaptive N inside one
+    # matrix); the slot-by-slot kernel that follows row_ptr, not a matrix-core path
+    rng = np.random.default_rng(synth.seed_for(synth.HEADLINE))
+    nk = rng.permutation(np.repeat([1, 2], R // 2)).astype(np.int32)
+    mask_r = np.where((nk == 1)[:, None], B.prune_n4(w, 1), mask).astype(np.uint8)
+    pr = B.pack_2bitcsr_rows(w, mask_r, nk, GRP, B.VAL_INT4)
+    cr = max(2, -(-2 * LLC_BYTES // pr.nbytes()))
+    pkr = [pr.to(dev) for _ in range(cr)]
+    fr = [B.prepared_sparse_gemv(pkr[i], xd, ys[0]) for i in range(cr)]
+    rag_bytes = pr.nbytes() - 4 + 2 * K + 2 * R
+    t["sparse_int4_rows_half_1to4_11008x4096"] = entry(timer(lambda i: fr[i % cr](), 200), rag_bytes)
+    t["sparse_int4_rows_half_1to4_11008x4096"]["bytes_saved_vs_2to4"] = packed_bytes_24 - pr.nbytes()
+    del pkr, fr
     # config 5: small M on both shapes; the M-sweep of one all-2:4 layer (q/k/v/o, gate/up,
     # down) feeds the trigger cost model of Sec. 3.4: verification ~ a + b*M, AR step = t(1)
     sweep_m = (1, 2, 4, 8, 16, 32, 64)
@@ -449,6 +476,13 @@ def table(torch, B, synth, timer, dev, w, mask, xd, ys, calls, packed):
             layer_us[M] += reps * t5["median"] * 1e6
             if mi < 2 and M in (1, 4, 16, 64):
                 t[f"config5_{r5}x{k5}_M{M}"] = entry(t5, algorithmic_bytes(r5, k5, 2, 128, 0, M), flops=2 * M * r5 * k5 / 2)
+            need = B.smallm_ws_bytes(pk5[0], M)
+            if mi < 2 and need:                       # K split over workgroups, partial sums in a caller's workspace
+                ws = torch.empty(need, dtype=torch.uint8, device=dev)
+                f5w = [B.prepared_sparse_gemm_smallm_ws(pk5[i], X, Y, ws) for i in range(c5)]
+                t[f"config5_{r5}x{k5}_M{M}_k_split_workspace"] = entry(
+                    timer(lambda i: f5w[i % c5](), 300), algorithmic_bytes(r5, k5, 2, 128, 0, M), flops=2 * M * r5 * k5 / 2)
+                del f5w, ws
         del pk5
     fit_a, fit_b = B.fit_verify_cost(list(sweep_m[1:]), [layer_us[m] for m in sweep_m[1:]])
     cand = [64, 24, 9, 4, 2, 1]                      # candidates left per trie depth (wide top, narrow bottom)

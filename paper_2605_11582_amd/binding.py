@@ -13,7 +13,9 @@ from dataclasses import dataclass
 import numpy as np
 
 _PKG = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_PKG, "libegt.so")
+# EGT_LIBRARY names another build of the same library (a tuning or ablation build made with
+# EGT_EXTRA_HIPCC_FLAGS, see build.py); the default is the in-tree one
+LIB_PATH = os.environ.get("EGT_LIBRARY") or os.path.join(_PKG, "libegt.so")
 
 VAL_INT4 = 0
 VAL_FP16 = 1

@@ -10,7 +10,8 @@
 // launch shape stay as they are, and every loaded register still reaches the stored value,
 // so nothing that is timed can be optimised away.
 //   bit 0: no dequantisation (the raw nibble dword goes to the instruction four times)
-//   bit 1: no matrix instructions (the operands are folded into the sum with an add)
+//   bit 1: no matrix instructions (the operands are folded into the sum with shifts, xors and
+//          one add; the shifts keep equal registers from cancelling)
 //   bit 2: no cross-lane reduction (each storing lane stores its own partial value)
 //   bit 3: x is not staged through LDS (no LDS write, no barrier, B operand = the raw pieces)
 #ifndef EGT_ABLATE
@@ -272,7 +273,7 @@ __device__ __forceinline__ void k_sparse_m1_body(const uint32_t *__restrict__ ro
         const int iw_abl = LIN ? (int)iwl[t][d] : (d < 2 ? (int)iw[t][0] : (int)iw[t][1]);
 #pragma unroll
         for (int m = 0; m < MT; ++m)
-          acc[m][0] += __builtin_bit_cast(float, a[0] ^ a[1] ^ a[2] ^ a[3] ^ bx[m][d][0] ^ (uint32_t)iw_abl);
+          acc[m][0] += __builtin_bit_cast(float, a[0] ^ (a[1] >> 1) ^ (a[2] << 1) ^ (a[3] >> 2) ^ bx[m][d][0] ^ (uint32_t)iw_abl);
         continue;
       }
       if constexpr (LIN) {

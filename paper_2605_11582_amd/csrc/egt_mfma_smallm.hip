@@ -79,9 +79,21 @@ struct SmallMKsGeom {
 
 template <int KIND, int QW>
 struct ATile {                        // A operand of one row tile, one K-step
-  u4 nib[KIND == EGT_VAL_INT4 ? 1 : 4];
+  static constexpr int VW = KIND == EGT_VAL_INT4 ? 1 : 4;        // 16-byte value registers per lane
+  // Vector-memory requests that fetch one tile: the index words, then either the nibbles
+  // and the quantisation parameters (any QW: one request) or VW requests of FP16 values.
+  // The kernel waits with hand-counted `s_waitcnt vmcnt(n)`; every n is a multiple of
+  // this number, and every request in load_a names its ordinal below it (TileRequest).
+  static constexpr int LOADS = KIND == EGT_VAL_INT4 ? 3 : 1 + VW;
+  u4 nib[VW];
   u2 iw;
   uint32_t qp[QW];                    // {scale, zero} pairs of the chunk (QW > 1: groups narrower than a chunk)
+};
+// Tag of the ORD-th request of a tile: a request added to load_a without raising
+// ATile::LOADS (and with it every wait count) does not compile.
+template <int ORD, int LOADS>
+struct TileRequest {
+  static_assert(ORD >= 0 && ORD < LOADS, "a tile request beyond the count the vmcnt waits are built on");
 };
 
 constexpr int KS_PAIR = 1024 + 32;                 // 2:4: LDS bytes of a pair of tokens (512 B each)
@@ -116,7 +128,8 @@ __global__ __launch_bounds__(64 * NWMAX) void k_sparse_smallm_ks(const uint32_t 
   extern __shared__ __align__(16) uint8_t xs[];       // X regions, later the partial sums
   static_assert(!(N1 && NT > 1), "1:4 runs one token group per pass");
   constexpr bool INT4 = KIND == EGT_VAL_INT4;
-  constexpr int VW = INT4 ? 1 : 4;
+  constexpr int VW = ATile<KIND, QW>::VW;
+  constexpr int LPT = ATile<KIND, QW>::LOADS;         // requests per tile: the unit of every vmcnt wait below
   constexpr bool HOLD = NT > 1;                       // A operands of a phase are kept for all token groups
   // FP16 values at 2:4: instruction k of a step takes chunk k, lane (i, kb) its 16-byte
   // piece kb, so the four lanes of a row fetch 64 contiguous bytes and what a lane
@@ -186,10 +199,13 @@ __global__ __launch_bounds__(64 * NWMAX) void k_sparse_smallm_ks(const uint32_t 
     const uint32_t lcc = (uint32_t)min((int)in_vgpr((uint32_t)lc), g.nchunks - 1 - 4 * s);  // chunk inside the step (clamped)
     const uint32_t cl = rel * (uint32_t)g.nchunks + lcc;                      // lane part of the chunk number
     const uint32_t cu = on ? (uint32_t)(16 * rt) * (uint32_t)g.nchunks + (uint32_t)(4 * s) : 0u;   // uniform part
+    (void)TileRequest<0, LPT>{};
     a.iw = __builtin_amdgcn_raw_buffer_load_b64(r_idx, on ? 8u * cl : off_range, 8u * cu, 0);
     a.qp[0] = 0;
     if (INT4) {
+      (void)TileRequest<1, LPT>{};
       a.nib[0] = __builtin_amdgcn_raw_buffer_load_b128(r_val, on ? 16u * cl : off_range, 16u * cu, 0);
+      (void)TileRequest<2, LPT>{};                    // one of the three forms below
       const uint32_t qrow_l = rel * (uint32_t)g.groups_per_row;
       const uint32_t qrow_u = on ? (uint32_t)(16 * rt) * (uint32_t)g.groups_per_row : 0u;
       if (QW == 4) {
@@ -209,10 +225,12 @@ __global__ __launch_bounds__(64 * NWMAX) void k_sparse_smallm_ks(const uint32_t 
     } else if (LINA) {
       const uint32_t vrow = (uint32_t)min((int)in_vgpr((uint32_t)i), g.rows - 1 - 16 * rt);
       const uint32_t vl = on ? 64u * vrow * (uint32_t)g.nchunks + 16u * (uint32_t)kb : off_range;
+      (void)TileRequest<VW, LPT>{};                   // requests 1 .. VW
 #pragma unroll
       for (int k = 0; k < VW; ++k)                    // chunk k of the step (clamped: uniform)
         a.nib[k] = __builtin_amdgcn_raw_buffer_load_b128(r_val, vl, on ? 64u * (cu + (uint32_t)min(k, g.nchunks - 1 - 4 * s)) : 0u, 0);
     } else {
+      (void)TileRequest<VW, LPT>{};                   // requests 1 .. VW
 #pragma unroll
       for (int k = 0; k < VW; ++k)
         a.nib[k] = __builtin_amdgcn_raw_buffer_load_b128(r_val, on ? 64u * cl + 16u * k : off_range, 64u * cu, 0);
@@ -399,18 +417,18 @@ __global__ __launch_bounds__(64 * NWMAX) void k_sparse_smallm_ks(const uint32_t 
     // that phase; it is the last one, nothing is requested in it.
     // DEEP: pending at the top of phase p are, in request order, A(p), X(p), A(p + 1)
     auto deep_phase = [&](ATile<KIND, QW> (&cur)[NIT], int p) {
-      constexpr int NA = NIT * 5;
+      constexpr int NA = NIT * LPT;
       const int step = step0 + p * nw + wave;
       u8v bx[NM];
       ATile<KIND, QW> t[NIT];
       if (p + 1 >= phases) {
         // last phase: the tiles are consumed as they arrive
-        wait_vmem<(NIT - 1) * 5>();
+        wait_vmem<(NIT - 1) * LPT>();
         zero_tail(step);
         read_b(bx);
         static_for<0, NIT>([&](auto ic) {
           constexpr int it = decltype(ic)::v;
-          if constexpr (it > 0) wait_vmem<(NIT - 1 - it) * 5>();
+          if constexpr (it > 0) wait_vmem<(NIT - 1 - it) * LPT>();
           if (it < nit) {
             ATile<KIND, QW> tl = cur[it];
             to_operand(tl);
@@ -452,14 +470,13 @@ __global__ __launch_bounds__(64 * NWMAX) void k_sparse_smallm_ks(const uint32_t 
     for (int p = 0; !DEEP && p < phases && step0 + p * nw + wave < nsteps; ++p) {
       const int step = step0 + p * nw + wave;
       const bool more = p + 1 < phases;
-      constexpr int NA = NIT * (INT4 ? 3 : 5);         // loads of the A tiles of one phase (any QW)
+      constexpr int NA = NIT * LPT;                    // loads of the A tiles of one phase (any QW)
       u8v bx[NM];
       ATile<KIND, QW> t[NIT];
       if constexpr (!HOLD) {
         if (!more) {
           // Last phase: nothing more is requested, so the tiles are consumed as they arrive
           // (loads return in request order: X first, then tile 0, 1, ...).
-          constexpr int LPT = INT4 ? 3 : 5;           // loads per tile
           wait_vmem<(NIT - 1) * LPT>();
           zero_tail(step);
           read_b(bx);
