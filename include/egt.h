@@ -208,9 +208,11 @@ egt_status egt_sparse_gemm_smallm(const egt_2bitcsr *w, const uint16_t *X, int64
  * only.  The workspace is dead after the call's kernels have run; calls that share one
  * must not overlap.
  * egt_sparse_gemm_smallm_ws_bytes (HOST): the bytes this matrix and M need; 0 where the
- * split form is not the faster one (it is for 2:4 INT4 with groups of 64 columns and more,
- * M > 16, K >= 8192 and at most 4096 rows: the down projection under verification), in
- * which case egt_sparse_gemm_smallm_ws ignores the workspace and is the one-launch call.
+ * split form is not the faster one (it is for 2:4 INT4 with groups of 64 columns and more
+ * and either M > 32 with K >= 8192 or at least 8192 rows - there the slice of X of a
+ * workgroup stays in LDS - or M > 16, K >= 8192 and at most 4096 rows: the down projection
+ * under verification), in which case egt_sparse_gemm_smallm_ws ignores the workspace and is
+ * the one-launch call.
  * EGT_ERR_SHAPE when workspace_bytes is smaller than required. */
 egt_status egt_sparse_gemm_smallm_ws_bytes(const egt_2bitcsr *w, int64_t ldx, int M, size_t *bytes);
 egt_status egt_sparse_gemm_smallm_ws(const egt_2bitcsr *w, const uint16_t *X, int64_t ldx,
@@ -227,7 +229,7 @@ egt_status egt_sparse_gemm_smallm_ws(const egt_2bitcsr *w, const uint16_t *X, in
  * calls on one GPU share that buffer: calls that overlap on one GPU (two streams, two
  * threads) race, whoever makes them must order them.  Results equal
  * egt_sparse_gemm_smallm_ws's bit for bit. */
-#define EGT_STATIC_SCRATCH_BYTES (4u << 20) /* four slices of 64 tokens x 4096 rows of FP32 */
+#define EGT_STATIC_SCRATCH_BYTES (16u << 20) /* 64 tokens: eleven slices x 4096 rows or four slices x 11008 rows of FP32 */
 egt_status egt_sparse_gemm_smallm_static(const egt_2bitcsr *w, const uint16_t *X, int64_t ldx,
                                          uint16_t *Y, int64_t ldy, int M, void *stream);
 

@@ -708,10 +708,23 @@ static int smallm_slices(const egt_2bitcsr &w, int M, int &row_blocks) {
   return s;
 }
 
+// the form with X held still in LDS (egt_mfma_smallm_xs.hip)
+size_t sparse_smallm_xs_bytes(const egt_2bitcsr &w, int64_t ldx, int M, bool force);
+hipError_t launch_sparse_smallm_xs(const egt_2bitcsr &w, const uint16_t *X, int64_t ldx, uint16_t *Y, int64_t ldy, int M,
+                                   float *ws, bool force, hipStream_t stream);
+static bool use_xs(const egt_2bitcsr &w, int64_t ldx, int M, size_t &bytes, bool &force) {
+  force = tune_flag("EGT_SM_XS");                     // developer build: wherever the form applies
+  if (tune_flag("EGT_SM_NOXS")) return false;
+  bytes = sparse_smallm_xs_bytes(w, ldx, M, force);
+  return bytes != 0;
+}
+
 bool sparse_smallm_split_bytes(const egt_2bitcsr &w, int64_t ldx, int M, size_t &bytes) {
   int row_blocks;
   bytes = 0;
   if (!sparse_smallm_supported(w, ldx, M)) return false;
+  bool force;
+  if (use_xs(w, ldx, M, bytes, force)) return true;
   const int s = smallm_slices(w, M, row_blocks);
   if (s < 2) return false;
   bytes = sizeof(float) * (size_t)s * (size_t)M * (size_t)w.rows;
@@ -721,6 +734,11 @@ bool sparse_smallm_split_bytes(const egt_2bitcsr &w, int64_t ldx, int M, size_t 
 hipError_t launch_sparse_smallm_split(const egt_2bitcsr &w, const uint16_t *X, int64_t ldx, uint16_t *Y, int64_t ldy, int M,
                                       float *ws, hipStream_t stream) {
   if (w.rows == 0) return hipSuccess;
+  {
+    size_t xs_bytes;
+    bool force;
+    if (use_xs(w, ldx, M, xs_bytes, force)) return launch_sparse_smallm_xs(w, X, ldx, Y, ldy, M, ws, force, stream);
+  }
   SmallMKsGeom g;
   int qw, row_blocks;
   smallm_geometry(w, ldx, Y, ldy, M, g, qw);

@@ -10,7 +10,8 @@
 //   EGT_SM_TUNE=waves,blocks_per_cu   small M     EGT_READ_TUNE=unroll,blocks_per_cu  streaming read
 //   EGT_STACK_TUNE=waves,tpi_mode  EGT_STREAM_TUNE=force,blocks_per_cu  EGT_STREAM_WAVES=waves  EGT_STREAM_ITEM=kilobytes
 //   EGT_SM_KS=slices,row_blocks    (multi-matrix launches; K split at small M)
-//   EGT_NO_M1T, EGT_M1_NOLIN, EGT_M1N1_NOLIN, EGT_M1_NOONE   (set = that path is not used)
+//   EGT_NO_M1T, EGT_M1_NOLIN, EGT_M1N1_NOLIN, EGT_M1_NOONE, EGT_M1_NOEVEN, EGT_SM_NOXS   (set = that path is not used)
+//   EGT_SM_XS   (set = the small-M form with X held in LDS wherever it applies, not only where it is the faster one)
 #ifndef EGT_TUNE_H
 #define EGT_TUNE_H
 

@@ -434,7 +434,8 @@ def test_config5_smallm_full_size(rows, cols, M):
     G.assert_close(y0[pick], Y_ref[0], A_ref[0], "row 0 as a GEMV")
 
 
-@pytest.mark.parametrize("rows,cols,M", [(4096, 11008, 64), (4096, 11008, 17), (2000, 8192, 33), (500, 12288, 40), (16, 8192, 64)])
+@pytest.mark.parametrize("rows,cols,M", [(4096, 11008, 64), (4096, 11008, 17), (2000, 8192, 33), (500, 12288, 40), (16, 8192, 64),
+                                         (11008, 4096, 64), (11008, 4096, 49), (4096, 11008, 32), (9000, 2048, 64), (8193, 1536, 33)])
 def test_smallm_split_over_k_with_a_workspace(rows, cols, M):
     # K split over workgroups, FP32 partial sums through a caller-provided workspace: sampled
     # rows against the oracle, every output close to the one-launch kernel's (same products,
@@ -446,7 +447,7 @@ def test_smallm_split_over_k_with_a_workspace(rows, cols, M):
     X = synth.activation_rows(M, cols, 5200 + M)
     pd = p.to("cuda")
     need = B.smallm_ws_bytes(pd, M)
-    assert need == 4 * 4 * M * rows                      # four slices of FP32 partial sums
+    assert need >= 2 * 4 * M * rows                      # at least two slices of FP32 partial sums
     ws = torch.full((need + 4096,), 0x5A, dtype=torch.uint8, device="cuda")
     Xd = G.to_dev(X.view(np.uint16)).view(torch.float16)
     Ybuf = torch.full((M + 2, rows + 8), G.CANARY, dtype=torch.int16, device="cuda")
@@ -493,7 +494,7 @@ def test_smallm_split_over_k_with_a_workspace(rows, cols, M):
 
 def test_smallm_workspace_not_needed_where_the_split_does_not_pay():
     torch = G.torch_mod()
-    for rows, cols, n, g, kind, M in ((11008, 4096, 2, 128, 0, 64), (4096, 11008, 2, 128, 0, 16), (300, 8192, 1, 128, 0, 40),
+    for rows, cols, n, g, kind, M in ((11008, 4096, 2, 128, 0, 32), (4096, 4096, 2, 128, 0, 64), (4096, 11008, 2, 128, 0, 16), (300, 8192, 1, 128, 0, 40),
                                       (300, 8192, 2, 0, 1, 40), (300, 8192, 2, 32, 0, 40)):
         p = B.Packed(rows, cols, n, g, kind, None, None, None, None)
         assert B.smallm_ws_bytes(p, M) == 0

@@ -559,10 +559,17 @@ def test_smallm_workspace_size_query():
     L = B.lib()
     out = ctypes.c_size_t(7)
     down = B.View(4096, 11008, 2, 128, 0, 16, 16, 16, 16)
-    assert L.egt_sparse_gemm_smallm_ws_bytes(ctypes.byref(down), 11008, 64, ctypes.byref(out)) == 0 and out.value == 4 * 4 * 64 * 4096
+    # 64 tokens, K = 11008: X held in LDS, 43 steps in 11 slices, 16 x 16 FP32 sums per (slice, row tile, token group)
+    assert L.egt_sparse_gemm_smallm_ws_bytes(ctypes.byref(down), 11008, 64, ctypes.byref(out)) == 0 and out.value == 11 * 256 * 4 * 1024
+    # 17..32 tokens there: four slices of K, X fetched per workgroup, partial sums per token and row
+    assert L.egt_sparse_gemm_smallm_ws_bytes(ctypes.byref(down), 11008, 32, ctypes.byref(out)) == 0 and out.value == 4 * 4 * 32 * 4096
     assert L.egt_sparse_gemm_smallm_ws_bytes(ctypes.byref(down), 11008, 16, ctypes.byref(out)) == 0 and out.value == 0
     gate = B.View(11008, 4096, 2, 128, 0, 16, 16, 16, 16)
-    assert L.egt_sparse_gemm_smallm_ws_bytes(ctypes.byref(gate), 4096, 64, ctypes.byref(out)) == 0 and out.value == 0
+    assert L.egt_sparse_gemm_smallm_ws_bytes(ctypes.byref(gate), 4096, 64, ctypes.byref(out)) == 0 and out.value == 4 * 688 * 4 * 1024
+    assert L.egt_sparse_gemm_smallm_ws_bytes(ctypes.byref(gate), 4096, 32, ctypes.byref(out)) == 0 and out.value == 0
+    assert L.egt_sparse_gemm_smallm_ws_bytes(ctypes.byref(gate), 4100, 64, ctypes.byref(out)) == 0 and out.value == 0   # rows of X not on 16 bytes
+    square = B.View(4096, 4096, 2, 128, 0, 16, 16, 16, 16)
+    assert L.egt_sparse_gemm_smallm_ws_bytes(ctypes.byref(square), 4096, 64, ctypes.byref(out)) == 0 and out.value == 0
     assert L.egt_sparse_gemm_smallm_ws_bytes(ctypes.byref(down), 11008, 65, ctypes.byref(out)) == 2
     assert L.egt_sparse_gemm_smallm_ws_bytes(ctypes.byref(down), 100, 64, ctypes.byref(out)) == 2
     assert L.egt_sparse_gemm_smallm_ws_bytes(ctypes.byref(down), 11008, 64, None) == 1

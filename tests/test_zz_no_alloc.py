@@ -14,13 +14,13 @@ def test_static_scratch_entry_point_equals_the_workspace_form():
     # the first call's contents and the second result must not depend on them
     torch = G.torch_mod()
     outs = []
-    for rows, cols, M in ((4096, 11008, 64), (2000, 8192, 33)):
+    for rows, cols, M in ((4096, 11008, 64), (2000, 8192, 33), (4096, 11008, 24)):
         print(f"case static scratch {rows}x{cols} M={M}", flush=True)
         w = synth.weights(rows, cols, 6100 + rows)
         p = B.pack_2bitcsr(w, B.prune_n4(w, 2), 2, 128, 0).to("cuda")
         X = G.to_dev(synth.activation_rows(M, cols, 6100 + M).view(np.uint16)).view(torch.float16)
         need = B.smallm_ws_bytes(p, M)
-        assert 0 < need <= (4 << 20)
+        assert 0 < need <= (16 << 20)
         ws = torch.empty(need, dtype=torch.uint8, device="cuda")
         Y_ws = torch.zeros((M, rows), dtype=torch.float16, device="cuda")
         Ybuf = torch.full((M + 2, rows), G.CANARY, dtype=torch.int16, device="cuda")
@@ -35,6 +35,9 @@ def test_static_scratch_entry_point_equals_the_workspace_form():
         assert np.all(host[0] == G.CANARY) and np.all(host[M + 1] == G.CANARY)
         assert np.array_equal(host[1:M + 1], Y_ws.cpu().numpy().view(np.uint16)), (rows, cols, M)
         outs.append(host[1:M + 1].copy())
-    assert np.isfinite(outs[0].view(np.float16)).all() and np.isfinite(outs[1].view(np.float16)).all()
-    # the largest request of the split form (64 tokens, 4096 rows, four slices) is what the buffer holds
-    assert B.smallm_ws_bytes(B.Packed(4096, 32768, 2, 128, 0, None, None, None, None), 64) == 4 << 20
+    assert all(np.isfinite(o.view(np.float16)).all() for o in outs)
+    # a request beyond the built-in buffer is refused on the host, before anything is launched
+    big = B.Packed(4096, 32768, 2, 128, 0, None, None, None, None)
+    assert B.smallm_ws_bytes(big, 64) > 16 << 20
+    v = B.View(4096, 32768, 2, 128, 0, 16, 16, 16, 16)    # fake aligned pointers: never used
+    assert B.lib().egt_sparse_gemm_smallm_static(__import__("ctypes").byref(v), 16, 32768, 16, 4096, 64, None) == 6
