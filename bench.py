@@ -459,39 +459,73 @@ def table(torch, B, synth, timer, dev, w, mask, xd, ys, calls, packed):
     t["sparse_int4_rows_half_1to4_11008x4096"] = entry(timer(lambda i: fr[i % cr](), 200), rag_bytes)
     t["sparse_int4_rows_half_1to4_11008x4096"]["bytes_saved_vs_2to4"] = packed_bytes_24 - pr.nbytes()
     del pkr, fr
-    # config 5: small M on both shapes; the M-sweep of one all-2:4 layer (q/k/v/o, gate/up,
-    # down) feeds the trigger cost model of Sec. 3.4: verification ~ a + b*M, AR step = t(1)
-    sweep_m = (1, 2, 4, 8, 16, 32, 64)
+    # config 5: small M on both shapes; the M-sweep (every M from 1 to 64) of an all-2:4 layer
+    # (q/k/v/o, gate/up, down) feeds the trigger cost model of Sec. 3.4: verification ~ a + b*M,
+    # AR step = t(1).  The workspace form is used wherever the library says it is the faster one.
+    sweep_m = tuple(range(1, 65))
     layer_us = {m: 0.0 for m in sweep_m}
+    pools, split_wins = {}, set()
     for (r5, k5, mi, reps) in ((11008, 4096, 0, 2), (4096, 11008, 1, 1), (4096, 4096, 2, 4)):
         w5 = synth.weights(r5, k5, synth.seed_for(5, mi))
         p5 = B.pack_2bitcsr(w5, B.prune_n4(w5, 2), 2, 128, B.VAL_INT4)
         c5 = max(2, -(-2 * LLC_BYTES // p5.nbytes()))
         pk5 = [p5.to(dev) for _ in range(c5)]
+        pools[mi] = (r5, k5, reps, pk5)
         for M in sweep_m:
             X = up16(synth.activation_rows(M, k5, 5))
             Y = torch.empty((M, r5), dtype=torch.float16, device=dev)
+            listed = mi < 2 and M in (1, 4, 16, 64)
+            steps5 = 300 if listed or M in (2, 8, 32) else 60
             f5 = [B.prepared_sparse_gemm_smallm(pk5[i], X, Y) for i in range(c5)]
-            t5 = timer(lambda i: f5[i % c5](), 300)
-            layer_us[M] += reps * t5["median"] * 1e6
-            if mi < 2 and M in (1, 4, 16, 64):
+            t5 = timer(lambda i: f5[i % c5](), steps5)
+            best = t5["median"]
+            if listed:
                 t[f"config5_{r5}x{k5}_M{M}"] = entry(t5, algorithmic_bytes(r5, k5, 2, 128, 0, M), flops=2 * M * r5 * k5 / 2)
             need = B.smallm_ws_bytes(pk5[0], M)
-            if mi < 2 and need:                       # K split over workgroups, partial sums in a caller's workspace
+            if need:                                  # K split over workgroups, partial sums in a caller's workspace
                 ws = torch.empty(need, dtype=torch.uint8, device=dev)
                 f5w = [B.prepared_sparse_gemm_smallm_ws(pk5[i], X, Y, ws) for i in range(c5)]
-                t[f"config5_{r5}x{k5}_M{M}_k_split_workspace"] = entry(
-                    timer(lambda i: f5w[i % c5](), 300), algorithmic_bytes(r5, k5, 2, 128, 0, M), flops=2 * M * r5 * k5 / 2)
+                t5w = timer(lambda i: f5w[i % c5](), steps5)
+                if t5w["median"] < best:
+                    best = t5w["median"]
+                    split_wins.add((mi, M))
+                if mi < 2 and M in (32, 48, 64):
+                    t[f"config5_{r5}x{k5}_M{M}_k_split_workspace"] = entry(
+                        t5w, algorithmic_bytes(r5, k5, 2, 128, 0, M), flops=2 * M * r5 * k5 / 2)
                 del f5w, ws
-        del pk5
+            layer_us[M] += reps * best * 1e6
     fit_a, fit_b = B.fit_verify_cost(list(sweep_m[1:]), [layer_us[m] for m in sweep_m[1:]])
     cand = [64, 24, 9, 4, 2, 1]                      # candidates left per trie depth (wide top, narrow bottom)
     rem = [6, 5, 4, 3, 2, 1]                         # tokens still to generate (average ID length 6)
     depth, gain = B.trigger_depth(layer_us[1], fit_a, fit_b, cand, rem)
-    t["trigger_model"] = {"layer_us_by_M": {str(m): round(v, 2) for m, v in layer_us.items()},
+    # the same products in layer order through a 32-layer all-2:4 stack (224 launches per pass)
+    stack_pass = {}
+    for M in (1, 16, 64):
+        seq = []
+        for layer in range(32):
+            for mi in (2, 2, 2, 2, 0, 0, 1):          # q, k, v, o, gate, up, down
+                r5, k5, _, pk5 = pools[mi]
+                X = up16(synth.activation_rows(M, k5, 5))
+                Y = torch.empty((M, r5), dtype=torch.float16, device=dev)
+                pk = pk5[(layer * 7 + len(seq)) % len(pk5)]
+                if (mi, M) in split_wins:
+                    ws = torch.empty(B.smallm_ws_bytes(pk, M), dtype=torch.uint8, device=dev)
+                    seq.append(B.prepared_sparse_gemm_smallm_ws(pk, X, Y, ws))
+                else:
+                    seq.append(B.prepared_sparse_gemm_smallm(pk, X, Y))
+
+        def run_seq(i):
+            for c in seq:
+                c()
+        stack_pass[str(M)] = round(timer(run_seq, 5, 1)["median"] * 1e6, 1)
+        del seq
+    t["trigger_model"] = {"layer_us_by_M": [round(layer_us[m], 2) for m in sweep_m], "M": [sweep_m[0], sweep_m[-1]],
+                          "stack_pass_us_224_launches_by_M": stack_pass,
+                          "stack_pass_us_32_times_layer_by_M": {str(m): round(32 * layer_us[m], 1) for m in (1, 16, 64)},
                           "fit_a_us": round(fit_a, 3), "fit_b_us_per_token": round(fit_b, 4),
                           "t_ar_us": round(layer_us[1], 2), "candidates": cand, "remaining": rem,
                           "trigger_depth": depth, "benefit_us_per_layer": round(gain, 2)}
+    del pools
     # config 4: the 32-layer stack (every layer its own seeded weights), 224 launches in
     # sequence, plain and as a HIP graph; then with q/k/v and gate/up fused (128 launches)
     del packed[:], calls[:]
