@@ -69,11 +69,7 @@ __device__ __forceinline__ void k_int4_m1_body(const uint8_t *__restrict__ q, co
   const int npieces = g.nchunks * 4;
   const int lds_pieces = multirow ? npieces : g.phases * 256;
   u4 xp[XP];
-#pragma unroll
-  for (int j = 0; j < XP; ++j) {
-    const int pi = threadIdx.x + j * blockDim.x;
-    xp[j] = *(const u4 *)(x + 8 * min(pi, npieces - 1));
-  }
+  x_request<XP>(x, npieces, xp);
 
   // ---- every load of the wave's TPI tiles: nibbles of the own chunk, and the
   //      {scale, zero} of the quad (lane & 15), whose diagonal this lane may hold
@@ -111,15 +107,7 @@ __device__ __forceinline__ void k_int4_m1_body(const uint8_t *__restrict__ q, co
 
   // ---- x through LDS: piece p at byte 16 p + 16 (p >> 4), i.e. one 16 B pad per
   //      256 B, so that lanes 256 B apart hit different banks; zero past the end
-#pragma unroll
-  for (int j = 0; j < XP; ++j) {
-    const int pi = threadIdx.x + j * blockDim.x;
-    if (pi < lds_pieces) {
-      u4 v = xp[j];
-      if (pi >= npieces) v = u4{0, 0, 0, 0};
-      *(u4 *)(xs + 16 * pi + 16 * (pi >> 4)) = v;
-    }
-  }
+  x_store<XP, 4>(xs, xp, npieces, lds_pieces);
   __syncthreads();
   // B operand: lane (n, kb) holds the activations of chunk 4 n + kb, 8 per instruction
   u4 bx[4];

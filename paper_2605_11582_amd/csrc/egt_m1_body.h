@@ -20,21 +20,6 @@
 
 namespace egt {
 
-// Eight INT4 codes of one dword (slot k in bits 4k..4k+3) -> four half2 registers
-// {slot 2p, slot 2p+1} holding s*(q - z).  Byte p of the dword carries the pair:
-// the low nibble becomes the mantissa of 1024 + q, the high nibble (left in
-// place) the mantissa of 64 + q; one packed subtract removes both offsets and z
-// exactly, one packed multiply applies the scale (a single rounding to FP16).
-__device__ __forceinline__ u4 dequant8(uint32_t d, uint32_t off, uint32_t s2, uint32_t mask, uint32_t magic) {
-  u4 r;
-#pragma unroll
-  for (int p = 0; p < 4; ++p) {
-    const uint32_t t = __builtin_amdgcn_perm(d, d, 0x0c000c00u + (uint32_t)p * 0x00010001u);
-    r[p] = pk_mul_f16(pk_sub_f16(and_or(t, mask, magic), off), s2);
-  }
-  return r;
-}
-
 // Geometry of a launch, computed on the host.
 struct M1Geom {
   int rows;
@@ -102,11 +87,7 @@ __device__ __forceinline__ void k_sparse_m1_body(const uint32_t *__restrict__ ro
 #pragma unroll
   for (int m = 0; m < MT; ++m) {
     const __half *xm = MT == 1 ? x : x + (int64_t)min(m, g.M - 1) * g.ldx;   // a token past M repeats the last one
-#pragma unroll
-    for (int j = 0; j < XP; ++j) {
-      const int pi = threadIdx.x + j * blockDim.x;
-      xp[m][j] = *(const u4 *)(xm + 8 * min(pi, npieces - 1));
-    }
+    x_request<XP>(xm, npieces, xp[m]);
   }
 
   constexpr int XSH = LIN ? 4 : 5;                    // x in LDS: one 16 B pad per 2^XSH pieces
@@ -182,17 +163,7 @@ __device__ __forceinline__ void k_sparse_m1_body(const uint32_t *__restrict__ ro
   //      apart, fall into different banks.  Pieces past the end of x are zero.
   if (!(EGT_ABLATE & 8)) {
 #pragma unroll
-    for (int m = 0; m < MT; ++m) {
-#pragma unroll
-      for (int j = 0; j < XP; ++j) {
-        const int pi = threadIdx.x + j * blockDim.x;
-        if (pi < lds_pieces) {
-          u4 v = xp[m][j];
-          if (pi >= npieces) v = u4{0, 0, 0, 0};
-          *(u4 *)(xs + m * g.xtok + 16 * pi + 16 * (pi >> XSH)) = v;
-        }
-      }
-    }
+    for (int m = 0; m < MT; ++m) x_store<XP, XSH>(xs + m * g.xtok, xp[m], npieces, lds_pieces);
     __syncthreads();
   }
   // B operand: column n = lane & 15 holds the activations of chunks 4n .. 4n+3;

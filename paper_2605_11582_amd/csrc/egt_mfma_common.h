@@ -37,6 +37,21 @@ __device__ __forceinline__ uint32_t pk_mul_f16(uint32_t a, uint32_t b) {
 __device__ __forceinline__ uint32_t and_or(uint32_t a, uint32_t mask, uint32_t magic) {
   return (a & mask) | magic;
 }
+// Eight INT4 codes of one dword (slot k in bits 4k..4k+3) -> four half2 registers
+// {slot 2p, slot 2p+1} holding s*(q - z).  Byte p of the dword carries the pair:
+// the low nibble becomes the mantissa of 1024 + q, the high nibble (left in
+// place) the mantissa of 64 + q; one packed subtract removes both offsets and z
+// exactly, one packed multiply applies the scale (a single rounding to FP16).
+__device__ __forceinline__ u4 dequant8(uint32_t d, uint32_t off, uint32_t s2, uint32_t mask, uint32_t magic) {
+  u4 r;
+#pragma unroll
+  for (int p = 0; p < 4; ++p) {
+    const uint32_t t = __builtin_amdgcn_perm(d, d, 0x0c000c00u + (uint32_t)p * 0x00010001u);
+    r[p] = pk_mul_f16(pk_sub_f16(and_or(t, mask, magic), off), s2);
+  }
+  return r;
+}
+
 // Pins a wave-uniform value into a vector register (an empty statement for the
 // assembler): with the mask in a scalar and the magic in a vector register the
 // fused and-or respects the one-scalar-operand limit of the encoding.
@@ -96,6 +111,35 @@ __device__ __forceinline__ void lds_barrier() {
   __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
   __builtin_amdgcn_s_barrier();
   __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+}
+
+// x through LDS, the two halves every row-per-wave kernel shares (Sec. 3.3 "Accelerate
+// Memory Access": the activations are fetched once per workgroup and shared, laid out so
+// that the reads do not collide on banks).  x_request: each thread asks for XP 16-byte
+// pieces (thread t: pieces t, t + blockDim, ...; a piece past the end of x repeats the last
+// one) before anything else is requested, so that x is the first data to come back.
+// x_store: piece p goes to byte 16 p + 16 (p >> XSH) of `xs` - one 16-byte pad after every
+// 2^XSH pieces, which puts the 16 lanes of a B operand read on different banks; pieces past
+// the end of x (up to lds_pieces, what the B reads may touch) are zeros.
+template <int XP>
+__device__ __forceinline__ void x_request(const __half *x, int npieces, u4 (&xp)[XP]) {
+#pragma unroll
+  for (int j = 0; j < XP; ++j) {
+    const int pi = threadIdx.x + j * blockDim.x;
+    xp[j] = *(const u4 *)(x + 8 * min(pi, npieces - 1));
+  }
+}
+template <int XP, int XSH>
+__device__ __forceinline__ void x_store(uint8_t *xs, const u4 (&xp)[XP], int npieces, int lds_pieces) {
+#pragma unroll
+  for (int j = 0; j < XP; ++j) {
+    const int pi = threadIdx.x + j * blockDim.x;
+    if (pi < lds_pieces) {
+      u4 v = xp[j];
+      if (pi >= npieces) v = u4{0, 0, 0, 0};
+      *(u4 *)(xs + 16 * pi + 16 * (pi >> XSH)) = v;
+    }
+  }
 }
 
 // Block shape of a launch of one of the M = 1 kernels, derived on the host from the matrix

@@ -46,16 +46,6 @@
 
 namespace egt {
 
-__device__ __forceinline__ u4 dequant8_sm(uint32_t d, uint32_t off, uint32_t s2, uint32_t mask, uint32_t magic) {
-  u4 r;
-#pragma unroll
-  for (int p = 0; p < 4; ++p) {
-    const uint32_t t = __builtin_amdgcn_perm(d, d, 0x0c000c00u + (uint32_t)p * 0x00010001u);
-    r[p] = pk_mul_f16(pk_sub_f16(and_or(t, mask, magic), off), s2);
-  }
-  return r;
-}
-
 struct SmallMKsGeom {
   int rows, M;
   int nchunks;         // cols / 64 (2:4) or cols / 128 (1:4)
@@ -376,7 +366,7 @@ __global__ __launch_bounds__(64 * NWMAX) void k_sparse_smallm_ks(const uint32_t 
       iwv[NM / 2 - 1] = t.iw[1];
 #pragma unroll
       for (int d = 0; d < NM; ++d) {
-        if constexpr (INT4) av[d] = dequant8_sm(t.nib[0][d & 3], off[(d & 3) * QW / 4], s2[(d & 3) * QW / 4], g.nib_mask, magic);
+        if constexpr (INT4) av[d] = dequant8(t.nib[0][d & 3], off[(d & 3) * QW / 4], s2[(d & 3) * QW / 4], g.nib_mask, magic);
         else av[d] = live ? t.nib[d & 3] : u4{0, 0, 0, 0};
       }
     }

@@ -189,13 +189,7 @@ __global__ __launch_bounds__(512) void k_smallm_xs(const uint32_t *__restrict__ 
           const uint32_t s2 = __builtin_amdgcn_perm(qp, qp, 0x01000100u);
           const uint32_t off = pk_add_f16(__builtin_amdgcn_perm(qp, qp, 0x03020302u), g.nib_magic);
 #pragma unroll
-          for (int d = 0; d < 4; ++d) {
-#pragma unroll
-            for (int p = 0; p < 4; ++p) {
-              const uint32_t t2 = __builtin_amdgcn_perm(nib[d], nib[d], 0x0c000c00u + (uint32_t)p * 0x00010001u);
-              av[k][d][p] = pk_mul_f16(pk_sub_f16(and_or(t2, g.nib_mask, magic), off), s2);
-            }
-          }
+          for (int d = 0; d < 4; ++d) av[k][d] = dequant8(nib[d], off, s2, g.nib_mask, magic);
         }
 #pragma unroll
         for (int m = 0; m < 4; ++m) {

@@ -58,11 +58,7 @@ __device__ __forceinline__ void k_sparse_m1_n1_body(const uint32_t *__restrict__
   constexpr int XSH = LIN ? 4 : 6;                    // x in LDS: one 16 B pad per 2^XSH pieces
   const int lds_pieces = LIN ? g.phases * NI * 256 : multirow ? npieces : g.phases * 1024;
   u4 xp[XP];
-#pragma unroll
-  for (int j = 0; j < XP; ++j) {
-    const int pi = threadIdx.x + j * blockDim.x;
-    xp[j] = *(const u4 *)(x + 8 * min(pi, npieces - 1));
-  }
+  x_request<XP>(x, npieces, xp);
 
   const int tile0 = (blockIdx.x * wpp + wslot) * TPI;
   // several tiles per row: the threads that add the phases up at the end fetch the row
@@ -131,15 +127,7 @@ __device__ __forceinline__ void k_sparse_m1_n1_body(const uint32_t *__restrict__
 
   // ---- x through LDS: piece p at byte 16 p + 16 (p >> 6), one 16 B pad per KiB (the
   //      16 lanes of a B read are 1 KiB apart); zero past the end of x
-#pragma unroll
-  for (int j = 0; j < XP; ++j) {
-    const int pi = threadIdx.x + j * blockDim.x;
-    if (pi < lds_pieces) {
-      u4 v = xp[j];
-      if (pi >= npieces) v = u4{0, 0, 0, 0};
-      *(u4 *)(xs + 16 * pi + 16 * (pi >> XSH)) = v;
-    }
-  }
+  x_store<XP, XSH>(xs, xp, npieces, lds_pieces);
   __syncthreads();
   // B operand of instruction m: the 16 dense columns 16 m .. 16 m + 15 of each chunk
   u8v bx[8];
