@@ -57,11 +57,33 @@ import numpy as np
 
 VAL_INT4 = 0
 VAL_FP16 = 1
+VAL_INT4_PAIRED = 2      # INT4 codes in the second nibble order, see PAIRED_ORDER
+
+# Sec. 3.3 reorders what it stores so that bit operations recover it cheaply; the reading
+# taken here for the codes: inside every word of eight slots (the 32 bits of values that one
+# index word speaks for) the nibbles, from the least-significant one up, hold the slots
+# 0, 2, 4, 6, 1, 3, 5, 7.  Then `word & 0x000F000F` is the slot pair (0, 1), `word & 0x00F000F0`
+# the pair (2, 3), and the same masks on `word >> 8` give (4, 5) and (6, 7).
+PAIRED_ORDER = (0, 2, 4, 6, 1, 3, 5, 7)
 
 
 # --------------------------------------------------------------------------
 # helpers
 # --------------------------------------------------------------------------
+def _is_int4(val_kind: int) -> bool:
+    return val_kind in (VAL_INT4, VAL_INT4_PAIRED)
+
+
+def _code_position(t, val_kind: int):
+    """Byte index and bit shift of the code of global slot t (array or scalar)."""
+    t = np.asarray(t, dtype=np.int64)
+    if val_kind == VAL_INT4_PAIRED:
+        nibble_of_slot = np.argsort(np.array(PAIRED_ORDER))      # slot j of a word -> its nibble
+        pos = nibble_of_slot[t & 7]
+        return 4 * (t >> 3) + (pos >> 1), 4 * (pos & 1)
+    return t >> 1, 4 * (t & 1)
+
+
 def _as_f16(w) -> np.ndarray:
     w = np.asarray(w)
     if w.dtype == np.uint16:
@@ -79,7 +101,7 @@ def check_shape(rows: int, cols: int, n_keep: int, group: int, val_kind: int) ->
         raise ValueError("cols must be a multiple of 32")
     if n_keep not in (1, 2, 3, 4):
         raise ValueError("n_keep must be 1..4")
-    if val_kind == VAL_INT4:
+    if val_kind in (VAL_INT4, VAL_INT4_PAIRED):
         if group <= 0 or group % 4 != 0 or cols % group != 0:
             raise ValueError("group must be a positive multiple of 4 dividing cols")
     elif val_kind == VAL_FP16:
@@ -273,8 +295,10 @@ def pack_2bitcsr(w, mask, n_keep: int, group: int, val_kind: int, row_group=None
     v_slot = w.astype(np.float64)[rows, col]
     q = np.where(slot_kept, quant_codes(v_slot, s_slot, z_slot), z_slot).astype(np.uint8)
 
+    if val_kind == VAL_INT4_PAIRED:                        # nibble k of a word of eight slots holds slot PAIRED_ORDER[k]
+        q = q.reshape(-1, 8)[:, list(PAIRED_ORDER)]
     qf = q.reshape(-1, 2)
-    out["values"] = (qf[:, 0] | (qf[:, 1] << 4)).astype(np.uint8)   # even slot = low nibble
+    out["values"] = (qf[:, 0] | (qf[:, 1] << 4)).astype(np.uint8)   # first of a pair = low nibble
     qp = np.empty((R, G, 2), dtype=np.uint16)
     qp[:, :, 0] = s16.view(np.uint16)
     qp[:, :, 1] = z.astype(np.float16).view(np.uint16)
@@ -301,8 +325,8 @@ def decode_2bitcsr(p: dict):
     if p["val_kind"] == VAL_FP16:
         bits = p["values"].view(np.uint16)[t]
         return col, bits.view(np.float16).astype(np.float64), bits
-    byte = p["values"].astype(np.int64)[t >> 1]
-    q = (byte >> (4 * (t & 1))) & 15
+    where, shift = _code_position(t, p["val_kind"])
+    q = (p["values"].astype(np.int64)[where] >> shift) & 15
     qp = p["qparams"]
     s = qp[:, :, 0].view(np.float16).astype(np.float64)
     z = qp[:, :, 1].view(np.float16).astype(np.float64)
@@ -386,12 +410,12 @@ def pack_2bitcsr_rows(w, mask, row_n_keep, group: int, val_kind: int) -> dict:
         one = pack_2bitcsr(w[r:r + 1], mask[r:r + 1], int(nk[r]), group, val_kind)
         values.append(one["values"])
         idx.append(one["idx"])
-        if val_kind == VAL_INT4:
+        if _is_int4(val_kind):
             qparams.append(one["qparams"])
     cat = lambda parts, dt: np.concatenate(parts) if parts else np.zeros(0, dtype=dt)
     return dict(rows=R, cols=K, n_keep=0, row_n_keep=nk.astype(np.int32), group=group, val_kind=val_kind,
                 row_ptr=row_ptr.astype(np.uint32), values=cat(values, np.uint8), idx=cat(idx, np.uint16),
-                qparams=(cat(qparams, np.uint16).reshape(R, K // group, 2) if val_kind == VAL_INT4 else None),
+                qparams=(cat(qparams, np.uint16).reshape(R, K // group, 2) if _is_int4(val_kind) else None),
                 total_slots=int(row_ptr[-1]))
 
 
@@ -409,7 +433,8 @@ def decode_row(p: dict, r: int):
     col = 4 * (np.arange(S, dtype=np.int64) // n) + offs
     if p["val_kind"] == VAL_FP16:
         return col, p["values"].view(np.uint16)[t].view(np.float16).astype(np.float64)
-    q = (p["values"].astype(np.int64)[t >> 1] >> (4 * (t & 1))) & 15
+    where, shift = _code_position(t, p["val_kind"])
+    q = (p["values"].astype(np.int64)[where] >> shift) & 15
     s = p["qparams"][r, :, 0].view(np.float16).astype(np.float64)
     z = p["qparams"][r, :, 1].view(np.float16).astype(np.float64)
     return col, s[col // g] * (q.astype(np.float64) - z[col // g])
@@ -457,8 +482,8 @@ def buffer_sizes_rows(cols: int, row_n_keep, group: int, val_kind: int):
     nk = np.asarray(row_n_keep, dtype=np.int64)
     T = int(nk.sum()) * (cols // 4)
     R = len(nk)
-    return (4 * (R + 1), T // 2 if val_kind == VAL_INT4 else 2 * T, T // 4,
-            4 * R * (cols // group) if val_kind == VAL_INT4 else 0)
+    return (4 * (R + 1), T // 2 if _is_int4(val_kind) else 2 * T, T // 4,
+            4 * R * (cols // group) if _is_int4(val_kind) else 0)
 
 
 # --------------------------------------------------------------------------
@@ -513,9 +538,9 @@ def buffer_sizes(rows: int, cols: int, n_keep: int, group: int, val_kind: int):
     check_shape(rows, cols, n_keep, group, val_kind)
     slots = rows * n_keep * cols // 4
     b_row = 4 * (rows + 1)
-    b_val = slots // 2 if val_kind == VAL_INT4 else 2 * slots
+    b_val = slots // 2 if _is_int4(val_kind) else 2 * slots
     b_idx = 2 * (slots // 8)
-    b_qp = 4 * rows * (cols // group) if val_kind == VAL_INT4 else 0
+    b_qp = 4 * rows * (cols // group) if _is_int4(val_kind) else 0
     return b_row, b_val, b_idx, b_qp
 
 

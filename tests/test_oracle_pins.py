@@ -597,3 +597,43 @@ def test_ragged_errors():
     p["row_ptr"][1] += 4
     with pytest.raises(ValueError):
         O.decode_row(p, 1)
+
+
+# ----------------------------------------------------------------- paired nibble order
+def test_handworked_paired_bytes_and_the_mask_property():
+    fx, w, mask = _fixture()
+    p = O.pack_2bitcsr(w, mask, 2, 32, O.VAL_INT4_PAIRED)
+    c = O.pack_2bitcsr(w, mask, 2, 32, O.VAL_INT4)
+    assert [int(v, 16) for v in fx["value_bytes_paired"]] == p["values"].tolist()
+    assert np.array_equal(p["idx"], c["idx"]) and np.array_equal(p["qparams"], c["qparams"]) and np.array_equal(p["row_ptr"], c["row_ptr"])
+    # what the order is for: two masks on the word and on the word >> 8 give the slot pairs (2j, 2j+1)
+    q = [int(v) for v in fx["q"]]
+    for wi, word in enumerate(p["values"].view("<u4").tolist()):
+        pairs = [word & 0x000F000F, (word & 0x00F000F0) >> 4, (word >> 8) & 0x000F000F, ((word >> 8) & 0x00F000F0) >> 4]
+        for j, pr in enumerate(pairs):
+            assert (pr & 0xF, pr >> 16) == (q[8 * wi + 2 * j], q[8 * wi + 2 * j + 1])
+    col_p, w_p, q_p = O.decode_2bitcsr(p)
+    col_c, w_c, q_c = O.decode_2bitcsr(c)
+    assert np.array_equal(col_p, col_c) and np.array_equal(w_p, w_c) and np.array_equal(q_p, q_c)
+    x = np.arange(1, 33).astype(np.float16)
+    assert O.gemv(p, x)[0][0] == float(fx["y"][0])
+
+
+@pytest.mark.parametrize("n,g", [(2, 128), (1, 32), (3, 16), (4, 64)])
+def test_paired_order_is_a_permutation_of_the_canonical_codes(n, g):
+    R, K = 12, 256
+    w = _rand_w(R, K, 140 + n)
+    mask = O.prune_n4_magnitude(w, n)
+    mask[2, 8:16] = 0
+    p = O.pack_2bitcsr(w, mask, n, g, O.VAL_INT4_PAIRED)
+    c = O.pack_2bitcsr(w, mask, n, g, O.VAL_INT4)
+    assert O.buffer_sizes(R, K, n, g, O.VAL_INT4_PAIRED) == O.buffer_sizes(R, K, n, g, O.VAL_INT4)
+    # nibble k of every word of the canonical bytes is slot k; of the paired bytes slot (0,2,4,6,1,3,5,7)[k]
+    nib = lambda b: np.stack([b & 15, b >> 4], axis=1).reshape(-1, 8)
+    assert np.array_equal(nib(p["values"]), nib(c["values"])[:, [0, 2, 4, 6, 1, 3, 5, 7]])
+    assert np.array_equal(O.dense_from_packed(p), O.dense_from_packed(c))
+    x = _rand_x(K, 141)
+    assert np.array_equal(O.gemv(p, x)[0], O.gemv(c, x)[0])
+    pr = O.pack_2bitcsr_rows(w[:4], O.prune_n4_magnitude(w[:4], 1), [1, 1, 1, 1], g, O.VAL_INT4_PAIRED)
+    assert np.array_equal(O.dense_from_packed_rows(pr),
+                          O.dense_from_packed(O.pack_2bitcsr(w[:4], O.prune_n4_magnitude(w[:4], 1), 1, g, O.VAL_INT4)))
