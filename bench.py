@@ -412,6 +412,14 @@ def table(torch, B, synth, timer, dev, w, mask, xd, ys, calls, packed):
     up16 = lambda a: torch.from_numpy(a.view(np.int16)).to(dev).view(torch.float16)
     # the headline launch on one copy only (weights stay in the last-level cache)
     t["headline_hot_cache"] = entry(timer(lambda i: calls[0](), 1000), algorithmic_bytes(R, K, N, GRP, 0))
+    # the headline matrix with its codes in the paired nibble order (one shift and four and-ors
+    # per eight codes instead of four byte permutes and four and-ors)
+    pp = B.pack_2bitcsr(w, mask, N, GRP, B.VAL_INT4_PAIRED)
+    cpp = len(packed)
+    pkp = [pp.to(dev) for _ in range(cpp)]
+    fp = [B.prepared_sparse_gemv(pkp[i], xd, ys[i]) for i in range(cpp)]
+    t["headline_paired_nibble_order"] = entry(timer(lambda i: fp[i % cpp](), 1000), algorithmic_bytes(R, K, N, GRP, 0))
+    del pkp, fp
     # config 1: 1024 x 1024, launch-bound
     w1 = synth.weights(1024, 1024, synth.seed_for(1))
     p1 = B.pack_2bitcsr(w1, B.prune_n4(w1, 2), 2, 128, B.VAL_INT4)

@@ -77,7 +77,17 @@ typedef enum {
   EGT_ERR_HIP = 7          /* the HIP runtime reported an error at launch                 */
 } egt_status;
 
-typedef enum { EGT_VAL_INT4 = 0, EGT_VAL_FP16 = 1 } egt_val_kind;
+/* EGT_VAL_INT4_PAIRED: INT4 values in a second nibble order (Sec. 3.3 reorders what it
+ * stores so that plain bit operations recover it; this is that idea applied to the codes).
+ * Inside every word of eight slots - the 32 bits of values that one index word speaks for -
+ * slot j sits in nibble (j >> 1) + 4 (j & 1): the nibbles of the word, from the low bits,
+ * hold the slots 0, 2, 4, 6, 1, 3, 5, 7, so that `word & 0x000F000F` is the slot pair (0, 1),
+ * `word & 0x00F000F0` the pair (2, 3), and the same two masks on `word >> 8` the pairs
+ * (4, 5) and (6, 7): the pairs a matrix-core operand register wants, without a byte
+ * permute.  Everything else (index words, parameters, sizes, row pointers) is as for
+ * EGT_VAL_INT4.  The M = 1 kernels for 2:4 with groups of 128 columns and more are tuned
+ * for it; every other call takes it through the slot-by-slot kernels. */
+typedef enum { EGT_VAL_INT4 = 0, EGT_VAL_FP16 = 1, EGT_VAL_INT4_PAIRED = 2 } egt_val_kind;
 
 /* A view of one matrix in 2bit-CSR.  The struct itself lives in host memory.
  * Its pointer fields are host pointers for pack/unpack and device pointers for

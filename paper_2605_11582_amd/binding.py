@@ -19,6 +19,7 @@ LIB_PATH = os.environ.get("EGT_LIBRARY") or os.path.join(_PKG, "libegt.so")
 
 VAL_INT4 = 0
 VAL_FP16 = 1
+VAL_INT4_PAIRED = 2       # INT4 codes in the paired nibble order (egt.h)
 
 SYMBOLS = (
     "egt_status_str", "egt_last_hip_error", "egt_2bitcsr_sizes", "egt_prune_n4", "egt_pack_2bitcsr",
@@ -216,7 +217,7 @@ class Packed:
     def sizes(self):
         """Bytes of (row_ptr, values, idx, qparams) the view speaks for."""
         if self.n_keep == 0:                             # total_slots is what the kernels trust
-            T, int4 = self.total_slots, self.val_kind == VAL_INT4
+            T, int4 = self.total_slots, self.val_kind != VAL_FP16
             return (4 * (self.rows + 1), T // 2 if int4 else 2 * T, T // 4,
                     4 * self.rows * (self.cols // self.group) if int4 else 0)
         return sizes(self.rows, self.cols, self.n_keep, self.group, self.val_kind)
@@ -246,7 +247,7 @@ def pack_2bitcsr(w: np.ndarray, mask: np.ndarray, n_keep: int, group: int, val_k
     row_ptr = np.empty(b[0] // 4, dtype=np.uint32)
     values = np.empty(b[1], dtype=np.uint8)
     idx = np.empty(b[2] // 2, dtype=np.uint16)
-    qparams = np.empty((rows, cols // group, 2), dtype=np.uint16) if val_kind == VAL_INT4 else None
+    qparams = np.empty((rows, cols // group, 2), dtype=np.uint16) if val_kind != VAL_FP16 else None
     p = Packed(rows, cols, n_keep, group, val_kind, row_ptr, values, idx, qparams)
     v = p.view()
     if row_group is None:
@@ -282,7 +283,7 @@ def pack_2bitcsr_rows(w: np.ndarray, mask: np.ndarray, row_n_keep, group: int, v
     row_ptr = np.empty(b[0] // 4, dtype=np.uint32)
     values = np.empty(b[1], dtype=np.uint8)
     idx = np.empty(b[2] // 2, dtype=np.uint16)
-    qparams = np.empty((rows, cols // group, 2), dtype=np.uint16) if val_kind == VAL_INT4 else None
+    qparams = np.empty((rows, cols // group, 2), dtype=np.uint16) if val_kind != VAL_FP16 else None
     p = Packed(rows, cols, 0, group, val_kind, row_ptr, values, idx, qparams, 0, nk)
     v = p.view()
     _check(lib().egt_pack_2bitcsr_rows(_np_ptr(w), _ld(w), _np_ptr(mask), _ld(mask), rows, cols, _np_ptr(nk),

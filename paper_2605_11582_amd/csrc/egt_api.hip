@@ -16,7 +16,7 @@ egt_status check_view(const egt_2bitcsr *w, bool pointers = true) {
   // n_keep == 0: rows of different lengths; the buffers hold total_slots whole index words
   if (w->n_keep == 0 && (w->total_slots % 8 != 0 || (uint64_t)w->total_slots > (uint64_t)w->rows * (uint64_t)w->cols))
     return EGT_ERR_SHAPE;
-  if (w->val_kind == EGT_VAL_INT4) {
+  if (w->val_kind == EGT_VAL_INT4 || w->val_kind == EGT_VAL_INT4_PAIRED) {
     if (w->group_size <= 0 || w->group_size % 4 != 0 || w->cols % w->group_size != 0)
       return EGT_ERR_SHAPE;
     if (pointers && !w->qparams && w->rows != 0) return EGT_ERR_NULL;

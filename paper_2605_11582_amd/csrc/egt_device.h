@@ -34,6 +34,8 @@ hipError_t launch_int4_generic(const uint8_t *q, const uint16_t *qparams, int ro
 // M = 1 kernels on the sparse matrix cores (2:4 only; see sparse_m1_supported)
 bool sparse_m1_supported(const egt_2bitcsr &w);
 hipError_t launch_sparse_m1(const egt_2bitcsr &w, const uint16_t *x, uint16_t *y, hipStream_t stream);
+bool sparse_m1_paired_supported(const egt_2bitcsr &w);      // INT4 values in the paired nibble order
+hipError_t launch_sparse_m1_paired(const egt_2bitcsr &w, const uint16_t *x, uint16_t *y, hipStream_t stream);
 
 // M = 1, 1:4 sparsity (see sparse_m1_n1_supported)
 bool sparse_m1_n1_supported(const egt_2bitcsr &w);

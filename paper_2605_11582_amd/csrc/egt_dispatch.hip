@@ -7,6 +7,10 @@ namespace egt {
 
 hipError_t launch_sparse(const egt_2bitcsr &w, const uint16_t *X, int64_t ldx, uint16_t *Y,
                          int64_t ldy, int M, hipStream_t stream) {
+  if (w.val_kind == EGT_VAL_INT4_PAIRED) {            // tuned for M = 1 at 2:4; everything else slot by slot
+    if (M == 1 && sparse_m1_paired_supported(w)) return launch_sparse_m1_paired(w, X, Y, stream);
+    return launch_sparse_generic(w, X, ldx, Y, ldy, M, stream);
+  }
   if (M == 1 && sparse_m1_supported(w)) return launch_sparse_m1(w, X, Y, stream);
   if (M == 1 && sparse_m1_n1_supported(w)) return launch_sparse_m1_n1(w, X, Y, stream);
   // 16-byte loads of X: token rows must start on a 16-byte boundary there
@@ -24,6 +28,13 @@ hipError_t launch_int4(const uint8_t *q, const uint16_t *qparams, int rows, int 
 
 hipError_t launch_sparse_batch(const egt_2bitcsr *ws, const uint16_t *const *xs, uint16_t *const *ys,
                                int count, hipStream_t stream) {
+  if (ws[0].val_kind == EGT_VAL_INT4_PAIRED) {        // no batched form: one launch each
+    for (int k = 0; k < count; ++k) {
+      const hipError_t e = launch_sparse(ws[k], xs[k], ws[k].cols, ys[k], ws[k].rows, 1, stream);
+      if (e != hipSuccess) return e;
+    }
+    return hipSuccess;
+  }
   if (sparse_m1_supported(ws[0])) return launch_sparse_m1_batch(ws, xs, ys, count, stream);
   if (sparse_m1_n1_supported(ws[0])) return launch_sparse_m1_n1_batch(ws, xs, ys, count, stream);
   for (int k = 0; k < count; ++k) {                   // shapes without a tuned kernel: one launch each

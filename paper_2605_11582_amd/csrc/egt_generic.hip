@@ -15,7 +15,7 @@ template <int VAL_KIND, int MT, bool RAGGED>
 __global__ __launch_bounds__(256) void k_sparse_generic(
     const uint32_t *__restrict__ row_ptr, const uint8_t *__restrict__ values,
     const uint16_t *__restrict__ idx, const uint16_t *__restrict__ qparams, int rows, int cols,
-    int n_keep, uint32_t total_slots, int group, const __half *__restrict__ X, int64_t ldx,
+    int n_keep, uint32_t total_slots, int group, int paired, const __half *__restrict__ X, int64_t ldx,
     __half *__restrict__ Y, int64_t ldy, int M) {
   const int lane = threadIdx.x & 63;
   const int r = blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
@@ -55,7 +55,8 @@ __global__ __launch_bounds__(256) void k_sparse_generic(
         const int col = 4 * (int)(j / (uint32_t)n_keep) + (int)((iw >> (2 * k)) & 3u);
         float wv;
         if (VAL_KIND == EGT_VAL_INT4) {
-          const int q = (nib >> (4 * k)) & 15;
+          // paired nibble order: slot k of the word sits in nibble (k >> 1) + 4 (k & 1)
+          const int q = (nib >> (paired ? 4 * ((k >> 1) + 4 * (k & 1)) : 4 * k)) & 15;
           const uint16_t *p = qparams + ((size_t)r * G + col / group) * 2;
           wv = __half2float(__ushort_as_half(p[0])) * ((float)q - __half2float(__ushort_as_half(p[1])));
         } else {
@@ -137,14 +138,16 @@ hipError_t launch_sparse_generic(const egt_2bitcsr &w, const uint16_t *X, int64_
   const dim3 block(256);
   const int mt = M == 1 ? 1 : 4;
   const dim3 grid((w.rows + 3) / 4, (M + mt - 1) / mt);
+  const int paired = w.val_kind == EGT_VAL_INT4_PAIRED ? 1 : 0;
 #define EGT_GO(KIND, MT, RAGGED)                                                                 \
   launch(k_sparse_generic<KIND, MT, RAGGED>, grid, block, 0, stream, w.row_ptr, (const uint8_t *)w.values, \
-         w.idx, w.qparams, w.rows, w.cols, w.n_keep, w.total_slots, w.group_size, (const __half *)X, ldx, \
+         w.idx, w.qparams, w.rows, w.cols, w.n_keep, w.total_slots, w.group_size, paired, (const __half *)X, ldx, \
          (__half *)Y, ldy, M)
 #define EGT_GO_MT(KIND, RAGGED) (mt == 1 ? EGT_GO(KIND, 1, RAGGED) : EGT_GO(KIND, 4, RAGGED))
+  const bool int4 = w.val_kind != EGT_VAL_FP16;
   if (w.n_keep == 0)                                  // rows of different lengths
-    return w.val_kind == EGT_VAL_INT4 ? EGT_GO_MT(EGT_VAL_INT4, true) : EGT_GO_MT(EGT_VAL_FP16, true);
-  return w.val_kind == EGT_VAL_INT4 ? EGT_GO_MT(EGT_VAL_INT4, false) : EGT_GO_MT(EGT_VAL_FP16, false);
+    return int4 ? EGT_GO_MT(EGT_VAL_INT4, true) : EGT_GO_MT(EGT_VAL_FP16, true);
+  return int4 ? EGT_GO_MT(EGT_VAL_INT4, false) : EGT_GO_MT(EGT_VAL_FP16, false);
 #undef EGT_GO_MT
 #undef EGT_GO
 }

@@ -60,12 +60,24 @@ void parallel_rows(int rows, F &&body) {
   for (auto &x : th) x.join();
 }
 
+// INT4 values in either nibble order
+inline bool is_int4(int val_kind) { return val_kind == EGT_VAL_INT4 || val_kind == EGT_VAL_INT4_PAIRED; }
+// Where the code of global slot t lives: byte and shift.  Canonical order: slot j of a word
+// of eight slots in nibble j.  Paired order: in nibble (j >> 1) + 4 (j & 1), i.e. the
+// nibbles of a word hold the slots 0, 2, 4, 6, 1, 3, 5, 7.
+inline int64_t nibble_byte(int64_t t, int val_kind, int &shift) {
+  const int j = (int)(t & 7);
+  const int pos = val_kind == EGT_VAL_INT4_PAIRED ? (j >> 1) + 4 * (j & 1) : j;
+  shift = 4 * (pos & 1);
+  return (t >> 3) * 4 + (pos >> 1);
+}
+
 // ---------------------------------------------------------------- shape rules
 egt_status check_shape(int rows, int cols, int n_keep, int group, int val_kind) {
   if (rows < 0 || cols < 0) return EGT_ERR_SHAPE;
   if (cols % 32 != 0) return EGT_ERR_SHAPE;
   if (n_keep < 1 || n_keep > 4) return EGT_ERR_SHAPE;
-  if (val_kind == EGT_VAL_INT4) {
+  if (is_int4(val_kind)) {
     if (group <= 0 || group % 4 != 0 || cols % group != 0) return EGT_ERR_SHAPE;
   } else if (val_kind == EGT_VAL_FP16) {
     if (group != 0) return EGT_ERR_SHAPE;
@@ -93,9 +105,9 @@ egt_status check_rows(int rows, int cols, const int32_t *row_n_keep, int group, 
 
 void fill_sizes(int rows, int cols, uint64_t slots, int group, int val_kind, size_t bytes[4]) {
   bytes[0] = sizeof(uint32_t) * ((size_t)rows + 1);
-  bytes[1] = val_kind == EGT_VAL_INT4 ? (size_t)(slots / 2) : (size_t)(slots * 2);
+  bytes[1] = is_int4(val_kind) ? (size_t)(slots / 2) : (size_t)(slots * 2);
   bytes[2] = (size_t)(slots / 8) * sizeof(uint16_t);
-  bytes[3] = val_kind == EGT_VAL_INT4 ? sizeof(uint16_t) * 2 * (size_t)rows * (size_t)(cols / group) : 0;
+  bytes[3] = is_int4(val_kind) ? sizeof(uint16_t) * 2 * (size_t)rows * (size_t)(cols / group) : 0;
 }
 
 egt_status pack_rows(const uint16_t *w, int64_t ldw, const uint8_t *mask, int64_t ldm, int rows, int cols,
@@ -154,9 +166,9 @@ egt_status egt_2bitcsr_sizes(int rows, int cols, int n_keep, int group, int val_
   if (st != EGT_OK) return st;
   const size_t slots = (size_t)rows * (size_t)n_keep * (size_t)(cols / 4);
   bytes[0] = 4 * ((size_t)rows + 1);
-  bytes[1] = val_kind == EGT_VAL_INT4 ? slots / 2 : slots * 2;
+  bytes[1] = is_int4(val_kind) ? slots / 2 : slots * 2;
   bytes[2] = 2 * (slots / 8);
-  bytes[3] = val_kind == EGT_VAL_INT4 ? 4 * (size_t)rows * (size_t)(cols / group) : 0;
+  bytes[3] = is_int4(val_kind) ? 4 * (size_t)rows * (size_t)(cols / group) : 0;
   return EGT_OK;
 }
 
@@ -283,9 +295,9 @@ egt_status pack_rows(const uint16_t *w, int64_t ldw, const uint8_t *mask, int64_
   auto n_of = [=](int r) { return row_n_keep ? (int)row_n_keep[r] : n_keep; };
   if (ldw < cols || ldm < cols) return EGT_ERR_SHAPE;
   if (!out->row_ptr || !out->values || !out->idx) return EGT_ERR_NULL;
-  if (val_kind == EGT_VAL_INT4 && !out->qparams) return EGT_ERR_NULL;
+  if (is_int4(val_kind) && !out->qparams) return EGT_ERR_NULL;
   if (row_group) {
-    if (val_kind != EGT_VAL_INT4) return EGT_ERR_SHAPE;
+    if (!is_int4(val_kind)) return EGT_ERR_SHAPE;
     for (int r = 0; r < rows; ++r)
       if (row_group[r] <= 0 || row_group[r] % group != 0 || cols % row_group[r] != 0) return EGT_ERR_SHAPE;
   }
@@ -320,7 +332,7 @@ egt_status pack_rows(const uint16_t *w, int64_t ldw, const uint8_t *mask, int64_
   });
   if (first.load() != INT64_MAX) return (egt_status)(first.load() & 7);
 
-  const int G = val_kind == EGT_VAL_INT4 ? cols / group : 0;
+  const int G = is_int4(val_kind) ? cols / group : 0;
   // first slot of every row (uniform rows: r * S)
   for (int64_t r = 0, t = 0; r <= rows; ++r) {
     out->row_ptr[r] = (uint32_t)t;
@@ -337,7 +349,7 @@ egt_status pack_rows(const uint16_t *w, int64_t ldw, const uint8_t *mask, int64_
       const uint16_t *wr = w + (int64_t)r * ldw;
       const uint8_t *mr = mask + (int64_t)r * ldm;
       const int n_row = n_of(r);
-      if (val_kind == EGT_VAL_INT4) {
+      if (is_int4(val_kind)) {
         // the row's own group size; its parameters are stored once per `group` columns
         const int gr = row_group ? row_group[r] : group, rep = gr / group;
         for (int g0 = 0; g0 < G; g0 += rep) {
@@ -360,7 +372,6 @@ egt_status pack_rows(const uint16_t *w, int64_t ldw, const uint8_t *mask, int64_
       }
       int64_t t = (int64_t)row_ptr[r];                            // global slot id
       uint32_t word = 0;
-      uint32_t byte = 0;
       for (int c = 0; c < cols; c += 4) {
         const int set = choose4(mr + c, n_row);
         for (int j = 0; j < 4; ++j) {
@@ -372,8 +383,11 @@ egt_status pack_rows(const uint16_t *w, int64_t ldw, const uint8_t *mask, int64_
           } else {
             const QParam &p = qp[(c + j) / group];
             const int q = kept ? make_code(half_to_double(wr[c + j]), p) : p.z;
-            if (t & 1) { vals8[t >> 1] = (uint8_t)(byte | (q << 4)); }
-            else byte = (uint32_t)q;
+            // (a row is a whole number of 4-byte words and no other row shares them: the
+            //  first nibble of a byte sets it, the second is or-ed in)
+            int shift;
+            const int64_t b = nibble_byte(t, val_kind, shift);
+            vals8[b] = shift ? (uint8_t)(vals8[b] | (q << 4)) : (uint8_t)q;
           }
           if ((t & 7) == 7) { idx[t >> 3] = (uint16_t)word; word = 0; }
           ++t;
@@ -399,7 +413,7 @@ egt_status egt_unpack_2bitcsr(const egt_2bitcsr *in, uint16_t *w_dense, int64_t 
   egt_status st = check_shape(rows, cols, mixed ? 1 : in->n_keep, group, in->val_kind);
   if (st != EGT_OK) return st;
   if (!in->row_ptr || !in->values || !in->idx) return EGT_ERR_NULL;
-  if (in->val_kind == EGT_VAL_INT4 && !in->qparams) return EGT_ERR_NULL;
+  if (is_int4(in->val_kind) && !in->qparams) return EGT_ERR_NULL;
   if ((w_dense && ldw < cols) || (mask && ldm < cols)) return EGT_ERR_SHAPE;
   // row_ptr: the uniform progression, or a running sum of whole rows that ends at total_slots
   const int64_t quarter = cols / 4;
@@ -439,7 +453,7 @@ egt_status egt_unpack_2bitcsr(const egt_2bitcsr *in, uint16_t *w_dense, int64_t 
   const uint16_t *vals16 = (const uint16_t *)in->values;
   const uint16_t *qparams = in->qparams;
   const int val_kind = in->val_kind;
-  const int G = val_kind == EGT_VAL_INT4 ? cols / group : 0;
+  const int G = is_int4(val_kind) ? cols / group : 0;
   const int *nr = n_row.data();
   parallel_rows(rows, [=](int r0, int r1) {
     for (int r = r0; r < r1; ++r) {
@@ -455,7 +469,9 @@ egt_status egt_unpack_2bitcsr(const egt_2bitcsr *in, uint16_t *w_dense, int64_t 
           if (val_kind == EGT_VAL_FP16) {
             bits = vals16[t];
           } else {
-            const int q = (vals8[t >> 1] >> (4 * (t & 1))) & 15;
+            int shift;
+            const int64_t b = nibble_byte(t, val_kind, shift);
+            const int q = (vals8[b] >> shift) & 15;
             const uint16_t *p = qparams + ((int64_t)r * G + col / group) * 2;
             bits = double_to_half(half_to_double(p[0]) * ((double)q - half_to_double(p[1])));
           }

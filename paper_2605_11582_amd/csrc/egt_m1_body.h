@@ -38,6 +38,8 @@ struct M1Geom {
   int64_t ldx, ldy;    // row strides of X and Y in elements (several-token form)
   uint32_t nib_mask;   // 0x00F0000F: low nibble of the low half, high nibble of the high half
   uint32_t nib_magic;  // 0x54006400: FP16 {1024.0, 64.0}
+  // (paired nibble order: nib_mask 0x000F000F, nib_magic {1024.0, 1024.0}, nib_magic2 {64.0, 64.0})
+  uint32_t nib_magic2;
 };
 
 // One wave = TPI tiles, all loaded before the first is consumed.
@@ -57,7 +59,8 @@ struct M1Geom {
 // projections of a 7B decoder and of the headline workload; tiles per row, rows per tile
 // and chunks per row are then constants and the index arithmetic of the general form
 // (two integer divisions before the first request goes out) folds away.
-template <int KIND, int TPI, int XP, int QW, bool LIN, int MT, bool ONE = false>
+// PAIRED: the INT4 codes are stored in the paired nibble order (EGT_VAL_INT4_PAIRED).
+template <int KIND, int TPI, int XP, int QW, bool LIN, int MT, bool ONE = false, bool PAIRED = false>
 __device__ __forceinline__ void k_sparse_m1_body(const uint32_t *__restrict__ row_ptr, const uint8_t *__restrict__ values,
     const uint8_t *__restrict__ idx, const uint8_t *__restrict__ qparams, const __half *__restrict__ x,
     __half *__restrict__ y, const M1Geom &g, int tile_base = -1) {
@@ -216,19 +219,22 @@ __device__ __forceinline__ void k_sparse_m1_body(const uint32_t *__restrict__ ro
 
   // ---- consume
   const uint32_t magic = in_vgpr(g.nib_magic);
+  const uint32_t magic2 = PAIRED ? in_vgpr(g.nib_magic2) : 0u;
   float s[TPI][MT];
 #pragma unroll
   for (int t = 0; t < TPI; ++t) {
     f4 acc[MT];
 #pragma unroll
     for (int m = 0; m < MT; ++m) acc[m] = f4{0.f, 0.f, 0.f, 0.f};
-    uint32_t s2[QW], off[QW];
+    uint32_t s2[QW], off[QW], off2[QW];
 #pragma unroll
     for (int k = 0; k < QW; ++k) {
-      s2[k] = off[k] = 0;
+      s2[k] = off[k] = off2[k] = 0;
       if (KIND == EGT_VAL_INT4) {
         s2[k] = __builtin_amdgcn_perm(qp[t][k], qp[t][k], 0x01000100u);                            // {s, s}
-        off[k] = pk_add_f16(__builtin_amdgcn_perm(qp[t][k], qp[t][k], 0x03020302u), g.nib_magic);  // {1024+z, 64+z}
+        const uint32_t zz = __builtin_amdgcn_perm(qp[t][k], qp[t][k], 0x03020302u);                // {z, z}
+        off[k] = pk_add_f16(zz, g.nib_magic);          // {1024+z, 64+z}; paired order: {1024+z, 1024+z}
+        if (PAIRED) off2[k] = pk_add_f16(zz, g.nib_magic2);                                         // {64+z, 64+z}
       }
     }
 #pragma unroll
@@ -236,6 +242,8 @@ __device__ __forceinline__ void k_sparse_m1_body(const uint32_t *__restrict__ ro
       u4 a;
       if (KIND == EGT_VAL_INT4) {
         if (EGT_ABLATE & 1) a = u4{nib[t][0][d], nib[t][0][d] ^ off[0], nib[t][0][d] ^ s2[0], nib[t][0][d]};
+        else if (PAIRED) a = dequant8_paired(nib[t][0][d], off[d * QW / 4], off2[d * QW / 4], s2[d * QW / 4], g.nib_mask,
+                                             g.nib_mask << 4, magic, magic2);
         else a = dequant8(nib[t][0][d], off[d * QW / 4], s2[d * QW / 4], g.nib_mask, magic);
       } else {
         a = nib[t][d];
@@ -335,6 +343,7 @@ inline void m1_geometry(const egt_2bitcsr &w, M1Geom &g) {
   g.last_chunk = (uint32_t)w.rows * (uint32_t)g.nchunks - 1u;
   g.nib_mask = 0x00F0000Fu;
   g.nib_magic = 0x54006400u;
+  g.nib_magic2 = 0;
   g.M = 1; g.ldx = 0; g.ldy = 0;
   g.hi_blocks = 0;
 }

@@ -52,6 +52,21 @@ __device__ __forceinline__ u4 dequant8(uint32_t d, uint32_t off, uint32_t s2, ui
   return r;
 }
 
+// The same for the paired nibble order (EGT_VAL_INT4_PAIRED): the word holds the slots
+// 0, 2, 4, 6, 1, 3, 5, 7 from its low nibble up, so slot pair (0, 1) is `d & 0x000F000F`,
+// (2, 3) is `d & 0x00F000F0`, and (4, 5), (6, 7) the same of d >> 8: one shift and four
+// and-ors instead of four byte permutes and four and-ors.  Both halves of a register carry
+// the same offset: 1024 (mask_lo, magic_lo, off_lo = {1024 + z} twice) or 64.
+__device__ __forceinline__ u4 dequant8_paired(uint32_t d, uint32_t off_lo, uint32_t off_hi, uint32_t s2, uint32_t mask_lo,
+                                              uint32_t mask_hi, uint32_t magic_lo, uint32_t magic_hi) {
+  const uint32_t d8 = d >> 8;
+  u4 r;
+  r[0] = pk_mul_f16(pk_sub_f16(and_or(d, mask_lo, magic_lo), off_lo), s2);
+  r[1] = pk_mul_f16(pk_sub_f16(and_or(d, mask_hi, magic_hi), off_hi), s2);
+  r[2] = pk_mul_f16(pk_sub_f16(and_or(d8, mask_lo, magic_lo), off_lo), s2);
+  r[3] = pk_mul_f16(pk_sub_f16(and_or(d8, mask_hi, magic_hi), off_hi), s2);
+  return r;
+}
 // Pins a wave-uniform value into a vector register (an empty statement for the
 // assembler): with the mask in a scalar and the magic in a vector register the
 // fused and-or respects the one-scalar-operand limit of the encoding.

@@ -32,7 +32,7 @@
 namespace egt {
 
 // One matrix per launch, one whole tile per row (K = 4096), INT4 values: the headline shape.
-template <int TPI, int XP, int QW>
+template <int TPI, int XP, int QW, bool PAIRED = false>
 __global__ __launch_bounds__(1024) void k_sparse_m1_one(const uint32_t *__restrict__ row_ptr,
                                                          const uint8_t *__restrict__ values,
                                                          const uint8_t *__restrict__ idx,
@@ -46,23 +46,24 @@ __global__ __launch_bounds__(1024) void k_sparse_m1_one(const uint32_t *__restri
   const int nw = blockDim.x >> 6;
   if constexpr (TPI > 1) {
     if ((int)blockIdx.x >= g.hi_blocks) {
-      k_sparse_m1_body<EGT_VAL_INT4, TPI - 1, XP, QW, false, 1, true>(
+      k_sparse_m1_body<EGT_VAL_INT4, TPI - 1, XP, QW, false, 1, true, PAIRED>(
           row_ptr, values, idx, qparams, x, y, g, (g.hi_blocks * TPI + ((int)blockIdx.x - g.hi_blocks) * (TPI - 1)) * nw);
       return;
     }
   }
-  k_sparse_m1_body<EGT_VAL_INT4, TPI, XP, QW, false, 1, true>(row_ptr, values, idx, qparams, x, y, g, (int)blockIdx.x * nw * TPI);
+  k_sparse_m1_body<EGT_VAL_INT4, TPI, XP, QW, false, 1, true, PAIRED>(row_ptr, values, idx, qparams, x, y, g,
+                                                                      (int)blockIdx.x * nw * TPI);
 }
 
 // One matrix per launch: the pointers are plain kernel arguments.
-template <int KIND, int TPI, int XP, int QW, bool LIN>
+template <int KIND, int TPI, int XP, int QW, bool LIN, bool PAIRED = false>
 __global__ __launch_bounds__(1024) void k_sparse_m1(const uint32_t *__restrict__ row_ptr,
                                                      const uint8_t *__restrict__ values,
                                                      const uint8_t *__restrict__ idx,
                                                      const uint8_t *__restrict__ qparams,
                                                      const __half *__restrict__ x,
                                                      __half *__restrict__ y, const M1Geom g) {
-  k_sparse_m1_body<KIND, TPI, XP, QW, LIN, 1>(row_ptr, values, idx, qparams, x, y, g);
+  k_sparse_m1_body<KIND, TPI, XP, QW, LIN, 1, false, PAIRED>(row_ptr, values, idx, qparams, x, y, g);
 }
 
 // Several tokens (2 <= M <= MT), one matrix.
@@ -192,6 +193,50 @@ hipError_t launch_sparse_m1_batch(const egt_2bitcsr *ws, const uint16_t *const *
 #undef EGT_GO4
 #undef EGT_GO5
 #undef EGT_GOL
+}
+
+// The paired nibble order (EGT_VAL_INT4_PAIRED): the shapes of sparse_m1_supported with one
+// {scale, zero} pair per chunk, at the default tiles per wave.
+bool sparse_m1_paired_supported(const egt_2bitcsr &w) {
+  if (w.val_kind != EGT_VAL_INT4_PAIRED || w.group_size < 64) return false;
+  egt_2bitcsr c = w;
+  c.val_kind = EGT_VAL_INT4;
+  return sparse_m1_supported(c);
+}
+
+hipError_t launch_sparse_m1_paired(const egt_2bitcsr &w, const uint16_t *x, uint16_t *y, hipStream_t stream) {
+  if (w.rows == 0) return hipSuccess;
+  egt_2bitcsr c = w;
+  c.val_kind = EGT_VAL_INT4;
+  M1Geom g;
+  m1_geometry(c, g);
+  g.nib_mask = 0x000F000Fu; g.nib_magic = 0x64006400u; g.nib_magic2 = 0x54005400u;
+  const int tpi = g.phases == 3 ? 2 : 4;
+  int wpp = (g.phases == 1 || g.phases == 3) ? 4 : 2;
+  if (wpp * g.phases > 16) wpp = 16 / g.phases;
+  LaunchShape ls;
+  if (!m1_block_shape(g, false, wpp, tpi, 1, 4, ls)) return hipErrorInvalidConfiguration;
+  const dim3 block(64 * ls.nwaves);
+#define EGT_ARGS w.row_ptr, (const uint8_t *)w.values, (const uint8_t *)w.idx, (const uint8_t *)w.qparams, (const __half *)x, (__half *)y, g
+  if (g.nchunks == 64 && ls.xp <= 2) {                 // one tile per row: rows spread evenly, see launch_sparse_m1_batch
+    int nb = ls.nblocks;
+    g.hi_blocks = nb;
+    const int per_hi = ls.nwaves * tpi, per_lo = ls.nwaves * (tpi - 1);
+    const int even = 256 * ((g.ntiles + 256 * per_hi - 1) / (256 * per_hi));
+    if (even <= 1024 && even * per_lo < g.ntiles) {
+      nb = even;
+      g.hi_blocks = (g.ntiles - nb * per_lo + ls.nwaves - 1) / ls.nwaves;
+    }
+    return ls.xp <= 1 ? launch(k_sparse_m1_one<4, 1, 1, true>, dim3(nb), block, ls.lds, stream, EGT_ARGS)
+                      : launch(k_sparse_m1_one<4, 2, 1, true>, dim3(nb), block, ls.lds, stream, EGT_ARGS);
+  }
+  const dim3 grid(ls.nblocks);
+#define EGT_P(TPI) (ls.xp <= 1 ? launch(k_sparse_m1<EGT_VAL_INT4, TPI, 1, 1, false, true>, grid, block, ls.lds, stream, EGT_ARGS) \
+                    : ls.xp == 2 ? launch(k_sparse_m1<EGT_VAL_INT4, TPI, 2, 1, false, true>, grid, block, ls.lds, stream, EGT_ARGS) \
+                                 : launch(k_sparse_m1<EGT_VAL_INT4, TPI, 4, 1, false, true>, grid, block, ls.lds, stream, EGT_ARGS))
+  return tpi == 2 ? EGT_P(2) : EGT_P(4);
+#undef EGT_P
+#undef EGT_ARGS
 }
 
 // Several-token form: 2:4, M = 2..4, INT4 values (groups of 64 << j) or FP16 values.  Used

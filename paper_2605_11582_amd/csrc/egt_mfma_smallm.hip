@@ -609,6 +609,7 @@ __global__ __launch_bounds__(64 * NWMAX) void k_sparse_smallm_ks(const uint32_t 
 // loads take 32-bit offsets).
 bool sparse_smallm_supported(const egt_2bitcsr &w, int64_t ldx, int M) {
   if (w.n_keep != 1 && w.n_keep != 2) return false;
+  if (w.val_kind != EGT_VAL_INT4 && w.val_kind != EGT_VAL_FP16) return false;   // the paired nibble order has no small-M kernel
   const int chunk = w.n_keep == 1 ? 128 : 64;
   if (w.cols % chunk != 0 || w.cols < chunk || ldx % 2 != 0) return false;
   const uint64_t vbytes = (uint64_t)w.rows * (w.cols / chunk) * (w.val_kind == EGT_VAL_INT4 ? 16 : 64);

@@ -114,7 +114,7 @@ egt_status classify(const egt_gemv_item &it, ItemShape &s) {
     const egt_2bitcsr &w = *it.sparse;
     if (w.rows < 0 || w.cols <= 0 || w.cols % 32 != 0 || w.val_kind != EGT_VAL_INT4 || w.group_size <= 0 ||
         w.cols % w.group_size != 0)
-      return w.val_kind == EGT_VAL_FP16 ? EGT_ERR_UNSUPPORTED : EGT_ERR_SHAPE;
+      return (w.val_kind == EGT_VAL_FP16 || w.val_kind == EGT_VAL_INT4_PAIRED) ? EGT_ERR_UNSUPPORTED : EGT_ERR_SHAPE;
     if ((uint64_t)w.rows * (uint64_t)w.n_keep * (uint64_t)(w.cols / 4) >= (1ull << 32)) return EGT_ERR_SHAPE;
     if (w.rows > 0 && (!w.row_ptr || !w.values || !w.idx || !w.qparams)) return EGT_ERR_NULL;
     if (!aligned16(w.row_ptr) || !aligned16(w.values) || !aligned16(w.idx) || !aligned16(w.qparams)) return EGT_ERR_BUFFER;

@@ -222,6 +222,67 @@ def test_full_size_sampled_rows(name, rows, cols, kind, g, cfg):
         G.assert_close(y[rr], yr, ar, f"{name} rows {r0}..")
 
 
+# ---------------------------------------------------------------- paired nibble order
+@pytest.mark.parametrize("rows,cols,n,g", [
+    (257, 4096, 2, 128), (45, 4096, 2, 64), (21, 11008, 2, 128), (70, 1024, 2, 128), (70, 2048, 2, 256), (33, 8192, 2, 128),
+    (4, 32768, 2, 128),                                    # the tuned M = 1 kernels
+    (45, 4096, 2, 32), (37, 96, 2, 32), (45, 4096, 1, 128), (64, 160, 3, 32), (3, 40960, 2, 128),   # slot by slot
+])
+def test_paired_order_gives_the_bits_of_the_canonical_order(rows, cols, n, g):
+    """The two nibble orders hold the same codes, the tuned kernels dequantise them to the same
+    FP16 values and add in the same order: same bits where both run a tuned kernel, the
+    oracle's tolerance everywhere."""
+    print(f"case paired {rows}x{cols} n={n} g={g}", flush=True)
+    rng = np.random.default_rng(rows + cols)
+    w = synth.weights(rows, cols, 7300 + rows + cols + g)
+    mask = O.prune_n4_magnitude(w, n)
+    mask = (mask & (rng.random(mask.shape) >= 0.1)).astype(np.uint8)
+    pp = B.pack_2bitcsr(w, mask, n, g, B.VAL_INT4_PAIRED)
+    pc = B.pack_2bitcsr(w, mask, n, g, B.VAL_INT4)
+    o = O.pack_2bitcsr(w, mask, n, g, O.VAL_INT4_PAIRED)
+    assert np.array_equal(pp.values, o["values"]) and np.array_equal(pp.idx, o["idx"])
+    x = synth.activations(cols, 7300 + rows)
+    y_ref, a_ref = O.gemv(o, x)
+    yp = G.run_sparse_gemv(pp, x)
+    G.assert_close(yp, y_ref, a_ref, "paired order")
+    tuned = n == 2 and g >= 64 and (cols in (1024, 2048) or (cols >= 4096 and cols % 64 == 0 and cols <= 32768))
+    if tuned:
+        assert np.array_equal(yp.view(np.uint16), G.run_sparse_gemv(pc, x).view(np.uint16))
+    X = synth.activation_rows(3, cols, 7300 + cols)
+    Y_ref, A_ref = O.gemm_smallm(o, X)
+    G.assert_close(G.run_sparse_gemm(pp, X), Y_ref, A_ref, "paired order, three tokens")
+
+
+def test_paired_order_full_size_and_in_other_entry_points():
+    rows, cols = 11008, 4096
+    seed = synth.seed_for(synth.HEADLINE)
+    w = synth.weights(rows, cols, seed)
+    mask = B.prune_n4(w, 2)
+    pp = B.pack_2bitcsr(w, mask, 2, 128, B.VAL_INT4_PAIRED)
+    pc = B.pack_2bitcsr(w, mask, 2, 128, B.VAL_INT4)
+    x = synth.activations(cols, seed)
+    yp = G.run_sparse_gemv(pp, x)
+    assert np.array_equal(yp.view(np.uint16), G.run_sparse_gemv(pc, x).view(np.uint16))
+    pick = G.sample_rows(rows, 128, seed)
+    o = O.pack_2bitcsr(w[pick], O.prune_n4_magnitude(w[pick], 2), 2, 128, O.VAL_INT4_PAIRED)
+    words = cols // 2 // 8 * 4                               # value bytes per row
+    assert np.array_equal(np.concatenate([pp.values[r * words:(r + 1) * words] for r in pick]), o["values"])
+    y_ref, a_ref = O.gemv(o, x)
+    G.assert_close(yp[pick], y_ref, a_ref, "paired order, headline shape")
+    # batched call: one launch per member; the workspace and table forms say so
+    torch = G.torch_mod()
+    pd = pp.to("cuda")
+    xd = G.to_dev(x.view(np.uint16)).view(torch.float16)
+    ys = [torch.zeros(rows, dtype=torch.float16, device="cuda") for _ in range(2)]
+    B.prepared_sparse_gemv_batch([pd, pd], [xd, xd], ys)()
+    torch.cuda.synchronize()
+    assert np.array_equal(ys[1].cpu().numpy().view(np.uint16), yp.view(np.uint16))
+    assert B.smallm_ws_bytes(pd, 64) == 0
+    with pytest.raises(B.EgtError) as e:
+        B.prepared_gemv_stack([("sparse", pd, xd, ys[0])])
+    assert e.value.status == 6
+
+
 # ---------------------------------------------------------------- rows of different lengths
 def _ragged_case(rows, cols, g, kind, seed, choices=(1, 2), drop=0.0):
     rng = np.random.default_rng(seed)

@@ -297,6 +297,46 @@ def test_unpack_rejects_broken_buffers():
     assert e.value.status == 5
 
 
+# ----------------------------------------------------------------- paired nibble order
+def test_library_packs_the_handworked_row_in_the_paired_order():
+    from helpers import read_fixture
+    fx = read_fixture("handworked_1x32.txt")
+    w = np.array([float(v) for v in fx["w"]], dtype=np.float16)[None, :]
+    mask = np.array([int(v) for v in fx["mask"]], dtype=np.uint8)[None, :]
+    p = B.pack_2bitcsr(w, mask, 2, 32, B.VAL_INT4_PAIRED)
+    assert p.values.tolist() == [int(v, 16) for v in fx["value_bytes_paired"]]
+    assert p.idx.tolist() == [int(v, 16) for v in fx["idx_words"]]
+    assert np.asarray(p.qparams).reshape(-1).tolist() == [int(v, 16) for v in fx["qparams"]]
+
+
+@pytest.mark.parametrize("n,g,drop", [(2, 128, False), (2, 32, True), (1, 64, True), (3, 16, False)])
+def test_paired_pack_bit_exact_and_round_trip(n, g, drop):
+    w = synth.weights(33, 512, 700 + n + g)
+    mask = O.prune_n4_magnitude(w, n)
+    if drop:
+        mask[np.random.default_rng(g).random(mask.shape) < 0.1] = 0
+    p = B.pack_2bitcsr(w, mask, n, g, B.VAL_INT4_PAIRED)
+    _same_packed(p, O.pack_2bitcsr(w, mask, n, g, O.VAL_INT4_PAIRED))
+    assert B.sizes(33, 512, n, g, B.VAL_INT4_PAIRED) == B.sizes(33, 512, n, g, B.VAL_INT4)
+    wd, md = B.unpack_2bitcsr(p)
+    wc, mc = B.unpack_2bitcsr(B.pack_2bitcsr(w, mask, n, g, B.VAL_INT4))
+    assert np.array_equal(wd.view(np.uint16), wc.view(np.uint16)) and np.array_equal(md, mc)
+    nk = np.random.default_rng(n).choice([1, 2], size=33).astype(np.int32)
+    mr = np.zeros_like(mask)
+    for k in (1, 2):
+        mr[nk == k] = O.prune_n4_magnitude(w[nk == k], k)
+    pr = B.pack_2bitcsr_rows(w, mr, nk, g, B.VAL_INT4_PAIRED)
+    orr = O.pack_2bitcsr_rows(w, mr, nk, g, O.VAL_INT4_PAIRED)
+    assert np.array_equal(pr.values, orr["values"]) and np.array_equal(pr.idx, orr["idx"])
+    assert L_status_of_fp16_group_rule() == 2
+
+
+def L_status_of_fp16_group_rule():
+    # the paired order follows the INT4 shape rules: a group size is required
+    out = (ctypes.c_size_t * 4)()
+    return B.lib().egt_2bitcsr_sizes(8, 64, 2, 0, B.VAL_INT4_PAIRED, out)
+
+
 # ----------------------------------------------------------------- rows of different lengths
 def _mixed(R, K, seed, choices=(1, 2), drop=False):
     rng = np.random.default_rng(seed)
