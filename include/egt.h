@@ -278,8 +278,13 @@ typedef struct {
 #define EGT_STACK_ENTRY_BYTES 160 /* bytes of one descriptor in the table */
 enum { EGT_STACK_AUTO = 0, EGT_STACK_GRID = 1, EGT_STACK_RESIDENT = 2 };
 
+/* One launch of a planned table.  A table whose matrices all run well in one kernel is one
+ * part.  A table that holds 1:4 matrices beside others is two: the 1:4 kernel body needs
+ * twice the registers of the others, and a kernel that carries every body runs every
+ * matrix at the occupancy of the widest one (the three-way mix of a 7B stack: 783 us in
+ * one kernel, 540 us in two).  The parts' tables follow each other in the table. */
 typedef struct {
-  int32_t count;         /* matrices in the table                                            */
+  int32_t count;         /* matrices of the part                                             */
   int32_t mode;          /* 0: one grid of short-lived workgroups per matrix;
                             1: resident workgroups that walk a list of row blocks            */
   int32_t grid_x;        /* mode 0: workgroups of the largest matrix; mode 1: workgroups     */
@@ -290,7 +295,15 @@ typedef struct {
   int32_t nitems;        /* mode 1: row blocks in the list                                   */
   int32_t part_offset;   /* mode 1: LDS offset of the partial sums                           */
   int32_t reserved;
-  uint64_t table_bytes;  /* bytes of the table                                               */
+  uint64_t table_bytes;  /* bytes of the part's table                                        */
+} egt_stack_part;
+
+#define EGT_STACK_MAX_PARTS 2
+typedef struct {
+  int32_t count;         /* matrices in the table                                            */
+  int32_t nparts;        /* launches                                                         */
+  egt_stack_part part[EGT_STACK_MAX_PARTS];
+  uint64_t table_bytes;  /* bytes of the whole table                                         */
 } egt_stack_plan;
 
 /* HOST.  Checks `count` (1..65535) items, chooses the launch form and writes the launch
@@ -305,11 +318,13 @@ typedef struct {
  * least 2048 (dense) or 4096 (2:4) columns that hold 256 MB or more (below that a workgroup
  * would see too few rows to make staying resident pay) and mode 0 otherwise; EGT_STACK_GRID
  * and EGT_STACK_RESIDENT ask for mode 0 or mode 1 (EGT_ERR_UNSUPPORTED if the shapes do not
- * allow mode 1).  Mode 1 sizes the launch for the 256 compute units of an MI355X. */
+ * allow mode 1).  Mode 1 sizes the launch for the 256 compute units of an MI355X.  The
+ * form is chosen per part: 1:4 matrices always run in mode 0 (with EGT_STACK_RESIDENT they
+ * are EGT_ERR_UNSUPPORTED), the other part of the same table in mode 1 if it qualifies. */
 egt_status egt_gemv_stack_plan(const egt_gemv_item *items, int count, int form, void *table,
                                size_t table_bytes, egt_stack_plan *plan);
 
-/* DEVICE.  Runs every product of a planned table in one launch on `stream`.  table_dev:
+/* DEVICE.  Runs every product of a planned table, one launch per part, on `stream`.  table_dev:
  * the device copy of the table egt_gemv_stack_plan wrote; it and every buffer it names
  * must stay valid until the launch has completed.  The products are independent: no y may
  * alias an x or another y of the same table.  Each y[r] is computed by the same code as

@@ -53,11 +53,35 @@ class GemvItem(C.Structure):
                 ("x", C.c_void_p), ("y", C.c_void_p)]
 
 
-class StackPlan(C.Structure):
-    """Mirror of `egt_stack_plan`."""
+class StackPart(C.Structure):
+    """Mirror of `egt_stack_part`: one launch of a planned table."""
     _fields_ = [("count", C.c_int32), ("mode", C.c_int32), ("grid_x", C.c_int32), ("block_threads", C.c_int32),
                 ("lds_bytes", C.c_int32), ("x_pieces", C.c_int32), ("forms", C.c_int32), ("nitems", C.c_int32),
                 ("part_offset", C.c_int32), ("reserved", C.c_int32), ("table_bytes", C.c_uint64)]
+
+
+STACK_MAX_PARTS = 2
+
+
+class StackPlan(C.Structure):
+    """Mirror of `egt_stack_plan`.  The launch shape of the first part is also reachable as
+    attributes of the plan itself (`plan.mode`, `plan.grid_x`, ...)."""
+    _fields_ = [("count", C.c_int32), ("nparts", C.c_int32), ("part", StackPart * STACK_MAX_PARTS), ("table_bytes", C.c_uint64)]
+
+    _FIRST = ("mode", "grid_x", "block_threads", "lds_bytes", "x_pieces", "forms", "nitems", "part_offset")
+
+    def __getattr__(self, name):
+        if name in StackPlan._FIRST:
+            return getattr(self.part[0], name)
+        raise AttributeError(name)
+
+    def __setattr__(self, name, value):
+        if name in StackPlan._FIRST:
+            setattr(self.part[0], name, value)
+        elif name in ("count", "nparts", "part", "table_bytes"):
+            super().__setattr__(name, value)
+        else:
+            raise AttributeError(f"egt_stack_plan has no field {name}")
 
 
 STACK_ENTRY_BYTES = 160

@@ -145,7 +145,7 @@ namespace {
 // table does not qualify.
 bool plan_stream(const egt_gemv_item *items, const std::vector<ItemShape> &shapes, const std::vector<StackEntry> &block_entries,
                  int count, int nwaves, bool whatever_the_size, std::vector<StreamMatrix> &mats, std::vector<uint32_t> &first,
-                 std::vector<StreamItem> &work, egt_stack_plan &plan) {
+                 std::vector<StreamItem> &work, egt_stack_part &plan) {
   std::vector<uint64_t> row_bytes_of;
   int force = -1, bpc = 2, item_kb = 4096;
   tune_pair("EGT_STREAM_TUNE", force, bpc);
@@ -253,13 +253,11 @@ bool plan_stream(const egt_gemv_item *items, const std::vector<ItemShape> &shape
 }  // namespace
 }  // namespace egt
 
-extern "C" {
+namespace egt {
+namespace {
 
-egt_status egt_gemv_stack_plan(const egt_gemv_item *items, int count, int form, void *table, size_t table_bytes,
-                               egt_stack_plan *plan) {
-  using namespace egt;
-  if (!items || !plan) return EGT_ERR_NULL;
-  if (count < 1 || count > 65535 || form < EGT_STACK_AUTO || form > EGT_STACK_RESIDENT) return EGT_ERR_SHAPE;
+// Plans one part: `count` classified items that share a kernel.
+egt_status plan_part(const egt_gemv_item *items, int count, int form, void *table, size_t table_bytes, egt_stack_part *plan) {
   std::vector<ItemShape> shapes((size_t)count);
   std::vector<StackEntry> entries((size_t)count);
   // pass 1: storage form and tiles per row ("phases") of every item
@@ -284,7 +282,7 @@ egt_status egt_gemv_stack_plan(const egt_gemv_item *items, int count, int form, 
   }
   if (nwaves == 0) return EGT_ERR_UNSUPPORTED;
 
-  egt_stack_plan out;
+  egt_stack_part out;
   std::memset(&out, 0, sizeof(out));
   out.count = count;
   std::vector<StreamMatrix> mats;
@@ -343,7 +341,7 @@ egt_status egt_gemv_stack_plan(const egt_gemv_item *items, int count, int form, 
     out.block_threads = 64 * nwaves;
     out.lds_bytes = (int32_t)lds;
     out.x_pieces = xp <= 2 ? 2 : xp <= 4 ? 4 : 8;
-    out.forms = (forms & 2) ? 7 : forms;
+    out.forms = forms;
     out.nitems = 0;
     out.part_offset = 0;
     out.table_bytes = (uint64_t)count * EGT_STACK_ENTRY_BYTES;
@@ -366,24 +364,89 @@ egt_status egt_gemv_stack_plan(const egt_gemv_item *items, int count, int form, 
   return EGT_OK;
 }
 
+}  // namespace
+}  // namespace egt
+
+extern "C" {
+
+egt_status egt_gemv_stack_plan(const egt_gemv_item *items, int count, int form, void *table, size_t table_bytes,
+                               egt_stack_plan *plan) {
+  using namespace egt;
+  if (!items || !plan) return EGT_ERR_NULL;
+  if (count < 1 || count > 65535 || form < EGT_STACK_AUTO || form > EGT_STACK_RESIDENT) return EGT_ERR_SHAPE;
+  // the 1:4 matrices of a table that holds others too run as a launch of their own
+  std::vector<egt_gemv_item> group[EGT_STACK_MAX_PARTS];
+  for (int k = 0; k < count; ++k) {
+    ItemShape shape;
+    const egt_status st = classify(items[k], shape);
+    if (st != EGT_OK) return st;
+    group[shape.form == FORM_S14 ? 1 : 0].push_back(items[k]);
+  }
+  if (group[0].empty()) group[0].swap(group[1]);
+  if (form == EGT_STACK_RESIDENT && !group[1].empty()) return EGT_ERR_UNSUPPORTED;
+  egt_stack_plan out;
+  std::memset(&out, 0, sizeof(out));
+  out.count = count;
+  // size query of every part first: nothing is written when a part is in error
+  for (int p = 0; p < EGT_STACK_MAX_PARTS && !group[p].empty(); ++p) {
+    const egt_status st = plan_part(group[p].data(), (int)group[p].size(), form, nullptr, 0, &out.part[p]);
+    if (st != EGT_OK) return st;
+    out.table_bytes += (out.part[p].table_bytes + 15) & ~(uint64_t)15;
+    out.nparts = p + 1;
+  }
+  if (table) {
+    if ((uint64_t)table_bytes < out.table_bytes) return EGT_ERR_SHAPE;
+    uint64_t at = 0;
+    for (int p = 0; p < out.nparts; ++p) {
+      const egt_status st = plan_part(group[p].data(), (int)group[p].size(), form, (uint8_t *)table + at,
+                                      (size_t)out.part[p].table_bytes, &out.part[p]);
+      if (st != EGT_OK) return st;
+      at += (out.part[p].table_bytes + 15) & ~(uint64_t)15;
+    }
+  }
+  *plan = out;
+  return EGT_OK;
+}
+
+static egt_status run_part(const uint8_t *t, const egt_stack_part *plan, hipStream_t st);
+
 egt_status egt_gemv_stack_run(const void *table_dev, const egt_stack_plan *plan, void *stream) {
   using namespace egt;
   if (!table_dev || !plan) return EGT_ERR_NULL;
   if (!aligned16(table_dev)) return EGT_ERR_BUFFER;
-  if (plan->count < 1 || plan->count > 65535 || plan->grid_x < 0 || plan->block_threads < 64 ||
-      plan->block_threads > 1024 || plan->block_threads % 64 != 0 || plan->lds_bytes < 0 ||
-      plan->lds_bytes > 64 * 1024 || (plan->x_pieces != 2 && plan->x_pieces != 4 && plan->x_pieces != 8) ||
-      plan->forms < 1 || plan->forms > 7 || plan->mode < 0 || plan->mode > 1)
-    return EGT_ERR_SHAPE;
-  if (plan->mode == 1 && (plan->nitems < 1 || plan->grid_x < 1 || plan->grid_x > 4 * DEVICE_CUS || (plan->forms & 2) ||
-                          plan->block_threads > 768 || plan->part_offset < 0 || plan->part_offset > plan->lds_bytes ||
-                          plan->table_bytes != (uint64_t)plan->count * EGT_STACK_ENTRY_BYTES + stream_first_bytes(plan->grid_x) +
-                                                   16ull * (uint64_t)plan->nitems))
-    return EGT_ERR_SHAPE;
+  if (plan->nparts < 1 || plan->nparts > EGT_STACK_MAX_PARTS) return EGT_ERR_SHAPE;
+  uint64_t at = 0;
+  int total = 0;
+  for (int p = 0; p < plan->nparts; ++p) {           // every part is checked before the first is launched
+    const egt_stack_part &q = plan->part[p];
+    if (q.count < 1 || q.count > 65535 || q.grid_x < 0 || q.block_threads < 64 || q.block_threads > 1024 ||
+        q.block_threads % 64 != 0 || q.lds_bytes < 0 || q.lds_bytes > 64 * 1024 ||
+        (q.x_pieces != 2 && q.x_pieces != 4 && q.x_pieces != 8) || q.mode < 0 || q.mode > 1 ||
+        (q.forms != 1 && q.forms != 2 && q.forms != 4 && q.forms != 5))   // 2:4 and dense together, 1:4 alone
+      return EGT_ERR_SHAPE;
+    if (q.mode == 0 && q.table_bytes != (uint64_t)q.count * EGT_STACK_ENTRY_BYTES) return EGT_ERR_SHAPE;
+    if (q.mode == 1 && (q.nitems < 1 || q.grid_x < 1 || q.grid_x > 4 * DEVICE_CUS || (q.forms & 2) || q.block_threads > 768 ||
+                        q.part_offset < 0 || q.part_offset > q.lds_bytes ||
+                        q.table_bytes != (uint64_t)q.count * EGT_STACK_ENTRY_BYTES + stream_first_bytes(q.grid_x) +
+                                             16ull * (uint64_t)q.nitems))
+      return EGT_ERR_SHAPE;
+    at += (q.table_bytes + 15) & ~(uint64_t)15;
+    total += q.count;
+  }
+  if (at != plan->table_bytes || total != plan->count) return EGT_ERR_SHAPE;
+  at = 0;
+  for (int p = 0; p < plan->nparts; ++p) {
+    const egt_status st = run_part((const uint8_t *)table_dev + at, &plan->part[p], (hipStream_t)stream);
+    if (st != EGT_OK) return st;
+    at += (plan->part[p].table_bytes + 15) & ~(uint64_t)15;
+  }
+  return EGT_OK;
+}
+
+static egt_status run_part(const uint8_t *t, const egt_stack_part *plan, hipStream_t st) {
+  using namespace egt;
   if (plan->grid_x == 0) return EGT_OK;               // every matrix is empty
-  const uint8_t *t = (const uint8_t *)table_dev;
   const size_t lds = (size_t)plan->lds_bytes;
-  const hipStream_t st = (hipStream_t)stream;
   const dim3 block(plan->block_threads);
   hipError_t e;
   if (plan->mode == 1) {
@@ -399,13 +462,13 @@ egt_status egt_gemv_stack_run(const void *table_dev, const egt_stack_plan *plan,
     }
 #undef EGT_STREAM_GO
   } else {
-    // (forms without the 1:4 body: the common case; any table with a 1:4 matrix: all bodies)
+    // (a part holds 2:4 and dense matrices, or 1:4 matrices)
     const dim3 grid(plan->grid_x, plan->count);
 #define EGT_STACK_GO(XP)                                                                         \
   (plan->forms == 1 ? launch(k_gemv_stack<XP, 1>, grid, block, lds, st, t)                        \
+   : plan->forms == 2 ? launch(k_gemv_stack<XP, 2>, grid, block, lds, st, t)                      \
    : plan->forms == 4 ? launch(k_gemv_stack<XP, 4>, grid, block, lds, st, t)                      \
-   : plan->forms == 5 ? launch(k_gemv_stack<XP, 5>, grid, block, lds, st, t)                      \
-                      : launch(k_gemv_stack<XP, 7>, grid, block, lds, st, t))
+                      : launch(k_gemv_stack<XP, 5>, grid, block, lds, st, t))
     switch (plan->x_pieces) {
       case 2: e = EGT_STACK_GO(2); break;
       case 4: e = EGT_STACK_GO(4); break;

@@ -196,7 +196,9 @@ def test_mixed_table_in_one_launch_small_shapes():
             B.sparse_gemv(p, xd, y1)
         singles.append((ybuf, y1))
     call = B.prepared_gemv_stack(items)
-    assert call.plan.count == len(specs) and call.plan.block_threads == 768 and call.plan.mode == 0   # 1, 2, 3, 4 and 6 tiles per row
+    # two launches: 2:4 and dense matrices with 1, 2, 3, 4 and 6 tiles per row (twelve waves), the 1:4 matrices (four waves)
+    assert call.plan.count == len(specs) and call.plan.nparts == 2
+    assert [(q.count, q.mode, q.block_threads, q.forms) for q in call.plan.part] == [(11, 0, 768, 5), (3, 0, 256, 2)]
     for rep in range(2):
         call()
         torch.cuda.synchronize()
@@ -210,7 +212,7 @@ def test_mixed_table_in_one_launch_small_shapes():
             ybuf[64:64 + rows].fill_(0)
     # other wave counts: one tile per row everywhere -> 4 waves; four tiles per row -> 4 waves too
     small = B.prepared_gemv_stack([items[0], items[2]])
-    assert small.plan.block_threads == 256
+    assert small.plan.nparts == 2 and small.plan.part[0].block_threads == 256 and small.plan.part[1].block_threads == 256
     small()
     torch.cuda.synchronize()
     for k in (0, 2):

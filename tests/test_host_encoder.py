@@ -498,10 +498,14 @@ def test_stack_plan_checks_items_and_reports_the_launch_shape():
     items = _fake_items([view, down, one4], [(4096, 11008, 128)])
     plan = B.StackPlan()
     assert L.egt_gemv_stack_plan(items, 4, 0, None, 0, ctypes.byref(plan)) == 0          # size query
-    # tiles per row 1, 3, 2 and 6: six waves; a 1:4 matrix: short-lived workgroups, every body;
-    # the widest x (1:4, K = 11008: 2048 pieces) needs 6 -> 8 pieces per thread
-    assert (plan.count, plan.mode, plan.block_threads, plan.x_pieces, plan.forms) == (4, 0, 384, 8, 7)
-    assert plan.table_bytes == 4 * B.STACK_ENTRY_BYTES and plan.grid_x == 512 and 0 < plan.lds_bytes <= 65536
+    # two launches: the 2:4 and dense matrices (tiles per row 1, 3 and 6: six waves), and the 1:4
+    # matrix by itself (two tiles per row: four waves; 1376 pieces of x: 8 per thread)
+    assert (plan.count, plan.nparts, plan.table_bytes) == (4, 2, 4 * B.STACK_ENTRY_BYTES)
+    a, b = plan.part[0], plan.part[1]
+    assert (a.count, a.mode, a.block_threads, a.forms, a.table_bytes) == (3, 0, 384, 5, 3 * B.STACK_ENTRY_BYTES)
+    assert (b.count, b.mode, b.block_threads, b.forms, b.x_pieces, b.table_bytes) == (1, 0, 256, 2, 8, B.STACK_ENTRY_BYTES)
+    assert a.grid_x >= 256 and 0 < a.lds_bytes <= 65536 and 0 < b.lds_bytes <= 65536
+    assert L.egt_gemv_stack_plan(items, 4, B.STACK_RESIDENT, None, 0, ctypes.byref(plan)) == 6   # no resident form at 1:4
     table = np.full(4 * B.STACK_ENTRY_BYTES, 0xA5, dtype=np.uint8)
     assert L.egt_gemv_stack_plan(items, 4, 0, table.ctypes.data, table.nbytes - 1, ctypes.byref(plan)) == 2
     assert np.all(table == 0xA5)
@@ -534,12 +538,14 @@ def test_stack_plan_checks_items_and_reports_the_launch_shape():
     assert L.egt_gemv_stack_run(None, ctypes.byref(plan), None) == 1
     assert L.egt_gemv_stack_run(24, ctypes.byref(plan), None) == 5
     for field, value in (("count", 0), ("block_threads", 100), ("block_threads", 2048), ("lds_bytes", 1 << 20), ("x_pieces", 3),
-                         ("forms", 0), ("forms", 8), ("mode", 2)):
-        broken = B.StackPlan.from_buffer_copy(plan)
-        setattr(broken, field, value)
-        assert L.egt_gemv_stack_run(16, ctypes.byref(broken), None) == 2, field
+                         ("forms", 0), ("forms", 8), ("forms", 3), ("mode", 2)):
+        for part in range(plan.nparts):
+            broken = B.StackPlan.from_buffer_copy(plan)
+            setattr(broken.part[part], field, value)
+            assert L.egt_gemv_stack_run(16, ctypes.byref(broken), None) == 2, (field, part)
     empty = B.StackPlan.from_buffer_copy(plan)
-    empty.grid_x = 0
+    for part in range(empty.nparts):
+        empty.part[part].grid_x = 0
     assert L.egt_gemv_stack_run(16, ctypes.byref(empty), None) == 0       # all matrices empty: nothing to launch
 
 
@@ -589,7 +595,11 @@ def test_stack_plan_cuts_a_large_table_into_row_blocks():
     assert L.egt_gemv_stack_plan(narrow, 1, B.STACK_RESIDENT, None, 0, ctypes.byref(plan)) == 6
     # inconsistent mode-1 plans are refused
     assert L.egt_gemv_stack_plan(items, 21, B.STACK_AUTO, None, 0, ctypes.byref(plan)) == 0
-    for field, value in (("nitems", 0), ("grid_x", plan.nitems + 1), ("table_bytes", 5), ("part_offset", 1 << 20)):
+    for field, value in (("nitems", 0), ("grid_x", plan.nitems + 1), ("table_bytes", 5), ("part_offset", 1 << 20), ("forms", 7)):
+        broken = B.StackPlan.from_buffer_copy(plan)
+        setattr(broken.part[0], field, value)
+        assert L.egt_gemv_stack_run(16, ctypes.byref(broken), None) == 2, field
+    for field, value in (("nparts", 0), ("nparts", 3), ("count", 20), ("table_bytes", plan.table_bytes + 16)):
         broken = B.StackPlan.from_buffer_copy(plan)
         setattr(broken, field, value)
         assert L.egt_gemv_stack_run(16, ctypes.byref(broken), None) == 2, field
