@@ -164,7 +164,8 @@ egt_status egt_sparse_gemm_smallm_ws_bytes(const egt_2bitcsr *w, int64_t ldx, in
   if (st != EGT_OK) return st;
   if (M < 1 || M > 64 || ldx < w->cols) return EGT_ERR_SHAPE;
   size_t need = 0;
-  if (w->rows > 0) egt::sparse_smallm_split_bytes(*w, ldx, M, need);
+  // (token rows of X off 16-byte boundaries: the split kernels do not apply, the call is the one-launch form)
+  if (w->rows > 0 && ldx % 8 == 0) egt::sparse_smallm_split_bytes(*w, ldx, M, need);
   *bytes = need;
   return EGT_OK;
 }

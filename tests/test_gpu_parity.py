@@ -553,6 +553,39 @@ def test_smallm_split_over_k_with_a_workspace(rows, cols, M):
     assert e.value.status == 2
 
 
+@pytest.mark.parametrize("rows,cols,M,ldx_pad,ldy_pad", [(2000, 8192, 40, 8, 3), (1000, 8192, 64, 16, 1), (8200, 1536, 33, 8, 4)])
+def test_smallm_split_with_strided_x_and_y(rows, cols, M, ldx_pad, ldy_pad):
+    # token rows of X and Y that do not follow each other: X rows on 16-byte boundaries (the
+    # form with X held in LDS), Y rows that do not allow 8-byte stores
+    torch = G.torch_mod()
+    print(f"case smallm split strided {rows}x{cols} M={M}", flush=True)
+    p, o = _small_case(rows, cols, 2, 128, 0, seed=5300 + rows)
+    X = synth.activation_rows(M, cols, 5300 + M)
+    pd = p.to("cuda")
+    need = B.smallm_ws_bytes(pd, M, cols + ldx_pad)
+    assert need > 0
+    ws = torch.full((need + 1024,), 0x5A, dtype=torch.uint8, device="cuda")
+    Xbuf = torch.full((M, cols + ldx_pad), float("nan"), dtype=torch.float16, device="cuda")
+    Xbuf[:, :cols] = G.to_dev(X.view(np.uint16)).view(torch.float16)
+    Ybuf = torch.full((M + 2, rows + ldy_pad), G.CANARY, dtype=torch.int16, device="cuda")
+    Y = Ybuf[1:M + 1, :rows].view(torch.float16)
+    B.sparse_gemm_smallm_ws(pd, Xbuf[:, :cols], Y, ws[:need])
+    torch.cuda.synchronize()
+    host = Ybuf.cpu().numpy().view(np.uint16)
+    assert np.all(host[0] == G.CANARY) and np.all(host[M + 1] == G.CANARY) and np.all(host[:, rows:] == G.CANARY)
+    assert torch.all(ws[need:] == 0x5A)
+    Y_ref, A_ref = O.gemm_smallm(o, X)
+    G.assert_close(host[1:M + 1, :rows].view(np.float16), Y_ref, A_ref, "split, strided")
+    # X rows that are not on 16-byte boundaries: the split form does not apply, the call still computes the product
+    Xodd = torch.zeros((M, cols + 2), dtype=torch.float16, device="cuda")
+    Xodd[:, :cols] = Xbuf[:, :cols]
+    assert B.smallm_ws_bytes(pd, M, cols + 2) == 0
+    Ybuf.fill_(G.CANARY)
+    B.sparse_gemm_smallm_ws(pd, Xodd[:, :cols], Y, None)
+    torch.cuda.synchronize()
+    G.assert_close(Ybuf.cpu().numpy().view(np.uint16)[1:M + 1, :rows].view(np.float16), Y_ref, A_ref, "one launch, odd ldx")
+
+
 def test_smallm_workspace_not_needed_where_the_split_does_not_pay():
     torch = G.torch_mod()
     for rows, cols, n, g, kind, M in ((11008, 4096, 2, 128, 0, 32), (4096, 4096, 2, 128, 0, 64), (4096, 11008, 2, 128, 0, 16), (300, 8192, 1, 128, 0, 40),
