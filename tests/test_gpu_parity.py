@@ -701,6 +701,49 @@ def test_seeded_sweep_of_sparse_shapes(block):
             G.assert_close(G.run_sparse_gemm(p, X, ldx_pad=pad, ldy_pad=pad), Y_ref, A_ref, what)
 
 
+@pytest.mark.parametrize("block", range(2))
+def test_seeded_sweep_of_the_workspace_form(block):
+    # the workspace entry point on shapes nobody picked by hand: whichever form the library
+    # chooses (X held in LDS, X fetched per workgroup, or no split), the product must be the
+    # oracle's, nothing may be written past the bytes it asked for, and a second run must
+    # give the same bits
+    torch = G.torch_mod()
+    rng = np.random.default_rng(4800 + block)
+    for case in range(10):
+        cols = int(rng.choice([512, 1024, 1536, 2048, 4096, 4352, 8192, 11008, 12288]))
+        rows = int(rng.choice([5, 16, 130, 1000, 2001, 4096, 8200, 9001]))
+        if rows * cols > 40_000_000:
+            rows = 40_000_000 // cols
+        M = int(rng.integers(17, 65))
+        g = int(rng.choice([64, 128, 256]))
+        if cols % g:
+            g = 128 if cols % 128 == 0 else 64
+        pad = int(rng.choice([0, 8, 24]))
+        what = f"workspace sweep {block}/{case}: {rows}x{cols} g={g} M={M} ldx=+{pad}"
+        print("case " + what, flush=True)
+        p, o = _small_case(rows, cols, 2, g, 0, seed=4800 + 100 * block + case)
+        X = synth.activation_rows(M, cols, 4800 + case)
+        pd = p.to("cuda")
+        need = B.smallm_ws_bytes(pd, M, cols + pad)
+        ws = torch.full((need + 512,), 0x5A, dtype=torch.uint8, device="cuda")
+        Xbuf = torch.zeros((M, cols + pad), dtype=torch.float16, device="cuda")
+        Xbuf[:, :cols] = G.to_dev(X.view(np.uint16)).view(torch.float16)
+        Ybuf = torch.full((M + 2, rows + 5), G.CANARY, dtype=torch.int16, device="cuda")
+        Y = Ybuf[1:M + 1, :rows].view(torch.float16)
+        outs = []
+        for rep in range(2):
+            B.sparse_gemm_smallm_ws(pd, Xbuf[:, :cols], Y, ws[:need] if need else None)
+            torch.cuda.synchronize()
+            host = Ybuf.cpu().numpy().view(np.uint16)
+            assert np.all(host[0] == G.CANARY) and np.all(host[M + 1] == G.CANARY) and np.all(host[:, rows:] == G.CANARY), what
+            assert torch.all(ws[need:] == 0x5A), what
+            outs.append(host[1:M + 1, :rows].copy())
+            ws[:need].fill_(0x77)
+        assert np.array_equal(outs[0], outs[1]), what
+        Y_ref, A_ref = O.gemm_smallm(o, X)
+        G.assert_close(outs[0].view(np.float16), Y_ref, A_ref, what)
+
+
 def test_seeded_sweep_of_dense_shapes():
     rng = np.random.default_rng(4500)
     for case in range(40):
