@@ -220,6 +220,50 @@ def test_mixed_table_in_one_launch_small_shapes():
         G.assert_close(y, refs[k][0], refs[k][1], f"4-wave table item {k}")
 
 
+@pytest.mark.parametrize("seed", range(3))
+def test_seeded_tables_equal_separate_calls(seed):
+    # tables nobody picked by hand: random storage forms, shapes and order, with and without 1:4
+    # members (one launch or two); every member bit for bit against its separate call
+    torch = G.torch_mod()
+    rng = np.random.default_rng(4900 + seed)
+    kinds = ["s24", "d", "s14"] if seed != 1 else ["s24", "d"]
+    colset = {"s24": [1024, 2048, 4096, 8192, 11008, 12288], "d": [1024, 2048, 4096, 8192, 11008], "s14": [2048, 4096, 8192, 11008]}
+    items, singles = [], []
+    for k in range(int(rng.integers(5, 12))):
+        kind = kinds[int(rng.integers(len(kinds)))]
+        cols = int(rng.choice(colset[kind]))
+        rows = int(rng.choice([0, 1, 15, 64, 200, 777, 1500])) if k else 333
+        print(f"  table {seed} item {k}: {kind} {rows}x{cols}", flush=True)
+        w = synth.weights(rows, cols, 4900 + 50 * seed + k)
+        xd = G.to_dev(synth.activations(cols, 4900 + k).view(np.uint16)).view(torch.float16)
+        ybuf = torch.full((rows + 128,), G.CANARY, dtype=torch.int16, device="cuda")
+        y = ybuf[64:64 + rows].view(torch.float16)
+        y1 = torch.zeros(rows, dtype=torch.float16, device="cuda")
+        if kind == "d":
+            q, qp = B.quant_int4(w, 128)
+            qd, qpd = G.to_dev(q), G.to_dev(qp)
+            items.append(("dense", qd, qpd, rows, cols, 128, xd, y))
+            B.int4_gemv(qd, qpd, rows, cols, 128, xd, y1)
+        else:
+            n = S.N_KEEP[kind]
+            p = B.pack_2bitcsr(w, B.prune_n4(w, n), n, 128, 0).to("cuda")
+            items.append(("sparse", p, xd, y))
+            B.sparse_gemv(p, xd, y1)
+        singles.append((ybuf, y1, rows))
+    call = B.prepared_gemv_stack(items)
+    has14 = any(it[0] == "sparse" and it[1].n_keep == 1 for it in items)
+    others = any(not (it[0] == "sparse" and it[1].n_keep == 1) for it in items)
+    assert call.plan.nparts == (2 if has14 and others else 1) and call.plan.count == len(items)
+    for rep in range(2):
+        call()
+        torch.cuda.synchronize()
+        for k, (ybuf, y1, rows) in enumerate(singles):
+            host = ybuf.cpu().numpy().view(np.uint16)
+            assert np.all(host[:64] == G.CANARY) and np.all(host[64 + rows:] == G.CANARY), ("write outside y", k)
+            assert np.array_equal(host[64:64 + rows], y1.cpu().numpy().view(np.uint16)), (seed, k)
+            ybuf[64:64 + rows].fill_(0)
+
+
 def test_row_block_list_on_ragged_shapes():
     # the resident-workgroup form on a table with row counts that are
     # no multiple of a row block, one, two and six tiles per row, a matrix shorter than one row
