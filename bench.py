@@ -454,6 +454,20 @@ def table(torch, B, synth, timer, dev, w, mask, xd, ys, calls, packed):
     f14 = [B.prepared_sparse_gemv(pk14[i], xd, ys[0]) for i in range(c14)]
     t["sparse_int4_1to4_11008x4096"] = entry(timer(lambda i: f14[i % c14](), 1000), algorithmic_bytes(R, K, 1, GRP, 0))
     del pk14, f14
+    # the same kernels on a matrix six times as tall (a 65536-word output projection): one launch
+    # moves 109 MB, so the launch gap that dominates the 18 MB headline weighs a sixth as much
+    Rt = 65536
+    wt = synth.weights(Rt, K, synth.seed_for(synth.HEADLINE, 7))
+    mask_t = B.prune_n4(wt, N)
+    yt = torch.empty(Rt, dtype=torch.float16, device=dev)
+    for tag, kind in (("sparse_int4_65536x4096", B.VAL_INT4), ("sparse_int4_65536x4096_paired_nibble_order", B.VAL_INT4_PAIRED)):
+        pt = B.pack_2bitcsr(wt, mask_t, N, GRP, kind)
+        ct = max(2, -(-2 * LLC_BYTES // pt.nbytes()))
+        pkt = [pt.to(dev) for _ in range(ct)]
+        ft = [B.prepared_sparse_gemv(pkt[i], xd, yt) for i in range(ct)]
+        t[tag] = entry(timer(lambda i: ft[i % ct](), 300), algorithmic_bytes(Rt, K, N, GRP, 0))
+        del pkt, ft, pt
+    del wt, mask_t
     # rows of different lengths: half of the rows keep 1 of 4 (Sec. 3.2's adaptive N inside one
     # matrix); the slot-by-slot kernel that follows row_ptr, not a matrix-core path
     rng = np.random.default_rng(synth.seed_for(synth.HEADLINE))

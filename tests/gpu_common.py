@@ -94,7 +94,7 @@ def row_subset(p: B.Packed, rows: np.ndarray) -> dict:
     """Oracle-side view of a few rows of a library-packed matrix (slices of the
     row-major buffers with a rebased row_ptr)."""
     S = p.n_keep * p.cols // 4
-    vb = S // 2 if p.val_kind == B.VAL_INT4 else 2 * S
+    vb = 2 * S if p.val_kind == B.VAL_FP16 else S // 2
     values = np.concatenate([p.values[r * vb:(r + 1) * vb] for r in rows])
     idx = np.concatenate([p.idx[r * (S // 8):(r + 1) * (S // 8)] for r in rows])
     qp = None if p.qparams is None else p.qparams[rows]

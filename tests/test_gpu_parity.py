@@ -222,6 +222,28 @@ def test_full_size_sampled_rows(name, rows, cols, kind, g, cfg):
         G.assert_close(y[rr], yr, ar, f"{name} rows {r0}..")
 
 
+@pytest.mark.parametrize("kind", [0, 2])
+def test_tall_matrix_sampled_rows(kind):
+    # 65536 x 4096 (the launch-amortised row of the bench table), both nibble orders: sampled rows
+    # against the oracle's own packing of them, and the last slab decoded from the library's bytes
+    rows, cols = 65536, 4096
+    print(f"case tall {rows}x{cols} kind={kind}", flush=True)
+    seed = synth.seed_for(synth.HEADLINE, 7)
+    w, mask, p = G.packed_full(rows, cols, 2, 128, kind, seed)
+    x = synth.activations(cols, seed)
+    y = G.run_sparse_gemv(p, x)
+    pick = G.sample_rows(rows, 256, seed)
+    o = O.pack_2bitcsr(w[pick], O.prune_n4_magnitude(w[pick], 2), 2, 128, kind)
+    sub = G.row_subset(p, pick)
+    for k in ("values", "idx", "qparams"):
+        assert np.array_equal(o[k], sub[k]), k
+    y_ref, a_ref = O.gemv(o, x)
+    G.assert_close(y[pick], y_ref, a_ref, "tall, sampled")
+    rr = np.arange(rows - 1024, rows)
+    yr, ar = O.gemv(G.row_subset(p, rr), x)
+    G.assert_close(y[rr], yr, ar, "tall, last rows")
+
+
 # ---------------------------------------------------------------- paired nibble order
 @pytest.mark.parametrize("rows,cols,n,g", [
     (257, 4096, 2, 128), (45, 4096, 2, 64), (21, 11008, 2, 128), (70, 1024, 2, 128), (70, 2048, 2, 256), (33, 8192, 2, 128),
