@@ -39,6 +39,9 @@ def _small_case(rows, cols, n, g, kind, seed, drop=0.0):
     (3, 40960, 2, 128, 0), (3, 36864, 1, 128, 0), (2, 65536, 2, 0, 1),
     # 1:4 with FP16 values: one, two and four load instructions per row, two phases, a partly filled one
     (70, 2048, 1, 0, 1), (133, 4096, 1, 0, 1), (40, 8192, 1, 0, 1), (37, 11008, 1, 0, 1), (18, 16384, 1, 0, 1), (9, 20608, 1, 0, 1),
+    # the slot-by-slot kernel past the first 128 columns of its LDS layout: every kept count, with a word of
+    # eight slots inside one quantisation group (16, 8, 32 columns) and across three (12 columns, 3 of 4 kept)
+    (9, 4128, 2, 16, 0), (6, 4128, 3, 12, 0), (5, 4160, 4, 8, 0), (5, 4128, 1, 32, 0), (5, 4128, 1, 16, 0),
 ])
 def test_sparse_gemv_small(rows, cols, n, g, kind):
     print(f"case sparse_gemv {rows}x{cols} n={n} g={g} kind={kind}", flush=True)
@@ -321,6 +324,9 @@ def _ragged_case(rows, cols, g, kind, seed, choices=(1, 2), drop=0.0):
 @pytest.mark.parametrize("rows,cols,g,kind,choices", [
     (37, 96, 32, 0, (1, 2)), (64, 4096, 128, 0, (1, 2)), (130, 1056, 96, 0, (1, 2, 3, 4)), (45, 4096, 0, 1, (1, 2)),
     (21, 11008, 128, 0, (1, 2)), (9, 2112, 12, 0, (2, 4)), (3, 40960, 128, 0, (1, 2)), (1, 32, 32, 0, (1,)),
+    # x at the 64 KB LDS limit of the one-token kernel; groups
+    # of 20 columns (a word of eight slots then spans up to three groups at 1:4); the paired nibble order
+    (5, 32768, 128, 0, (1, 2, 3, 4)), (40, 4160, 20, 0, (1, 2, 3, 4)), (33, 2048, 64, 2, (1, 2, 4)),
 ])
 @pytest.mark.parametrize("M", [1, 5])
 def test_ragged_rows_small(rows, cols, g, kind, choices, M):
