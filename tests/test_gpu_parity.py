@@ -729,6 +729,49 @@ def test_seeded_sweep_of_sparse_shapes(block):
             G.assert_close(G.run_sparse_gemm(p, X, ldx_pad=pad, ldy_pad=pad), Y_ref, A_ref, what)
 
 
+def test_seeded_sweep_of_row_lengths_nibble_orders_and_narrow_groups():
+    # the same for what the sweep above leaves out: rows of different lengths, the paired nibble
+    # order, quantisation groups down to four columns
+    rng = np.random.default_rng(4700)
+    for case in range(36):
+        rows = int(rng.integers(1, 300))
+        cols = 32 * int(rng.integers(1, 300))
+        if rng.random() < 0.3:
+            cols = int(rng.choice([4096, 11008, 8192, 1024, 2048, 4160, 12288, 16384]))
+        kind = int(rng.choice([0, 0, 1, 2]))
+        g = 0 if kind == 1 else int(rng.choice([g for g in (4, 8, 12, 16, 20, 24, 32, 64, 96, 128, 256, 512, cols) if cols % g == 0]))
+        ragged = rng.random() < 0.5
+        M = 1 if rng.random() < 0.5 else int(rng.choice([2, 3, 4, 5, 8, 16, 17, 33, 64]))
+        w = synth.weights(rows, cols, 4700 + case)
+        if ragged:
+            choices = [(1, 2), (1, 2, 3, 4), (2, 4), (3,), (1,)][int(rng.integers(0, 5))]
+            nk = rng.choice(choices, size=rows).astype(np.int32)
+            mask = np.zeros((rows, cols), dtype=np.uint8)
+            for n in np.unique(nk):
+                mask[nk == n] = B.prune_n4(np.ascontiguousarray(w[nk == n]), int(n))
+        else:
+            n = int(rng.choice([1, 2, 2, 3, 4]))
+            mask = B.prune_n4(w, n)
+        if rng.random() < 0.3:
+            mask = (mask & (rng.random(mask.shape) >= 0.3)).astype(np.uint8)
+        what = f"sweep {case}: {rows}x{cols} kind={kind} g={g} M={M} " + (f"rows keep {choices}" if ragged else f"n={n}")
+        print("case " + what, flush=True)
+        if ragged:
+            p, o = B.pack_2bitcsr_rows(w, mask, nk, g, kind), O.pack_2bitcsr_rows(w, mask, nk, g, kind)
+        else:
+            p, o = B.pack_2bitcsr(w, mask, n, g, kind), O.pack_2bitcsr(w, mask, n, g, kind)
+        for k in ("values", "idx", "qparams", "row_ptr"):
+            assert (getattr(p, k) is None and o[k] is None) or np.array_equal(getattr(p, k), o[k]), what + " " + k
+        if M == 1:
+            x = synth.activations(cols, 4700 + case)
+            y_ref, a_ref = (O.gemv_rows if ragged else O.gemv)(o, x)
+            G.assert_close(G.run_sparse_gemv(p, x), y_ref, a_ref, what)
+        else:
+            X = synth.activation_rows(M, cols, 4700 + case)
+            Y_ref, A_ref = (O.gemm_rows if ragged else O.gemm_smallm)(o, X)
+            G.assert_close(G.run_sparse_gemm(p, X), Y_ref, A_ref, what)
+
+
 @pytest.mark.parametrize("block", range(2))
 def test_seeded_sweep_of_the_workspace_form(block):
     # the workspace entry point on shapes nobody picked by hand: whichever form the library
