@@ -253,7 +253,7 @@ def main():
         stk = S.LayerStack.build(dev, distinct_layers=1)     # the traffic of all 224 matrices; the numbers repeat
         whole = stk.one_launch()
         plan = whole.plan
-        row = entry(timer(lambda i: whole(), 10, 2), stk.nbytes)
+        row = entry(timer(lambda i: whole(), 30, 5), stk.nbytes)
         row.update(mode=plan.mode, grid=plan.grid_x, block_threads=plan.block_threads, lds_bytes=plan.lds_bytes, items=plan.nitems)
         print(json.dumps({"only_stack": True, "config4_whole_stack": row}))
         return
@@ -570,7 +570,7 @@ def table(torch, B, synth, timer, dev, w, mask, xd, ys, calls, packed):
                 c()
         row["launches_32_one_per_layer"] = entry(timer(run_layers, 10, 2), stk.nbytes)
         whole = stk.one_launch()
-        row["one_call_whole_stack"] = entry(timer(lambda i: whole(), 10, 2), stk.nbytes)
+        row["one_call_whole_stack"] = entry(timer(lambda i: whole(), 30, 5), stk.nbytes)
         row["one_call_whole_stack"]["launches"] = whole.plan.nparts      # 1:4 layers run as a launch of their own
         if plan == "config4":
             with torch.cuda.stream(side):

@@ -64,13 +64,16 @@ __global__ __launch_bounds__(1024) void k_gemv_stack(const uint8_t *__restrict__
 
 static_assert(sizeof(StreamItem) == 16, "item layout");
 static_assert(sizeof(StreamMatrix) <= EGT_STACK_ENTRY_BYTES, "descriptor larger than the published entry size");
+// Tiles in flight per wave.  Two 12-wave workgroups fit a compute unit only at 80 registers a
+// lane or fewer (6 waves per SIMD); deeper rings (3 and 4) took 86 - 92 and left one workgroup
+// resident: 590 us for the 7B stack against 520 with these.
 #ifndef EGT_STREAM_DEPTH_S
-#define EGT_STREAM_DEPTH_S 3
+#define EGT_STREAM_DEPTH_S 2
 #endif
 #ifndef EGT_STREAM_DEPTH_D
-#define EGT_STREAM_DEPTH_D 4
+#define EGT_STREAM_DEPTH_D 3
 #endif
-constexpr int STREAM_DEPTH_S = EGT_STREAM_DEPTH_S;    // tiles in flight per wave, 2:4 (28 B per lane and tile)
+constexpr int STREAM_DEPTH_S = EGT_STREAM_DEPTH_S;    // 2:4 (28 B per lane and tile)
 constexpr int STREAM_DEPTH_D = EGT_STREAM_DEPTH_D;    // dense INT4 (20 B per lane and tile)
 constexpr int DEVICE_CUS = 256;                       // compute units of an MI355X
 // bytes of the per-workgroup first-item array of a table for `nblocks` resident workgroups
@@ -79,8 +82,14 @@ __host__ __device__ constexpr size_t stream_first_bytes(int nblocks) { return ((
 // Resident workgroups walking the work items of a table (see egt_stream_body.h).  The table:
 // `count` matrix descriptors, the first item of every workgroup (gridDim.x + 1 words, padded
 // to 16 bytes), the items.
+// (the second launch bound: waves per SIMD the register allocation has to leave room for - two
+//  workgroups of 12 waves; with 8 pieces of x per thread, rows wider than 12288 columns, that
+//  would spill, and one workgroup stays resident)
+#ifndef EGT_STREAM_WAVES_PER_SIMD
+#define EGT_STREAM_WAVES_PER_SIMD 6
+#endif
 template <int XP, int FORMS>
-__global__ __launch_bounds__(768) void k_gemv_stream(const uint8_t *__restrict__ table, int count, int part_offset,
+__global__ __launch_bounds__(768, XP <= 4 ? EGT_STREAM_WAVES_PER_SIMD : 3) void k_gemv_stream(const uint8_t *__restrict__ table, int count, int part_offset,
                                                      int nthreads, int nblocks) {
   // (block and grid size come in as arguments: read through the dispatch packet they would
   //  be loaded again for every item)
@@ -147,11 +156,10 @@ bool plan_stream(const egt_gemv_item *items, const std::vector<ItemShape> &shape
                  int count, int nwaves, bool whatever_the_size, std::vector<StreamMatrix> &mats, std::vector<uint32_t> &first,
                  std::vector<StreamItem> &work, egt_stack_part &plan) {
   std::vector<uint64_t> row_bytes_of;
-  int force = -1, bpc = 2, item_kb = 4096;
-  tune_pair("EGT_STREAM_TUNE", force, bpc);
+  int force = -1, bpc = 0, item_kb = 4096;
+  tune_pair("EGT_STREAM_TUNE", force, bpc);             // developer build: 1 = whatever the size; workgroups per compute unit
   { int unused = 0; tune_pair("EGT_STREAM_ITEM", item_kb, unused); }
   if (force == 0 || nwaves == 0) return false;
-  bpc = bpc < 1 ? 1 : bpc > 4 ? 4 : bpc;
   item_kb = item_kb < 16 ? 16 : item_kb > 4096 ? 4096 : item_kb;
   uint64_t total = 0;
   int forms = 0;
@@ -215,6 +223,11 @@ bool plan_stream(const egt_gemv_item *items, const std::vector<ItemShape> &shape
   if (lds > 64 * 1024) return false;
   // spans of equal byte count, one per workgroup, in table order: workgroup b streams the
   // bytes [b, b + 1) * total / blocks of the concatenated matrices (cut at row boundaries)
+  // Two to eight workgroups per compute unit, two of them resident at a time: spans of about
+  // 1.4 MB (x is staged once per item, so a span should hold many rows; shorter spans finish
+  // more evenly: the 3 GB stack takes 546 us with 512 spans, 530 with 1024, 520 with 2048).
+  if (bpc < 1) bpc = (int)((total + (179ull << 20)) / (358ull << 20));
+  bpc = bpc < 2 ? 2 : bpc > 8 ? 8 : bpc;
   int blocks = DEVICE_CUS * bpc;
   first.assign(1, 0u);
   uint64_t done = 0;                                   // bytes of the rows handed out so far
@@ -288,8 +301,8 @@ egt_status plan_part(const egt_gemv_item *items, int count, int form, void *tabl
   std::vector<StreamMatrix> mats;
   std::vector<StreamItem> work;
   std::vector<uint32_t> first;
-  // resident workgroups: the largest of 12, 8, 6, 4 waves that every item's phases divide (two
-  // workgroups per compute unit; a big workgroup stages x once for many rows)
+  // streaming workgroups: the largest of 12, 8, 6, 4 waves that every item's phases divide (two
+  // workgroups resident per compute unit; a big workgroup stages x once for many rows)
   int swaves = 0, swant = 12, sunused = 0;
   tune_pair("EGT_STREAM_WAVES", swant, sunused);
   for (int cand : {12, 8, 6, 4}) {
@@ -425,7 +438,7 @@ egt_status egt_gemv_stack_run(const void *table_dev, const egt_stack_plan *plan,
         (q.forms != 1 && q.forms != 2 && q.forms != 4 && q.forms != 5))   // 2:4 and dense together, 1:4 alone
       return EGT_ERR_SHAPE;
     if (q.mode == 0 && q.table_bytes != (uint64_t)q.count * EGT_STACK_ENTRY_BYTES) return EGT_ERR_SHAPE;
-    if (q.mode == 1 && (q.nitems < 1 || q.grid_x < 1 || q.grid_x > 4 * DEVICE_CUS || (q.forms & 2) || q.block_threads > 768 ||
+    if (q.mode == 1 && (q.nitems < 1 || q.grid_x < 1 || q.grid_x > 8 * DEVICE_CUS || (q.forms & 2) || q.block_threads > 768 ||
                         q.part_offset < 0 || q.part_offset > q.lds_bytes ||
                         q.table_bytes != (uint64_t)q.count * EGT_STACK_ENTRY_BYTES + stream_first_bytes(q.grid_x) +
                                              16ull * (uint64_t)q.nitems))

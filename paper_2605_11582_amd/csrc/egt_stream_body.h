@@ -5,9 +5,10 @@
 // waits, computes, and leaves.  That is the right shape for a matrix of a few megabytes -
 // the whole matrix is on its way within a microsecond - but as a stream of short-lived
 // workgroups it leaves the memory system idle whenever a workgroup starts up or drains.
-// Here a fixed number of workgroups (two per compute unit) stays resident.  The planner cuts
-// the concatenation of all matrices into as many spans of equal byte count as there are
-// workgroups, so a workgroup streams one contiguous stretch of the table; a span is a short
+// Here the planner cuts the concatenation of all matrices into spans of equal byte count, one
+// per workgroup (eight per compute unit, two of them resident at a time: 24 waves, each with
+// its own requests in flight; spans this short also even out the finish), so a workgroup
+// streams one contiguous stretch of the table; a span is a short
 // list of work items, an item being a block of consecutive rows of one matrix.  Per item the
 // workgroup stages x in LDS once; every wave then owns one tile column of the rows (a
 // "phase": 4096 dense columns at 2:4, 2048 for dense INT4), keeps the B operand of that

@@ -559,7 +559,7 @@ def test_stack_plan_cuts_a_large_table_into_row_blocks():
     plan = B.StackPlan()
     assert L.egt_gemv_stack_plan(items, 21, B.STACK_AUTO, None, 0, ctypes.byref(plan)) == 0
     assert (plan.mode, plan.block_threads, plan.forms) == (1, 768, 5)      # tiles per row 1, 2, 3, 6: twelve waves
-    assert plan.grid_x == 512 and plan.nitems >= plan.grid_x
+    assert plan.grid_x == 512 and plan.nitems >= plan.grid_x               # 300 MB: two spans per compute unit
     first_bytes = (4 * (plan.grid_x + 1) + 15) // 16 * 16
     assert plan.table_bytes == 21 * B.STACK_ENTRY_BYTES + first_bytes + 16 * plan.nitems
     table = np.zeros(plan.table_bytes, dtype=np.uint8)
