@@ -315,8 +315,8 @@ typedef struct {
  * allocates nothing) and may run it any number of times.  Nothing is written when an
  * error is returned.  Items with rows == 0 are legal and compute nothing.
  * `form`: EGT_STACK_AUTO picks mode 1 for tables of 2:4 and dense INT4 matrices with at
- * least 2048 (dense) or 4096 (2:4) columns that hold 256 MB or more (below that a workgroup
- * would see too few rows to make staying resident pay) and mode 0 otherwise; EGT_STACK_GRID
+ * least 2048 (dense) or 4096 (2:4) columns that hold 32 MB or more (below that a workgroup
+ * would see too few rows to make walking a list pay) and mode 0 otherwise; EGT_STACK_GRID
  * and EGT_STACK_RESIDENT ask for mode 0 or mode 1 (EGT_ERR_UNSUPPORTED if the shapes do not
  * allow mode 1).  Mode 1 sizes the launch for the 256 compute units of an MI355X.  The
  * form is chosen per part: 1:4 matrices always run in mode 0 (with EGT_STACK_RESIDENT they

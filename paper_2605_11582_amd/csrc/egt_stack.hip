@@ -217,7 +217,9 @@ bool plan_stream(const egt_gemv_item *items, const std::vector<ItemShape> &shape
     const int need = (lds_pieces + 64 * nwaves - 1) / (64 * nwaves);
     xp = need > xp ? need : xp;
   }
-  if (force != 1 && !whatever_the_size && total < (256ull << 20)) return false;   // smaller tables: one-shot workgroups are faster
+  // smaller tables: one-shot workgroups are as fast or faster (20 MB: 6.9 against 7.4 us; 37 MB: 9.8 against 9.5;
+  // 48 MB: 13.1 against 11.4; a decoder layer of 83 MB: 23.6 against 17.7)
+  if (force != 1 && !whatever_the_size && total < (32ull << 20)) return false;
   if (xp > 8 || total == 0) return false;
   const size_t lds = x_bytes + sizeof(float) * part_floats;
   if (lds > 64 * 1024) return false;
@@ -226,8 +228,9 @@ bool plan_stream(const egt_gemv_item *items, const std::vector<ItemShape> &shape
   // Two to eight workgroups per compute unit, two of them resident at a time: spans of about
   // 1.4 MB (x is staged once per item, so a span should hold many rows; shorter spans finish
   // more evenly: the 3 GB stack takes 546 us with 512 spans, 530 with 1024, 520 with 2048).
-  if (bpc < 1) bpc = (int)((total + (179ull << 20)) / (358ull << 20));
-  bpc = bpc < 2 ? 2 : bpc > 8 ? 8 : bpc;
+  // below 72 MB one span per compute unit
+  if (bpc < 1) { bpc = (int)((total + (179ull << 20)) / (358ull << 20)); bpc = total < (72ull << 20) ? 1 : bpc < 2 ? 2 : bpc; }
+  bpc = bpc < 1 ? 1 : bpc > 8 ? 8 : bpc;
   int blocks = DEVICE_CUS * bpc;
   first.assign(1, 0u);
   uint64_t done = 0;                                   // bytes of the rows handed out so far

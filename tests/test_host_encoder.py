@@ -492,10 +492,11 @@ def _fake_items(views, dense=()):
 
 def test_stack_plan_checks_items_and_reports_the_launch_shape():
     L = B.lib()
-    view = B.View(4096, 4096, 2, 128, 0, 16, 16, 16, 16)          # fake aligned device pointers, never used
-    down = B.View(4096, 11008, 2, 128, 0, 16, 16, 16, 16)
-    one4 = B.View(4096, 11008, 1, 128, 0, 16, 16, 16, 16)
-    items = _fake_items([view, down, one4], [(4096, 11008, 128)])
+    # (25 MB of 2:4 and dense matrices: below the 32 MB from which a table is streamed)
+    view = B.View(2048, 4096, 2, 128, 0, 16, 16, 16, 16)          # fake aligned device pointers, never used
+    down = B.View(2048, 11008, 2, 128, 0, 16, 16, 16, 16)
+    one4 = B.View(2048, 11008, 1, 128, 0, 16, 16, 16, 16)
+    items = _fake_items([view, down, one4], [(2048, 11008, 128)])
     plan = B.StackPlan()
     assert L.egt_gemv_stack_plan(items, 4, 0, None, 0, ctypes.byref(plan)) == 0          # size query
     # two launches: the 2:4 and dense matrices (tiles per row 1, 3 and 6: six waves), and the 1:4
@@ -504,7 +505,7 @@ def test_stack_plan_checks_items_and_reports_the_launch_shape():
     a, b = plan.part[0], plan.part[1]
     assert (a.count, a.mode, a.block_threads, a.forms, a.table_bytes) == (3, 0, 384, 5, 3 * B.STACK_ENTRY_BYTES)
     assert (b.count, b.mode, b.block_threads, b.forms, b.x_pieces, b.table_bytes) == (1, 0, 256, 2, 8, B.STACK_ENTRY_BYTES)
-    assert a.grid_x >= 256 and 0 < a.lds_bytes <= 65536 and 0 < b.lds_bytes <= 65536
+    assert a.grid_x >= 128 and 0 < a.lds_bytes <= 65536 and 0 < b.lds_bytes <= 65536
     assert L.egt_gemv_stack_plan(items, 4, B.STACK_RESIDENT, None, 0, ctypes.byref(plan)) == 6   # no resident form at 1:4
     table = np.full(4 * B.STACK_ENTRY_BYTES, 0xA5, dtype=np.uint8)
     assert L.egt_gemv_stack_plan(items, 4, 0, table.ctypes.data, table.nbytes - 1, ctypes.byref(plan)) == 2
@@ -514,7 +515,7 @@ def test_stack_plan_checks_items_and_reports_the_launch_shape():
     # errors leave table and plan untouched
     table[:] = 0xA5
     plan2 = B.StackPlan(-1)
-    bad = B.View(4096, 4096, 2, 0, 1, 16, 16, 16, None)                # FP16 values: no multi-matrix form
+    bad = B.View(2048, 4096, 2, 0, 1, 16, 16, 16, None)                # FP16 values: no multi-matrix form
     items[1].sparse = ctypes.pointer(bad)
     assert L.egt_gemv_stack_plan(items, 4, 0, table.ctypes.data, table.nbytes, ctypes.byref(plan2)) == 6
     assert np.all(table == 0xA5) and plan2.count == -1
