@@ -282,7 +282,7 @@ enum { EGT_STACK_AUTO = 0, EGT_STACK_GRID = 1, EGT_STACK_RESIDENT = 2 };
  * part.  A table that holds 1:4 matrices beside others is two: the 1:4 kernel body needs
  * twice the registers of the others, and a kernel that carries every body runs every
  * matrix at the occupancy of the widest one (the three-way mix of a 7B stack: 783 us in
- * one kernel, 540 us in two).  The parts' tables follow each other in the table. */
+ * one kernel, 480 us in two).  The parts' tables follow each other in the table. */
 typedef struct {
   int32_t count;         /* matrices of the part                                             */
   int32_t mode;          /* 0: one grid of short-lived workgroups per matrix;
@@ -319,8 +319,8 @@ typedef struct {
  * would see too few rows to make walking a list pay) and mode 0 otherwise; EGT_STACK_GRID
  * and EGT_STACK_RESIDENT ask for mode 0 or mode 1 (EGT_ERR_UNSUPPORTED if the shapes do not
  * allow mode 1).  Mode 1 sizes the launch for the 256 compute units of an MI355X.  The
- * form is chosen per part: 1:4 matrices always run in mode 0 (with EGT_STACK_RESIDENT they
- * are EGT_ERR_UNSUPPORTED), the other part of the same table in mode 1 if it qualifies. */
+ * form is chosen per part (with EGT_STACK_RESIDENT every part has to allow mode 1); 1:4
+ * matrices take mode 1 with 2048, 4096 or 8192 to 16384 columns and groups of 128 and more. */
 egt_status egt_gemv_stack_plan(const egt_gemv_item *items, int count, int form, void *table,
                                size_t table_bytes, egt_stack_plan *plan);
 

@@ -88,8 +88,9 @@ __host__ __device__ constexpr size_t stream_first_bytes(int nblocks) { return ((
 #ifndef EGT_STREAM_WAVES_PER_SIMD
 #define EGT_STREAM_WAVES_PER_SIMD 6
 #endif
+// (1:4 tables, FORMS == 2: workgroups of 8 waves at up to 128 registers, two resident)
 template <int XP, int FORMS>
-__global__ __launch_bounds__(768, XP <= 4 ? EGT_STREAM_WAVES_PER_SIMD : 3) void k_gemv_stream(const uint8_t *__restrict__ table, int count, int part_offset,
+__global__ __launch_bounds__(768, FORMS == 2 ? 4 : XP <= 4 ? EGT_STREAM_WAVES_PER_SIMD : 3) void k_gemv_stream(const uint8_t *__restrict__ table, int count, int part_offset,
                                                      int nthreads, int nblocks) {
   // (block and grid size come in as arguments: read through the dispatch packet they would
   //  be loaded again for every item)
@@ -156,6 +157,7 @@ bool plan_stream(const egt_gemv_item *items, const std::vector<ItemShape> &shape
                  int count, int nwaves, bool whatever_the_size, std::vector<StreamMatrix> &mats, std::vector<uint32_t> &first,
                  std::vector<StreamItem> &work, egt_stack_part &plan) {
   std::vector<uint64_t> row_bytes_of;
+  std::vector<int> rpt_of;
   int force = -1, bpc = 0, item_kb = 4096;
   tune_pair("EGT_STREAM_TUNE", force, bpc);             // developer build: 1 = whatever the size; workgroups per compute unit
   { int unused = 0; tune_pair("EGT_STREAM_ITEM", item_kb, unused); }
@@ -171,7 +173,8 @@ bool plan_stream(const egt_gemv_item *items, const std::vector<ItemShape> &shape
     const StackEntry &e = block_entries[k];
     StreamMatrix &m = mats[k];
     uint64_t row_bytes;
-    int lds_pieces, pad_shift;
+    int lds_pieces, pad_shift, rpt = 1;                 // rpt: rows of a tile (1:4 with short rows: 2 or 4)
+    m.mr_shift = -1;
     if (e.form == FORM_S24) {
       const M1Geom &g = e.g.s24;
       if (g.mr_shift >= 0) return false;
@@ -192,6 +195,18 @@ bool plan_stream(const egt_gemv_item *items, const std::vector<ItemShape> &shape
       m.qp_bytes = (uint32_t)(4ull * (uint64_t)shapes[k].rows * (uint64_t)g.groups_per_row);
       row_bytes = (uint64_t)shapes[k].cols / 2 + 4ull * g.groups_per_row;
       lds_pieces = g.phases * 256; pad_shift = 4;
+    } else if (e.form == FORM_S14) {
+      const M1N1Geom &g = e.g.s14;
+      const egt_2bitcsr &w = shapes[k].w;
+      m.row_ptr = w.row_ptr; m.values = (const uint8_t *)w.values; m.idx = (const uint8_t *)w.idx; m.qparams = (const uint8_t *)w.qparams;
+      m.rows = g.rows; m.nchunks = g.nchunks; m.phases = g.phases; m.gshift = g.gshift; m.groups_per_row = g.groups_per_row;
+      const uint64_t slots = (uint64_t)w.rows * (uint64_t)(w.cols / 4);
+      m.val_bytes = (uint32_t)(slots / 2); m.idx_bytes = (uint32_t)(slots / 4);
+      m.qp_bytes = (uint32_t)(4ull * (uint64_t)w.rows * (uint64_t)g.groups_per_row);
+      row_bytes = (uint64_t)w.cols / 8 + w.cols / 16 + 4ull * g.groups_per_row;
+      lds_pieces = g.mr_shift >= 0 ? g.nchunks * 16 : g.phases * 1024; pad_shift = 6;
+      rpt = g.mr_shift >= 0 ? 64 >> g.mr_shift : 1;
+      m.mr_shift = g.mr_shift;
     } else {
       return false;
     }
@@ -201,18 +216,19 @@ bool plan_stream(const egt_gemv_item *items, const std::vector<ItemShape> &shape
     // rows of an item at most: what the partial sums of an item may take in LDS (24 KB), a
     // whole number of rows per wave
     const int wpp = nwaves / m.phases;
-    int cap = (24 * 1024) / (16 * m.phases);
+    int cap = (24 * 1024) / (16 * m.phases) * rpt;
     if (cap > STREAM_MAX_ITEM_ROWS) cap = STREAM_MAX_ITEM_ROWS;
     const uint64_t by_bytes = ((uint64_t)item_kb * 1024 + row_bytes - 1) / row_bytes;
     if ((uint64_t)cap > by_bytes) cap = (int)by_bytes;
-    cap -= cap % wpp;
-    if (cap < wpp) return false;
+    cap -= cap % (wpp * rpt);
+    if (cap < wpp * rpt) return false;
     m.item_rows = cap;
+    rpt_of.push_back(rpt);
     row_bytes_of.push_back(row_bytes);
     total += (uint64_t)m.rows * row_bytes;
     const size_t xb = 16 * (size_t)lds_pieces + 16 * (size_t)((lds_pieces + (1 << pad_shift) - 1) >> pad_shift);
     x_bytes = xb > x_bytes ? xb : x_bytes;
-    const size_t pf = 4 * (size_t)m.phases * (size_t)m.item_rows;
+    const size_t pf = 4 * (size_t)m.phases * (size_t)(m.item_rows / rpt);
     part_floats = pf > part_floats ? pf : part_floats;
     const int need = (lds_pieces + 64 * nwaves - 1) / (64 * nwaves);
     xp = need > xp ? need : xp;
@@ -229,7 +245,8 @@ bool plan_stream(const egt_gemv_item *items, const std::vector<ItemShape> &shape
   // 1.4 MB (x is staged once per item, so a span should hold many rows; shorter spans finish
   // more evenly: the 3 GB stack takes 546 us with 512 spans, 530 with 1024, 520 with 2048).
   // below 72 MB one span per compute unit
-  if (bpc < 1) { bpc = (int)((total + (179ull << 20)) / (358ull << 20)); bpc = total < (72ull << 20) ? 1 : bpc < 2 ? 2 : bpc; }
+  // (1:4: two at least - its workgroups have 8 waves, and one per compute unit would leave half the waves out)
+  if (bpc < 1) { bpc = (int)((total + (179ull << 20)) / (358ull << 20)); bpc = (total < (72ull << 20) && forms != 2) ? 1 : bpc < 2 ? 2 : bpc; }
   bpc = bpc < 1 ? 1 : bpc > 8 ? 8 : bpc;
   int blocks = DEVICE_CUS * bpc;
   first.assign(1, 0u);
@@ -246,6 +263,8 @@ bool plan_stream(const egt_gemv_item *items, const std::vector<ItemShape> &shape
       int n = m.rows - r;
       if ((uint64_t)n > room_rows && b + 1 < blocks) n = (int)room_rows;
       if (n > m.item_rows) n = m.item_rows;
+      if (n % rpt_of[k]) n += rpt_of[k] - n % rpt_of[k];                     // an item starts on a tile (item_rows is a multiple)
+      if (n > m.rows - r) n = m.rows - r;
       work.push_back(StreamItem{(uint32_t)k, (uint32_t)r, (uint32_t)n, 0u});
       r += n;
       done += (uint64_t)n * rb;
@@ -306,8 +325,10 @@ egt_status plan_part(const egt_gemv_item *items, int count, int form, void *tabl
   std::vector<uint32_t> first;
   // streaming workgroups: the largest of 12, 8, 6, 4 waves that every item's phases divide (two
   // workgroups resident per compute unit; a big workgroup stages x once for many rows)
+  // (1:4 matrices: 8 waves at most, so that two workgroups fit the registers of their body)
   int swaves = 0, swant = 12, sunused = 0;
   tune_pair("EGT_STREAM_WAVES", swant, sunused);
+  if (shapes[0].form == FORM_S14 && swant > 8) swant = 8;
   for (int cand : {12, 8, 6, 4}) {
     bool ok = cand <= swant;
     for (int k = 0; k < count && ok; ++k) ok = cand % shapes[k].phases == 0;
@@ -399,7 +420,6 @@ egt_status egt_gemv_stack_plan(const egt_gemv_item *items, int count, int form, 
     group[shape.form == FORM_S14 ? 1 : 0].push_back(items[k]);
   }
   if (group[0].empty()) group[0].swap(group[1]);
-  if (form == EGT_STACK_RESIDENT && !group[1].empty()) return EGT_ERR_UNSUPPORTED;
   egt_stack_plan out;
   std::memset(&out, 0, sizeof(out));
   out.count = count;
@@ -441,7 +461,7 @@ egt_status egt_gemv_stack_run(const void *table_dev, const egt_stack_plan *plan,
         (q.forms != 1 && q.forms != 2 && q.forms != 4 && q.forms != 5))   // 2:4 and dense together, 1:4 alone
       return EGT_ERR_SHAPE;
     if (q.mode == 0 && q.table_bytes != (uint64_t)q.count * EGT_STACK_ENTRY_BYTES) return EGT_ERR_SHAPE;
-    if (q.mode == 1 && (q.nitems < 1 || q.grid_x < 1 || q.grid_x > 8 * DEVICE_CUS || (q.forms & 2) || q.block_threads > 768 ||
+    if (q.mode == 1 && (q.nitems < 1 || q.grid_x < 1 || q.grid_x > 8 * DEVICE_CUS || q.block_threads > (q.forms == 2 ? 512 : 768) ||
                         q.part_offset < 0 || q.part_offset > q.lds_bytes ||
                         q.table_bytes != (uint64_t)q.count * EGT_STACK_ENTRY_BYTES + stream_first_bytes(q.grid_x) +
                                              16ull * (uint64_t)q.nitems))
@@ -469,6 +489,7 @@ static egt_status run_part(const uint8_t *t, const egt_stack_part *plan, hipStre
     const dim3 grid(plan->grid_x);
 #define EGT_STREAM_GO(XP)                                                                                    \
   (plan->forms == 1 ? launch(k_gemv_stream<XP, 1>, grid, block, lds, st, t, plan->count, plan->part_offset, plan->block_threads, plan->grid_x) \
+   : plan->forms == 2 ? launch(k_gemv_stream<XP, 2>, grid, block, lds, st, t, plan->count, plan->part_offset, plan->block_threads, plan->grid_x) \
    : plan->forms == 4 ? launch(k_gemv_stream<XP, 4>, grid, block, lds, st, t, plan->count, plan->part_offset, plan->block_threads, plan->grid_x) \
                       : launch(k_gemv_stream<XP, 5>, grid, block, lds, st, t, plan->count, plan->part_offset, plan->block_threads, plan->grid_x))
     switch (plan->x_pieces) {

@@ -335,6 +335,66 @@ def test_row_block_list_on_ragged_shapes():
     rp[[7, 4000]] = saved
 
 
+def test_row_block_list_on_1to4_shapes():
+    # the same form for 1:4 matrices: rows of 16, 32, 64 and 86 chunks (four, two and one row per tile of 64
+    # chunks, two tiles per row), row counts that are no multiple of a tile, a matrix shorter than one row
+    # block and an empty one: sampled rows against the oracle, all rows bit for bit against the separate
+    # calls, nothing written outside y, and NaN for a broken row pointer
+    torch = G.torch_mod()
+    specs = [(11008, 4096), (4099, 11008), (4097, 8192), (1001, 2048), (0, 4096), (37, 4096), (5, 2048), (145, 11008), (3, 4096)]
+    items, checks = [], []
+    for k, (rows, cols) in enumerate(specs):
+        print(f"  packing 1:4 {rows}x{cols}", flush=True)
+        w = synth.weights(rows, cols, 4900 + k)
+        x = synth.activations(cols, 4900 + k)
+        xd = G.to_dev(x.view(np.uint16)).view(torch.float16)
+        ybuf = torch.full((rows + 128,), G.CANARY, dtype=torch.int16, device="cuda")
+        y = ybuf[64:64 + rows].view(torch.float16)
+        y1 = torch.empty(rows, dtype=torch.float16, device="cuda")
+        pick = G.sample_rows(rows, 40, k) if rows else np.zeros(0, dtype=np.int64)
+        ph = B.pack_2bitcsr(w, B.prune_n4(w, 1), 1, 128, 0)
+        if rows:
+            o = O.pack_2bitcsr(w[pick], O.prune_n4_magnitude(w[pick], 1), 1, 128, 0)
+            sub = G.row_subset(ph, pick)
+            for name in ("values", "idx", "qparams"):
+                assert np.array_equal(o[name], sub[name]), name
+            ref = O.gemv(o, x)
+        else:
+            ref = (np.zeros(0), np.zeros(0))
+        pd = ph.to("cuda")
+        items.append(("sparse", pd, xd, y))
+        B.sparse_gemv(pd, xd, y1)
+        checks.append((ybuf, y1, pick, ref))
+    call = B.prepared_gemv_stack(items, form=B.STACK_RESIDENT)
+    assert (call.plan.nparts, call.plan.mode, call.plan.block_threads, call.plan.forms) == (1, 1, 512, 2) and call.plan.nitems > 0
+    for rep in range(3):
+        call()
+        torch.cuda.synchronize()
+        for k, (rows, cols) in enumerate(specs):
+            ybuf, y1, pick, ref = checks[k]
+            host = ybuf.cpu().numpy().view(np.uint16)
+            assert np.all(host[:64] == G.CANARY) and np.all(host[64 + rows:] == G.CANARY), ("write outside y", k)
+            y = host[64:64 + rows].view(np.float16)
+            if rows:
+                G.assert_close(y[pick], ref[0], ref[1], f"row blocks item {k} 1:4 {rows}x{cols}")
+            assert np.array_equal(y.view(np.uint16), y1.cpu().numpy().view(np.uint16)), (k, rows, cols)
+            ybuf[64:64 + rows].fill_(0)
+    p0 = items[0][1]
+    rp = p0.row_ptr.view(torch.int32)
+    saved = rp[[7, 4000]].clone()
+    rp[7] += 8
+    rp[4000] = 0
+    call()
+    torch.cuda.synchronize()
+    y = checks[0][0].cpu().numpy().view(np.uint16)[64:64 + 11008].view(np.float16)
+    good = checks[0][1].cpu().numpy()
+    assert np.isnan(y[7]) and np.isnan(y[4000])
+    keep = np.ones(11008, dtype=bool)
+    keep[[7, 4000]] = False
+    assert np.array_equal(y[keep].view(np.uint16), good[keep].view(np.uint16))
+    rp[[7, 4000]] = saved
+
+
 def test_trigger_model_on_a_measured_sweep():
     # Sec. 3.4: time one all-2:4 layer (q/k/v/o, gate/up, down) for M = 1..64 on the GPU, fit
     # the verification cost with the library and compare fit and trigger point with the

@@ -506,7 +506,10 @@ def test_stack_plan_checks_items_and_reports_the_launch_shape():
     assert (a.count, a.mode, a.block_threads, a.forms, a.table_bytes) == (3, 0, 384, 5, 3 * B.STACK_ENTRY_BYTES)
     assert (b.count, b.mode, b.block_threads, b.forms, b.x_pieces, b.table_bytes) == (1, 0, 256, 2, 8, B.STACK_ENTRY_BYTES)
     assert a.grid_x >= 128 and 0 < a.lds_bytes <= 65536 and 0 < b.lds_bytes <= 65536
-    assert L.egt_gemv_stack_plan(items, 4, B.STACK_RESIDENT, None, 0, ctypes.byref(plan)) == 6   # no resident form at 1:4
+    # asked for, both parts walk lists of row blocks: 12 waves for the one, 8 for the 1:4 matrix (two tiles per row)
+    res = B.StackPlan()
+    assert L.egt_gemv_stack_plan(items, 4, B.STACK_RESIDENT, None, 0, ctypes.byref(res)) == 0
+    assert [(res.part[p].mode, res.part[p].block_threads, res.part[p].forms) for p in range(2)] == [(1, 768, 5), (1, 512, 2)]
     table = np.full(4 * B.STACK_ENTRY_BYTES, 0xA5, dtype=np.uint8)
     assert L.egt_gemv_stack_plan(items, 4, 0, table.ctypes.data, table.nbytes - 1, ctypes.byref(plan)) == 2
     assert np.all(table == 0xA5)
@@ -586,6 +589,29 @@ def test_stack_plan_cuts_a_large_table_into_row_blocks():
     assert per_block.max() - per_block.min() <= 2 * max(row_bytes)
     flat = [(int(m), int(r0)) for m, r0, _, _ in work]
     assert flat == sorted(flat)
+    # a table of 1:4 matrices: workgroups of eight waves; an item starts on a tile (two rows of 4096 columns, four
+    # of 2048) and every row is covered exactly once
+    shapes14 = [(4097, 4096), (1001, 2048), (4099, 11008), (11008, 4096), (130, 8192)]
+    it14 = _fake_items([B.View(r, c, 1, 128, 0, 16, 16, 16, 16) for (r, c) in shapes14])
+    p14 = B.StackPlan()
+    assert L.egt_gemv_stack_plan(it14, 5, B.STACK_RESIDENT, None, 0, ctypes.byref(p14)) == 0       # (21 MB: asked for)
+    assert (p14.nparts, p14.mode, p14.block_threads, p14.forms) == (1, 1, 512, 2)
+    t14 = np.zeros(p14.table_bytes, dtype=np.uint8)
+    assert L.egt_gemv_stack_plan(it14, 5, B.STACK_RESIDENT, t14.ctypes.data, t14.nbytes, ctypes.byref(p14)) == 0
+    off14 = 5 * B.STACK_ENTRY_BYTES
+    fb14 = (4 * (p14.grid_x + 1) + 15) // 16 * 16
+    first14 = t14[off14:off14 + 4 * (p14.grid_x + 1)].view(np.uint32)
+    work14 = t14[off14 + fb14:].view(np.uint32).reshape(-1, 4)
+    assert first14[0] == 0 and first14[-1] == p14.nitems == len(work14)
+    cov14 = [np.zeros(r, dtype=np.int32) for (r, _) in shapes14]
+    for m, r0, n, _ in work14:
+        desc = t14[m * B.STACK_ENTRY_BYTES:(m + 1) * B.STACK_ENTRY_BYTES].view(np.int32)
+        rpt = {4096: 2, 2048: 4}.get(shapes14[m][1], 1)
+        assert int(desc[22]) == {4096: 5, 2048: 4}.get(shapes14[m][1], -1)          # log2(chunks per row) where a tile holds several rows
+        assert r0 % rpt == 0 and 0 < n <= int(desc[21]) and int(desc[21]) % rpt == 0
+        assert 16 * int(desc[15]) * -(-int(n) // rpt) <= 24 * 1024                  # the item's partial sums fit their LDS share
+        cov14[m][r0:r0 + n] += 1
+    assert all(np.all(c == 1) for c in cov14)
     # a smaller table keeps the short-lived workgroups unless the caller asks otherwise
     one = _fake_items(layer[:4])
     assert L.egt_gemv_stack_plan(one, 4, B.STACK_AUTO, None, 0, ctypes.byref(plan)) == 0 and plan.mode == 0
