@@ -486,7 +486,7 @@ def table(torch, B, synth, timer, dev, w, mask, xd, ys, calls, packed):
     # AR step = t(1).  The workspace form is used wherever the library says it is the faster one.
     sweep_m = tuple(range(1, 65))
     layer_us = {m: 0.0 for m in sweep_m}
-    pools, split_wins = {}, set()
+    pools, split_wins, best_us = {}, set(), {}
     for (r5, k5, mi, reps) in ((11008, 4096, 0, 2), (4096, 11008, 1, 1), (4096, 4096, 2, 4)):
         w5 = synth.weights(r5, k5, synth.seed_for(5, mi))
         p5 = B.pack_2bitcsr(w5, B.prune_n4(w5, 2), 2, 128, B.VAL_INT4)
@@ -516,6 +516,48 @@ def table(torch, B, synth, timer, dev, w, mask, xd, ys, calls, packed):
                         t5w, algorithmic_bytes(r5, k5, 2, 128, 0, M), flops=2 * M * r5 * k5 / 2)
                 del f5w, ws
             layer_us[M] += reps * best * 1e6
+            best_us[(mi, M)] = best * 1e6
+    # the same layer with q/k/v and gate/up each packed as one matrix (their rows concatenated at packing time,
+    # the usual fused projections): 4 products per layer instead of 7, and X is staged once for the three (two)
+    fused_m = (1, 2, 4, 8, 16, 32, 64)
+    fused_layer = {m: best_us[(2, m)] + best_us[(1, m)] for m in fused_m}          # o and down as above
+    for (r5, k5, mi) in ((3 * 4096, 4096, 3), (2 * 11008, 4096, 4)):
+        w5 = synth.weights(r5, k5, synth.seed_for(5, mi))
+        p5 = B.pack_2bitcsr(w5, B.prune_n4(w5, 2), 2, 128, B.VAL_INT4)
+        c5 = max(2, -(-2 * LLC_BYTES // p5.nbytes()))
+        pk5 = [p5.to(dev) for _ in range(c5)]
+        for M in fused_m:
+            X = up16(synth.activation_rows(M, k5, 5))
+            Y = torch.empty((M, r5), dtype=torch.float16, device=dev)
+            f5 = [B.prepared_sparse_gemm_smallm(pk5[i], X, Y) for i in range(c5)]
+            best = timer(lambda i: f5[i % c5](), 200)["median"]
+            need = B.smallm_ws_bytes(pk5[0], M)
+            if need:
+                ws = torch.empty(need, dtype=torch.uint8, device=dev)
+                f5w = [B.prepared_sparse_gemm_smallm_ws(pk5[i], X, Y, ws) for i in range(c5)]
+                best = min(best, timer(lambda i: f5w[i % c5](), 200)["median"])
+                del f5w, ws
+            fused_layer[M] += best * 1e6
+            if mi == 3 and M == 16:
+                qkv_fused_us = best * 1e6
+            del f5
+        del pk5, p5, w5
+    # q/k/v as three matrices under the same 16 tokens: three launches against the batched entry point
+    r5, k5, _, pk5 = pools[2]
+    X = up16(synth.activation_rows(16, k5, 5))
+    Ys = [torch.empty((16, r5), dtype=torch.float16, device=dev) for _ in range(3)]
+    nq = len(pk5) // 3
+    sep = [[B.prepared_sparse_gemm_smallm(pk5[3 * i + k], X, Ys[k]) for k in range(3)] for i in range(nq)]
+    bat = [B.prepared_sparse_gemm_smallm_batch(pk5[3 * i:3 * i + 3], [X] * 3, Ys) for i in range(nq)]
+
+    def run_sep(i):
+        for c in sep[i % nq]:
+            c()
+    t["smallm_qkv_3x4096x4096_M16"] = {"three_launches_us": round(timer(run_sep, 200)["median"] * 1e6, 3),
+                                        "one_batched_launch_us": round(timer(lambda i: bat[i % nq](), 200)["median"] * 1e6, 3),
+                                        "one_matrix_of_12288_rows_us": round(qkv_fused_us, 3)}
+    del sep, bat
+    fused_a, fused_b = B.fit_verify_cost(list(fused_m[1:]), [fused_layer[m] for m in fused_m[1:]])
     fit_a, fit_b = B.fit_verify_cost(list(sweep_m[1:]), [layer_us[m] for m in sweep_m[1:]])
     cand = [64, 24, 9, 4, 2, 1]                      # candidates left per trie depth (wide top, narrow bottom)
     rem = [6, 5, 4, 3, 2, 1]                         # tokens still to generate (average ID length 6)
@@ -546,7 +588,10 @@ def table(torch, B, synth, timer, dev, w, mask, xd, ys, calls, packed):
                           "stack_pass_us_32_times_layer_by_M": {str(m): round(32 * layer_us[m], 1) for m in (1, 16, 64)},
                           "fit_a_us": round(fit_a, 3), "fit_b_us_per_token": round(fit_b, 4),
                           "t_ar_us": round(layer_us[1], 2), "candidates": cand, "remaining": rem,
-                          "trigger_depth": depth, "benefit_us_per_layer": round(gain, 2)}
+                          "trigger_depth": depth, "benefit_us_per_layer": round(gain, 2),
+                          "fused_projections": {"layer_us_by_M": {str(m): round(fused_layer[m], 2) for m in fused_m},
+                                                "launches_per_layer": 4, "fit_a_us": round(fused_a, 3),
+                                                "fit_b_us_per_token": round(fused_b, 4)}}
     del pools
     # config 4: the 32-layer stack (every layer its own seeded weights), 224 launches in
     # sequence, plain and as a HIP graph; then with q/k/v and gate/up fused (128 launches)

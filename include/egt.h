@@ -256,6 +256,17 @@ egt_status egt_int4_gemv_batch(const uint8_t *const *q, const uint16_t *const *q
                                int cols, int group, const uint16_t *const *x, uint16_t *const *y,
                                int count, void *stream);
 
+/* DEVICE.  The same for 1 <= M <= 64 activation rows (Sec. 3.4: all candidates of a trie level
+ * pass the q/k/v or the gate/up projections together): Y[k] = X[k] . W[k]^T for `count` (1..4)
+ * identically shaped matrices in one launch.  X, Y: host arrays of `count` device pointers
+ * (the members may share one X); every X[k] has leading dimension ldx, every Y[k] ldy; the
+ * other arguments are those of egt_sparse_gemm_smallm.  Where no batched kernel takes the
+ * shape or M (one to four tokens at K = 4096, the paired nibble order, shapes of the
+ * slot-by-slot kernel) the members run as one launch each.  Results equal those of `count`
+ * separate egt_sparse_gemm_smallm calls bit for bit. */
+egt_status egt_sparse_gemm_smallm_batch(const egt_2bitcsr *w, const uint16_t *const *X, int64_t ldx,
+                                        uint16_t *const *Y, int64_t ldy, int M, int count, void *stream);
+
 /* Several products of different shapes and storage forms in one launch (Sec. 3.3 starts
  * from one kernel per linear layer; Sec. 3.2 makes the stack a layer-adaptive mix of 2:4,
  * 1:4 and dense INT4 layers): the fixed cost of a launch, about half the time of a GEMV of

@@ -28,7 +28,7 @@ SYMBOLS = (
     "egt_fit_verify_cost", "egt_trigger_depth", "egt_prune_n4_importance", "egt_pack_2bitcsr_rowgroups",
     "egt_pack_2bitcsr_rows", "egt_2bitcsr_sizes_rows",
     "egt_gemv_stack_plan", "egt_gemv_stack_run", "egt_sparse_gemm_smallm_ws_bytes", "egt_sparse_gemm_smallm_ws",
-    "egt_sparse_gemm_smallm_static",
+    "egt_sparse_gemm_smallm_static", "egt_sparse_gemm_smallm_batch",
 )
 
 
@@ -113,6 +113,8 @@ def _declare(L: C.CDLL, names=None) -> C.CDLL:
         "egt_sparse_gemm_smallm": ([C.POINTER(View), C.c_void_p, C.c_int64, C.c_void_p, C.c_int64, C.c_int, C.c_void_p], C.c_int),
         "egt_stream_read": ([C.c_void_p, C.c_size_t, C.c_void_p, C.c_void_p], C.c_int),
         "egt_sparse_gemv_batch": ([C.POINTER(View), C.POINTER(C.c_void_p), C.POINTER(C.c_void_p), C.c_int, C.c_void_p], C.c_int),
+        "egt_sparse_gemm_smallm_batch": ([C.POINTER(View), C.POINTER(C.c_void_p), C.c_int64, C.POINTER(C.c_void_p), C.c_int64,
+                                          C.c_int, C.c_int, C.c_void_p], C.c_int),
         "egt_int4_gemv_batch": ([C.POINTER(C.c_void_p), C.POINTER(C.c_void_p), C.c_int, C.c_int, C.c_int,
                                  C.POINTER(C.c_void_p), C.POINTER(C.c_void_p), C.c_int, C.c_void_p], C.c_int),
         "egt_fit_verify_cost": ([C.c_void_p, C.c_void_p, C.c_int, C.POINTER(C.c_double), C.POINTER(C.c_double)], C.c_int),
@@ -527,6 +529,32 @@ def prepared_sparse_gemv_batch(ps, xs, ys, stream=None):
         if st:
             _check(st)
     return call
+
+
+def prepared_sparse_gemm_smallm_batch(ps, Xs, Ys, stream=None):
+    """One launch for len(ps) identically shaped matrices and M tokens each: Ys[k] = Xs[k] . W[k]^T.
+    Xs[k]: (M, K), Ys[k]: (M, R) float16 device tensors, all Xs with one row stride, all Ys with one
+    (the members may share one X)."""
+    fn = lib().egt_sparse_gemm_smallm_batch
+    for p, X, Y in zip(ps, Xs, Ys):
+        _check_xy(p, X, Y)
+        if X.shape[0] != Xs[0].shape[0] or X.stride(0) != Xs[0].stride(0) or Y.stride(0) != Ys[0].stride(0):
+            raise ValueError("the members of a batch share M, ldx and ldy")
+    views = (View * len(ps))(*[p.view() for p in ps])
+    xa = (C.c_void_p * len(ps))(*[X.data_ptr() for X in Xs])
+    ya = (C.c_void_p * len(ps))(*[Y.data_ptr() for Y in Ys])
+    args = (views, xa, Xs[0].stride(0), ya, Ys[0].stride(0), Xs[0].shape[0], len(ps))
+    sp = _stream_ptr(stream)
+
+    def call(stream_ptr=sp, _keep=(views, ps, Xs, Ys, xa, ya)):
+        st = fn(*args, stream_ptr)
+        if st:
+            _check(st)
+    return call
+
+
+def sparse_gemm_smallm_batch(ps, Xs, Ys, stream=None) -> None:
+    prepared_sparse_gemm_smallm_batch(ps, Xs, Ys, stream)()
 
 
 def prepared_int4_gemv_batch(qs, qparams, rows: int, cols: int, group: int, xs, ys, stream=None):

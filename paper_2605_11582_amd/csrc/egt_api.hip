@@ -234,6 +234,28 @@ egt_status egt_sparse_gemv_batch(const egt_2bitcsr *w, const uint16_t *const *x,
   return done(egt::launch_sparse_batch(w, x, y, count, (hipStream_t)stream));
 }
 
+egt_status egt_sparse_gemm_smallm_batch(const egt_2bitcsr *w, const uint16_t *const *X, int64_t ldx,
+                                        uint16_t *const *Y, int64_t ldy, int M, int count, void *stream) {
+  if (!w || !X || !Y) return EGT_ERR_NULL;
+  if (count < 1 || count > 4) return EGT_ERR_SHAPE;
+  for (int k = 0; k < count; ++k) {
+    const egt_status st = check_view(&w[k]);
+    if (st != EGT_OK) return st;
+    if (w[k].rows != w[0].rows || w[k].cols != w[0].cols || w[k].n_keep != w[0].n_keep ||
+        w[k].group_size != w[0].group_size || w[k].val_kind != w[0].val_kind || w[k].total_slots != w[0].total_slots)
+      return EGT_ERR_SHAPE;
+  }
+  if (M < 1 || M > 64 || ldx < w[0].cols || ldy < w[0].rows) return EGT_ERR_SHAPE;
+  if (w[0].rows == 0) return EGT_OK;
+  for (int k = 0; k < count; ++k) {
+    if (!X[k] || !Y[k]) return EGT_ERR_NULL;
+    if (!aligned16(w[k].row_ptr) || !aligned16(w[k].values) || !aligned16(w[k].idx) ||
+        (w[k].qparams && !aligned16(w[k].qparams)) || !aligned16(X[k]))
+      return EGT_ERR_BUFFER;
+  }
+  return done(egt::launch_sparse_gemm_batch(w, X, ldx, Y, ldy, M, count, (hipStream_t)stream));
+}
+
 egt_status egt_int4_gemv_batch(const uint8_t *const *q, const uint16_t *const *qparams, int rows,
                                int cols, int group, const uint16_t *const *x, uint16_t *const *y,
                                int count, void *stream) {

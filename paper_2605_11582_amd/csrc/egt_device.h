@@ -45,6 +45,11 @@ hipError_t launch_sparse_m1_n1(const egt_2bitcsr &w, const uint16_t *x, uint16_t
 bool sparse_smallm_supported(const egt_2bitcsr &w, int64_t ldx, int M);
 hipError_t launch_sparse_smallm(const egt_2bitcsr &w, const uint16_t *X, int64_t ldx, uint16_t *Y,
                                 int64_t ldy, int M, hipStream_t stream);
+hipError_t launch_sparse_smallm_batch(const egt_2bitcsr *ws, const uint16_t *const *Xs, int64_t ldx, uint16_t *const *Ys,
+                                      int64_t ldy, int M, int count, hipStream_t stream);
+// (dispatch: identically shaped members; falls back to one launch per member where no batched kernel applies)
+hipError_t launch_sparse_gemm_batch(const egt_2bitcsr *ws, const uint16_t *const *Xs, int64_t ldx, uint16_t *const *Ys,
+                                    int64_t ldy, int M, int count, hipStream_t stream);
 
 // the same with K split over workgroups and FP32 partial sums in a workspace of the caller
 // (sparse_smallm_split_bytes: false if this shape and M do not use the split form)

@@ -44,6 +44,21 @@ hipError_t launch_sparse_batch(const egt_2bitcsr *ws, const uint16_t *const *xs,
   return hipSuccess;
 }
 
+hipError_t launch_sparse_gemm_batch(const egt_2bitcsr *ws, const uint16_t *const *Xs, int64_t ldx, uint16_t *const *Ys,
+                                    int64_t ldy, int M, int count, hipStream_t stream) {
+  const egt_2bitcsr &w = ws[0];
+  // the small-M kernel where a single call would take it (M = 1 and the few-token form of the M = 1 kernel have
+  // batched forms of their own or none: one launch per member there)
+  const bool tokens_form = M >= 2 && ldx % 8 == 0 && sparse_m1_tokens_supported(w, M) && !tune_flag("EGT_NO_M1T");
+  if (count >= 2 && M >= 2 && w.val_kind != EGT_VAL_INT4_PAIRED && !tokens_form && sparse_smallm_supported(w, ldx, M))
+    return launch_sparse_smallm_batch(ws, Xs, ldx, Ys, ldy, M, count, stream);
+  for (int k = 0; k < count; ++k) {
+    const hipError_t e = launch_sparse(ws[k], Xs[k], ldx, Ys[k], ldy, M, stream);
+    if (e != hipSuccess) return e;
+  }
+  return hipSuccess;
+}
+
 hipError_t launch_int4_batch(const uint8_t *const *qs, const uint16_t *const *qps, int rows, int cols,
                              int group, const uint16_t *const *xs, uint16_t *const *ys, int count,
                              hipStream_t stream) {

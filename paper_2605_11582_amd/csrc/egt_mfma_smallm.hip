@@ -108,13 +108,9 @@ __device__ __forceinline__ uint32_t quad_bcast(uint32_t v) {     // value of lan
 // KS: the grid's y dimension splits K; a workgroup walks only the K-steps of its slice and
 // leaves FP32 partial sums in the caller's workspace (k_smallm_sum_slices finishes them).
 template <int KIND, int NT, int NIT, int NWMAX, int QW, bool N1, bool RND, bool KS = false>
-__global__ __launch_bounds__(64 * NWMAX) void k_sparse_smallm_ks(const uint32_t *__restrict__ row_ptr,
-                                                                  const uint8_t *__restrict__ values,
-                                                                  const uint8_t *__restrict__ idx,
-                                                                  const uint8_t *__restrict__ qparams,
-                                                                  const __half *__restrict__ X,
-                                                                  __half *__restrict__ Y,
-                                                                  const SmallMKsGeom g) {
+__device__ __forceinline__ void smallm_ks_body(const uint32_t *__restrict__ row_ptr, const uint8_t *__restrict__ values,
+                                               const uint8_t *__restrict__ idx, const uint8_t *__restrict__ qparams,
+                                               const __half *__restrict__ X, __half *__restrict__ Y, const SmallMKsGeom &g) {
   extern __shared__ __align__(16) uint8_t xs[];       // X regions, later the partial sums
   static_assert(!(N1 && NT > 1), "1:4 runs one token group per pass");
   constexpr bool INT4 = KIND == EGT_VAL_INT4;
@@ -604,6 +600,33 @@ __global__ __launch_bounds__(64 * NWMAX) void k_sparse_smallm_ks(const uint32_t 
   }
 }
 
+template <int KIND, int NT, int NIT, int NWMAX, int QW, bool N1, bool RND, bool KS = false>
+__global__ __launch_bounds__(64 * NWMAX) void k_sparse_smallm_ks(const uint32_t *__restrict__ row_ptr,
+                                                                  const uint8_t *__restrict__ values,
+                                                                  const uint8_t *__restrict__ idx,
+                                                                  const uint8_t *__restrict__ qparams,
+                                                                  const __half *__restrict__ X,
+                                                                  __half *__restrict__ Y,
+                                                                  const SmallMKsGeom g) {
+  smallm_ks_body<KIND, NT, NIT, NWMAX, QW, N1, RND, KS>(row_ptr, values, idx, qparams, X, Y, g);
+}
+
+// Up to four identically shaped products (the q/k/v or gate/up projections under the same
+// tokens or under tokens of their own) in one launch: blockIdx.y names the member, whose
+// workgroups run the very body of the single-matrix kernel.
+struct SmallMBatch {
+  const uint32_t *row_ptr[EGT_MAX_BATCH];
+  const uint8_t *values[EGT_MAX_BATCH], *idx[EGT_MAX_BATCH], *qparams[EGT_MAX_BATCH];
+  const __half *X[EGT_MAX_BATCH];
+  __half *Y[EGT_MAX_BATCH];
+};
+template <int KIND, int NT, int NIT, int NWMAX, int QW, bool N1, bool RND>
+__global__ __launch_bounds__(64 * NWMAX) void k_sparse_smallm_ks_batch(const SmallMBatch b, const SmallMKsGeom g) {
+  const unsigned k = blockIdx.y;
+  smallm_ks_body<KIND, NT, NIT, NWMAX, QW, N1, RND, false>(pick4(b.row_ptr, k), pick4(b.values, k), pick4(b.idx, k), pick4(b.qparams, k),
+                                                           pick4(b.X, k), pick4(b.Y, k), g);
+}
+
 // Shapes covered: 2:4 with K a multiple of 64, 1:4 with K a multiple of 128; INT4 groups
 // of 32 << j; token rows of X on a dword boundary; values and X below 4 GiB each (the
 // loads take 32-bit offsets).
@@ -636,12 +659,16 @@ __global__ __launch_bounds__(256) void k_smallm_sum_slices(const float *__restri
 
 template <int KIND, int NT, int NIT, int NWMAX, int QW, bool N1, bool RND, bool KS = false>
 static hipError_t go_ks(const egt_2bitcsr &w, const uint16_t *X, uint16_t *Y, const SmallMKsGeom &g, int nw,
-                        int nblocks, hipStream_t stream) {
+                        int nblocks, hipStream_t stream, const SmallMBatch *batch = nullptr, int count = 1) {
   const size_t region = N1 ? 16 * KS_TOKEN_N1 : 8 * KS_PAIR;
   const size_t x_bytes = (size_t)nw * region, p_bytes = (size_t)nw * NIT * NT * 1024;
   // partial sums behind the X regions where the kernel keeps them apart (NT > 1), else at
   // the start of each wave's own region; + row-pointer flags
   const size_t lds = (NT > 1 ? x_bytes + p_bytes : x_bytes) + 64 * NIT;
+  if constexpr (!KS) {
+    if (batch)
+      return launch(k_sparse_smallm_ks_batch<KIND, NT, NIT, NWMAX, QW, N1, RND>, dim3(nblocks, count), dim3(64 * nw), lds, stream, *batch, g);
+  }
   return launch(k_sparse_smallm_ks<KIND, NT, NIT, NWMAX, QW, N1, RND, KS>, dim3(nblocks, KS ? g.nslices : 1), dim3(64 * nw),
                 lds, stream, w.row_ptr, (const uint8_t *)w.values, (const uint8_t *)w.idx, (const uint8_t *)w.qparams,
                 (const __half *)X, (__half *)Y, g);
@@ -753,8 +780,8 @@ hipError_t launch_sparse_smallm_split(const egt_2bitcsr &w, const uint16_t *X, i
                 g.nslices, M, w.rows, (__half *)Y, ldy);
 }
 
-hipError_t launch_sparse_smallm(const egt_2bitcsr &w, const uint16_t *X, int64_t ldx, uint16_t *Y,
-                                int64_t ldy, int M, hipStream_t stream) {
+static hipError_t smallm_one_launch(const egt_2bitcsr &w, const uint16_t *X, int64_t ldx, uint16_t *Y,
+                                    int64_t ldy, int M, hipStream_t stream, const SmallMBatch *batch, int count) {
   if (w.rows == 0) return hipSuccess;
   const bool int4 = w.val_kind == EGT_VAL_INT4, n1 = w.n_keep == 1;
   SmallMKsGeom g;
@@ -765,6 +792,9 @@ hipError_t launch_sparse_smallm(const egt_2bitcsr &w, const uint16_t *X, int64_t
     if (vb >= (1ull << 32) || xb >= (1ull << 32)) return hipErrorInvalidValue;   // 32-bit offsets
   }
   smallm_geometry(w, ldx, Y, ldy, M, g, qw);
+  if (batch)                                          // 8-byte stores only where every member's Y allows them
+    for (int k = 0; k < count; ++k)
+      if ((uintptr_t)batch->Y[k] % 8 != 0) g.vec_store = 0;
   // One workgroup per compute unit while its row tiles fit the registers (NIT of them).
   // 2:4 INT4, up to 16 tokens: 16 waves of 128 registers; everything else 8 waves of 256
   // (more than 16 tokens at 2:4: two token groups per pass).
@@ -785,8 +815,8 @@ hipError_t launch_sparse_smallm(const egt_2bitcsr &w, const uint16_t *X, int64_t
   const int nw = g.nsteps < nwmax ? g.nsteps : nwmax;
   // (NIT > 1: the form with rounds only where a workgroup owns more than NIT row tiles)
 #define EGT_KS(KIND, NT, NIT, NWMAX, QW, N1)                                                     \
-  ((NIT > 1 && (int64_t)nblocks * NIT < g.ntiles) ? go_ks<KIND, NT, NIT, NWMAX, QW, N1, (NIT > 1)>(w, X, Y, g, nw, nblocks, stream) \
-                                                  : go_ks<KIND, NT, NIT, NWMAX, QW, N1, false>(w, X, Y, g, nw, nblocks, stream))
+  ((NIT > 1 && (int64_t)nblocks * NIT < g.ntiles) ? go_ks<KIND, NT, NIT, NWMAX, QW, N1, (NIT > 1)>(w, X, Y, g, nw, nblocks, stream, batch, count) \
+                                                  : go_ks<KIND, NT, NIT, NWMAX, QW, N1, false>(w, X, Y, g, nw, nblocks, stream, batch, count))
   if (n1) {
     if (!int4) return one ? EGT_KS(EGT_VAL_FP16, 1, 1, 8, 1, true) : EGT_KS(EGT_VAL_FP16, 1, 4, 8, 1, true);
     if (qw == 4) return one ? EGT_KS(EGT_VAL_INT4, 1, 1, 8, 4, true) : EGT_KS(EGT_VAL_INT4, 1, 4, 8, 4, true);
@@ -807,6 +837,24 @@ hipError_t launch_sparse_smallm(const egt_2bitcsr &w, const uint16_t *X, int64_t
   }
   return one ? EGT_KS(EGT_VAL_FP16, 2, 1, 8, 1, false) : EGT_KS(EGT_VAL_FP16, 2, 4, 8, 1, false);
 #undef EGT_KS
+}
+
+hipError_t launch_sparse_smallm(const egt_2bitcsr &w, const uint16_t *X, int64_t ldx, uint16_t *Y,
+                                int64_t ldy, int M, hipStream_t stream) {
+  return smallm_one_launch(w, X, ldx, Y, ldy, M, stream, nullptr, 1);
+}
+
+// `count` (2..4) identically shaped members in one launch (the caller has checked the shapes
+// and that sparse_smallm_supported holds for them).
+hipError_t launch_sparse_smallm_batch(const egt_2bitcsr *ws, const uint16_t *const *Xs, int64_t ldx, uint16_t *const *Ys,
+                                      int64_t ldy, int M, int count, hipStream_t stream) {
+  SmallMBatch b;
+  for (int k = 0; k < EGT_MAX_BATCH; ++k) {
+    const int j = k < count ? k : 0;                  // unused slots repeat member 0
+    b.row_ptr[k] = ws[j].row_ptr; b.values[k] = (const uint8_t *)ws[j].values; b.idx[k] = (const uint8_t *)ws[j].idx;
+    b.qparams[k] = (const uint8_t *)ws[j].qparams; b.X[k] = (const __half *)Xs[j]; b.Y[k] = (__half *)Ys[j];
+  }
+  return smallm_one_launch(ws[0], Xs[0], ldx, Ys[0], ldy, M, stream, &b, count);
 }
 
 }  // namespace egt

@@ -670,6 +670,38 @@ def test_sparse_gemv_batch_equals_separate_calls(rows, cols, n, g, kind, count):
         assert np.array_equal(y.view(np.uint16), G.run_sparse_gemv(ps[k], xs[k]).view(np.uint16))
 
 
+@pytest.mark.parametrize("rows,cols,n,g,kind,M,count,shared", [
+    (70, 4096, 2, 128, 0, 16, 3, True), (33, 11008, 2, 128, 0, 7, 2, False), (300, 4096, 2, 128, 0, 33, 3, True),
+    (4100, 1024, 2, 64, 0, 5, 4, False), (40, 4096, 1, 128, 0, 16, 2, True), (21, 4096, 2, 0, 1, 8, 2, False),
+    (50, 4096, 2, 32, 0, 64, 2, True),
+    # no batched kernel: two tokens on the M = 1 kernel's mapping, the paired nibble order, a slot-by-slot shape, one token
+    (70, 4096, 2, 128, 0, 2, 3, True), (37, 4096, 2, 128, 2, 16, 2, False), (19, 96, 3, 32, 0, 5, 3, True), (45, 4096, 2, 128, 0, 1, 2, False),
+])
+def test_sparse_gemm_batch_equals_separate_calls(rows, cols, n, g, kind, M, count, shared):
+    torch = G.torch_mod()
+    print(f"case gemm batch {rows}x{cols} n={n} g={g} kind={kind} M={M} x{count} shared={shared}", flush=True)
+    ps, Xs, refs = [], [], []
+    for k in range(count):
+        p, o = _small_case(rows, cols, n, g, kind, seed=7300 + 13 * k + rows)
+        X = synth.activation_rows(M, cols, 7300 + (0 if shared else k))
+        ps.append(p); Xs.append(X); refs.append(O.gemm_smallm(o, X))
+    pds = [p.to("cuda") for p in ps]
+    xbuf = [G.to_dev(X.view(np.uint16)).view(torch.float16) for X in (Xs[:1] if shared else Xs)]
+    Xd = [xbuf[0] if shared else xbuf[k] for k in range(count)]
+    ybufs = [torch.full((M + 2, rows + 8), G.CANARY, dtype=torch.int16, device="cuda") for _ in range(count)]
+    Yd = [yb[1:M + 1, :rows].view(torch.float16) for yb in ybufs]
+    for rep in range(2):
+        B.sparse_gemm_smallm_batch(pds, Xd, Yd)
+        torch.cuda.synchronize()
+        for k in range(count):
+            host = ybufs[k].cpu().numpy().view(np.uint16)
+            assert np.all(host[0] == G.CANARY) and np.all(host[M + 1] == G.CANARY) and np.all(host[:, rows:] == G.CANARY), ("write outside Y", k)
+            Y = host[1:M + 1, :rows].view(np.float16)
+            G.assert_close(Y, refs[k][0], refs[k][1], f"gemm batch member {k}")
+            assert np.array_equal(Y.view(np.uint16), G.run_sparse_gemm(ps[k], Xs[k]).view(np.uint16)), k
+            ybufs[k][1:M + 1, :rows].fill_(0)
+
+
 @pytest.mark.parametrize("rows,cols,g,count", [(50, 4096, 128, 3), (21, 11008, 128, 2), (30, 320, 64, 2),
                                                (40, 4096, 64, 4), (40, 4096, 256, 2)])
 def test_int4_gemv_batch_equals_separate_calls(rows, cols, g, count):

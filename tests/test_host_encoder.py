@@ -474,6 +474,17 @@ def test_device_entry_points_reject_bad_arguments_without_a_gpu():
     assert L.egt_sparse_gemv_batch(views, ptrs, ptrs, 5, None) == 2
     assert L.egt_sparse_gemv_batch(None, ptrs, ptrs, 1, None) == 1
     assert L.egt_int4_gemv_batch(ptrs, ptrs, 8, 64, 32, ptrs, ptrs, 0, None) == 2
+    assert L.egt_sparse_gemm_smallm_batch(views, ptrs, 64, ptrs, 8, 4, 2, None) == 2      # members of different group size
+    same = (B.View * 2)(v, v)
+    assert L.egt_sparse_gemm_smallm_batch(same, ptrs, 64, ptrs, 8, 4, 0, None) == 2       # count
+    assert L.egt_sparse_gemm_smallm_batch(same, ptrs, 64, ptrs, 8, 65, 2, None) == 2      # M
+    assert L.egt_sparse_gemm_smallm_batch(same, ptrs, 32, ptrs, 8, 4, 2, None) == 2       # ldx < cols
+    assert L.egt_sparse_gemm_smallm_batch(same, ptrs, 64, ptrs, 4, 4, 2, None) == 2       # ldy < rows
+    assert L.egt_sparse_gemm_smallm_batch(None, ptrs, 64, ptrs, 8, 4, 2, None) == 1
+    nulls = (ctypes.c_void_p * 2)(16, None)
+    assert L.egt_sparse_gemm_smallm_batch(same, nulls, 64, ptrs, 8, 4, 2, None) == 1
+    odd = (ctypes.c_void_p * 2)(16, 24)
+    assert L.egt_sparse_gemm_smallm_batch(same, odd, 64, ptrs, 8, 4, 2, None) == 5        # X off a 16-byte boundary
     assert L.egt_stream_read(None, 32, 16, None) == 1
 
 
