@@ -110,7 +110,7 @@ __device__ __forceinline__ uint32_t quad_bcast(uint32_t v) {     // value of lan
 template <int KIND, int NT, int NIT, int NWMAX, int QW, bool N1, bool RND, bool KS = false>
 __device__ __forceinline__ void smallm_ks_body(const uint32_t *__restrict__ row_ptr, const uint8_t *__restrict__ values,
                                                const uint8_t *__restrict__ idx, const uint8_t *__restrict__ qparams,
-                                               const __half *__restrict__ X, __half *__restrict__ Y, const SmallMKsGeom &g) {
+                                               const __half *__restrict__ X, __half *__restrict__ Y, const SmallMKsGeom g) {
   extern __shared__ __align__(16) uint8_t xs[];       // X regions, later the partial sums
   static_assert(!(N1 && NT > 1), "1:4 runs one token group per pass");
   constexpr bool INT4 = KIND == EGT_VAL_INT4;
