@@ -341,10 +341,12 @@ def test_row_block_list_on_1to4_shapes():
     # block and an empty one: sampled rows against the oracle, all rows bit for bit against the separate
     # calls, nothing written outside y, and NaN for a broken row pointer
     torch = G.torch_mod()
-    specs = [(11008, 4096), (4099, 11008), (4097, 8192), (1001, 2048), (0, 4096), (37, 4096), (5, 2048), (145, 11008), (3, 4096)]
+    # (rows, columns, quantisation group)
+    specs = [(11008, 4096, 128), (4099, 11008, 128), (4097, 8192, 128), (1001, 2048, 128), (0, 4096, 128), (37, 4096, 128),
+             (5, 2048, 128), (145, 11008, 128), (3, 4096, 128), (301, 16384, 256), (64, 12288, 512), (77, 4096, 4096), (130, 8192, 256)]
     items, checks = [], []
-    for k, (rows, cols) in enumerate(specs):
-        print(f"  packing 1:4 {rows}x{cols}", flush=True)
+    for k, (rows, cols, grp) in enumerate(specs):
+        print(f"  packing 1:4 {rows}x{cols} g={grp}", flush=True)
         w = synth.weights(rows, cols, 4900 + k)
         x = synth.activations(cols, 4900 + k)
         xd = G.to_dev(x.view(np.uint16)).view(torch.float16)
@@ -352,9 +354,9 @@ def test_row_block_list_on_1to4_shapes():
         y = ybuf[64:64 + rows].view(torch.float16)
         y1 = torch.empty(rows, dtype=torch.float16, device="cuda")
         pick = G.sample_rows(rows, 40, k) if rows else np.zeros(0, dtype=np.int64)
-        ph = B.pack_2bitcsr(w, B.prune_n4(w, 1), 1, 128, 0)
+        ph = B.pack_2bitcsr(w, B.prune_n4(w, 1), 1, grp, 0)
         if rows:
-            o = O.pack_2bitcsr(w[pick], O.prune_n4_magnitude(w[pick], 1), 1, 128, 0)
+            o = O.pack_2bitcsr(w[pick], O.prune_n4_magnitude(w[pick], 1), 1, grp, 0)
             sub = G.row_subset(ph, pick)
             for name in ("values", "idx", "qparams"):
                 assert np.array_equal(o[name], sub[name]), name
@@ -370,13 +372,13 @@ def test_row_block_list_on_1to4_shapes():
     for rep in range(3):
         call()
         torch.cuda.synchronize()
-        for k, (rows, cols) in enumerate(specs):
+        for k, (rows, cols, grp) in enumerate(specs):
             ybuf, y1, pick, ref = checks[k]
             host = ybuf.cpu().numpy().view(np.uint16)
             assert np.all(host[:64] == G.CANARY) and np.all(host[64 + rows:] == G.CANARY), ("write outside y", k)
             y = host[64:64 + rows].view(np.float16)
             if rows:
-                G.assert_close(y[pick], ref[0], ref[1], f"row blocks item {k} 1:4 {rows}x{cols}")
+                G.assert_close(y[pick], ref[0], ref[1], f"row blocks item {k} 1:4 {rows}x{cols} g={grp}")
             assert np.array_equal(y.view(np.uint16), y1.cpu().numpy().view(np.uint16)), (k, rows, cols)
             ybuf[64:64 + rows].fill_(0)
     p0 = items[0][1]
