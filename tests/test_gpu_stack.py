@@ -270,11 +270,13 @@ def test_row_block_list_on_ragged_shapes():
     # block and an empty one: sampled rows against the oracle (which re-encodes them), all
     # rows bit for bit against the separate calls, and nothing written outside y
     torch = G.torch_mod()
-    specs = [("s24", 11008, 4096), ("d", 4099, 11008), ("s24", 4097, 8192), ("d", 1001, 4096), ("s24", 0, 4096),
-             ("s24", 37, 4096), ("d", 5, 4096), ("s24", 145, 11008)]
+    # (storage form, rows, columns, quantisation group)
+    specs = [("s24", 11008, 4096, 128), ("d", 4099, 11008, 128), ("s24", 4097, 8192, 128), ("d", 1001, 4096, 128), ("s24", 0, 4096, 128),
+             ("s24", 37, 4096, 128), ("d", 5, 4096, 128), ("s24", 145, 11008, 128),
+             ("s24", 500, 4096, 64), ("s24", 300, 8192, 256), ("d", 200, 4096, 256), ("d", 100, 11008, 256), ("s24", 90, 12288, 4096)]
     items, checks = [], []
-    for k, (kind, rows, cols) in enumerate(specs):
-        print(f"  packing {kind} {rows}x{cols}", flush=True)
+    for k, (kind, rows, cols, grp) in enumerate(specs):
+        print(f"  packing {kind} {rows}x{cols} g={grp}", flush=True)
         w = synth.weights(rows, cols, 4700 + k)
         x = synth.activations(cols, 4700 + k)
         xd = G.to_dev(x.view(np.uint16)).view(torch.float16)
@@ -283,17 +285,17 @@ def test_row_block_list_on_ragged_shapes():
         y1 = torch.empty(rows, dtype=torch.float16, device="cuda")
         pick = G.sample_rows(rows, 40, k) if rows else np.zeros(0, dtype=np.int64)
         if kind == "d":
-            q, qp = B.quant_int4(w, 128)
+            q, qp = B.quant_int4(w, grp)
             qd, qpd = G.to_dev(q), G.to_dev(qp)
-            items.append(("dense", qd, qpd, rows, cols, 128, xd, y))
-            oq, oqp = O.quant_int4_dense(w[pick], 128)
+            items.append(("dense", qd, qpd, rows, cols, grp, xd, y))
+            oq, oqp = O.quant_int4_dense(w[pick], grp)
             assert np.array_equal(oq, q[pick]) and np.array_equal(oqp, qp[pick])
-            ref = O.int4_gemv(oq, oqp, 128, x)
-            B.int4_gemv(qd, qpd, rows, cols, 128, xd, y1)
+            ref = O.int4_gemv(oq, oqp, grp, x)
+            B.int4_gemv(qd, qpd, rows, cols, grp, xd, y1)
         else:
-            ph = B.pack_2bitcsr(w, B.prune_n4(w, 2), 2, 128, 0)
+            ph = B.pack_2bitcsr(w, B.prune_n4(w, 2), 2, grp, 0)
             if rows:
-                o = O.pack_2bitcsr(w[pick], O.prune_n4_magnitude(w[pick], 2), 2, 128, 0)
+                o = O.pack_2bitcsr(w[pick], O.prune_n4_magnitude(w[pick], 2), 2, grp, 0)
                 sub = G.row_subset(ph, pick)
                 for name in ("values", "idx", "qparams"):
                     assert np.array_equal(o[name], sub[name]), name
@@ -309,7 +311,7 @@ def test_row_block_list_on_ragged_shapes():
     for rep in range(3):
         call()
         torch.cuda.synchronize()
-        for k, (kind, rows, cols) in enumerate(specs):
+        for k, (kind, rows, cols, grp) in enumerate(specs):
             ybuf, y1, pick, ref = checks[k]
             host = ybuf.cpu().numpy().view(np.uint16)
             assert np.all(host[:64] == G.CANARY) and np.all(host[64 + rows:] == G.CANARY), ("write outside y", k)
