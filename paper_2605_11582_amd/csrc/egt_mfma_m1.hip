@@ -125,7 +125,13 @@ hipError_t launch_sparse_m1_batch(const egt_2bitcsr *ws, const uint16_t *const *
   if (g32) tpi = 4;
   const bool lin = w.val_kind == EGT_VAL_FP16 && !multirow && !tune_flag("EGT_M1_NOLIN");
   LaunchShape ls;
-  if (!m1_block_shape(g, lin, wpp, tpi, 1, 4, ls)) return hipErrorInvalidConfiguration;
+  if (!m1_block_shape(g, lin, wpp, tpi, 1, 4, ls)) {
+    // (a developer build's knobs may ask for a workgroup too small to stage x: the shipped shape then)
+    tpi = (g.phases == 3 || g32) ? (g32 ? 4 : 2) : 4;
+    wpp = (g.phases == 1 || g.phases == 3) ? 4 : 2;
+    if (wpp * g.phases > 16) wpp = 16 / g.phases;
+    if (!m1_block_shape(g, lin, wpp, tpi, 1, 4, ls)) return hipErrorInvalidConfiguration;
+  }
   const dim3 grid(ls.nblocks, count), block(64 * ls.nwaves);
   const size_t lds = ls.lds;
   const int xp = ls.xp;
