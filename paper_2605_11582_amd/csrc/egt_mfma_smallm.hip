@@ -652,8 +652,16 @@ __global__ __launch_bounds__(256) void k_smallm_sum_slices(const float *__restri
                                                            int rows, __half *__restrict__ Y, int64_t ldy) {
   const int r = blockIdx.x * 256 + threadIdx.x, m = blockIdx.y;
   if (r >= rows) return;
+  // (four slices requested before the first is added; the additions stay in ascending slice order)
   float sum = 0.f;
-  for (int s = 0; s < nslices; ++s) sum += ws[((int64_t)s * M + m) * ws_ld + r];
+  for (int s0 = 0; s0 < nslices; s0 += 4) {
+    float p[4];
+#pragma unroll
+    for (int k = 0; k < 4; ++k) p[k] = ws[((int64_t)min(s0 + k, nslices - 1) * M + m) * ws_ld + r];
+#pragma unroll
+    for (int k = 0; k < 4; ++k)
+      if (s0 + k < nslices) sum += p[k];
+  }
   Y[(int64_t)m * ldy + r] = sum != sum ? __ushort_as_half((uint16_t)0x7E00) : __float2half(sum);
 }
 

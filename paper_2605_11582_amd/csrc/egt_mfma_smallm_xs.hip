@@ -292,8 +292,18 @@ __global__ __launch_bounds__(256) void k_smallm_xs_sum(const float *__restrict__
   if (unit >= (int64_t)ntiles * ng) return;
   const int lane = threadIdx.x & 63, tile = (int)(unit / ng), grp = (int)(unit % ng);
   const int tok = 16 * grp + (lane & 15), row0 = 16 * tile + 4 * (lane >> 4);
+  // four slices are requested before the first is added (one memory latency per four slices, not per slice);
+  // the additions stay in ascending slice order
   f4 sum = f4{0.f, 0.f, 0.f, 0.f};
-  for (int s = 0; s < nslices; ++s) sum += *(const f4 *)(ws + (((int64_t)s * ntiles + tile) * ng + grp) * 256 + 4 * lane);
+  for (int s0 = 0; s0 < nslices; s0 += 4) {
+    f4 p[4];
+#pragma unroll
+    for (int k = 0; k < 4; ++k)
+      p[k] = *(const f4 *)(ws + (((int64_t)min(s0 + k, nslices - 1) * ntiles + tile) * ng + grp) * 256 + 4 * lane);
+#pragma unroll
+    for (int k = 0; k < 4; ++k)
+      if (s0 + k < nslices) sum += p[k];
+  }
   if (tok >= M || row0 >= rows) return;
   uint32_t h[4];
 #pragma unroll
