@@ -262,6 +262,27 @@ class Packed:
                       self.total_slots, self.row_n_keep)
 
 
+def concat_rows(packs) -> Packed:
+    """The host matrices `packs` (same columns, kept count, group size and value kind, uniform rows)
+    as one matrix with their rows one after the other: q/k/v or gate/up as a single product.  A row
+    of 2bit-CSR depends on nothing outside it, so this is a concatenation of the buffers (with the
+    row pointers continued) and equals packing the stacked dense matrix."""
+    p0 = packs[0]
+    for p in packs:
+        if not isinstance(p.values, np.ndarray):
+            raise ValueError("concat_rows takes host matrices")
+        if (p.cols, p.n_keep, p.group, p.val_kind) != (p0.cols, p0.n_keep, p0.group, p0.val_kind) or p.n_keep == 0:
+            raise ValueError("concat_rows takes uniformly shaped matrices of one format")
+    rows = sum(p.rows for p in packs)
+    slots_per_row = p0.n_keep * (p0.cols // 4)
+    if rows * slots_per_row >= 1 << 32:
+        raise ValueError("row pointers are 32-bit")
+    row_ptr = (np.arange(rows + 1, dtype=np.uint64) * slots_per_row).astype(np.uint32)
+    qparams = None if p0.qparams is None else np.concatenate([p.qparams for p in packs], axis=0)
+    return Packed(rows, p0.cols, p0.n_keep, p0.group, p0.val_kind, row_ptr,
+                  np.concatenate([p.values for p in packs]), np.concatenate([p.idx for p in packs]), qparams)
+
+
 def pack_2bitcsr(w: np.ndarray, mask: np.ndarray, n_keep: int, group: int, val_kind: int,
                  row_group=None) -> Packed:
     w = _row_major(_f16_bits(w))

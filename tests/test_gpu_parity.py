@@ -702,6 +702,27 @@ def test_sparse_gemm_batch_equals_separate_calls(rows, cols, n, g, kind, M, coun
             ybufs[k][1:M + 1, :rows].fill_(0)
 
 
+@pytest.mark.parametrize("M", [1, 3, 16, 40])
+def test_fused_projections_equal_the_separate_products(M):
+    # q/k/v packed as one matrix (concat_rows): every output has the bits of the separate product
+    torch = G.torch_mod()
+    rows, cols = (300, 70, 133), 4096
+    ps, os_ = [], []
+    for k, r in enumerate(rows):
+        p, o = _small_case(r, cols, 2, 128, 0, seed=7600 + k)
+        ps.append(p); os_.append(o)
+    fused = B.concat_rows(ps)
+    X = synth.activation_rows(M, cols, 7600 + M)
+    Yf = G.run_sparse_gemm(fused, X) if M > 1 else G.run_sparse_gemv(fused, X[0])[None, :]
+    at = 0
+    for k, r in enumerate(rows):
+        Y_ref, A_ref = O.gemm_smallm(os_[k], X)
+        G.assert_close(Yf[:, at:at + r], Y_ref, A_ref, f"fused member {k}")
+        Yk = G.run_sparse_gemm(ps[k], X) if M > 1 else G.run_sparse_gemv(ps[k], X[0])[None, :]
+        assert np.array_equal(np.ascontiguousarray(Yf[:, at:at + r]).view(np.uint16), Yk.view(np.uint16)), k
+        at += r
+
+
 @pytest.mark.parametrize("rows,cols,g,count", [(50, 4096, 128, 3), (21, 11008, 128, 2), (30, 320, 64, 2),
                                                (40, 4096, 64, 4), (40, 4096, 256, 2)])
 def test_int4_gemv_batch_equals_separate_calls(rows, cols, g, count):

@@ -488,6 +488,21 @@ def test_device_entry_points_reject_bad_arguments_without_a_gpu():
     assert L.egt_stream_read(None, 32, 16, None) == 1
 
 
+@pytest.mark.parametrize("n,g,kind", [(2, 128, 0), (1, 64, 0), (2, 0, 1), (3, 32, 2)])
+def test_concat_rows_equals_packing_the_stacked_matrix(n, g, kind):
+    # q/k/v as one matrix: concatenating three packed matrices gives the bytes of packing their rows stacked
+    ws = [synth.weights(r, 256, 8800 + k) for k, r in enumerate((37, 16, 50))]
+    masks = [B.prune_n4(w, n) for w in ws]
+    fused = B.concat_rows([B.pack_2bitcsr(w, m, n, g, kind) for w, m in zip(ws, masks)])
+    whole = B.pack_2bitcsr(np.concatenate(ws), np.concatenate(masks), n, g, kind)
+    assert (fused.rows, fused.cols, fused.n_keep, fused.group, fused.val_kind) == (103, 256, n, g, kind)
+    for name in ("row_ptr", "values", "idx", "qparams"):
+        a, b = getattr(fused, name), getattr(whole, name)
+        assert (a is None and b is None) or np.array_equal(a, b), name
+    with pytest.raises(ValueError):
+        B.concat_rows([B.pack_2bitcsr(ws[0], masks[0], n, g, kind), B.pack_2bitcsr(synth.weights(8, 128, 1), B.prune_n4(synth.weights(8, 128, 1), n), n, g, kind)])
+
+
 def _fake_items(views, dense=()):
     """Items over fake, aligned, never dereferenced device pointers."""
     n = len(views) + len(dense)
