@@ -563,15 +563,16 @@ def table(torch, B, synth, timer, dev, w, mask, xd, ys, calls, packed):
     rem = [6, 5, 4, 3, 2, 1]                         # tokens still to generate (average ID length 6)
     depth, gain = B.trigger_depth(layer_us[1], fit_a, fit_b, cand, rem)
     # the same products in layer order through a 32-layer all-2:4 stack (224 launches per pass)
-    stack_pass = {}
+    stack_pass, stack_one = {}, {}
     for M in (1, 16, 64):
-        seq = []
+        seq, items = [], []
         for layer in range(32):
             for mi in (2, 2, 2, 2, 0, 0, 1):          # q, k, v, o, gate, up, down
                 r5, k5, _, pk5 = pools[mi]
                 X = up16(synth.activation_rows(M, k5, 5))
                 Y = torch.empty((M, r5), dtype=torch.float16, device=dev)
                 pk = pk5[(layer * 7 + len(seq)) % len(pk5)]
+                items.append((pk, X, Y))
                 if (mi, M) in split_wins:
                     ws = torch.empty(B.smallm_ws_bytes(pk, M), dtype=torch.uint8, device=dev)
                     seq.append(B.prepared_sparse_gemm_smallm_ws(pk, X, Y, ws))
@@ -582,9 +583,14 @@ def table(torch, B, synth, timer, dev, w, mask, xd, ys, calls, packed):
             for c in seq:
                 c()
         stack_pass[str(M)] = round(timer(run_seq, 5, 1)["median"] * 1e6, 1)
-        del seq
+        if M >= 2:                                    # the same 224 products as one table, one launch
+            whole = B.prepared_gemm_stack(items)
+            stack_one[str(M)] = round(timer(lambda i: whole(), 5, 1)["median"] * 1e6, 1)
+            del whole
+        del seq, items
     t["trigger_model"] = {"layer_us_by_M": [round(layer_us[m], 2) for m in sweep_m], "M": [sweep_m[0], sweep_m[-1]],
                           "stack_pass_us_224_launches_by_M": stack_pass,
+                          "stack_pass_us_one_launch_by_M": stack_one,
                           "stack_pass_us_32_times_layer_by_M": {str(m): round(32 * layer_us[m], 1) for m in (1, 16, 64)},
                           "fit_a_us": round(fit_a, 3), "fit_b_us_per_token": round(fit_b, 4),
                           "t_ar_us": round(layer_us[1], 2), "candidates": cand, "remaining": rem,

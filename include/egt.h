@@ -342,6 +342,48 @@ egt_status egt_gemv_stack_plan(const egt_gemv_item *items, int count, int form, 
  * in egt_sparse_gemv / egt_int4_gemv (a broken row_ptr entry gives NaN in that row). */
 egt_status egt_gemv_stack_run(const void *table_dev, const egt_stack_plan *plan, void *stream);
 
+/* A verification step through a stack of layers (Sec. 3.4 "Parallel Verification Trigger":
+ * one step checks M candidate tokens against every layer): any number of small-M products
+ * Y_k = X_k . W_k^T of different shapes in one launch.  A single product has to spread one
+ * matrix over the whole chip; a table of them lets every compute unit work on several
+ * matrices at once with small workgroups, which more than halves the time per product
+ * (and the fixed cost of a launch is paid once per table).  Items: W a 2:4 INT4 2bit-CSR
+ * view with group_size >= 64 (device buffers) and at least 832 columns (four K-steps of
+ * 256); X: M x cols FP16 with the token rows back to back (ldx = cols), Y: M x rows FP16
+ * (ldy = rows), device pointers, X 16-byte aligned.  Other shapes give
+ * EGT_ERR_UNSUPPORTED: they run as single products. */
+typedef struct {
+  const egt_2bitcsr *sparse;
+  const uint16_t *X;
+  uint16_t *Y;
+} egt_gemm_item;
+
+typedef struct {
+  int32_t count;         /* matrices in the table                                            */
+  int32_t M;             /* tokens of every product (2..64)                                  */
+  int32_t grid_x;        /* workgroups per matrix                                            */
+  int32_t block_threads; /* threads per workgroup                                            */
+  int32_t lds_bytes;     /* dynamic LDS per workgroup                                        */
+  int32_t reserved;
+  uint64_t table_bytes;  /* count * EGT_STACK_ENTRY_BYTES                                    */
+} egt_gemm_plan;
+
+/* HOST.  As egt_gemv_stack_plan: checks `count` (1..65535) items for M tokens each, writes
+ * the launch shape to *plan and, with table != NULL, one descriptor per item to `table`
+ * (HOST memory of the caller, table_bytes >= plan->table_bytes, else EGT_ERR_SHAPE), which
+ * the caller copies to 16-byte aligned device memory.  Items with rows == 0 compute
+ * nothing.  Nothing is written when an error is returned. */
+egt_status egt_gemm_stack_plan(const egt_gemm_item *items, int count, int M, void *table,
+                               size_t table_bytes, egt_gemm_plan *plan);
+
+/* DEVICE.  Runs every product of the table in one launch on `stream`.  The table and every
+ * buffer it names stay valid until the launch has completed; no Y may alias an X or another
+ * Y of the table.  Each Y[m][r] is the FP16 rounding of an FP32 sum of the same products as
+ * in egt_sparse_gemm_smallm; the sum is split over 4 waves instead of 8 or 16, so the two
+ * may differ in the last bit.  The result does not depend on the other items of the table
+ * or on the run.  A broken row_ptr entry gives NaN in that row. */
+egt_status egt_gemm_stack_run(const void *table_dev, const egt_gemm_plan *plan, void *stream);
+
 /* HOST.  Cost model of the parallel-verification trigger (Sec. 3.4 "Parallel
  * Verification Trigger"): the paper observes that the cost of a verification step grows
  * linearly with the number of candidate tokens while an autoregressive step costs a

@@ -29,6 +29,7 @@ SYMBOLS = (
     "egt_pack_2bitcsr_rows", "egt_2bitcsr_sizes_rows",
     "egt_gemv_stack_plan", "egt_gemv_stack_run", "egt_sparse_gemm_smallm_ws_bytes", "egt_sparse_gemm_smallm_ws",
     "egt_sparse_gemm_smallm_static", "egt_sparse_gemm_smallm_batch",
+    "egt_gemm_stack_plan", "egt_gemm_stack_run",
 )
 
 
@@ -58,6 +59,17 @@ class StackPart(C.Structure):
     _fields_ = [("count", C.c_int32), ("mode", C.c_int32), ("grid_x", C.c_int32), ("block_threads", C.c_int32),
                 ("lds_bytes", C.c_int32), ("x_pieces", C.c_int32), ("forms", C.c_int32), ("nitems", C.c_int32),
                 ("part_offset", C.c_int32), ("reserved", C.c_int32), ("table_bytes", C.c_uint64)]
+
+
+class GemmItem(C.Structure):
+    """Mirror of `egt_gemm_item`."""
+    _fields_ = [("sparse", C.POINTER(View)), ("X", C.c_void_p), ("Y", C.c_void_p)]
+
+
+class GemmPlan(C.Structure):
+    """Mirror of `egt_gemm_plan`."""
+    _fields_ = [("count", C.c_int32), ("M", C.c_int32), ("grid_x", C.c_int32), ("block_threads", C.c_int32),
+                ("lds_bytes", C.c_int32), ("reserved", C.c_int32), ("table_bytes", C.c_uint64)]
 
 
 STACK_MAX_PARTS = 2
@@ -122,6 +134,8 @@ def _declare(L: C.CDLL, names=None) -> C.CDLL:
                                C.POINTER(C.c_double)], C.c_int),
         "egt_gemv_stack_plan": ([C.POINTER(GemvItem), C.c_int, C.c_int, C.c_void_p, C.c_size_t, C.POINTER(StackPlan)], C.c_int),
         "egt_gemv_stack_run": ([C.c_void_p, C.POINTER(StackPlan), C.c_void_p], C.c_int),
+        "egt_gemm_stack_plan": ([C.POINTER(GemmItem), C.c_int, C.c_int, C.c_void_p, C.c_size_t, C.POINTER(GemmPlan)], C.c_int),
+        "egt_gemm_stack_run": ([C.c_void_p, C.POINTER(GemmPlan), C.c_void_p], C.c_int),
         "egt_sparse_gemm_smallm_ws_bytes": ([C.POINTER(View), C.c_int64, C.c_int, C.POINTER(C.c_size_t)], C.c_int),
         "egt_sparse_gemm_smallm_ws": ([C.POINTER(View), C.c_void_p, C.c_int64, C.c_void_p, C.c_int64, C.c_int, C.c_void_p,
                                        C.c_size_t, C.c_void_p], C.c_int),
@@ -638,6 +652,41 @@ def prepared_gemv_stack(items, stream=None, form=STACK_AUTO):
     dev = keep[0][-1].device
     table_dev = torch.from_numpy(table).to(dev)
     fn, tp, ref, sp = lib().egt_gemv_stack_run, table_dev.data_ptr(), C.byref(plan), _stream_ptr(stream)
+
+    def call(stream_ptr=sp, _keep=(table_dev, plan, keep, views, arr)):
+        st = fn(tp, ref, stream_ptr)
+        if st:
+            _check(st)
+    call.plan = plan
+    return call
+
+
+def prepared_gemm_stack(items, stream=None):
+    """One launch for a list of small-M products Y = X . W^T under the same number of tokens.
+
+    items: tuples (Packed, X, Y) with contiguous device tensors X (M, cols) and Y (M, rows).
+    The descriptor table is planned by the library on the host and uploaded here into a
+    device tensor that the returned call keeps alive."""
+    import torch
+    n = len(items)
+    arr = (GemmItem * n)()
+    views, keep = [], []
+    M = int(items[0][1].shape[0]) if n else 0
+    for k, (p, X, Y) in enumerate(items):
+        _check_xy(p, X, Y)
+        if X.shape[0] != M or not X.is_contiguous() or not Y.is_contiguous():
+            raise ValueError("every X and Y of the table must be contiguous and hold the same number of tokens")
+        v = p.view()
+        views.append(v)
+        arr[k].sparse = C.pointer(v)
+        arr[k].X, arr[k].Y = _dev(X), _dev(Y)
+        keep.append((p, X, Y))
+    plan = GemmPlan()
+    _check(lib().egt_gemm_stack_plan(arr, n, M, None, 0, C.byref(plan)))    # size query
+    table = np.zeros(int(plan.table_bytes), dtype=np.uint8)
+    _check(lib().egt_gemm_stack_plan(arr, n, M, _np_ptr(table), table.nbytes, C.byref(plan)))
+    table_dev = torch.from_numpy(table).to(keep[0][2].device)
+    fn, tp, ref, sp = lib().egt_gemm_stack_run, table_dev.data_ptr(), C.byref(plan), _stream_ptr(stream)
 
     def call(stream_ptr=sp, _keep=(table_dev, plan, keep, views, arr)):
         st = fn(tp, ref, stream_ptr)

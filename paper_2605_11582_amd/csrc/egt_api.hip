@@ -4,6 +4,7 @@
 
 #include "egt_tune.h"
 
+#include <cstring>
 #include <mutex>
 
 namespace {
@@ -254,6 +255,49 @@ egt_status egt_sparse_gemm_smallm_batch(const egt_2bitcsr *w, const uint16_t *co
       return EGT_ERR_BUFFER;
   }
   return done(egt::launch_sparse_gemm_batch(w, X, ldx, Y, ldy, M, count, (hipStream_t)stream));
+}
+
+egt_status egt_gemm_stack_plan(const egt_gemm_item *items, int count, int M, void *table, size_t table_bytes,
+                               egt_gemm_plan *plan) {
+  if (!items || !plan) return EGT_ERR_NULL;
+  if (count < 1 || count > 65535 || M < 2 || M > 64) return EGT_ERR_SHAPE;
+  for (int k = 0; k < count; ++k) {
+    const egt_2bitcsr *w = items[k].sparse;
+    if (!w) return EGT_ERR_NULL;
+    const egt_status st = check_view(w);
+    if (st != EGT_OK) return st;
+    if (w->rows != 0 && (!items[k].X || !items[k].Y)) return EGT_ERR_NULL;
+    if (!aligned16(w->row_ptr) || !aligned16(w->values) || !aligned16(w->idx) || !aligned16(w->qparams) ||
+        !aligned16(items[k].X))
+      return EGT_ERR_BUFFER;
+    if (!egt::smallm_stack_item_ok(*w, M)) return EGT_ERR_UNSUPPORTED;
+  }
+  egt_gemm_plan out;
+  std::memset(&out, 0, sizeof(out));
+  out.count = count;
+  out.M = M;
+  out.grid_x = egt::smallm_stack_blocks(M);
+  egt::smallm_stack_shape(M, out.block_threads, out.lds_bytes);
+  out.table_bytes = (uint64_t)count * EGT_STACK_ENTRY_BYTES;
+  if (table) {
+    if ((uint64_t)table_bytes < out.table_bytes) return EGT_ERR_SHAPE;
+    for (int k = 0; k < count; ++k)
+      egt::smallm_stack_entry(*items[k].sparse, items[k].X, items[k].Y, M, (uint8_t *)table + (size_t)k * EGT_STACK_ENTRY_BYTES);
+  }
+  *plan = out;
+  return EGT_OK;
+}
+
+egt_status egt_gemm_stack_run(const void *table_dev, const egt_gemm_plan *plan, void *stream) {
+  if (!table_dev || !plan) return EGT_ERR_NULL;
+  if (!aligned16(table_dev)) return EGT_ERR_BUFFER;
+  if (plan->count < 1 || plan->count > 65535 || plan->M < 2 || plan->M > 64) return EGT_ERR_SHAPE;
+  int threads, lds;
+  egt::smallm_stack_shape(plan->M, threads, lds);
+  if (plan->grid_x != egt::smallm_stack_blocks(plan->M) || plan->block_threads != threads || plan->lds_bytes != lds ||
+      plan->table_bytes != (uint64_t)plan->count * EGT_STACK_ENTRY_BYTES)
+    return EGT_ERR_SHAPE;
+  return done(egt::launch_smallm_stack(table_dev, plan->count, plan->M, (hipStream_t)stream));
 }
 
 egt_status egt_int4_gemv_batch(const uint8_t *const *q, const uint16_t *const *qparams, int rows,

@@ -44,6 +44,8 @@
 
 #include "egt_tune.h"
 
+#include <cstring>
+
 namespace egt {
 
 struct SmallMKsGeom {
@@ -850,6 +852,94 @@ static hipError_t smallm_one_launch(const egt_2bitcsr &w, const uint16_t *X, int
 hipError_t launch_sparse_smallm(const egt_2bitcsr &w, const uint16_t *X, int64_t ldx, uint16_t *Y,
                                 int64_t ldy, int M, hipStream_t stream) {
   return smallm_one_launch(w, X, ldx, Y, ldy, M, stream, nullptr, 1);
+}
+
+// ---- Any number of small-M products in one launch (a verification pass through a whole
+// stack of 2:4 INT4 layers): blockIdx.y names the matrix, whose descriptor - pointers and
+// geometry - lies in a table in device memory of the caller; its workgroups run the body of
+// the single-matrix kernel in the form that takes row tiles in rounds.
+// The single product spreads one matrix over the whole chip: one 16-wave workgroup per
+// compute unit, K split over its waves.  Such a workgroup runs its loads, products and the
+// sum across waves one after the other, and nothing else is resident to fill the gaps.  With
+// many matrices at hand the stack does the opposite: 4-wave workgroups, four (two beyond 16
+// tokens) resident per compute unit, and few of them per matrix - each takes several rounds
+// of row tiles, and the compute units work on several matrices at once (16 layers of a 7B
+// stack, 1.3 GB, 16 tokens: 461 us against 951 us of single products replayed from a
+// graph; 64 tokens: 954 against 2008 us).
+struct SmallMStackEntry {
+  uint64_t row_ptr, values, idx, qparams, X, Y;      // device addresses
+  SmallMKsGeom g;
+};
+static_assert(sizeof(SmallMStackEntry) <= EGT_STACK_ENTRY_BYTES, "descriptor larger than the published entry size");
+// Launch shape: waves per workgroup, row tiles per round, workgroups per matrix; up to 16
+// tokens and beyond.  Build macros, for timing other shapes.
+#ifndef EGT_GS_WAVES
+#define EGT_GS_WAVES 4
+#endif
+#ifndef EGT_GS_BLOCKS
+#define EGT_GS_BLOCKS 96
+#endif
+#ifndef EGT_GSW_WAVES
+#define EGT_GSW_WAVES 4
+#endif
+#ifndef EGT_GSW_BLOCKS
+#define EGT_GSW_BLOCKS 64
+#endif
+constexpr int GS_NIT = 3, GSW_NIT = 4;
+
+// (minimum waves per SIMD: 128 registers a lane with one token group per pass, 256 with two)
+template <int NT, int NIT, int NWMAX>
+__global__ __launch_bounds__(64 * NWMAX, NT == 1 ? 4 : 2) void k_smallm_stack(const uint8_t *__restrict__ table) {
+  typedef __attribute__((address_space(1))) const uint32_t *g_u32;
+  typedef __attribute__((address_space(1))) const uint8_t *g_u8;
+  typedef __attribute__((address_space(1))) const __half *g_h;
+  typedef __attribute__((address_space(1))) __half *g_hw;
+  const SmallMStackEntry *e = (const SmallMStackEntry *)(table + (size_t)blockIdx.y * EGT_STACK_ENTRY_BYTES);
+  const SmallMKsGeom g = e->g;
+  if ((int)blockIdx.x >= g.ntiles) return;            // (uniform: the whole workgroup leaves)
+  // (addresses from a table are cast to the global address space: as generic pointers their loads would be flat)
+  smallm_ks_body<EGT_VAL_INT4, NT, NIT, NWMAX, 1, false, true, false>(
+      (const uint32_t *)(g_u32)e->row_ptr, (const uint8_t *)(g_u8)e->values, (const uint8_t *)(g_u8)e->idx,
+      (const uint8_t *)(g_u8)e->qparams, (const __half *)(g_h)e->X, (__half *)(g_hw)e->Y, g);
+}
+
+// Shapes the stack form takes: what the single call runs on this kernel with one {scale, zero} pair per chunk,
+// and rows long enough for every wave of the workgroup to own a K-step of 256 columns.
+bool smallm_stack_item_ok(const egt_2bitcsr &w, int M) {
+  if (w.val_kind != EGT_VAL_INT4 || w.n_keep != 2 || w.group_size < 64) return false;
+  if (!sparse_smallm_supported(w, w.cols, M)) return false;
+  const int nsteps = (w.cols / 64 + 3) / 4;
+  return nsteps >= (M > 16 ? EGT_GSW_WAVES : EGT_GS_WAVES);
+}
+
+int smallm_stack_blocks(int M) { return M > 16 ? EGT_GSW_BLOCKS : EGT_GS_BLOCKS; }
+
+void smallm_stack_shape(int M, int &block_threads, int &lds_bytes) {
+  const bool wide = M > 16;
+  const int nw = wide ? EGT_GSW_WAVES : EGT_GS_WAVES, nit = wide ? GSW_NIT : GS_NIT, nt = wide ? 2 : 1;
+  const size_t x_bytes = (size_t)nw * 8 * KS_PAIR, p_bytes = (size_t)nw * nit * nt * 1024;
+  block_threads = 64 * nw;
+  lds_bytes = (int)((nt > 1 ? x_bytes + p_bytes : x_bytes) + 64 * nit);
+}
+
+// Descriptor of one item into 160 bytes of the table.
+void smallm_stack_entry(const egt_2bitcsr &w, const uint16_t *X, uint16_t *Y, int M, void *entry) {
+  SmallMStackEntry e;
+  std::memset(&e, 0, sizeof(e));
+  int qw;
+  smallm_geometry(w, w.cols, Y, w.rows, M, e.g, qw);
+  e.row_ptr = (uint64_t)(uintptr_t)w.row_ptr; e.values = (uint64_t)(uintptr_t)w.values; e.idx = (uint64_t)(uintptr_t)w.idx;
+  e.qparams = (uint64_t)(uintptr_t)w.qparams; e.X = (uint64_t)(uintptr_t)X; e.Y = (uint64_t)(uintptr_t)Y;
+  std::memset(entry, 0, EGT_STACK_ENTRY_BYTES);
+  std::memcpy(entry, &e, sizeof(e));
+}
+
+hipError_t launch_smallm_stack(const void *table_dev, int count, int M, hipStream_t stream) {
+  int threads, lds;
+  smallm_stack_shape(M, threads, lds);
+  const dim3 grid(smallm_stack_blocks(M), count), block(threads);
+  if (M > 16) return launch(k_smallm_stack<2, GSW_NIT, EGT_GSW_WAVES>, grid, block, (size_t)lds, stream, (const uint8_t *)table_dev);
+  return launch(k_smallm_stack<1, GS_NIT, EGT_GS_WAVES>, grid, block, (size_t)lds, stream, (const uint8_t *)table_dev);
 }
 
 // `count` (2..4) identically shaped members in one launch (the caller has checked the shapes

@@ -475,6 +475,73 @@ def test_smallm_kernels_replay_in_a_hip_graph():
             assert np.array_equal(Y.cpu().numpy().view(np.uint16), eager[k].view(np.uint16)), (rep, k)
 
 
+@pytest.mark.parametrize("M", [2, 5, 16, 17, 40, 64])
+def test_gemm_stack_equals_the_oracle_and_the_separate_products(M):
+    # a verification step through several layers in one launch: shapes with fewer row tiles than
+    # workgroups, a ragged last tile, several rounds of row tiles, a row length that ends inside
+    # a K-step, an empty matrix; Y buffers with and without 8-byte alignment, canaries around
+    torch = G.torch_mod()
+    print(f"case gemm stack M={M}", flush=True)
+    shapes = [(300, 4096, 128), (70, 11008, 128), (16 * 96 * 8 + 40, 4096, 4096), (133, 8192, 64), (0, 4096, 128),
+              (21, 4160, 64), (50, 832, 64), (1700, 2048, 128)]
+    ps, os_, Xs = [], [], []
+    for k, (rows, cols, g) in enumerate(shapes):
+        w = synth.weights(rows, cols, 8800 + 7 * k + M)
+        mask = O.prune_n4_magnitude(w, 2)
+        ps.append(B.pack_2bitcsr(w, mask, 2, g, B.VAL_INT4))
+        os_.append(O.pack_2bitcsr(w, mask, 2, g, B.VAL_INT4) if 0 < rows <= 400 else None)
+        Xs.append(synth.activation_rows(M, cols, 8800 + k))
+    pds = [p.to("cuda:0") for p in ps]
+    Xd = [G.to_dev(X.view(np.uint16)).view(torch.float16) for X in Xs]
+    guards = [64, 3, 64, 1, 64, 64, 2, 64]
+    ybufs = [torch.full((2 * gd + M * p.rows,), G.CANARY, dtype=torch.int16, device="cuda:0") for gd, p in zip(guards, ps)]
+    Yd = [yb[gd:gd + M * p.rows].view(torch.float16).view(M, p.rows) for yb, gd, p in zip(ybufs, guards, ps)]
+    call = B.prepared_gemm_stack(list(zip(pds, Xd, Yd)))
+    assert (call.plan.count, call.plan.M, call.plan.grid_x, call.plan.block_threads) == (len(shapes), M, 96 if M <= 16 else 64, 256)
+    first = {}
+    for rep in range(2):
+        call()
+        torch.cuda.synchronize()
+        for k, p in enumerate(ps):
+            host = ybufs[k].cpu().numpy().view(np.uint16)
+            gd = guards[k]
+            assert np.all(host[:gd] == G.CANARY) and np.all(host[gd + M * p.rows:] == G.CANARY), ("write outside Y", k)
+            if p.rows == 0:
+                continue
+            Y = host[gd:gd + M * p.rows].view(np.float16).reshape(M, p.rows)
+            rows = G.sample_rows(p.rows, 400, 8800 + k) if p.rows > 400 else np.arange(p.rows)
+            Y_ref, A_ref = O.gemm_smallm(G.row_subset(ps[k], rows) if p.rows > 400 else os_[k], Xs[k])
+            G.assert_close(Y[:, rows], Y_ref, A_ref, f"gemm stack member {k}")
+            if rep == 0:
+                first[k] = Y.copy()
+            else:
+                assert np.array_equal(Y.view(np.uint16), first[k].view(np.uint16)), ("second run differs", k)
+            ybufs[k][gd:gd + M * p.rows].fill_(0)
+    # the same bits whatever else the table holds: two of the members, in the other order, as a table of their own
+    Y2 = {k: torch.zeros((M, ps[k].rows), dtype=torch.float16, device="cuda:0") for k in (3, 0)}
+    B.prepared_gemm_stack([(pds[k], Xd[k], Y2[k]) for k in (3, 0)])()
+    torch.cuda.synchronize()
+    for k in (3, 0):
+        assert np.array_equal(Y2[k].cpu().numpy().view(np.uint16), first[k].view(np.uint16)), ("other table differs", k)
+
+
+def test_gemm_stack_rejects_what_it_does_not_run():
+    torch = G.torch_mod()
+    w = synth.weights(64, 4096, 1)
+    X = torch.zeros((8, 4096), dtype=torch.float16, device="cuda:0")
+    Y = torch.zeros((8, 64), dtype=torch.float16, device="cuda:0")
+    for n, g, kind in ((1, 128, B.VAL_INT4), (2, 32, B.VAL_INT4), (2, 0, B.VAL_FP16)):
+        p = B.pack_2bitcsr(w, B.prune_n4(w, n), n, g, kind).to("cuda:0")
+        with pytest.raises(B.EgtError) as e:
+            B.prepared_gemm_stack([(p, X, Y)])
+        assert e.value.status == 6
+    w2 = synth.weights(64, 768, 2)                        # three K-steps: too few for the four waves
+    p2 = B.pack_2bitcsr(w2, B.prune_n4(w2, 2), 2, 128, B.VAL_INT4).to("cuda:0")
+    with pytest.raises(B.EgtError) as e:
+        B.prepared_gemm_stack([(p2, X[:, :768].contiguous(), Y)])
+    assert e.value.status == 6
+
+
 def test_two_streams_at_once_give_the_serial_results():
     # the library keeps no state between calls: products enqueued on two streams (default
     # priority) at the same time equal the ones computed one after the other, bit for bit

@@ -579,6 +579,59 @@ def test_stack_plan_checks_items_and_reports_the_launch_shape():
     assert L.egt_gemv_stack_run(16, ctypes.byref(empty), None) == 0       # all matrices empty: nothing to launch
 
 
+def test_gemm_stack_plan_checks_items_and_reports_the_launch_shape():
+    L = B.lib()
+    views = [B.View(4096, 4096, 2, 128, 0, 16, 16, 16, 16), B.View(4096, 11008, 2, 128, 0, 16, 16, 16, 16),
+             B.View(0, 4096, 2, 128, 0, None, None, None, None)]
+    items = (B.GemmItem * 3)()
+    for k, v in enumerate(views):
+        items[k].sparse, items[k].X, items[k].Y = ctypes.pointer(v), 16, 16
+    plan = B.GemmPlan()
+    assert L.egt_gemm_stack_plan(items, 3, 16, None, 0, ctypes.byref(plan)) == 0
+    # up to 16 tokens: 96 workgroups of 4 waves per matrix; per wave eight pairs of token rows of 1056 bytes;
+    # row flags of three tiles
+    assert (plan.count, plan.M, plan.grid_x, plan.block_threads, plan.lds_bytes, plan.table_bytes) == \
+        (3, 16, 96, 256, 4 * 8 * 1056 + 192, 3 * B.STACK_ENTRY_BYTES)
+    wide = B.GemmPlan()
+    assert L.egt_gemm_stack_plan(items, 3, 17, None, 0, ctypes.byref(wide)) == 0
+    # beyond: 64 workgroups; the partial sums (4 tiles x 2 token groups of 1 KiB per wave) behind the token rows
+    assert (wide.grid_x, wide.block_threads, wide.lds_bytes) == (64, 256, 4 * 8 * 1056 + 4 * 8 * 1024 + 256)
+    table = np.full(3 * B.STACK_ENTRY_BYTES, 0xA5, dtype=np.uint8)
+    assert L.egt_gemm_stack_plan(items, 3, 16, table.ctypes.data, table.nbytes - 1, ctypes.byref(plan)) == 2
+    assert np.all(table == 0xA5)
+    assert L.egt_gemm_stack_plan(items, 3, 16, table.ctypes.data, table.nbytes, ctypes.byref(plan)) == 0
+    assert not np.all(table == 0xA5)
+    # errors leave table and plan untouched
+    table[:] = 0xA5
+    plan2 = B.GemmPlan(-1)
+    for M in (1, 65):
+        assert L.egt_gemm_stack_plan(items, 3, M, table.ctypes.data, table.nbytes, ctypes.byref(plan2)) == 2
+    assert L.egt_gemm_stack_plan(items, 0, 16, table.ctypes.data, table.nbytes, ctypes.byref(plan2)) == 2
+    assert L.egt_gemm_stack_plan(None, 3, 16, table.ctypes.data, table.nbytes, ctypes.byref(plan2)) == 1
+    items[1].X = None
+    assert L.egt_gemm_stack_plan(items, 3, 16, table.ctypes.data, table.nbytes, ctypes.byref(plan2)) == 1
+    items[1].X = 24
+    assert L.egt_gemm_stack_plan(items, 3, 16, table.ctypes.data, table.nbytes, ctypes.byref(plan2)) == 5
+    items[1].X = 16
+    for bad in (B.View(64, 4096, 1, 128, 0, 16, 16, 16, 16), B.View(64, 4096, 2, 32, 0, 16, 16, 16, 16),
+                B.View(64, 4096, 2, 0, 1, 16, 16, 16, None), B.View(64, 768, 2, 128, 0, 16, 16, 16, 16)):
+        items[0].sparse = ctypes.pointer(bad)
+        assert L.egt_gemm_stack_plan(items, 3, 16, table.ctypes.data, table.nbytes, ctypes.byref(plan2)) == 6
+    assert np.all(table == 0xA5) and plan2.count == -1
+    short = B.View(64, 832, 2, 64, 0, 16, 16, 16, 16)       # 13 chunks of 64 columns: the fourth K-step has begun
+    items[0].sparse = ctypes.pointer(short)
+    assert L.egt_gemm_stack_plan(items, 3, 17, table.ctypes.data, table.nbytes, ctypes.byref(plan2)) == 0
+    assert not np.all(table == 0xA5) and plan2.count == 3
+    # the run call checks the plan before anything is launched
+    assert L.egt_gemm_stack_run(None, ctypes.byref(plan), None) == 1
+    assert L.egt_gemm_stack_run(24, ctypes.byref(plan), None) == 5
+    for field, value in (("count", 0), ("M", 1), ("M", 17), ("grid_x", 256), ("block_threads", 512), ("lds_bytes", 1024),
+                         ("table_bytes", 160)):
+        broken = B.GemmPlan.from_buffer_copy(plan)
+        setattr(broken, field, value)
+        assert L.egt_gemm_stack_run(16, ctypes.byref(broken), None) == 2, field
+
+
 def test_stack_plan_cuts_a_large_table_into_row_blocks():
     # three decoder layers of 2:4 and dense INT4 matrices (more than 256 MB): resident
     # workgroups walk a list of row blocks; the list covers every row of every matrix exactly once
