@@ -203,6 +203,8 @@ def main():
                          "ceilings, table or oracle, then the --counter-workloads launches and five whole-stack launches")
     ap.add_argument("--only-stack", action="store_true",
                     help="time the whole-stack launch of configuration 4 only (for sweeps of a tuning build)")
+    ap.add_argument("--only-verify-stack", type=int, default=0, metavar="M",
+                    help="time the one-launch verification step of M tokens through the 2:4 layers of configuration 4 only")
     ap.add_argument("--cpu-worker", default=None, help=argparse.SUPPRESS)
     args = ap.parse_args()
     if args.cpu_worker:
@@ -256,6 +258,17 @@ def main():
         row = entry(timer(lambda i: whole(), 30, 5), stk.nbytes)
         row.update(mode=plan.mode, grid=plan.grid_x, block_threads=plan.block_threads, lds_bytes=plan.lds_bytes, items=plan.nitems)
         print(json.dumps({"only_stack": True, "config4_whole_stack": row}))
+        return
+
+    if args.only_verify_stack:
+        from paper_2605_11582_amd import stack as S
+        del packed[:], calls[:]
+        stk = S.LayerStack.build(dev, distinct_layers=1)     # the traffic of all matrices; the numbers repeat
+        step, step_bytes = stk.verify_step(args.only_verify_stack)
+        plan = step.plan
+        row = entry(timer(lambda i: step(), 30, 5), step_bytes)
+        row.update(M=plan.M, matrices=plan.count, grid=[plan.grid_x, plan.count], block_threads=plan.block_threads, lds_bytes=plan.lds_bytes)
+        print(json.dumps({"only_verify_stack": True, "config4_sparse_layers_one_launch": row}))
         return
 
     if args.counter_run:

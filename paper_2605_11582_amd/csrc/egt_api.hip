@@ -261,6 +261,7 @@ egt_status egt_gemm_stack_plan(const egt_gemm_item *items, int count, int M, voi
                                egt_gemm_plan *plan) {
   if (!items || !plan) return EGT_ERR_NULL;
   if (count < 1 || count > 65535 || M < 2 || M > 64) return EGT_ERR_SHAPE;
+  int max_rows = 0;
   for (int k = 0; k < count; ++k) {
     const egt_2bitcsr *w = items[k].sparse;
     if (!w) return EGT_ERR_NULL;
@@ -271,12 +272,13 @@ egt_status egt_gemm_stack_plan(const egt_gemm_item *items, int count, int M, voi
         !aligned16(items[k].X))
       return EGT_ERR_BUFFER;
     if (!egt::smallm_stack_item_ok(*w, M)) return EGT_ERR_UNSUPPORTED;
+    max_rows = w->rows > max_rows ? w->rows : max_rows;
   }
   egt_gemm_plan out;
   std::memset(&out, 0, sizeof(out));
   out.count = count;
   out.M = M;
-  out.grid_x = egt::smallm_stack_blocks(M);
+  out.grid_x = egt::smallm_stack_blocks(M, max_rows);
   egt::smallm_stack_shape(M, out.block_threads, out.lds_bytes);
   out.table_bytes = (uint64_t)count * EGT_STACK_ENTRY_BYTES;
   if (table) {
@@ -294,10 +296,13 @@ egt_status egt_gemm_stack_run(const void *table_dev, const egt_gemm_plan *plan, 
   if (plan->count < 1 || plan->count > 65535 || plan->M < 2 || plan->M > 64) return EGT_ERR_SHAPE;
   int threads, lds;
   egt::smallm_stack_shape(plan->M, threads, lds);
-  if (plan->grid_x != egt::smallm_stack_blocks(plan->M) || plan->block_threads != threads || plan->lds_bytes != lds ||
+  // (workgroups per matrix: what the plan call derived from the tallest matrix of the table)
+  if (plan->grid_x < 0 || plan->grid_x > (1 << 20) || (plan->M > 16 && plan->grid_x > egt::smallm_stack_blocks(plan->M, 1)) ||
+      plan->block_threads != threads || plan->lds_bytes != lds ||
       plan->table_bytes != (uint64_t)plan->count * EGT_STACK_ENTRY_BYTES)
     return EGT_ERR_SHAPE;
-  return done(egt::launch_smallm_stack(table_dev, plan->count, plan->M, (hipStream_t)stream));
+  if (plan->grid_x == 0) return EGT_OK;               // every matrix is empty
+  return done(egt::launch_smallm_stack(table_dev, plan->count, plan->M, plan->grid_x, (hipStream_t)stream));
 }
 
 egt_status egt_int4_gemv_batch(const uint8_t *const *q, const uint16_t *const *qparams, int rows,

@@ -856,40 +856,36 @@ hipError_t launch_sparse_smallm(const egt_2bitcsr &w, const uint16_t *X, int64_t
 
 // ---- Any number of small-M products in one launch (a verification pass through a whole
 // stack of 2:4 INT4 layers): blockIdx.y names the matrix, whose descriptor - pointers and
-// geometry - lies in a table in device memory of the caller; its workgroups run the body of
-// the single-matrix kernel in the form that takes row tiles in rounds.
-// The single product spreads one matrix over the whole chip: one 16-wave workgroup per
+// geometry - lies in a table in device memory of the caller.
+// The single product has to spread one matrix over the whole chip: one 16-wave workgroup per
 // compute unit, K split over its waves.  Such a workgroup runs its loads, products and the
-// sum across waves one after the other, and nothing else is resident to fill the gaps.  With
-// many matrices at hand the stack does the opposite: 4-wave workgroups, four (two beyond 16
-// tokens) resident per compute unit, and few of them per matrix - each takes several rounds
-// of row tiles, and the compute units work on several matrices at once (16 layers of a 7B
-// stack, 1.3 GB, 16 tokens: 461 us against 951 us of single products replayed from a
-// graph; 64 tokens: 954 against 2008 us).
+// sum across waves one after the other, and nothing else is resident to fill the gaps.  A
+// table offers many matrices at once, so the stack uses small workgroups, two or more
+// resident per compute unit, few per matrix, and the compute units work on several matrices
+// at the same time.  Two forms:
+//   more than 16 tokens: the body of the single-matrix kernel (K split over 4 waves, row tiles
+//     in rounds of 4, two token groups per pass), 64 workgroups per matrix (16 layers of a 7B
+//     stack, 1.3 GB, 64 tokens: 954 us against 2008 us of single products replayed from a
+//     graph; 32 tokens: 545 against 1220 us);
+//   up to 16 tokens: k_smallm_rows below, rows split over the waves (16 tokens: 389 against
+//     951 us; 4 tokens: 358 against 782 us; the K-split body in its place: 461 and 356 us).
 struct SmallMStackEntry {
   uint64_t row_ptr, values, idx, qparams, X, Y;      // device addresses
   SmallMKsGeom g;
 };
 static_assert(sizeof(SmallMStackEntry) <= EGT_STACK_ENTRY_BYTES, "descriptor larger than the published entry size");
-// Launch shape: waves per workgroup, row tiles per round, workgroups per matrix; up to 16
-// tokens and beyond.  Build macros, for timing other shapes.
-#ifndef EGT_GS_WAVES
-#define EGT_GS_WAVES 4
-#endif
-#ifndef EGT_GS_BLOCKS
-#define EGT_GS_BLOCKS 96
-#endif
+// Launch shape beyond 16 tokens: waves per workgroup, workgroups per matrix (build macros, for timing other shapes)
 #ifndef EGT_GSW_WAVES
 #define EGT_GSW_WAVES 4
 #endif
 #ifndef EGT_GSW_BLOCKS
 #define EGT_GSW_BLOCKS 64
 #endif
-constexpr int GS_NIT = 3, GSW_NIT = 4;
+constexpr int GSW_NIT = 4;
 
-// (minimum waves per SIMD: 128 registers a lane with one token group per pass, 256 with two)
+// (at least two waves per SIMD: 256 registers a lane)
 template <int NT, int NIT, int NWMAX>
-__global__ __launch_bounds__(64 * NWMAX, NT == 1 ? 4 : 2) void k_smallm_stack(const uint8_t *__restrict__ table) {
+__global__ __launch_bounds__(64 * NWMAX, 2) void k_smallm_stack(const uint8_t *__restrict__ table) {
   typedef __attribute__((address_space(1))) const uint32_t *g_u32;
   typedef __attribute__((address_space(1))) const uint8_t *g_u8;
   typedef __attribute__((address_space(1))) const __half *g_h;
@@ -903,23 +899,254 @@ __global__ __launch_bounds__(64 * NWMAX, NT == 1 ? 4 : 2) void k_smallm_stack(co
       (const uint8_t *)(g_u8)e->qparams, (const __half *)(g_h)e->X, (__half *)(g_hw)e->Y, g);
 }
 
-// Shapes the stack form takes: what the single call runs on this kernel with one {scale, zero} pair per chunk,
-// and rows long enough for every wave of the workgroup to own a K-step of 256 columns.
+// ---- The stack form for up to 16 tokens: rows, not K, split over the waves.
+// With K split over the waves (above) every wave stages its own slice of X, and a round of
+// row tiles pulls the whole of X through the L2: at 16 tokens and three tiles a round that is
+// 128 KB of X for 61 KB of weights, and the counters show it (16 layers of a 7B stack: 5.9 GB
+// from the L2 to the compute units for 1.36 GB of weights and tokens).  A table offers
+// enough row tiles to fill the chip without cutting K, so here a workgroup of 8 waves owns 8
+// consecutive row tiles for all of K, one tile per wave, in rounds of four K-steps (1024
+// columns): the token rows of a round (32 KB) are staged once per workgroup - each wave
+// requests an eighth - and read by all waves, and every wave keeps the sums of its tile in
+// registers from the first K-step to the last: no sum across waves, the results go from the
+// registers to Y.
+// What a wave requests of its tile follows the cache lines.  A request of the kernel above
+// covers one K-step of 16 rows: 64 B of nibbles, 32 B of idx words and 8 B of scales per row.
+// There the waves of a workgroup ask for neighbouring K-steps at the same time; a wave that
+// walks its rows alone, one K-step after the other, finds the rest of each line gone from the
+// caches a step later (measured that way: 4.6 GB fetched for 1.36 GB).  Here a request covers
+// 8 rows x 8 chunks - two K-steps, 128 B of nibbles per row - and the four requests per array
+// of a round are issued together.
+// X of round j + 1 and the A tiles of round j + 2 are requested while round j is computed
+// (two regions in LDS, one barrier a round, two sets of fetch registers).
+#ifndef EGT_RS_WAVES
+#define EGT_RS_WAVES 8
+#endif
+constexpr int RS_WAVES = EGT_RS_WAVES, RS_Q = 4, RS_BUFS = 2, RS_STEP = 8 * KS_PAIR, RS_REGION = RS_Q * RS_STEP;
+constexpr int RS_REQ = 8 * RS_Q / RS_WAVES;          // requests of X a wave issues per round
+static_assert(RS_WAVES % RS_Q == 0 && RS_REQ * RS_WAVES == 8 * RS_Q, "the waves share the 32 requests of a round evenly");
+
+__global__ __launch_bounds__(64 * RS_WAVES, 4) void k_smallm_rows(const uint8_t *__restrict__ table) {
+  extern __shared__ __align__(16) uint8_t xs[];       // RS_BUFS regions of RS_REGION bytes
+  typedef __attribute__((address_space(1))) const uint32_t *g_u32;
+  typedef __attribute__((address_space(1))) const uint8_t *g_u8;
+  typedef __attribute__((address_space(1))) const __half *g_h;
+  typedef __attribute__((address_space(1))) __half *g_hw;
+  typedef ATile<EGT_VAL_INT4, 1> Tile;
+  constexpr int LPT = Tile::LOADS;
+  const SmallMStackEntry *e = (const SmallMStackEntry *)(table + (size_t)blockIdx.y * EGT_STACK_ENTRY_BYTES);
+  const SmallMKsGeom g = e->g;
+  if ((int)blockIdx.x * RS_WAVES >= g.ntiles) return; // (uniform: the whole workgroup leaves)
+  const uint32_t *row_ptr = (const uint32_t *)(g_u32)e->row_ptr;
+  __half *Y = (__half *)(g_hw)e->Y;
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int i = lane & 15, kb = lane >> 4;            // operand form: row i of the tile, chunk kb of the step
+  // this wave's row tile (a wave past the last tile has none, but still stages its share of X
+  // and meets the barriers)
+  const int tile = (int)blockIdx.x * RS_WAVES + wave;
+  const bool has_tile = tile < g.ntiles;
+  const int nsteps = g.nsteps, nrounds = (nsteps + RS_Q - 1) / RS_Q;
+  const uint32_t magic = in_vgpr(g.nib_magic);
+  const uint32_t S_row = (uint32_t)g.nchunks * 32u;
+  // row pointers first, checked at the end: a row whose pointer is not r * S yields NaN
+  const int frow = 16 * tile + lane;
+  const bool fchecked = has_tile && lane < 16 && frow < g.rows;
+  const uint32_t frp = fchecked ? row_ptr[frow] : 0u;
+
+  const __amdgpu_buffer_rsrc_t r_val = make_rsrc((const uint8_t *)(g_u8)e->values, g.val_bytes);
+  const __amdgpu_buffer_rsrc_t r_idx = make_rsrc((const uint8_t *)(g_u8)e->idx, g.idx_bytes);
+  const __amdgpu_buffer_rsrc_t r_qp = make_rsrc((const uint8_t *)(g_u8)e->qparams, g.qp_bytes);
+  const __amdgpu_buffer_rsrc_t r_x = make_rsrc((const __half *)(g_h)e->X, g.x_bytes);
+  const uint32_t off_range = 0xFFFFFFF0u;             // past every buffer: such a request returns zeros and moves no data
+  // A round of a tile is 16 rows x 16 chunks.  A request covers 8 rows x 8 chunks - lane
+  // (r, c) = (lane >> 3, lane & 7) fetches chunk 8 p + c of row 8 h + r: 128 contiguous bytes
+  // of nibbles per row, whole cache lines - so four requests (h, p) per array fetch the round,
+  // and request (h, p) holds the K-steps 2 p and 2 p + 1 of half h of the rows.
+  struct RoundRegs {
+    u4 nib[2][2];
+    u2 iw[2][2];
+    uint32_t qp[2][2];
+  };
+  const int r8 = lane >> 3, c8 = lane & 7;
+  auto load_half = [&](RoundRegs &a, int round, int p) {   // the requests (0, p) and (1, p): 2 * LPT of them
+    const bool on = has_tile && RS_Q * round + 2 * p < nsteps;                // uniform
+    const int c0 = 4 * RS_Q * round + 8 * p;                                  // first chunk of the request
+    const uint32_t lcc = (uint32_t)min((int)in_vgpr((uint32_t)c8), g.nchunks - 1 - c0);       // chunk inside the request (clamped)
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+      const uint32_t rel = (uint32_t)min(8 * h + r8, max(g.rows - 1 - 16 * tile, 0));          // row inside the tile (clamped)
+      const uint32_t cl = rel * (uint32_t)g.nchunks + lcc;                    // lane part of the chunk number
+      const uint32_t cu = on ? (uint32_t)(16 * tile) * (uint32_t)g.nchunks + (uint32_t)c0 : 0u;   // uniform part
+      (void)TileRequest<0, LPT>{};
+      a.iw[h][p] = __builtin_amdgcn_raw_buffer_load_b64(r_idx, on ? 8u * cl : off_range, 8u * cu, 0);
+      (void)TileRequest<1, LPT>{};
+      a.nib[h][p] = __builtin_amdgcn_raw_buffer_load_b128(r_val, on ? 16u * cl : off_range, 16u * cu, 0);
+      (void)TileRequest<2, LPT>{};
+      const uint32_t qrow_l = rel * (uint32_t)g.groups_per_row;
+      const uint32_t qrow_u = on ? (uint32_t)(16 * tile) * (uint32_t)g.groups_per_row : 0u;
+      a.qp[h][p] = __builtin_amdgcn_raw_buffer_load_b32(r_qp, on ? 4u * (qrow_l + (lcc >> g.gshift)) : off_range,
+                                                        on ? 4u * (qrow_u + (uint32_t)(c0 >> g.gshift)) : 0u, 0);
+    }
+  };
+  // operand of K-step q of the round: lane (i, kb) takes chunk 4 (q & 1) + kb of row i & 7 from
+  // request (i >> 3, q >> 1): one lane permutation of either half, then the choice between them
+  const int from_even = 4 * (8 * (i & 7) + kb);
+  const bool upper = i >= 8;
+  auto pick = [&](int from, uint32_t lo, uint32_t hi) {
+    const uint32_t a = lane_perm(from, lo), b = lane_perm(from, hi);
+    return upper ? b : a;
+  };
+  auto to_operand = [&](const RoundRegs &a, int q, Tile &t) {
+    const int from = from_even + 16 * (q & 1), p = q >> 1;
+#pragma unroll
+    for (int d = 0; d < 4; ++d) t.nib[0][d] = pick(from, a.nib[0][p][d], a.nib[1][p][d]);
+    t.iw[0] = pick(from, a.iw[0][p][0], a.iw[1][p][0]);
+    t.iw[1] = pick(from, a.iw[0][p][1], a.iw[1][p][1]);
+    t.qp[0] = pick(from, a.qp[0][p], a.qp[1][p]);
+  };
+  // X of a round: 32 requests, one per K-step and pair of tokens, each landing in one
+  // kilobyte of the region in the layout of the kernel above (lane l delivers to byte 16 l;
+  // the odd token of a pair has neighbouring pieces swapped).  Wave w issues requests 2 w
+  // and 2 w + 1 - always two, so that the wait counts are fixed; a pair past M or a step past
+  // K asks out of range.
+  const int xtl = lane >> 5;
+  const int slot_piece = (lane & 31) ^ xtl;           // piece of X this lane delivers
+  const int xq = wave / (RS_WAVES / RS_Q);            // K-step of the round this wave stages
+  const int xu = (wave % (RS_WAVES / RS_Q)) * RS_REQ; // its first pair of tokens
+  auto dma_x = [&](int round, int buf) {
+    const int step = RS_Q * round + xq;
+    const int vp = max(1, min(32, g.kpieces - 32 * step));   // pieces of the step inside K
+    const uint32_t xs0 = 512u * (uint32_t)step;
+    const uint32_t off_lo = 16u * (uint32_t)min(slot_piece, vp - 1);
+    const uint32_t off_hi = off_lo + (uint32_t)xtl * (uint32_t)(2 * g.ldx);
+    uint8_t *region = xs + buf * RS_REGION + xq * RS_STEP;
+    asm volatile("" ::: "memory");                    // the requests stay together, in program order
+#pragma unroll
+    for (int q = 0; q < RS_REQ; ++q) {
+      const int u = xu + q, t0 = 2 * u;
+      const bool on = t0 < g.M && step < nsteps;      // uniform
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(r_x, (__attribute__((address_space(3))) void *)(region + KS_PAIR * u), 16,
+                                               on ? (t0 + 1 < g.M ? off_hi : off_lo) : off_range,
+                                               on ? xs0 + (uint32_t)t0 * (uint32_t)(2 * g.ldx) : 0u, 0, 0);
+    }
+    asm volatile("" ::: "memory");
+  };
+  // the pieces of a partly filled step that lie past K become zeros (the issuing wave's own two pairs)
+  auto zero_tail = [&](int round, int buf) {
+    const int vp = g.kpieces - 32 * (RS_Q * round + xq);
+    if (vp > 0 && vp < 32 && slot_piece >= vp) {
+#pragma unroll
+      for (int q = 0; q < RS_REQ; ++q)
+        *(u4 *)(xs + buf * RS_REGION + xq * RS_STEP + KS_PAIR * (xu + q) + 16 * lane) = u4{0, 0, 0, 0};
+    }
+  };
+  // B operand of instruction m of a K-step (as in the kernel above: lane (n, b) holds token n,
+  // k-octets b and 4 + b of the instruction's 16-column group)
+  const int b_off = KS_PAIR * ((lane & 15) >> 1) + 512 * (lane & 1) + 16 * (8 * (lane >> 5) + (((lane >> 4) ^ lane) & 1));
+  auto read_b = [&](const uint8_t *region, int m) {
+    const u4 lo = *(const u4 *)(region + b_off + 32 * m), hi = *(const u4 *)(region + b_off + 256 + 32 * m);
+    return u8v{lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+  };
+
+  f4 acc = f4{0.f, 0.f, 0.f, 0.f};
+  // The A tiles are requested two rounds ahead (two sets of fetch registers), X one round
+  // ahead.  Requests in a round, in this order: X(j + 1), then A(j + 2) - so that at the top
+  // of round j the requests still allowed to be pending are exactly the RS_Q * LPT of A(j + 1).
+  // The barrier is issued with its own wait counts: a fence would wait for every pending
+  // request, the LDS-bound ones of X among them, and give the depth away.
+  RoundRegs raw0, raw1;
+  load_half(raw0, 0, 0);
+  load_half(raw0, 0, 1);
+  dma_x(0, 0);
+  if (nrounds > 1) {
+    load_half(raw1, 1, 0);
+    load_half(raw1, 1, 1);
+  }
+  int buf = 0;                                        // region of round j: j % 2
+  auto round = [&](RoundRegs &cur, int j) {
+    if (j + 1 < nrounds) wait_vmem<RS_Q * LPT>(); else wait_vmem<0>();   // A(j) and this wave's share of X(j) have arrived
+    zero_tail(j, buf);
+    // X(j) of every wave has landed; nobody reads the region of round j - 1 any more
+    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+    if (j + 1 < nrounds) dma_x(j + 1, buf ^ 1);
+#pragma unroll
+    for (int q = 0; q < RS_Q; ++q) {
+      // (a step past K, a wave without a tile: requested out of range, zeros with scale 0)
+      const int step = RS_Q * j + q;
+      Tile t;
+      to_operand(cur, q, t);
+      // (both K-steps of a pair of requests consumed: their fetch registers are free again)
+      if ((q & 1) && j + 2 < nrounds) {
+        wait_lds();
+        load_half(cur, j + 2, q >> 1);
+      }
+      const uint8_t *bregion = xs + buf * RS_REGION + q * RS_STEP;
+      const bool live = 4 * step + kb < g.nchunks;    // false: a chunk past the end of K
+      const uint32_t s2 = live ? __builtin_amdgcn_perm(t.qp[0], t.qp[0], 0x01000100u) : 0u;
+      const uint32_t off = pk_add_f16(__builtin_amdgcn_perm(t.qp[0], t.qp[0], 0x03020302u), g.nib_magic);
+#pragma unroll
+      for (int m = 0; m < 4; ++m) {
+        const u8v bx = read_b(bregion, m);            // (read per instruction: 8 registers of B at a time instead of 32)
+        const u4 av = dequant8(t.nib[0][m], off, s2, g.nib_mask, magic);
+        const int iword = (int)t.iw[m >> 1];
+        if (m & 1)
+          acc = __builtin_amdgcn_smfmac_f32_16x16x64_f16(__builtin_bit_cast(h8, av), __builtin_bit_cast(h16, bx), acc, iword, 0, 1);
+        else
+          acc = __builtin_amdgcn_smfmac_f32_16x16x64_f16(__builtin_bit_cast(h8, av), __builtin_bit_cast(h16, bx), acc, iword, 0, 0);
+      }
+    }
+    buf ^= 1;
+  };
+  for (int j = 0; j < nrounds; j += 2) {
+    round(raw0, j);
+    if (j + 1 < nrounds) round(raw1, j + 1);
+  }
+  // register v of lane l = D[row 4 (l >> 4) + v][token l & 15]: four consecutive rows of one token
+  const uint64_t good = __builtin_amdgcn_ballot_w64(fchecked && frp == (uint32_t)frow * S_row);
+  const int tok = lane & 15;
+  if (!has_tile || tok >= g.M) return;
+  const int row0 = 16 * tile + 4 * (lane >> 4);
+  uint32_t hv[4];
+#pragma unroll
+  for (int v = 0; v < 4; ++v)
+    hv[v] = ((good >> (4 * (lane >> 4) + v)) & 1) ? (uint32_t)__half_as_ushort(__float2half(acc[v])) : 0x7E00u;
+  __half *dst = Y + (int64_t)tok * g.ldy + row0;
+  if (g.vec_store && row0 + 3 < g.rows) {
+    *(u2 *)dst = u2{hv[0] | (hv[1] << 16), hv[2] | (hv[3] << 16)};
+  } else {
+#pragma unroll
+    for (int v = 0; v < 4; ++v)
+      if (row0 + v < g.rows) dst[v] = __ushort_as_half((uint16_t)hv[v]);
+  }
+}
+
+// Shapes the stack forms take: 2:4 INT4 with one {scale, zero} pair per chunk; beyond 16 tokens also rows long
+// enough for every wave of the workgroup to own a K-step of 256 columns.
 bool smallm_stack_item_ok(const egt_2bitcsr &w, int M) {
   if (w.val_kind != EGT_VAL_INT4 || w.n_keep != 2 || w.group_size < 64) return false;
   if (!sparse_smallm_supported(w, w.cols, M)) return false;
   const int nsteps = (w.cols / 64 + 3) / 4;
-  return nsteps >= (M > 16 ? EGT_GSW_WAVES : EGT_GS_WAVES);
+  return M <= 16 || nsteps >= EGT_GSW_WAVES;          // (K split over the waves: every wave owns a K-step)
 }
 
-int smallm_stack_blocks(int M) { return M > 16 ? EGT_GSW_BLOCKS : EGT_GS_BLOCKS; }
+// workgroups per matrix: up to 16 tokens one per RS_WAVES row tiles of the tallest matrix, beyond a fixed number
+int smallm_stack_blocks(int M, int max_rows) {
+  if (M > 16) return max_rows > 0 ? EGT_GSW_BLOCKS : 0;
+  const int ntiles = (max_rows + 15) / 16;
+  return (ntiles + RS_WAVES - 1) / RS_WAVES;
+}
 
 void smallm_stack_shape(int M, int &block_threads, int &lds_bytes) {
-  const bool wide = M > 16;
-  const int nw = wide ? EGT_GSW_WAVES : EGT_GS_WAVES, nit = wide ? GSW_NIT : GS_NIT, nt = wide ? 2 : 1;
+  if (M <= 16) {
+    block_threads = 64 * RS_WAVES;
+    lds_bytes = RS_BUFS * RS_REGION;
+    return;
+  }
+  const int nw = EGT_GSW_WAVES, nit = GSW_NIT, nt = 2;
   const size_t x_bytes = (size_t)nw * 8 * KS_PAIR, p_bytes = (size_t)nw * nit * nt * 1024;
   block_threads = 64 * nw;
-  lds_bytes = (int)((nt > 1 ? x_bytes + p_bytes : x_bytes) + 64 * nit);
+  lds_bytes = (int)(x_bytes + p_bytes + 64 * nit);
 }
 
 // Descriptor of one item into 160 bytes of the table.
@@ -934,12 +1161,12 @@ void smallm_stack_entry(const egt_2bitcsr &w, const uint16_t *X, uint16_t *Y, in
   std::memcpy(entry, &e, sizeof(e));
 }
 
-hipError_t launch_smallm_stack(const void *table_dev, int count, int M, hipStream_t stream) {
+hipError_t launch_smallm_stack(const void *table_dev, int count, int M, int grid_x, hipStream_t stream) {
   int threads, lds;
   smallm_stack_shape(M, threads, lds);
-  const dim3 grid(smallm_stack_blocks(M), count), block(threads);
+  const dim3 grid(grid_x, count), block(threads);
   if (M > 16) return launch(k_smallm_stack<2, GSW_NIT, EGT_GSW_WAVES>, grid, block, (size_t)lds, stream, (const uint8_t *)table_dev);
-  return launch(k_smallm_stack<1, GS_NIT, EGT_GS_WAVES>, grid, block, (size_t)lds, stream, (const uint8_t *)table_dev);
+  return launch(k_smallm_rows, grid, block, (size_t)lds, stream, (const uint8_t *)table_dev);
 }
 
 // `count` (2..4) identically shaped members in one launch (the caller has checked the shapes

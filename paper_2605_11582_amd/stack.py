@@ -120,6 +120,22 @@ class LayerStack:
         """The whole stack - 224 products of mixed storage forms - in a single launch."""
         return B.prepared_gemv_stack([self._item(m) for m in self.matrices])
 
+    def verify_step(self, M: int):
+        """A verification step of M candidate tokens (Sec. 3.4) through the 2:4 layers of the
+        stack in one launch: every 2:4 matrix times M token rows of its own.  Returns the
+        pre-marshalled call and the algorithmic bytes of one launch."""
+        import torch
+        items, nbytes = [], 0
+        for m in self.matrices:
+            if m.kind != "s24":
+                continue
+            dev = m.y.device
+            X = torch.randn((M, m.cols), device=dev).to(torch.float16)
+            Y = torch.empty((M, m.rows), dtype=torch.float16, device=dev)
+            items.append((m.keep[0], X, Y))
+            nbytes += m.nbytes + (M - 1) * 2 * (m.cols + m.rows)
+        return B.prepared_gemm_stack(items), nbytes
+
     @staticmethod
     def build(device="cuda:0", distinct_layers=None, progress=None, plan="config4", on_matrix=None) -> "LayerStack":
         """Uploads the whole stack.  `distinct_layers`: how many layers of each kind get

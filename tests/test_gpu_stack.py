@@ -484,6 +484,8 @@ def test_gemm_stack_equals_the_oracle_and_the_separate_products(M):
     print(f"case gemm stack M={M}", flush=True)
     shapes = [(300, 4096, 128), (70, 11008, 128), (16 * 96 * 8 + 40, 4096, 4096), (133, 8192, 64), (0, 4096, 128),
               (21, 4160, 64), (50, 832, 64), (1700, 2048, 128)]
+    if M <= 16:                                       # rows shorter than a round of four K-steps, and than a K-step
+        shapes += [(40, 64, 64), (33, 320, 64), (18, 1280, 256)]
     ps, os_, Xs = [], [], []
     for k, (rows, cols, g) in enumerate(shapes):
         w = synth.weights(rows, cols, 8800 + 7 * k + M)
@@ -493,11 +495,13 @@ def test_gemm_stack_equals_the_oracle_and_the_separate_products(M):
         Xs.append(synth.activation_rows(M, cols, 8800 + k))
     pds = [p.to("cuda:0") for p in ps]
     Xd = [G.to_dev(X.view(np.uint16)).view(torch.float16) for X in Xs]
-    guards = [64, 3, 64, 1, 64, 64, 2, 64]
+    guards = [64, 3, 64, 1, 64, 64, 2, 64, 64, 5, 64]
     ybufs = [torch.full((2 * gd + M * p.rows,), G.CANARY, dtype=torch.int16, device="cuda:0") for gd, p in zip(guards, ps)]
     Yd = [yb[gd:gd + M * p.rows].view(torch.float16).view(M, p.rows) for yb, gd, p in zip(ybufs, guards, ps)]
     call = B.prepared_gemm_stack(list(zip(pds, Xd, Yd)))
-    assert (call.plan.count, call.plan.M, call.plan.grid_x, call.plan.block_threads) == (len(shapes), M, 96 if M <= 16 else 64, 256)
+    assert (call.plan.count, call.plan.M) == (len(shapes), M)
+    if M <= 16:                                       # a row tile per wave: the workgroups of the tallest matrix cover its rows
+        assert call.plan.grid_x == -(-max(p.rows for p in ps) // (16 * (call.plan.block_threads // 64)))
     first = {}
     for rep in range(2):
         call()
@@ -535,11 +539,6 @@ def test_gemm_stack_rejects_what_it_does_not_run():
         with pytest.raises(B.EgtError) as e:
             B.prepared_gemm_stack([(p, X, Y)])
         assert e.value.status == 6
-    w2 = synth.weights(64, 768, 2)                        # three K-steps: too few for the four waves
-    p2 = B.pack_2bitcsr(w2, B.prune_n4(w2, 2), 2, 128, B.VAL_INT4).to("cuda:0")
-    with pytest.raises(B.EgtError) as e:
-        B.prepared_gemm_stack([(p2, X[:, :768].contiguous(), Y)])
-    assert e.value.status == 6
 
 
 def test_two_streams_at_once_give_the_serial_results():

@@ -588,10 +588,10 @@ def test_gemm_stack_plan_checks_items_and_reports_the_launch_shape():
         items[k].sparse, items[k].X, items[k].Y = ctypes.pointer(v), 16, 16
     plan = B.GemmPlan()
     assert L.egt_gemm_stack_plan(items, 3, 16, None, 0, ctypes.byref(plan)) == 0
-    # up to 16 tokens: 96 workgroups of 4 waves per matrix; per wave eight pairs of token rows of 1056 bytes;
-    # row flags of three tiles
+    # up to 16 tokens: workgroups of 8 waves that own a row tile each (the tallest matrix has 256 tiles);
+    # two regions of four K-steps of eight pairs of token rows of 1056 bytes
     assert (plan.count, plan.M, plan.grid_x, plan.block_threads, plan.lds_bytes, plan.table_bytes) == \
-        (3, 16, 96, 256, 4 * 8 * 1056 + 192, 3 * B.STACK_ENTRY_BYTES)
+        (3, 16, 32, 512, 2 * 4 * 8 * 1056, 3 * B.STACK_ENTRY_BYTES)
     wide = B.GemmPlan()
     assert L.egt_gemm_stack_plan(items, 3, 17, None, 0, ctypes.byref(wide)) == 0
     # beyond: 64 workgroups; the partial sums (4 tiles x 2 token groups of 1 KiB per wave) behind the token rows
@@ -616,7 +616,7 @@ def test_gemm_stack_plan_checks_items_and_reports_the_launch_shape():
     for bad in (B.View(64, 4096, 1, 128, 0, 16, 16, 16, 16), B.View(64, 4096, 2, 32, 0, 16, 16, 16, 16),
                 B.View(64, 4096, 2, 0, 1, 16, 16, 16, None), B.View(64, 768, 2, 128, 0, 16, 16, 16, 16)):
         items[0].sparse = ctypes.pointer(bad)
-        assert L.egt_gemm_stack_plan(items, 3, 16, table.ctypes.data, table.nbytes, ctypes.byref(plan2)) == 6
+        assert L.egt_gemm_stack_plan(items, 3, 17, table.ctypes.data, table.nbytes, ctypes.byref(plan2)) == 6
     assert np.all(table == 0xA5) and plan2.count == -1
     short = B.View(64, 832, 2, 64, 0, 16, 16, 16, 16)       # 13 chunks of 64 columns: the fourth K-step has begun
     items[0].sparse = ctypes.pointer(short)
@@ -625,7 +625,7 @@ def test_gemm_stack_plan_checks_items_and_reports_the_launch_shape():
     # the run call checks the plan before anything is launched
     assert L.egt_gemm_stack_run(None, ctypes.byref(plan), None) == 1
     assert L.egt_gemm_stack_run(24, ctypes.byref(plan), None) == 5
-    for field, value in (("count", 0), ("M", 1), ("M", 17), ("grid_x", 256), ("block_threads", 512), ("lds_bytes", 1024),
+    for field, value in (("count", 0), ("M", 1), ("M", 17), ("grid_x", -1), ("grid_x", 1 << 21), ("block_threads", 256), ("lds_bytes", 1024),
                          ("table_bytes", 160)):
         broken = B.GemmPlan.from_buffer_copy(plan)
         setattr(broken, field, value)
