@@ -22,10 +22,23 @@ def _hipcc():
     return None
 
 
-def test_tile_requests_of_the_small_m_kernels_match_the_wait_counts(tmp_path):
+@pytest.fixture(scope="module")
+def smallm_asm(tmp_path_factory):
+    """The small-M source compiled to gfx950 assembly, split into (kernel name, body) pairs."""
     hipcc = _hipcc()
     if hipcc is None:
         pytest.skip("hipcc not found")
+    asm = str(tmp_path_factory.mktemp("asm") / "smallm.s")
+    res = subprocess.run([hipcc, "--offload-arch=gfx950", "-O3", "-std=c++17", "-ffp-contract=off",
+                          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Wno-unused-command-line-argument",
+                          "-I" + os.path.join(ROOT, "include"), "-I" + CSRC, "--cuda-device-only", "-S",
+                          os.path.join(CSRC, "egt_mfma_smallm.hip"), "-o", asm], capture_output=True, text=True)
+    assert res.returncode == 0, res.stderr[-2000:]
+    parts = re.split(r"\n(_Z\w+):[^\n]*\n", open(asm).read())
+    return [(name, body.split(".Lfunc_end")[0]) for name, body in zip(parts[1::2], parts[2::2])]
+
+
+def test_tile_requests_of_the_small_m_kernels_match_the_wait_counts(smallm_asm):
     text = open(os.path.join(CSRC, "egt_mfma_smallm.hip")).read()
     loads = re.search(r"static constexpr int LOADS = KIND == EGT_VAL_INT4 \? (\d+) : 1 \+ VW;", text)
     vw = re.search(r"static constexpr int VW = KIND == EGT_VAL_INT4 \? 1 : (\d+);", text)
@@ -33,20 +46,12 @@ def test_tile_requests_of_the_small_m_kernels_match_the_wait_counts(tmp_path):
     per_tile = {0: int(loads.group(1)), 1: 1 + int(vw.group(1))}          # by value kind
     # no hand-written count survives beside the constant
     assert not re.search(r"wait_vmem<[^>]*\b[2-9]\b[^>]*>", text), "a literal request count in a wait"
-    asm = str(tmp_path / "smallm.s")
-    res = subprocess.run([hipcc, "--offload-arch=gfx950", "-O3", "-std=c++17", "-ffp-contract=off",
-                          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Wno-unused-command-line-argument",
-                          "-I" + os.path.join(ROOT, "include"), "-I" + CSRC, "--cuda-device-only", "-S",
-                          os.path.join(CSRC, "egt_mfma_smallm.hip"), "-o", asm], capture_output=True, text=True)
-    assert res.returncode == 0, res.stderr[-2000:]
-    parts = re.split(r"\n(_Z\w+):[^\n]*\n", open(asm).read())
     seen = 0
-    for name, body in zip(parts[1::2], parts[2::2]):
+    for name, body in smallm_asm:
         m = re.search(r"k_sparse_smallm_ksILi(\d)ELi(\d+)ELi(\d+)E", name)   # KIND, NT, NIT
         if not m:
             continue
         kind, nit = int(m.group(1)), int(m.group(3))
-        body = body.split(".Lfunc_end")[0]
         requests = [ln for ln in body.split("\n") if re.search(r"\bbuffer_load_dword", ln)]
         tile_requests = [ln for ln in requests if " lds" not in ln]           # X goes straight to LDS: counted apart
         assert tile_requests, name
@@ -55,3 +60,24 @@ def test_tile_requests_of_the_small_m_kernels_match_the_wait_counts(tmp_path):
         assert max(waits) <= 2 * nit * per_tile[kind], (name, sorted(waits))   # at most two phases of tiles pending
         seen += 1
     assert seen >= 20
+
+
+def test_requests_of_the_row_split_stack_kernel_match_its_wait_counts(smallm_asm):
+    # k_smallm_rows allows exactly the RS_Q * LOADS requests of the next round's A tiles to stay pending at the
+    # top of a round; the round body is compiled twice (two sets of fetch registers) after a prologue of two rounds
+    text = open(os.path.join(CSRC, "egt_mfma_smallm.hip")).read()
+    loads = int(re.search(r"static constexpr int LOADS = KIND == EGT_VAL_INT4 \? (\d+) : 1 \+ VW;", text).group(1))
+    waves = int(re.search(r"#define EGT_RS_WAVES (\d+)", text).group(1))
+    rs_q = int(re.search(r"RS_Q = (\d+)", text).group(1))
+    per_round, x_per_round = rs_q * loads, 8 * rs_q // waves
+    bodies = [body for name, body in smallm_asm if "k_smallm_rows" in name]
+    assert len(bodies) == 1
+    body = bodies[0]
+    requests = [ln for ln in body.split("\n") if re.search(r"\bbuffer_load_dword", ln)]
+    to_lds = [ln for ln in requests if " lds" in ln]
+    assert len(requests) - len(to_lds) == 4 * per_round, (len(requests), len(to_lds))       # rounds 0, 1 and j + 2 twice
+    assert len(to_lds) == 3 * x_per_round, len(to_lds)                                      # X(0) and X(j + 1) twice
+    waits = [int(v) for v in re.findall(r"vmcnt\((\d+)\)", body)]
+    assert waits.count(per_round) >= 2 and max(waits) <= 2 * per_round + x_per_round + 1, sorted(set(waits))
+    assert len(re.findall(r"\bs_barrier\b", body)) == 2
+    assert not re.search(r"\bscratch_|\bflat_", body)
