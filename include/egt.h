@@ -348,10 +348,10 @@ egt_status egt_gemv_stack_run(const void *table_dev, const egt_stack_plan *plan,
  * matrix over the whole chip; a table of them lets every compute unit work on several
  * matrices at once with small workgroups, which more than halves the time per product
  * (and the fixed cost of a launch is paid once per table).  Items: W a 2:4 INT4 2bit-CSR
- * view with group_size >= 64 (device buffers), cols a multiple of 64 and, beyond 16 tokens,
- * at least 832 (four K-steps of 256 columns); X: M x cols FP16 with the token rows back to
- * back (ldx = cols), Y: M x rows FP16 (ldy = rows), device pointers, X 16-byte aligned.
- * Other shapes give EGT_ERR_UNSUPPORTED: they run as single products. */
+ * view with group_size >= 64 (device buffers) and cols a multiple of 64; X: M x cols FP16
+ * with the token rows back to back (ldx = cols), Y: M x rows FP16 (ldy = rows), device
+ * pointers, X 16-byte aligned.  Other shapes give EGT_ERR_UNSUPPORTED: they run as single
+ * products. */
 typedef struct {
   const egt_2bitcsr *sparse;
   const uint16_t *X;
@@ -379,8 +379,8 @@ egt_status egt_gemm_stack_plan(const egt_gemm_item *items, int count, int M, voi
 /* DEVICE.  Runs every product of the table in one launch on `stream`.  The table and every
  * buffer it names stay valid until the launch has completed; no Y may alias an X or another
  * Y of the table.  Each Y[m][r] is the FP16 rounding of an FP32 sum of the same products as
- * in egt_sparse_gemm_smallm; the sum runs in another order (up to 16 tokens: along the row
- * from its first column to its last), so the two may differ in the last bit.  The result
+ * in egt_sparse_gemm_smallm; the sum runs in another order (along the row from its first
+ * column to its last), so the two may differ in the last bit.  The result
  * does not depend on the other items of the table or on the run.  A broken row_ptr entry
  * gives NaN in that row. */
 egt_status egt_gemm_stack_run(const void *table_dev, const egt_gemm_plan *plan, void *stream);

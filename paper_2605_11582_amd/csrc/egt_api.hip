@@ -297,7 +297,7 @@ egt_status egt_gemm_stack_run(const void *table_dev, const egt_gemm_plan *plan, 
   int threads, lds;
   egt::smallm_stack_shape(plan->M, threads, lds);
   // (workgroups per matrix: what the plan call derived from the tallest matrix of the table)
-  if (plan->grid_x < 0 || plan->grid_x > (1 << 20) || (plan->M > 16 && plan->grid_x > egt::smallm_stack_blocks(plan->M, 1)) ||
+  if (plan->grid_x < 0 || plan->grid_x > (1 << 20) || 
       plan->block_threads != threads || plan->lds_bytes != lds ||
       plan->table_bytes != (uint64_t)plan->count * EGT_STACK_ENTRY_BYTES)
     return EGT_ERR_SHAPE;

@@ -860,47 +860,19 @@ hipError_t launch_sparse_smallm(const egt_2bitcsr &w, const uint16_t *X, int64_t
 // The single product has to spread one matrix over the whole chip: one 16-wave workgroup per
 // compute unit, K split over its waves.  Such a workgroup runs its loads, products and the
 // sum across waves one after the other, and nothing else is resident to fill the gaps.  A
-// table offers many matrices at once, so the stack uses small workgroups, two or more
-// resident per compute unit, few per matrix, and the compute units work on several matrices
-// at the same time.  Two forms:
-//   more than 16 tokens: the body of the single-matrix kernel (K split over 4 waves, row tiles
-//     in rounds of 4, two token groups per pass), 64 workgroups per matrix (16 layers of a 7B
-//     stack, 1.3 GB, 64 tokens: 954 us against 2008 us of single products replayed from a
-//     graph; 32 tokens: 545 against 1220 us);
-//   up to 16 tokens: k_smallm_rows below, rows split over the waves (16 tokens: 389 against
-//     951 us; 4 tokens: 358 against 782 us; the K-split body in its place: 461 and 356 us).
+// table offers many matrices at once, so the stack uses smaller workgroups, few per matrix,
+// and the compute units work on several matrices at the same time (16 layers of a 7B stack,
+// 1.3 GB: 374 us at 16 tokens against 951 us of single products replayed from a graph, 660
+// against 2008 us at 64 tokens).
 struct SmallMStackEntry {
   uint64_t row_ptr, values, idx, qparams, X, Y;      // device addresses
   SmallMKsGeom g;
 };
 static_assert(sizeof(SmallMStackEntry) <= EGT_STACK_ENTRY_BYTES, "descriptor larger than the published entry size");
-// Launch shape beyond 16 tokens: waves per workgroup, workgroups per matrix (build macros, for timing other shapes)
-#ifndef EGT_GSW_WAVES
-#define EGT_GSW_WAVES 4
-#endif
-#ifndef EGT_GSW_BLOCKS
-#define EGT_GSW_BLOCKS 64
-#endif
-constexpr int GSW_NIT = 4;
 
-// (at least two waves per SIMD: 256 registers a lane)
-template <int NT, int NIT, int NWMAX>
-__global__ __launch_bounds__(64 * NWMAX, 2) void k_smallm_stack(const uint8_t *__restrict__ table) {
-  typedef __attribute__((address_space(1))) const uint32_t *g_u32;
-  typedef __attribute__((address_space(1))) const uint8_t *g_u8;
-  typedef __attribute__((address_space(1))) const __half *g_h;
-  typedef __attribute__((address_space(1))) __half *g_hw;
-  const SmallMStackEntry *e = (const SmallMStackEntry *)(table + (size_t)blockIdx.y * EGT_STACK_ENTRY_BYTES);
-  const SmallMKsGeom g = e->g;
-  if ((int)blockIdx.x >= g.ntiles) return;            // (uniform: the whole workgroup leaves)
-  // (addresses from a table are cast to the global address space: as generic pointers their loads would be flat)
-  smallm_ks_body<EGT_VAL_INT4, NT, NIT, NWMAX, 1, false, true, false>(
-      (const uint32_t *)(g_u32)e->row_ptr, (const uint8_t *)(g_u8)e->values, (const uint8_t *)(g_u8)e->idx,
-      (const uint8_t *)(g_u8)e->qparams, (const __half *)(g_h)e->X, (__half *)(g_hw)e->Y, g);
-}
-
-// ---- The stack form for up to 16 tokens: rows, not K, split over the waves.
-// With K split over the waves (above) every wave stages its own slice of X, and a round of
+// Rows, not K, are split over the waves.
+// With K split over the waves (the kernels above; the stack ran on that body first, 4 waves
+// and three row tiles a round) every wave stages its own slice of X, and a round of
 // row tiles pulls the whole of X through the L2: at 16 tokens and three tiles a round that is
 // 128 KB of X for 61 KB of weights, and the counters show it (16 layers of a 7B stack: 5.9 GB
 // from the L2 to the compute units for 1.36 GB of weights and tokens).  A table offers
@@ -915,18 +887,26 @@ __global__ __launch_bounds__(64 * NWMAX, 2) void k_smallm_stack(const uint8_t *_
 // There the waves of a workgroup ask for neighbouring K-steps at the same time; a wave that
 // walks its rows alone, one K-step after the other, finds the rest of each line gone from the
 // caches a step later (measured that way: 4.6 GB fetched for 1.36 GB).  Here a request covers
-// 8 rows x 8 chunks - two K-steps, 128 B of nibbles per row - and the four requests per array
-// of a round are issued together.
+// 8 rows x 8 chunks - two K-steps, 128 B of nibbles per row - and the requests of a round are
+// issued together.
 // X of round j + 1 and the A tiles of round j + 2 are requested while round j is computed
 // (two regions in LDS, one barrier a round, two sets of fetch registers).
+// More than 16 tokens: NG token groups of 16.  The token rows of all groups are staged per
+// round, the operands of a K-step are dequantised once and serve every group (NG sums per
+// wave), and a round is two K-steps, so that the regions still fit: up to 32 tokens two
+// groups and 8 waves (two workgroups per compute unit), beyond four groups and 16 waves.
 #ifndef EGT_RS_WAVES
 #define EGT_RS_WAVES 8
 #endif
-constexpr int RS_WAVES = EGT_RS_WAVES, RS_Q = 4, RS_BUFS = 2, RS_STEP = 8 * KS_PAIR, RS_REGION = RS_Q * RS_STEP;
-constexpr int RS_REQ = 8 * RS_Q / RS_WAVES;          // requests of X a wave issues per round
-static_assert(RS_WAVES % RS_Q == 0 && RS_REQ * RS_WAVES == 8 * RS_Q, "the waves share the 32 requests of a round evenly");
+constexpr int RS_WAVES = EGT_RS_WAVES, RS_Q = 4, RS_BUFS = 2, RS_STEP = 8 * KS_PAIR;
+// NG token groups of 16 (M <= 16 NG), rounds of Q K-steps, W waves: LDS bytes of a workgroup
+constexpr int rs_lds_bytes(int ng, int q) { return RS_BUFS * ng * q * RS_STEP; }
 
-__global__ __launch_bounds__(64 * RS_WAVES, 4) void k_smallm_rows(const uint8_t *__restrict__ table) {
+template <int NG, int Q, int W>
+__global__ __launch_bounds__(64 * W, 4) void k_smallm_rows(const uint8_t *__restrict__ table) {
+  constexpr int RS_WAVES = W, RS_Q = Q, RS_REGION = NG * Q * RS_STEP;
+  constexpr int RS_REQ = NG * Q * 8 / W;              // requests of X a wave issues per round
+  static_assert(RS_REQ * W == NG * Q * 8 && Q % 2 == 0, "the waves share the requests of a round evenly");
   extern __shared__ __align__(16) uint8_t xs[];       // RS_BUFS regions of RS_REGION bytes
   typedef __attribute__((address_space(1))) const uint32_t *g_u32;
   typedef __attribute__((address_space(1))) const uint8_t *g_u8;
@@ -964,9 +944,9 @@ __global__ __launch_bounds__(64 * RS_WAVES, 4) void k_smallm_rows(const uint8_t 
   // of nibbles per row, whole cache lines - so four requests (h, p) per array fetch the round,
   // and request (h, p) holds the K-steps 2 p and 2 p + 1 of half h of the rows.
   struct RoundRegs {
-    u4 nib[2][2];
-    u2 iw[2][2];
-    uint32_t qp[2][2];
+    u4 nib[2][Q / 2];
+    u2 iw[2][Q / 2];
+    uint32_t qp[2][Q / 2];
   };
   const int r8 = lane >> 3, c8 = lane & 7;
   auto load_half = [&](RoundRegs &a, int round, int p) {   // the requests (0, p) and (1, p): 2 * LPT of them
@@ -1005,40 +985,38 @@ __global__ __launch_bounds__(64 * RS_WAVES, 4) void k_smallm_rows(const uint8_t 
     t.iw[1] = pick(from, a.iw[0][p][1], a.iw[1][p][1]);
     t.qp[0] = pick(from, a.qp[0][p], a.qp[1][p]);
   };
-  // X of a round: 32 requests, one per K-step and pair of tokens, each landing in one
-  // kilobyte of the region in the layout of the kernel above (lane l delivers to byte 16 l;
-  // the odd token of a pair has neighbouring pieces swapped).  Wave w issues requests 2 w
-  // and 2 w + 1 - always two, so that the wait counts are fixed; a pair past M or a step past
-  // K asks out of range.
+  // X of a round: one request per token group, K-step and pair of tokens, each landing in one
+  // kilobyte of the region ([group][K-step][pair], a K-step in the layout of the kernel above:
+  // lane l delivers to byte 16 l; the odd token of a pair has neighbouring pieces swapped).
+  // Every wave issues the same number of them, so that the wait counts are fixed; a pair past
+  // M or a step past K asks out of range.
   const int xtl = lane >> 5;
   const int slot_piece = (lane & 31) ^ xtl;           // piece of X this lane delivers
-  const int xq = wave / (RS_WAVES / RS_Q);            // K-step of the round this wave stages
-  const int xu = (wave % (RS_WAVES / RS_Q)) * RS_REQ; // its first pair of tokens
   auto dma_x = [&](int round, int buf) {
-    const int step = RS_Q * round + xq;
-    const int vp = max(1, min(32, g.kpieces - 32 * step));   // pieces of the step inside K
-    const uint32_t xs0 = 512u * (uint32_t)step;
-    const uint32_t off_lo = 16u * (uint32_t)min(slot_piece, vp - 1);
-    const uint32_t off_hi = off_lo + (uint32_t)xtl * (uint32_t)(2 * g.ldx);
-    uint8_t *region = xs + buf * RS_REGION + xq * RS_STEP;
     asm volatile("" ::: "memory");                    // the requests stay together, in program order
 #pragma unroll
-    for (int q = 0; q < RS_REQ; ++q) {
-      const int u = xu + q, t0 = 2 * u;
+    for (int k = 0; k < RS_REQ; ++k) {
+      const int r = wave * RS_REQ + k;                // request r of the round: token group, K-step, pair of tokens
+      const int grp = r / (8 * RS_Q), xq = (r >> 3) % RS_Q, u = r & 7, t0 = 16 * grp + 2 * u;
+      const int step = RS_Q * round + xq;
+      const int vp = max(1, min(32, g.kpieces - 32 * step));   // pieces of the step inside K
+      const uint32_t off_lo = 16u * (uint32_t)min(slot_piece, vp - 1);
+      const uint32_t off_hi = off_lo + (uint32_t)xtl * (uint32_t)(2 * g.ldx);
       const bool on = t0 < g.M && step < nsteps;      // uniform
-      __builtin_amdgcn_raw_ptr_buffer_load_lds(r_x, (__attribute__((address_space(3))) void *)(region + KS_PAIR * u), 16,
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(r_x, (__attribute__((address_space(3))) void *)(xs + buf * RS_REGION + (r >> 3) * RS_STEP + KS_PAIR * u), 16,
                                                on ? (t0 + 1 < g.M ? off_hi : off_lo) : off_range,
-                                               on ? xs0 + (uint32_t)t0 * (uint32_t)(2 * g.ldx) : 0u, 0, 0);
+                                               on ? 512u * (uint32_t)step + (uint32_t)t0 * (uint32_t)(2 * g.ldx) : 0u, 0, 0);
     }
     asm volatile("" ::: "memory");
   };
-  // the pieces of a partly filled step that lie past K become zeros (the issuing wave's own two pairs)
+  // the pieces of a partly filled step that lie past K become zeros (the issuing wave's own requests)
   auto zero_tail = [&](int round, int buf) {
-    const int vp = g.kpieces - 32 * (RS_Q * round + xq);
-    if (vp > 0 && vp < 32 && slot_piece >= vp) {
 #pragma unroll
-      for (int q = 0; q < RS_REQ; ++q)
-        *(u4 *)(xs + buf * RS_REGION + xq * RS_STEP + KS_PAIR * (xu + q) + 16 * lane) = u4{0, 0, 0, 0};
+    for (int k = 0; k < RS_REQ; ++k) {
+      const int r = wave * RS_REQ + k;
+      const int vp = g.kpieces - 32 * (RS_Q * round + (r >> 3) % RS_Q);
+      if (vp > 0 && vp < 32 && slot_piece >= vp)
+        *(u4 *)(xs + buf * RS_REGION + (r >> 3) * RS_STEP + KS_PAIR * (r & 7) + 16 * lane) = u4{0, 0, 0, 0};
     }
   };
   // B operand of instruction m of a K-step (as in the kernel above: lane (n, b) holds token n,
@@ -1049,19 +1027,21 @@ __global__ __launch_bounds__(64 * RS_WAVES, 4) void k_smallm_rows(const uint8_t 
     return u8v{lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
   };
 
-  f4 acc = f4{0.f, 0.f, 0.f, 0.f};
+  f4 acc[NG];
+#pragma unroll
+  for (int grp = 0; grp < NG; ++grp) acc[grp] = f4{0.f, 0.f, 0.f, 0.f};
   // The A tiles are requested two rounds ahead (two sets of fetch registers), X one round
   // ahead.  Requests in a round, in this order: X(j + 1), then A(j + 2) - so that at the top
   // of round j the requests still allowed to be pending are exactly the RS_Q * LPT of A(j + 1).
   // The barrier is issued with its own wait counts: a fence would wait for every pending
   // request, the LDS-bound ones of X among them, and give the depth away.
   RoundRegs raw0, raw1;
-  load_half(raw0, 0, 0);
-  load_half(raw0, 0, 1);
+#pragma unroll
+  for (int p = 0; p < RS_Q / 2; ++p) load_half(raw0, 0, p);
   dma_x(0, 0);
   if (nrounds > 1) {
-    load_half(raw1, 1, 0);
-    load_half(raw1, 1, 1);
+#pragma unroll
+    for (int p = 0; p < RS_Q / 2; ++p) load_half(raw1, 1, p);
   }
   int buf = 0;                                        // region of round j: j % 2
   auto round = [&](RoundRegs &cur, int j) {
@@ -1081,19 +1061,26 @@ __global__ __launch_bounds__(64 * RS_WAVES, 4) void k_smallm_rows(const uint8_t 
         wait_lds();
         load_half(cur, j + 2, q >> 1);
       }
-      const uint8_t *bregion = xs + buf * RS_REGION + q * RS_STEP;
       const bool live = 4 * step + kb < g.nchunks;    // false: a chunk past the end of K
       const uint32_t s2 = live ? __builtin_amdgcn_perm(t.qp[0], t.qp[0], 0x01000100u) : 0u;
       const uint32_t off = pk_add_f16(__builtin_amdgcn_perm(t.qp[0], t.qp[0], 0x03020302u), g.nib_magic);
+      // the operands of the step's four instructions serve every token group
+      u4 av[4];
 #pragma unroll
-      for (int m = 0; m < 4; ++m) {
-        const u8v bx = read_b(bregion, m);            // (read per instruction: 8 registers of B at a time instead of 32)
-        const u4 av = dequant8(t.nib[0][m], off, s2, g.nib_mask, magic);
-        const int iword = (int)t.iw[m >> 1];
-        if (m & 1)
-          acc = __builtin_amdgcn_smfmac_f32_16x16x64_f16(__builtin_bit_cast(h8, av), __builtin_bit_cast(h16, bx), acc, iword, 0, 1);
-        else
-          acc = __builtin_amdgcn_smfmac_f32_16x16x64_f16(__builtin_bit_cast(h8, av), __builtin_bit_cast(h16, bx), acc, iword, 0, 0);
+      for (int m = 0; m < 4; ++m) av[m] = dequant8(t.nib[0][m], off, s2, g.nib_mask, magic);
+#pragma unroll
+      for (int grp = 0; grp < NG; ++grp) {
+        if (NG > 1 && 16 * grp >= g.M) continue;      // uniform
+        const uint8_t *bregion = xs + buf * RS_REGION + (grp * RS_Q + q) * RS_STEP;
+#pragma unroll
+        for (int m = 0; m < 4; ++m) {
+          const u8v bx = read_b(bregion, m);          // (read per instruction: 8 registers of B at a time instead of 32)
+          const int iword = (int)t.iw[m >> 1];
+          if (m & 1)
+            acc[grp] = __builtin_amdgcn_smfmac_f32_16x16x64_f16(__builtin_bit_cast(h8, av[m]), __builtin_bit_cast(h16, bx), acc[grp], iword, 0, 1);
+          else
+            acc[grp] = __builtin_amdgcn_smfmac_f32_16x16x64_f16(__builtin_bit_cast(h8, av[m]), __builtin_bit_cast(h16, bx), acc[grp], iword, 0, 0);
+        }
       }
     }
     buf ^= 1;
@@ -1104,49 +1091,44 @@ __global__ __launch_bounds__(64 * RS_WAVES, 4) void k_smallm_rows(const uint8_t 
   }
   // register v of lane l = D[row 4 (l >> 4) + v][token l & 15]: four consecutive rows of one token
   const uint64_t good = __builtin_amdgcn_ballot_w64(fchecked && frp == (uint32_t)frow * S_row);
-  const int tok = lane & 15;
-  if (!has_tile || tok >= g.M) return;
+  if (!has_tile) return;
   const int row0 = 16 * tile + 4 * (lane >> 4);
-  uint32_t hv[4];
 #pragma unroll
-  for (int v = 0; v < 4; ++v)
-    hv[v] = ((good >> (4 * (lane >> 4) + v)) & 1) ? (uint32_t)__half_as_ushort(__float2half(acc[v])) : 0x7E00u;
-  __half *dst = Y + (int64_t)tok * g.ldy + row0;
-  if (g.vec_store && row0 + 3 < g.rows) {
-    *(u2 *)dst = u2{hv[0] | (hv[1] << 16), hv[2] | (hv[3] << 16)};
-  } else {
+  for (int grp = 0; grp < NG; ++grp) {
+    const int tok = 16 * grp + (lane & 15);
+    if (tok >= g.M) continue;
+    uint32_t hv[4];
 #pragma unroll
     for (int v = 0; v < 4; ++v)
-      if (row0 + v < g.rows) dst[v] = __ushort_as_half((uint16_t)hv[v]);
+      hv[v] = ((good >> (4 * (lane >> 4) + v)) & 1) ? (uint32_t)__half_as_ushort(__float2half(acc[grp][v])) : 0x7E00u;
+    __half *dst = Y + (int64_t)tok * g.ldy + row0;
+    if (g.vec_store && row0 + 3 < g.rows) {
+      *(u2 *)dst = u2{hv[0] | (hv[1] << 16), hv[2] | (hv[3] << 16)};
+    } else {
+#pragma unroll
+      for (int v = 0; v < 4; ++v)
+        if (row0 + v < g.rows) dst[v] = __ushort_as_half((uint16_t)hv[v]);
+    }
   }
 }
 
-// Shapes the stack forms take: 2:4 INT4 with one {scale, zero} pair per chunk; beyond 16 tokens also rows long
-// enough for every wave of the workgroup to own a K-step of 256 columns.
+// Shapes the stack takes: 2:4 INT4 with one {scale, zero} pair per chunk.
 bool smallm_stack_item_ok(const egt_2bitcsr &w, int M) {
   if (w.val_kind != EGT_VAL_INT4 || w.n_keep != 2 || w.group_size < 64) return false;
-  if (!sparse_smallm_supported(w, w.cols, M)) return false;
-  const int nsteps = (w.cols / 64 + 3) / 4;
-  return M <= 16 || nsteps >= EGT_GSW_WAVES;          // (K split over the waves: every wave owns a K-step)
+  return sparse_smallm_supported(w, w.cols, M);
 }
 
-// workgroups per matrix: up to 16 tokens one per RS_WAVES row tiles of the tallest matrix, beyond a fixed number
+static int stack_waves(int M) { return M <= 32 ? RS_WAVES : 16; }
+
+// workgroups per matrix: one per row tile and wave of the tallest matrix
 int smallm_stack_blocks(int M, int max_rows) {
-  if (M > 16) return max_rows > 0 ? EGT_GSW_BLOCKS : 0;
-  const int ntiles = (max_rows + 15) / 16;
-  return (ntiles + RS_WAVES - 1) / RS_WAVES;
+  const int ntiles = (max_rows + 15) / 16, w = stack_waves(M);
+  return (ntiles + w - 1) / w;
 }
 
 void smallm_stack_shape(int M, int &block_threads, int &lds_bytes) {
-  if (M <= 16) {
-    block_threads = 64 * RS_WAVES;
-    lds_bytes = RS_BUFS * RS_REGION;
-    return;
-  }
-  const int nw = EGT_GSW_WAVES, nit = GSW_NIT, nt = 2;
-  const size_t x_bytes = (size_t)nw * 8 * KS_PAIR, p_bytes = (size_t)nw * nit * nt * 1024;
-  block_threads = 64 * nw;
-  lds_bytes = (int)(x_bytes + p_bytes + 64 * nit);
+  block_threads = 64 * stack_waves(M);
+  lds_bytes = M <= 16 ? rs_lds_bytes(1, RS_Q) : M <= 32 ? rs_lds_bytes(2, 2) : rs_lds_bytes(4, 2);
 }
 
 // Descriptor of one item into 160 bytes of the table.
@@ -1165,8 +1147,10 @@ hipError_t launch_smallm_stack(const void *table_dev, int count, int M, int grid
   int threads, lds;
   smallm_stack_shape(M, threads, lds);
   const dim3 grid(grid_x, count), block(threads);
-  if (M > 16) return launch(k_smallm_stack<2, GSW_NIT, EGT_GSW_WAVES>, grid, block, (size_t)lds, stream, (const uint8_t *)table_dev);
-  return launch(k_smallm_rows, grid, block, (size_t)lds, stream, (const uint8_t *)table_dev);
+  const uint8_t *t = (const uint8_t *)table_dev;
+  if (M <= 16) return launch(k_smallm_rows<1, RS_Q, RS_WAVES>, grid, block, (size_t)lds, stream, t);
+  if (M <= 32) return launch(k_smallm_rows<2, 2, RS_WAVES>, grid, block, (size_t)lds, stream, t);
+  return launch(k_smallm_rows<4, 2, 16>, grid, block, (size_t)lds, stream, t);
 }
 
 // `count` (2..4) identically shaped members in one launch (the caller has checked the shapes

@@ -475,7 +475,7 @@ def test_smallm_kernels_replay_in_a_hip_graph():
             assert np.array_equal(Y.cpu().numpy().view(np.uint16), eager[k].view(np.uint16)), (rep, k)
 
 
-@pytest.mark.parametrize("M", [2, 5, 16, 17, 40, 64])
+@pytest.mark.parametrize("M", [2, 5, 16, 17, 32, 33, 40, 64])
 def test_gemm_stack_equals_the_oracle_and_the_separate_products(M):
     # a verification step through several layers in one launch: shapes with fewer row tiles than
     # workgroups, a ragged last tile, several rounds of row tiles, a row length that ends inside
@@ -484,8 +484,7 @@ def test_gemm_stack_equals_the_oracle_and_the_separate_products(M):
     print(f"case gemm stack M={M}", flush=True)
     shapes = [(300, 4096, 128), (70, 11008, 128), (16 * 96 * 8 + 40, 4096, 4096), (133, 8192, 64), (0, 4096, 128),
               (21, 4160, 64), (50, 832, 64), (1700, 2048, 128)]
-    if M <= 16:                                       # rows shorter than a round of four K-steps, and than a K-step
-        shapes += [(40, 64, 64), (33, 320, 64), (18, 1280, 256)]
+    shapes += [(40, 64, 64), (33, 320, 64), (18, 1280, 256)]     # rows shorter than a round of K-steps, and than a K-step
     ps, os_, Xs = [], [], []
     for k, (rows, cols, g) in enumerate(shapes):
         w = synth.weights(rows, cols, 8800 + 7 * k + M)
@@ -500,8 +499,8 @@ def test_gemm_stack_equals_the_oracle_and_the_separate_products(M):
     Yd = [yb[gd:gd + M * p.rows].view(torch.float16).view(M, p.rows) for yb, gd, p in zip(ybufs, guards, ps)]
     call = B.prepared_gemm_stack(list(zip(pds, Xd, Yd)))
     assert (call.plan.count, call.plan.M) == (len(shapes), M)
-    if M <= 16:                                       # a row tile per wave: the workgroups of the tallest matrix cover its rows
-        assert call.plan.grid_x == -(-max(p.rows for p in ps) // (16 * (call.plan.block_threads // 64)))
+    # a row tile per wave: the workgroups of the tallest matrix cover its rows
+    assert call.plan.grid_x == -(-max(p.rows for p in ps) // (16 * (call.plan.block_threads // 64)))
     first = {}
     for rep in range(2):
         call()

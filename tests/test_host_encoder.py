@@ -594,8 +594,10 @@ def test_gemm_stack_plan_checks_items_and_reports_the_launch_shape():
         (3, 16, 32, 512, 2 * 4 * 8 * 1056, 3 * B.STACK_ENTRY_BYTES)
     wide = B.GemmPlan()
     assert L.egt_gemm_stack_plan(items, 3, 17, None, 0, ctypes.byref(wide)) == 0
-    # beyond: 64 workgroups; the partial sums (4 tiles x 2 token groups of 1 KiB per wave) behind the token rows
-    assert (wide.grid_x, wide.block_threads, wide.lds_bytes) == (64, 256, 4 * 8 * 1056 + 4 * 8 * 1024 + 256)
+    # up to 32 tokens: two token groups, rounds of two K-steps; beyond: four groups, 16 waves
+    assert (wide.grid_x, wide.block_threads, wide.lds_bytes) == (32, 512, 2 * 2 * 2 * 8 * 1056)
+    assert L.egt_gemm_stack_plan(items, 3, 33, None, 0, ctypes.byref(wide)) == 0
+    assert (wide.grid_x, wide.block_threads, wide.lds_bytes) == (16, 1024, 2 * 4 * 2 * 8 * 1056)
     table = np.full(3 * B.STACK_ENTRY_BYTES, 0xA5, dtype=np.uint8)
     assert L.egt_gemm_stack_plan(items, 3, 16, table.ctypes.data, table.nbytes - 1, ctypes.byref(plan)) == 2
     assert np.all(table == 0xA5)
@@ -614,18 +616,18 @@ def test_gemm_stack_plan_checks_items_and_reports_the_launch_shape():
     assert L.egt_gemm_stack_plan(items, 3, 16, table.ctypes.data, table.nbytes, ctypes.byref(plan2)) == 5
     items[1].X = 16
     for bad in (B.View(64, 4096, 1, 128, 0, 16, 16, 16, 16), B.View(64, 4096, 2, 32, 0, 16, 16, 16, 16),
-                B.View(64, 4096, 2, 0, 1, 16, 16, 16, None), B.View(64, 768, 2, 128, 0, 16, 16, 16, 16)):
+                B.View(64, 4096, 2, 0, 1, 16, 16, 16, None)):
         items[0].sparse = ctypes.pointer(bad)
         assert L.egt_gemm_stack_plan(items, 3, 17, table.ctypes.data, table.nbytes, ctypes.byref(plan2)) == 6
     assert np.all(table == 0xA5) and plan2.count == -1
-    short = B.View(64, 832, 2, 64, 0, 16, 16, 16, 16)       # 13 chunks of 64 columns: the fourth K-step has begun
+    short = B.View(64, 64, 2, 64, 0, 16, 16, 16, 16)        # a single chunk of 64 columns
     items[0].sparse = ctypes.pointer(short)
     assert L.egt_gemm_stack_plan(items, 3, 17, table.ctypes.data, table.nbytes, ctypes.byref(plan2)) == 0
     assert not np.all(table == 0xA5) and plan2.count == 3
     # the run call checks the plan before anything is launched
     assert L.egt_gemm_stack_run(None, ctypes.byref(plan), None) == 1
     assert L.egt_gemm_stack_run(24, ctypes.byref(plan), None) == 5
-    for field, value in (("count", 0), ("M", 1), ("M", 17), ("grid_x", -1), ("grid_x", 1 << 21), ("block_threads", 256), ("lds_bytes", 1024),
+    for field, value in (("count", 0), ("M", 1), ("M", 40), ("grid_x", -1), ("grid_x", 1 << 21), ("block_threads", 256), ("lds_bytes", 1024),
                          ("table_bytes", 160)):
         broken = B.GemmPlan.from_buffer_copy(plan)
         setattr(broken, field, value)

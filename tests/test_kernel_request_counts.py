@@ -63,21 +63,24 @@ def test_tile_requests_of_the_small_m_kernels_match_the_wait_counts(smallm_asm):
 
 
 def test_requests_of_the_row_split_stack_kernel_match_its_wait_counts(smallm_asm):
-    # k_smallm_rows allows exactly the RS_Q * LOADS requests of the next round's A tiles to stay pending at the
-    # top of a round; the round body is compiled twice (two sets of fetch registers) after a prologue of two rounds
+    # k_smallm_rows<NG, Q, W> allows exactly the Q * LOADS requests of the next round's A tiles to stay pending at
+    # the top of a round; the round body is compiled twice (two sets of fetch registers) after a prologue of two rounds
     text = open(os.path.join(CSRC, "egt_mfma_smallm.hip")).read()
     loads = int(re.search(r"static constexpr int LOADS = KIND == EGT_VAL_INT4 \? (\d+) : 1 \+ VW;", text).group(1))
-    waves = int(re.search(r"#define EGT_RS_WAVES (\d+)", text).group(1))
-    rs_q = int(re.search(r"RS_Q = (\d+)", text).group(1))
-    per_round, x_per_round = rs_q * loads, 8 * rs_q // waves
-    bodies = [body for name, body in smallm_asm if "k_smallm_rows" in name]
-    assert len(bodies) == 1
-    body = bodies[0]
-    requests = [ln for ln in body.split("\n") if re.search(r"\bbuffer_load_dword", ln)]
-    to_lds = [ln for ln in requests if " lds" in ln]
-    assert len(requests) - len(to_lds) == 4 * per_round, (len(requests), len(to_lds))       # rounds 0, 1 and j + 2 twice
-    assert len(to_lds) == 3 * x_per_round, len(to_lds)                                      # X(0) and X(j + 1) twice
-    waits = [int(v) for v in re.findall(r"vmcnt\((\d+)\)", body)]
-    assert waits.count(per_round) >= 2 and max(waits) <= 2 * per_round + x_per_round + 1, sorted(set(waits))
-    assert len(re.findall(r"\bs_barrier\b", body)) == 2
-    assert not re.search(r"\bscratch_|\bflat_", body)
+    seen = 0
+    for name, body in smallm_asm:
+        m = re.search(r"k_smallm_rowsILi(\d+)ELi(\d+)ELi(\d+)E", name)       # NG, Q, W
+        if not m:
+            continue
+        ng, q, w = (int(v) for v in m.groups())
+        per_round, x_per_round = q * loads, ng * q * 8 // w
+        requests = [ln for ln in body.split("\n") if re.search(r"\bbuffer_load_dword", ln)]
+        to_lds = [ln for ln in requests if " lds" in ln]
+        assert len(requests) - len(to_lds) == 4 * per_round, (name, len(requests), len(to_lds))   # rounds 0, 1 and j + 2 twice
+        assert len(to_lds) == 3 * x_per_round, (name, len(to_lds))                                # X(0) and X(j + 1) twice
+        waits = [int(v) for v in re.findall(r"vmcnt\((\d+)\)", body)]
+        assert waits.count(per_round) >= 2 and max(waits) <= 2 * per_round + x_per_round + 1, (name, sorted(set(waits)))
+        assert len(re.findall(r"\bs_barrier\b", body)) == 2, name
+        assert not re.search(r"\bscratch_|\bflat_", body), name
+        seen += 1
+    assert seen == 3
