@@ -577,15 +577,17 @@ def table(torch, B, synth, timer, dev, w, mask, xd, ys, calls, packed):
     depth, gain = B.trigger_depth(layer_us[1], fit_a, fit_b, cand, rem)
     # the same products in layer order through a 32-layer all-2:4 stack (224 launches per pass)
     stack_pass, stack_one = {}, {}
-    for M in (1, 16, 64):
+    for M in (1, 2, 4, 8, 16, 32, 64):
         seq, items = [], []
         for layer in range(32):
             for mi in (2, 2, 2, 2, 0, 0, 1):          # q, k, v, o, gate, up, down
                 r5, k5, _, pk5 = pools[mi]
                 X = up16(synth.activation_rows(M, k5, 5))
                 Y = torch.empty((M, r5), dtype=torch.float16, device=dev)
-                pk = pk5[(layer * 7 + len(seq)) % len(pk5)]
+                pk = pk5[(layer * 7 + len(items)) % len(pk5)]
                 items.append((pk, X, Y))
+                if M not in (1, 16, 64):
+                    continue                          # (the 224 single launches: at three widths only)
                 if (mi, M) in split_wins:
                     ws = torch.empty(B.smallm_ws_bytes(pk, M), dtype=torch.uint8, device=dev)
                     seq.append(B.prepared_sparse_gemm_smallm_ws(pk, X, Y, ws))
@@ -595,15 +597,21 @@ def table(torch, B, synth, timer, dev, w, mask, xd, ys, calls, packed):
         def run_seq(i):
             for c in seq:
                 c()
-        stack_pass[str(M)] = round(timer(run_seq, 5, 1)["median"] * 1e6, 1)
-        if M >= 2:                                    # the same 224 products as one table, one launch
-            whole = B.prepared_gemm_stack(items)
-            stack_one[str(M)] = round(timer(lambda i: whole(), 5, 1)["median"] * 1e6, 1)
-            del whole
-        del seq, items
+        if seq:
+            stack_pass[str(M)] = round(timer(run_seq, 5, 1)["median"] * 1e6, 1)
+        # the same 224 products as one table, one launch (one token: the M = 1 stack of Sec. 3.3's kernels)
+        whole = (B.prepared_gemm_stack(items) if M >= 2 else
+                 B.prepared_gemv_stack([("sparse", pk, X.view(-1), Y.view(-1)) for pk, X, Y in items]))
+        stack_one[str(M)] = round(timer(lambda i: whole(), 5, 1)["median"] * 1e6, 1)
+        del whole, seq, items
+    one_m = [m for m in (2, 4, 8, 16, 32, 64)]
+    one_a, one_b = B.fit_verify_cost(one_m, [stack_one[str(m)] for m in one_m])
+    one_depth, one_gain = B.trigger_depth(stack_one["1"], one_a, one_b, cand, rem)
     t["trigger_model"] = {"layer_us_by_M": [round(layer_us[m], 2) for m in sweep_m], "M": [sweep_m[0], sweep_m[-1]],
                           "stack_pass_us_224_launches_by_M": stack_pass,
                           "stack_pass_us_one_launch_by_M": stack_one,
+                          "one_launch": {"t_ar_us": stack_one["1"], "fit_a_us": round(one_a, 2), "fit_b_us_per_token": round(one_b, 3),
+                                         "trigger_depth": one_depth, "benefit_us_per_pass": round(one_gain, 1)},
                           "stack_pass_us_32_times_layer_by_M": {str(m): round(32 * layer_us[m], 1) for m in (1, 16, 64)},
                           "fit_a_us": round(fit_a, 3), "fit_b_us_per_token": round(fit_b, 4),
                           "t_ar_us": round(layer_us[1], 2), "candidates": cand, "remaining": rem,
