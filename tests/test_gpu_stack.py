@@ -528,6 +528,36 @@ def test_gemm_stack_equals_the_oracle_and_the_separate_products(M):
         assert np.array_equal(Y2[k].cpu().numpy().view(np.uint16), first[k].view(np.uint16)), ("other table differs", k)
 
 
+@pytest.mark.parametrize("M", [3, 16, 24, 50])
+def test_gemm_stack_broken_row_ptr_yields_nan_for_every_token(M):
+    # rows 7 and 40 of the second matrix point somewhere else: NaN for every token of those rows, the other
+    # rows and the other matrices as before
+    torch = G.torch_mod()
+    print(f"case gemm stack broken row_ptr M={M}", flush=True)
+    ps, Xd, goods = [], [], []
+    for k, (rows, cols) in enumerate(((150, 4096), (200, 2048), (40, 11008))):
+        w = synth.weights(rows, cols, 8900 + k)
+        ps.append(B.pack_2bitcsr(w, B.prune_n4(w, 2), 2, 128, B.VAL_INT4))
+        Xd.append(G.to_dev(synth.activation_rows(M, cols, 8900 + k).view(np.uint16)).view(torch.float16))
+
+    def run():
+        pds = [p.to("cuda:0") for p in ps]
+        Ys = [torch.zeros((M, p.rows), dtype=torch.float16, device="cuda:0") for p in ps]
+        B.prepared_gemm_stack(list(zip(pds, Xd, Ys)))()
+        torch.cuda.synchronize()
+        return [Y.cpu().numpy() for Y in Ys]
+    goods = run()
+    ps[1].row_ptr[7] += 8
+    ps[1].row_ptr[40] = 0xFFFFFFF8
+    Ys = run()
+    assert np.all(np.isnan(Ys[1][:, 7])) and np.all(np.isnan(Ys[1][:, 40]))
+    keep = np.ones(200, dtype=bool)
+    keep[[7, 40]] = False
+    assert np.array_equal(Ys[1][:, keep].view(np.uint16), goods[1][:, keep].view(np.uint16))
+    for k in (0, 2):
+        assert np.array_equal(Ys[k].view(np.uint16), goods[k].view(np.uint16)), k
+
+
 def test_gemm_stack_rejects_what_it_does_not_run():
     torch = G.torch_mod()
     w = synth.weights(64, 4096, 1)
