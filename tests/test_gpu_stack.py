@@ -451,6 +451,16 @@ def test_smallm_kernels_replay_in_a_hip_graph():
         X = G.to_dev(synth.activation_rows(M, cols, 9000 + M).view(np.uint16)).view(torch.float16)
         Y = torch.zeros((M, rows), dtype=torch.float16, device="cuda:0")
         cases.append((B.prepared_sparse_gemm_smallm(p, X, Y), Y))
+    # and tables of several products in one launch (one and four token groups)
+    for M in (9, 50):
+        items = []
+        for (rows, cols) in ((300, 4096), (70, 11008), (130, 2048)):
+            w = synth.weights(rows, cols, 9100 + rows + M)
+            p = B.pack_2bitcsr(w, B.prune_n4(w, 2), 2, 128, B.VAL_INT4).to("cuda:0")
+            X = G.to_dev(synth.activation_rows(M, cols, 9100 + M).view(np.uint16)).view(torch.float16)
+            items.append((p, X, torch.zeros((M, rows), dtype=torch.float16, device="cuda:0")))
+        table = B.prepared_gemm_stack(items)
+        cases += [(table if k == 0 else (lambda stream_ptr=None: None), it[2]) for k, it in enumerate(items)]
     for call, _ in cases:
         call()
     torch.cuda.synchronize()
