@@ -898,7 +898,10 @@ static_assert(sizeof(SmallMStackEntry) <= EGT_STACK_ENTRY_BYTES, "descriptor lar
 #ifndef EGT_RS_WAVES
 #define EGT_RS_WAVES 8
 #endif
-constexpr int RS_WAVES = EGT_RS_WAVES, RS_Q = 4, RS_BUFS = 2, RS_STEP = 8 * KS_PAIR;
+#ifndef EGT_RS_Q
+#define EGT_RS_Q 4
+#endif
+constexpr int RS_WAVES = EGT_RS_WAVES, RS_Q = EGT_RS_Q, RS_BUFS = 2, RS_STEP = 8 * KS_PAIR;
 // NG token groups of 16 (M <= 16 NG), rounds of Q K-steps, W waves: LDS bytes of a workgroup
 constexpr int rs_lds_bytes(int ng, int q) { return RS_BUFS * ng * q * RS_STEP; }
 

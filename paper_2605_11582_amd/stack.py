@@ -126,11 +126,14 @@ class LayerStack:
         pre-marshalled call and the algorithmic bytes of one launch."""
         import torch
         items, nbytes = [], 0
-        for m in self.matrices:
+        rows_of = {}                                   # seeded token rows, drawn once per row length
+        for k, m in enumerate(self.matrices):
             if m.kind != "s24":
                 continue
             dev = m.y.device
-            X = torch.randn((M, m.cols), device=dev).to(torch.float16)
+            if m.cols not in rows_of:
+                rows_of[m.cols] = synth.activation_rows(M, m.cols, synth.seed_for(4, 1000 + m.cols)).view(np.int16)
+            X = torch.from_numpy(rows_of[m.cols]).to(dev).view(torch.float16)       # a device copy per matrix
             Y = torch.empty((M, m.rows), dtype=torch.float16, device=dev)
             items.append((m.keep[0], X, Y))
             nbytes += m.nbytes + (M - 1) * 2 * (m.cols + m.rows)
