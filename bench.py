@@ -268,7 +268,17 @@ def main():
         plan = step.plan
         row = entry(timer(lambda i: step(), 30, 5), step_bytes)
         row.update(M=plan.M, matrices=plan.count, grid=[plan.grid_x, plan.count], block_threads=plan.block_threads, lds_bytes=plan.lds_bytes)
-        print(json.dumps({"only_verify_stack": True, "config4_sparse_layers_one_launch": row}))
+        out = {"only_verify_stack": True, "config4_sparse_layers_one_launch": row}
+        if args.only_verify_stack <= 32:              # the 1:4 layers of the three-way mix (11 layers, 77 products)
+            del stk, step
+            torch.cuda.empty_cache()
+            stk = S.LayerStack.build(dev, distinct_layers=1, plan="mix3")
+            step, step_bytes = stk.verify_step(args.only_verify_stack, "s14")
+            plan = step.plan
+            row = entry(timer(lambda i: step(), 30, 5), step_bytes)
+            row.update(M=plan.M, matrices=plan.count, grid=[plan.grid_x, plan.count], block_threads=plan.block_threads, lds_bytes=plan.lds_bytes)
+            out["mix3_1to4_layers_one_launch"] = row
+        print(json.dumps(out))
         return
 
     if args.counter_run:

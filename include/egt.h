@@ -347,11 +347,13 @@ egt_status egt_gemv_stack_run(const void *table_dev, const egt_stack_plan *plan,
  * Y_k = X_k . W_k^T of different shapes in one launch.  A single product has to spread one
  * matrix over the whole chip; a table of them lets every compute unit work on several
  * matrices at once with small workgroups, which more than halves the time per product
- * (and the fixed cost of a launch is paid once per table).  Items: W a 2:4 INT4 2bit-CSR
- * view with group_size >= 64 (device buffers) and cols a multiple of 64; X: M x cols FP16
- * with the token rows back to back (ldx = cols), Y: M x rows FP16 (ldy = rows), device
- * pointers, X 16-byte aligned.  Other shapes give EGT_ERR_UNSUPPORTED: they run as single
- * products. */
+ * (and the fixed cost of a launch is paid once per table).  Items: W an INT4 2bit-CSR view
+ * (device buffers), all of a table of one storage form - 2:4 with group_size >= 64 and cols
+ * a multiple of 64, or (Sec. 3.2's sparser layers) 1:4 with group_size >= 128, cols a
+ * multiple of 128 and at most 32 tokens; X: M x cols FP16 with the token rows back to back
+ * (ldx = cols), Y: M x rows FP16 (ldy = rows), device pointers, X 16-byte aligned.  Other
+ * shapes, and tables that mix the two forms, give EGT_ERR_UNSUPPORTED: a mix runs as one
+ * table per form, anything else as single products. */
 typedef struct {
   const egt_2bitcsr *sparse;
   const uint16_t *X;
@@ -364,7 +366,7 @@ typedef struct {
   int32_t grid_x;        /* workgroups per matrix (0: every matrix is empty)                 */
   int32_t block_threads; /* threads per workgroup                                            */
   int32_t lds_bytes;     /* dynamic LDS per workgroup                                        */
-  int32_t reserved;
+  int32_t n_keep;        /* storage form of every matrix of the table: 2 (2:4) or 1 (1:4)    */
   uint64_t table_bytes;  /* count * EGT_STACK_ENTRY_BYTES                                    */
 } egt_gemm_plan;
 

@@ -69,7 +69,7 @@ class GemmItem(C.Structure):
 class GemmPlan(C.Structure):
     """Mirror of `egt_gemm_plan`."""
     _fields_ = [("count", C.c_int32), ("M", C.c_int32), ("grid_x", C.c_int32), ("block_threads", C.c_int32),
-                ("lds_bytes", C.c_int32), ("reserved", C.c_int32), ("table_bytes", C.c_uint64)]
+                ("lds_bytes", C.c_int32), ("n_keep", C.c_int32), ("table_bytes", C.c_uint64)]
 
 
 STACK_MAX_PARTS = 2

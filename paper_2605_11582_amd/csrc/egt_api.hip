@@ -272,14 +272,17 @@ egt_status egt_gemm_stack_plan(const egt_gemm_item *items, int count, int M, voi
         !aligned16(items[k].X))
       return EGT_ERR_BUFFER;
     if (!egt::smallm_stack_item_ok(*w, M)) return EGT_ERR_UNSUPPORTED;
+    if (w->n_keep != items[0].sparse->n_keep) return EGT_ERR_UNSUPPORTED;   // one storage form per table (one kernel)
     max_rows = w->rows > max_rows ? w->rows : max_rows;
   }
+  const int n_keep = items[0].sparse->n_keep;
   egt_gemm_plan out;
   std::memset(&out, 0, sizeof(out));
   out.count = count;
   out.M = M;
-  out.grid_x = egt::smallm_stack_blocks(M, max_rows);
-  egt::smallm_stack_shape(M, out.block_threads, out.lds_bytes);
+  out.n_keep = n_keep;
+  out.grid_x = egt::smallm_stack_blocks(M, n_keep, max_rows);
+  egt::smallm_stack_shape(M, n_keep, out.block_threads, out.lds_bytes);
   out.table_bytes = (uint64_t)count * EGT_STACK_ENTRY_BYTES;
   if (table) {
     if ((uint64_t)table_bytes < out.table_bytes) return EGT_ERR_SHAPE;
@@ -293,16 +296,18 @@ egt_status egt_gemm_stack_plan(const egt_gemm_item *items, int count, int M, voi
 egt_status egt_gemm_stack_run(const void *table_dev, const egt_gemm_plan *plan, void *stream) {
   if (!table_dev || !plan) return EGT_ERR_NULL;
   if (!aligned16(table_dev)) return EGT_ERR_BUFFER;
-  if (plan->count < 1 || plan->count > 65535 || plan->M < 2 || plan->M > 64) return EGT_ERR_SHAPE;
+  if (plan->count < 1 || plan->count > 65535 || plan->M < 2 || plan->M > 64 || (plan->n_keep != 1 && plan->n_keep != 2) ||
+      (plan->n_keep == 1 && plan->M > 32))
+    return EGT_ERR_SHAPE;
   int threads, lds;
-  egt::smallm_stack_shape(plan->M, threads, lds);
+  egt::smallm_stack_shape(plan->M, plan->n_keep, threads, lds);
   // (workgroups per matrix: what the plan call derived from the tallest matrix of the table)
   if (plan->grid_x < 0 || plan->grid_x > (1 << 20) || 
       plan->block_threads != threads || plan->lds_bytes != lds ||
       plan->table_bytes != (uint64_t)plan->count * EGT_STACK_ENTRY_BYTES)
     return EGT_ERR_SHAPE;
   if (plan->grid_x == 0) return EGT_OK;               // every matrix is empty
-  return done(egt::launch_smallm_stack(table_dev, plan->count, plan->M, plan->grid_x, (hipStream_t)stream));
+  return done(egt::launch_smallm_stack(table_dev, plan->count, plan->M, plan->n_keep, plan->grid_x, (hipStream_t)stream));
 }
 
 egt_status egt_int4_gemv_batch(const uint8_t *const *q, const uint16_t *const *qparams, int rows,

@@ -47,12 +47,12 @@ hipError_t launch_sparse_smallm(const egt_2bitcsr &w, const uint16_t *X, int64_t
                                 int64_t ldy, int M, hipStream_t stream);
 hipError_t launch_sparse_smallm_batch(const egt_2bitcsr *ws, const uint16_t *const *Xs, int64_t ldx, uint16_t *const *Ys,
                                       int64_t ldy, int M, int count, hipStream_t stream);
-// any number of 2:4 INT4 small-M products in one launch (egt_gemm_stack_plan / egt_gemm_stack_run)
+// any number of 2:4 (or of 1:4) INT4 small-M products in one launch (egt_gemm_stack_plan / egt_gemm_stack_run)
 bool smallm_stack_item_ok(const egt_2bitcsr &w, int M);
-int smallm_stack_blocks(int M, int max_rows);
-void smallm_stack_shape(int M, int &block_threads, int &lds_bytes);
+int smallm_stack_blocks(int M, int n_keep, int max_rows);
+void smallm_stack_shape(int M, int n_keep, int &block_threads, int &lds_bytes);
 void smallm_stack_entry(const egt_2bitcsr &w, const uint16_t *X, uint16_t *Y, int M, void *entry);
-hipError_t launch_smallm_stack(const void *table_dev, int count, int M, int grid_x, hipStream_t stream);
+hipError_t launch_smallm_stack(const void *table_dev, int count, int M, int n_keep, int grid_x, hipStream_t stream);
 // (dispatch: identically shaped members; falls back to one launch per member where no batched kernel applies)
 hipError_t launch_sparse_gemm_batch(const egt_2bitcsr *ws, const uint16_t *const *Xs, int64_t ldx, uint16_t *const *Ys,
                                     int64_t ldy, int M, int count, hipStream_t stream);

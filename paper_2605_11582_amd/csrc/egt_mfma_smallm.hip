@@ -901,15 +901,22 @@ static_assert(sizeof(SmallMStackEntry) <= EGT_STACK_ENTRY_BYTES, "descriptor lar
 #ifndef EGT_RS_Q
 #define EGT_RS_Q 4
 #endif
-constexpr int RS_WAVES = EGT_RS_WAVES, RS_Q = EGT_RS_Q, RS_BUFS = 2, RS_STEP = 8 * KS_PAIR;
-// NG token groups of 16 (M <= 16 NG), rounds of Q K-steps, W waves: LDS bytes of a workgroup
-constexpr int rs_lds_bytes(int ng, int q) { return RS_BUFS * ng * q * RS_STEP; }
+constexpr int RS_WAVES = EGT_RS_WAVES, RS_Q = EGT_RS_Q, RS_BUFS = 2;
+// LDS bytes of the token rows of one K-step and token group: 2:4 eight pairs of tokens (256 columns), 1:4 sixteen
+// tokens of 512 columns
+constexpr int rs_step_bytes(bool n1) { return n1 ? 16 * KS_TOKEN_N1 : 8 * KS_PAIR; }
+// NG token groups of 16 (M <= 16 NG), rounds of Q K-steps: LDS bytes of a workgroup
+constexpr int rs_lds_bytes(int ng, int q, bool n1 = false) { return RS_BUFS * ng * q * rs_step_bytes(n1); }
 
-template <int NG, int Q, int W>
+// N1: 1:4 sparsity (chunks of 128 columns, eight instructions a K-step, a request of X per token).
+template <int NG, int Q, int W, bool N1 = false>
 __global__ __launch_bounds__(64 * W, 4) void k_smallm_rows(const uint8_t *__restrict__ table) {
-  constexpr int RS_WAVES = W, RS_Q = Q, RS_REGION = NG * Q * RS_STEP;
-  constexpr int RS_REQ = NG * Q * 8 / W;              // requests of X a wave issues per round
-  static_assert(RS_REQ * W == NG * Q * 8 && Q % 2 == 0, "the waves share the requests of a round evenly");
+  constexpr int RS_WAVES = W, RS_Q = Q, RS_STEP = rs_step_bytes(N1), RS_REGION = NG * Q * RS_STEP;
+  constexpr int XREQ = N1 ? 16 : 8;                   // requests of X per K-step and token group
+  constexpr int NM = N1 ? 8 : 4;                      // matrix instructions per K-step
+  constexpr int PIECES = N1 ? 64 : 32;                // 16-byte pieces of a token row in a K-step
+  constexpr int RS_REQ = NG * Q * XREQ / W;           // requests of X a wave issues per round
+  static_assert(RS_REQ * W == NG * Q * XREQ && Q % 2 == 0, "the waves share the requests of a round evenly");
   extern __shared__ __align__(16) uint8_t xs[];       // RS_BUFS regions of RS_REGION bytes
   typedef __attribute__((address_space(1))) const uint32_t *g_u32;
   typedef __attribute__((address_space(1))) const uint8_t *g_u8;
@@ -994,21 +1001,22 @@ __global__ __launch_bounds__(64 * W, 4) void k_smallm_rows(const uint8_t *__rest
   // Every wave issues the same number of them, so that the wait counts are fixed; a pair past
   // M or a step past K asks out of range.
   const int xtl = lane >> 5;
-  const int slot_piece = (lane & 31) ^ xtl;           // piece of X this lane delivers
+  const int slot_piece = N1 ? lane : ((lane & 31) ^ xtl);   // piece of X this lane delivers
   auto dma_x = [&](int round, int buf) {
     asm volatile("" ::: "memory");                    // the requests stay together, in program order
 #pragma unroll
     for (int k = 0; k < RS_REQ; ++k) {
-      const int r = wave * RS_REQ + k;                // request r of the round: token group, K-step, pair of tokens
-      const int grp = r / (8 * RS_Q), xq = (r >> 3) % RS_Q, u = r & 7, t0 = 16 * grp + 2 * u;
-      const int step = RS_Q * round + xq;
-      const int vp = max(1, min(32, g.kpieces - 32 * step));   // pieces of the step inside K
+      const int r = wave * RS_REQ + k;                // request r of the round: token group, K-step, pair of tokens (1:4: token)
+      const int gq = r / XREQ, u = r % XREQ;          // (group, K-step) as one index: the region's order
+      const int grp = gq / RS_Q, t0 = 16 * grp + (N1 ? u : 2 * u);
+      const int step = RS_Q * round + gq % RS_Q;
+      const int vp = max(1, min(PIECES, g.kpieces - PIECES * step));   // pieces of the step inside K
       const uint32_t off_lo = 16u * (uint32_t)min(slot_piece, vp - 1);
-      const uint32_t off_hi = off_lo + (uint32_t)xtl * (uint32_t)(2 * g.ldx);
+      const uint32_t off_hi = N1 ? off_lo : off_lo + (uint32_t)xtl * (uint32_t)(2 * g.ldx);
       const bool on = t0 < g.M && step < nsteps;      // uniform
-      __builtin_amdgcn_raw_ptr_buffer_load_lds(r_x, (__attribute__((address_space(3))) void *)(xs + buf * RS_REGION + (r >> 3) * RS_STEP + KS_PAIR * u), 16,
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(r_x, (__attribute__((address_space(3))) void *)(xs + buf * RS_REGION + gq * RS_STEP + (N1 ? KS_TOKEN_N1 : KS_PAIR) * u), 16,
                                                on ? (t0 + 1 < g.M ? off_hi : off_lo) : off_range,
-                                               on ? 512u * (uint32_t)step + (uint32_t)t0 * (uint32_t)(2 * g.ldx) : 0u, 0, 0);
+                                               on ? (uint32_t)(16 * PIECES) * (uint32_t)step + (uint32_t)t0 * (uint32_t)(2 * g.ldx) : 0u, 0, 0);
     }
     asm volatile("" ::: "memory");
   };
@@ -1017,16 +1025,17 @@ __global__ __launch_bounds__(64 * W, 4) void k_smallm_rows(const uint8_t *__rest
 #pragma unroll
     for (int k = 0; k < RS_REQ; ++k) {
       const int r = wave * RS_REQ + k;
-      const int vp = g.kpieces - 32 * (RS_Q * round + (r >> 3) % RS_Q);
-      if (vp > 0 && vp < 32 && slot_piece >= vp)
-        *(u4 *)(xs + buf * RS_REGION + (r >> 3) * RS_STEP + KS_PAIR * (r & 7) + 16 * lane) = u4{0, 0, 0, 0};
+      const int vp = g.kpieces - PIECES * (RS_Q * round + (r / XREQ) % RS_Q);
+      if (vp > 0 && vp < PIECES && slot_piece >= vp)
+        *(u4 *)(xs + buf * RS_REGION + (r / XREQ) * RS_STEP + (N1 ? KS_TOKEN_N1 : KS_PAIR) * (r % XREQ) + 16 * lane) = u4{0, 0, 0, 0};
     }
   };
   // B operand of instruction m of a K-step (as in the kernel above: lane (n, b) holds token n,
   // k-octets b and 4 + b of the instruction's 16-column group)
-  const int b_off = KS_PAIR * ((lane & 15) >> 1) + 512 * (lane & 1) + 16 * (8 * (lane >> 5) + (((lane >> 4) ^ lane) & 1));
+  const int b_off = N1 ? KS_TOKEN_N1 * (lane & 15) + 16 * (16 * (lane >> 5) + ((lane >> 4) & 1))
+                       : KS_PAIR * ((lane & 15) >> 1) + 512 * (lane & 1) + 16 * (8 * (lane >> 5) + (((lane >> 4) ^ lane) & 1));
   auto read_b = [&](const uint8_t *region, int m) {
-    const u4 lo = *(const u4 *)(region + b_off + 32 * m), hi = *(const u4 *)(region + b_off + 256 + 32 * m);
+    const u4 lo = *(const u4 *)(region + b_off + 32 * m), hi = *(const u4 *)(region + b_off + (N1 ? 512 : 256) + 32 * m);
     return u8v{lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
   };
 
@@ -1067,18 +1076,41 @@ __global__ __launch_bounds__(64 * W, 4) void k_smallm_rows(const uint8_t *__rest
       const bool live = 4 * step + kb < g.nchunks;    // false: a chunk past the end of K
       const uint32_t s2 = live ? __builtin_amdgcn_perm(t.qp[0], t.qp[0], 0x01000100u) : 0u;
       const uint32_t off = pk_add_f16(__builtin_amdgcn_perm(t.qp[0], t.qp[0], 0x03020302u), g.nib_magic);
-      // the operands of the step's four instructions serve every token group
-      u4 av[4];
+      // the operands of the step's instructions serve every token group
+      u4 av[NM];
+      uint32_t iwv[NM / 2];
+      if constexpr (N1) {
+        // every slot becomes the pair {value, 0} with its offset in the even index field; instruction m takes
+        // slots 4 m .. 4 m + 3 of the chunk: bytes 2 (m & 1), 2 (m & 1) + 1 of dword m >> 1
+        iwv[0] = spread_idx(t.iw[0] & 0xFFFFu, g.m8, g.m4, g.m2);
+        iwv[1] = spread_idx(t.iw[0] >> 16, g.m8, g.m4, g.m2);
+        iwv[2] = spread_idx(t.iw[1] & 0xFFFFu, g.m8, g.m4, g.m2);
+        iwv[3] = spread_idx(t.iw[1] >> 16, g.m8, g.m4, g.m2);
 #pragma unroll
-      for (int m = 0; m < 4; ++m) av[m] = dequant8(t.nib[0][m], off, s2, g.nib_mask, magic);
+        for (int m = 0; m < NM; ++m) {
+          const uint32_t d = t.nib[0][m >> 1];
+#pragma unroll
+          for (int p = 0; p < 2; ++p) {
+            const uint32_t t2 = __builtin_amdgcn_perm(d, d, 0x0c000c00u + (uint32_t)(2 * (m & 1) + p) * 0x00010001u);
+            const uint32_t pair = pk_mul_f16(pk_sub_f16(and_or(t2, g.nib_mask, magic), off), s2);
+            av[m][2 * p] = pair & 0xFFFFu;
+            av[m][2 * p + 1] = pair >> 16;
+          }
+        }
+      } else {
+        iwv[0] = t.iw[0];
+        iwv[1] = t.iw[1];
+#pragma unroll
+        for (int m = 0; m < NM; ++m) av[m] = dequant8(t.nib[0][m], off, s2, g.nib_mask, magic);
+      }
 #pragma unroll
       for (int grp = 0; grp < NG; ++grp) {
         if (NG > 1 && 16 * grp >= g.M) continue;      // uniform
         const uint8_t *bregion = xs + buf * RS_REGION + (grp * RS_Q + q) * RS_STEP;
 #pragma unroll
-        for (int m = 0; m < 4; ++m) {
-          const u8v bx = read_b(bregion, m);          // (read per instruction: 8 registers of B at a time instead of 32)
-          const int iword = (int)t.iw[m >> 1];
+        for (int m = 0; m < NM; ++m) {
+          const u8v bx = read_b(bregion, m);          // (read per instruction: 8 registers of B at a time)
+          const int iword = (int)iwv[m >> 1];
           if (m & 1)
             acc[grp] = __builtin_amdgcn_smfmac_f32_16x16x64_f16(__builtin_bit_cast(h8, av[m]), __builtin_bit_cast(h16, bx), acc[grp], iword, 0, 1);
           else
@@ -1115,23 +1147,27 @@ __global__ __launch_bounds__(64 * W, 4) void k_smallm_rows(const uint8_t *__rest
   }
 }
 
-// Shapes the stack takes: 2:4 INT4 with one {scale, zero} pair per chunk.
+// Shapes the stack takes: INT4 with one {scale, zero} pair per chunk, 2:4 (up to 64 tokens) or 1:4 (up to 32: the
+// token rows of a K-step are twice as long).
 bool smallm_stack_item_ok(const egt_2bitcsr &w, int M) {
-  if (w.val_kind != EGT_VAL_INT4 || w.n_keep != 2 || w.group_size < 64) return false;
+  if (w.val_kind != EGT_VAL_INT4) return false;
+  if (!(w.n_keep == 2 && w.group_size >= 64) && !(w.n_keep == 1 && w.group_size >= 128 && M <= 32)) return false;
   return sparse_smallm_supported(w, w.cols, M);
 }
 
-static int stack_waves(int M) { return M <= 32 ? RS_WAVES : 16; }
+static int stack_waves(int M, bool n1) { return M <= (n1 ? 16 : 32) ? RS_WAVES : 16; }
 
 // workgroups per matrix: one per row tile and wave of the tallest matrix
-int smallm_stack_blocks(int M, int max_rows) {
-  const int ntiles = (max_rows + 15) / 16, w = stack_waves(M);
+int smallm_stack_blocks(int M, int n_keep, int max_rows) {
+  const int ntiles = (max_rows + 15) / 16, w = stack_waves(M, n_keep == 1);
   return (ntiles + w - 1) / w;
 }
 
-void smallm_stack_shape(int M, int &block_threads, int &lds_bytes) {
-  block_threads = 64 * stack_waves(M);
-  lds_bytes = M <= 16 ? rs_lds_bytes(1, RS_Q) : M <= 32 ? rs_lds_bytes(2, 2) : rs_lds_bytes(4, 2);
+void smallm_stack_shape(int M, int n_keep, int &block_threads, int &lds_bytes) {
+  const bool n1 = n_keep == 1;
+  block_threads = 64 * stack_waves(M, n1);
+  if (n1) lds_bytes = rs_lds_bytes(M <= 16 ? 1 : 2, 2, true);
+  else lds_bytes = M <= 16 ? rs_lds_bytes(1, RS_Q) : M <= 32 ? rs_lds_bytes(2, 2) : rs_lds_bytes(4, 2);
 }
 
 // Descriptor of one item into 160 bytes of the table.
@@ -1146,11 +1182,15 @@ void smallm_stack_entry(const egt_2bitcsr &w, const uint16_t *X, uint16_t *Y, in
   std::memcpy(entry, &e, sizeof(e));
 }
 
-hipError_t launch_smallm_stack(const void *table_dev, int count, int M, int grid_x, hipStream_t stream) {
+hipError_t launch_smallm_stack(const void *table_dev, int count, int M, int n_keep, int grid_x, hipStream_t stream) {
   int threads, lds;
-  smallm_stack_shape(M, threads, lds);
+  smallm_stack_shape(M, n_keep, threads, lds);
   const dim3 grid(grid_x, count), block(threads);
   const uint8_t *t = (const uint8_t *)table_dev;
+  if (n_keep == 1) {
+    if (M <= 16) return launch(k_smallm_rows<1, 2, RS_WAVES, true>, grid, block, (size_t)lds, stream, t);
+    return launch(k_smallm_rows<2, 2, 16, true>, grid, block, (size_t)lds, stream, t);
+  }
   if (M <= 16) return launch(k_smallm_rows<1, RS_Q, RS_WAVES>, grid, block, (size_t)lds, stream, t);
   if (M <= 32) return launch(k_smallm_rows<2, 2, RS_WAVES>, grid, block, (size_t)lds, stream, t);
   return launch(k_smallm_rows<4, 2, 16>, grid, block, (size_t)lds, stream, t);

@@ -485,22 +485,27 @@ def test_smallm_kernels_replay_in_a_hip_graph():
             assert np.array_equal(Y.cpu().numpy().view(np.uint16), eager[k].view(np.uint16)), (rep, k)
 
 
-@pytest.mark.parametrize("M", [2, 5, 16, 17, 32, 33, 40, 64])
-def test_gemm_stack_equals_the_oracle_and_the_separate_products(M):
+@pytest.mark.parametrize("M,n", [(2, 2), (5, 2), (16, 2), (17, 2), (32, 2), (33, 2), (40, 2), (64, 2),
+                                 (3, 1), (16, 1), (20, 1), (32, 1)])
+def test_gemm_stack_equals_the_oracle_and_the_separate_products(M, n):
     # a verification step through several layers in one launch: shapes with fewer row tiles than
     # workgroups, a ragged last tile, several rounds of row tiles, a row length that ends inside
     # a K-step, an empty matrix; Y buffers with and without 8-byte alignment, canaries around
     torch = G.torch_mod()
-    print(f"case gemm stack M={M}", flush=True)
-    shapes = [(300, 4096, 128), (70, 11008, 128), (16 * 96 * 8 + 40, 4096, 4096), (133, 8192, 64), (0, 4096, 128),
-              (21, 4160, 64), (50, 832, 64), (1700, 2048, 128)]
-    shapes += [(40, 64, 64), (33, 320, 64), (18, 1280, 256)]     # rows shorter than a round of K-steps, and than a K-step
+    print(f"case gemm stack M={M} n={n}", flush=True)
+    if n == 2:
+        shapes = [(300, 4096, 128), (70, 11008, 128), (16 * 96 * 8 + 40, 4096, 4096), (133, 8192, 64), (0, 4096, 128),
+                  (21, 4160, 64), (50, 832, 64), (1700, 2048, 128)]
+        shapes += [(40, 64, 64), (33, 320, 64), (18, 1280, 256)]     # rows shorter than a round of K-steps, and than a K-step
+    else:                                             # 1:4: chunks of 128 columns, K-steps of 512
+        shapes = [(300, 4096, 128), (70, 11008, 128), (16 * 96 * 4 + 40, 4096, 4096), (133, 8192, 256), (0, 4096, 128),
+                  (21, 4224, 128), (50, 1664, 128), (1700, 2048, 128), (40, 128, 128), (33, 640, 128), (18, 1536, 512)]
     ps, os_, Xs = [], [], []
     for k, (rows, cols, g) in enumerate(shapes):
         w = synth.weights(rows, cols, 8800 + 7 * k + M)
-        mask = O.prune_n4_magnitude(w, 2)
-        ps.append(B.pack_2bitcsr(w, mask, 2, g, B.VAL_INT4))
-        os_.append(O.pack_2bitcsr(w, mask, 2, g, B.VAL_INT4) if 0 < rows <= 400 else None)
+        mask = O.prune_n4_magnitude(w, n)
+        ps.append(B.pack_2bitcsr(w, mask, n, g, B.VAL_INT4))
+        os_.append(O.pack_2bitcsr(w, mask, n, g, B.VAL_INT4) if 0 < rows <= 400 else None)
         Xs.append(synth.activation_rows(M, cols, 8800 + k))
     pds = [p.to("cuda:0") for p in ps]
     Xd = [G.to_dev(X.view(np.uint16)).view(torch.float16) for X in Xs]
@@ -573,11 +578,21 @@ def test_gemm_stack_rejects_what_it_does_not_run():
     w = synth.weights(64, 4096, 1)
     X = torch.zeros((8, 4096), dtype=torch.float16, device="cuda:0")
     Y = torch.zeros((8, 64), dtype=torch.float16, device="cuda:0")
-    for n, g, kind in ((1, 128, B.VAL_INT4), (2, 32, B.VAL_INT4), (2, 0, B.VAL_FP16)):
+    for n, g, kind in ((1, 64, B.VAL_INT4), (2, 32, B.VAL_INT4), (2, 0, B.VAL_FP16)):
         p = B.pack_2bitcsr(w, B.prune_n4(w, n), n, g, kind).to("cuda:0")
         with pytest.raises(B.EgtError) as e:
             B.prepared_gemm_stack([(p, X, Y)])
         assert e.value.status == 6
+    # the two storage forms in one table; 1:4 beyond 32 tokens
+    p2 = B.pack_2bitcsr(w, B.prune_n4(w, 2), 2, 128, B.VAL_INT4).to("cuda:0")
+    p1 = B.pack_2bitcsr(w, B.prune_n4(w, 1), 1, 128, B.VAL_INT4).to("cuda:0")
+    with pytest.raises(B.EgtError) as e:
+        B.prepared_gemm_stack([(p2, X, Y), (p1, X, torch.zeros_like(Y))])
+    assert e.value.status == 6
+    X40 = torch.zeros((40, 4096), dtype=torch.float16, device="cuda:0")
+    with pytest.raises(B.EgtError) as e:
+        B.prepared_gemm_stack([(p1, X40, torch.zeros((40, 64), dtype=torch.float16, device="cuda:0"))])
+    assert e.value.status == 6
 
 
 def test_two_streams_at_once_give_the_serial_results():

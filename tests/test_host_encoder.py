@@ -615,6 +615,7 @@ def test_gemm_stack_plan_checks_items_and_reports_the_launch_shape():
     items[1].X = 24
     assert L.egt_gemm_stack_plan(items, 3, 16, table.ctypes.data, table.nbytes, ctypes.byref(plan2)) == 5
     items[1].X = 16
+    # (1:4 beside 2:4, 1:4 with groups below 128, 2:4 with groups below 64, FP16 values)
     for bad in (B.View(64, 4096, 1, 128, 0, 16, 16, 16, 16), B.View(64, 4096, 2, 32, 0, 16, 16, 16, 16),
                 B.View(64, 4096, 2, 0, 1, 16, 16, 16, None)):
         items[0].sparse = ctypes.pointer(bad)
@@ -624,10 +625,24 @@ def test_gemm_stack_plan_checks_items_and_reports_the_launch_shape():
     items[0].sparse = ctypes.pointer(short)
     assert L.egt_gemm_stack_plan(items, 3, 17, table.ctypes.data, table.nbytes, ctypes.byref(plan2)) == 0
     assert not np.all(table == 0xA5) and plan2.count == 3
+    # a table of 1:4 matrices: rounds of two K-steps of 512 columns, sixteen token rows of 1040 bytes per K-step
+    one4 = (B.GemmItem * 2)()
+    v14 = [B.View(4096, 4096, 1, 128, 0, 16, 16, 16, 16), B.View(11008, 4096, 1, 256, 0, 16, 16, 16, 16)]
+    for k, v in enumerate(v14):
+        one4[k].sparse, one4[k].X, one4[k].Y = ctypes.pointer(v), 16, 16
+    p14 = B.GemmPlan()
+    assert L.egt_gemm_stack_plan(one4, 2, 16, None, 0, ctypes.byref(p14)) == 0
+    assert (p14.n_keep, p14.grid_x, p14.block_threads, p14.lds_bytes) == (1, 86, 512, 2 * 2 * 16 * 1040)
+    assert L.egt_gemm_stack_plan(one4, 2, 32, None, 0, ctypes.byref(p14)) == 0
+    assert (p14.n_keep, p14.grid_x, p14.block_threads, p14.lds_bytes) == (1, 43, 1024, 2 * 2 * 2 * 16 * 1040)
+    assert L.egt_gemm_stack_plan(one4, 2, 33, None, 0, ctypes.byref(p14)) == 6
+    v14[1].group_size = 64
+    assert L.egt_gemm_stack_plan(one4, 2, 16, None, 0, ctypes.byref(p14)) == 6
+    assert plan.n_keep == 2
     # the run call checks the plan before anything is launched
     assert L.egt_gemm_stack_run(None, ctypes.byref(plan), None) == 1
     assert L.egt_gemm_stack_run(24, ctypes.byref(plan), None) == 5
-    for field, value in (("count", 0), ("M", 1), ("M", 40), ("grid_x", -1), ("grid_x", 1 << 21), ("block_threads", 256), ("lds_bytes", 1024),
+    for field, value in (("count", 0), ("M", 1), ("M", 40), ("n_keep", 0), ("n_keep", 3), ("grid_x", -1), ("grid_x", 1 << 21), ("block_threads", 256), ("lds_bytes", 1024),
                          ("table_bytes", 160)):
         broken = B.GemmPlan.from_buffer_copy(plan)
         setattr(broken, field, value)
