@@ -69,11 +69,11 @@ def test_requests_of_the_row_split_stack_kernel_match_its_wait_counts(smallm_asm
     loads = int(re.search(r"static constexpr int LOADS = KIND == EGT_VAL_INT4 \? (\d+) : 1 \+ VW;", text).group(1))
     seen = 0
     for name, body in smallm_asm:
-        m = re.search(r"k_smallm_rowsILi(\d+)ELi(\d+)ELi(\d+)E", name)       # NG, Q, W
+        m = re.search(r"k_smallm_rowsILi(\d+)ELi(\d+)ELi(\d+)ELb(\d)E", name)       # NG, Q, W, N1
         if not m:
             continue
-        ng, q, w = (int(v) for v in m.groups())
-        per_round, x_per_round = q * loads, ng * q * 8 // w
+        ng, q, w, n1 = (int(v) for v in m.groups())
+        per_round, x_per_round = q * loads, ng * q * (16 if n1 else 8) // w      # (1:4: a request of X per token, 2:4: per pair)
         requests = [ln for ln in body.split("\n") if re.search(r"\bbuffer_load_dword", ln)]
         to_lds = [ln for ln in requests if " lds" in ln]
         assert len(requests) - len(to_lds) == 4 * per_round, (name, len(requests), len(to_lds))   # rounds 0, 1 and j + 2 twice
@@ -83,4 +83,4 @@ def test_requests_of_the_row_split_stack_kernel_match_its_wait_counts(smallm_asm
         assert len(re.findall(r"\bs_barrier\b", body)) == 2, name
         assert not re.search(r"\bscratch_|\bflat_", body), name
         seen += 1
-    assert seen == 3
+    assert seen == 5
