@@ -278,6 +278,10 @@ def main():
             row = entry(timer(lambda i: step(), 30, 5), step_bytes)
             row.update(M=plan.M, matrices=plan.count, grid=[plan.grid_x, plan.count], block_threads=plan.block_threads, lds_bytes=plan.lds_bytes)
             out["mix3_1to4_layers_one_launch"] = row
+            both, both_bytes = stk.verify_step(args.only_verify_stack, ("s24", "s14"))
+            row = entry(timer(lambda i: both(), 30, 5), both_bytes)
+            row.update(M=plan.M, matrices=sum(p.count for p in both.plans), launches=len(both.plans))
+            out["mix3_sparse_layers_one_call"] = row
         print(json.dumps(out))
         return
 

@@ -661,38 +661,51 @@ def prepared_gemv_stack(items, stream=None, form=STACK_AUTO):
     return call
 
 
-def prepared_gemm_stack(items, stream=None):
-    """One launch for a list of small-M products Y = X . W^T under the same number of tokens.
-
-    items: tuples (Packed, X, Y) with contiguous device tensors X (M, cols) and Y (M, rows).
-    The descriptor table is planned by the library on the host and uploaded here into a
-    device tensor that the returned call keeps alive."""
+def _prepared_gemm_table(items, M, stream):
     import torch
     n = len(items)
     arr = (GemmItem * n)()
-    views, keep = [], []
-    M = int(items[0][1].shape[0]) if n else 0
+    views = []
     for k, (p, X, Y) in enumerate(items):
-        _check_xy(p, X, Y)
-        if X.shape[0] != M or not X.is_contiguous() or not Y.is_contiguous():
-            raise ValueError("every X and Y of the table must be contiguous and hold the same number of tokens")
         v = p.view()
         views.append(v)
         arr[k].sparse = C.pointer(v)
         arr[k].X, arr[k].Y = _dev(X), _dev(Y)
-        keep.append((p, X, Y))
     plan = GemmPlan()
     _check(lib().egt_gemm_stack_plan(arr, n, M, None, 0, C.byref(plan)))    # size query
     table = np.zeros(int(plan.table_bytes), dtype=np.uint8)
     _check(lib().egt_gemm_stack_plan(arr, n, M, _np_ptr(table), table.nbytes, C.byref(plan)))
-    table_dev = torch.from_numpy(table).to(keep[0][2].device)
-    fn, tp, ref, sp = lib().egt_gemm_stack_run, table_dev.data_ptr(), C.byref(plan), _stream_ptr(stream)
+    table_dev = torch.from_numpy(table).to(items[0][2].device)
+    return lib().egt_gemm_stack_run, table_dev.data_ptr(), C.byref(plan), plan, (table_dev, views, arr, items)
 
-    def call(stream_ptr=sp, _keep=(table_dev, plan, keep, views, arr)):
-        st = fn(tp, ref, stream_ptr)
-        if st:
-            _check(st)
-    call.plan = plan
+
+def prepared_gemm_stack(items, stream=None):
+    """One launch per storage form for a list of small-M products Y = X . W^T under the same
+    number of tokens.
+
+    items: tuples (Packed, X, Y) with contiguous device tensors X (M, cols) and Y (M, rows).
+    A list that holds 2:4 and 1:4 matrices becomes two tables (the library takes one form
+    per table), run one after the other.  The descriptor tables are planned by the library
+    on the host and uploaded here into device tensors that the returned call keeps alive."""
+    if not items:
+        raise ValueError("no items")
+    M = int(items[0][1].shape[0])
+    by_form = {}
+    for (p, X, Y) in items:
+        _check_xy(p, X, Y)
+        if X.shape[0] != M or not X.is_contiguous() or not Y.is_contiguous():
+            raise ValueError("every X and Y of the table must be contiguous and hold the same number of tokens")
+        by_form.setdefault(p.n_keep, []).append((p, X, Y))
+    tables = [_prepared_gemm_table(group, M, stream) for group in by_form.values()]
+    sp = _stream_ptr(stream)
+
+    def call(stream_ptr=sp, _tables=tables):
+        for fn, tp, ref, _, _ in _tables:
+            st = fn(tp, ref, stream_ptr)
+            if st:
+                _check(st)
+    call.plans = [t[3] for t in tables]
+    call.plan = call.plans[0]
     return call
 
 

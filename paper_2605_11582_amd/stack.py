@@ -120,16 +120,17 @@ class LayerStack:
         """The whole stack - 224 products of mixed storage forms - in a single launch."""
         return B.prepared_gemv_stack([self._item(m) for m in self.matrices])
 
-    def verify_step(self, M: int, kind: str = "s24"):
-        """A verification step of M candidate tokens (Sec. 3.4) through the 2:4 (kind "s24")
-        or the 1:4 ("s14") layers of the stack in one launch: every such matrix times M token
-        rows of its own.  Returns the pre-marshalled call and the algorithmic bytes of one
-        launch."""
+    def verify_step(self, M: int, kind="s24"):
+        """A verification step of M candidate tokens (Sec. 3.4) through the 2:4 (kind "s24"),
+        the 1:4 ("s14") or all sparse (("s24", "s14"): one launch per form) layers of the
+        stack: every such matrix times M token rows of its own.  Returns the pre-marshalled
+        call and the algorithmic bytes of one call."""
+        kinds = (kind,) if isinstance(kind, str) else tuple(kind)
         import torch
         items, nbytes = [], 0
         rows_of = {}                                   # seeded token rows, drawn once per row length
         for k, m in enumerate(self.matrices):
-            if m.kind != kind:
+            if m.kind not in kinds:
                 continue
             dev = m.y.device
             if m.cols not in rows_of:

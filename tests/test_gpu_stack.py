@@ -583,12 +583,25 @@ def test_gemm_stack_rejects_what_it_does_not_run():
         with pytest.raises(B.EgtError) as e:
             B.prepared_gemm_stack([(p, X, Y)])
         assert e.value.status == 6
-    # the two storage forms in one table; 1:4 beyond 32 tokens
+    # the two storage forms in one table (the binding makes a table per form; here through the C ABI); 1:4 beyond 32 tokens
     p2 = B.pack_2bitcsr(w, B.prune_n4(w, 2), 2, 128, B.VAL_INT4).to("cuda:0")
     p1 = B.pack_2bitcsr(w, B.prune_n4(w, 1), 1, 128, B.VAL_INT4).to("cuda:0")
-    with pytest.raises(B.EgtError) as e:
-        B.prepared_gemm_stack([(p2, X, Y), (p1, X, torch.zeros_like(Y))])
-    assert e.value.status == 6
+    import ctypes
+    arr, views = (B.GemmItem * 2)(), [p2.view(), p1.view()]
+    for k in range(2):
+        arr[k].sparse, arr[k].X, arr[k].Y = ctypes.pointer(views[k]), X.data_ptr(), Y.data_ptr()
+    assert B.lib().egt_gemm_stack_plan(arr, 2, 8, None, 0, ctypes.byref(B.GemmPlan())) == 6
+    # ... and the binding's two tables give each member the bits of a table of its own
+    Ya, Yb, Yc, Yd = (torch.zeros_like(Y) for _ in range(4))
+    Xr = G.to_dev(synth.activation_rows(8, 4096, 77).view(np.uint16)).view(torch.float16)
+    mixed = B.prepared_gemm_stack([(p2, Xr, Ya), (p1, Xr, Yb)])
+    assert [pl.n_keep for pl in mixed.plans] == [2, 1]
+    mixed()
+    B.prepared_gemm_stack([(p2, Xr, Yc)])()
+    B.prepared_gemm_stack([(p1, Xr, Yd)])()
+    torch.cuda.synchronize()
+    assert torch.equal(Ya.view(torch.int16), Yc.view(torch.int16)) and torch.equal(Yb.view(torch.int16), Yd.view(torch.int16))
+    assert float(Ya.abs().max()) > 0 and float(Yb.abs().max()) > 0
     X40 = torch.zeros((40, 4096), dtype=torch.float16, device="cuda:0")
     with pytest.raises(B.EgtError) as e:
         B.prepared_gemm_stack([(p1, X40, torch.zeros((40, 64), dtype=torch.float16, device="cuda:0"))])
