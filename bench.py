@@ -200,7 +200,8 @@ def main():
                          "M = 16 / 64), for rocprofv3 counter runs")
     ap.add_argument("--counter-run", action="store_true",
                     help="a short run for rocprofv3 --pmc: --steps headline launches without clock warm-up, read "
-                         "ceilings, table or oracle, then the --counter-workloads launches and five whole-stack launches")
+                         "ceilings, table or oracle, then the --counter-workloads launches, five whole-stack launches and five "
+                         "verification-step launches at 16 and at 64 tokens")
     ap.add_argument("--only-stack", action="store_true",
                     help="time the whole-stack launch of configuration 4 only (for sweeps of a tuning build)")
     ap.add_argument("--only-verify-stack", type=int, default=0, metavar="M",
@@ -309,6 +310,12 @@ def main():
         for _ in range(5):
             whole()
         torch.cuda.synchronize()
+        for m_tokens in (16, 64):                     # a verification step through the 2:4 layers in one launch
+            step, _ = stk.verify_step(m_tokens)
+            for _ in range(5):
+                step()
+            torch.cuda.synchronize()
+            del step
         print(json.dumps({"counter_run": True, "headline_launches": args.steps}))
         return
 

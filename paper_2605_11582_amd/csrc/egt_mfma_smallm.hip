@@ -950,7 +950,7 @@ __global__ __launch_bounds__(64 * W, 4) void k_smallm_rows(const uint8_t *__rest
   const __amdgpu_buffer_rsrc_t r_x = make_rsrc((const __half *)(g_h)e->X, g.x_bytes);
   const uint32_t off_range = 0xFFFFFFF0u;             // past every buffer: such a request returns zeros and moves no data
   // A round of a tile is 16 rows x 16 chunks.  A request covers 8 rows x 8 chunks - lane
-  // (r, c) = (lane >> 3, lane & 7) fetches chunk 8 p + c of row 8 h + r: 128 contiguous bytes
+  // (r, c) = (lane >> 3, lane & 7, see below) fetches chunk 8 p + c of row 8 h + r: 128 contiguous bytes
   // of nibbles per row, whole cache lines - so four requests (h, p) per array fetch the round,
   // and request (h, p) holds the K-steps 2 p and 2 p + 1 of half h of the rows.
   struct RoundRegs {
@@ -958,7 +958,9 @@ __global__ __launch_bounds__(64 * W, 4) void k_smallm_rows(const uint8_t *__rest
     u2 iw[2][Q / 2];
     uint32_t qp[2][Q / 2];
   };
-  const int r8 = lane >> 3, c8 = lane & 7;
+  // (rows 4 to 7 of a request keep their chunks in the other order of halves - lane (r, c) fetches chunk c ^ (r & 4):
+  //  the lanes that a lane permutation reads for rows r and r + 4 then lie in different LDS banks)
+  const int r8 = lane >> 3, c8 = (lane & 7) ^ ((lane >> 3) & 4);
   auto load_half = [&](RoundRegs &a, int round, int p) {   // the requests (0, p) and (1, p): 2 * LPT of them
     const bool on = has_tile && RS_Q * round + 2 * p < nsteps;                // uniform
     const int c0 = 4 * RS_Q * round + 8 * p;                                  // first chunk of the request
@@ -981,14 +983,15 @@ __global__ __launch_bounds__(64 * W, 4) void k_smallm_rows(const uint8_t *__rest
   };
   // operand of K-step q of the round: lane (i, kb) takes chunk 4 (q & 1) + kb of row i & 7 from
   // request (i >> 3, q >> 1): one lane permutation of either half, then the choice between them
-  const int from_even = 4 * (8 * (i & 7) + kb);
+  // (the chunk sits in lane 8 (i & 7) + (chunk ^ (i & 4)) of the request)
+  const int from_even = 4 * (8 * (i & 7) + (kb ^ (i & 4)));
   const bool upper = i >= 8;
   auto pick = [&](int from, uint32_t lo, uint32_t hi) {
     const uint32_t a = lane_perm(from, lo), b = lane_perm(from, hi);
     return upper ? b : a;
   };
   auto to_operand = [&](const RoundRegs &a, int q, Tile &t) {
-    const int from = from_even + 16 * (q & 1), p = q >> 1;
+    const int from = from_even ^ (16 * (q & 1)), p = q >> 1;
 #pragma unroll
     for (int d = 0; d < 4; ++d) t.nib[0][d] = pick(from, a.nib[0][p][d], a.nib[1][p][d]);
     t.iw[0] = pick(from, a.iw[0][p][0], a.iw[1][p][0]);
