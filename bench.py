@@ -268,7 +268,7 @@ def main():
         step, step_bytes = stk.verify_step(args.only_verify_stack)
         plan = step.plan
         row = entry(timer(lambda i: step(), 30, 5), step_bytes)
-        row.update(M=plan.M, matrices=plan.count, grid=[plan.grid_x, plan.count], block_threads=plan.block_threads, lds_bytes=plan.lds_bytes)
+        row.update(M=plan.M, matrices=plan.count, grid=plan.grid_x, block_threads=plan.block_threads, lds_bytes=plan.lds_bytes)
         out = {"only_verify_stack": True, "config4_sparse_layers_one_launch": row}
         if args.only_verify_stack <= 32:              # the 1:4 layers of the three-way mix (11 layers, 77 products)
             del stk, step
@@ -277,7 +277,7 @@ def main():
             step, step_bytes = stk.verify_step(args.only_verify_stack, "s14")
             plan = step.plan
             row = entry(timer(lambda i: step(), 30, 5), step_bytes)
-            row.update(M=plan.M, matrices=plan.count, grid=[plan.grid_x, plan.count], block_threads=plan.block_threads, lds_bytes=plan.lds_bytes)
+            row.update(M=plan.M, matrices=plan.count, grid=plan.grid_x, block_threads=plan.block_threads, lds_bytes=plan.lds_bytes)
             out["mix3_1to4_layers_one_launch"] = row
             both, both_bytes = stk.verify_step(args.only_verify_stack, ("s24", "s14"))
             row = entry(timer(lambda i: both(), 30, 5), both_bytes)

@@ -363,16 +363,16 @@ typedef struct {
 typedef struct {
   int32_t count;         /* matrices in the table                                            */
   int32_t M;             /* tokens of every product (2..64)                                  */
-  int32_t grid_x;        /* workgroups per matrix (0: every matrix is empty)                 */
+  int32_t grid_x;        /* workgroups of the launch (0: every matrix is empty)              */
   int32_t block_threads; /* threads per workgroup                                            */
   int32_t lds_bytes;     /* dynamic LDS per workgroup                                        */
   int32_t n_keep;        /* storage form of every matrix of the table: 2 (2:4) or 1 (1:4)    */
-  uint64_t table_bytes;  /* count * EGT_STACK_ENTRY_BYTES                                    */
+  uint64_t table_bytes;  /* the descriptors and 4 bytes per workgroup, a multiple of 16      */
 } egt_gemm_plan;
 
 /* HOST.  As egt_gemv_stack_plan: checks `count` (1..65535) items for M tokens each, writes
- * the launch shape to *plan and, with table != NULL, one descriptor per item to `table`
- * (HOST memory of the caller, table_bytes >= plan->table_bytes, else EGT_ERR_SHAPE), which
+ * the launch shape to *plan and, with table != NULL, one descriptor per item and the list
+ * of the launch's workgroups to `table` (HOST memory of the caller, table_bytes >= plan->table_bytes, else EGT_ERR_SHAPE), which
  * the caller copies to 16-byte aligned device memory.  Items with rows == 0 compute
  * nothing.  Nothing is written when an error is returned. */
 egt_status egt_gemm_stack_plan(const egt_gemm_item *items, int count, int M, void *table,

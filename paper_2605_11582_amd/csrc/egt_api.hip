@@ -4,8 +4,10 @@
 
 #include "egt_tune.h"
 
+#include <algorithm>
 #include <cstring>
 #include <mutex>
+#include <vector>
 
 namespace {
 
@@ -257,11 +259,16 @@ egt_status egt_sparse_gemm_smallm_batch(const egt_2bitcsr *w, const uint16_t *co
   return done(egt::launch_sparse_gemm_batch(w, X, ldx, Y, ldy, M, count, (hipStream_t)stream));
 }
 
+// descriptors, then one 32-bit word per workgroup, rounded up to 16 bytes
+static uint64_t gemm_table_bytes(int count, int grid_x) {
+  return (uint64_t)count * EGT_STACK_ENTRY_BYTES + (((uint64_t)grid_x * 4 + 15) & ~(uint64_t)15);
+}
+
 egt_status egt_gemm_stack_plan(const egt_gemm_item *items, int count, int M, void *table, size_t table_bytes,
                                egt_gemm_plan *plan) {
   if (!items || !plan) return EGT_ERR_NULL;
   if (count < 1 || count > 65535 || M < 2 || M > 64) return EGT_ERR_SHAPE;
-  int max_rows = 0;
+  uint64_t nwg = 0;
   for (int k = 0; k < count; ++k) {
     const egt_2bitcsr *w = items[k].sparse;
     if (!w) return EGT_ERR_NULL;
@@ -273,21 +280,36 @@ egt_status egt_gemm_stack_plan(const egt_gemm_item *items, int count, int M, voi
       return EGT_ERR_BUFFER;
     if (!egt::smallm_stack_item_ok(*w, M)) return EGT_ERR_UNSUPPORTED;
     if (w->n_keep != items[0].sparse->n_keep) return EGT_ERR_UNSUPPORTED;   // one storage form per table (one kernel)
-    max_rows = w->rows > max_rows ? w->rows : max_rows;
+    const int blocks = egt::smallm_stack_blocks(M, w->n_keep, w->rows);
+    if (blocks > 0xFFFF) return EGT_ERR_UNSUPPORTED;                         // (the list names a workgroup's place in 16 bits)
+    nwg += (uint64_t)blocks;
   }
+  if (nwg > (1u << 24)) return EGT_ERR_UNSUPPORTED;
   const int n_keep = items[0].sparse->n_keep;
   egt_gemm_plan out;
   std::memset(&out, 0, sizeof(out));
   out.count = count;
   out.M = M;
   out.n_keep = n_keep;
-  out.grid_x = egt::smallm_stack_blocks(M, n_keep, max_rows);
+  out.grid_x = (int32_t)nwg;
   egt::smallm_stack_shape(M, n_keep, out.block_threads, out.lds_bytes);
-  out.table_bytes = (uint64_t)count * EGT_STACK_ENTRY_BYTES;
+  out.table_bytes = gemm_table_bytes(count, out.grid_x);
   if (table) {
     if ((uint64_t)table_bytes < out.table_bytes) return EGT_ERR_SHAPE;
-    for (int k = 0; k < count; ++k)
-      egt::smallm_stack_entry(*items[k].sparse, items[k].X, items[k].Y, M, (uint8_t *)table + (size_t)k * EGT_STACK_ENTRY_BYTES);
+    // Descriptors in the order of falling row length (a stable sort): a workgroup walks all of K, so the matrices
+    // with the longest rows start first and the launch ends on short workgroups.  The order of the table is
+    // nobody's business but the kernel's: every descriptor names its own X and Y.
+    std::vector<int> order((size_t)count);
+    for (int k = 0; k < count; ++k) order[(size_t)k] = k;
+    std::stable_sort(order.begin(), order.end(), [&](int a, int b) { return items[a].sparse->cols > items[b].sparse->cols; });
+    std::memset(table, 0, (size_t)out.table_bytes);
+    uint32_t *list = (uint32_t *)((uint8_t *)table + (size_t)count * EGT_STACK_ENTRY_BYTES);
+    for (int k = 0; k < count; ++k) {
+      const egt_gemm_item &it = items[order[(size_t)k]];
+      egt::smallm_stack_entry(*it.sparse, it.X, it.Y, M, (uint8_t *)table + (size_t)k * EGT_STACK_ENTRY_BYTES);
+      const int blocks = egt::smallm_stack_blocks(M, n_keep, it.sparse->rows);
+      for (int x = 0; x < blocks; ++x) *list++ = ((uint32_t)k << 16) | (uint32_t)x;   // matrix, place in the matrix
+    }
   }
   *plan = out;
   return EGT_OK;
@@ -301,10 +323,8 @@ egt_status egt_gemm_stack_run(const void *table_dev, const egt_gemm_plan *plan, 
     return EGT_ERR_SHAPE;
   int threads, lds;
   egt::smallm_stack_shape(plan->M, plan->n_keep, threads, lds);
-  // (workgroups per matrix: what the plan call derived from the tallest matrix of the table)
-  if (plan->grid_x < 0 || plan->grid_x > (1 << 20) || 
-      plan->block_threads != threads || plan->lds_bytes != lds ||
-      plan->table_bytes != (uint64_t)plan->count * EGT_STACK_ENTRY_BYTES)
+  if (plan->grid_x < 0 || plan->grid_x > (1 << 24) || plan->block_threads != threads || plan->lds_bytes != lds ||
+      plan->table_bytes != gemm_table_bytes(plan->count, plan->grid_x))
     return EGT_ERR_SHAPE;
   if (plan->grid_x == 0) return EGT_OK;               // every matrix is empty
   return done(egt::launch_smallm_stack(table_dev, plan->count, plan->M, plan->n_keep, plan->grid_x, (hipStream_t)stream));

@@ -49,7 +49,7 @@ hipError_t launch_sparse_smallm_batch(const egt_2bitcsr *ws, const uint16_t *con
                                       int64_t ldy, int M, int count, hipStream_t stream);
 // any number of 2:4 (or of 1:4) INT4 small-M products in one launch (egt_gemm_stack_plan / egt_gemm_stack_run)
 bool smallm_stack_item_ok(const egt_2bitcsr &w, int M);
-int smallm_stack_blocks(int M, int n_keep, int max_rows);
+int smallm_stack_blocks(int M, int n_keep, int rows);
 void smallm_stack_shape(int M, int n_keep, int &block_threads, int &lds_bytes);
 void smallm_stack_entry(const egt_2bitcsr &w, const uint16_t *X, uint16_t *Y, int M, void *entry);
 hipError_t launch_smallm_stack(const void *table_dev, int count, int M, int n_keep, int grid_x, hipStream_t stream);

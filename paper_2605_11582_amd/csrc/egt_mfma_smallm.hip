@@ -855,8 +855,8 @@ hipError_t launch_sparse_smallm(const egt_2bitcsr &w, const uint16_t *X, int64_t
 }
 
 // ---- Any number of small-M products in one launch (a verification pass through a whole
-// stack of 2:4 INT4 layers): blockIdx.y names the matrix, whose descriptor - pointers and
-// geometry - lies in a table in device memory of the caller.
+// stack of 2:4 INT4 layers): a table in device memory of the caller holds a descriptor per
+// matrix - pointers and geometry - and behind them a list of the workgroups of the launch.
 // The single product has to spread one matrix over the whole chip: one 16-wave workgroup per
 // compute unit, K split over its waves.  Such a workgroup runs its loads, products and the
 // sum across waves one after the other, and nothing else is resident to fill the gaps.  A
@@ -910,7 +910,7 @@ constexpr int rs_lds_bytes(int ng, int q, bool n1 = false) { return RS_BUFS * ng
 
 // N1: 1:4 sparsity (chunks of 128 columns, eight instructions a K-step, a request of X per token).
 template <int NG, int Q, int W, bool N1 = false>
-__global__ __launch_bounds__(64 * W, 4) void k_smallm_rows(const uint8_t *__restrict__ table) {
+__global__ __launch_bounds__(64 * W, 4) void k_smallm_rows(const uint8_t *__restrict__ table, int count) {
   constexpr int RS_WAVES = W, RS_Q = Q, RS_STEP = rs_step_bytes(N1), RS_REGION = NG * Q * RS_STEP;
   constexpr int XREQ = N1 ? 16 : 8;                   // requests of X per K-step and token group
   constexpr int NM = N1 ? 8 : 4;                      // matrix instructions per K-step
@@ -924,9 +924,11 @@ __global__ __launch_bounds__(64 * W, 4) void k_smallm_rows(const uint8_t *__rest
   typedef __attribute__((address_space(1))) __half *g_hw;
   typedef ATile<EGT_VAL_INT4, 1> Tile;
   constexpr int LPT = Tile::LOADS;
-  const SmallMStackEntry *e = (const SmallMStackEntry *)(table + (size_t)blockIdx.y * EGT_STACK_ENTRY_BYTES);
+  // the list behind the descriptors names the matrix (high half) and the workgroup's place in it (low half)
+  const uint32_t where = ((const uint32_t *)(table + (size_t)count * EGT_STACK_ENTRY_BYTES))[blockIdx.x];
+  const int wg = (int)(where & 0xFFFFu);
+  const SmallMStackEntry *e = (const SmallMStackEntry *)(table + (size_t)(where >> 16) * EGT_STACK_ENTRY_BYTES);
   const SmallMKsGeom g = e->g;
-  if ((int)blockIdx.x * RS_WAVES >= g.ntiles) return; // (uniform: the whole workgroup leaves)
   const uint32_t *row_ptr = (const uint32_t *)(g_u32)e->row_ptr;
   __half *Y = (__half *)(g_hw)e->Y;
   const int lane = threadIdx.x & 63;
@@ -934,7 +936,7 @@ __global__ __launch_bounds__(64 * W, 4) void k_smallm_rows(const uint8_t *__rest
   const int i = lane & 15, kb = lane >> 4;            // operand form: row i of the tile, chunk kb of the step
   // this wave's row tile (a wave past the last tile has none, but still stages its share of X
   // and meets the barriers)
-  const int tile = (int)blockIdx.x * RS_WAVES + wave;
+  const int tile = wg * RS_WAVES + wave;
   const bool has_tile = tile < g.ntiles;
   const int nsteps = g.nsteps, nrounds = (nsteps + RS_Q - 1) / RS_Q;
   const uint32_t magic = in_vgpr(g.nib_magic);
@@ -1160,9 +1162,9 @@ bool smallm_stack_item_ok(const egt_2bitcsr &w, int M) {
 
 static int stack_waves(int M, bool n1) { return M <= (n1 ? 16 : 32) ? RS_WAVES : 16; }
 
-// workgroups per matrix: one per row tile and wave of the tallest matrix
-int smallm_stack_blocks(int M, int n_keep, int max_rows) {
-  const int ntiles = (max_rows + 15) / 16, w = stack_waves(M, n_keep == 1);
+// workgroups of a matrix: one per row tile and wave
+int smallm_stack_blocks(int M, int n_keep, int rows) {
+  const int ntiles = (rows + 15) / 16, w = stack_waves(M, n_keep == 1);
   return (ntiles + w - 1) / w;
 }
 
@@ -1188,15 +1190,15 @@ void smallm_stack_entry(const egt_2bitcsr &w, const uint16_t *X, uint16_t *Y, in
 hipError_t launch_smallm_stack(const void *table_dev, int count, int M, int n_keep, int grid_x, hipStream_t stream) {
   int threads, lds;
   smallm_stack_shape(M, n_keep, threads, lds);
-  const dim3 grid(grid_x, count), block(threads);
+  const dim3 grid(grid_x), block(threads);
   const uint8_t *t = (const uint8_t *)table_dev;
   if (n_keep == 1) {
-    if (M <= 16) return launch(k_smallm_rows<1, 2, RS_WAVES, true>, grid, block, (size_t)lds, stream, t);
-    return launch(k_smallm_rows<2, 2, 16, true>, grid, block, (size_t)lds, stream, t);
+    if (M <= 16) return launch(k_smallm_rows<1, 2, RS_WAVES, true>, grid, block, (size_t)lds, stream, t, count);
+    return launch(k_smallm_rows<2, 2, 16, true>, grid, block, (size_t)lds, stream, t, count);
   }
-  if (M <= 16) return launch(k_smallm_rows<1, RS_Q, RS_WAVES>, grid, block, (size_t)lds, stream, t);
-  if (M <= 32) return launch(k_smallm_rows<2, 2, RS_WAVES>, grid, block, (size_t)lds, stream, t);
-  return launch(k_smallm_rows<4, 2, 16>, grid, block, (size_t)lds, stream, t);
+  if (M <= 16) return launch(k_smallm_rows<1, RS_Q, RS_WAVES>, grid, block, (size_t)lds, stream, t, count);
+  if (M <= 32) return launch(k_smallm_rows<2, 2, RS_WAVES>, grid, block, (size_t)lds, stream, t, count);
+  return launch(k_smallm_rows<4, 2, 16>, grid, block, (size_t)lds, stream, t, count);
 }
 
 // `count` (2..4) identically shaped members in one launch (the caller has checked the shapes

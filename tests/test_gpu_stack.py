@@ -514,8 +514,8 @@ def test_gemm_stack_equals_the_oracle_and_the_separate_products(M, n):
     Yd = [yb[gd:gd + M * p.rows].view(torch.float16).view(M, p.rows) for yb, gd, p in zip(ybufs, guards, ps)]
     call = B.prepared_gemm_stack(list(zip(pds, Xd, Yd)))
     assert (call.plan.count, call.plan.M) == (len(shapes), M)
-    # a row tile per wave: the workgroups of the tallest matrix cover its rows
-    assert call.plan.grid_x == -(-max(p.rows for p in ps) // (16 * (call.plan.block_threads // 64)))
+    # a row tile per wave: the workgroups of the launch cover the rows of every matrix
+    assert call.plan.grid_x == sum(-(-p.rows // (16 * (call.plan.block_threads // 64))) for p in ps)
     first = {}
     for rep in range(2):
         call()

@@ -590,19 +590,26 @@ def test_gemm_stack_plan_checks_items_and_reports_the_launch_shape():
     assert L.egt_gemm_stack_plan(items, 3, 16, None, 0, ctypes.byref(plan)) == 0
     # up to 16 tokens: workgroups of 8 waves that own a row tile each (the tallest matrix has 256 tiles);
     # two regions of four K-steps of eight pairs of token rows of 1056 bytes
+    # (the launch: 32 workgroups for each of the two matrices with rows, named in a list behind the descriptors)
     assert (plan.count, plan.M, plan.grid_x, plan.block_threads, plan.lds_bytes, plan.table_bytes) == \
-        (3, 16, 32, 512, 2 * 4 * 8 * 1056, 3 * B.STACK_ENTRY_BYTES)
+        (3, 16, 64, 512, 2 * 4 * 8 * 1056, 3 * B.STACK_ENTRY_BYTES + 4 * 64)
     wide = B.GemmPlan()
     assert L.egt_gemm_stack_plan(items, 3, 17, None, 0, ctypes.byref(wide)) == 0
     # up to 32 tokens: two token groups, rounds of two K-steps; beyond: four groups, 16 waves
-    assert (wide.grid_x, wide.block_threads, wide.lds_bytes) == (32, 512, 2 * 2 * 2 * 8 * 1056)
+    assert (wide.grid_x, wide.block_threads, wide.lds_bytes) == (64, 512, 2 * 2 * 2 * 8 * 1056)
     assert L.egt_gemm_stack_plan(items, 3, 33, None, 0, ctypes.byref(wide)) == 0
-    assert (wide.grid_x, wide.block_threads, wide.lds_bytes) == (16, 1024, 2 * 4 * 2 * 8 * 1056)
-    table = np.full(3 * B.STACK_ENTRY_BYTES, 0xA5, dtype=np.uint8)
+    assert (wide.grid_x, wide.block_threads, wide.lds_bytes) == (32, 1024, 2 * 4 * 2 * 8 * 1056)
+    table = np.full(3 * B.STACK_ENTRY_BYTES + 4 * 64, 0xA5, dtype=np.uint8)
     assert L.egt_gemm_stack_plan(items, 3, 16, table.ctypes.data, table.nbytes - 1, ctypes.byref(plan)) == 2
     assert np.all(table == 0xA5)
     assert L.egt_gemm_stack_plan(items, 3, 16, table.ctypes.data, table.nbytes, ctypes.byref(plan)) == 0
     assert not np.all(table == 0xA5)
+    # the descriptors stand in the order of falling row length (11008 columns = 172 chunks first; geometry behind six
+    # pointers: rows, tokens, chunks), the list names matrix and place for every workgroup
+    geom = table[:3 * B.STACK_ENTRY_BYTES].reshape(3, B.STACK_ENTRY_BYTES)[:, 48:60].copy().view(np.int32)
+    assert geom.tolist() == [[4096, 16, 172], [4096, 16, 64], [0, 16, 64]]
+    wgs = table[3 * B.STACK_ENTRY_BYTES:].view(np.uint32)
+    assert np.array_equal(wgs >> 16, np.repeat([0, 1], 32)) and np.array_equal(wgs & 0xFFFF, np.tile(np.arange(32), 2))
     # errors leave table and plan untouched
     table[:] = 0xA5
     plan2 = B.GemmPlan(-1)
@@ -632,9 +639,9 @@ def test_gemm_stack_plan_checks_items_and_reports_the_launch_shape():
         one4[k].sparse, one4[k].X, one4[k].Y = ctypes.pointer(v), 16, 16
     p14 = B.GemmPlan()
     assert L.egt_gemm_stack_plan(one4, 2, 16, None, 0, ctypes.byref(p14)) == 0
-    assert (p14.n_keep, p14.grid_x, p14.block_threads, p14.lds_bytes) == (1, 86, 512, 2 * 2 * 16 * 1040)
+    assert (p14.n_keep, p14.grid_x, p14.block_threads, p14.lds_bytes) == (1, 32 + 86, 512, 2 * 2 * 16 * 1040)
     assert L.egt_gemm_stack_plan(one4, 2, 32, None, 0, ctypes.byref(p14)) == 0
-    assert (p14.n_keep, p14.grid_x, p14.block_threads, p14.lds_bytes) == (1, 43, 1024, 2 * 2 * 2 * 16 * 1040)
+    assert (p14.n_keep, p14.grid_x, p14.block_threads, p14.lds_bytes) == (1, 16 + 43, 1024, 2 * 2 * 2 * 16 * 1040)
     assert L.egt_gemm_stack_plan(one4, 2, 33, None, 0, ctypes.byref(p14)) == 6
     v14[1].group_size = 64
     assert L.egt_gemm_stack_plan(one4, 2, 16, None, 0, ctypes.byref(p14)) == 6
