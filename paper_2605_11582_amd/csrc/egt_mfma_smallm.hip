@@ -862,8 +862,9 @@ hipError_t launch_sparse_smallm(const egt_2bitcsr &w, const uint16_t *X, int64_t
 // sum across waves one after the other, and nothing else is resident to fill the gaps.  A
 // table offers many matrices at once, so the stack uses smaller workgroups, few per matrix,
 // and the compute units work on several matrices at the same time (16 layers of a 7B stack,
-// 1.3 GB: 374 us at 16 tokens against 951 us of single products replayed from a graph, 660
-// against 2008 us at 64 tokens).
+// 1.3 GB: 347 us at 16 tokens against 951 us of single products replayed from a graph, 594
+// against 2008 us at 64 tokens).  The host writes the descriptors in the order of falling row
+// length, so that the launch ends on short workgroups.
 struct SmallMStackEntry {
   uint64_t row_ptr, values, idx, qparams, X, Y;      // device addresses
   SmallMKsGeom g;
