@@ -543,6 +543,42 @@ def test_gemm_stack_equals_the_oracle_and_the_separate_products(M, n):
         assert np.array_equal(Y2[k].cpu().numpy().view(np.uint16), first[k].view(np.uint16)), ("other table differs", k)
 
 
+@pytest.mark.parametrize("seed", range(8))
+def test_gemm_stack_seeded_sweep_of_shapes(seed):
+    # seeded tables: row counts around the tile and workgroup sizes, row lengths that end anywhere inside a K-step or
+    # a round, every group size the form takes, both storage forms, any number of tokens; every output against the oracle
+    torch = G.torch_mod()
+    rng = np.random.default_rng(9200 + seed)
+    n = 2 if seed % 3 else 1
+    chunk = 64 if n == 2 else 128
+    M = int(rng.integers(2, 65 if n == 2 else 33))
+    print(f"case gemm stack sweep seed={seed} n={n} M={M}", flush=True)
+    ps, os_, Xs = [], [], []
+    for k in range(6):
+        rows = int(rng.choice([1, 15, 16, 17, 127, 128, 129, 200, int(rng.integers(1, 300))]))
+        cols = chunk * int(rng.integers(1, 8192 // chunk + 1))
+        groups = [g for g in (64, 128, 256, 512, 1024, 2048, 4096, 8192) if g >= (64 if n == 2 else 128) and cols % g == 0]
+        g = int(rng.choice(groups))
+        w = synth.weights(rows, cols, 9200 + 10 * seed + k)
+        mask = O.prune_n4_magnitude(w, n)
+        ps.append(B.pack_2bitcsr(w, mask, n, g, B.VAL_INT4))
+        os_.append(O.pack_2bitcsr(w, mask, n, g, B.VAL_INT4))
+        Xs.append(synth.activation_rows(M, cols, 9200 + 10 * seed + k))
+        print(f"  member {k}: {rows} x {cols} g={g}", flush=True)
+    pds = [p.to("cuda:0") for p in ps]
+    Xd = [G.to_dev(X.view(np.uint16)).view(torch.float16) for X in Xs]
+    ybufs = [torch.full((128 + M * p.rows,), G.CANARY, dtype=torch.int16, device="cuda:0") for p in ps]
+    Yd = [yb[64:64 + M * p.rows].view(torch.float16).view(M, p.rows) for yb, p in zip(ybufs, ps)]
+    B.prepared_gemm_stack(list(zip(pds, Xd, Yd)))()
+    torch.cuda.synchronize()
+    for k, p in enumerate(ps):
+        host = ybufs[k].cpu().numpy().view(np.uint16)
+        assert np.all(host[:64] == G.CANARY) and np.all(host[64 + M * p.rows:] == G.CANARY), ("write outside Y", k)
+        Y = host[64:64 + M * p.rows].view(np.float16).reshape(M, p.rows)
+        Y_ref, A_ref = O.gemm_smallm(os_[k], Xs[k])
+        G.assert_close(Y, Y_ref, A_ref, f"sweep seed {seed} member {k}")
+
+
 @pytest.mark.parametrize("M", [3, 16, 24, 50])
 def test_gemm_stack_broken_row_ptr_yields_nan_for_every_token(M):
     # rows 7 and 40 of the second matrix point somewhere else: NaN for every token of those rows, the other
